@@ -1,0 +1,81 @@
+"""Exact dot products and error statistics of an emulated D against them.
+Test infrastructure: see oracle/__init__.py.
+
+Methodology after the paper's accuracy study (Sec. 6.2.4: deviation
+delta = D_model - D_real of a model's output from the real result), with the real
+result taken as the exact rational c + sum_k a_k b_k rather than an FP64 product.
+
+Sampling rule (this build's definition): flattened output index i*n + j is sampled
+when it is a multiple of `stride`.
+
+Per sample, with R = RNE-FP32(exact):
+  integer part : n_samples; n_equal_rne (D bits == R bits); n_above / n_below
+                 (ordered key of D greater / less than that of R);
+                 ulp_hist[34] of |key(D) - key(R)| bucketed as in oracle/stats.py
+  float64 part : sum and max of |D - exact|, sum and max of |D - exact| / |exact|
+                 (samples with exact == 0 skipped for the relative figures),
+                 sum of (D - exact)
+"""
+from fractions import Fraction
+
+import numpy as np
+
+from . import formats as fm
+from .rounding import rne_fp32
+from .stats import ordered_key, N_BUCKETS
+
+
+def exact_dot(a_bits, b_bits, ta, tb, c_bits=0):
+    v = fm.decode(c_bits, fm.FP32).value
+    for x, y in zip(a_bits, b_bits):
+        v += fm.decode(int(x), ta).value * fm.decode(int(y), tb).value
+    return v
+
+
+def fp32_value(bits):
+    d = fm.decode(bits, fm.FP32)
+    assert d.finite
+    return d.value
+
+
+def empty_err_stats():
+    return dict(n_samples=0, n_equal_rne=0, n_above=0, n_below=0, ulp_hist=[0] * N_BUCKETS,
+                sum_abs_err=0.0, max_abs_err=0.0, sum_rel_err=0.0, max_rel_err=0.0, sum_signed_err=0.0)
+
+
+def sample_indices(m, n, stride):
+    return range(0, m * n, stride)
+
+
+def error_stats(A, B, D, ta, tb, stride, stats=None, indices=None):
+    """A[m][k], B[n][k] raw bits, D[m][n] FP32 bits (C is zero)."""
+    st = empty_err_stats() if stats is None else stats
+    A = np.asarray(A); B = np.asarray(B); D = np.asarray(D, dtype=np.uint32)
+    m, n = D.shape
+    sums = dict(abs=Fraction(0), rel=Fraction(0), sgn=Fraction(0))
+    for idx in (sample_indices(m, n, stride) if indices is None else indices):
+        i, j = divmod(idx, n)
+        ex = exact_dot(A[i].tolist(), B[j].tolist(), ta, tb)
+        r = rne_fp32(ex)
+        dbits = int(D[i, j])
+        st["n_samples"] += 1
+        kd, kr = int(ordered_key(dbits)), int(ordered_key(r))
+        if dbits == r:
+            st["n_equal_rne"] += 1
+        if kd > kr:
+            st["n_above"] += 1
+        elif kd < kr:
+            st["n_below"] += 1
+        st["ulp_hist"][abs(kd - kr).bit_length()] += 1
+        err = fp32_value(dbits) - ex
+        sums["abs"] += abs(err)
+        sums["sgn"] += err
+        st["max_abs_err"] = max(st["max_abs_err"], float(abs(err)))
+        if ex != 0:
+            rel = abs(err) / abs(ex)
+            sums["rel"] += rel
+            st["max_rel_err"] = max(st["max_rel_err"], float(rel))
+    st["sum_abs_err"] += float(sums["abs"])
+    st["sum_rel_err"] += float(sums["rel"])
+    st["sum_signed_err"] += float(sums["sgn"])
+    return st

@@ -1,0 +1,208 @@
+"""The arithmetic-behaviour model: chained fused dot-product-add with truncated
+alignment.  Test infrastructure: see oracle/__init__.py.
+
+Follows the paper's Sec. 4.1.3:
+  * Algorithm "Phi_FDPA"  : L = min(K, L_max); d <- c; for each consecutive group of
+                            L products, d <- FDPA(a_group, b_group, d).
+  * Algorithm "T-FDPA"    : exact unnormalised products; e_max over the L products
+                            and the accumulator; every term aligned at e_max and
+                            truncated toward zero to F fractional bits; exact
+                            fixed-point sum; conversion rho.
+  * Algorithm "E-FDPA"    : rho = RNE-FP32 applied to the exact c + sum(a_k b_k)
+                            (the wide-F limit of T-FDPA; used as a closed form).
+  * Sec. 4.2              : NaN / infinity rules.
+  * Algorithm "FTZ-Add/Mul": output flush  |z| < 2^-126 -> zero of the same sign.
+  * Algorithm "Phi_FTZ-AddMul" (its FlushSubnormal lines): input subnormals -> +0.0.
+
+Everything is done on Python ints and Fractions, one step per statement, in the
+paper's order and notation (s_k, e_k, e_max, s'_k, S).
+
+Readings of points the paper leaves open (each is a parameter or stated here):
+  * zero operands keep Exp = 1 - bias and their products take part in e_max;
+  * K must be a multiple of L (the paper's loop would silently drop a tail);
+  * c_mode = C_AFTER_EXACT is an additional accumulation shape (not one of the
+    paper's algorithms): the truncated fused sum T runs over the L products only
+    (e_max over the products), then d = rho(T * 2^e_max + c) with that two-term sum
+    exact.  It is Algorithm "TR-FDPA" with both of its RD roundings removed.
+  * output flush is applied after every group's conversion.
+"""
+from dataclasses import dataclass, replace
+from fractions import Fraction
+
+import numpy as np
+
+from . import formats as fm
+from .rounding import to_fp32, RNE, RZ
+
+C_IN_GROUP, C_AFTER_EXACT = 0, 1
+ALIGN_RZ = 0
+DEFAULT_NAN = 0x7FC00000
+NVIDIA_NAN = 0x7FFFFFFF  # Sec. 4.2: canonical NaN of T-FDPA on NVIDIA parts
+
+
+@dataclass(frozen=True)
+class ModelParams:
+    group_len: int = 0          # L_max; 0 means fully fused (L = K)
+    frac_bits: int = 24         # F
+    align_round: int = ALIGN_RZ
+    c_mode: int = C_IN_GROUP
+    out_round: int = RNE        # rho: RNE-FP32 or RZ-FP32
+    ftz_in: bool = False
+    ftz_out: bool = False
+    nan_bits: int = DEFAULT_NAN
+
+    def with_(self, **kw):
+        return replace(self, **kw)
+
+
+def _rz_frac(x, F):
+    """RZ_F(x): truncate the rational x toward zero to F fractional bits."""
+    scaled = abs(x) * (1 << F) if F >= 0 else abs(x) / (1 << -F)
+    n = scaled.numerator // scaled.denominator
+    r = Fraction(n, 1 << F) if F >= 0 else Fraction(n * (1 << -F))
+    return -r if x < 0 else r
+
+
+def _specials(p, da, db, dc):
+    """Sec. 4.2.  Returns output bits if the group's result is NaN or infinite, else None."""
+    if dc.cls == fm.NAN or any(x.cls == fm.NAN for x in da) or any(x.cls == fm.NAN for x in db):
+        return p.nan_bits
+    pos_inf = neg_inf = False
+    for x, y in zip(da, db):
+        if x.cls == fm.INF or y.cls == fm.INF:
+            other = y if x.cls == fm.INF else x
+            if other.cls == fm.ZERO:
+                return p.nan_bits                      # inf * 0
+            if x.sign ^ y.sign:
+                neg_inf = True
+            else:
+                pos_inf = True
+    if dc.cls == fm.INF:
+        if dc.sign:
+            neg_inf = True
+        else:
+            pos_inf = True
+    if pos_inf and neg_inf:
+        return p.nan_bits                              # +inf + -inf
+    if pos_inf:
+        return 0x7F800000
+    if neg_inf:
+        return 0xFF800000
+    return None
+
+
+def _flush_out(p, d):
+    if p.ftz_out and (d & 0x7F800000) == 0:
+        return d & 0x80000000
+    return d
+
+
+def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb):
+    """One FDPA operation on L = len(a_bits) products and the accumulator c (FP32 bits)."""
+    L = len(a_bits)
+    assert len(b_bits) == L and L >= 1
+    if p.align_round != ALIGN_RZ:
+        raise NotImplementedError("only RZ alignment")
+    F = p.frac_bits
+    if p.ftz_in:
+        a_bits = [fm.flush_subnormal(x, ta) for x in a_bits]
+        b_bits = [fm.flush_subnormal(x, tb) for x in b_bits]
+        c_bits = fm.flush_subnormal(c_bits, fm.FP32)
+    da = [fm.decode(x, ta) for x in a_bits]
+    db = [fm.decode(x, tb) for x in b_bits]
+    dc = fm.decode(c_bits, fm.FP32)
+
+    sp = _specials(p, da, db, dc)
+    if sp is not None:
+        return sp
+
+    # Step 1: exact products
+    s = [da[k].signed_sig * db[k].signed_sig for k in range(L)]
+    e = [da[k].exp + db[k].exp for k in range(L)]
+
+    if p.c_mode == C_IN_GROUP:
+        # Step 2: truncated fused sum of L+1 terms
+        s.append(dc.signed_sig)
+        e.append(dc.exp)
+        e_max = max(e)
+        s_al = [_rz_frac(s[k] * Fraction(2) ** (e[k] - e_max), F) for k in range(L + 1)]
+        S = sum(s_al, Fraction(0))
+        V = S * Fraction(2) ** e_max
+    elif p.c_mode == C_AFTER_EXACT:
+        e_max = max(e)
+        s_al = [_rz_frac(s[k] * Fraction(2) ** (e[k] - e_max), F) for k in range(L)]
+        T = sum(s_al, Fraction(0))
+        V = T * Fraction(2) ** e_max + dc.value
+    else:
+        raise ValueError(p.c_mode)
+
+    # Step 3: convert
+    d = to_fp32(V, p.out_round)
+    return _flush_out(p, d)
+
+
+def group_length(p, K):
+    L = K if p.group_len == 0 else min(K, p.group_len)
+    if K % L:
+        raise ValueError("K=%d is not a multiple of L=%d" % (K, L))
+    return L
+
+
+def emulate_element(p, a_bits, b_bits, c_bits, ta, tb):
+    """Algorithm "Phi_FDPA" for one output element: chain over K/L groups."""
+    K = len(a_bits)
+    L = group_length(p, K)
+    d = int(c_bits)
+    for k in range(0, K, L):
+        d = fdpa_group(p, [int(x) for x in a_bits[k:k + L]], [int(x) for x in b_bits[k:k + L]], d, ta, tb)
+    return d
+
+
+def emulate_mma(p, A, B, C, ta, tb):
+    """A[batch][m][k], B[batch][n][k] (both K-contiguous), C[batch][m][n] as raw bit
+    patterns (any integer dtype); returns D[batch][m][n] as uint32 FP32 bits."""
+    A = np.asarray(A)
+    B = np.asarray(B)
+    C = np.asarray(C)
+    if A.ndim == 2:
+        A, B, C = A[None], B[None], C[None]
+    nb, m, k = A.shape
+    n = B.shape[1]
+    assert B.shape == (nb, n, k) and C.shape == (nb, m, n)
+    D = np.zeros((nb, m, n), dtype=np.uint32)
+    for t in range(nb):
+        for i in range(m):
+            ai = A[t, i].tolist()
+            for j in range(n):
+                D[t, i, j] = emulate_element(p, ai, B[t, j].tolist(), int(C[t, i, j]), ta, tb)
+    return D
+
+
+def exact_value(a_bits, b_bits, c_bits, ta, tb):
+    """c + sum a_k b_k as a Fraction (all inputs finite)."""
+    v = fm.decode(c_bits, fm.FP32).value
+    for x, y in zip(a_bits, b_bits):
+        v += fm.decode(x, ta).value * fm.decode(y, tb).value
+    return v
+
+
+def e_fdpa(a_bits, b_bits, c_bits, ta, tb, nan_bits=DEFAULT_NAN):
+    """Algorithm "E-FDPA": RNE-FP32 of the exact c + sum a_k b_k (specials per Sec. 4.2)."""
+    p = ModelParams(nan_bits=nan_bits)
+    sp = _specials(p, [fm.decode(x, ta) for x in a_bits], [fm.decode(x, tb) for x in b_bits],
+                   fm.decode(c_bits, fm.FP32))
+    if sp is not None:
+        return sp
+    return to_fp32(exact_value(a_bits, b_bits, c_bits, ta, tb), RNE)
+
+
+def exact_width(a_bits, b_bits, c_bits, ta, tb):
+    """Smallest F for which the truncation in T-FDPA drops nothing for these inputs
+    (so that T-FDPA(F) must equal E-FDPA): distance from e_max down to the lowest
+    possibly-set bit of any term."""
+    da = [fm.decode(x, ta) for x in a_bits]
+    db = [fm.decode(x, tb) for x in b_bits]
+    dc = fm.decode(c_bits, fm.FP32)
+    e = [x.exp + y.exp for x, y in zip(da, db)] + [dc.exp]
+    low = [x.exp + y.exp - x.mbits - y.mbits for x, y in zip(da, db)] + [dc.exp - dc.mbits]
+    return max(e) - min(low)

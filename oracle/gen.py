@@ -1,0 +1,218 @@
+"""Synthetic tile generators (CPU twins of the on-device generators).
+Test infrastructure: see oracle/__init__.py.
+
+The paper's randomized validation (Sec. 3.1, Step 4) draws inputs from common
+distributions and from random bit streams; it fixes no generator.  This file is
+this build's definition, stated so that an integer-exact twin can exist on the
+device:
+
+Random words.  Element with global index g = (first_tile + t) * elems_per_tile + e
+of operand `operand` (0 = A, 1 = B, 2 = C) owns `wpe` consecutive words starting at
+word index w = g * wpe of the stream
+    word(w) = Philox4x32-10(counter = (lo32(w >> 2), hi32(w >> 2), operand, 0),
+                            key = (lo32(seed), hi32(seed)))[w & 3].
+wpe is 2 for FP32 output of the UNIFORM_EXP family and 1 otherwise.
+
+Families (r = first word, r1 = second word):
+  ZERO          all bits zero.
+  FINITE_BITS   uniform over all finite bit patterns: v = (r * ncodes) >> 32 with
+                ncodes = 2 * nmag (nmag = number of finite magnitudes of the format);
+                sign = v >= nmag; magnitude code = v - sign * nmag.
+  UNIFORM_EXP   sign = r >> 31; exponent field uniform over `exp_lo..exp_hi`
+                (plus the value 0 as one extra, equally likely, choice when
+                `exp_zero`), drawn as idx = (sel * nchoices) >> nsel with
+                sel = bits m..30 of r (nsel = 31 - m) -- for FP32: sel = r & 0x7FFFFFFF,
+                nsel = 31 and the mantissa comes from r1; mantissa = low m bits.
+  RANDOM_BITS   the low `width` bits of r (NaN and infinities included).
+  NORMAL        Box-Muller on word pairs (elements 2i, 2i+1 of the flattened
+                operand share (r_2i, r_2i+1)):  u1 = (r_2i + 0.5) / 2^32,
+                phi = 2 pi r_2i+1 / 2^32 (+ half a step), radius = sqrt(-2 ln u1);
+                element 2i gets radius*cos(phi), element 2i+1 radius*sin(phi).
+                ln, sin, cos and sqrt are evaluated in binary64 with +, *, / only
+                (series below, fixed operation order, no fused multiply-add), so
+                that any IEEE-754 machine produces the same bits.  The value is
+                optionally multiplied by scale_target / absmax (absmax over the
+                whole call, or over each tile), rounded to binary32 (RNE), then to
+                the output format (RNE, saturating at the largest finite value).
+"""
+import math
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import formats as fm
+from .philox import philox4x32_10
+
+GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
+SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
+
+
+@dataclass(frozen=True)
+class GenParams:
+    family: int
+    seed: int = 0
+    operand: int = 0
+    exp_lo: int = 0
+    exp_hi: int = 0
+    exp_zero: bool = False
+    scale_scope: int = SCALE_NONE
+    scale_target: float = 1.0
+
+
+def _words(seed, operand, w):
+    """word(w) for an array of word indices."""
+    w = np.asarray(w, dtype=np.uint64)
+    blk = w >> np.uint64(2)
+    out = philox4x32_10(blk & np.uint64(0xFFFFFFFF), blk >> np.uint64(32), operand, 0,
+                        seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)
+    lane = (w & np.uint64(3)).astype(np.int64)
+    return np.choose(lane, out)
+
+
+def _n_finite_magnitudes(f):
+    return (f.emax_field << f.mbits) if f.ieee_specials else ((f.emax_field + 1) << f.mbits) - 1
+
+
+def max_finite_code(f):
+    return _n_finite_magnitudes(f) - 1
+
+
+def cast_from_fp32(bits32, fmt_id):
+    """RNE conversion of finite binary32 bit patterns to `fmt_id`, saturating at the
+    largest finite magnitude.  Integer arithmetic only."""
+    f = fm.FORMATS[fmt_id]
+    b = np.asarray(bits32, dtype=np.uint32).astype(np.uint64)
+    if fmt_id == fm.FP32:
+        return b.astype(np.uint32)
+    sign = b >> np.uint64(31)
+    E32 = (b >> np.uint64(23)) & np.uint64(0xFF)
+    sig = (b & np.uint64(0x7FFFFF)) | np.where(E32 > 0, np.uint64(1 << 23), np.uint64(0))
+    exp = np.maximum(E32, 1).astype(np.int64) - 127              # value = sig * 2^(exp-23)
+    q = np.maximum(exp, 1 - f.bias) - f.mbits                    # exponent of the target's last place
+    shift = np.minimum(q - (exp - 23), 40).astype(np.uint64)     # >= 23 - m > 0
+    n = sig >> shift
+    rem = sig & ((np.uint64(1) << shift) - np.uint64(1))
+    half = np.uint64(1) << (shift - np.uint64(1))
+    n = n + ((rem > half) | ((rem == half) & ((n & np.uint64(1)) == 1))).astype(np.uint64)
+    Et = np.maximum(exp + f.bias, 1).astype(np.uint64)
+    code = ((Et - np.uint64(1)) << np.uint64(f.mbits)) + n
+    code = np.minimum(code, np.uint64(max_finite_code(f)))
+    return ((sign << np.uint64(f.width - 1)) | code).astype(np.uint32)
+
+
+# ---- binary64 elementary functions from +, *, / only (fixed order) -------------------
+
+LN2 = float.fromhex("0x1.62e42fefa39efp-1")
+HALF_PI = float.fromhex("0x1.921fb54442d18p+0")
+LOG_TERMS = 12     # ln m = 2 s (1 + s^2/3 + ... + s^(2*12)/(2*12+1)),  s = (m-1)/(m+1)
+SIN_TERMS = 10     # through theta^19
+COS_TERMS = 11     # through theta^20
+SQRT_ITERS = 5
+SQRT_SEED = 0x1FF8000000000000
+
+
+def _ln_unit(r):
+    """ln((r + 0.5) / 2^32) for uint32 r."""
+    t = 2.0 * r.astype(np.float64) + 1.0                  # odd integer < 2^33, exact
+    mant, ex = np.frexp(t)                                # t = mant * 2^ex, mant in [0.5, 1)
+    m = mant * 2.0                                        # [1, 2)
+    s = (m - 1.0) / (m + 1.0)
+    s2 = s * s
+    poly = np.full_like(s, 1.0 / (2 * LOG_TERMS + 1))
+    for n in range(LOG_TERMS - 1, 0, -1):
+        poly = poly * s2 + 1.0 / (2 * n + 1)
+    poly = poly * s2 + 1.0
+    lnm = (2.0 * s) * poly
+    return lnm + (ex - 1 - 33).astype(np.float64) * LN2
+
+
+def _sqrt_heron(x):
+    y = ((x.view(np.uint64) >> np.uint64(1)) + np.uint64(SQRT_SEED)).view(np.float64)
+    for _ in range(SQRT_ITERS):
+        y = 0.5 * (y + x / y)
+    return y
+
+
+def _sincos_quarter(theta):
+    t2 = theta * theta
+    ps = np.full_like(theta, (-1.0) ** (SIN_TERMS - 1) / math.factorial(2 * SIN_TERMS - 1))
+    for n in range(SIN_TERMS - 2, -1, -1):
+        ps = ps * t2 + (-1.0) ** n / math.factorial(2 * n + 1)
+    pc = np.full_like(theta, (-1.0) ** (COS_TERMS - 1) / math.factorial(2 * COS_TERMS - 2))
+    for n in range(COS_TERMS - 2, -1, -1):
+        pc = pc * t2 + (-1.0) ** n / math.factorial(2 * n)
+    return theta * ps, pc
+
+
+def normal_pairs(r_even, r_odd):
+    """Box-Muller: two uint32 arrays -> (z_even, z_odd) binary64."""
+    radius = _sqrt_heron(-2.0 * _ln_unit(r_even))
+    quad = (r_odd >> np.uint32(30)).astype(np.int64)
+    frac = ((r_odd & np.uint32(0x3FFFFFFF)).astype(np.float64) + 0.5) * (1.0 / (1 << 30))
+    s, c = _sincos_quarter(frac * HALF_PI)
+    cosphi = np.choose(quad, [c, -s, -c, s])
+    sinphi = np.choose(quad, [s, c, -s, -c])
+    return radius * cosphi, radius * sinphi
+
+
+# ---- the generators ------------------------------------------------------------------
+
+def words_per_elem(gp, fmt_id):
+    return 2 if (gp.family == GEN_UNIFORM_EXP and fmt_id == fm.FP32) else 1
+
+
+def normal_values(gp, elems_per_tile, first_tile, n_tiles):
+    """Unscaled binary64 N(0,1) values of the NORMAL family, shape (n_tiles, elems_per_tile)."""
+    g0 = first_tile * elems_per_tile
+    total = n_tiles * elems_per_tile
+    g = np.arange(g0, g0 + total, dtype=np.uint64)
+    pair = g >> np.uint64(1)
+    ze, zo = normal_pairs(_words(gp.seed, gp.operand, pair * np.uint64(2)),
+                          _words(gp.seed, gp.operand, pair * np.uint64(2) + np.uint64(1)))
+    z = np.where((g & np.uint64(1)) == 0, ze, zo)
+    return z.reshape(n_tiles, elems_per_tile)
+
+
+def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles):
+    """Raw bit patterns (uint32 array, shape (n_tiles, elems_per_tile)) of one operand."""
+    f = fm.FORMATS[fmt_id]
+    total = n_tiles * elems_per_tile
+    if gp.family == GEN_ZERO:
+        return np.zeros((n_tiles, elems_per_tile), dtype=np.uint32)
+    g = np.arange(first_tile * elems_per_tile, first_tile * elems_per_tile + total, dtype=np.uint64)
+    wpe = words_per_elem(gp, fmt_id)
+    if gp.family == GEN_NORMAL:
+        z = normal_values(gp, elems_per_tile, first_tile, n_tiles)
+        if gp.scale_scope == SCALE_TENSOR:
+            z = z * (np.float64(gp.scale_target) / np.abs(z).max())
+        elif gp.scale_scope == SCALE_TILE:
+            z = z * (np.float64(gp.scale_target) / np.abs(z).max(axis=1, keepdims=True))
+        b32 = z.astype(np.float32).view(np.uint32)
+        return cast_from_fp32(b32, fmt_id).reshape(n_tiles, elems_per_tile)
+    r = _words(gp.seed, gp.operand, g * np.uint64(wpe)).astype(np.uint64)
+    if gp.family == GEN_RANDOM_BITS:
+        out = r & np.uint64((1 << f.width) - 1)
+    elif gp.family == GEN_FINITE_BITS:
+        nmag = _n_finite_magnitudes(f)
+        v = (r * np.uint64(2 * nmag)) >> np.uint64(32)
+        sign = (v >= nmag).astype(np.uint64)
+        out = (sign << np.uint64(f.width - 1)) | (v - sign * np.uint64(nmag))
+    elif gp.family == GEN_UNIFORM_EXP:
+        nch = gp.exp_hi - gp.exp_lo + 1 + (1 if gp.exp_zero else 0)
+        sign = r >> np.uint64(31)
+        if fmt_id == fm.FP32:
+            sel, nsel = r & np.uint64(0x7FFFFFFF), 31
+            mant = _words(gp.seed, gp.operand, g * np.uint64(2) + np.uint64(1)).astype(np.uint64) & np.uint64(0x7FFFFF)
+        else:
+            nsel = 31 - f.mbits
+            sel = (r >> np.uint64(f.mbits)) & np.uint64((1 << nsel) - 1)
+            mant = r & np.uint64((1 << f.mbits) - 1)
+        idx = (sel * np.uint64(nch)) >> np.uint64(nsel)
+        if gp.exp_zero:
+            E = np.where(idx == 0, np.uint64(0), np.uint64(gp.exp_lo) + idx - np.uint64(1))
+        else:
+            E = np.uint64(gp.exp_lo) + idx
+        out = (sign << np.uint64(f.width - 1)) | (E << np.uint64(f.mbits)) | mant
+    else:
+        raise ValueError(gp.family)
+    return out.astype(np.uint32).reshape(n_tiles, elems_per_tile)

@@ -1,0 +1,355 @@
+/*
+ * CPU oracle, second form: the chained truncated fused-dot-product-add model in
+ * plain C with fixed wide integers, one output element at a time, OpenMP over rows.
+ *
+ * TEST INFRASTRUCTURE ONLY: used by the test-suite, the smoke check and the
+ * CPU-baseline leg of the benchmark.  It shares no code with the HIP library.
+ *
+ * What it computes (paper Sec. 4.1.3): Algorithm "Phi_FDPA" (chain of groups of
+ * L = min(K, L_max) products, d <- c first) around Algorithm "T-FDPA" (exact
+ * unnormalised products, e_max over the L products and the accumulator, alignment
+ * with truncation toward zero to F fractional bits, exact fixed-point sum,
+ * conversion rho), the special-value rules of Sec. 4.2, the output flush of
+ * Algorithm "FTZ-Add/FTZ-Mul" and the input flush of Algorithm "Phi_FTZ-AddMul".
+ * It is checked bit for bit against the rational-arithmetic form in ../fdpa.py and
+ * against the paper's printed values by the CPU tests.
+ *
+ * Number representation: every aligned term is an integer count of 2^(e_max - F);
+ * products have at most 22 significant bits, so with F <= 64 and at most 2^20
+ * terms per group every sum fits a signed 128-bit integer.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+#include <math.h>
+#include <omp.h>
+
+typedef __int128 i128;
+typedef unsigned __int128 u128;
+
+enum { T_E4M3 = 0, T_E5M2 = 1, T_FP16 = 2, T_BF16 = 3, T_FP32 = 4 };
+enum { CLS_ZERO, CLS_SUB, CLS_NORMAL, CLS_INF, CLS_NAN };
+enum { C_IN_GROUP = 0, C_AFTER_EXACT = 1 };
+enum { R_RNE = 0, R_RZ = 1 };
+
+typedef struct {
+    uint32_t group_len, frac_bits, align_round, c_mode, out_round, ftz_in, ftz_out, nan_bits;
+} o2_params;
+
+typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
+static const fmt_t FMT[5] = {
+    {4, 3, 7, 0}, {5, 2, 15, 1}, {5, 10, 15, 1}, {8, 7, 127, 1}, {8, 23, 127, 1}};
+
+typedef struct { int cls, sign, exp; uint32_t sig; } dec_t;
+
+static dec_t decode(uint32_t bits, int t)
+{
+    const fmt_t f = FMT[t];
+    dec_t d;
+    uint32_t emask = (1u << f.ebits) - 1u;
+    uint32_t E = (bits >> f.mbits) & emask;
+    uint32_t M = bits & ((1u << f.mbits) - 1u);
+    d.sign = (bits >> (f.ebits + f.mbits)) & 1u;
+    d.exp = 0; d.sig = 0;
+    if (f.ieee && E == emask) { d.cls = M ? CLS_NAN : CLS_INF; return d; }
+    if (!f.ieee && E == emask && M == ((1u << f.mbits) - 1u)) { d.cls = CLS_NAN; return d; }
+    if (E == 0) { d.cls = M ? CLS_SUB : CLS_ZERO; d.exp = 1 - f.bias; d.sig = M; return d; }
+    d.cls = CLS_NORMAL; d.exp = (int)E - f.bias; d.sig = (1u << f.mbits) | M;
+    return d;
+}
+
+static uint32_t load_elem(const void *p, size_t i, int t)
+{
+    switch (t) {
+    case T_E4M3: case T_E5M2: return ((const uint8_t *)p)[i];
+    case T_FP16: case T_BF16: return ((const uint16_t *)p)[i];
+    default: return ((const uint32_t *)p)[i];
+    }
+}
+
+static int bitlen128(u128 x)
+{
+    uint64_t hi = (uint64_t)(x >> 64), lo = (uint64_t)x;
+    if (hi) return 128 - __builtin_clzll(hi);
+    if (lo) return 64 - __builtin_clzll(lo);
+    return 0;
+}
+
+/* rho: round (-1)^neg * mag * 2^lsb to binary32.  `sticky` says the true magnitude is
+ * a little more (sticky > 0) or less (sticky < 0) than mag * 2^lsb, by less than one
+ * unit of 2^lsb; the caller guarantees the unit is far below any rounding boundary. */
+static uint32_t to_fp32(int neg, u128 mag, int lsb, int sticky, int mode)
+{
+    if (mag == 0) return 0u; /* exact zero -> +0.0 */
+    if (sticky < 0) { mag -= 1; sticky = 1; } /* value in (mag-1, mag) units: floor is mag-1, remainder non-zero */
+    int bl = bitlen128(mag);
+    int e = bl - 1 + lsb;               /* floor(log2 |value|) */
+    int eg = e < -126 ? -126 : e;       /* exponent of the grid */
+    int qexp = eg - 23;                 /* weight of the last place */
+    int sh = qexp - lsb;                /* drop `sh` low bits of mag (if positive) */
+    u128 n; int half = 0, rest = sticky != 0;
+    if (sh <= 0) {
+        n = mag << (-sh);               /* exact; fits since the result has <= 24 bits */
+    } else if (sh > 127) {
+        n = 0; rest |= (mag != 0);
+    } else {
+        n = mag >> sh;
+        u128 rem = mag & ((((u128)1) << sh) - 1);
+        u128 h = ((u128)1) << (sh - 1);
+        half = (rem & h) != 0;
+        rest |= (rem & (h - 1)) != 0;
+    }
+    if (mode == R_RNE && half && (rest || (n & 1))) n += 1;
+    if (n == ((u128)1 << 24)) { n >>= 1; eg += 1; }
+    uint32_t out;
+    if (eg > 127) out = (mode == R_RNE) ? 0x7F800000u : 0x7F7FFFFFu;
+    else if (n < ((u128)1 << 23)) out = (uint32_t)n;           /* subnormal / zero, eg == -126 */
+    else out = ((uint32_t)(eg + 127) << 23) | ((uint32_t)n & 0x7FFFFFu);
+    return ((uint32_t)neg << 31) | out;
+}
+
+/* exact x + y with x = sx*mx*2^lx, y likewise, then rho */
+static uint32_t add_exact_round(int sx, u128 mx, int lx, int sy, u128 my, int ly, int mode)
+{
+    if (mx == 0 && my == 0) return 0u;
+    if (mx == 0) return to_fp32(sy, my, ly, 0, mode);
+    if (my == 0) return to_fp32(sx, mx, lx, 0, mode);
+    if (lx < ly) { /* make x the one with the larger last-place exponent */
+        int ts = sx; sx = sy; sy = ts; u128 tm = mx; mx = my; my = tm; int tl = lx; lx = ly; ly = tl;
+    }
+    int d = lx - ly;
+    if (bitlen128(my) + 26 > d) {
+        /* the terms overlap or nearly do: both magnitudes have at most 40 bits (checked
+         * by the caller), so d < 66 and the exact sum fits 128 bits */
+        i128 v = (i128)(mx << d) * (sx ? -1 : 1) + (i128)my * (sy ? -1 : 1);
+        if (v == 0) return 0u;
+        int neg = v < 0;
+        return to_fp32(neg, (u128)(neg ? -v : v), ly, 0, mode);
+    }
+    /* |y| < 2^(lx - 26): y lies more than 26 binary places below x's last place, while
+     * binary32 rounding boundaries of x + y are multiples of 2^(lx - 25) or coarser;
+     * so y only decides on which side of x the sum falls */
+    u128 big = mx << 60;
+    int st = (sx == sy) ? 1 : -1;
+    return to_fp32(sx, big, lx - 60, st, mode);
+}
+
+/* align magnitude `mag` (units 2^lsb) to units 2^(unit) with truncation toward zero */
+static u128 align_rz(u128 mag, int lsb, int unit)
+{
+    int sh = lsb - unit;
+    if (sh >= 0) return mag << sh;
+    if (-sh > 127) return 0;
+    return mag >> (-sh);
+}
+
+static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t c,
+                           uint32_t L, int ta, int tb)
+{
+    const int F = (int)p->frac_bits;
+    const int fa = FMT[ta].mbits, fb = FMT[tb].mbits;
+    dec_t dc = decode(c, T_FP32);
+    if (p->ftz_in && dc.cls == CLS_SUB) dc = decode(0u, T_FP32);
+
+    /* pass over the inputs: specials (Sec. 4.2) and e_max */
+    int any_nan = dc.cls == CLS_NAN, pinf = 0, ninf = 0;
+    int emax = -100000;
+    for (uint32_t k = 0; k < L; ++k) {
+        dec_t x = decode(a[k], ta), y = decode(b[k], tb);
+        if (p->ftz_in) { if (x.cls == CLS_SUB) x = decode(0u, ta); if (y.cls == CLS_SUB) y = decode(0u, tb); }
+        if (x.cls == CLS_NAN || y.cls == CLS_NAN) any_nan = 1;
+        else if (x.cls == CLS_INF || y.cls == CLS_INF) {
+            if (x.cls == CLS_ZERO || y.cls == CLS_ZERO) any_nan = 1;
+            else if (x.sign ^ y.sign) ninf = 1; else pinf = 1;
+        } else {
+            int e = x.exp + y.exp;
+            if (e > emax) emax = e;
+        }
+    }
+    if (dc.cls == CLS_INF) { if (dc.sign) ninf = 1; else pinf = 1; }
+    if (any_nan || (pinf && ninf)) return p->nan_bits;
+    if (pinf) return 0x7F800000u;
+    if (ninf) return 0xFF800000u;
+
+    if (p->c_mode == C_IN_GROUP && dc.exp > emax) emax = dc.exp;
+    const int unit = emax - F;
+
+    i128 S = 0;
+    for (uint32_t k = 0; k < L; ++k) {
+        dec_t x = decode(a[k], ta), y = decode(b[k], tb);
+        if (p->ftz_in) { if (x.cls == CLS_SUB) x = decode(0u, ta); if (y.cls == CLS_SUB) y = decode(0u, tb); }
+        u128 prod = (u128)((uint64_t)x.sig * (uint64_t)y.sig);      /* exact product of significands */
+        int e = x.exp + y.exp;                                       /* sum of exponents */
+        u128 al = align_rz(prod, e - fa - fb, unit);                 /* RZ_F(s_k 2^(e_k - e_max)) */
+        if (x.sign ^ y.sign) S -= (i128)al; else S += (i128)al;
+    }
+    uint32_t d;
+    if (p->c_mode == C_IN_GROUP) {
+        u128 al = align_rz((u128)dc.sig, dc.exp - 23, unit);
+        if (dc.sign) S -= (i128)al; else S += (i128)al;
+        int neg = S < 0;
+        d = to_fp32(neg, (u128)(neg ? -S : S), unit, 0, (int)p->out_round);
+    } else {
+        int neg = S < 0;
+        d = add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, (int)p->out_round);
+    }
+    if (p->ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
+    return d;
+}
+
+static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out)
+{
+    if (ta < 0 || ta > T_BF16 || tb < 0 || tb > T_BF16) return -2;
+    if (p->align_round != 0 || p->c_mode > 1 || p->out_round > 1 || p->frac_bits > 64) return -2;
+    if (k == 0 || k > (1u << 20)) return -3;
+    uint32_t L = (p->group_len == 0 || p->group_len > k) ? k : p->group_len;
+    if (k % L) return -3;
+    if (p->c_mode == C_AFTER_EXACT) {   /* add_exact_round() needs magnitudes of at most 40 bits */
+        int lg = 0; while ((1u << lg) < L) ++lg;
+        if ((int)p->frac_bits + 2 + lg > 40) return -2;
+    }
+    *L_out = L;
+    return 0;
+}
+
+static uint32_t element(const o2_params *p, const void *A, const void *B, uint32_t c,
+                        size_t arow, size_t brow, uint32_t k, uint32_t L, int ta, int tb,
+                        uint32_t *abuf, uint32_t *bbuf)
+{
+    uint32_t d = c;
+    for (uint32_t k0 = 0; k0 < k; k0 += L) {
+        for (uint32_t q = 0; q < L; ++q) {
+            abuf[q] = load_elem(A, arow + k0 + q, ta);
+            bbuf[q] = load_elem(B, brow + k0 + q, tb);
+        }
+        d = fdpa_group(p, abuf, bbuf, d, L, ta, tb);
+    }
+    return d;
+}
+
+/* D[b][i][j] for A[b][m][k], B[b][n][k], C[b][m][n].  Returns 0, or a negative code
+ * (-2 unsupported parameter, -3 bad shape).  *threads_used receives the team size. */
+int o2_emulate_mma(const o2_params *p, const void *A, const void *B, const uint32_t *C, uint32_t *D,
+                   uint32_t m, uint32_t n, uint32_t k, uint64_t batch, int ta, int tb,
+                   int nthreads, int *threads_used)
+{
+    uint32_t L;
+    int rc = check(p, k, ta, tb, &L);
+    if (rc) return rc;
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+    int used = 1;
+    int64_t rows = (int64_t)batch * m;
+#pragma omp parallel
+    {
+        uint32_t abuf[L], bbuf[L];
+#pragma omp single
+        used = omp_get_num_threads();
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t r = 0; r < rows; ++r) {
+            uint64_t t = (uint64_t)r / m; uint32_t i = (uint32_t)((uint64_t)r % m);
+            for (uint32_t j = 0; j < n; ++j) {
+                size_t o = ((size_t)t * m + i) * n + j;
+                D[o] = element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
+            }
+        }
+    }
+    if (threads_used) *threads_used = used;
+    return 0;
+}
+
+/* The same, only at the flattened output indices idx[0..count) (index = (b*m + i)*n + j). */
+int o2_emulate_sample(const o2_params *p, const void *A, const void *B, const uint32_t *C,
+                      const uint64_t *idx, uint64_t count, uint32_t *D_sample,
+                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, int ta, int tb,
+                      int nthreads, int *threads_used)
+{
+    uint32_t L;
+    int rc = check(p, k, ta, tb, &L);
+    if (rc) return rc;
+    for (uint64_t s = 0; s < count; ++s) if (idx[s] >= batch * m * n) return -3;
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+    int used = 1;
+#pragma omp parallel
+    {
+        uint32_t abuf[L], bbuf[L];
+#pragma omp single
+        used = omp_get_num_threads();
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t s = 0; s < (int64_t)count; ++s) {
+            uint64_t o = idx[s];
+            uint64_t t = o / ((uint64_t)m * n);
+            uint32_t i = (uint32_t)((o / n) % m), j = (uint32_t)(o % n);
+            D_sample[s] = element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
+        }
+    }
+    if (threads_used) *threads_used = used;
+    return 0;
+}
+
+/* Exact dot products (C = 0) and the error of D against them, at flattened indices
+ * 0, stride, 2*stride, ... of one m x n output (A[m][k], B[n][k]).  Only FP8 operand
+ * pairs: every product is a multiple of 2^-(32) below 2^33, so a signed 128-bit
+ * accumulator in units of 2^lsb0 is exact for any k <= 2^20.
+ *
+ * int_out[0..4] = n_samples, n_equal_rne, n_above, n_below; int_out[4..38) = ulp_hist[34]
+ * dbl_out[0..5) = sum_abs_err, max_abs_err, sum_rel_err, max_rel_err, sum_signed_err */
+static int64_t okey(uint32_t b) { return (b & 0x80000000u) ? -(int64_t)(b & 0x7FFFFFFFu) : (int64_t)b; }
+
+static long double ld_of(int neg, u128 mag, int lsb)
+{
+    long double v = ldexpl((long double)(uint64_t)(mag >> 64), 64) + (long double)(uint64_t)mag;
+    v = ldexpl(v, lsb);
+    return neg ? -v : v;
+}
+
+int o2_exact_dot_stats(const void *A, const void *B, const uint32_t *D, uint32_t m, uint32_t n, uint32_t k,
+                       int ta, int tb, uint64_t stride, uint64_t *int_out, double *dbl_out)
+{
+    if (ta > T_E5M2 || tb > T_E5M2 || ta < 0 || tb < 0) return -2;
+    if (stride == 0 || k == 0 || k > (1u << 20)) return -3;
+    const int lsb0 = (1 - FMT[ta].bias - FMT[ta].mbits) + (1 - FMT[tb].bias - FMT[tb].mbits);
+    memset(int_out, 0, 38 * sizeof(uint64_t));
+    long double sabs = 0, srel = 0, ssgn = 0, mabs = 0, mrel = 0;
+    for (uint64_t o = 0; o < (uint64_t)m * n; o += stride) {
+        uint32_t i = (uint32_t)(o / n), j = (uint32_t)(o % n);
+        i128 acc = 0;
+        for (uint32_t q = 0; q < k; ++q) {
+            dec_t x = decode(load_elem(A, (size_t)i * k + q, ta), ta);
+            dec_t y = decode(load_elem(B, (size_t)j * k + q, tb), tb);
+            if (x.cls >= CLS_INF || y.cls >= CLS_INF) return -2;
+            int sh = (x.exp - FMT[ta].mbits) + (y.exp - FMT[tb].mbits) - lsb0;   /* >= 0 */
+            i128 pr = (i128)((uint64_t)x.sig * y.sig) << sh;
+            acc += (x.sign ^ y.sign) ? -pr : pr;
+        }
+        int neg = acc < 0; u128 mag = (u128)(neg ? -acc : acc);
+        uint32_t r = to_fp32(neg, mag, lsb0, 0, R_RNE);
+        uint32_t d = D[o];
+        if ((d & 0x7FFFFFFFu) > 0x7F800000u) return -2;
+        int_out[0] += 1;
+        if (d == r) int_out[1] += 1;
+        int64_t kd = okey(d), kr = okey(r);
+        if (kd > kr) int_out[2] += 1; else if (kd < kr) int_out[3] += 1;
+        uint64_t dist = (uint64_t)(kd > kr ? kd - kr : kr - kd);
+        int_out[4 + (dist ? 64 - __builtin_clzll(dist) : 0)] += 1;
+        /* D - exact, exactly: D = sig * 2^(e-23) */
+        dec_t dd = decode(d, T_FP32);
+        if (dd.cls == CLS_INF) return -2;
+        int ld = dd.exp - 23;
+        int lo = ld < lsb0 ? ld : lsb0;
+        if (ld - lo > 60 || lsb0 - lo > 30) return -2;   /* cannot happen for FP32 D near the exact value */
+        i128 dv = (i128)dd.sig << (ld - lo); if (dd.sign) dv = -dv;
+        i128 ev = acc << (lsb0 - lo);
+        i128 err = dv - ev;
+        int eneg = err < 0; u128 emag = (u128)(eneg ? -err : err);
+        long double e_ld = ld_of(eneg, emag, lo);
+        long double ae = fabsl(e_ld);
+        sabs += ae; ssgn += e_ld; if (ae > mabs) mabs = ae;
+        if (mag != 0) {
+            long double rel = ae / ld_of(0, mag, lsb0);
+            srel += rel; if (rel > mrel) mrel = rel;
+        }
+    }
+    dbl_out[0] = (double)sabs; dbl_out[1] = (double)mabs; dbl_out[2] = (double)srel;
+    dbl_out[3] = (double)mrel; dbl_out[4] = (double)ssgn;
+    return 0;
+}

@@ -1,0 +1,104 @@
+"""ctypes loader for oracle/o2/oracle2.c.  Test infrastructure: see oracle/__init__.py."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+from . import formats as fm
+
+_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "o2")
+_SO = os.path.join(_DIR, "liboracle2.so")
+_lib = None
+
+
+def build(force=False):
+    src = os.path.join(_DIR, "oracle2.c")
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(src):
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-o", _SO, src, "-lm"])
+    return _SO
+
+
+class O2Params(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in
+                ("group_len", "frac_bits", "align_round", "c_mode", "out_round", "ftz_in", "ftz_out", "nan_bits")]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_SO)
+    return _lib
+
+
+def _params(p):
+    return O2Params(p.group_len, p.frac_bits, p.align_round, p.c_mode, p.out_round,
+                    int(p.ftz_in), int(p.ftz_out), p.nan_bits)
+
+
+_NP = {fm.E4M3: np.uint8, fm.E5M2: np.uint8, fm.FP16: np.uint16, fm.BF16: np.uint16, fm.FP32: np.uint32}
+
+
+def _prep(A, B, C, ta, tb):
+    A = np.ascontiguousarray(np.asarray(A).astype(_NP[ta], copy=False))
+    B = np.ascontiguousarray(np.asarray(B).astype(_NP[tb], copy=False))
+    C = np.ascontiguousarray(np.asarray(C).astype(np.uint32, copy=False))
+    if A.ndim == 2:
+        A, B, C = A[None], B[None], C[None]
+    nb, m, k = A.shape
+    n = B.shape[1]
+    assert B.shape == (nb, n, k) and C.shape == (nb, m, n), (A.shape, B.shape, C.shape)
+    return A, B, C, nb, m, n, k
+
+
+def _vp(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def emulate_mma(p, A, B, C, ta, tb, nthreads=0):
+    """Same contract as oracle.fdpa.emulate_mma; returns (D, threads_used)."""
+    A, B, C, nb, m, n, k = _prep(A, B, C, ta, tb)
+    D = np.empty((nb, m, n), dtype=np.uint32)
+    used = ctypes.c_int(0)
+    pp = _params(p)
+    rc = _load().o2_emulate_mma(ctypes.byref(pp), _vp(A), _vp(B), _vp(C), _vp(D),
+                                ctypes.c_uint32(m), ctypes.c_uint32(n), ctypes.c_uint32(k),
+                                ctypes.c_uint64(nb), ta, tb, nthreads, ctypes.byref(used))
+    if rc:
+        raise ValueError("o2_emulate_mma failed: %d" % rc)
+    return D, used.value
+
+
+def emulate_sample(p, A, B, C, idx, ta, tb, nthreads=0):
+    """D at flattened indices idx (index = (b*m + i)*n + j)."""
+    A, B, C, nb, m, n, k = _prep(A, B, C, ta, tb)
+    idx = np.ascontiguousarray(idx, dtype=np.uint64)
+    out = np.empty(idx.shape, dtype=np.uint32)
+    used = ctypes.c_int(0)
+    pp = _params(p)
+    rc = _load().o2_emulate_sample(ctypes.byref(pp), _vp(A), _vp(B), _vp(C), _vp(idx),
+                                   ctypes.c_uint64(idx.size), _vp(out),
+                                   ctypes.c_uint32(m), ctypes.c_uint32(n), ctypes.c_uint32(k),
+                                   ctypes.c_uint64(nb), ta, tb, nthreads, ctypes.byref(used))
+    if rc:
+        raise ValueError("o2_emulate_sample failed: %d" % rc)
+    return out
+
+
+def exact_dot_stats(A, B, D, ta, tb, stride):
+    A = np.ascontiguousarray(np.asarray(A).astype(_NP[ta], copy=False))
+    B = np.ascontiguousarray(np.asarray(B).astype(_NP[tb], copy=False))
+    D = np.ascontiguousarray(D, dtype=np.uint32)
+    m, k = A.shape
+    n = B.shape[0]
+    assert D.shape == (m, n)
+    io = np.zeros(38, dtype=np.uint64)
+    do = np.zeros(5, dtype=np.float64)
+    rc = _load().o2_exact_dot_stats(_vp(A), _vp(B), _vp(D), ctypes.c_uint32(m), ctypes.c_uint32(n),
+                                    ctypes.c_uint32(k), ta, tb, ctypes.c_uint64(stride), _vp(io), _vp(do))
+    if rc:
+        raise ValueError("o2_exact_dot_stats failed: %d" % rc)
+    return dict(n_samples=int(io[0]), n_equal_rne=int(io[1]), n_above=int(io[2]), n_below=int(io[3]),
+                ulp_hist=[int(x) for x in io[4:38]], sum_abs_err=float(do[0]), max_abs_err=float(do[1]),
+                sum_rel_err=float(do[2]), max_rel_err=float(do[3]), sum_signed_err=float(do[4]))

@@ -1,0 +1,168 @@
+"""Pins for the oracle's generators, Philox, and comparison statistics."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import formats as fm, gen, stats
+from oracle.philox import philox4x32_10
+from helpers import f32_bits
+
+
+def test_philox_known_answers():
+    # known-answer vectors distributed with the reference implementation of
+    # Salmon et al., "Parallel random numbers: as easy as 1, 2, 3" (SC'11), Philox-4x32-10
+    kat = [((0, 0, 0, 0), (0, 0), (0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8)),
+           ((0xffffffff,) * 4, (0xffffffff,) * 2, (0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd)),
+           ((0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344), (0xa4093822, 0x299f31d0),
+            (0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1))]
+    for ctr, key, want in kat:
+        assert tuple(int(x) for x in philox4x32_10(*ctr, *key)) == want
+
+
+def test_philox_vectorised_equals_scalar():
+    c0 = np.arange(10, dtype=np.uint64)
+    out = philox4x32_10(c0, 7, 1, 0, 123, 456)
+    for i in range(10):
+        assert tuple(int(x[i]) for x in out) == tuple(int(x) for x in philox4x32_10(i, 7, 1, 0, 123, 456))
+
+
+def test_word_stream_is_chunk_independent():
+    gp = gen.GenParams(family=gen.GEN_FINITE_BITS, seed=5, operand=1)
+    whole = gen.generate(gp, fm.FP16, 256, 0, 8)
+    parts = np.concatenate([gen.generate(gp, fm.FP16, 256, 0, 3), gen.generate(gp, fm.FP16, 256, 3, 5)])
+    assert np.array_equal(whole, parts)
+    other = gen.generate(gen.GenParams(family=gen.GEN_FINITE_BITS, seed=5, operand=0), fm.FP16, 256, 0, 8)
+    assert not np.array_equal(whole, other)
+
+
+@pytest.mark.parametrize("fmt,ncodes", [(fm.FP16, 63488), (fm.BF16, 65280), (fm.E5M2, 248), (fm.E4M3, 254)])
+def test_finite_bits_family(fmt, ncodes):
+    gp = gen.GenParams(family=gen.GEN_FINITE_BITS, seed=0, operand=0)
+    out = gen.generate(gp, fmt, 4096, 0, 64).ravel()
+    cls = [fm.decode(int(b), fmt).cls for b in np.unique(out)]
+    assert fm.NAN not in cls and fm.INF not in cls
+    if ncodes <= 256:
+        assert len(np.unique(out)) == ncodes       # every finite pattern appears
+        counts = np.unique(out, return_counts=True)[1]
+        assert counts.min() > 0.8 * out.size / ncodes and counts.max() < 1.2 * out.size / ncodes
+    else:
+        assert len(np.unique(out)) > 0.9 * ncodes
+    f = fm.FORMATS[fmt]
+    assert abs(((out >> (f.width - 1)) & 1).mean() - 0.5) < 0.01
+
+
+def test_uniform_exp_family_fp16():
+    gp = gen.GenParams(family=gen.GEN_UNIFORM_EXP, seed=0, operand=0, exp_lo=0, exp_hi=30)
+    out = gen.generate(gp, fm.FP16, 256, 0, 2048).ravel()
+    E = (out >> 10) & 31
+    counts = np.bincount(E, minlength=32)
+    assert counts[31] == 0
+    assert counts[:31].min() > 0.95 * out.size / 31 and counts[:31].max() < 1.05 * out.size / 31
+    assert abs((out >> 15).mean() - 0.5) < 0.01
+    assert len(np.unique(out & 0x3FF)) == 1024
+
+
+def test_uniform_exp_family_fp32_with_zero_choice():
+    gp = gen.GenParams(family=gen.GEN_UNIFORM_EXP, seed=3, operand=2, exp_lo=79, exp_hi=158, exp_zero=True)
+    out = gen.generate(gp, fm.FP32, 1024, 0, 512).ravel()
+    E = (out >> 23) & 255
+    vals, counts = np.unique(E, return_counts=True)
+    assert set(vals.tolist()) == {0} | set(range(79, 159))
+    assert counts.min() > 0.9 * out.size / 81 and counts.max() < 1.1 * out.size / 81
+    # mantissa bits come from an independent word
+    assert abs(np.corrcoef((out & 0x7FFFFF).astype(np.float64), E.astype(np.float64))[0, 1]) < 0.01
+
+
+def test_normal_family_moments_and_tails():
+    gp = gen.GenParams(family=gen.GEN_NORMAL, seed=0, operand=0)
+    z = gen.normal_values(gp, 1 << 20, 0, 1).ravel()
+    n = z.size
+    assert abs(z.mean()) < 4 / np.sqrt(n)
+    assert abs(z.var() - 1) < 4 * np.sqrt(2 / n)
+    assert abs((z ** 3).mean()) < 4 * np.sqrt(15 / n)
+    assert abs((z ** 4).mean() - 3) < 4 * np.sqrt(96 / n)
+    # tail mass beyond 3 sigma: 2.6998e-3
+    assert abs((np.abs(z) > 3).mean() - 2.6998e-3) < 4 * np.sqrt(2.7e-3 / n)
+    # the two outputs of a pair are uncorrelated
+    assert abs(np.corrcoef(z[0::2], z[1::2])[0, 1]) < 4 / np.sqrt(n / 2)
+
+
+def test_elementary_functions_against_libm():
+    r = np.random.default_rng(1).integers(0, 1 << 32, size=20000, dtype=np.uint64).astype(np.uint32)
+    want = np.log((r.astype(np.float64) + 0.5) / 2.0 ** 32)
+    assert np.abs(gen._ln_unit(r) - want).max() < 1e-12
+    x = np.exp(np.random.default_rng(2).uniform(np.log(1e-10), np.log(50), 20000))
+    assert np.abs(gen._sqrt_heron(x) / np.sqrt(x) - 1).max() < 1e-15
+    th = np.linspace(0, np.pi / 2, 10001)
+    s, c = gen._sincos_quarter(th)
+    assert np.abs(s - np.sin(th)).max() < 1e-15 and np.abs(c - np.cos(th)).max() < 1e-15
+
+
+def test_cast_against_library_casts():
+    b = np.random.default_rng(0).integers(0, 1 << 32, 300000, dtype=np.uint64).astype(np.uint32)
+    b = b[((b >> 23) & 0xFF) != 255]
+    f = b.view(np.float32)
+    t32 = torch.from_numpy(f.copy())
+    ok = np.abs(f) < 65504
+    assert np.array_equal(gen.cast_from_fp32(b[ok], fm.FP16), f[ok].astype(np.float16).view(np.uint16))
+    ok = np.abs(f) < 3e38
+    assert np.array_equal(gen.cast_from_fp32(b, fm.BF16)[ok], t32.to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)[ok])
+    for fmt, tdt, mx in ((fm.E4M3, torch.float8_e4m3fn, 448.0), (fm.E5M2, torch.float8_e5m2, 57344.0)):
+        ok = np.abs(f) <= mx
+        assert ok.sum() > 50000
+        assert np.array_equal(gen.cast_from_fp32(b[ok], fmt), t32[torch.from_numpy(ok)].to(tdt).view(torch.uint8).numpy())
+    # dense sweep of small magnitudes (subnormal targets) for FP8/FP16
+    x = (np.random.default_rng(1).standard_normal(200000) * np.exp(np.random.default_rng(2).uniform(-25, 6, 200000))).astype(np.float32)
+    xb = x.view(np.uint32)
+    assert np.array_equal(gen.cast_from_fp32(xb, fm.FP16), x.astype(np.float16).view(np.uint16))
+    tx = torch.from_numpy(x.copy())
+    ok = np.abs(x) <= 448
+    assert np.array_equal(gen.cast_from_fp32(xb[ok], fm.E4M3), tx[torch.from_numpy(ok)].to(torch.float8_e4m3fn).view(torch.uint8).numpy())
+    # saturation
+    assert gen.cast_from_fp32(np.array([f32_bits(1e6)], dtype=np.uint32), fm.E4M3)[0] == 0x7E
+    assert gen.cast_from_fp32(np.array([f32_bits(-1e9)], dtype=np.uint32), fm.E5M2)[0] == 0xFB
+    assert gen.cast_from_fp32(np.array([f32_bits(1e9)], dtype=np.uint32), fm.FP16)[0] == 0x7BFF
+
+
+def test_normal_scaled_hits_target_maximum():
+    for scope in (gen.SCALE_TENSOR, gen.SCALE_TILE):
+        for fmt, target in ((fm.E4M3, 448.0), (fm.E5M2, 57344.0)):
+            gp = gen.GenParams(family=gen.GEN_NORMAL, seed=0, operand=0, scale_scope=scope, scale_target=target)
+            out = gen.generate(gp, fmt, 256, 0, 16)
+            mags = out & 0x7F
+            top = gen.max_finite_code(fm.FORMATS[fmt])
+            if scope == gen.SCALE_TILE:
+                assert (mags.max(axis=1) == top).all()
+            else:
+                assert mags.max() == top and (mags.max(axis=1) == top).sum() == 1
+            assert not any(fm.decode(int(b), fmt).cls in (fm.NAN, fm.INF) for b in np.unique(out))
+
+
+def test_compare_stats_definition():
+    one = f32_bits(1.0)
+    d0 = np.array([one, one, one, 0x00000000, 0x7FC00000, 0x7FC00000, one, 0x00000001, 0x7F7FFFFF], dtype=np.uint32)
+    d1 = np.array([one, one + 1, one + 5, 0x80000000, 0x7FC00001, one, 0x7FFFFFFF, 0x80000001, 0xFF7FFFFF], dtype=np.uint32)
+    st = stats.compare(d0, d1, index_base=100)
+    assert st["n_compared"] == 9
+    assert st["n_mismatch_bits"] == 8
+    assert st["n_mismatch_nan_equiv"] == 1
+    assert st["first_mismatch_index"] == 101
+    h = st["ulp_hist"]
+    assert h[0] == 3            # equal, +0 vs -0, NaN vs NaN
+    assert h[1] == 1            # distance 1
+    assert h[2] == 1            # 1 vs -1 denormal steps: distance 2
+    assert h[3] == 1            # distance 5
+    assert h[33] == 2           # NaN against a number, both directions
+    assert h[32] == 1 and st["max_ulp_dist"] == 2 * 0x7F7FFFFF
+    assert sum(h) == 9
+    st2 = stats.compare(d0, d0, stats=st, index_base=200)
+    assert st2["n_compared"] == 18 and st2["first_mismatch_index"] == 101 and st2["ulp_hist"][0] == 12
+    empty = stats.compare(d0[:0], d0[:0])
+    assert empty["first_mismatch_index"] == stats.NO_MISMATCH and empty["n_compared"] == 0
+
+
+def test_ordered_distance_matches_float_neighbours():
+    x = np.array([1.0, -1.0, 1e-40, 0.0], dtype=np.float32)
+    up = np.nextafter(x, np.float32(np.inf))
+    d = np.abs(stats.ordered_key(x.view(np.uint32)) - stats.ordered_key(up.view(np.uint32)))
+    assert (d == 1).all()
