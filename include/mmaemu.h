@@ -1,0 +1,250 @@
+/*
+ * libmmaemu -- evaluation of parameterised bit-accurate matrix-multiply-accumulate
+ * arithmetic models on AMD CDNA4 (gfx950), after "Bit-Accurate Modeling of GPU Matrix
+ * Multiply-Accumulate Units" (closed-loop feature probing, CLFP).
+ *
+ * The library is the data-parallel part of CLFP's randomized validation (paper
+ * Sec. 3.1, Step 4): generate random operand tiles on the device, push them through
+ * one or more arithmetic-behaviour models Phi (Sec. 4.1.3) and through the native
+ * matrix instruction, and count bitwise disagreements (Eq. 2).
+ *
+ * Conventions, valid for every call unless stated otherwise
+ *   - Pointers named A, B, C, D, out, dev_* and workspace are DEVICE pointers owned by
+ *     the caller; the library never allocates, frees or retains device memory.
+ *     All other pointers are HOST pointers.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).  Work is
+ *     enqueued on it and the call returns without synchronising.
+ *   - Errors are return codes; nothing aborts or throws.  Arguments are validated on
+ *     the host before anything is launched; on error nothing has been enqueued.
+ *     mmaemu_last_error() gives a thread-local description of the last failure.
+ *   - Matrix layout: a batch of independent tiles, tile-major and K-contiguous for both
+ *     multiplicands: A[batch][m][k], B[batch][n][k], C[batch][m][n], D[batch][m][n];
+ *     batch = 1 is an ordinary GEMM-shaped problem.  Elements are raw bit patterns:
+ *     1 byte (FP8), 2 bytes (FP16, BF16) or 4 bytes (FP32), little endian.
+ */
+#ifndef MMAEMU_H
+#define MMAEMU_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MMAEMU_OK = 0,
+    MMAEMU_ERR_INVALID_ARG = 1, /* NULL pointer, bad enum value, bad struct_size */
+    MMAEMU_ERR_UNSUPPORTED = 2, /* valid in the paper's terms but outside what the kernels cover */
+    MMAEMU_ERR_SHAPE = 3,       /* zero dimension, K not a multiple of L, size over a stated limit */
+    MMAEMU_ERR_HIP = 4,         /* a HIP runtime call failed; text in mmaemu_last_error() */
+    MMAEMU_ERR_NOMEM = 5
+} mmaemu_status;
+
+/* Operand encodings.  FP8 flavours are the OCP ones (E4M3: no infinity, one NaN
+ * mantissa, max 448; E5M2: IEEE-like, max 57344).  Decoding follows the paper's
+ * "exact unnormalized products" (Sec. 4.1.3, T-FDPA): exponent field 0 means
+ * Exp = 1 - bias and no hidden bit, for zeros as well. */
+typedef enum {
+    MMAEMU_FP8_E4M3 = 0,
+    MMAEMU_FP8_E5M2 = 1,
+    MMAEMU_FP16 = 2,
+    MMAEMU_BF16 = 3,
+    MMAEMU_FP32 = 4
+} mmaemu_dtype;
+
+typedef struct {
+    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16}; c = d = FP32 */
+} mmaemu_dtypes;
+
+enum { MMAEMU_C_IN_GROUP = 0, MMAEMU_C_AFTER_EXACT = 1 };
+enum { MMAEMU_ROUND_RNE = 0, MMAEMU_ROUND_RZ = 1 };
+enum { MMAEMU_ALIGN_RZ = 0 };
+
+/*
+ * One arithmetic-behaviour model: the chained FDPA model (paper Algorithm "Phi_FDPA")
+ * around the truncated fused dot-product-add (Algorithm "T-FDPA"):
+ *   L = min(K, group_len)            (group_len = 0: fully fused, L = K)
+ *   d <- c; for each consecutive group of L products: d <- FDPA(a_group, b_group, d)
+ *   FDPA: exact products s_k, e_k = Exp(a_k) + Exp(b_k); e_max over the L products and
+ *         the accumulator; each term aligned at e_max and truncated toward zero to
+ *         frac_bits (F) fractional bits; exact fixed-point sum; conversion rho.
+ * c_mode = MMAEMU_C_AFTER_EXACT keeps the accumulator out of the truncated sum:
+ *   T over the L products only (e_max over the products), d = rho(T * 2^e_max + c)
+ *   with that two-term sum exact (Algorithm "TR-FDPA" without its two RD roundings).
+ * out_round: rho = RNE-FP32 or RZ-FP32 (Table "Conversion functions"); overflow gives
+ *   infinity (RNE) or the largest finite value (RZ); an exact-zero sum gives +0.0.
+ * ftz_in : subnormal A, B and C inputs are replaced by +0.0 first (Algorithm
+ *          "Phi_FTZ-AddMul", FlushSubnormal).
+ * ftz_out: after every group's conversion, |d| < 2^-126 becomes zero of the same
+ *          sign (Algorithm "FTZ-Add/FTZ-Mul", last line).
+ * nan_bits: pattern written for every NaN result (Sec. 4.2; 0x7FFFFFFF on NVIDIA parts).
+ *
+ * Limits: frac_bits <= 40; K <= 2^20; with C_AFTER_EXACT also
+ * frac_bits + 2 + ceil(log2 L) <= 56.
+ */
+typedef struct {
+    uint32_t struct_size;   /* sizeof(mmaemu_model_params), checked */
+    uint32_t group_len;     /* L_max */
+    uint32_t frac_bits;     /* F */
+    uint32_t align_round;   /* MMAEMU_ALIGN_RZ */
+    uint32_t c_mode;
+    uint32_t frac_bits2;    /* reserved (F2 of TR-FDPA), must be 0 */
+    uint32_t out_round;
+    uint32_t out_mant_bits; /* 23 (FP32 output); other values reserved */
+    uint32_t ftz_in, ftz_out;
+    uint32_t nan_bits;
+} mmaemu_model_params;
+
+typedef struct mmaemu_model mmaemu_model; /* opaque, host memory, owned by the library */
+
+/* Validates *params (host) and creates a model.  *out receives the handle.
+ * Errors: INVALID_ARG (NULL, struct_size), UNSUPPORTED (reserved field set, F too large). */
+mmaemu_status mmaemu_model_create(const mmaemu_model_params *params, mmaemu_model **out);
+/* Frees a model.  NULL is accepted.  No kernel keeps a reference to a model after the
+ * enqueueing call has returned. */
+mmaemu_status mmaemu_model_destroy(mmaemu_model *model);
+mmaemu_status mmaemu_model_get_params(const mmaemu_model *model, mmaemu_model_params *out);
+
+/*
+ * D = Phi_model(A, B, C) for `batch` independent m x n x k tiles (paper Eq. 1 / Eq. 3:
+ * every d_ij is an independent dot-product-accumulate).  D may alias C; D may not
+ * overlap A or B.  batch = 0 is a no-op.
+ * Errors: SHAPE (m, n or k zero; k > 2^20; k % L != 0; m*n or batch*m*n overflow),
+ *         UNSUPPORTED (dtype combination), INVALID_ARG, HIP.
+ */
+mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const void *B,
+                                 const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                                 uint64_t batch, mmaemu_dtypes dtypes, void *hip_stream);
+
+/*
+ * Bitwise comparison statistics (paper Eq. 2: Phi(A,B,C) = MMA-Interface(A,B,C) bit for
+ * bit; Sec. 3.1 Step 4).  The struct lives in DEVICE memory and is accumulated with
+ * atomics, so chunked runs add up.
+ *   ulp_hist[0]      ordered-integer distance 0 (equal bits, +0 vs -0, or both NaN)
+ *   ulp_hist[i]      distance in [2^(i-1), 2^i), i = 1..32
+ *   ulp_hist[33]     exactly one of the two values is NaN
+ * Ordered-integer distance: key(b) = b if the sign bit is clear, else -(b & 0x7FFFFFFF);
+ * distance = |key(x) - key(y)|.
+ */
+typedef struct {
+    uint64_t n_compared;
+    uint64_t n_mismatch_bits;      /* bit patterns differ */
+    uint64_t n_mismatch_nan_equiv; /* both NaN, patterns differ (also counted above) */
+    uint64_t first_mismatch_index; /* smallest index_base + i with differing bits; UINT64_MAX if none */
+    uint64_t max_ulp_dist;         /* over pairs of non-NaN values */
+    uint64_t ulp_hist[34];
+} mmaemu_stats;
+
+/* Sets *dev_stats to the empty state (all zero, first_mismatch_index = UINT64_MAX). */
+mmaemu_status mmaemu_stats_reset(mmaemu_stats *dev_stats, void *hip_stream);
+/* Accumulates the comparison of D0[0..count) with D1[0..count) (FP32 bit patterns; `d`
+ * must be MMAEMU_FP32).  count = 0 is a no-op. */
+mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uint64_t index_base,
+                             mmaemu_dtype d, mmaemu_stats *dev_stats, void *hip_stream);
+
+/*
+ * Synthetic operand generation (the input families of Sec. 3.1 Step 4: common
+ * distributions and random bit streams).  Counter-based: element g (global index
+ * (first_tile + t) * elems_per_tile + e) of operand `operand` owns words
+ * g*wpe .. g*wpe + wpe-1 of the stream
+ *   word(w) = Philox4x32-10(counter = (lo32(w>>2), hi32(w>>2), operand, 0),
+ *                           key = (lo32(seed), hi32(seed)))[w & 3],
+ * so any chunk of tiles can be generated independently.  wpe = 2 for FP32 output of
+ * UNIFORM_EXP, else 1.
+ *   ZERO         all-zero bits
+ *   FINITE_BITS  uniform over all finite bit patterns of the format
+ *   UNIFORM_EXP  random sign and mantissa; exponent field uniform over exp_lo..exp_hi,
+ *                plus the value 0 as one more equally likely choice if exp_zero
+ *   RANDOM_BITS  uniform over all bit patterns (NaN and infinities included)
+ *   NORMAL       N(0,1) by Box-Muller on word pairs, evaluated in binary64 with a fixed
+ *                sequence of +, *, / (bit-reproducible on any IEEE-754 machine),
+ *                optionally multiplied by scale_target / max|z| (max over the call's
+ *                elements, or per tile), rounded to binary32 then to the output format
+ *                (RNE, saturating at the largest finite value)
+ */
+enum { MMAEMU_GEN_ZERO = 0, MMAEMU_GEN_FINITE_BITS = 1, MMAEMU_GEN_UNIFORM_EXP = 2,
+       MMAEMU_GEN_RANDOM_BITS = 3, MMAEMU_GEN_NORMAL = 4 };
+enum { MMAEMU_SCALE_NONE = 0, MMAEMU_SCALE_TENSOR = 1, MMAEMU_SCALE_TILE = 2 };
+
+typedef struct {
+    uint32_t struct_size;
+    uint32_t family;
+    uint64_t seed;
+    uint32_t operand;        /* 0 = A, 1 = B, 2 = C: selects the word stream */
+    uint32_t exp_lo, exp_hi; /* UNIFORM_EXP */
+    uint32_t exp_zero;       /* UNIFORM_EXP */
+    uint32_t scale_scope;    /* NORMAL */
+    double scale_target;     /* NORMAL with a scale scope */
+} mmaemu_gen_params;
+
+/* Writes n_tiles * elems_per_tile elements of type `dtype` to `out`.
+ * `workspace`: device memory of at least 8 bytes, 8-byte aligned, needed (and
+ * overwritten) only for NORMAL with MMAEMU_SCALE_TENSOR; may be NULL otherwise.
+ * Errors: INVALID_ARG, UNSUPPORTED (exponent range outside the format), SHAPE
+ * (elems_per_tile = 0 or total elements >= 2^62). */
+mmaemu_status mmaemu_generate(const mmaemu_gen_params *gen, void *out, mmaemu_dtype dtype,
+                              uint64_t elems_per_tile, uint64_t first_tile, uint64_t n_tiles,
+                              void *workspace, void *hip_stream);
+
+/*
+ * Native-instruction probe: the device under test of the closed loop (paper Sec. 3.3:
+ * instruction-level MMA interfaces through intrinsics).  Runs one real v_mfma
+ * instruction per tile on the same operand layout as mmaemu_emulate_mma:
+ * A[batch][M][k], B[batch][N][k], C/D[batch][M][N] (FP32) with M, N and K_native fixed by
+ * the instruction; k <= K_native, the missing k positions are fed as zeros.
+ */
+typedef enum {
+    MMAEMU_MFMA_F32_16X16X16_F16 = 0,
+    MMAEMU_MFMA_F32_16X16X16_BF16 = 1,
+    MMAEMU_MFMA_F32_32X32X8_F16 = 2,
+    MMAEMU_MFMA_F32_32X32X8_BF16 = 3,
+    MMAEMU_MFMA_F32_16X16X32_F16 = 4,
+    MMAEMU_MFMA_F32_16X16X32_BF16 = 5,
+    MMAEMU_MFMA_F32_16X16X32_FP8_FP8 = 6, /* A E4M3, B E4M3 */
+    MMAEMU_MFMA_F32_16X16X32_FP8_BF8 = 7, /* A E4M3, B E5M2 */
+    MMAEMU_MFMA_F32_16X16X32_BF8_FP8 = 8, /* A E5M2, B E4M3 */
+    MMAEMU_MFMA_F32_16X16X32_BF8_BF8 = 9, /* A E5M2, B E5M2 */
+    MMAEMU_MFMA_COUNT = 10
+} mmaemu_mfma_instr;
+
+/* Shape and operand types of an instruction (host-side query). */
+mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n, uint32_t *k_native,
+                               mmaemu_dtype *a, mmaemu_dtype *b);
+mmaemu_status mmaemu_mfma_probe(mmaemu_mfma_instr instr, const void *A, const void *B, const void *C,
+                                void *D, uint32_t k, uint64_t batch, void *hip_stream);
+
+/*
+ * Error of an emulated D against the exact dot product on a sample (methodology of the
+ * paper's Sec. 6.2.4: deviation of a model's output from the real result; here the real
+ * result is the exact integer dot product, C = 0).  One m x n output, A[m][k], B[n][k],
+ * both FP8; flattened output index i*n + j is sampled when it is a multiple of `stride`.
+ * With R = RNE-FP32(exact):
+ *   n_equal_rne       D bits == R bits
+ *   n_above / n_below ordered key of D greater / less than that of R
+ *   ulp_hist          |key(D) - key(R)| bucketed as in mmaemu_stats
+ *   sum/max_abs_err   |D - exact| (binary64, accumulation order unspecified)
+ *   sum/max_rel_err   |D - exact| / |exact| over samples with exact != 0
+ *   sum_signed_err    D - exact
+ * Accumulates into *dev_err (device memory).  D must hold no NaN/Inf at sampled places
+ * (such samples are skipped and counted in n_skipped).
+ */
+typedef struct {
+    uint64_t n_samples, n_equal_rne, n_above, n_below, n_skipped;
+    uint64_t ulp_hist[34];
+    double sum_abs_err, max_abs_err, sum_rel_err, max_rel_err, sum_signed_err;
+} mmaemu_err_stats;
+
+mmaemu_status mmaemu_err_stats_reset(mmaemu_err_stats *dev_err, void *hip_stream);
+mmaemu_status mmaemu_exact_dot_sample(const void *A, const void *B, const void *D, uint32_t m,
+                                      uint32_t n, uint32_t k, mmaemu_dtypes dtypes, uint64_t stride,
+                                      mmaemu_err_stats *dev_err, void *hip_stream);
+
+const char *mmaemu_status_string(mmaemu_status s);
+const char *mmaemu_last_error(void); /* thread-local, never NULL */
+/* Library version as major*10000 + minor*100 + patch. */
+uint32_t mmaemu_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MMAEMU_H */

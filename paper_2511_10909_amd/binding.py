@@ -1,0 +1,198 @@
+"""ctypes binding of libmmaemu: same names as the C entry points, argument marshalling only.
+
+Device memory and streams come from PyTorch (tensors are passed as their data_ptr(), the
+stream as torch's current HIP stream handle); every computation happens inside the library.
+"""
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmmaemu.so")
+
+E4M3, E5M2, FP16, BF16, FP32 = 0, 1, 2, 3, 4
+C_IN_GROUP, C_AFTER_EXACT = 0, 1
+RNE, RZ = 0, 1
+GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
+SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
+(MFMA_F32_16X16X16_F16, MFMA_F32_16X16X16_BF16, MFMA_F32_32X32X8_F16, MFMA_F32_32X32X8_BF16,
+ MFMA_F32_16X16X32_F16, MFMA_F32_16X16X32_BF16, MFMA_F32_16X16X32_FP8_FP8, MFMA_F32_16X16X32_FP8_BF8,
+ MFMA_F32_16X16X32_BF8_FP8, MFMA_F32_16X16X32_BF8_BF8) = range(10)
+ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4}
+NO_MISMATCH = (1 << 64) - 1
+
+
+class MmaemuError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("libmmaemu: %s (status %d): %s" % (_status_string(status), status, text))
+        self.status = status
+
+
+class ModelParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in
+                ("struct_size", "group_len", "frac_bits", "align_round", "c_mode", "frac_bits2", "out_round",
+                 "out_mant_bits", "ftz_in", "ftz_out", "nan_bits")]
+
+
+class Dtypes(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in ("a", "b", "c", "d")]
+
+
+class GenParams(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("family", ctypes.c_uint32), ("seed", ctypes.c_uint64),
+                ("operand", ctypes.c_uint32), ("exp_lo", ctypes.c_uint32), ("exp_hi", ctypes.c_uint32),
+                ("exp_zero", ctypes.c_uint32), ("scale_scope", ctypes.c_uint32), ("scale_target", ctypes.c_double)]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("n_compared", ctypes.c_uint64), ("n_mismatch_bits", ctypes.c_uint64),
+                ("n_mismatch_nan_equiv", ctypes.c_uint64), ("first_mismatch_index", ctypes.c_uint64),
+                ("max_ulp_dist", ctypes.c_uint64), ("ulp_hist", ctypes.c_uint64 * 34)]
+
+
+class ErrStats(ctypes.Structure):
+    _fields_ = [("n_samples", ctypes.c_uint64), ("n_equal_rne", ctypes.c_uint64), ("n_above", ctypes.c_uint64),
+                ("n_below", ctypes.c_uint64), ("n_skipped", ctypes.c_uint64), ("ulp_hist", ctypes.c_uint64 * 34),
+                ("sum_abs_err", ctypes.c_double), ("max_abs_err", ctypes.c_double), ("sum_rel_err", ctypes.c_double),
+                ("max_rel_err", ctypes.c_double), ("sum_signed_err", ctypes.c_double)]
+
+
+STATS_BYTES = ctypes.sizeof(Stats)
+ERR_STATS_BYTES = ctypes.sizeof(ErrStats)
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libmmaemu.so is not built (%s); run `python -m paper_2511_10909_amd.build` or "
+                      "__graft_entry__.build() first -- there is no fallback path" % LIB_PATH)
+_lib = ctypes.CDLL(LIB_PATH)
+
+_vp, _u32, _u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
+_lib.mmaemu_status_string.restype = ctypes.c_char_p
+_lib.mmaemu_status_string.argtypes = [ctypes.c_int]
+_lib.mmaemu_last_error.restype = ctypes.c_char_p
+_lib.mmaemu_version.restype = _u32
+_lib.mmaemu_model_create.argtypes = [ctypes.POINTER(ModelParams), ctypes.POINTER(_vp)]
+_lib.mmaemu_model_destroy.argtypes = [_vp]
+_lib.mmaemu_model_get_params.argtypes = [_vp, ctypes.POINTER(ModelParams)]
+_lib.mmaemu_emulate_mma.argtypes = [_vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u64, Dtypes, _vp]
+_lib.mmaemu_stats_reset.argtypes = [_vp, _vp]
+_lib.mmaemu_compare.argtypes = [_vp, _vp, _u64, _u64, ctypes.c_int, _vp, _vp]
+_lib.mmaemu_generate.argtypes = [ctypes.POINTER(GenParams), _vp, ctypes.c_int, _u64, _u64, _u64, _vp, _vp]
+_lib.mmaemu_mfma_info.argtypes = [ctypes.c_int] + [ctypes.POINTER(_u32)] * 3 + [ctypes.POINTER(ctypes.c_int)] * 2
+_lib.mmaemu_mfma_probe.argtypes = [ctypes.c_int, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
+_lib.mmaemu_err_stats_reset.argtypes = [_vp, _vp]
+_lib.mmaemu_exact_dot_sample.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, Dtypes, _u64, _vp, _vp]
+
+
+def _status_string(s):
+    return _lib.mmaemu_status_string(int(s)).decode()
+
+
+def _check(status):
+    if status != 0:
+        raise MmaemuError(status, _lib.mmaemu_last_error().decode())
+
+
+def _ptr(x):
+    """Device pointer of a torch tensor (or a raw integer address / None)."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def version():
+    return int(_lib.mmaemu_version())
+
+
+def last_error():
+    return _lib.mmaemu_last_error().decode()
+
+
+def model_create(group_len=0, frac_bits=24, c_mode=C_IN_GROUP, out_round=RNE, ftz_in=False, ftz_out=False,
+                 nan_bits=0x7FC00000, align_round=0, frac_bits2=0, out_mant_bits=23, struct_size=None):
+    p = ModelParams(ctypes.sizeof(ModelParams) if struct_size is None else struct_size, group_len, frac_bits,
+                    align_round, c_mode, frac_bits2, out_round, out_mant_bits, int(ftz_in), int(ftz_out), nan_bits)
+    h = _vp()
+    _check(_lib.mmaemu_model_create(ctypes.byref(p), ctypes.byref(h)))
+    return h
+
+
+def model_destroy(model):
+    _check(_lib.mmaemu_model_destroy(model))
+
+
+def model_get_params(model):
+    p = ModelParams()
+    _check(_lib.mmaemu_model_get_params(model, ctypes.byref(p)))
+    return {n: getattr(p, n) for n, _ in ModelParams._fields_}
+
+
+def emulate_mma(model, A, B, C, D, m, n, k, batch, dtypes, stream=None):
+    dt = dtypes if isinstance(dtypes, Dtypes) else Dtypes(*dtypes)
+    _check(_lib.mmaemu_emulate_mma(model, _ptr(A), _ptr(B), _ptr(C), _ptr(D), m, n, k, batch, dt, _stream(stream)))
+
+
+def stats_reset(dev_stats, stream=None):
+    _check(_lib.mmaemu_stats_reset(_ptr(dev_stats), _stream(stream)))
+
+
+def compare(D0, D1, count, dev_stats, index_base=0, d=FP32, stream=None):
+    _check(_lib.mmaemu_compare(_ptr(D0), _ptr(D1), count, index_base, d, _ptr(dev_stats), _stream(stream)))
+
+
+def generate(out, dtype, elems_per_tile, first_tile, n_tiles, family, seed=0, operand=0, exp_lo=0, exp_hi=0,
+             exp_zero=False, scale_scope=SCALE_NONE, scale_target=1.0, workspace=None, stream=None, struct_size=None):
+    g = GenParams(ctypes.sizeof(GenParams) if struct_size is None else struct_size, family, seed, operand,
+                  exp_lo, exp_hi, int(exp_zero), scale_scope, scale_target)
+    _check(_lib.mmaemu_generate(ctypes.byref(g), _ptr(out), dtype, elems_per_tile, first_tile, n_tiles,
+                                _ptr(workspace), _stream(stream)))
+
+
+def mfma_info(instr):
+    m, n, k = _u32(), _u32(), _u32()
+    a, b = ctypes.c_int(), ctypes.c_int()
+    _check(_lib.mmaemu_mfma_info(instr, ctypes.byref(m), ctypes.byref(n), ctypes.byref(k), ctypes.byref(a), ctypes.byref(b)))
+    return dict(m=m.value, n=n.value, k=k.value, a=a.value, b=b.value)
+
+
+def mfma_probe(instr, A, B, C, D, k, batch, stream=None):
+    _check(_lib.mmaemu_mfma_probe(instr, _ptr(A), _ptr(B), _ptr(C), _ptr(D), k, batch, _stream(stream)))
+
+
+def err_stats_reset(dev_err, stream=None):
+    _check(_lib.mmaemu_err_stats_reset(_ptr(dev_err), _stream(stream)))
+
+
+def exact_dot_sample(A, B, D, m, n, k, dtypes, stride, dev_err, stream=None):
+    dt = dtypes if isinstance(dtypes, Dtypes) else Dtypes(*dtypes)
+    _check(_lib.mmaemu_exact_dot_sample(_ptr(A), _ptr(B), _ptr(D), m, n, k, dt, stride, _ptr(dev_err), _stream(stream)))
+
+
+# ---- unpacking of the device-side result structs (host copies; no arithmetic) -----------
+
+def _unpack(struct_type, dev_tensor):
+    raw = bytes(dev_tensor.cpu().numpy().tobytes())
+    st = struct_type.from_buffer_copy(raw[:ctypes.sizeof(struct_type)])
+    out = {}
+    for name, typ in struct_type._fields_:
+        v = getattr(st, name)
+        out[name] = list(v) if hasattr(v, "__len__") else v
+    return out
+
+
+def read_stats(dev_stats):
+    """Synchronising copy of a device mmaemu_stats (a uint8 tensor of STATS_BYTES) to a dict."""
+    return _unpack(Stats, dev_stats)
+
+
+def read_err_stats(dev_err):
+    return _unpack(ErrStats, dev_err)

@@ -1,0 +1,260 @@
+// C-ABI entry points of libmmaemu: argument validation, error reporting, dispatch.
+// All validation happens here, on the host, before any kernel is enqueued.
+#include "common.hpp"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+struct mmaemu_model {
+    uint32_t magic;
+    mmaemu_model_params params;
+};
+
+namespace mmaemu {
+
+static constexpr uint32_t MODEL_MAGIC = 0x4D4D4145u;   // "MMAE"
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+mmaemu_status hip_fail(hipError_t e, const char *what)
+{
+    set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
+    return MMAEMU_ERR_HIP;
+}
+
+static bool is_ab_type(uint32_t t) { return t <= MMAEMU_BF16; }
+
+static uint32_t ceil_log2(uint32_t x)
+{
+    uint32_t l = 0;
+    while ((1ull << l) < x) ++l;
+    return l;
+}
+
+} // namespace mmaemu
+
+using namespace mmaemu;
+
+extern "C" {
+
+const char *mmaemu_status_string(mmaemu_status s)
+{
+    switch (s) {
+    case MMAEMU_OK: return "ok";
+    case MMAEMU_ERR_INVALID_ARG: return "invalid argument";
+    case MMAEMU_ERR_UNSUPPORTED: return "unsupported";
+    case MMAEMU_ERR_SHAPE: return "bad shape";
+    case MMAEMU_ERR_HIP: return "HIP runtime error";
+    case MMAEMU_ERR_NOMEM: return "out of memory";
+    }
+    return "unknown status";
+}
+
+const char *mmaemu_last_error(void) { return g_err; }
+
+uint32_t mmaemu_version(void) { return 100; }
+
+mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **out)
+{
+    if (!p || !out) { set_error("model_create: NULL argument"); return MMAEMU_ERR_INVALID_ARG; }
+    *out = nullptr;
+    if (p->struct_size != sizeof(mmaemu_model_params)) {
+        set_error("model_create: struct_size %u, expected %zu", p->struct_size, sizeof(mmaemu_model_params));
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (p->c_mode > MMAEMU_C_AFTER_EXACT || p->out_round > MMAEMU_ROUND_RZ || p->ftz_in > 1 || p->ftz_out > 1) {
+        set_error("model_create: enum field out of range");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (p->align_round != MMAEMU_ALIGN_RZ || p->frac_bits2 != 0 || p->out_mant_bits != 23) {
+        set_error("model_create: only RZ alignment, frac_bits2 = 0 and FP32 output (out_mant_bits = 23) are supported");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if (p->frac_bits > 40) { set_error("model_create: frac_bits %u > 40", p->frac_bits); return MMAEMU_ERR_UNSUPPORTED; }
+    if (p->group_len > (1u << 20)) { set_error("model_create: group_len %u > 2^20", p->group_len); return MMAEMU_ERR_UNSUPPORTED; }
+    mmaemu_model *m = new (std::nothrow) mmaemu_model;
+    if (!m) { set_error("model_create: allocation failed"); return MMAEMU_ERR_NOMEM; }
+    m->magic = MODEL_MAGIC;
+    m->params = *p;
+    *out = m;
+    return MMAEMU_OK;
+}
+
+mmaemu_status mmaemu_model_destroy(mmaemu_model *m)
+{
+    if (!m) return MMAEMU_OK;
+    if (m->magic != MODEL_MAGIC) { set_error("model_destroy: not a model handle"); return MMAEMU_ERR_INVALID_ARG; }
+    m->magic = 0;
+    delete m;
+    return MMAEMU_OK;
+}
+
+mmaemu_status mmaemu_model_get_params(const mmaemu_model *m, mmaemu_model_params *out)
+{
+    if (!m || !out || m->magic != MODEL_MAGIC) { set_error("model_get_params: bad argument"); return MMAEMU_ERR_INVALID_ARG; }
+    *out = m->params;
+    return MMAEMU_OK;
+}
+
+mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const void *B, const void *C, void *D,
+                                 uint32_t m, uint32_t n, uint32_t k, uint64_t batch, mmaemu_dtypes dt,
+                                 void *hip_stream)
+{
+    if (!model || model->magic != MODEL_MAGIC) { set_error("emulate_mma: bad model handle"); return MMAEMU_ERR_INVALID_ARG; }
+    if (m == 0 || n == 0 || k == 0) { set_error("emulate_mma: zero dimension (m=%u n=%u k=%u)", m, n, k); return MMAEMU_ERR_SHAPE; }
+    if (k > (1u << 20)) { set_error("emulate_mma: k=%u > 2^20", k); return MMAEMU_ERR_SHAPE; }
+    if (dt.a > MMAEMU_FP32 || dt.b > MMAEMU_FP32 || dt.c > MMAEMU_FP32 || dt.d > MMAEMU_FP32) {
+        set_error("emulate_mma: dtype out of range");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (!is_ab_type(dt.a) || !is_ab_type(dt.b) || dt.c != MMAEMU_FP32 || dt.d != MMAEMU_FP32) {
+        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16} and c = d = FP32");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    const mmaemu_model_params &mp = model->params;
+    const uint32_t L = (mp.group_len == 0 || mp.group_len > k) ? k : mp.group_len;
+    if (k % L) { set_error("emulate_mma: k=%u is not a multiple of the group length L=%u", k, L); return MMAEMU_ERR_SHAPE; }
+    if (mp.c_mode == MMAEMU_C_AFTER_EXACT && mp.frac_bits + 2 + ceil_log2(L) > 56) {
+        set_error("emulate_mma: C_AFTER_EXACT needs frac_bits + 2 + ceil(log2 L) <= 56");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    const uint64_t mn = (uint64_t)m * n;
+    if (batch && (mn > (1ull << 40) || batch > (1ull << 62) / mn || batch * mn > (1ull << 48) ||
+                  batch * (uint64_t)(m > n ? m : n) > (1ull << 62) / k)) {
+        set_error("emulate_mma: problem too large");
+        return MMAEMU_ERR_SHAPE;
+    }
+    if (batch == 0) return MMAEMU_OK;
+    if (!A || !B || !C || !D) { set_error("emulate_mma: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+    ModelArgs ma;
+    ma.L = L;
+    ma.F = (int32_t)mp.frac_bits;
+    ma.c_mode = mp.c_mode;
+    ma.out_round = mp.out_round;
+    ma.ftz_in = mp.ftz_in;
+    ma.ftz_out = mp.ftz_out;
+    ma.nan_bits = mp.nan_bits;
+    return launch_emulate(ma, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream);
+}
+
+mmaemu_status mmaemu_stats_reset(mmaemu_stats *st, void *hip_stream)
+{
+    if (!st) { set_error("stats_reset: NULL"); return MMAEMU_ERR_INVALID_ARG; }
+    return launch_stats_reset(st, (hipStream_t)hip_stream);
+}
+
+mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uint64_t index_base, mmaemu_dtype d,
+                             mmaemu_stats *st, void *hip_stream)
+{
+    if (d != MMAEMU_FP32) { set_error("compare: only FP32 outputs"); return MMAEMU_ERR_UNSUPPORTED; }
+    if (!st) { set_error("compare: NULL stats"); return MMAEMU_ERR_INVALID_ARG; }
+    if (count == 0) return MMAEMU_OK;
+    if (!D0 || !D1) { set_error("compare: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+    if (((uintptr_t)D0 | (uintptr_t)D1) & 3) { set_error("compare: pointers must be 4-byte aligned"); return MMAEMU_ERR_INVALID_ARG; }
+    if (count > (1ull << 48)) { set_error("compare: count too large"); return MMAEMU_ERR_SHAPE; }
+    return launch_compare((const uint32_t *)D0, (const uint32_t *)D1, count, index_base, st, (hipStream_t)hip_stream);
+}
+
+mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtype dtype, uint64_t ept,
+                              uint64_t first_tile, uint64_t n_tiles, void *workspace, void *hip_stream)
+{
+    if (!g) { set_error("generate: NULL params"); return MMAEMU_ERR_INVALID_ARG; }
+    if (g->struct_size != sizeof(mmaemu_gen_params)) {
+        set_error("generate: struct_size %u, expected %zu", g->struct_size, sizeof(mmaemu_gen_params));
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if ((uint32_t)dtype > MMAEMU_FP32 || g->family > MMAEMU_GEN_NORMAL || g->scale_scope > MMAEMU_SCALE_TILE) {
+        set_error("generate: enum out of range");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (ept == 0) { set_error("generate: elems_per_tile = 0"); return MMAEMU_ERR_SHAPE; }
+    if (n_tiles > (1ull << 62) / ept || first_tile > (1ull << 62) / ept || (first_tile + n_tiles) > (1ull << 62) / ept) {
+        set_error("generate: element index range too large");
+        return MMAEMU_ERR_SHAPE;
+    }
+    const FmtInfo f = fmt_info(dtype);
+    if (g->family == MMAEMU_GEN_UNIFORM_EXP) {
+        const uint32_t emax_field = (1u << f.ebits) - 1u;
+        if (g->exp_lo > g->exp_hi || g->exp_hi > emax_field) {
+            set_error("generate: exponent-field range %u..%u outside 0..%u", g->exp_lo, g->exp_hi, emax_field);
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+    }
+    if (g->family == MMAEMU_GEN_NORMAL && g->scale_scope != MMAEMU_SCALE_NONE && !(g->scale_target > 0.0)) {
+        set_error("generate: scale_target must be positive");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (n_tiles == 0) return MMAEMU_OK;
+    if (!out) { set_error("generate: NULL output"); return MMAEMU_ERR_INVALID_ARG; }
+    if ((uintptr_t)out & (uintptr_t)(f.width / 8 - 1)) { set_error("generate: output not aligned to its element size"); return MMAEMU_ERR_INVALID_ARG; }
+    if (g->family == MMAEMU_GEN_NORMAL && g->scale_scope == MMAEMU_SCALE_TENSOR) {
+        if (!workspace || ((uintptr_t)workspace & 7)) { set_error("generate: SCALE_TENSOR needs an 8-byte aligned workspace"); return MMAEMU_ERR_INVALID_ARG; }
+    }
+    return launch_generate(*g, out, dtype, ept, first_tile, n_tiles, workspace, (hipStream_t)hip_stream);
+}
+
+mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n, uint32_t *k_native, mmaemu_dtype *a,
+                               mmaemu_dtype *b)
+{
+    static const struct { uint32_t m, n, k; mmaemu_dtype a, b; } T[MMAEMU_MFMA_COUNT] = {
+        {16, 16, 16, MMAEMU_FP16, MMAEMU_FP16},         {16, 16, 16, MMAEMU_BF16, MMAEMU_BF16},
+        {32, 32, 8, MMAEMU_FP16, MMAEMU_FP16},          {32, 32, 8, MMAEMU_BF16, MMAEMU_BF16},
+        {16, 16, 32, MMAEMU_FP16, MMAEMU_FP16},         {16, 16, 32, MMAEMU_BF16, MMAEMU_BF16},
+        {16, 16, 32, MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3}, {16, 16, 32, MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2},
+        {16, 16, 32, MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3}, {16, 16, 32, MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2}};
+    if ((uint32_t)instr >= MMAEMU_MFMA_COUNT) { set_error("mfma_info: unknown instruction %u", (uint32_t)instr); return MMAEMU_ERR_INVALID_ARG; }
+    if (m) *m = T[instr].m;
+    if (n) *n = T[instr].n;
+    if (k_native) *k_native = T[instr].k;
+    if (a) *a = T[instr].a;
+    if (b) *b = T[instr].b;
+    return MMAEMU_OK;
+}
+
+mmaemu_status mmaemu_mfma_probe(mmaemu_mfma_instr instr, const void *A, const void *B, const void *C, void *D, uint32_t k,
+                                uint64_t batch, void *hip_stream)
+{
+    uint32_t m, n, kn;
+    mmaemu_dtype ta, tb;
+    mmaemu_status st = mmaemu_mfma_info(instr, &m, &n, &kn, &ta, &tb);
+    if (st != MMAEMU_OK) return st;
+    if (k == 0 || k > kn) { set_error("mfma_probe: k=%u outside 1..%u", k, kn); return MMAEMU_ERR_SHAPE; }
+    if (batch > (1ull << 40)) { set_error("mfma_probe: batch too large"); return MMAEMU_ERR_SHAPE; }
+    if (batch == 0) return MMAEMU_OK;
+    if (!A || !B || !C || !D) { set_error("mfma_probe: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+    const uintptr_t ab_align = (uintptr_t)(fmt_info(ta).width / 8 - 1);
+    if (((uintptr_t)A | (uintptr_t)B) & ab_align || ((uintptr_t)C | (uintptr_t)D) & 3) {
+        set_error("mfma_probe: misaligned pointer");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    return launch_mfma_probe((uint32_t)instr, A, B, C, D, k, batch, (hipStream_t)hip_stream);
+}
+
+mmaemu_status mmaemu_err_stats_reset(mmaemu_err_stats *st, void *hip_stream)
+{
+    if (!st) { set_error("err_stats_reset: NULL"); return MMAEMU_ERR_INVALID_ARG; }
+    return launch_err_stats_reset(st, (hipStream_t)hip_stream);
+}
+
+mmaemu_status mmaemu_exact_dot_sample(const void *A, const void *B, const void *D, uint32_t m, uint32_t n, uint32_t k,
+                                      mmaemu_dtypes dt, uint64_t stride, mmaemu_err_stats *st, void *hip_stream)
+{
+    if (!A || !B || !D || !st) { set_error("exact_dot_sample: NULL pointer"); return MMAEMU_ERR_INVALID_ARG; }
+    if (m == 0 || n == 0 || k == 0 || k > (1u << 20) || stride == 0) { set_error("exact_dot_sample: bad shape or stride"); return MMAEMU_ERR_SHAPE; }
+    if (dt.a > MMAEMU_FP8_E5M2 || dt.b > MMAEMU_FP8_E5M2 || dt.d != MMAEMU_FP32) {
+        set_error("exact_dot_sample: operands must be FP8 and D FP32");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    return launch_exact_dot_sample(A, B, (const uint32_t *)D, m, n, k, dt.a, dt.b, stride, st, (hipStream_t)hip_stream);
+}
+
+} // extern "C"

@@ -1,0 +1,128 @@
+// Internal declarations shared by the translation units of libmmaemu.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "mmaemu.h"
+
+namespace mmaemu {
+
+// Operand encodings (OCP FP8, IEEE binary16, bfloat16, binary32).
+template <int T> struct Fmt;
+template <> struct Fmt<MMAEMU_FP8_E4M3> { static constexpr int EB = 4, MB = 3, BIAS = 7, W = 8; static constexpr bool IEEE = false; using elem = uint8_t; };
+template <> struct Fmt<MMAEMU_FP8_E5M2> { static constexpr int EB = 5, MB = 2, BIAS = 15, W = 8; static constexpr bool IEEE = true; using elem = uint8_t; };
+template <> struct Fmt<MMAEMU_FP16> { static constexpr int EB = 5, MB = 10, BIAS = 15, W = 16; static constexpr bool IEEE = true; using elem = uint16_t; };
+template <> struct Fmt<MMAEMU_BF16> { static constexpr int EB = 8, MB = 7, BIAS = 127, W = 16; static constexpr bool IEEE = true; using elem = uint16_t; };
+template <> struct Fmt<MMAEMU_FP32> { static constexpr int EB = 8, MB = 23, BIAS = 127, W = 32; static constexpr bool IEEE = true; using elem = uint32_t; };
+
+struct FmtInfo { int ebits, mbits, bias, width; bool ieee; };
+inline FmtInfo fmt_info(uint32_t t)
+{
+    switch (t) {
+    case MMAEMU_FP8_E4M3: return {4, 3, 7, 8, false};
+    case MMAEMU_FP8_E5M2: return {5, 2, 15, 8, true};
+    case MMAEMU_FP16: return {5, 10, 15, 16, true};
+    case MMAEMU_BF16: return {8, 7, 127, 16, true};
+    default: return {8, 23, 127, 32, true};
+    }
+}
+
+// Model parameters as the kernels take them (by value).
+struct ModelArgs {
+    uint32_t L;          // group length actually used: min(K, L_max)
+    int32_t F;           // fractional bits of the aligned terms
+    uint32_t c_mode, out_round, ftz_in, ftz_out, nan_bits;
+};
+
+// error plumbing (api.hip)
+void set_error(const char *fmt, ...);
+mmaemu_status hip_fail(hipError_t e, const char *what);
+#define MMAEMU_HIP(call)                                            \
+    do {                                                            \
+        hipError_t e__ = (call);                                    \
+        if (e__ != hipSuccess) return ::mmaemu::hip_fail(e__, #call); \
+    } while (0)
+
+// launchers implemented in the kernel translation units; all validate nothing (the
+// entry points do) and return the launch status
+mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
+                             uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb,
+                             hipStream_t s);
+mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
+                                     uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
+                                     uint32_t tb, hipStream_t s);
+mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s);
+mmaemu_status launch_compare(const uint32_t *d0, const uint32_t *d1, uint64_t count, uint64_t base,
+                             mmaemu_stats *st, hipStream_t s);
+mmaemu_status launch_generate(const mmaemu_gen_params &g, void *out, uint32_t dtype, uint64_t ept,
+                              uint64_t first_tile, uint64_t n_tiles, void *workspace, hipStream_t s);
+mmaemu_status launch_mfma_probe(uint32_t instr, const void *A, const void *B, const void *C, void *D,
+                                uint32_t k, uint64_t batch, hipStream_t s);
+mmaemu_status launch_err_stats_reset(mmaemu_err_stats *st, hipStream_t s);
+mmaemu_status launch_exact_dot_sample(const void *A, const void *B, const uint32_t *D, uint32_t m, uint32_t n,
+                                      uint32_t k, uint32_t ta, uint32_t tb, uint64_t stride,
+                                      mmaemu_err_stats *st, hipStream_t s);
+
+// ---- device helpers -----------------------------------------------------------------
+#if defined(__HIPCC__)
+
+// rho (paper Table "Conversion functions"): (-1)^neg * mag * 2^lsb -> binary32 bits, RNE or
+// RZ.  `sticky` != 0 means the true magnitude lies strictly between mag and mag + 1 units;
+// callers only set it when mag >= 2^60, far above the rounding position.  mag != 0.
+__device__ __forceinline__ uint32_t round_to_fp32(uint32_t neg, uint64_t mag, int lsb, uint32_t sticky, uint32_t mode)
+{
+    const int bl = 64 - __builtin_clzll(mag);
+    const int e = bl - 1 + lsb;
+    int eg = e < -126 ? -126 : e;
+    const int sh = eg - 23 - lsb;
+    uint64_t n;
+    uint32_t half = 0, rest = sticky;
+    if (sh <= 0) {
+        n = mag << (-sh);
+    } else if (sh >= 64) {
+        n = 0;
+        if (sh == 64) { half = (uint32_t)(mag >> 63); rest |= (mag << 1) != 0; }
+        else rest |= 1u;
+    } else {
+        n = mag >> sh;
+        half = (uint32_t)(mag >> (sh - 1)) & 1u;
+        rest |= (mag & ((1ull << (sh - 1)) - 1ull)) != 0;
+    }
+    if (mode == MMAEMU_ROUND_RNE && half && (rest || (n & 1ull))) n += 1;
+    if (n == (1ull << 24)) { n >>= 1; eg += 1; }
+    uint32_t out;
+    if (eg > 127) out = (mode == MMAEMU_ROUND_RNE) ? 0x7F800000u : 0x7F7FFFFFu;
+    else if (n < (1ull << 23)) out = (uint32_t)n;
+    else out = ((uint32_t)(eg + 127) << 23) | ((uint32_t)n & 0x7FFFFFu);
+    return (neg << 31) | out;
+}
+
+// rho(x + y) with the two-term sum exact: x = (-1)^sx mx 2^lx, y likewise; magnitudes
+// below 2^60.  Both are left-justified to bit 62; the smaller is shifted down with the
+// lost bits remembered, which happens only when the gap exceeds 3 places, i.e. when at
+// most one leading bit can cancel, so the remembered bits stay below the rounding place.
+__device__ __forceinline__ uint32_t add_exact_round(uint32_t sx, uint64_t mx, int lx, uint32_t sy, uint64_t my, int ly, uint32_t mode)
+{
+    if (mx == 0 && my == 0) return 0u;
+    if (mx == 0) return round_to_fp32(sy, my, ly, 0, mode);
+    if (my == 0) return round_to_fp32(sx, mx, lx, 0, mode);
+    int nx = __builtin_clzll(mx) - 1, ny = __builtin_clzll(my) - 1;
+    mx <<= nx; lx -= nx;
+    my <<= ny; ly -= ny;
+    if (lx < ly || (lx == ly && mx < my)) {
+        uint64_t tm = mx; mx = my; my = tm;
+        int tl = lx; lx = ly; ly = tl;
+        uint32_t ts = sx; sx = sy; sy = ts;
+    }
+    const int g = lx - ly;                 // >= 0; |x| >= |y|
+    uint64_t ys; uint32_t lost;
+    if (g >= 64) { ys = 0; lost = 1; }
+    else { ys = my >> g; lost = (g > 0) && ((my & ((1ull << g) - 1ull)) != 0); }
+    uint64_t r;
+    if (sx == sy) r = mx + ys;             // true sum in [r, r+1)
+    else r = mx - ys - lost;               // true difference in (r, r+1) when lost, == r otherwise
+    if (r == 0 && !lost) return 0u;        // exact cancellation -> +0.0
+    return round_to_fp32(sx, r, lx, lost, mode);
+}
+
+#endif // __HIPCC__
+} // namespace mmaemu

@@ -1,0 +1,132 @@
+// Bitwise comparison of two FP32 outputs with mismatch statistics (paper Eq. 2 and
+// Sec. 3.1 Step 4: the model must reproduce the interface bit by bit).
+//
+// HBM-bound: 8 bytes read per compared pair.  Each lane handles four consecutive
+// elements (one 128-bit load per input); counters are gathered per workgroup in LDS and
+// flushed with one global atomic per non-zero counter per workgroup.
+#include "common.hpp"
+
+namespace mmaemu {
+
+__global__ void stats_reset_kernel(mmaemu_stats *st)
+{
+    uint64_t *w = reinterpret_cast<uint64_t *>(st);
+    const uint32_t i = threadIdx.x;
+    if (i < sizeof(mmaemu_stats) / 8) w[i] = (i == 3) ? ~0ull : 0ull;   // word 3: first_mismatch_index
+}
+
+__device__ __forceinline__ int64_t ordered_key(uint32_t b)
+{
+    return (b & 0x80000000u) ? -(int64_t)(b & 0x7FFFFFFFu) : (int64_t)b;
+}
+
+struct Local {
+    uint32_t mism, nan_equiv;
+    uint64_t first, maxd;
+};
+
+__device__ __forceinline__ void one_pair(uint32_t x, uint32_t y, uint64_t idx, Local &lc, uint32_t *hist)
+{
+    const bool nx = (x & 0x7FFFFFFFu) > 0x7F800000u, ny = (y & 0x7FFFFFFFu) > 0x7F800000u;
+    uint32_t bucket;
+    if (x != y) {
+        lc.mism += 1;
+        lc.first = idx < lc.first ? idx : lc.first;
+    }
+    if (nx || ny) {
+        bucket = (nx && ny) ? 0u : 33u;
+        if (nx && ny && x != y) lc.nan_equiv += 1;
+    } else {
+        const int64_t kx = ordered_key(x), ky = ordered_key(y);
+        const uint64_t dist = (uint64_t)(kx > ky ? kx - ky : ky - kx);
+        lc.maxd = dist > lc.maxd ? dist : lc.maxd;
+        bucket = dist ? 64u - (uint32_t)__builtin_clzll(dist) : 0u;
+    }
+    if (bucket) atomicAdd(&hist[bucket], 1u);       // bucket 0 is derived from the total
+}
+
+__global__ void __launch_bounds__(256)
+compare_kernel(const uint32_t *__restrict__ d0, const uint32_t *__restrict__ d1, uint64_t count,
+               uint64_t base, mmaemu_stats *st)
+{
+    __shared__ uint32_t hist[34];
+    __shared__ uint32_t s_mism, s_nan;
+    __shared__ unsigned long long s_first, s_maxd, s_count;
+    if (threadIdx.x < 34) hist[threadIdx.x] = 0;
+    if (threadIdx.x == 0) { s_mism = 0; s_nan = 0; s_first = ~0ull; s_maxd = 0; s_count = 0; }
+    __syncthreads();
+
+    Local lc = {0, 0, ~0ull, 0};
+    const uint64_t nvec = count / 4;
+    const bool aligned = ((reinterpret_cast<uintptr_t>(d0) | reinterpret_cast<uintptr_t>(d1)) & 15) == 0;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    uint64_t handled = 0;        // elements this thread looked at
+    if (aligned) {
+        const uint4 *v0 = reinterpret_cast<const uint4 *>(d0), *v1 = reinterpret_cast<const uint4 *>(d1);
+        for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride) {
+            const uint4 x = v0[v], y = v1[v];
+            const uint64_t i0 = base + 4 * v;
+            one_pair(x.x, y.x, i0, lc, hist);
+            one_pair(x.y, y.y, i0 + 1, lc, hist);
+            one_pair(x.z, y.z, i0 + 2, lc, hist);
+            one_pair(x.w, y.w, i0 + 3, lc, hist);
+            handled += 4;
+        }
+        for (uint64_t i = 4 * nvec + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+            one_pair(d0[i], d1[i], base + i, lc, hist);
+            handled += 1;
+        }
+    } else {
+        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
+            one_pair(d0[i], d1[i], base + i, lc, hist);
+            handled += 1;
+        }
+    }
+    if (handled) atomicAdd(&s_count, (unsigned long long)handled);
+    if (lc.mism) {
+        atomicAdd(&s_mism, lc.mism);
+        atomicMin(&s_first, (unsigned long long)lc.first);
+    }
+    if (lc.nan_equiv) atomicAdd(&s_nan, lc.nan_equiv);
+    if (lc.maxd) atomicMax(&s_maxd, (unsigned long long)lc.maxd);
+    __syncthreads();
+
+    unsigned long long *g = reinterpret_cast<unsigned long long *>(st);
+    if (threadIdx.x >= 1 && threadIdx.x < 34 && hist[threadIdx.x])
+        atomicAdd(&g[5 + threadIdx.x], (unsigned long long)hist[threadIdx.x]);
+    if (threadIdx.x == 0) {
+        const unsigned long long mine = s_count;
+        uint32_t nonzero = 0;
+        for (int b = 1; b < 34; ++b) nonzero += hist[b];
+        if (mine) {
+            atomicAdd(&g[0], (unsigned long long)mine);
+            atomicAdd(&g[5 + 0], (unsigned long long)(mine - nonzero));
+        }
+        if (s_mism) {
+            atomicAdd(&g[1], (unsigned long long)s_mism);
+            atomicMin(&g[3], s_first);
+        }
+        if (s_nan) atomicAdd(&g[2], (unsigned long long)s_nan);
+        if (s_maxd) atomicMax(&g[4], s_maxd);
+    }
+}
+
+mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s)
+{
+    hipLaunchKernelGGL(stats_reset_kernel, dim3(1), dim3(64), 0, s, st);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
+mmaemu_status launch_compare(const uint32_t *d0, const uint32_t *d1, uint64_t count, uint64_t base,
+                             mmaemu_stats *st, hipStream_t s)
+{
+    uint64_t blocks = (count / 4 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 256 * 8) blocks = 256 * 8;         // 8 workgroups per compute unit, grid-stride
+    hipLaunchKernelGGL(compare_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, d0, d1, count, base, st);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
+} // namespace mmaemu

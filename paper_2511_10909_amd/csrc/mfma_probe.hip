@@ -1,0 +1,163 @@
+// Native-instruction probe: the device under test of the closed loop (paper Sec. 3.3:
+// instruction-level MMA interfaces through intrinsics).  One wavefront executes exactly
+// one v_mfma instruction per tile; operands go from the tile-major, K-contiguous layout
+// of the emulation entry point straight into the instruction's register layout.
+//
+// Register layouts (wave64), l = lane:
+//   16x16xK : A row  i = l % 16, k = (K/4) * (l / 16) + 0 .. K/4-1   (same for B with column j)
+//             C/D column j = l % 16, rows i = 4 * (l / 16) + r, r = 0..3
+//   32x32x8 : A row  i = l % 32, k = 4 * (l / 32) + 0..3             (same for B with column j)
+//             C/D column j = l % 32, rows i = 8 * (r / 4) + 4 * (l / 32) + r % 4, r = 0..15
+// k positions at or beyond the caller's k are fed as zeros.
+#include "common.hpp"
+
+namespace mmaemu {
+
+typedef _Float16 v4f16 __attribute__((ext_vector_type(4)));
+typedef _Float16 v8f16 __attribute__((ext_vector_type(8)));
+typedef short v4i16 __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf16 __attribute__((ext_vector_type(8)));
+typedef float v4f32 __attribute__((ext_vector_type(4)));
+typedef float v16f32 __attribute__((ext_vector_type(16)));
+
+template <int INSTR> struct Instr;
+#define DEF_INSTR(ID, M_, N_, K_, EB)                                 \
+    template <> struct Instr<ID> {                                    \
+        static constexpr int M = M_, N = N_, K = K_, ELEM_BYTES = EB; \
+    }
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X16_F16, 16, 16, 16, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X16_BF16, 16, 16, 16, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X8_F16, 32, 32, 8, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X8_BF16, 32, 32, 8, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_F16, 16, 16, 32, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_BF16, 16, 16, 32, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_FP8_FP8, 16, 16, 32, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_FP8_BF8, 16, 16, 32, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_BF8_FP8, 16, 16, 32, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_BF8_BF8, 16, 16, 32, 1);
+#undef DEF_INSTR
+
+// gather this lane's K/4 (16-wide) or 4 (32-wide) consecutive k elements of one row,
+// zero beyond the caller's k; returns them packed little-endian in up to 128 bits
+template <int NELEM, int EB>
+__device__ __forceinline__ void load_row_slice(const uint8_t *row, uint32_t k0, uint32_t k, uint32_t out[4])
+{
+    out[0] = out[1] = out[2] = out[3] = 0u;
+#pragma unroll
+    for (int q = 0; q < NELEM; ++q) {
+        const uint32_t kk = k0 + q;
+        uint32_t v = 0;
+        if (kk < k) v = (EB == 1) ? row[kk] : reinterpret_cast<const uint16_t *>(row)[kk];
+        const int bit = q * EB * 8;
+        out[bit / 32] |= v << (bit % 32);
+    }
+}
+
+template <int INSTR>
+__global__ void __launch_bounds__(256)
+mfma_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const float *C, float *D,
+                  uint32_t k, uint64_t batch)
+{
+    using I = Instr<INSTR>;
+    constexpr int KL = (I::M == 16) ? I::K / 4 : 4;       // k elements per lane
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const uint64_t nwaves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    for (uint64_t t = wave; t < batch; t += nwaves) {
+        const uint32_t rc = lane % I::M;                  // row of A / column of B held by this lane
+        const uint32_t k0 = KL * (lane / I::M);
+        uint32_t ra[4], rb[4];
+        load_row_slice<KL, I::ELEM_BYTES>(A + ((t * I::M + rc) * (uint64_t)k) * I::ELEM_BYTES, k0, k, ra);
+        load_row_slice<KL, I::ELEM_BYTES>(B + ((t * I::N + rc) * (uint64_t)k) * I::ELEM_BYTES, k0, k, rb);
+        const float *c = C + t * (uint64_t)(I::M * I::N);
+        float *d = D + t * (uint64_t)(I::M * I::N);
+        if constexpr (I::M == 16) {
+            const uint32_t j = lane % 16, i0 = 4 * (lane / 16);
+            v4f32 acc;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = c[(i0 + r) * 16 + j];
+            if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X16_F16) {
+                v4f16 a, b;
+                __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, acc, 0, 0, 0);
+            } else if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X16_BF16) {
+                v4i16 a, b;
+                __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+                acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, acc, 0, 0, 0);
+            } else if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X32_F16) {
+                v8f16 a, b;
+                __builtin_memcpy(&a, ra, 16); __builtin_memcpy(&b, rb, 16);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, acc, 0, 0, 0);
+            } else if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X32_BF16) {
+                v8bf16 a, b;
+                __builtin_memcpy(&a, ra, 16); __builtin_memcpy(&b, rb, 16);
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+            } else {
+                long a, b;
+                __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+                if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X32_FP8_FP8)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a, b, acc, 0, 0, 0);
+                else if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X32_FP8_BF8)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_fp8_bf8(a, b, acc, 0, 0, 0);
+                else if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X32_BF8_FP8)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf8_fp8(a, b, acc, 0, 0, 0);
+                else
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(a, b, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) d[(i0 + r) * 16 + j] = acc[r];
+        } else {
+            const uint32_t j = lane % 32, ib = 4 * (lane / 32);
+            v16f32 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = c[(8 * (r / 4) + ib + r % 4) * 32 + j];
+            if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X8_F16) {
+                v4f16 a, b;
+                __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+                acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, acc, 0, 0, 0);
+            } else {
+                v4i16 a, b;
+                __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+                acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(a, b, acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) d[(8 * (r / 4) + ib + r % 4) * 32 + j] = acc[r];
+        }
+    }
+}
+
+template <int INSTR>
+static mmaemu_status launch_i(const void *A, const void *B, const void *C, void *D, uint32_t k, uint64_t batch,
+                              hipStream_t s)
+{
+    uint64_t blocks = (batch + 3) / 4;                   // 4 wavefronts (tiles) per workgroup
+    if (blocks > 256 * 64) blocks = 256 * 64;            // wave-stride beyond that
+    hipLaunchKernelGGL((mfma_probe_kernel<INSTR>), dim3((uint32_t)blocks), dim3(256), 0, s, (const uint8_t *)A,
+                       (const uint8_t *)B, (const float *)C, (float *)D, k, batch);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
+mmaemu_status launch_mfma_probe(uint32_t instr, const void *A, const void *B, const void *C, void *D,
+                                uint32_t k, uint64_t batch, hipStream_t s)
+{
+    switch (instr) {
+#define CASE(ID) case ID: return launch_i<ID>(A, B, C, D, k, batch, s)
+        CASE(MMAEMU_MFMA_F32_16X16X16_F16);
+        CASE(MMAEMU_MFMA_F32_16X16X16_BF16);
+        CASE(MMAEMU_MFMA_F32_32X32X8_F16);
+        CASE(MMAEMU_MFMA_F32_32X32X8_BF16);
+        CASE(MMAEMU_MFMA_F32_16X16X32_F16);
+        CASE(MMAEMU_MFMA_F32_16X16X32_BF16);
+        CASE(MMAEMU_MFMA_F32_16X16X32_FP8_FP8);
+        CASE(MMAEMU_MFMA_F32_16X16X32_FP8_BF8);
+        CASE(MMAEMU_MFMA_F32_16X16X32_BF8_FP8);
+        CASE(MMAEMU_MFMA_F32_16X16X32_BF8_BF8);
+#undef CASE
+    default:
+        set_error("unknown mfma instruction %u", instr);
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+}
+
+} // namespace mmaemu
