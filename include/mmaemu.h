@@ -241,6 +241,9 @@ mmaemu_status mmaemu_exact_dot_sample(const void *A, const void *B, const void *
 
 const char *mmaemu_status_string(mmaemu_status s);
 const char *mmaemu_last_error(void); /* thread-local, never NULL */
+/* Name of the kernel family the calling thread's last successful mmaemu_emulate_mma
+ * enqueued ("general", or "tiled TMxTN kc=.. L=.. c_mode=.."); for tests and reports. */
+const char *mmaemu_last_kernel(void);
 /* Library version as major*10000 + minor*100 + patch. */
 uint32_t mmaemu_version(void);
 

@@ -68,6 +68,7 @@ _vp, _u32, _u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
 _lib.mmaemu_status_string.restype = ctypes.c_char_p
 _lib.mmaemu_status_string.argtypes = [ctypes.c_int]
 _lib.mmaemu_last_error.restype = ctypes.c_char_p
+_lib.mmaemu_last_kernel.restype = ctypes.c_char_p
 _lib.mmaemu_version.restype = _u32
 _lib.mmaemu_model_create.argtypes = [ctypes.POINTER(ModelParams), ctypes.POINTER(_vp)]
 _lib.mmaemu_model_destroy.argtypes = [_vp]
@@ -111,6 +112,10 @@ def _stream(stream):
 
 def version():
     return int(_lib.mmaemu_version())
+
+
+def last_kernel():
+    return _lib.mmaemu_last_kernel().decode()
 
 
 def last_error():

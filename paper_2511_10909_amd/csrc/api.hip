@@ -25,6 +25,16 @@ void set_error(const char *fmt, ...)
     va_end(ap);
 }
 
+static thread_local char g_kernel[128] = "";
+
+void set_last_kernel(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_kernel, sizeof(g_kernel), fmt, ap);
+    va_end(ap);
+}
+
 mmaemu_status hip_fail(hipError_t e, const char *what)
 {
     set_error("HIP error %d (%s) in %s", (int)e, hipGetErrorString(e), what);
@@ -60,6 +70,8 @@ const char *mmaemu_status_string(mmaemu_status s)
 }
 
 const char *mmaemu_last_error(void) { return g_err; }
+
+const char *mmaemu_last_kernel(void) { return g_kernel; }
 
 uint32_t mmaemu_version(void) { return 100; }
 

@@ -35,6 +35,7 @@ struct ModelArgs {
 
 // error plumbing (api.hip)
 void set_error(const char *fmt, ...);
+void set_last_kernel(const char *fmt, ...);
 mmaemu_status hip_fail(hipError_t e, const char *what);
 #define MMAEMU_HIP(call)                                            \
     do {                                                            \

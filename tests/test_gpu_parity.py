@@ -34,6 +34,7 @@ def gpu_emulate(mm, p, A, B, C, ta, tb):
         dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(np.uint32))
         dD = dev_empty((nb, m, n), np.uint32)
         mm.emulate_mma(h, dA, dB, dC, dD, m, n, k, nb, (ta, tb, fm.FP32, fm.FP32))
+        gpu_emulate.last_kernel = mm.last_kernel()
         return to_host(dD, np.uint32)
     finally:
         mm.model_destroy(h)
