@@ -1,0 +1,499 @@
+// Tiled emulation kernels: the fast path of mmaemu_emulate_mma.
+//
+// What is computed is the chained FDPA model (paper Algorithm "Phi_FDPA") around the
+// truncated fused dot-product-add (Algorithm "T-FDPA"); how it is computed is specific
+// to CDNA4:
+//
+//   * A workgroup of 256 threads owns a block of D (one TMxTN block of a large problem,
+//     or several whole 16x16 / 32x32 tiles of a batch); each thread owns an RxC register
+//     block of D elements (outputs are independent: paper Sec. 3.1 Step 1).
+//   * A and B are decoded once per workgroup while being staged into LDS: each element
+//     becomes its exact binary32 value and a 16-bit biased copy of its unnormalised
+//     exponent e' = max(E, 1) - 1.  Two exponents share one LDS dword.
+//   * Pass 1 per group, e_max: packed 16-bit add and max (two products per instruction).
+//   * Pass 2 per group: the product a*b is exact in binary32 (<= 22 significant bits);
+//     multiplying by 2^(F - e_max) aligns it, and the float->int conversion truncates
+//     toward zero -- exactly RZ_F of the paper.  Terms are summed in a 32-bit integer for
+//     as many terms as cannot overflow, then folded exactly into a binary64 accumulator.
+//   * rho: the integer sum times 2^(e_max - F) is exact in binary64; one hardware
+//     binary64->binary32 conversion gives RNE with gradual underflow and overflow.
+//     With the accumulator outside the truncated sum (C_AFTER_EXACT) the exact two-term
+//     sum is formed by an error-free binary64 addition whose result is rounded to odd
+//     when inexact, so that the conversion to binary32 still rounds once.
+//
+// Elements whose value leaves the range in which the binary32 product is exact and
+// normal (|x| outside [2^-31, 2^32), only possible for BF16), and NaN/infinity, are
+// tagged with an exponent sentinel; a group that meets one is recomputed by the integer
+// routine of the general kernel from the raw operands in global memory.
+#pragma once
+#include "fdpa_int.hpp"
+
+namespace mmaemu {
+
+constexpr uint32_t SENTINEL = 0x4000u;      // exponent tag of an element the fast path cannot take
+constexpr uint32_t SENTINEL_MASK = 0xC000C000u;
+
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_add_u16(uint32_t a, uint32_t b)
+{
+    u16x2 x, y;
+    __builtin_memcpy(&x, &a, 4); __builtin_memcpy(&y, &b, 4);
+    x = x + y;
+    uint32_t r; __builtin_memcpy(&r, &x, 4);
+    return r;
+}
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
+{
+    u16x2 x, y;
+    __builtin_memcpy(&x, &a, 4); __builtin_memcpy(&y, &b, 4);
+    x = __builtin_elementwise_max(x, y);
+    uint32_t r; __builtin_memcpy(&r, &x, 4);
+    return r;
+}
+
+// ---- decode while staging --------------------------------------------------------------
+
+template <int T>
+__device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, float &val, uint32_t &ex)
+{
+    using F = Fmt<T>;
+    constexpr uint32_t EMASK = (1u << F::EB) - 1u, MMASK = (1u << F::MB) - 1u;
+    const uint32_t E = (bits >> F::MB) & EMASK;
+    uint32_t M = bits & MMASK, sign = (bits >> (F::W - 1)) & 1u;
+    const bool special = F::IEEE ? (E == EMASK) : (E == EMASK && M == MMASK);
+    if (ftz_in && E == 0) { M = 0; sign = 0; }                 // FlushSubnormal: -> +0.0
+    const uint32_t sig = E ? (M | (1u << F::MB)) : M;
+    ex = (E ? E : 1u) - 1u;
+    const float mag = ldexpf((float)sig, (int)ex + 1 - F::BIAS - F::MB);   // exact
+    const uint32_t vb = __float_as_uint(mag);
+    const uint32_t E32 = vb >> 23;
+    const bool wild = sig != 0 && (E32 < 96u || E32 > 158u);
+    val = __uint_as_float(vb | (sign << 31));
+    if (special || wild) { ex = SENTINEL; val = 0.0f; }
+}
+
+// four consecutive k elements of one row: raw little-endian bytes in `raw`
+template <int T>
+__device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float4 &v, uint2 &e)
+{
+    uint32_t b[4];
+    if (Fmt<T>::W == 8) {
+        b[0] = raw.x & 0xFFu; b[1] = (raw.x >> 8) & 0xFFu; b[2] = (raw.x >> 16) & 0xFFu; b[3] = raw.x >> 24;
+    } else {
+        b[0] = raw.x & 0xFFFFu; b[1] = raw.x >> 16; b[2] = raw.y & 0xFFFFu; b[3] = raw.y >> 16;
+    }
+    float f[4]; uint32_t x[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, f[q], x[q]);
+    v = make_float4(f[0], f[1], f[2], f[3]);
+    e = make_uint2(x[0] | (x[1] << 16), x[2] | (x[3] << 16));
+}
+
+// Where a workgroup's slots sit in the problem
+struct Geometry {
+    uint64_t item0, nitems;
+    uint32_t bm_count, bn_count, rows_a, rows_b;     // rows_a = m, rows_b = n (rows per tile in A and B)
+};
+
+// Stage ROWS rows x KC k-elements (k contiguous in global memory) for each slot.
+// IS_A selects which of the item's two block coordinates positions the rows.
+template <int T, int ROWS, int KC, int SLOTS, int VS, int ES, bool IS_A>
+__device__ __forceinline__ void stage_panel(const void *base, const Geometry &g, uint32_t k, uint32_t k0,
+                                            uint32_t ftz_in, float *lv, uint32_t *le)
+{
+    constexpr int QUADS = SLOTS * ROWS * (KC / 4);
+    using elem = typename Fmt<T>::elem;
+#pragma unroll 1
+    for (int q = threadIdx.x; q < QUADS; q += 256) {
+        const int kq = q % (KC / 4), row = (q / (KC / 4)) % ROWS, slot = q / ((KC / 4) * ROWS);
+        uint64_t it = g.item0 + slot;
+        it = it < g.nitems ? it : g.nitems - 1;               // surplus slots re-read the last item
+        const uint32_t per_tile = g.bm_count * g.bn_count;
+        const uint64_t tile = it / per_tile;
+        const uint32_t rem = (uint32_t)(it - tile * per_tile);
+        const uint32_t blk = IS_A ? rem / g.bn_count : rem % g.bn_count;
+        const uint64_t grow = tile * (IS_A ? g.rows_a : g.rows_b) + (uint64_t)blk * ROWS + row;
+        const elem *src = reinterpret_cast<const elem *>(base) + grow * k + k0 + 4 * kq;
+        uint2 raw;
+        if (Fmt<T>::W == 8) { raw.x = *reinterpret_cast<const uint32_t *>(src); raw.y = 0; }
+        else raw = *reinterpret_cast<const uint2 *>(src);
+        float4 v; uint2 e;
+        decode4<T>(raw, ftz_in, v, e);
+        *reinterpret_cast<float4 *>(lv + (slot * ROWS + row) * VS + 4 * kq) = v;
+        *reinterpret_cast<uint2 *>(le + (slot * ROWS + row) * ES + 2 * kq) = e;
+    }
+}
+
+template <int ROWS, int KC, int SLOTS, int VS, int ES, bool IS_A>
+__device__ __forceinline__ void stage_any(uint32_t t, const void *base, const Geometry &g, uint32_t k, uint32_t k0,
+                                          uint32_t ftz_in, float *lv, uint32_t *le)
+{
+    switch (t) {   // uniform
+    case MMAEMU_FP8_E4M3: stage_panel<MMAEMU_FP8_E4M3, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
+    case MMAEMU_FP8_E5M2: stage_panel<MMAEMU_FP8_E5M2, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
+    case MMAEMU_FP16: stage_panel<MMAEMU_FP16, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
+    default: stage_panel<MMAEMU_BF16, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
+    }
+}
+
+// ---- per-group arithmetic ---------------------------------------------------------------
+
+struct TiledArgs {
+    ModelArgs p;
+    uint32_t ta, tb;
+    int32_t ebase;       // Exp = e' + ebase for a product: 2 - bias_a - bias_b
+};
+
+// binary64 -> binary32 under rho, with canonical NaN and the optional output flush.
+// `v` is either exact or rounded to odd, so one RNE conversion rounds correctly.
+__device__ __forceinline__ uint32_t convert_out(const ModelArgs &p, double v)
+{
+    const float f = (float)v;                              // RNE, gradual underflow, overflow -> inf
+    uint32_t d = __float_as_uint(f);
+    if (p.out_round == MMAEMU_ROUND_RZ) {
+        const double back = (double)f;
+        if (__builtin_fabs(back) > __builtin_fabs(v)) d -= 1u;   // rounded away from zero: one step back
+    }
+    if (v == 0.0) d = 0u;                                  // exact zero -> +0.0
+    if (v != v) d = p.nan_bits;
+    if (p.ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
+    return d;
+}
+
+// ---- the kernel -------------------------------------------------------------------------
+// TM x TN : block of D per slot;  R x C: register block per thread;
+// KC      : k elements staged at a time;
+// LT      : group length if it divides KC, 0 if a group spans whole chunks (L % KC == 0);
+// NF      : terms summed in 32 bits between folds into binary64 (0: once per group/chunk).
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF>
+__global__ void __launch_bounds__(256)
+emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm,
+                     uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nitems, uint32_t bm_count,
+                     uint32_t bn_count, uint32_t xcd_remap)
+{
+    constexpr int TI = TM / R, TJ = TN / C, TPS = TI * TJ, SLOTS = 256 / TPS;
+    static_assert(TPS * SLOTS == 256, "thread layout");
+    constexpr int VS = KC + 4;                       // LDS row strides (dwords), padded against bank conflicts
+    constexpr int ES = KC / 2 + (KC == 16 ? 2 : 4);
+    constexpr int GL = LT ? LT : KC;                 // terms per inner step
+    constexpr int FOLD = NF ? NF : GL;
+    constexpr bool USE_SD = (NF != 0) || (LT == 0);  // binary64 accumulator needed
+    __shared__ __attribute__((aligned(16))) float Av[SLOTS * TM * VS];
+    __shared__ __attribute__((aligned(16))) float Bv[SLOTS * TN * VS];
+    __shared__ __attribute__((aligned(16))) uint32_t Ae[SLOTS * TM * ES];
+    __shared__ __attribute__((aligned(16))) uint32_t Be[SLOTS * TN * ES];
+
+    const ModelArgs &p = ta_.p;
+    const int F = p.F;
+    const uint32_t tid = threadIdx.x, slot = tid / TPS, ti = (tid % TPS) / TJ, tj = tid % TJ;
+
+    // workgroup -> items.  Consecutive workgroup ids go to different XCDs (8 of them, each
+    // with its own L2); the remap hands every XCD a contiguous range of blocks so that
+    // neighbours sharing A/B panels share an L2.
+    uint32_t wg = blockIdx.x;
+    if (xcd_remap) wg = (wg & 7u) * (gridDim.x >> 3) + (wg >> 3);
+    Geometry geo;
+    geo.item0 = (uint64_t)wg * SLOTS;
+    geo.nitems = nitems;
+    geo.bm_count = bm_count; geo.bn_count = bn_count; geo.rows_a = m; geo.rows_b = n;
+
+    const bool live = geo.item0 + slot < nitems;
+    uint64_t my_it = geo.item0 + slot;
+    my_it = my_it < nitems ? my_it : nitems - 1;
+    const uint32_t per_tile = bm_count * bn_count;
+    const uint64_t my_tile = my_it / per_tile;
+    const uint32_t my_rem = (uint32_t)(my_it - my_tile * per_tile);
+    const uint32_t i_base = (my_rem / bn_count) * TM + ti, j_base = (my_rem % bn_count) * TN + tj;
+    const uint64_t d_off = (my_tile * m + i_base) * (uint64_t)n + j_base;     // + TI*r*n + TJ*c
+
+    uint32_t d[R][C];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int c = 0; c < C; ++c) d[r][c] = Cm[d_off + (uint64_t)(TI * r) * n + TJ * c];
+
+    const float *av = Av + (slot * TM + ti) * VS;
+    const float *bv = Bv + (slot * TN + tj) * VS;
+    const uint32_t *ae = Ae + (slot * TM + ti) * ES;
+    const uint32_t *be = Be + (slot * TN + tj) * ES;
+
+    uint32_t m2[R][C];                                          // packed running maxima of e'
+    int32_t S32[R][C];
+    double Sd[R][C];
+
+    // pass 1: running maxima of e' = e'_a + e'_b, two products per packed instruction;
+    // EW dwords (2*EW exponents) per LDS read and row
+    constexpr int EW = (ES % 4 == 0 && (GL / 2) % 4 == 0) ? 4 : 2;
+    constexpr int U1 = (GL / 2 / EW <= 2) ? 2 : 1;
+    auto pass1 = [&](int g) {
+#pragma unroll U1
+        for (int q = 0; q < GL / 2; q += EW) {
+            uint32_t ea[R][EW], eb[C][EW];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const uint32_t *src = ae + TI * r * ES + g * (GL / 2) + q;
+                if (EW == 4) { const uint4 v = *reinterpret_cast<const uint4 *>(src); ea[r][0] = v.x; ea[r][1] = v.y; ea[r][2 % EW] = v.z; ea[r][3 % EW] = v.w; }
+                else { const uint2 v = *reinterpret_cast<const uint2 *>(src); ea[r][0] = v.x; ea[r][1] = v.y; }
+            }
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const uint32_t *src = be + TJ * c * ES + g * (GL / 2) + q;
+                if (EW == 4) { const uint4 v = *reinterpret_cast<const uint4 *>(src); eb[c][0] = v.x; eb[c][1] = v.y; eb[c][2 % EW] = v.z; eb[c][3 % EW] = v.w; }
+                else { const uint2 v = *reinterpret_cast<const uint2 *>(src); eb[c][0] = v.x; eb[c][1] = v.y; }
+            }
+#pragma unroll
+            for (int w = 0; w < EW; ++w)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) m2[r][c] = pk_max_u16(m2[r][c], pk_add_u16(ea[r][w], eb[c][w]));
+        }
+    };
+
+    // pass 2: aligned, truncated terms summed in 32 bits; four k per LDS read and row
+    constexpr int U2 = (GL / 4 <= 2) ? 2 : 1;
+    auto pass2 = [&](int g, const float (&scale)[R][C]) {
+#pragma unroll U2
+        for (int q = 0; q < GL; q += 4) {
+            float a[R][4], b[C][4];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float4 v = *reinterpret_cast<const float4 *>(av + TI * r * VS + g * GL + q);
+                a[r][0] = v.x; a[r][1] = v.y; a[r][2] = v.z; a[r][3] = v.w;
+            }
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const float4 v = *reinterpret_cast<const float4 *>(bv + TJ * c * VS + g * GL + q);
+                b[c][0] = v.x; b[c][1] = v.y; b[c][2] = v.z; b[c][3] = v.w;
+            }
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) S32[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale[r][c]);
+                if (USE_SD && (FOLD < 4) && (w + 1) % FOLD == 0) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) { Sd[r][c] += (double)S32[r][c]; S32[r][c] = 0; }
+                }
+            }
+            if (USE_SD && (FOLD >= 4) && (q + 4) % FOLD == 0) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) { Sd[r][c] += (double)S32[r][c]; S32[r][c] = 0; }
+            }
+        }
+    };
+
+    // end of pass 1 for one element: e_max and the alignment factor 2^(F - e_max)
+    auto exponents = [&](int r, int c, int &emax, float &scale, uint32_t &tagged) {
+        const uint32_t e = m2[r][c];
+        tagged |= e;
+        const uint32_t lo = e & 0xFFFFu, hi = e >> 16;
+        int em = (int)(lo > hi ? lo : hi) + ta_.ebase;
+        if (CMODE == MMAEMU_C_IN_GROUP) {
+            const uint32_t Ec = (d[r][c] >> 23) & 0xFFu;               // (a flushed subnormal keeps Exp = -126)
+            const int ec = (int)(Ec ? Ec : 1u) - 127;
+            em = ec > em ? ec : em;
+        }
+        emax = em;
+        int se = F + 127 - em;                                         // biased exponent of 2^(F - e_max)
+        se = se < 1 ? 1 : (se > 254 ? 254 : se);                       // the clamps never change a truncated term
+        scale = __uint_as_float((uint32_t)se << 23);
+    };
+
+    // conversion at the end of a group; T is the exact integer sum of the aligned products
+    auto finish = [&](int r, int c, int emax, double T) -> uint32_t {
+        const int unit = emax - F;
+        uint32_t cb = d[r][c];
+        if (p.ftz_in && (cb & 0x7F800000u) == 0) cb = 0;               // FlushSubnormal on the accumulator
+        const double cd = (double)__uint_as_float(cb);
+        if (CMODE == MMAEMU_C_IN_GROUP) {
+            const double tc = __builtin_trunc(ldexp(cd, -unit));       // the accumulator, aligned and truncated
+            return convert_out(p, ldexp(T + tc, unit));                // exact: integers below 2^53
+        } else {
+            // s = RN(a + b) and its exact error (Knuth's TwoSum); an inexact s is rounded to odd:
+            // truncate toward zero, then set the last bit
+            const double a = ldexp(T, unit);
+            double s = a + cd;
+            const double bb = s - a;
+            const double err = (a - (s - bb)) + (cd - bb);
+            if (__builtin_fabs(err) > 0.0) {                           // false for NaN (infinite operands)
+                long long sb = __double_as_longlong(s);
+                const bool toward_zero = (err < 0.0) != (s < 0.0);     // the true value is nearer zero than s
+                sb -= toward_zero ? 1 : 0;
+                s = __longlong_as_double(sb | 1ll);
+            }
+            return convert_out(p, s);
+        }
+    };
+
+    auto slow_group = [&](int r, int c, uint32_t kg, uint32_t cin) -> uint32_t {
+        const uint64_t arow = my_tile * m + i_base + TI * r;
+        const uint64_t brow = my_tile * n + j_base + TJ * c;
+        const uint32_t esa = ta_.ta <= MMAEMU_FP8_E5M2 ? 1u : 2u, esb = ta_.tb <= MMAEMU_FP8_E5M2 ? 1u : 2u;
+        const uint8_t *a = reinterpret_cast<const uint8_t *>(A) + (arow * k + kg) * esa;
+        const uint8_t *b = reinterpret_cast<const uint8_t *>(B) + (brow * k + kg) * esb;
+        return fdpa_group_raw(p, ta_.ta, ta_.tb, a, b, p.L, cin);
+    };
+
+    auto end_of_group = [&](uint32_t kg, const int (&emax)[R][C], uint32_t tagged) {
+        uint32_t dn[R][C];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];
+                dn[r][c] = finish(r, c, emax[r][c], T);
+            }
+        if (tagged & SENTINEL_MASK) {                                   // rare: the group met a tagged element
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if (m2[r][c] & SENTINEL_MASK) dn[r][c] = slow_group(r, c, kg, d[r][c]);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+    };
+
+    auto reset_group = [&]() {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) { m2[r][c] = 0; S32[r][c] = 0; Sd[r][c] = 0.0; }
+    };
+
+    auto stage = [&](uint32_t k0) {
+        __syncthreads();
+        stage_any<TM, KC, SLOTS, VS, ES, true>(ta_.ta, A, geo, k, k0, p.ftz_in, Av, Ae);
+        stage_any<TN, KC, SLOTS, VS, ES, false>(ta_.tb, B, geo, k, k0, p.ftz_in, Bv, Be);
+        __syncthreads();
+    };
+
+    if (LT != 0) {
+        for (uint32_t k0 = 0; k0 < k; k0 += KC) {
+            stage(k0);
+#pragma unroll 1
+            for (int g = 0; g < KC / GL; ++g) {
+                reset_group();
+                pass1(g);
+                float scale[R][C]; int emax[R][C]; uint32_t tagged = 0;
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], scale[r][c], tagged);
+                pass2(g, scale);
+                end_of_group(k0 + g * GL, emax, tagged);
+            }
+        }
+    } else {
+        // a group of p.L terms spans p.L / KC chunks: sweep the group's chunks twice
+        for (uint32_t kg = 0; kg < k; kg += p.L) {
+            reset_group();
+            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0); pass1(0); }
+            float scale[R][C]; int emax[R][C]; uint32_t tagged = 0;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], scale[r][c], tagged);
+            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0); pass2(0, scale); }
+            end_of_group(kg, emax, tagged);
+        }
+    }
+
+    if (live) {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) D[d_off + (uint64_t)(TI * r) * n + TJ * c] = d[r][c];
+    }
+}
+
+// ---- host side ---------------------------------------------------------------------------
+
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF>
+static mmaemu_status launch_cfg(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
+                                uint32_t n, uint32_t k, uint64_t batch, hipStream_t s)
+{
+    constexpr int SLOTS = 256 / ((TM / R) * (TN / C));
+    const uint32_t bm = m / TM, bn = n / TN;
+    const uint64_t nitems = batch * bm * bn;
+    const uint64_t blocks = (nitems + SLOTS - 1) / SLOTS;
+    if (blocks > 0x7FFFFFFFull) { set_error("emulate_mma: too many blocks"); return MMAEMU_ERR_SHAPE; }
+    const uint32_t remap = (blocks % 8 == 0 && blocks >= 64) ? 1u : 0u;
+    hipLaunchKernelGGL((emulate_tiled_kernel<TM, TN, R, C, KC, LT, CMODE, NF>), dim3((uint32_t)blocks), dim3(256), 0, s,
+                       ta, A, B, (const uint32_t *)Cm, (uint32_t *)D, m, n, k, nitems, bm, bn, remap);
+    MMAEMU_HIP(hipGetLastError());
+    set_last_kernel("tiled %dx%d r%dx%d kc=%d L=%d c_mode=%d fold=%d", TM, TN, R, C, KC, LT ? LT : (int)ta.p.L, CMODE, NF);
+    return MMAEMU_OK;
+}
+
+// choose the fold period: the largest of {whole group, 4, 1} whose 32-bit partial sums cannot overflow
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE>
+static mmaemu_status launch_fold(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
+                                 uint32_t n, uint32_t k, uint64_t batch, hipStream_t s)
+{
+    constexpr int GL = LT ? LT : KC;
+    const uint64_t term = 1ull << (ta.p.F + 2);                 // |aligned term| < 2^(F+2)
+    if (GL * term <= (1ull << 31)) return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if (4 * term <= (1ull << 31)) return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 4>(ta, A, B, Cm, D, m, n, k, batch, s);
+    return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 1>(ta, A, B, Cm, D, m, n, k, batch, s);
+}
+
+template <int TM, int TN, int R, int C, int KC, int CMODE>
+static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
+                              uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
+{
+    handled = true;
+    const uint32_t L = ta.p.L;
+    if (L == 4) return launch_fold<TM, TN, R, C, KC, 4, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if (L == 8) return launch_fold<TM, TN, R, C, KC, 8, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if constexpr (KC >= 16) {
+        if (L == 16) return launch_fold<TM, TN, R, C, KC, 16, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+    }
+    if constexpr (KC >= 32) {
+        if (L == 32) return launch_fold<TM, TN, R, C, KC, 32, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+    }
+    if (L % KC == 0) return launch_fold<TM, TN, R, C, KC, 0, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+    handled = false;
+    return MMAEMU_OK;
+}
+
+template <int CMODE>
+mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
+                                  uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
+{
+    handled = false;
+    const uint64_t outputs = batch * m * n;
+    // whole small tiles of a batch
+    if (m == 16 && n == 16 && k % 16 == 0) return launch_L<16, 16, 4, 4, 16, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (m == 32 && n == 32 && k % 8 == 0 && k % 32 != 0)
+        return launch_L<32, 32, 4, 4, 8, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    // blocks of a larger problem: 4x4 register blocks once there are enough outputs to fill
+    // the chip with them (256 CUs x 4 SIMDs x 2 waves x 64 lanes x 16), 2x2 blocks otherwise
+    if (m % 64 == 0 && n % 64 == 0 && k % 32 == 0 && outputs >= (1ull << 21))
+        return launch_L<64, 64, 4, 4, 32, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (m % 32 == 0 && n % 32 == 0 && k % 32 == 0)
+        return launch_L<32, 32, 2, 2, 32, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
+        return launch_L<32, 32, 4, 4, 8, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0)
+        return launch_L<16, 16, 4, 4, 16, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    return MMAEMU_OK;
+}
+
+
+// explicit instantiations live in emulate_tiled_c0.hip / emulate_tiled_c1.hip (one per accumulation mode)
+extern template mmaemu_status launch_tiled_shape<MMAEMU_C_IN_GROUP>(const TiledArgs &, const void *, const void *, const void *,
+                                                                   void *, uint32_t, uint32_t, uint32_t, uint64_t, hipStream_t, bool &);
+extern template mmaemu_status launch_tiled_shape<MMAEMU_C_AFTER_EXACT>(const TiledArgs &, const void *, const void *, const void *,
+                                                                      void *, uint32_t, uint32_t, uint32_t, uint64_t, hipStream_t, bool &);
+
+} // namespace mmaemu
