@@ -2,8 +2,10 @@
 // Sec. 3.1 Step 4: the model must reproduce the interface bit by bit).
 //
 // HBM-bound: 8 bytes read per compared pair.  Each lane handles four consecutive
-// elements (one 128-bit load per input); counters are gathered per workgroup in LDS and
-// flushed with one global atomic per non-zero counter per workgroup.
+// elements (one 128-bit load per input).  The histogram is kept in LDS in 32 copies per
+// bucket (copy = lane mod 32), so that lanes counting the same bucket do not serialise
+// on one address; counters are flushed with one global atomic per non-zero counter per
+// workgroup.
 #include "common.hpp"
 
 namespace mmaemu {
@@ -42,17 +44,17 @@ __device__ __forceinline__ void one_pair(uint32_t x, uint32_t y, uint64_t idx, L
         lc.maxd = dist > lc.maxd ? dist : lc.maxd;
         bucket = dist ? 64u - (uint32_t)__builtin_clzll(dist) : 0u;
     }
-    if (bucket) atomicAdd(&hist[bucket], 1u);       // bucket 0 is derived from the total
+    if (bucket) atomicAdd(&hist[bucket * 32u + (threadIdx.x & 31u)], 1u);   // bucket 0 is derived from the total
 }
 
 __global__ void __launch_bounds__(256)
 compare_kernel(const uint32_t *__restrict__ d0, const uint32_t *__restrict__ d1, uint64_t count,
                uint64_t base, mmaemu_stats *st)
 {
-    __shared__ uint32_t hist[34];
+    __shared__ uint32_t hist[34 * 32];
     __shared__ uint32_t s_mism, s_nan;
     __shared__ unsigned long long s_first, s_maxd, s_count;
-    if (threadIdx.x < 34) hist[threadIdx.x] = 0;
+    for (uint32_t i = threadIdx.x; i < 34 * 32; i += blockDim.x) hist[i] = 0;
     if (threadIdx.x == 0) { s_mism = 0; s_nan = 0; s_first = ~0ull; s_maxd = 0; s_count = 0; }
     __syncthreads();
 
@@ -92,12 +94,18 @@ compare_kernel(const uint32_t *__restrict__ d0, const uint32_t *__restrict__ d1,
     __syncthreads();
 
     unsigned long long *g = reinterpret_cast<unsigned long long *>(st);
-    if (threadIdx.x >= 1 && threadIdx.x < 34 && hist[threadIdx.x])
-        atomicAdd(&g[5 + threadIdx.x], (unsigned long long)hist[threadIdx.x]);
+    __shared__ uint32_t tot[34];
+    if (threadIdx.x < 34) {
+        uint32_t t = 0;
+        for (int cpy = 0; cpy < 32; ++cpy) t += hist[threadIdx.x * 32 + cpy];
+        tot[threadIdx.x] = t;
+        if (threadIdx.x >= 1 && t) atomicAdd(&g[5 + threadIdx.x], (unsigned long long)t);
+    }
+    __syncthreads();
     if (threadIdx.x == 0) {
         const unsigned long long mine = s_count;
         uint32_t nonzero = 0;
-        for (int b = 1; b < 34; ++b) nonzero += hist[b];
+        for (int b = 1; b < 34; ++b) nonzero += tot[b];
         if (mine) {
             atomicAdd(&g[0], (unsigned long long)mine);
             atomicAdd(&g[5 + 0], (unsigned long long)(mine - nonzero));

@@ -54,23 +54,39 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 
 // ---- decode while staging --------------------------------------------------------------
 
+// One element -> (exact binary32 value, e' = max(E, 1) - 1), or the sentinel tag for NaN,
+// infinities and values outside [2^-31, 2^32) (only BF16 has such finite values).
 template <int T>
 __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, float &val, uint32_t &ex)
 {
     using F = Fmt<T>;
     constexpr uint32_t EMASK = (1u << F::EB) - 1u, MMASK = (1u << F::MB) - 1u;
     const uint32_t E = (bits >> F::MB) & EMASK;
-    uint32_t M = bits & MMASK, sign = (bits >> (F::W - 1)) & 1u;
-    const bool special = F::IEEE ? (E == EMASK) : (E == EMASK && M == MMASK);
-    if (ftz_in && E == 0) { M = 0; sign = 0; }                 // FlushSubnormal: -> +0.0
-    const uint32_t sig = E ? (M | (1u << F::MB)) : M;
     ex = (E ? E : 1u) - 1u;
-    const float mag = ldexpf((float)sig, (int)ex + 1 - F::BIAS - F::MB);   // exact
-    const uint32_t vb = __float_as_uint(mag);
-    const uint32_t E32 = vb >> 23;
-    const bool wild = sig != 0 && (E32 < 96u || E32 > 158u);
-    val = __uint_as_float(vb | (sign << 31));
-    if (special || wild) { ex = SENTINEL; val = 0.0f; }
+    if (T == MMAEMU_BF16) {
+        // the value is the pattern moved to the top half of a binary32 word
+        const uint32_t mag = bits & 0x7FFFu;
+        const bool tagged = mag != 0 && (E - 96u) > 62u;        // covers E = 255 and subnormals
+        uint32_t vb = bits << 16;
+        if (ftz_in && E == 0) vb = 0;                           // FlushSubnormal: -> +0.0
+        val = __uint_as_float(vb);
+        if (tagged && !(ftz_in && E == 0)) { ex = SENTINEL; val = 0.0f; }
+    } else if (T == MMAEMU_FP16) {
+        _Float16 h;
+        const uint16_t hb = (uint16_t)bits;
+        __builtin_memcpy(&h, &hb, 2);
+        val = (float)h;                                          // exact, subnormals included
+        if (ftz_in && E == 0) val = 0.0f;
+        if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
+    } else {
+        uint32_t M = bits & MMASK, sign = (bits >> 7) & 1u;
+        const bool special = F::IEEE ? (E == EMASK) : (E == EMASK && M == MMASK);
+        if (ftz_in && E == 0) { M = 0; sign = 0; }
+        const uint32_t sig = E ? (M | (1u << F::MB)) : M;
+        const float mag = ldexpf((float)sig, (int)ex + 1 - F::BIAS - F::MB);   // exact
+        val = __uint_as_float(__float_as_uint(mag) | (sign << 31));
+        if (special) { ex = SENTINEL; val = 0.0f; }
+    }
 }
 
 // four consecutive k elements of one row: raw little-endian bytes in `raw`
@@ -90,50 +106,70 @@ __device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float4 &v, u
     e = make_uint2(x[0] | (x[1] << 16), x[2] | (x[3] << 16));
 }
 
-// Where a workgroup's slots sit in the problem
-struct Geometry {
-    uint64_t item0, nitems;
-    uint32_t bm_count, bn_count, rows_a, rows_b;     // rows_a = m, rows_b = n (rows per tile in A and B)
+// Per-thread staging plan: each thread moves NQ quads (4 consecutive k elements of one
+// row) per matrix and chunk; the quad's global row and its LDS offsets do not change
+// along k, so they are worked out once.
+template <int NQ>
+struct StagePlan {
+    const uint8_t *src[NQ];      // row start in global memory (bytes), + (k0 + 4*kq) * esize per chunk
+    uint32_t voff[NQ], eoff[NQ]; // LDS dword offsets of the quad's values / packed exponents
+    uint32_t kq4[NQ];            // 4 * kq
 };
 
-// Stage ROWS rows x KC k-elements (k contiguous in global memory) for each slot.
-// IS_A selects which of the item's two block coordinates positions the rows.
-template <int T, int ROWS, int KC, int SLOTS, int VS, int ES, bool IS_A>
-__device__ __forceinline__ void stage_panel(const void *base, const Geometry &g, uint32_t k, uint32_t k0,
-                                            uint32_t ftz_in, float *lv, uint32_t *le)
+template <int ROWS, int KC, int SLOTS, int VS, int ES, bool IS_A, int NQ>
+__device__ __forceinline__ void make_plan(StagePlan<NQ> &pl, const void *base, uint32_t esize, uint64_t item0, uint64_t nitems,
+                                          uint32_t bm_count, uint32_t bn_count, uint32_t rows_per_tile, uint32_t k)
 {
     constexpr int QUADS = SLOTS * ROWS * (KC / 4);
-    using elem = typename Fmt<T>::elem;
-#pragma unroll 1
-    for (int q = threadIdx.x; q < QUADS; q += 256) {
+    static_assert(QUADS % 256 == 0 || QUADS < 256, "quads per thread");
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        int q = threadIdx.x + 256 * i;
+        q = q < QUADS ? q : QUADS - 1;                        // (threads beyond the panel repeat its last quad)
         const int kq = q % (KC / 4), row = (q / (KC / 4)) % ROWS, slot = q / ((KC / 4) * ROWS);
-        uint64_t it = g.item0 + slot;
-        it = it < g.nitems ? it : g.nitems - 1;               // surplus slots re-read the last item
-        const uint32_t per_tile = g.bm_count * g.bn_count;
+        uint64_t it = item0 + slot;
+        it = it < nitems ? it : nitems - 1;                   // surplus slots re-read the last item
+        const uint32_t per_tile = bm_count * bn_count;
         const uint64_t tile = it / per_tile;
         const uint32_t rem = (uint32_t)(it - tile * per_tile);
-        const uint32_t blk = IS_A ? rem / g.bn_count : rem % g.bn_count;
-        const uint64_t grow = tile * (IS_A ? g.rows_a : g.rows_b) + (uint64_t)blk * ROWS + row;
-        const elem *src = reinterpret_cast<const elem *>(base) + grow * k + k0 + 4 * kq;
-        uint2 raw;
-        if (Fmt<T>::W == 8) { raw.x = *reinterpret_cast<const uint32_t *>(src); raw.y = 0; }
-        else raw = *reinterpret_cast<const uint2 *>(src);
-        float4 v; uint2 e;
-        decode4<T>(raw, ftz_in, v, e);
-        *reinterpret_cast<float4 *>(lv + (slot * ROWS + row) * VS + 4 * kq) = v;
-        *reinterpret_cast<uint2 *>(le + (slot * ROWS + row) * ES + 2 * kq) = e;
+        const uint32_t blk = IS_A ? rem / bn_count : rem % bn_count;
+        const uint64_t grow = tile * rows_per_tile + (uint64_t)blk * ROWS + row;
+        pl.src[i] = reinterpret_cast<const uint8_t *>(base) + grow * k * esize;
+        pl.voff[i] = (slot * ROWS + row) * VS + 4 * kq;
+        pl.eoff[i] = (slot * ROWS + row) * ES + 2 * kq;
+        pl.kq4[i] = 4 * kq;
     }
 }
 
-template <int ROWS, int KC, int SLOTS, int VS, int ES, bool IS_A>
-__device__ __forceinline__ void stage_any(uint32_t t, const void *base, const Geometry &g, uint32_t k, uint32_t k0,
-                                          uint32_t ftz_in, float *lv, uint32_t *le)
+template <int T, int NQ>
+__device__ __forceinline__ void stage_panel(const StagePlan<NQ> &pl, uint32_t k0, uint32_t ftz_in, float *lv, uint32_t *le)
+{
+    using elem = typename Fmt<T>::elem;
+    uint2 raw[NQ];
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        const elem *src = reinterpret_cast<const elem *>(pl.src[i]) + k0 + pl.kq4[i];
+        if (Fmt<T>::W == 8) { raw[i].x = *reinterpret_cast<const uint32_t *>(src); raw[i].y = 0; }
+        else raw[i] = *reinterpret_cast<const uint2 *>(src);
+    }
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        float4 v; uint2 e;
+        decode4<T>(raw[i], ftz_in, v, e);
+        *reinterpret_cast<float4 *>(lv + pl.voff[i]) = v;
+        *reinterpret_cast<uint2 *>(le + pl.eoff[i]) = e;
+    }
+}
+
+template <int NQ>
+__device__ __forceinline__ void stage_any(uint32_t t, const StagePlan<NQ> &pl, uint32_t k0, uint32_t ftz_in, float *lv,
+                                          uint32_t *le)
 {
     switch (t) {   // uniform
-    case MMAEMU_FP8_E4M3: stage_panel<MMAEMU_FP8_E4M3, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
-    case MMAEMU_FP8_E5M2: stage_panel<MMAEMU_FP8_E5M2, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
-    case MMAEMU_FP16: stage_panel<MMAEMU_FP16, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
-    default: stage_panel<MMAEMU_BF16, ROWS, KC, SLOTS, VS, ES, IS_A>(base, g, k, k0, ftz_in, lv, le); break;
+    case MMAEMU_FP8_E4M3: stage_panel<MMAEMU_FP8_E4M3, NQ>(pl, k0, ftz_in, lv, le); break;
+    case MMAEMU_FP8_E5M2: stage_panel<MMAEMU_FP8_E5M2, NQ>(pl, k0, ftz_in, lv, le); break;
+    case MMAEMU_FP16: stage_panel<MMAEMU_FP16, NQ>(pl, k0, ftz_in, lv, le); break;
+    default: stage_panel<MMAEMU_BF16, NQ>(pl, k0, ftz_in, lv, le); break;
     }
 }
 
@@ -144,22 +180,6 @@ struct TiledArgs {
     uint32_t ta, tb;
     int32_t ebase;       // Exp = e' + ebase for a product: 2 - bias_a - bias_b
 };
-
-// binary64 -> binary32 under rho, with canonical NaN and the optional output flush.
-// `v` is either exact or rounded to odd, so one RNE conversion rounds correctly.
-__device__ __forceinline__ uint32_t convert_out(const ModelArgs &p, double v)
-{
-    const float f = (float)v;                              // RNE, gradual underflow, overflow -> inf
-    uint32_t d = __float_as_uint(f);
-    if (p.out_round == MMAEMU_ROUND_RZ) {
-        const double back = (double)f;
-        if (__builtin_fabs(back) > __builtin_fabs(v)) d -= 1u;   // rounded away from zero: one step back
-    }
-    if (v == 0.0) d = 0u;                                  // exact zero -> +0.0
-    if (v != v) d = p.nan_bits;
-    if (p.ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
-    return d;
-}
 
 // ---- the kernel -------------------------------------------------------------------------
 // TM x TN : block of D per slot;  R x C: register block per thread;
@@ -193,13 +213,15 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     // neighbours sharing A/B panels share an L2.
     uint32_t wg = blockIdx.x;
     if (xcd_remap) wg = (wg & 7u) * (gridDim.x >> 3) + (wg >> 3);
-    Geometry geo;
-    geo.item0 = (uint64_t)wg * SLOTS;
-    geo.nitems = nitems;
-    geo.bm_count = bm_count; geo.bn_count = bn_count; geo.rows_a = m; geo.rows_b = n;
+    const uint64_t item0 = (uint64_t)wg * SLOTS;
+    constexpr int NQA = (SLOTS * TM * (KC / 4) + 255) / 256, NQB = (SLOTS * TN * (KC / 4) + 255) / 256;
+    StagePlan<NQA> plan_a;
+    StagePlan<NQB> plan_b;
+    make_plan<TM, KC, SLOTS, VS, ES, true, NQA>(plan_a, A, ta_.ta <= MMAEMU_FP8_E5M2 ? 1u : 2u, item0, nitems, bm_count, bn_count, m, k);
+    make_plan<TN, KC, SLOTS, VS, ES, false, NQB>(plan_b, B, ta_.tb <= MMAEMU_FP8_E5M2 ? 1u : 2u, item0, nitems, bm_count, bn_count, n, k);
 
-    const bool live = geo.item0 + slot < nitems;
-    uint64_t my_it = geo.item0 + slot;
+    const bool live = item0 + slot < nitems;
+    uint64_t my_it = item0 + slot;
     my_it = my_it < nitems ? my_it : nitems - 1;
     const uint32_t per_tile = bm_count * bn_count;
     const uint64_t my_tile = my_it / per_tile;
@@ -306,32 +328,6 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         scale = __uint_as_float((uint32_t)se << 23);
     };
 
-    // conversion at the end of a group; T is the exact integer sum of the aligned products
-    auto finish = [&](int r, int c, int emax, double T) -> uint32_t {
-        const int unit = emax - F;
-        uint32_t cb = d[r][c];
-        if (p.ftz_in && (cb & 0x7F800000u) == 0) cb = 0;               // FlushSubnormal on the accumulator
-        const double cd = (double)__uint_as_float(cb);
-        if (CMODE == MMAEMU_C_IN_GROUP) {
-            const double tc = __builtin_trunc(ldexp(cd, -unit));       // the accumulator, aligned and truncated
-            return convert_out(p, ldexp(T + tc, unit));                // exact: integers below 2^53
-        } else {
-            // s = RN(a + b) and its exact error (Knuth's TwoSum); an inexact s is rounded to odd:
-            // truncate toward zero, then set the last bit
-            const double a = ldexp(T, unit);
-            double s = a + cd;
-            const double bb = s - a;
-            const double err = (a - (s - bb)) + (cd - bb);
-            if (__builtin_fabs(err) > 0.0) {                           // false for NaN (infinite operands)
-                long long sb = __double_as_longlong(s);
-                const bool toward_zero = (err < 0.0) != (s < 0.0);     // the true value is nearer zero than s
-                sb -= toward_zero ? 1 : 0;
-                s = __longlong_as_double(sb | 1ll);
-            }
-            return convert_out(p, s);
-        }
-    };
-
     auto slow_group = [&](int r, int c, uint32_t kg, uint32_t cin) -> uint32_t {
         const uint64_t arow = my_tile * m + i_base + TI * r;
         const uint64_t brow = my_tile * n + j_base + TJ * c;
@@ -341,15 +337,80 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         return fdpa_group_raw(p, ta_.ta, ta_.tb, a, b, p.L, cin);
     };
 
+    // End of a group: rho of (sum of aligned terms) * 2^unit.  The value to convert is held
+    // in binary64, exact or rounded to odd, so that the single hardware conversion to
+    // binary32 (RNE, gradual underflow, overflow to infinity) rounds correctly.
     auto end_of_group = [&](uint32_t kg, const int (&emax)[R][C], uint32_t tagged) {
+        if (p.ftz_in) {                                                 // FlushSubnormal on the accumulator
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if ((d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;
+        }
+        double v[R][C];
+        if (CMODE == MMAEMU_C_IN_GROUP) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];
+                    const int unit = emax[r][c] - F;
+                    // the accumulator, aligned and truncated like every other term
+                    const double tc = __builtin_trunc(ldexp((double)__uint_as_float(d[r][c]), -unit));
+                    v[r][c] = ldexp(T + tc, unit);                      // exact: integers below 2^53
+                }
+        } else {
+            // d = rho(T 2^unit + c) with the two-term sum exact: s = RN(a + c) and its exact
+            // error (Knuth's TwoSum); an inexact s is then rounded to odd (truncated toward
+            // zero, last bit set), which the conversion below cannot tell from the exact sum
+            double err[R][C];
+            bool inexact = false;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];
+                    const double a = ldexp(T, emax[r][c] - F);
+                    const double cd = (double)__uint_as_float(d[r][c]);
+                    const double s = a + cd;
+                    const double bb = s - a;
+                    err[r][c] = (a - (s - bb)) + (cd - bb);
+                    v[r][c] = s;
+                    inexact |= __builtin_fabs(err[r][c]) > 0.0;        // false for NaN (infinite operands)
+                }
+            if (inexact) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+                        if (__builtin_fabs(err[r][c]) > 0.0) {
+                            long long sb = __double_as_longlong(v[r][c]);
+                            const bool toward_zero = (err[r][c] < 0.0) != (v[r][c] < 0.0);   // true value nearer zero
+                            sb -= toward_zero ? 1 : 0;
+                            v[r][c] = __longlong_as_double(sb | 1ll);
+                        }
+            }
+        }
         uint32_t dn[R][C];
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];
-                dn[r][c] = finish(r, c, emax[r][c], T);
-            }
+            for (int c = 0; c < C; ++c) dn[r][c] = __float_as_uint((float)v[r][c]);
+        if (p.out_round != MMAEMU_ROUND_RNE || p.ftz_out) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    uint32_t o = dn[r][c];
+                    if (p.out_round == MMAEMU_ROUND_RZ) {
+                        const double back = (double)__uint_as_float(o);
+                        if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) o -= 1u;   // rounded away from zero: step back
+                    }
+                    if (p.ftz_out && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                    dn[r][c] = o;
+                }
+        }
         if (tagged & SENTINEL_MASK) {                                   // rare: the group met a tagged element
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -372,8 +433,8 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 
     auto stage = [&](uint32_t k0) {
         __syncthreads();
-        stage_any<TM, KC, SLOTS, VS, ES, true>(ta_.ta, A, geo, k, k0, p.ftz_in, Av, Ae);
-        stage_any<TN, KC, SLOTS, VS, ES, false>(ta_.tb, B, geo, k, k0, p.ftz_in, Bv, Be);
+        stage_any<NQA>(ta_.ta, plan_a, k0, p.ftz_in, Av, Ae);
+        stage_any<NQB>(ta_.tb, plan_b, k0, p.ftz_in, Bv, Be);
         __syncthreads();
     };
 
@@ -412,7 +473,12 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) D[d_off + (uint64_t)(TI * r) * n + TJ * c] = d[r][c];
+            for (int c = 0; c < C; ++c) {
+                // a NaN accumulator propagates through the groups with whatever payload the
+                // hardware gives it; the model's NaN encoding is applied once here
+                const uint32_t o = d[r][c];
+                D[d_off + (uint64_t)(TI * r) * n + TJ * c] = (o & 0x7FFFFFFFu) > 0x7F800000u ? p.nan_bits : o;
+            }
     }
 }
 
