@@ -161,19 +161,33 @@ def words_per_elem(gp, fmt_id):
     return 2 if (gp.family == GEN_UNIFORM_EXP and fmt_id == fm.FP32) else 1
 
 
-def normal_values(gp, elems_per_tile, first_tile, n_tiles):
-    """Unscaled binary64 N(0,1) values of the NORMAL family, shape (n_tiles, elems_per_tile)."""
-    g0 = first_tile * elems_per_tile
-    total = n_tiles * elems_per_tile
-    g = np.arange(g0, g0 + total, dtype=np.uint64)
-    pair = g >> np.uint64(1)
+def _normal_range(gp, g0, count):
+    p0, p1 = g0 >> 1, (g0 + count + 1) >> 1                       # pairs covering elements g0 .. g0+count-1
+    pair = np.arange(p0, p1, dtype=np.uint64)
     ze, zo = normal_pairs(_words(gp.seed, gp.operand, pair * np.uint64(2)),
                           _words(gp.seed, gp.operand, pair * np.uint64(2) + np.uint64(1)))
-    z = np.where((g & np.uint64(1)) == 0, ze, zo)
-    return z.reshape(n_tiles, elems_per_tile)
+    z = np.stack([ze, zo], axis=1).ravel()                         # element 2i from the cosine, 2i+1 from the sine
+    off = g0 - 2 * p0
+    return z[off:off + count]
 
 
-def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles):
+def normal_values(gp, elems_per_tile, first_tile, n_tiles, threads=1):
+    """Unscaled binary64 N(0,1) values of the NORMAL family, shape (n_tiles, elems_per_tile).
+    `threads` > 1 only splits the element range over a thread pool (numpy releases the GIL);
+    every element is computed by the same operations either way."""
+    g0 = first_tile * elems_per_tile
+    total = n_tiles * elems_per_tile
+    step = 1 << 18                                                 # cache-sized pieces
+    if total <= step:
+        return _normal_range(gp, g0, total).reshape(n_tiles, elems_per_tile)
+    from concurrent.futures import ThreadPoolExecutor
+    starts = list(range(0, total, step))
+    with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
+        parts = list(ex.map(lambda s0: _normal_range(gp, g0 + s0, min(step, total - s0)), starts))
+    return np.concatenate(parts).reshape(n_tiles, elems_per_tile)
+
+
+def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
     """Raw bit patterns (uint32 array, shape (n_tiles, elems_per_tile)) of one operand."""
     f = fm.FORMATS[fmt_id]
     total = n_tiles * elems_per_tile
@@ -182,13 +196,15 @@ def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles):
     g = np.arange(first_tile * elems_per_tile, first_tile * elems_per_tile + total, dtype=np.uint64)
     wpe = words_per_elem(gp, fmt_id)
     if gp.family == GEN_NORMAL:
-        z = normal_values(gp, elems_per_tile, first_tile, n_tiles)
+        z = normal_values(gp, elems_per_tile, first_tile, n_tiles, threads)
         if gp.scale_scope == SCALE_TENSOR:
             z = z * (np.float64(gp.scale_target) / np.abs(z).max())
         elif gp.scale_scope == SCALE_TILE:
             z = z * (np.float64(gp.scale_target) / np.abs(z).max(axis=1, keepdims=True))
-        b32 = z.astype(np.float32).view(np.uint32)
-        return cast_from_fp32(b32, fmt_id).reshape(n_tiles, elems_per_tile)
+        b32 = z.astype(np.float32).view(np.uint32).ravel()
+        step = 1 << 18
+        out = np.concatenate([cast_from_fp32(b32[i:i + step], fmt_id) for i in range(0, b32.size, step)])
+        return out.reshape(n_tiles, elems_per_tile)
     r = _words(gp.seed, gp.operand, g * np.uint64(wpe)).astype(np.uint64)
     if gp.family == GEN_RANDOM_BITS:
         out = r & np.uint64((1 << f.width) - 1)

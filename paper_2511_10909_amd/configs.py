@@ -1,0 +1,232 @@
+"""The five probing workloads, run through libmmaemu (device memory from PyTorch, every
+computation inside the library).  Each runner returns a dict of results; tensors it leaves
+on the device are returned under "dev" so that tests can check them against the CPU oracle.
+
+Workloads (synthetic stand-ins for the randomized validation of the paper's Sec. 3.1 Step 4;
+recipes in the design doc):
+  config1  10,000 fp16 16x16x16 tiles, uniform finite bit patterns, C ~ N(0,1); F = 27, L = 16,
+           RNE against RZ output
+  config2  bf16 1024^3 GEMM, N(0,1) operands, C = 0; groups of 8 added exactly to the running
+           sum (C_AFTER_EXACT) against the fully fused model
+  config3  e4m3 x e5m2 4096^3 GEMM, N(0,1) scaled per tensor to the format maximum; F = 14,
+           L = 32; error statistics against exact dot products on a 1 % sample
+  config4  subnormal stress: fp16 32x32x8 tiles with uniform exponent fields; input-flush,
+           output-flush and no-flush variants, histogram of each against the no-flush run
+  config5  closed-loop scan: 16 parameter sets x {bf16, fp8} 16x16x16 tiles against the native
+           MFMA instruction
+"""
+import time
+
+import torch
+
+from . import binding as mm
+
+_TORCH = {1: torch.uint8, 2: torch.int16, 4: torch.int32}
+
+
+def _buf(shape, dtype_id, dev):
+    return torch.empty(shape, dtype=_TORCH[mm.ELEM_BYTES[dtype_id]], device=dev)
+
+
+def _stats_buf(dev):
+    st = torch.empty(mm.STATS_BYTES, dtype=torch.uint8, device=dev)
+    mm.stats_reset(st)
+    return st
+
+
+def _timed(fn):
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    out = fn()
+    torch.cuda.synchronize()
+    return out, time.perf_counter() - t0
+
+
+def config1(n_tiles=10000, seed=0, dev="cuda"):
+    m = n = k = 16
+    dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
+    A, B = _buf((n_tiles, m, k), mm.FP16, dev), _buf((n_tiles, n, k), mm.FP16, dev)
+    C, D0, D1 = (_buf((n_tiles, m, n), mm.FP32, dev) for _ in range(3))
+    st = _stats_buf(dev)
+    m0 = mm.model_create(group_len=16, frac_bits=27, out_round=mm.RNE)
+    m1 = mm.model_create(group_len=16, frac_bits=27, out_round=mm.RZ)
+
+    def run():
+        mm.generate(A, mm.FP16, m * k, 0, n_tiles, mm.GEN_FINITE_BITS, seed=seed, operand=0)
+        mm.generate(B, mm.FP16, n * k, 0, n_tiles, mm.GEN_FINITE_BITS, seed=seed, operand=1)
+        mm.generate(C, mm.FP32, m * n, 0, n_tiles, mm.GEN_NORMAL, seed=seed, operand=2)
+        mm.emulate_mma(m0, A, B, C, D0, m, n, k, n_tiles, dt)
+        k0 = mm.last_kernel()
+        mm.emulate_mma(m1, A, B, C, D1, m, n, k, n_tiles, dt)
+        mm.compare(D0, D1, n_tiles * m * n, st)
+        return k0
+
+    kernel, secs = _timed(run)
+    mm.model_destroy(m0)
+    mm.model_destroy(m1)
+    return dict(terms=2 * n_tiles * m * n * k, seconds=secs, kernel=kernel, stats=mm.read_stats(st),
+                dev=dict(A=A, B=B, C=C, D0=D0, D1=D1))
+
+
+def config2(size=1024, seed=0, dev="cuda"):
+    m = n = k = size
+    dt = (mm.BF16, mm.BF16, mm.FP32, mm.FP32)
+    A, B = _buf((m, k), mm.BF16, dev), _buf((n, k), mm.BF16, dev)
+    C, D0, D1 = (_buf((m, n), mm.FP32, dev) for _ in range(3))
+    st = _stats_buf(dev)
+    chained = mm.model_create(group_len=8, frac_bits=24, c_mode=mm.C_AFTER_EXACT)
+    fused = mm.model_create(group_len=0, frac_bits=24, c_mode=mm.C_IN_GROUP)
+
+    def run():
+        mm.generate(A, mm.BF16, m * k, 0, 1, mm.GEN_NORMAL, seed=seed, operand=0)
+        mm.generate(B, mm.BF16, n * k, 0, 1, mm.GEN_NORMAL, seed=seed, operand=1)
+        mm.generate(C, mm.FP32, m * n, 0, 1, mm.GEN_ZERO, seed=seed, operand=2)
+        mm.emulate_mma(chained, A, B, C, D0, m, n, k, 1, dt)
+        k0 = mm.last_kernel()
+        mm.emulate_mma(fused, A, B, C, D1, m, n, k, 1, dt)
+        k1 = mm.last_kernel()
+        mm.compare(D0, D1, m * n, st)
+        return k0, k1
+
+    kernels, secs = _timed(run)
+    mm.model_destroy(chained)
+    mm.model_destroy(fused)
+    return dict(terms=2 * m * n * k, seconds=secs, kernels=kernels, stats=mm.read_stats(st),
+                dev=dict(A=A, B=B, C=C, D0=D0, D1=D1))
+
+
+def config3(size=4096, seed=0, stride=100, dev="cuda"):
+    m = n = k = size
+    dt = (mm.E4M3, mm.E5M2, mm.FP32, mm.FP32)
+    A, B = _buf((m, k), mm.E4M3, dev), _buf((n, k), mm.E5M2, dev)
+    C, D = _buf((m, n), mm.FP32, dev), _buf((m, n), mm.FP32, dev)
+    ws = torch.empty(8, dtype=torch.uint8, device=dev)
+    err = torch.empty(mm.ERR_STATS_BYTES, dtype=torch.uint8, device=dev)
+    mm.err_stats_reset(err)
+    model = mm.model_create(group_len=32, frac_bits=14, out_round=mm.RNE)
+
+    def run():
+        mm.generate(A, mm.E4M3, m * k, 0, 1, mm.GEN_NORMAL, seed=seed, operand=0, scale_scope=mm.SCALE_TENSOR,
+                    scale_target=448.0, workspace=ws)
+        mm.generate(B, mm.E5M2, n * k, 0, 1, mm.GEN_NORMAL, seed=seed, operand=1, scale_scope=mm.SCALE_TENSOR,
+                    scale_target=57344.0, workspace=ws)
+        mm.generate(C, mm.FP32, m * n, 0, 1, mm.GEN_ZERO, seed=seed, operand=2)
+        mm.emulate_mma(model, A, B, C, D, m, n, k, 1, dt)
+        kern = mm.last_kernel()
+        mm.exact_dot_sample(A, B, D, m, n, k, dt, stride, err)
+        return kern
+
+    kernel, secs = _timed(run)
+    mm.model_destroy(model)
+    return dict(terms=m * n * k, seconds=secs, kernel=kernel, err_stats=mm.read_err_stats(err),
+                dev=dict(A=A, B=B, C=C, D=D))
+
+
+CONFIG4_VARIANTS = (("none", dict()), ("ftz_in", dict(ftz_in=True)), ("ftz_out", dict(ftz_out=True)))
+
+
+def config4_generate(A, B, C, first_tile, n_tiles, seed=0):
+    """fp16 A/B with sign, exponent field 0..30 and mantissa all uniform; fp32 C with exponent field
+    uniform over {0} and 79..158 (zero/subnormal, or the span of fp16 products)."""
+    mm.generate(A, mm.FP16, 32 * 8, first_tile, n_tiles, mm.GEN_UNIFORM_EXP, seed=seed, operand=0, exp_lo=0, exp_hi=30)
+    mm.generate(B, mm.FP16, 32 * 8, first_tile, n_tiles, mm.GEN_UNIFORM_EXP, seed=seed, operand=1, exp_lo=0, exp_hi=30)
+    mm.generate(C, mm.FP32, 32 * 32, first_tile, n_tiles, mm.GEN_UNIFORM_EXP, seed=seed, operand=2, exp_lo=79,
+                exp_hi=158, exp_zero=True)
+
+
+def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk=False):
+    m = n = 32
+    k = 8
+    dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
+    chunk = min(chunk, n_tiles)
+    A, B = _buf((chunk, m, k), mm.FP16, dev), _buf((chunk, n, k), mm.FP16, dev)
+    C = _buf((chunk, m, n), mm.FP32, dev)
+    Ds = [_buf((chunk, m, n), mm.FP32, dev) for _ in CONFIG4_VARIANTS]
+    stats = [_stats_buf(dev) for _ in CONFIG4_VARIANTS]
+    models = [mm.model_create(group_len=8, frac_bits=24, out_round=mm.RNE, **kw) for _, kw in CONFIG4_VARIANTS]
+    kept = {}
+
+    def run():
+        kern = None
+        for t0 in range(0, n_tiles, chunk):
+            nt = min(chunk, n_tiles - t0)
+            config4_generate(A, B, C, t0, nt, seed)
+            for h, D in zip(models, Ds):
+                mm.emulate_mma(h, A, B, C, D, m, n, k, nt, dt)
+            kern = mm.last_kernel()
+            for st, D in zip(stats, Ds):
+                mm.compare(D, Ds[0], nt * m * n, st, index_base=t0 * m * n)
+            if keep_first_chunk and t0 == 0:
+                torch.cuda.synchronize()
+                kept.update(A=A.clone(), B=B.clone(), C=C.clone(), D=[D.clone() for D in Ds])
+        return kern
+
+    kernel, secs = _timed(run)
+    for h in models:
+        mm.model_destroy(h)
+    return dict(terms=3 * n_tiles * m * n * k, seconds=secs, kernel=kernel,
+                stats={name: mm.read_stats(st) for (name, _), st in zip(CONFIG4_VARIANTS, stats)}, dev=kept)
+
+
+# (F, L_max, output rounding, flush both ways)
+CONFIG5_MODELS = [(16, 4, mm.RNE, 0), (16, 8, mm.RZ, 1), (16, 16, mm.RNE, 1), (16, 64, mm.RZ, 0),
+                  (20, 4, mm.RZ, 1), (20, 8, mm.RNE, 0), (20, 16, mm.RZ, 0), (20, 32, mm.RNE, 1),
+                  (24, 4, mm.RNE, 1), (24, 8, mm.RZ, 0), (24, 16, mm.RNE, 0), (24, 32, mm.RZ, 1),
+                  (28, 8, mm.RNE, 1), (32, 4, mm.RZ, 0), (32, 16, mm.RZ, 1), (32, 64, mm.RNE, 0)]
+
+
+def config5_generate(kind, A, B, C, first_tile, n_tiles, seed=0):
+    """kind "bf16": uniform finite bf16 bit patterns; kind "fp8": N(0,1) scaled per tile to the format
+    maximum, A e4m3 and B e5m2.  C ~ N(0,1) fp32 for both."""
+    if kind == "bf16":
+        mm.generate(A, mm.BF16, 256, first_tile, n_tiles, mm.GEN_FINITE_BITS, seed=seed, operand=0)
+        mm.generate(B, mm.BF16, 256, first_tile, n_tiles, mm.GEN_FINITE_BITS, seed=seed, operand=1)
+    else:
+        mm.generate(A, mm.E4M3, 256, first_tile, n_tiles, mm.GEN_NORMAL, seed=seed, operand=0,
+                    scale_scope=mm.SCALE_TILE, scale_target=448.0)
+        mm.generate(B, mm.E5M2, 256, first_tile, n_tiles, mm.GEN_NORMAL, seed=seed, operand=1,
+                    scale_scope=mm.SCALE_TILE, scale_target=57344.0)
+    mm.generate(C, mm.FP32, 256, first_tile, n_tiles, mm.GEN_NORMAL, seed=seed, operand=2)
+
+
+def config5(n_tiles=1 << 24, chunk=1 << 16, seed=0, dev="cuda", kinds=("bf16", "fp8"), keep_first_chunk=False):
+    m = n = k = 16
+    out = {}
+    for kind in kinds:
+        ta, tb = (mm.BF16, mm.BF16) if kind == "bf16" else (mm.E4M3, mm.E5M2)
+        instr = mm.MFMA_F32_16X16X16_BF16 if kind == "bf16" else mm.MFMA_F32_16X16X32_FP8_BF8
+        dt = (ta, tb, mm.FP32, mm.FP32)
+        ch = min(chunk, n_tiles)
+        A, B = _buf((ch, m, k), ta, dev), _buf((ch, n, k), tb, dev)
+        C, Dhw, D = (_buf((ch, m, n), mm.FP32, dev) for _ in range(3))
+        stats = [_stats_buf(dev) for _ in CONFIG5_MODELS]
+        models = [mm.model_create(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(ftz), ftz_out=bool(ftz))
+                  for F, L, rho, ftz in CONFIG5_MODELS]
+        kept = {}
+        kernels = []
+
+        def run():
+            for t0 in range(0, n_tiles, ch):
+                nt = min(ch, n_tiles - t0)
+                config5_generate(kind, A, B, C, t0, nt, seed)
+                mm.mfma_probe(instr, A, B, C, Dhw, k, nt)          # fp8: k positions 16..31 are fed as zeros
+                keep = keep_first_chunk and t0 == 0
+                if keep:
+                    torch.cuda.synchronize()
+                    kept.update(A=A.clone(), B=B.clone(), C=C.clone(), Dhw=Dhw.clone(), D=[])
+                for i, (h, st) in enumerate(zip(models, stats)):
+                    mm.emulate_mma(h, A, B, C, D, m, n, k, nt, dt)
+                    if t0 == 0:
+                        kernels.append(mm.last_kernel())
+                    mm.compare(D, Dhw, nt * m * n, st, index_base=t0 * m * n)
+                    if keep:
+                        torch.cuda.synchronize()
+                        kept["D"].append(D.clone())
+
+        _, secs = _timed(run)
+        for h in models:
+            mm.model_destroy(h)
+        res = [mm.read_stats(st) for st in stats]
+        out[kind] = dict(terms=len(CONFIG5_MODELS) * n_tiles * m * n * k, seconds=secs, kernels=kernels, stats=res,
+                         agreement=[1.0 - s["n_mismatch_bits"] / max(s["n_compared"], 1) for s in res], dev=kept)
+    return out
