@@ -29,6 +29,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--size", type=int, default=1024, help="m = n = k of the GEMM-shaped workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="before the timed region, run 5 plain device copies of 64 MiB (a kernel of known traffic, "
+                         "to scale FETCH_SIZE / WRITE_SIZE counters collected under rocprofv3 --pmc)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target duration of the CPU-oracle sample")
     return ap.parse_args()
 
@@ -102,6 +105,12 @@ def main():
             events[2].record()
         mm.compare(D0, D1, m * n, stats)
 
+    if args.copy_calibration:
+        src = torch.arange(16 * 1024 * 1024, dtype=torch.int32, device=dev)       # 64 MiB read + 64 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)                                             # one elementwise kernel per call
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

@@ -129,9 +129,12 @@ mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s)
 mmaemu_status launch_compare(const uint32_t *d0, const uint32_t *d1, uint64_t count, uint64_t base,
                              mmaemu_stats *st, hipStream_t s)
 {
-    uint64_t blocks = (count / 4 + 255) / 256;
+    // Few, fat workgroups: every workgroup ends with up to ~40 global atomics on the same
+    // few addresses, and those serialise across the chip, so a workgroup should cover at
+    // least 32K pairs (128 per thread) before it pays for them.
+    uint64_t blocks = (count + 32767) / 32768;
     if (blocks < 1) blocks = 1;
-    if (blocks > 256 * 8) blocks = 256 * 8;         // 8 workgroups per compute unit, grid-stride
+    if (blocks > 1024) blocks = 1024;               // grid-stride beyond that
     hipLaunchKernelGGL(compare_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, d0, d1, count, base, st);
     MMAEMU_HIP(hipGetLastError());
     return MMAEMU_OK;

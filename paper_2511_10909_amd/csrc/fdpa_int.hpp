@@ -92,7 +92,8 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
 
 
 // run-time operand types (used where a template per type pair is not worth its code size)
-__device__ __noinline__ uint32_t fdpa_group_raw(const ModelArgs &p, uint32_t ta, uint32_t tb, const void *a, const void *b,
+// (parameters by value: a reference would force the caller to keep a copy of them in scratch memory)
+__device__ __noinline__ uint32_t fdpa_group_raw(ModelArgs p, uint32_t ta, uint32_t tb, const void *a, const void *b,
                                                 uint32_t L, uint32_t c)
 {
 #define MMAEMU_CASE(X, Y)                                                                             \
