@@ -4,24 +4,33 @@
 
 namespace mmaemu {
 
+template <int VM>
+static mmaemu_status launch_vm(const TiledArgs &t, const void *A, const void *B, const void *Cm, void *D, uint32_t m, uint32_t n,
+                               uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
+{
+    return t.p.c_mode == MMAEMU_C_IN_GROUP
+               ? launch_tiled_shape<MMAEMU_C_IN_GROUP, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled)
+               : launch_tiled_shape<MMAEMU_C_AFTER_EXACT, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+}
+
 mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *Cm, void *D,
                              uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb,
                              hipStream_t s)
 {
-    // the tiled kernels take F <= 29 (an aligned term must fit a 32-bit integer), 8-byte
-    // aligned operand arrays (four consecutive k elements are loaded at once) and group
-    // sums below 2^52
+    // the tiled kernels need 8-byte aligned operand arrays (four consecutive k elements are
+    // loaded at once) and group sums below 2^52
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) == 0;
-    if (p.F <= 29 && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
+    if (aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;
         t.ta = ta;
         t.tb = tb;
         t.ebase = 2 - fmt_info(ta).bias - fmt_info(tb).bias;
         bool handled = false;
-        mmaemu_status st = p.c_mode == MMAEMU_C_IN_GROUP
-                               ? launch_tiled_shape<MMAEMU_C_IN_GROUP>(t, A, B, Cm, D, m, n, k, batch, s, handled)
-                               : launch_tiled_shape<MMAEMU_C_AFTER_EXACT>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        mmaemu_status st;
+        if (p.F >= 30) st = launch_vm<2>(t, A, B, Cm, D, m, n, k, batch, s, handled);             // wide F: binary64 terms
+        else if (ta == MMAEMU_BF16 || tb == MMAEMU_BF16) st = launch_vm<1>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        else st = launch_vm<0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         if (handled) return st;
     }
     return launch_emulate_generic(p, A, B, Cm, D, m, n, k, batch, ta, tb, s);

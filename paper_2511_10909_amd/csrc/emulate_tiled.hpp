@@ -21,10 +21,18 @@
 //     sum is formed by an error-free binary64 addition whose result is rounded to odd
 //     when inexact, so that the conversion to binary32 still rounds once.
 //
-// Elements whose value leaves the range in which the binary32 product is exact and
-// normal (|x| outside [2^-31, 2^32), only possible for BF16), and NaN/infinity, are
-// tagged with an exponent sentinel; a group that meets one is recomputed by the integer
-// routine of the general kernel from the raw operands in global memory.
+// Value modes (template parameter VM):
+//   0  binary32 values only: FP8 / FP16 operands, whose products always fit binary32;
+//   1  adaptive: BF16 operands.  A staged chunk whose elements all lie in [2^-31, 2^32) (or
+//      are zero) is handled in binary32 as above; a chunk with any element outside that
+//      range is staged as binary64 values and pass 2 runs in binary64 (product and
+//      alignment exact for any finite operands), still truncating with the float->int
+//      conversion;
+//   2  wide F (30..40): binary64 values, terms truncated with v_trunc_f64 and summed in
+//      binary64 (exact below 2^53).
+// NaN and infinities are tagged with an exponent sentinel; a group that meets one is
+// recomputed by the integer routine of the general kernel from the raw operands in
+// global memory.
 #pragma once
 #include "fdpa_int.hpp"
 
@@ -54,8 +62,8 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 
 // ---- decode while staging --------------------------------------------------------------
 
-// One element -> (exact binary32 value, e' = max(E, 1) - 1), or the sentinel tag for NaN,
-// infinities and values outside [2^-31, 2^32) (only BF16 has such finite values).
+// One element -> exact binary32 value (every supported operand value is a binary32 number)
+// and e' = max(E, 1) - 1, or the sentinel tag for NaN / infinities.
 template <int T>
 __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, float &val, uint32_t &ex)
 {
@@ -65,12 +73,9 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, floa
     ex = (E ? E : 1u) - 1u;
     if (T == MMAEMU_BF16) {
         // the value is the pattern moved to the top half of a binary32 word
-        const uint32_t mag = bits & 0x7FFFu;
-        const bool tagged = mag != 0 && (E - 96u) > 62u;        // covers E = 255 and subnormals
-        uint32_t vb = bits << 16;
-        if (ftz_in && E == 0) vb = 0;                           // FlushSubnormal: -> +0.0
-        val = __uint_as_float(vb);
-        if (tagged && !(ftz_in && E == 0)) { ex = SENTINEL; val = 0.0f; }
+        const bool flushed = ftz_in && E == 0;                  // FlushSubnormal: -> +0.0
+        val = __uint_as_float(flushed ? 0u : bits << 16);
+        if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
     } else if (T == MMAEMU_FP16) {
         _Float16 h;
         const uint16_t hb = (uint16_t)bits;
@@ -91,7 +96,7 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, floa
 
 // four consecutive k elements of one row: raw little-endian bytes in `raw`
 template <int T>
-__device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float4 &v, uint2 &e)
+__device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float (&f)[4], uint2 &e)
 {
     uint32_t b[4];
     if (Fmt<T>::W == 8) {
@@ -99,10 +104,9 @@ __device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float4 &v, u
     } else {
         b[0] = raw.x & 0xFFFFu; b[1] = raw.x >> 16; b[2] = raw.y & 0xFFFFu; b[3] = raw.y >> 16;
     }
-    float f[4]; uint32_t x[4];
+    uint32_t x[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, f[q], x[q]);
-    v = make_float4(f[0], f[1], f[2], f[3]);
     e = make_uint2(x[0] | (x[1] << 16), x[2] | (x[3] << 16));
 }
 
@@ -141,35 +145,70 @@ __device__ __forceinline__ void make_plan(StagePlan<NQ> &pl, const void *base, u
     }
 }
 
-template <int T, int NQ>
-__device__ __forceinline__ void stage_panel(const StagePlan<NQ> &pl, uint32_t k0, uint32_t ftz_in, float *lv, uint32_t *le)
+// global -> registers
+template <int NQ>
+__device__ __forceinline__ void load_panel(uint32_t esize, const StagePlan<NQ> &pl, uint32_t k0, uint2 (&raw)[NQ])
 {
-    using elem = typename Fmt<T>::elem;
-    uint2 raw[NQ];
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-        const elem *src = reinterpret_cast<const elem *>(pl.src[i]) + k0 + pl.kq4[i];
-        if (Fmt<T>::W == 8) { raw[i].x = *reinterpret_cast<const uint32_t *>(src); raw[i].y = 0; }
+        const uint8_t *src = pl.src[i] + (uint64_t)(k0 + pl.kq4[i]) * esize;
+        if (esize == 1) { raw[i].x = *reinterpret_cast<const uint32_t *>(src); raw[i].y = 0; }
         else raw[i] = *reinterpret_cast<const uint2 *>(src);
-    }
-#pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-        float4 v; uint2 e;
-        decode4<T>(raw[i], ftz_in, v, e);
-        *reinterpret_cast<float4 *>(lv + pl.voff[i]) = v;
-        *reinterpret_cast<uint2 *>(le + pl.eoff[i]) = e;
     }
 }
 
+// registers -> decoded LDS.  `as_double`: values are written as binary64 (row stride VSD
+// doubles) instead of binary32 (row stride VS floats); WHAT bit 0: exponents, bit 1: values.
+template <int T, int NQ, int VS, int VSD>
+__device__ __forceinline__ void decode_panel(const StagePlan<NQ> &pl, const uint2 (&raw)[NQ], uint32_t ftz_in, void *lv,
+                                             uint32_t *le, bool as_double, int what)
+{
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        float f[4]; uint2 e;
+        decode4<T>(raw[i], ftz_in, f, e);
+        if (what & 1) *reinterpret_cast<uint2 *>(le + pl.eoff[i]) = e;
+        if (what & 2) {
+            if (as_double) {
+                // voff = row * VS + 4*kq  ->  row * VSD + 4*kq
+                const uint32_t row = pl.voff[i] / VS, kq4 = pl.voff[i] - row * VS;
+                double *dst = reinterpret_cast<double *>(lv) + row * VSD + kq4;
+                *reinterpret_cast<double2 *>(dst) = make_double2((double)f[0], (double)f[1]);
+                *reinterpret_cast<double2 *>(dst + 2) = make_double2((double)f[2], (double)f[3]);
+            } else {
+                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(lv) + pl.voff[i]) = make_float4(f[0], f[1], f[2], f[3]);
+            }
+        }
+    }
+}
+
+// is any element of the loaded quads a finite BF16 value outside [2^-31, 2^32)?
 template <int NQ>
-__device__ __forceinline__ void stage_any(uint32_t t, const StagePlan<NQ> &pl, uint32_t k0, uint32_t ftz_in, float *lv,
-                                          uint32_t *le)
+__device__ __forceinline__ bool any_wild_bf16(const uint2 (&raw)[NQ], uint32_t ftz_in)
+{
+    bool wild = false;
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) {
+        const uint32_t w[2] = {raw[i].x, raw[i].y};
+#pragma unroll
+        for (int h = 0; h < 4; ++h) {
+            const uint32_t bits = (w[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
+            const uint32_t E = (bits >> 7) & 0xFFu;
+            wild |= !(ftz_in && E == 0) && (bits & 0x7FFFu) != 0 && E != 0xFFu && (E - 96u) > 62u;
+        }
+    }
+    return wild;
+}
+
+template <int NQ, int VS, int VSD>
+__device__ __forceinline__ void decode_any(uint32_t t, const StagePlan<NQ> &pl, const uint2 (&raw)[NQ], uint32_t ftz_in,
+                                           void *lv, uint32_t *le, bool as_double, int what)
 {
     switch (t) {   // uniform
-    case MMAEMU_FP8_E4M3: stage_panel<MMAEMU_FP8_E4M3, NQ>(pl, k0, ftz_in, lv, le); break;
-    case MMAEMU_FP8_E5M2: stage_panel<MMAEMU_FP8_E5M2, NQ>(pl, k0, ftz_in, lv, le); break;
-    case MMAEMU_FP16: stage_panel<MMAEMU_FP16, NQ>(pl, k0, ftz_in, lv, le); break;
-    default: stage_panel<MMAEMU_BF16, NQ>(pl, k0, ftz_in, lv, le); break;
+    case MMAEMU_FP8_E4M3: decode_panel<MMAEMU_FP8_E4M3, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
+    case MMAEMU_FP8_E5M2: decode_panel<MMAEMU_FP8_E5M2, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
+    case MMAEMU_FP16: decode_panel<MMAEMU_FP16, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
+    default: decode_panel<MMAEMU_BF16, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
     }
 }
 
@@ -185,8 +224,9 @@ struct TiledArgs {
 // TM x TN : block of D per slot;  R x C: register block per thread;
 // KC      : k elements staged at a time;
 // LT      : group length if it divides KC, 0 if a group spans whole chunks (L % KC == 0);
-// NF      : terms summed in 32 bits between folds into binary64 (0: once per group/chunk).
-template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF>
+// NF      : terms summed in 32 bits between folds into binary64 (0: once per group/chunk);
+// VM      : value mode (see the head of this file).
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF, int VM>
 __global__ void __launch_bounds__(256)
 emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm,
                      uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nitems, uint32_t bm_count,
@@ -194,13 +234,16 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 {
     constexpr int TI = TM / R, TJ = TN / C, TPS = TI * TJ, SLOTS = 256 / TPS;
     static_assert(TPS * SLOTS == 256, "thread layout");
-    constexpr int VS = KC + 4;                       // LDS row strides (dwords), padded against bank conflicts
-    constexpr int ES = KC / 2 + (KC == 16 ? 2 : 4);
+    constexpr int VS = KC + 4;                       // LDS row stride of binary32 values (floats), padded
+    constexpr int VSD = KC + 2;                      // LDS row stride of binary64 values (doubles)
+    constexpr int ES = KC / 2 + (KC == 16 ? 2 : 4);  // LDS row stride of packed exponents (dwords)
     constexpr int GL = LT ? LT : KC;                 // terms per inner step
     constexpr int FOLD = NF ? NF : GL;
-    constexpr bool USE_SD = (NF != 0) || (LT == 0);  // binary64 accumulator needed
-    __shared__ __attribute__((aligned(16))) float Av[SLOTS * TM * VS];
-    __shared__ __attribute__((aligned(16))) float Bv[SLOTS * TN * VS];
+    constexpr bool USE_SD = (NF != 0) || (LT == 0) || (VM == 2);   // binary64 accumulator needed
+    constexpr int VBYTES_A = SLOTS * TM * (VM == 0 ? VS * 4 : VSD * 8);
+    constexpr int VBYTES_B = SLOTS * TN * (VM == 0 ? VS * 4 : VSD * 8);
+    __shared__ __attribute__((aligned(16))) unsigned char Av_raw[VBYTES_A];
+    __shared__ __attribute__((aligned(16))) unsigned char Bv_raw[VBYTES_B];
     __shared__ __attribute__((aligned(16))) uint32_t Ae[SLOTS * TM * ES];
     __shared__ __attribute__((aligned(16))) uint32_t Be[SLOTS * TN * ES];
 
@@ -215,10 +258,11 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     if (xcd_remap) wg = (wg & 7u) * (gridDim.x >> 3) + (wg >> 3);
     const uint64_t item0 = (uint64_t)wg * SLOTS;
     constexpr int NQA = (SLOTS * TM * (KC / 4) + 255) / 256, NQB = (SLOTS * TN * (KC / 4) + 255) / 256;
+    const uint32_t esa = ta_.ta <= MMAEMU_FP8_E5M2 ? 1u : 2u, esb = ta_.tb <= MMAEMU_FP8_E5M2 ? 1u : 2u;
     StagePlan<NQA> plan_a;
     StagePlan<NQB> plan_b;
-    make_plan<TM, KC, SLOTS, VS, ES, true, NQA>(plan_a, A, ta_.ta <= MMAEMU_FP8_E5M2 ? 1u : 2u, item0, nitems, bm_count, bn_count, m, k);
-    make_plan<TN, KC, SLOTS, VS, ES, false, NQB>(plan_b, B, ta_.tb <= MMAEMU_FP8_E5M2 ? 1u : 2u, item0, nitems, bm_count, bn_count, n, k);
+    make_plan<TM, KC, SLOTS, VS, ES, true, NQA>(plan_a, A, esa, item0, nitems, bm_count, bn_count, m, k);
+    make_plan<TN, KC, SLOTS, VS, ES, false, NQB>(plan_b, B, esb, item0, nitems, bm_count, bn_count, n, k);
 
     const bool live = item0 + slot < nitems;
     uint64_t my_it = item0 + slot;
@@ -235,14 +279,17 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 #pragma unroll
         for (int c = 0; c < C; ++c) d[r][c] = Cm[d_off + (uint64_t)(TI * r) * n + TJ * c];
 
-    const float *av = Av + (slot * TM + ti) * VS;
-    const float *bv = Bv + (slot * TN + tj) * VS;
+    const float *av = reinterpret_cast<const float *>(Av_raw) + (slot * TM + ti) * VS;
+    const float *bv = reinterpret_cast<const float *>(Bv_raw) + (slot * TN + tj) * VS;
+    const double *avd = reinterpret_cast<const double *>(Av_raw) + (slot * TM + ti) * VSD;
+    const double *bvd = reinterpret_cast<const double *>(Bv_raw) + (slot * TN + tj) * VSD;
     const uint32_t *ae = Ae + (slot * TM + ti) * ES;
     const uint32_t *be = Be + (slot * TN + tj) * ES;
 
     uint32_t m2[R][C];                                          // packed running maxima of e'
     int32_t S32[R][C];
     double Sd[R][C];
+    bool chunk_is_double = (VM == 2);                           // how the staged chunk's values are held
 
     // pass 1: running maxima of e' = e'_a + e'_b, two products per packed instruction;
     // EW dwords (2*EW exponents) per LDS read and row
@@ -273,9 +320,25 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         }
     };
 
-    // pass 2: aligned, truncated terms summed in 32 bits; four k per LDS read and row
+    auto fold = [&]() {
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) { Sd[r][c] += (double)S32[r][c]; S32[r][c] = 0; }
+    };
+
+    // pass 2, binary32 values: aligned, truncated terms summed in 32 bits; four k per LDS read and row
     constexpr int U2 = (GL / 4 <= 2) ? 2 : 1;
-    auto pass2 = [&](int g, const float (&scale)[R][C]) {
+    auto pass2f = [&](int g, const int (&emax)[R][C]) {
+        float scale[R][C];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                int se = F + 127 - emax[r][c];                         // biased exponent of 2^(F - e_max)
+                se = se < 1 ? 1 : (se > 254 ? 254 : se);               // the clamps never change a truncated term
+                scale[r][c] = __uint_as_float((uint32_t)se << 23);
+            }
 #pragma unroll U2
         for (int q = 0; q < GL; q += 4) {
             float a[R][4], b[C][4];
@@ -295,24 +358,51 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                 for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int c = 0; c < C; ++c) S32[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale[r][c]);
-                if (USE_SD && (FOLD < 4) && (w + 1) % FOLD == 0) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int c = 0; c < C; ++c) { Sd[r][c] += (double)S32[r][c]; S32[r][c] = 0; }
-                }
+                if (USE_SD && (FOLD < 4) && (w + 1) % FOLD == 0) fold();
             }
-            if (USE_SD && (FOLD >= 4) && (q + 4) % FOLD == 0) {
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int c = 0; c < C; ++c) { Sd[r][c] += (double)S32[r][c]; S32[r][c] = 0; }
-            }
+            if (USE_SD && (FOLD >= 4) && (q + 4) % FOLD == 0) fold();
         }
     };
 
-    // end of pass 1 for one element: e_max and the alignment factor 2^(F - e_max)
-    auto exponents = [&](int r, int c, int &emax, float &scale, uint32_t &tagged) {
+    // pass 2, binary64 values (any finite operands; also wide F): two k per LDS read and row
+    auto pass2d = [&](int g, const int (&emax)[R][C]) {
+        double scale[R][C];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+                scale[r][c] = __hiloint2double((F - emax[r][c] + 1023) << 20, 0);      // 2^(F - e_max), always normal
+#pragma unroll 1
+        for (int q = 0; q < GL; q += 2) {
+            double a[R][2], b[C][2];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const double2 v = *reinterpret_cast<const double2 *>(avd + TI * r * VSD + g * GL + q);
+                a[r][0] = v.x; a[r][1] = v.y;
+            }
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const double2 v = *reinterpret_cast<const double2 *>(bvd + TJ * c * VSD + g * GL + q);
+                b[c][0] = v.x; b[c][1] = v.y;
+            }
+#pragma unroll
+            for (int w = 0; w < 2; ++w) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        const double t = (a[r][w] * b[c][w]) * scale[r][c];            // exact product, exact scaling
+                        if (VM == 2) Sd[r][c] += __builtin_trunc(t);
+                        else S32[r][c] += (int32_t)t;
+                    }
+                if (VM != 2 && USE_SD && FOLD == 1) fold();
+            }
+            if (VM != 2 && USE_SD && FOLD >= 2 && (q + 2) % FOLD == 0) fold();
+        }
+    };
+
+    // end of pass 1 for one element: e_max (products, and the accumulator when it is a term)
+    auto exponents = [&](int r, int c, int &emax, uint32_t &tagged) {
         const uint32_t e = m2[r][c];
         tagged |= e;
         const uint32_t lo = e & 0xFFFFu, hi = e >> 16;
@@ -323,15 +413,11 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
             em = ec > em ? ec : em;
         }
         emax = em;
-        int se = F + 127 - em;                                         // biased exponent of 2^(F - e_max)
-        se = se < 1 ? 1 : (se > 254 ? 254 : se);                       // the clamps never change a truncated term
-        scale = __uint_as_float((uint32_t)se << 23);
     };
 
     auto slow_group = [&](int r, int c, uint32_t kg, uint32_t cin) -> uint32_t {
         const uint64_t arow = my_tile * m + i_base + TI * r;
         const uint64_t brow = my_tile * n + j_base + TJ * c;
-        const uint32_t esa = ta_.ta <= MMAEMU_FP8_E5M2 ? 1u : 2u, esb = ta_.tb <= MMAEMU_FP8_E5M2 ? 1u : 2u;
         const uint8_t *a = reinterpret_cast<const uint8_t *>(A) + (arow * k + kg) * esa;
         const uint8_t *b = reinterpret_cast<const uint8_t *>(B) + (brow * k + kg) * esb;
         return fdpa_group_raw(p, ta_.ta, ta_.tb, a, b, p.L, cin);
@@ -431,40 +517,62 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
             for (int c = 0; c < C; ++c) { m2[r][c] = 0; S32[r][c] = 0; Sd[r][c] = 0.0; }
     };
 
-    auto stage = [&](uint32_t k0) {
+    // Stage one chunk.  WHAT bit 0: exponents, bit 1: values.  In the adaptive mode the
+    // workgroup first agrees (through the barrier that also protects the previous chunk's
+    // readers) on whether any loaded element needs binary64.
+    auto stage = [&](uint32_t k0, int what) {
+        uint2 raw_a[NQA], raw_b[NQB];
+        load_panel<NQA>(esa, plan_a, k0, raw_a);
+        load_panel<NQB>(esb, plan_b, k0, raw_b);
+        if (VM == 1) {
+            bool wild = false;
+            if (what & 2) {
+                if (ta_.ta == MMAEMU_BF16) wild |= any_wild_bf16<NQA>(raw_a, p.ftz_in);
+                if (ta_.tb == MMAEMU_BF16) wild |= any_wild_bf16<NQB>(raw_b, p.ftz_in);
+            }
+            chunk_is_double = __syncthreads_or(wild) != 0;
+        } else {
+            __syncthreads();
+        }
+        decode_any<NQA, VS, VSD>(ta_.ta, plan_a, raw_a, p.ftz_in, Av_raw, Ae, chunk_is_double, what);
+        decode_any<NQB, VS, VSD>(ta_.tb, plan_b, raw_b, p.ftz_in, Bv_raw, Be, chunk_is_double, what);
         __syncthreads();
-        stage_any<NQA>(ta_.ta, plan_a, k0, p.ftz_in, Av, Ae);
-        stage_any<NQB>(ta_.tb, plan_b, k0, p.ftz_in, Bv, Be);
-        __syncthreads();
+    };
+
+    auto pass2 = [&](int g, const int (&emax)[R][C]) {
+        if (VM == 0) pass2f(g, emax);
+        else if (VM == 2) pass2d(g, emax);
+        else if (chunk_is_double) pass2d(g, emax);
+        else pass2f(g, emax);
     };
 
     if (LT != 0) {
         for (uint32_t k0 = 0; k0 < k; k0 += KC) {
-            stage(k0);
+            stage(k0, 3);
 #pragma unroll 1
             for (int g = 0; g < KC / GL; ++g) {
                 reset_group();
                 pass1(g);
-                float scale[R][C]; int emax[R][C]; uint32_t tagged = 0;
+                int emax[R][C]; uint32_t tagged = 0;
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], scale[r][c], tagged);
-                pass2(g, scale);
+                    for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], tagged);
+                pass2(g, emax);
                 end_of_group(k0 + g * GL, emax, tagged);
             }
         }
     } else {
-        // a group of p.L terms spans p.L / KC chunks: sweep the group's chunks twice
+        // a group of p.L terms spans p.L / KC chunks: one sweep for the exponents, one for the values
         for (uint32_t kg = 0; kg < k; kg += p.L) {
             reset_group();
-            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0); pass1(0); }
-            float scale[R][C]; int emax[R][C]; uint32_t tagged = 0;
+            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0, 1); pass1(0); }
+            int emax[R][C]; uint32_t tagged = 0;
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], scale[r][c], tagged);
-            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0); pass2(0, scale); }
+                for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], tagged);
+            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0, 2); pass2(0, emax); }
             end_of_group(kg, emax, tagged);
         }
     }
@@ -484,7 +592,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 
 // ---- host side ---------------------------------------------------------------------------
 
-template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF>
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF, int VM>
 static mmaemu_status launch_cfg(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
                                 uint32_t n, uint32_t k, uint64_t batch, hipStream_t s)
 {
@@ -494,72 +602,86 @@ static mmaemu_status launch_cfg(const TiledArgs &ta, const void *A, const void *
     const uint64_t blocks = (nitems + SLOTS - 1) / SLOTS;
     if (blocks > 0x7FFFFFFFull) { set_error("emulate_mma: too many blocks"); return MMAEMU_ERR_SHAPE; }
     const uint32_t remap = (blocks % 8 == 0 && blocks >= 64) ? 1u : 0u;
-    hipLaunchKernelGGL((emulate_tiled_kernel<TM, TN, R, C, KC, LT, CMODE, NF>), dim3((uint32_t)blocks), dim3(256), 0, s,
+    hipLaunchKernelGGL((emulate_tiled_kernel<TM, TN, R, C, KC, LT, CMODE, NF, VM>), dim3((uint32_t)blocks), dim3(256), 0, s,
                        ta, A, B, (const uint32_t *)Cm, (uint32_t *)D, m, n, k, nitems, bm, bn, remap);
     MMAEMU_HIP(hipGetLastError());
-    set_last_kernel("tiled %dx%d r%dx%d kc=%d L=%d c_mode=%d fold=%d", TM, TN, R, C, KC, LT ? LT : (int)ta.p.L, CMODE, NF);
+    set_last_kernel("tiled %dx%d r%dx%d kc=%d L=%d c_mode=%d fold=%d vm=%d", TM, TN, R, C, KC, LT ? LT : (int)ta.p.L, CMODE,
+                    NF, VM);
     return MMAEMU_OK;
 }
 
 // choose the fold period: the largest of {whole group, 4, 1} whose 32-bit partial sums cannot overflow
-template <int TM, int TN, int R, int C, int KC, int LT, int CMODE>
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int VM>
 static mmaemu_status launch_fold(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
                                  uint32_t n, uint32_t k, uint64_t batch, hipStream_t s)
 {
-    constexpr int GL = LT ? LT : KC;
-    const uint64_t term = 1ull << (ta.p.F + 2);                 // |aligned term| < 2^(F+2)
-    if (GL * term <= (1ull << 31)) return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0>(ta, A, B, Cm, D, m, n, k, batch, s);
-    if (4 * term <= (1ull << 31)) return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 4>(ta, A, B, Cm, D, m, n, k, batch, s);
-    return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 1>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if constexpr (VM == 2) {
+        return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0, VM>(ta, A, B, Cm, D, m, n, k, batch, s);   // terms summed in binary64
+    } else {
+        constexpr int GL = LT ? LT : KC;
+        const uint64_t term = 1ull << (ta.p.F + 2);             // |aligned term| < 2^(F+2)
+        if (GL * term <= (1ull << 31)) return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+        if (4 * term <= (1ull << 31)) return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 4, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+        return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 1, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+    }
 }
 
-template <int TM, int TN, int R, int C, int KC, int CMODE>
+template <int TM, int TN, int R, int C, int KC, int CMODE, int VM>
 static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
                               uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
 {
     handled = true;
     const uint32_t L = ta.p.L;
-    if (L == 4) return launch_fold<TM, TN, R, C, KC, 4, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
-    if (L == 8) return launch_fold<TM, TN, R, C, KC, 8, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if (L == 4) return launch_fold<TM, TN, R, C, KC, 4, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if (L == 8) return launch_fold<TM, TN, R, C, KC, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     if constexpr (KC >= 16) {
-        if (L == 16) return launch_fold<TM, TN, R, C, KC, 16, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+        if (L == 16) return launch_fold<TM, TN, R, C, KC, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     }
     if constexpr (KC >= 32) {
-        if (L == 32) return launch_fold<TM, TN, R, C, KC, 32, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+        if (L == 32) return launch_fold<TM, TN, R, C, KC, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     }
-    if (L % KC == 0) return launch_fold<TM, TN, R, C, KC, 0, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if (L % KC == 0) return launch_fold<TM, TN, R, C, KC, 0, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     handled = false;
     return MMAEMU_OK;
 }
 
-template <int CMODE>
+template <int CMODE, int VM>
 mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
-                                  uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
+                                 uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
 {
     handled = false;
     const uint64_t outputs = batch * m * n;
-    // whole small tiles of a batch
-    if (m == 16 && n == 16 && k % 16 == 0) return launch_L<16, 16, 4, 4, 16, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    // whole small tiles of a batch (binary64 values need twice the LDS: fewer tiles per workgroup)
+    if (m == 16 && n == 16 && k % 16 == 0) {
+        if constexpr (VM == 0) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    }
     if (m == 32 && n == 32 && k % 8 == 0 && k % 32 != 0)
-        return launch_L<32, 32, 4, 4, 8, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     // blocks of a larger problem: 4x4 register blocks once there are enough outputs to fill
     // the chip with them (256 CUs x 4 SIMDs x 2 waves x 64 lanes x 16), 2x2 blocks otherwise
     if (m % 64 == 0 && n % 64 == 0 && k % 32 == 0 && outputs >= (1ull << 21))
-        return launch_L<64, 64, 4, 4, 32, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_L<64, 64, 4, 4, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 32 == 0 && n % 32 == 0 && k % 32 == 0)
-        return launch_L<32, 32, 2, 2, 32, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_L<32, 32, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
-        return launch_L<32, 32, 4, 4, 8, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
-    if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0)
-        return launch_L<16, 16, 4, 4, 16, CMODE>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) {
+        if constexpr (VM == 0) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    }
     return MMAEMU_OK;
 }
 
-
-// explicit instantiations live in emulate_tiled_c0.hip / emulate_tiled_c1.hip (one per accumulation mode)
-extern template mmaemu_status launch_tiled_shape<MMAEMU_C_IN_GROUP>(const TiledArgs &, const void *, const void *, const void *,
-                                                                   void *, uint32_t, uint32_t, uint32_t, uint64_t, hipStream_t, bool &);
-extern template mmaemu_status launch_tiled_shape<MMAEMU_C_AFTER_EXACT>(const TiledArgs &, const void *, const void *, const void *,
-                                                                      void *, uint32_t, uint32_t, uint32_t, uint64_t, hipStream_t, bool &);
+// explicit instantiations live in emulate_tiled_c<CMODE>v<VM>.hip (one translation unit each)
+#define MMAEMU_TILED_SIG(CM, VM)                                                                                        \
+    mmaemu_status launch_tiled_shape<CM, VM>(const TiledArgs &, const void *, const void *, const void *, void *, uint32_t, \
+                                             uint32_t, uint32_t, uint64_t, hipStream_t, bool &)
+extern template MMAEMU_TILED_SIG(MMAEMU_C_IN_GROUP, 0);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_IN_GROUP, 1);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_IN_GROUP, 2);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 0);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 1);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 2);
 
 } // namespace mmaemu
