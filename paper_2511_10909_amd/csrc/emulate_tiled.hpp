@@ -63,9 +63,10 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 // ---- decode while staging --------------------------------------------------------------
 
 // One element -> exact binary32 value (every supported operand value is a binary32 number)
-// and e' = max(E, 1) - 1, or the sentinel tag for NaN / infinities.
+// and e' = max(E, 1) - 1, or the sentinel tag for NaN / infinities.  `wild` is raised by a
+// finite non-zero value outside [2^-31, 2^32), whose products may leave binary32 (BF16 only).
 template <int T>
-__device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, float &val, uint32_t &ex)
+__device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, float &val, uint32_t &ex, bool &wild)
 {
     using F = Fmt<T>;
     constexpr uint32_t EMASK = (1u << F::EB) - 1u, MMASK = (1u << F::MB) - 1u;
@@ -76,6 +77,7 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, floa
         const bool flushed = ftz_in && E == 0;                  // FlushSubnormal: -> +0.0
         val = __uint_as_float(flushed ? 0u : bits << 16);
         if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
+        else wild |= !flushed && (bits & 0x7FFFu) != 0 && (E - 96u) > 62u;
     } else if (T == MMAEMU_FP16) {
         _Float16 h;
         const uint16_t hb = (uint16_t)bits;
@@ -96,7 +98,7 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, floa
 
 // four consecutive k elements of one row: raw little-endian bytes in `raw`
 template <int T>
-__device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float (&f)[4], uint2 &e)
+__device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float (&f)[4], uint2 &e, bool &wild)
 {
     uint32_t b[4];
     if (Fmt<T>::W == 8) {
@@ -106,7 +108,7 @@ __device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float (&f)[4
     }
     uint32_t x[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, f[q], x[q]);
+    for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, f[q], x[q], wild);
     e = make_uint2(x[0] | (x[1] << 16), x[2] | (x[3] << 16));
 }
 
@@ -157,58 +159,47 @@ __device__ __forceinline__ void load_panel(uint32_t esize, const StagePlan<NQ> &
     }
 }
 
-// registers -> decoded LDS.  `as_double`: values are written as binary64 (row stride VSD
+// raw registers -> decoded registers; returns whether any element needs binary64 products
+template <int T, int NQ>
+__device__ __forceinline__ bool decode_panel(const uint2 (&raw)[NQ], uint32_t ftz_in, float (&f)[NQ][4], uint2 (&e)[NQ])
+{
+    bool wild = false;
+#pragma unroll
+    for (int i = 0; i < NQ; ++i) decode4<T>(raw[i], ftz_in, f[i], e[i], wild);
+    return wild;
+}
+
+template <int NQ>
+__device__ __forceinline__ bool decode_any(uint32_t t, const uint2 (&raw)[NQ], uint32_t ftz_in, float (&f)[NQ][4], uint2 (&e)[NQ])
+{
+    switch (t) {   // uniform
+    case MMAEMU_FP8_E4M3: return decode_panel<MMAEMU_FP8_E4M3, NQ>(raw, ftz_in, f, e);
+    case MMAEMU_FP8_E5M2: return decode_panel<MMAEMU_FP8_E5M2, NQ>(raw, ftz_in, f, e);
+    case MMAEMU_FP16: return decode_panel<MMAEMU_FP16, NQ>(raw, ftz_in, f, e);
+    default: return decode_panel<MMAEMU_BF16, NQ>(raw, ftz_in, f, e);
+    }
+}
+
+// decoded registers -> LDS.  `as_double`: values are written as binary64 (row stride VSD
 // doubles) instead of binary32 (row stride VS floats); WHAT bit 0: exponents, bit 1: values.
-template <int T, int NQ, int VS, int VSD>
-__device__ __forceinline__ void decode_panel(const StagePlan<NQ> &pl, const uint2 (&raw)[NQ], uint32_t ftz_in, void *lv,
-                                             uint32_t *le, bool as_double, int what)
+template <int NQ, int VS, int VSD>
+__device__ __forceinline__ void store_panel(const StagePlan<NQ> &pl, const float (&f)[NQ][4], const uint2 (&e)[NQ], void *lv,
+                                            uint32_t *le, bool as_double, int what)
 {
 #pragma unroll
     for (int i = 0; i < NQ; ++i) {
-        float f[4]; uint2 e;
-        decode4<T>(raw[i], ftz_in, f, e);
-        if (what & 1) *reinterpret_cast<uint2 *>(le + pl.eoff[i]) = e;
+        if (what & 1) *reinterpret_cast<uint2 *>(le + pl.eoff[i]) = e[i];
         if (what & 2) {
             if (as_double) {
                 // voff = row * VS + 4*kq  ->  row * VSD + 4*kq
                 const uint32_t row = pl.voff[i] / VS, kq4 = pl.voff[i] - row * VS;
                 double *dst = reinterpret_cast<double *>(lv) + row * VSD + kq4;
-                *reinterpret_cast<double2 *>(dst) = make_double2((double)f[0], (double)f[1]);
-                *reinterpret_cast<double2 *>(dst + 2) = make_double2((double)f[2], (double)f[3]);
+                *reinterpret_cast<double2 *>(dst) = make_double2((double)f[i][0], (double)f[i][1]);
+                *reinterpret_cast<double2 *>(dst + 2) = make_double2((double)f[i][2], (double)f[i][3]);
             } else {
-                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(lv) + pl.voff[i]) = make_float4(f[0], f[1], f[2], f[3]);
+                *reinterpret_cast<float4 *>(reinterpret_cast<float *>(lv) + pl.voff[i]) = make_float4(f[i][0], f[i][1], f[i][2], f[i][3]);
             }
         }
-    }
-}
-
-// is any element of the loaded quads a finite BF16 value outside [2^-31, 2^32)?
-template <int NQ>
-__device__ __forceinline__ bool any_wild_bf16(const uint2 (&raw)[NQ], uint32_t ftz_in)
-{
-    bool wild = false;
-#pragma unroll
-    for (int i = 0; i < NQ; ++i) {
-        const uint32_t w[2] = {raw[i].x, raw[i].y};
-#pragma unroll
-        for (int h = 0; h < 4; ++h) {
-            const uint32_t bits = (w[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
-            const uint32_t E = (bits >> 7) & 0xFFu;
-            wild |= !(ftz_in && E == 0) && (bits & 0x7FFFu) != 0 && E != 0xFFu && (E - 96u) > 62u;
-        }
-    }
-    return wild;
-}
-
-template <int NQ, int VS, int VSD>
-__device__ __forceinline__ void decode_any(uint32_t t, const StagePlan<NQ> &pl, const uint2 (&raw)[NQ], uint32_t ftz_in,
-                                           void *lv, uint32_t *le, bool as_double, int what)
-{
-    switch (t) {   // uniform
-    case MMAEMU_FP8_E4M3: decode_panel<MMAEMU_FP8_E4M3, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
-    case MMAEMU_FP8_E5M2: decode_panel<MMAEMU_FP8_E5M2, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
-    case MMAEMU_FP16: decode_panel<MMAEMU_FP16, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
-    default: decode_panel<MMAEMU_BF16, NQ, VS, VSD>(pl, raw, ftz_in, lv, le, as_double, what); break;
     }
 }
 
@@ -517,25 +508,25 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
             for (int c = 0; c < C; ++c) { m2[r][c] = 0; S32[r][c] = 0; Sd[r][c] = 0.0; }
     };
 
-    // Stage one chunk.  WHAT bit 0: exponents, bit 1: values.  In the adaptive mode the
-    // workgroup first agrees (through the barrier that also protects the previous chunk's
-    // readers) on whether any loaded element needs binary64.
-    auto stage = [&](uint32_t k0, int what) {
-        uint2 raw_a[NQA], raw_b[NQB];
+    // Staging is split in two: `prefetch` issues the global loads of a chunk (they complete
+    // while the previous chunk is being computed), `commit` decodes and writes LDS.
+    // WHAT bit 0: exponents, bit 1: values.  Elements are decoded into registers first; in the adaptive mode the workgroup then agrees (through the barrier
+    // that also protects the previous chunk's readers) on whether any of them needs
+    // binary64, and the values go to LDS in that form.
+    uint2 raw_a[NQA], raw_b[NQB];                               // the next chunk's operands, in flight
+    auto prefetch = [&](uint32_t k0) {
         load_panel<NQA>(esa, plan_a, k0, raw_a);
         load_panel<NQB>(esb, plan_b, k0, raw_b);
-        if (VM == 1) {
-            bool wild = false;
-            if (what & 2) {
-                if (ta_.ta == MMAEMU_BF16) wild |= any_wild_bf16<NQA>(raw_a, p.ftz_in);
-                if (ta_.tb == MMAEMU_BF16) wild |= any_wild_bf16<NQB>(raw_b, p.ftz_in);
-            }
-            chunk_is_double = __syncthreads_or(wild) != 0;
-        } else {
-            __syncthreads();
-        }
-        decode_any<NQA, VS, VSD>(ta_.ta, plan_a, raw_a, p.ftz_in, Av_raw, Ae, chunk_is_double, what);
-        decode_any<NQB, VS, VSD>(ta_.tb, plan_b, raw_b, p.ftz_in, Bv_raw, Be, chunk_is_double, what);
+    };
+    auto commit = [&](int what) {
+        float fa[NQA][4], fb[NQB][4];
+        uint2 xa[NQA], xb[NQB];
+        bool wild = decode_any<NQA>(ta_.ta, raw_a, p.ftz_in, fa, xa);
+        wild |= decode_any<NQB>(ta_.tb, raw_b, p.ftz_in, fb, xb);
+        if (VM == 1) chunk_is_double = __syncthreads_or(wild && (what & 2)) != 0;
+        else __syncthreads();
+        store_panel<NQA, VS, VSD>(plan_a, fa, xa, Av_raw, Ae, chunk_is_double, what);
+        store_panel<NQB, VS, VSD>(plan_b, fb, xb, Bv_raw, Be, chunk_is_double, what);
         __syncthreads();
     };
 
@@ -546,9 +537,11 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         else pass2f(g, emax);
     };
 
+    prefetch(0);
     if (LT != 0) {
         for (uint32_t k0 = 0; k0 < k; k0 += KC) {
-            stage(k0, 3);
+            commit(3);
+            if (k0 + KC < k) prefetch(k0 + KC);
 #pragma unroll 1
             for (int g = 0; g < KC / GL; ++g) {
                 reset_group();
@@ -566,13 +559,21 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         // a group of p.L terms spans p.L / KC chunks: one sweep for the exponents, one for the values
         for (uint32_t kg = 0; kg < k; kg += p.L) {
             reset_group();
-            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0, 1); pass1(0); }
+            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) {
+                commit(1);
+                prefetch(k0 + KC < kg + p.L ? k0 + KC : kg);            // next chunk of this sweep, or back to the group's start
+                pass1(0);
+            }
             int emax[R][C]; uint32_t tagged = 0;
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], tagged);
-            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) { stage(k0, 2); pass2(0, emax); }
+            for (uint32_t k0 = kg; k0 < kg + p.L; k0 += KC) {
+                commit(2);
+                if (k0 + KC < k) prefetch(k0 + KC);                     // runs on into the next group's first chunk
+                pass2(0, emax);
+            }
             end_of_group(kg, emax, tagged);
         }
     }
