@@ -112,6 +112,14 @@ __device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float (&f)[4
     e = make_uint2(x[0] | (x[1] << 16), x[2] | (x[3] << 16));
 }
 
+// item -> (tile, block index inside the tile) without a 64-bit division where it can be avoided
+__device__ __forceinline__ void split_item(uint64_t it, uint32_t per_tile, uint64_t &tile, uint32_t &rem)
+{
+    if (per_tile == 1) { tile = it; rem = 0; }
+    else if ((it >> 32) == 0) { const uint32_t i32 = (uint32_t)it; tile = i32 / per_tile; rem = i32 - (uint32_t)tile * per_tile; }
+    else { tile = it / per_tile; rem = (uint32_t)(it - tile * per_tile); }
+}
+
 // Per-thread staging plan: each thread moves NQ quads (4 consecutive k elements of one
 // row) per matrix and chunk; the quad's global row and its LDS offsets do not change
 // along k, so they are worked out once.
@@ -135,9 +143,8 @@ __device__ __forceinline__ void make_plan(StagePlan<NQ> &pl, const void *base, u
         const int kq = q % (KC / 4), row = (q / (KC / 4)) % ROWS, slot = q / ((KC / 4) * ROWS);
         uint64_t it = item0 + slot;
         it = it < nitems ? it : nitems - 1;                   // surplus slots re-read the last item
-        const uint32_t per_tile = bm_count * bn_count;
-        const uint64_t tile = it / per_tile;
-        const uint32_t rem = (uint32_t)(it - tile * per_tile);
+        uint64_t tile; uint32_t rem;
+        split_item(it, bm_count * bn_count, tile, rem);
         const uint32_t blk = IS_A ? rem / bn_count : rem % bn_count;
         const uint64_t grow = tile * rows_per_tile + (uint64_t)blk * ROWS + row;
         pl.src[i] = reinterpret_cast<const uint8_t *>(base) + grow * k * esize;
@@ -233,10 +240,12 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     constexpr bool USE_SD = (NF != 0) || (LT == 0) || (VM == 2);   // binary64 accumulator needed
     constexpr int VBYTES_A = SLOTS * TM * (VM == 0 ? VS * 4 : VSD * 8);
     constexpr int VBYTES_B = SLOTS * TN * (VM == 0 ? VS * 4 : VSD * 8);
-    __shared__ __attribute__((aligned(16))) unsigned char Av_raw[VBYTES_A];
-    __shared__ __attribute__((aligned(16))) unsigned char Bv_raw[VBYTES_B];
-    __shared__ __attribute__((aligned(16))) uint32_t Ae[SLOTS * TM * ES];
-    __shared__ __attribute__((aligned(16))) uint32_t Be[SLOTS * TN * ES];
+    constexpr int EBYTES_A = SLOTS * TM * ES * 4, EBYTES_B = SLOTS * TN * ES * 4;
+    constexpr int LDS_BYTES = VBYTES_A + VBYTES_B + EBYTES_A + EBYTES_B;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[LDS_BYTES];
+    unsigned char *Av_raw = smem, *Bv_raw = smem + VBYTES_A;
+    uint32_t *Ae = reinterpret_cast<uint32_t *>(smem + VBYTES_A + VBYTES_B);
+    uint32_t *Be = reinterpret_cast<uint32_t *>(smem + VBYTES_A + VBYTES_B + EBYTES_A);
 
     const ModelArgs &p = ta_.p;
     const int F = p.F;
@@ -259,11 +268,12 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     uint64_t my_it = item0 + slot;
     my_it = my_it < nitems ? my_it : nitems - 1;
     const uint32_t per_tile = bm_count * bn_count;
-    const uint64_t my_tile = my_it / per_tile;
-    const uint32_t my_rem = (uint32_t)(my_it - my_tile * per_tile);
+    uint64_t my_tile; uint32_t my_rem;
+    split_item(my_it, per_tile, my_tile, my_rem);
     const uint32_t i_base = (my_rem / bn_count) * TM + ti, j_base = (my_rem % bn_count) * TN + tj;
     const uint64_t d_off = (my_tile * m + i_base) * (uint64_t)n + j_base;     // + TI*r*n + TJ*c
 
+    // C in (each thread its own elements; measured faster here than moving the block through LDS)
     uint32_t d[R][C];
 #pragma unroll
     for (int r = 0; r < R; ++r)
@@ -578,16 +588,18 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         }
     }
 
+    // a NaN accumulator propagates through the groups with whatever payload the hardware
+    // gives it; the model's NaN encoding is applied once here
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+            if ((d[r][c] & 0x7FFFFFFFu) > 0x7F800000u) d[r][c] = p.nan_bits;
     if (live) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                // a NaN accumulator propagates through the groups with whatever payload the
-                // hardware gives it; the model's NaN encoding is applied once here
-                const uint32_t o = d[r][c];
-                D[d_off + (uint64_t)(TI * r) * n + TJ * c] = (o & 0x7FFFFFFFu) > 0x7F800000u ? p.nan_bits : o;
-            }
+            for (int c = 0; c < C; ++c) D[d_off + (uint64_t)(TI * r) * n + TJ * c] = d[r][c];
     }
 }
 

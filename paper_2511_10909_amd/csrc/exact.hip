@@ -5,7 +5,8 @@
 // One wavefront per sampled output: lanes stride over k, each accumulating exact integer
 // products in units of 2^LSB0 (LSB0 = the smallest last-place exponent a product can
 // have); an FP8 product is below 2^33 in value and a multiple of 2^-32, so it needs at
-// most 65 bits and a two-limb (128-bit) signed accumulator is exact for any k <= 2^20.
+// most 66 bits; per-lane sums are kept in two 64-bit integers split by shift size and
+// combined into a two-limb (128-bit) signed value that is exact for any k <= 2^20.
 #include "common.hpp"
 
 namespace mmaemu {
@@ -73,26 +74,48 @@ exact_dot_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, c
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const uint64_t nwaves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
-    unsigned long long *g = reinterpret_cast<unsigned long long *>(st);
-    double *gd = reinterpret_cast<double *>(g + 5 + 34);
+    // statistics are gathered per workgroup in LDS (same layout as mmaemu_err_stats) and
+    // flushed once at the end: global atomics on a handful of addresses serialise chip-wide
+    constexpr int NW = sizeof(mmaemu_err_stats) / 8;
+    __shared__ unsigned long long ls[NW];
+    if (threadIdx.x < NW) ls[threadIdx.x] = 0ull;                 // +0.0 is all-zero bits
+    __syncthreads();
+    unsigned long long *g = ls;
+    double *gd = reinterpret_cast<double *>(ls + 5 + 34);
     for (uint64_t sidx = wave; sidx < nsamples; sidx += nwaves) {
         const uint64_t o = sidx * stride;
         const uint32_t i = (uint32_t)(o / n), j = (uint32_t)(o % n);
         const uint8_t *a = A + (uint64_t)i * k, *b = B + (uint64_t)j * k;
-        I128 acc = {0ull, 0ll};
+        // Per lane: four consecutive k per 32-bit load.  A product p * 2^sh (p < 2^8, sh <= 58)
+        // goes to one of two 64-bit sums by the size of its shift -- units 2^LSB0 for sh < 32,
+        // units 2^(LSB0+32) otherwise -- so each addend is below 2^39 and neither sum can
+        // overflow for any k <= 2^20; the two are combined into 128 bits once per sample.
+        int64_t acc_lo = 0, acc_hi = 0;
         bool bad = false;
-        for (uint32_t q = lane; q < k; q += 64) {
-            uint32_t sa, sb, na, nb; int ea, eb; bool xa, xb;
-            dec8<TA>(a[q], sa, ea, na, xa);
-            dec8<TB>(b[q], sb, eb, nb, xb);
-            bad |= xa | xb;
-            const int sh = (ea - Fmt<TA>::MB) + (eb - Fmt<TB>::MB) - LSB0;    // 0 .. 57
-            const uint64_t p = (uint64_t)(sa * sb);                            // <= 8 bits
-            I128 t;
-            t.lo = p << sh;
-            t.hi = sh > 56 ? (int64_t)(p >> (64 - sh)) : 0;                    // p < 2^8: spills only past bit 56
-            acc = add128(acc, (na ^ nb) ? neg128(t) : t);
+        for (uint32_t q = 4 * lane; q < k; q += 256) {
+            uint32_t wa, wb;
+            if (q + 4 <= k && (((uintptr_t)(a + q) | (uintptr_t)(b + q)) & 3) == 0) {
+                wa = *reinterpret_cast<const uint32_t *>(a + q);
+                wb = *reinterpret_cast<const uint32_t *>(b + q);
+            } else {
+                wa = wb = 0;
+                for (uint32_t u = 0; u < 4 && q + u < k; ++u) { wa |= (uint32_t)a[q + u] << (8 * u); wb |= (uint32_t)b[q + u] << (8 * u); }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                uint32_t sa, sb, na, nb; int ea, eb; bool xa, xb;
+                dec8<TA>((wa >> (8 * u)) & 0xFFu, sa, ea, na, xa);
+                dec8<TB>((wb >> (8 * u)) & 0xFFu, sb, eb, nb, xb);
+                bad |= xa | xb;                                                 // (padding bytes are zero: finite)
+                const int sh = (ea - Fmt<TA>::MB) + (eb - Fmt<TB>::MB) - LSB0;  // 0 .. 58
+                const int64_t pr = (int64_t)(sa * sb);
+                const int64_t sp = (na ^ nb) ? -pr : pr;
+                if (sh < 32) acc_lo += (int64_t)((uint64_t)sp << sh);
+                else acc_hi += (int64_t)((uint64_t)sp << (sh - 32));
+            }
         }
+        I128 acc = {(uint64_t)acc_lo, acc_lo < 0 ? -1ll : 0ll};
+        acc = add128(acc, shl128(I128{(uint64_t)acc_hi, acc_hi < 0 ? -1ll : 0ll}, 32));
         // wavefront reduction of the two-limb sums
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
@@ -161,6 +184,14 @@ exact_dot_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, c
         }   // finite sample
         }   // lane 0
     }
+    __syncthreads();
+    if (threadIdx.x < NW && ls[threadIdx.x] != 0ull) {
+        unsigned long long *out = reinterpret_cast<unsigned long long *>(st) + threadIdx.x;
+        const int w = (int)threadIdx.x - (5 + 34);                 // index among the binary64 fields
+        if (w < 0) atomicAdd(out, ls[threadIdx.x]);
+        else if (w == 1 || w == 3) atomicMax(out, ls[threadIdx.x]);             // maxima of non-negative doubles
+        else atomicAdd(reinterpret_cast<double *>(out), __longlong_as_double((long long)ls[threadIdx.x]));
+    }
 }
 
 mmaemu_status launch_err_stats_reset(mmaemu_err_stats *st, hipStream_t s)
@@ -177,7 +208,7 @@ static mmaemu_status launch_t(const void *A, const void *B, const uint32_t *D, u
     const uint64_t total = (uint64_t)m * n;
     const uint64_t nsamples = (total + stride - 1) / stride;
     uint64_t blocks = (nsamples + 3) / 4;
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks > 1024) blocks = 1024;                      // wave-stride beyond that
     hipLaunchKernelGGL((exact_dot_kernel<TA, TB>), dim3((uint32_t)blocks), dim3(256), 0, s, (const uint8_t *)A,
                        (const uint8_t *)B, D, m, n, k, stride, nsamples, st);
     MMAEMU_HIP(hipGetLastError());

@@ -131,3 +131,33 @@ def test_tiled_cancellation_and_ties(mm):
                     p = ModelParams(group_len=L, frac_bits=F, c_mode=cm, out_round=rho)
                     want, _ = o2lib.emulate_mma(p, A, B, C, fm.FP16, fm.FP16)
                     assert_same(gpu_emulate(mm, p, A, B, C, fm.FP16, fm.FP16), want, "cancel %s" % (p,))
+
+
+def test_tiled_unaligned_pointers(mm):
+    # C and D 4 bytes off a 16-byte boundary (the tiled kernels then move C/D element by element);
+    # A and B 2 bytes off an 8-byte boundary (the library then takes its general kernel)
+    import torch
+    from gpu_utils import to_dev, to_host
+    rng = np.random.default_rng(80)
+    nb, m, n, k = 5, 16, 16, 16
+    A, B, C = operands(rng, fm.FP16, fm.FP16, nb, m, n, k, "narrow")
+    p = ModelParams(group_len=8, frac_bits=24)
+    want, _ = o2lib.emulate_mma(p, A, B, C, fm.FP16, fm.FP16)
+    h = mm.model_create(group_len=8, frac_bits=24)
+    dt = (fm.FP16, fm.FP16, fm.FP32, fm.FP32)
+    dA, dB = to_dev(A), to_dev(B)
+    cbuf = torch.zeros(C.size + 1, dtype=torch.int32, device="cuda")
+    dbuf = torch.zeros(C.size + 1, dtype=torch.int32, device="cuda")
+    cbuf[1:] = to_dev(C).flatten()
+    mm.emulate_mma(h, dA, dB, cbuf[1:], dbuf[1:], m, n, k, nb, dt)
+    assert mm.last_kernel().startswith("tiled")
+    assert_same(to_host(dbuf[1:], np.uint32).reshape(nb, m, n), want, "C/D off by 4 bytes")
+    abuf = torch.zeros(A.size + 1, dtype=torch.int16, device="cuda")
+    bbuf = torch.zeros(B.size + 1, dtype=torch.int16, device="cuda")
+    abuf[1:] = dA.flatten()
+    bbuf[1:] = dB.flatten()
+    dD = torch.zeros(C.size, dtype=torch.int32, device="cuda")
+    mm.emulate_mma(h, abuf[1:], bbuf[1:], to_dev(C), dD, m, n, k, nb, dt)
+    assert mm.last_kernel() == "general"
+    assert_same(to_host(dD, np.uint32).reshape(nb, m, n), want, "A/B off by 2 bytes")
+    mm.model_destroy(h)
