@@ -11,6 +11,15 @@ Follows the paper's Sec. 4.1.3:
   * Algorithm "E-FDPA"    : rho = RNE-FP32 applied to the exact c + sum(a_k b_k)
                             (the wide-F limit of T-FDPA; used as a closed form).
   * Sec. 4.2              : NaN / infinity rules.
+  * Algorithm "TR-FDPA"   : truncated fused sum T of the L products only (e_max over the
+                            products); E = max(e_max, e_c); T rounded DOWN to F2 and c
+                            rounded DOWN to F fractional bits at E; S = T' + s_c'; rho.
+  * Algorithm "GTR-FDPA"  : products of even and of odd index are fused separately (each
+                            aligned at its own maximum exponent and truncated to F bits);
+                            the two sums are rounded down to F bits at their common
+                            maximum and added; then as TR-FDPA, with the accumulator's
+                            term dropped when e_c < E - F - 1.
+  * Sec. 4.2, last paragraph: in TR-FDPA a product of magnitude >= 2^128 overflows to infinity.
   * Algorithm "FTZ-Add/Mul": output flush  |z| < 2^-126 -> zero of the same sign.
   * Algorithm "Phi_FTZ-AddMul" (its FlushSubnormal lines): input subnormals -> +0.0.
 
@@ -34,7 +43,7 @@ import numpy as np
 from . import formats as fm
 from .rounding import to_fp32, RNE, RZ
 
-C_IN_GROUP, C_AFTER_EXACT = 0, 1
+C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 ALIGN_RZ = 0
 DEFAULT_NAN = 0x7FC00000
 NVIDIA_NAN = 0x7FFFFFFF  # Sec. 4.2: canonical NaN of T-FDPA on NVIDIA parts
@@ -44,6 +53,7 @@ NVIDIA_NAN = 0x7FFFFFFF  # Sec. 4.2: canonical NaN of T-FDPA on NVIDIA parts
 class ModelParams:
     group_len: int = 0          # L_max; 0 means fully fused (L = K)
     frac_bits: int = 24         # F
+    frac_bits2: int = 0         # F2 (TR-FDPA / GTR-FDPA only)
     align_round: int = ALIGN_RZ
     c_mode: int = C_IN_GROUP
     out_round: int = RNE        # rho: RNE-FP32 or RZ-FP32
@@ -63,13 +73,27 @@ def _rz_frac(x, F):
     return -r if x < 0 else r
 
 
+def _rd_frac(x, F):
+    """RD_F(x): round the rational x down (toward minus infinity) to F fractional bits."""
+    scaled = x * (1 << F)
+    n = scaled.numerator // scaled.denominator            # floor, also for negative x
+    return Fraction(n, 1 << F)
+
+
 def _specials(p, da, db, dc):
     """Sec. 4.2.  Returns output bits if the group's result is NaN or infinite, else None."""
     if dc.cls == fm.NAN or any(x.cls == fm.NAN for x in da) or any(x.cls == fm.NAN for x in db):
         return p.nan_bits
     pos_inf = neg_inf = False
     for x, y in zip(da, db):
-        if x.cls == fm.INF or y.cls == fm.INF:
+        if p.c_mode in (C_AFTER_RD, C_AFTER_RD_EVEN_ODD) and x.finite and y.finite \
+                and abs(x.value * y.value) >= Fraction(2) ** 128:
+            # TR-FDPA: the multiplication result overflows to infinity
+            if x.sign ^ y.sign:
+                neg_inf = True
+            else:
+                pos_inf = True
+        elif x.cls == fm.INF or y.cls == fm.INF:
             other = y if x.cls == fm.INF else x
             if other.cls == fm.ZERO:
                 return p.nan_bits                      # inf * 0
@@ -133,6 +157,31 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb):
         s_al = [_rz_frac(s[k] * Fraction(2) ** (e[k] - e_max), F) for k in range(L)]
         T = sum(s_al, Fraction(0))
         V = T * Fraction(2) ** e_max + dc.value
+    elif p.c_mode == C_AFTER_RD:
+        # Algorithm "TR-FDPA"
+        F2 = p.frac_bits2
+        e_max = max(e)
+        T = sum((_rz_frac(s[k] * Fraction(2) ** (e[k] - e_max), F) for k in range(L)), Fraction(0))
+        E = max(e_max, dc.exp)
+        T_al = _rd_frac(T * Fraction(2) ** (e_max - E), F2)
+        sc_al = _rd_frac(dc.signed_sig * Fraction(2) ** (dc.exp - E), F)
+        V = (T_al + sc_al) * Fraction(2) ** E
+    elif p.c_mode == C_AFTER_RD_EVEN_ODD:
+        # Algorithm "GTR-FDPA"
+        if L % 2:
+            raise ValueError("GTR-FDPA needs an even group length")
+        F2 = p.frac_bits2
+        e_even, e_odd = max(e[0::2]), max(e[1::2])
+        T_even = sum((_rz_frac(s[k] * Fraction(2) ** (e[k] - e_even), F) for k in range(0, L, 2)), Fraction(0))
+        T_odd = sum((_rz_frac(s[k] * Fraction(2) ** (e[k] - e_odd), F) for k in range(1, L, 2)), Fraction(0))
+        e_max = max(e_even, e_odd)
+        T = _rd_frac(T_even * Fraction(2) ** (e_even - e_max), F) + _rd_frac(T_odd * Fraction(2) ** (e_odd - e_max), F)
+        E = max(e_max, dc.exp)
+        T_al = _rd_frac(T * Fraction(2) ** (e_max - E), F2)
+        sc_al = _rd_frac(dc.signed_sig * Fraction(2) ** (dc.exp - E), F)
+        if dc.exp < E - F - 1:
+            sc_al = Fraction(0)                                   # special truncation
+        V = (T_al + sc_al) * Fraction(2) ** E
     else:
         raise ValueError(p.c_mode)
 

@@ -11,6 +11,12 @@
  * with truncation toward zero to F fractional bits, exact fixed-point sum,
  * conversion rho), the special-value rules of Sec. 4.2, the output flush of
  * Algorithm "FTZ-Add/FTZ-Mul" and the input flush of Algorithm "Phi_FTZ-AddMul".
+ * c_mode 2 is Algorithm "TR-FDPA" and c_mode 3 Algorithm "GTR-FDPA" (Sec. 4.1.3):
+ * the products are fused without the accumulator (in GTR-FDPA, even and odd products
+ * apart, the two sums then rounded down to F bits at their common exponent), the sum
+ * is rounded down to F2 and the accumulator to F fractional bits at E = max(e_max,
+ * e_c), and the two are added; a product of magnitude 2^128 or more counts as an
+ * infinity (Sec. 4.2).
  * It is checked bit for bit against the rational-arithmetic form in ../fdpa.py and
  * against the paper's printed values by the CPU tests.
  *
@@ -29,11 +35,11 @@ typedef unsigned __int128 u128;
 
 enum { T_E4M3 = 0, T_E5M2 = 1, T_FP16 = 2, T_BF16 = 3, T_FP32 = 4 };
 enum { CLS_ZERO, CLS_SUB, CLS_NORMAL, CLS_INF, CLS_NAN };
-enum { C_IN_GROUP = 0, C_AFTER_EXACT = 1 };
+enum { C_IN_GROUP = 0, C_AFTER_EXACT = 1, C_AFTER_RD = 2, C_AFTER_RD_EVEN_ODD = 3 };
 enum { R_RNE = 0, R_RZ = 1 };
 
 typedef struct {
-    uint32_t group_len, frac_bits, align_round, c_mode, out_round, ftz_in, ftz_out, nan_bits;
+    uint32_t group_len, frac_bits, align_round, c_mode, out_round, ftz_in, ftz_out, nan_bits, frac_bits2;
 } o2_params;
 
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
@@ -143,6 +149,32 @@ static u128 align_rz(u128 mag, int lsb, int unit)
     return mag >> (-sh);
 }
 
+/* RD: v (units 2^lsb) to units 2^unit, rounding toward minus infinity */
+static i128 align_rd(i128 v, int lsb, int unit)
+{
+    int sh = lsb - unit;
+    if (sh >= 0) return v * ((i128)1 << sh);
+    if (-sh > 126) return v < 0 ? -1 : 0;
+    i128 q = v / ((i128)1 << (-sh)), r = v % ((i128)1 << (-sh));   /* C division truncates toward zero */
+    return (r < 0) ? q - 1 : q;
+}
+
+/* Steps 3 and 4 of Algorithm "TR-FDPA" (steps 4 and 5 of "GTR-FDPA"): T counts units of
+ * 2^(emax - F); returns rho(RD_F2(T at E) + RD_F(c at E)). */
+static uint32_t rounded_sum_with_c(const o2_params *p, i128 T, int emax, dec_t dc, int special_truncation)
+{
+    const int F = (int)p->frac_bits, F2 = (int)p->frac_bits2;
+    const int E = dc.exp > emax ? dc.exp : emax;
+    i128 T2 = align_rd(T, emax - F, E - F2);
+    i128 sc = dc.sign ? -(i128)dc.sig : (i128)dc.sig;
+    i128 sc2 = align_rd(sc, dc.exp - 23, E - F);
+    if (special_truncation && dc.exp < E - F - 1) sc2 = 0;
+    const int Fm = F2 > F ? F2 : F;                                  /* common unit 2^(E - Fm) */
+    i128 S = T2 * ((i128)1 << (Fm - F2)) + sc2 * ((i128)1 << (Fm - F));
+    int neg = S < 0;
+    return to_fp32(neg, (u128)(neg ? -S : S), E - Fm, 0, (int)p->out_round);
+}
+
 static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t c,
                            uint32_t L, int ta, int tb)
 {
@@ -153,7 +185,7 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
 
     /* pass over the inputs: specials (Sec. 4.2) and e_max */
     int any_nan = dc.cls == CLS_NAN, pinf = 0, ninf = 0;
-    int emax = -100000;
+    int emax = -100000, eeven = -100000, eodd = -100000;
     for (uint32_t k = 0; k < L; ++k) {
         dec_t x = decode(a[k], ta), y = decode(b[k], tb);
         if (p->ftz_in) { if (x.cls == CLS_SUB) x = decode(0u, ta); if (y.cls == CLS_SUB) y = decode(0u, tb); }
@@ -164,12 +196,34 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
         } else {
             int e = x.exp + y.exp;
             if (e > emax) emax = e;
+            if (k & 1) { if (e > eodd) eodd = e; } else { if (e > eeven) eeven = e; }
+            if (p->c_mode >= C_AFTER_RD) {                           /* product overflow, Sec. 4.2 */
+                uint64_t prod = (uint64_t)x.sig * (uint64_t)y.sig;
+                if (prod && bitlen128((u128)prod) - 1 + e - fa - fb >= 128) { if (x.sign ^ y.sign) ninf = 1; else pinf = 1; }
+            }
         }
     }
     if (dc.cls == CLS_INF) { if (dc.sign) ninf = 1; else pinf = 1; }
     if (any_nan || (pinf && ninf)) return p->nan_bits;
     if (pinf) return 0x7F800000u;
     if (ninf) return 0xFF800000u;
+
+    if (p->c_mode == C_AFTER_RD_EVEN_ODD) {
+        i128 Te = 0, To = 0;
+        for (uint32_t k = 0; k < L; ++k) {
+            dec_t x = decode(a[k], ta), y = decode(b[k], tb);
+            if (p->ftz_in) { if (x.cls == CLS_SUB) x = decode(0u, ta); if (y.cls == CLS_SUB) y = decode(0u, tb); }
+            u128 prod = (u128)((uint64_t)x.sig * (uint64_t)y.sig);
+            int e = x.exp + y.exp;
+            i128 al = (i128)align_rz(prod, e - fa - fb, ((k & 1) ? eodd : eeven) - F);
+            if (x.sign ^ y.sign) al = -al;
+            if (k & 1) To += al; else Te += al;
+        }
+        i128 T = align_rd(Te, eeven - F, emax - F) + align_rd(To, eodd - F, emax - F);
+        uint32_t d = rounded_sum_with_c(p, T, emax, dc, 1);
+        if (p->ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
+        return d;
+    }
 
     if (p->c_mode == C_IN_GROUP && dc.exp > emax) emax = dc.exp;
     const int unit = emax - F;
@@ -189,6 +243,8 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
         if (dc.sign) S -= (i128)al; else S += (i128)al;
         int neg = S < 0;
         d = to_fp32(neg, (u128)(neg ? -S : S), unit, 0, (int)p->out_round);
+    } else if (p->c_mode == C_AFTER_RD) {
+        d = rounded_sum_with_c(p, S, emax, dc, 0);
     } else {
         int neg = S < 0;
         d = add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, (int)p->out_round);
@@ -200,13 +256,19 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
 static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out)
 {
     if (ta < 0 || ta > T_BF16 || tb < 0 || tb > T_BF16) return -2;
-    if (p->align_round != 0 || p->c_mode > 1 || p->out_round > 1 || p->frac_bits > 64) return -2;
+    if (p->align_round != 0 || p->c_mode > 3 || p->out_round > 1 || p->frac_bits > 64) return -2;
     if (k == 0 || k > (1u << 20)) return -3;
     uint32_t L = (p->group_len == 0 || p->group_len > k) ? k : p->group_len;
     if (k % L) return -3;
     if (p->c_mode == C_AFTER_EXACT) {   /* add_exact_round() needs magnitudes of at most 40 bits */
         int lg = 0; while ((1u << lg) < L) ++lg;
         if ((int)p->frac_bits + 2 + lg > 40) return -2;
+    }
+    if (p->c_mode >= C_AFTER_RD) {      /* keep every intermediate of rounded_sum_with_c() below 2^120 */
+        int lg = 0; while ((1u << lg) < L) ++lg;
+        int Fm = p->frac_bits2 > p->frac_bits ? (int)p->frac_bits2 : (int)p->frac_bits;
+        if (p->frac_bits2 > 64 || Fm + 3 + lg > 100) return -2;
+        if (p->c_mode == C_AFTER_RD_EVEN_ODD && (L & 1)) return -3;
     }
     *L_out = L;
     return 0;

@@ -21,7 +21,7 @@ def build(force=False):
 
 class O2Params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
-                ("group_len", "frac_bits", "align_round", "c_mode", "out_round", "ftz_in", "ftz_out", "nan_bits")]
+                ("group_len", "frac_bits", "align_round", "c_mode", "out_round", "ftz_in", "ftz_out", "nan_bits", "frac_bits2")]
 
 
 def _load():
@@ -34,7 +34,7 @@ def _load():
 
 def _params(p):
     return O2Params(p.group_len, p.frac_bits, p.align_round, p.c_mode, p.out_round,
-                    int(p.ftz_in), int(p.ftz_out), p.nan_bits)
+                    int(p.ftz_in), int(p.ftz_out), p.nan_bits, p.frac_bits2)
 
 
 _NP = {fm.E4M3: np.uint8, fm.E5M2: np.uint8, fm.FP16: np.uint16, fm.BF16: np.uint16, fm.FP32: np.uint32}

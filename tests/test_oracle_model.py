@@ -9,7 +9,7 @@ import torch
 
 from oracle import formats as fm
 from oracle.fdpa import (ModelParams, emulate_element, fdpa_group, e_fdpa, exact_value, exact_width,
-                         C_IN_GROUP, C_AFTER_EXACT, NVIDIA_NAN)
+                         C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD, NVIDIA_NAN)
 from oracle.rounding import RNE, RZ, rne_fp32
 from helpers import f32_bits, bits_f32, ENCODERS, fp16_bits, bf16_bits
 from paper_2511_10909_amd import synth
@@ -35,6 +35,8 @@ def test_table_d00(row):
     c = f32_bits(2.0 ** 23)
     p = ModelParams(group_len=int(lmax), frac_bits=WIDE if F == "exact" else int(F),
                     out_round=RZ if rho == "RZ" else RNE)
+    if rho in ("TR", "GTR"):
+        p = p.with_(frac_bits2=31, c_mode=C_AFTER_RD if rho == "TR" else C_AFTER_RD_EVEN_ODD)
     got = emulate_element(p, a, b, c, t, t)
     assert bits_f32(got) == float(want)
     if float(want) == 0.0:

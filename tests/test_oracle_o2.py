@@ -5,7 +5,7 @@ import pytest
 import torch
 
 from oracle import formats as fm, o2lib, exact as ex
-from oracle.fdpa import ModelParams, emulate_mma, C_IN_GROUP, C_AFTER_EXACT
+from oracle.fdpa import ModelParams, emulate_mma, C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD
 from oracle.rounding import RNE, RZ
 from helpers import f32_bits, bits_f32, ENCODERS
 from paper_2511_10909_amd import synth
@@ -82,6 +82,8 @@ def test_o2_table_d00(row):
     A, B = np.array([[a]]), np.array([[b]])
     C = np.array([[[f32_bits(2.0 ** 23)]]], dtype=np.uint32)
     p = ModelParams(group_len=int(lmax), frac_bits=64 if F == "exact" else int(F), out_round=RZ if rho == "RZ" else RNE)
+    if rho in ("TR", "GTR"):
+        p = p.with_(frac_bits2=31, c_mode=C_AFTER_RD if rho == "TR" else C_AFTER_RD_EVEN_ODD)
     got, _ = o2lib.emulate_mma(p, A, B, C, t, t)
     assert bits_f32(got[0, 0, 0]) == float(want)
 

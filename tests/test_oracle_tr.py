@@ -1,0 +1,254 @@
+"""CPU tests of the oracle's TR-FDPA and GTR-FDPA operations (paper Sec. 4.1.3, Algorithms
+"TR-FDPA" and "GTR-FDPA"; overflow rule of Sec. 4.2; parameters of Table "TR-FDPA and GTR-FDPA
+parameter selection": F = 24, F2 = 31, RNE-FP32, L_max = 8 for 16-bit and 16 for 8-bit inputs).
+
+The paper's printed values for these operations (Table of d_00, CDNA3 rows) are checked with the
+other rows of that table in test_oracle_model.py / test_oracle_o2.py.  That example exercises the
+round-down of the even/odd merge only, so the other roundings are pinned here by cases whose results
+are worked out by hand from the algorithms' steps (derivations beside each case), by the closed form
+the operations reduce to when nothing is lost, and by order relations that hold for any input.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import formats as fm, o2lib
+from oracle.fdpa import (ModelParams, fdpa_group, emulate_mma, e_fdpa,
+                         C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD)
+from oracle.rounding import RNE, RZ
+from oracle.stats import ordered_key
+from helpers import f32_bits, bits_f32, fp16_bits, bf16_bits
+from paper_2511_10909_amd import synth
+
+TR = ModelParams(group_len=8, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD)
+GTR = ModelParams(group_len=16, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD_EVEN_ODD)
+WIDE = 700
+
+
+def _pad(vals, L, enc=fp16_bits):
+    return [enc(v) for v in vals] + [enc(0.0)] * (L - len(vals))
+
+
+def _run(p, a, b, c, L=8, enc=fp16_bits, t=fm.FP16):
+    return fdpa_group(p, _pad(a, L, enc), _pad(b, L, enc), f32_bits(c), t, t)
+
+
+# ------------------------------------------------------------------ hand-derived cases
+def test_accumulator_is_rounded_down_to_F_bits():
+    # one product 1*1: T = 1 at e_max = 0.  c = -2^-30: E = 0, s_c' = RD_24(-2^-30) = -2^-24,
+    # S = 1 - 2^-24, which binary32 holds exactly (0x3F7FFFFF).  Truncation toward zero would give 1.0.
+    assert _run(TR, [1.0], [1.0], -2.0 ** -30) == 0x3F7FFFFF
+    # a positive accumulator of the same size is rounded down to 0
+    assert _run(TR, [1.0], [1.0], 2.0 ** -30) == 0x3F800000
+    # so small a negative accumulator never vanishes, however far below the sum it lies
+    assert _run(TR, [1.0], [1.0], -2.0 ** -126) == 0x3F7FFFFF
+
+
+def test_special_truncation_of_the_accumulator():
+    # the same case in GTR-FDPA: e_c = -30 < E - F - 1 = -25, so the accumulator's term is dropped
+    assert _run(GTR, [1.0], [1.0], -2.0 ** -30, L=16) == 0x3F800000
+    # e_c = -25 is the last exponent that is kept: RD_24(-2^-25) = -2^-24
+    assert _run(GTR, [1.0], [1.0], -2.0 ** -25, L=16) == 0x3F7FFFFF
+    assert _run(GTR, [1.0], [1.0], -2.0 ** -26, L=16) == 0x3F800000
+    # TR-FDPA has no such rule
+    assert _run(TR, [1.0], [1.0], -2.0 ** -26) == 0x3F7FFFFF
+
+
+def test_product_sum_is_rounded_down_to_F2_bits():
+    # products -64*1 and 2^-10*1: e_max = 6, T = -(1 - 2^-16).  c = 2^30 (1 + 2^-23): E = 30,
+    # T 2^-24 = -(2^-24 - 2^-40), RD_31 -> -2^-24; S = 1 + 2^-23 - 2^-24 = 1 + 2^-24: a tie, to even: 2^30.
+    # Without the rounding (or with truncation toward zero) S > 1 + 2^-24 and the result is the next float up.
+    c = bits_f32(0x4E800001)
+    assert _run(TR, [-64.0, 2.0 ** -10], [1.0, 1.0], c) == 0x4E800000
+    assert _run(GTR, [-64.0, 2.0 ** -10], [1.0, 1.0], c, L=16) == 0x4E800000
+    assert _run(TR.with_(c_mode=C_AFTER_EXACT), [-64.0, 2.0 ** -10], [1.0, 1.0], c) == 0x4E800001
+    # F2 = 40 keeps the sum exact here
+    assert _run(TR.with_(frac_bits2=40), [-64.0, 2.0 ** -10], [1.0, 1.0], c) == 0x4E800001
+
+
+def test_even_odd_merge_rounds_down():
+    # even products: 2^13 * 2^10 = 2^23 (e_even = 23, T_even = 1); odd products: -0.25 (e_odd = -2, T_odd = -1).
+    # merge at e_max = 23: RD_24(-2^-25) = -2^-24, T = 1 - 2^-24, d = 2^23 - 0.5 (exactly a binary32 number)
+    assert bits_f32(_run(GTR, [2.0 ** 13, -0.25], [2.0 ** 10, 1.0], 0.0, L=16)) == 2.0 ** 23 - 0.5
+    # a positive small odd sum is rounded down to nothing
+    assert bits_f32(_run(GTR, [2.0 ** 13, 0.25], [2.0 ** 10, 1.0], 0.0, L=16)) == 2.0 ** 23
+    # the same two products in one fused group (TR-FDPA) are truncated toward zero at e_max instead
+    assert bits_f32(_run(TR, [2.0 ** 13, -0.25], [2.0 ** 10, 1.0], 0.0)) == 2.0 ** 23
+    # both in the even group (indices 0 and 2): truncated toward zero as well
+    assert bits_f32(_run(GTR, [2.0 ** 13, 0.0, -0.25], [2.0 ** 10, 0.0, 1.0], 0.0, L=16)) == 2.0 ** 23
+
+
+def test_groups_use_their_own_maximum_exponent():
+    # odd group: 2^-12 and 2^-13 * (1 + 2^-10) ... kept to 24 bits below e_odd, not below e_even.
+    # even: 2^12 (e = 12); odd: 2^-12 (e = -12).  T_odd = 1 at e_odd; merged at 12: 2^-24 survives exactly.
+    d = _run(GTR, [2.0 ** 12, 2.0 ** -12], [1.0, 1.0], -(2.0 ** 12), L=16)
+    assert bits_f32(d) == 2.0 ** -12
+    # one place lower and the round-down takes it away
+    d = _run(GTR, [2.0 ** 12, 2.0 ** -13], [1.0, 1.0], -(2.0 ** 12), L=16)
+    assert d == 0
+
+
+def test_product_overflow_is_an_infinity():
+    p = TR.with_(group_len=2)
+    big = bf16_bits(2.0 ** 64)
+    # 2^64 * 2^64 = 2^128: the product itself overflows although the sum 2^128 - 2^127 would be finite
+    a, b = [big, bf16_bits(-(2.0 ** 63))], [big, big]
+    assert fdpa_group(p, a, b, 0, fm.BF16, fm.BF16) == 0x7F800000
+    assert fdpa_group(p.with_(c_mode=C_IN_GROUP), a, b, 0, fm.BF16, fm.BF16) == f32_bits(2.0 ** 127)
+    assert fdpa_group(p, [big, big], [bf16_bits(-(2.0 ** 64)), big], 0, fm.BF16, fm.BF16) == p.nan_bits
+    assert fdpa_group(p, [bf16_bits(-(2.0 ** 64)), 0], [big, 0], 0, fm.BF16, fm.BF16) == 0xFF800000
+    # just below the limit nothing overflows: (2^64 - 2^56)^2 < 2^128
+    near = bf16_bits(2.0 ** 64 - 2.0 ** 56)
+    d = fdpa_group(p, [near, 0], [near, 0], 0, fm.BF16, fm.BF16)
+    assert d == f32_bits((2.0 ** 64 - 2.0 ** 56) ** 2)
+    # a subnormal-times-large product whose unnormalised exponent sum is high but whose value is small
+    assert fdpa_group(p, [0x0001, 0], [bf16_bits(2.0 ** 127), 0], 0, fm.BF16, fm.BF16) == f32_bits(2.0 ** -6)
+    # GTR-FDPA on FP8 can never overflow (|a b| <= 57344^2 < 2^32)
+    assert fdpa_group(GTR, [0x7B] * 16, [0x7B] * 16, 0, fm.E5M2, fm.E5M2) == f32_bits(16 * 57344.0 ** 2)
+
+
+# ------------------------------------------------------------------ closed forms and order relations
+@pytest.mark.parametrize("mode", [C_AFTER_RD, C_AFTER_RD_EVEN_ODD])
+def test_wide_F_is_the_correctly_rounded_exact_result(mode):
+    # with F and F2 wide enough no alignment loses a bit and both operations reduce to E-FDPA
+    rng = np.random.default_rng(31 + mode)
+    p = ModelParams(frac_bits=WIDE, frac_bits2=WIDE, c_mode=mode)
+    for t in (fm.FP16, fm.E5M2, fm.E4M3):
+        for _ in range(80):
+            a = synth.random_bits(rng, 8, t).tolist()
+            b = synth.random_bits(rng, 8, t).tolist()
+            c = int(synth.narrow_exponent_bits(rng, 1, fm.FP32, 90, 160)[0])
+            if mode == C_AFTER_RD_EVEN_ODD:
+                # the special truncation is part of the operation at any F; keep the accumulator above its threshold
+                c = (c & 0x807FFFFF) | (140 << 23)
+            assert fdpa_group(p, a, b, c, t, t) == e_fdpa(a, b, c, t, t)
+
+
+@pytest.mark.parametrize("mode,L,t", [(C_AFTER_RD, 8, fm.FP16), (C_AFTER_RD, 8, fm.BF16),
+                                      (C_AFTER_RD_EVEN_ODD, 16, fm.E5M2), (C_AFTER_RD_EVEN_ODD, 16, fm.E4M3)])
+def test_round_down_brackets(mode, L, t):
+    """Every rounding after the truncated product sums is downward and rho is monotonic, so
+         d(a, b, c) <= d_no_RD(a, b, c) <= -d(-a, b, -c),
+    where d_no_RD adds the same truncated sums and c exactly (for TR-FDPA that is c_mode C_AFTER_EXACT;
+    for GTR-FDPA it is built here from the two group sums)."""
+    rng = np.random.default_rng(77 + mode + t)
+    p = ModelParams(group_len=L, frac_bits=24, frac_bits2=31, c_mode=mode)
+    sign_in = 0x8000 if t in (fm.FP16, fm.BF16) else 0x80
+    strict_lo = strict_hi = 0
+    for trial in range(300):
+        a = synth.narrow_exponent_bits(rng, L, t, 10, 20).tolist() if t != fm.E4M3 else synth.random_bits(rng, L, t).tolist()
+        b = synth.narrow_exponent_bits(rng, L, t, 10, 20).tolist() if t != fm.E4M3 else synth.random_bits(rng, L, t).tolist()
+        if t == fm.BF16:
+            a = synth.narrow_exponent_bits(rng, L, t, 120, 135).tolist()
+            b = synth.narrow_exponent_bits(rng, L, t, 120, 135).tolist()
+        if t == fm.E4M3:
+            a = [x if (x & 0x7F) != 0x7F else 0x38 for x in a]      # no NaN codes
+            b = [x if (x & 0x7F) != 0x7F else 0x38 for x in b]
+        base = 127 + (0 if t == fm.BF16 else (-10 if t != fm.E4M3 else 0))
+        c = int(synth.narrow_exponent_bits(rng, 1, fm.FP32, base - 30, base + 12)[0])
+        d = fdpa_group(p, a, b, c, t, t)
+        d_mirror = fdpa_group(p, [x ^ sign_in for x in a], b, c ^ 0x80000000, t, t) ^ 0x80000000
+        if mode == C_AFTER_RD:
+            mid = fdpa_group(p.with_(c_mode=C_AFTER_EXACT), a, b, c, t, t)
+            lo, m_, hi = (int(ordered_key(x)) for x in (d, mid, d_mirror))
+            assert lo <= m_ <= hi, (trial, hex(d), hex(mid), hex(d_mirror))
+        else:
+            lo, hi = int(ordered_key(d)), int(ordered_key(d_mirror))
+            assert lo <= hi
+        strict_lo += lo < hi
+    assert strict_lo > 10          # the bracket is not trivially tight: the rounding direction does matter
+
+
+def test_loss_is_bounded_and_one_sided():
+    # S 2^E lies below T 2^e_max + c by less than 2^(E - F2) + 2^(E - F)   (TR-FDPA, before rho)
+    rng = np.random.default_rng(5)
+    p = ModelParams(group_len=8, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD)
+    q = p.with_(c_mode=C_AFTER_EXACT)
+    for _ in range(200):
+        a = synth.narrow_exponent_bits(rng, 8, fm.FP16, 8, 22).tolist()
+        b = synth.narrow_exponent_bits(rng, 8, fm.FP16, 8, 22).tolist()
+        c = int(synth.narrow_exponent_bits(rng, 1, fm.FP32, 100, 150)[0])
+        d, ref = fdpa_group(p, a, b, c, fm.FP16, fm.FP16), fdpa_group(q, a, b, c, fm.FP16, fm.FP16)
+        x, y = Fraction(bits_f32(d)), Fraction(bits_f32(ref))
+        da = [fm.decode(v, fm.FP16) for v in a]
+        db = [fm.decode(v, fm.FP16) for v in b]
+        E = max(max(u.exp + v.exp for u, v in zip(da, db)), fm.decode(c, fm.FP32).exp)
+        ulp = Fraction(2) ** (max(E + 5, -126) - 23)       # |S| < 2^5 * 2^E: generous bound on one output ulp
+        assert x <= y
+        assert y - x <= Fraction(2) ** (E - 31) + Fraction(2) ** (E - 24) + 2 * ulp
+
+
+def test_bias_toward_minus_infinity():
+    """Sec. 6 (numerical bias): with A, B ~ 1000 N(0,1) in FP16, C ~ N(0,1) and K = 8 the error of the TR-FDPA
+    result against the real value leans negative, while the same operation without the RD steps is centred."""
+    rng = np.random.default_rng(2024)
+    n = 40000
+    A = (1000.0 * rng.standard_normal((n, 1, 8))).astype(np.float16).view(np.uint16)
+    B = (1000.0 * rng.standard_normal((n, 1, 8))).astype(np.float16).view(np.uint16)
+    Cf = rng.standard_normal((n, 1, 1)).astype(np.float32)
+    C = Cf.view(np.uint32)
+    real = (A.view(np.float16).astype(np.float64) * B.view(np.float16).astype(np.float64)).sum(axis=2)[:, :, None] + Cf
+    d_rd = o2lib.emulate_mma(TR, A, B, C, fm.FP16, fm.FP16)[0].view(np.float32).astype(np.float64)
+    d_ex = o2lib.emulate_mma(TR.with_(c_mode=C_AFTER_EXACT), A, B, C, fm.FP16, fm.FP16)[0].view(np.float32).astype(np.float64)
+    delta_rd, delta_ex = (d_rd - real).ravel(), (d_ex - real).ravel()
+    se = delta_ex.std() / np.sqrt(n)
+    assert delta_rd.mean() < -6 * se
+    assert abs(delta_ex.mean()) < 4 * se
+    assert (delta_rd <= delta_ex).all() and (delta_rd < delta_ex).mean() > 0.05
+
+
+# ------------------------------------------------------------------ the C form agrees with the rational form
+@pytest.mark.parametrize("ta,tb", [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, fm.E5M2),
+                                   (fm.E4M3, fm.E4M3), (fm.FP16, fm.BF16)])
+def test_o2_equals_rational_oracle_tr_gtr(ta, tb):
+    rng = np.random.default_rng(300 + 8 * ta + tb)
+    for trial in range(16):
+        mode = C_AFTER_RD if trial % 2 else C_AFTER_RD_EVEN_ODD
+        L = int(rng.choice([2, 4, 8, 16, 0]))
+        k = int(rng.choice([8, 16, 32])) if L == 0 else L * int(rng.integers(1, 4))
+        F = int(rng.choice([0, 3, 13, 23, 24, 25, 31, 40]))
+        F2 = int(rng.choice([0, 24, 31, 31, 31, 36, 48]))
+        p = ModelParams(group_len=L, frac_bits=F, frac_bits2=F2, c_mode=mode, out_round=int(rng.integers(0, 2)),
+                        ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)),
+                        nan_bits=0x7FFFFFFF if trial % 3 == 0 else 0x7FC00000)
+        nb, m, n = 2, 3, 4
+        A = synth.random_bits(rng, (nb, m, k), ta)
+        B = synth.random_bits(rng, (nb, n, k), tb)
+        lo, hi = ((90, 165) if trial % 4 < 2 else (1, 254))
+        if ta == fm.BF16 and tb == fm.BF16 and trial % 4 < 2:
+            A = synth.narrow_exponent_bits(rng, (nb, m, k), ta, 100, 150)
+            B = synth.narrow_exponent_bits(rng, (nb, n, k), tb, 100, 150)
+        C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, lo, hi)
+        if trial % 5 == 0:
+            A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[ta], 0.02)
+            B = synth.sprinkle(rng, B, synth.SPECIAL_CODES[tb], 0.02)
+            C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32], 0.05)
+        want = emulate_mma(p, A, B, C, ta, tb)
+        got, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
+        assert np.array_equal(got, want), (p, np.argwhere(got != want)[:3])
+
+
+def test_o2_accumulator_exponent_sweep():
+    # the accumulator's exponent swept across every alignment distance, both signs, extreme significands
+    for mode, L in ((C_AFTER_RD, 2), (C_AFTER_RD_EVEN_ODD, 2)):
+        p = ModelParams(group_len=L, frac_bits=24, frac_bits2=31, c_mode=mode)
+        A = np.array([[[fp16_bits(1.5), fp16_bits(-2.0 ** -8 * 1.0009765625)]]], dtype=np.uint16)
+        B = np.array([[[fp16_bits(1.25), fp16_bits(1.0)]]], dtype=np.uint16)
+        for ec in range(127 - 70, 127 + 45):
+            for csig in (0, 1, 0x7FFFFF, 0x400000, 0x2AAAAA):
+                for sgn in (0, 1):
+                    C = np.array([[[(sgn << 31) | (ec << 23) | csig]]], dtype=np.uint32)
+                    for rho in (RNE, RZ):
+                        q = p.with_(out_round=rho)
+                        assert np.array_equal(o2lib.emulate_mma(q, A, B, C, fm.FP16, fm.FP16)[0],
+                                              emulate_mma(q, A, B, C, fm.FP16, fm.FP16)), (mode, ec, csig, sgn, rho)
+
+
+def test_o2_rejects_odd_group_for_gtr():
+    p = ModelParams(group_len=3, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD_EVEN_ODD)
+    A = np.zeros((1, 1, 3), dtype=np.uint16)
+    with pytest.raises(ValueError):
+        o2lib.emulate_mma(p, A, A, np.zeros((1, 1, 1), dtype=np.uint32), fm.FP16, fm.FP16)
+    with pytest.raises(ValueError):
+        emulate_mma(p, A, A, np.zeros((1, 1, 1), dtype=np.uint32), fm.FP16, fm.FP16)
