@@ -10,7 +10,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmmaemu.so")
 
 E4M3, E5M2, FP16, BF16, FP32 = 0, 1, 2, 3, 4
-C_IN_GROUP, C_AFTER_EXACT = 0, 1
+C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 RNE, RZ = 0, 1
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
 SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2

@@ -83,14 +83,20 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: struct_size %u, expected %zu", p->struct_size, sizeof(mmaemu_model_params));
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if (p->c_mode > MMAEMU_C_AFTER_EXACT || p->out_round > MMAEMU_ROUND_RZ || p->ftz_in > 1 || p->ftz_out > 1) {
+    if (p->c_mode > MMAEMU_C_AFTER_RD_EVEN_ODD || p->out_round > MMAEMU_ROUND_RZ || p->ftz_in > 1 || p->ftz_out > 1) {
         set_error("model_create: enum field out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if (p->align_round != MMAEMU_ALIGN_RZ || p->frac_bits2 != 0 || p->out_mant_bits != 23) {
-        set_error("model_create: only RZ alignment, frac_bits2 = 0 and FP32 output (out_mant_bits = 23) are supported");
+    if (p->align_round != MMAEMU_ALIGN_RZ || p->out_mant_bits != 23) {
+        set_error("model_create: only RZ alignment and FP32 output (out_mant_bits = 23) are supported");
         return MMAEMU_ERR_UNSUPPORTED;
     }
+    const bool rd_mode = p->c_mode == MMAEMU_C_AFTER_RD || p->c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD;
+    if (!rd_mode && p->frac_bits2 != 0) {
+        set_error("model_create: frac_bits2 is used by the C_AFTER_RD modes only and must be 0 otherwise");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if (rd_mode && p->frac_bits2 > 48) { set_error("model_create: frac_bits2 %u > 48", p->frac_bits2); return MMAEMU_ERR_UNSUPPORTED; }
     if (p->frac_bits > 40) { set_error("model_create: frac_bits %u > 40", p->frac_bits); return MMAEMU_ERR_UNSUPPORTED; }
     if (p->group_len > (1u << 20)) { set_error("model_create: group_len %u > 2^20", p->group_len); return MMAEMU_ERR_UNSUPPORTED; }
     mmaemu_model *m = new (std::nothrow) mmaemu_model;
@@ -139,6 +145,17 @@ mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const
         set_error("emulate_mma: C_AFTER_EXACT needs frac_bits + 2 + ceil(log2 L) <= 56");
         return MMAEMU_ERR_UNSUPPORTED;
     }
+    if (mp.c_mode == MMAEMU_C_AFTER_RD || mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD) {
+        const uint32_t fm = mp.frac_bits > mp.frac_bits2 ? mp.frac_bits : mp.frac_bits2;
+        if (fm + 3 + ceil_log2(L) > 53) {
+            set_error("emulate_mma: the C_AFTER_RD modes need max(frac_bits, frac_bits2) + 3 + ceil(log2 L) <= 53");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        if (mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD && (L & 1u)) {
+            set_error("emulate_mma: C_AFTER_RD_EVEN_ODD needs an even group length (L=%u)", L);
+            return MMAEMU_ERR_SHAPE;
+        }
+    }
     const uint64_t mn = (uint64_t)m * n;
     if (batch && (mn > (1ull << 40) || batch > (1ull << 62) / mn || batch * mn > (1ull << 48) ||
                   batch * (uint64_t)(m > n ? m : n) > (1ull << 62) / k)) {
@@ -150,6 +167,7 @@ mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const
     ModelArgs ma;
     ma.L = L;
     ma.F = (int32_t)mp.frac_bits;
+    ma.F2 = (int32_t)mp.frac_bits2;
     ma.c_mode = mp.c_mode;
     ma.out_round = mp.out_round;
     ma.ftz_in = mp.ftz_in;

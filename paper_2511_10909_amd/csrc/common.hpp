@@ -30,6 +30,7 @@ inline FmtInfo fmt_info(uint32_t t)
 struct ModelArgs {
     uint32_t L;          // group length actually used: min(K, L_max)
     int32_t F;           // fractional bits of the aligned terms
+    int32_t F2;          // fractional bits kept of the product sum (TR-FDPA / GTR-FDPA)
     uint32_t c_mode, out_round, ftz_in, ftz_out, nan_bits;
 };
 

@@ -52,11 +52,15 @@ def test_host_side_validation_needs_no_gpu():
     mm.model_destroy(h)
     mm.model_destroy(None)
     for kw, status in ((dict(frac_bits=41), 2), (dict(out_round=2), 1), (dict(c_mode=5), 1), (dict(align_round=1), 2),
-                       (dict(out_mant_bits=13), 2), (dict(struct_size=40), 1), (dict(group_len=(1 << 20) + 1), 2)):
+                       (dict(out_mant_bits=13), 2), (dict(frac_bits2=31), 2), (dict(c_mode=2, frac_bits2=49), 2), (dict(struct_size=40), 1), (dict(group_len=(1 << 20) + 1), 2)):
         with pytest.raises(mm.MmaemuError) as ei:
             mm.model_create(**kw)
         assert ei.value.status == status, kw
     assert "frac_bits" in mm.last_error() or "group_len" in mm.last_error()
+    for mode in (mm.C_AFTER_RD, mm.C_AFTER_RD_EVEN_ODD):
+        h = mm.model_create(group_len=8, frac_bits=24, frac_bits2=31, c_mode=mode)
+        assert mm.model_get_params(h)["frac_bits2"] == 31
+        mm.model_destroy(h)
     info = mm.mfma_info(mm.MFMA_F32_16X16X32_FP8_BF8)
     assert info == dict(m=16, n=16, k=32, a=mm.E4M3, b=mm.E5M2)
     with pytest.raises(mm.MmaemuError):

@@ -28,7 +28,7 @@ PAIRS = [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, f
 def gpu_emulate(mm, p, A, B, C, ta, tb):
     nb, m, k = A.shape
     n = B.shape[1]
-    h = mm.model_create(group_len=p.group_len, frac_bits=p.frac_bits, c_mode=p.c_mode, out_round=p.out_round,
+    h = mm.model_create(group_len=p.group_len, frac_bits=p.frac_bits, frac_bits2=p.frac_bits2, c_mode=p.c_mode, out_round=p.out_round,
                         ftz_in=p.ftz_in, ftz_out=p.ftz_out, nan_bits=p.nan_bits)
     try:
         dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(np.uint32))
