@@ -40,6 +40,7 @@ enum { R_RNE = 0, R_RZ = 1 };
 
 typedef struct {
     uint32_t group_len, frac_bits, align_round, c_mode, out_round, ftz_in, ftz_out, nan_bits, frac_bits2;
+    uint32_t split, acc_special_truncation, frac_bits_merge, frac_bits_acc, skip_zero_terms, f2_at_leading_bit, zero_result_positive;
 } o2_params;
 
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
@@ -159,20 +160,86 @@ static i128 align_rd(i128 v, int lsb, int unit)
     return (r < 0) ? q - 1 : q;
 }
 
-/* Steps 3 and 4 of Algorithm "TR-FDPA" (steps 4 and 5 of "GTR-FDPA"): T counts units of
- * 2^(emax - F); returns rho(RD_F2(T at E) + RD_F(c at E)). */
-static uint32_t rounded_sum_with_c(const o2_params *p, i128 T, int emax, dec_t dc, int special_truncation)
+static dec_t dec_in(const o2_params *p, uint32_t bits, int t)
+{
+    dec_t x = decode(bits, t);
+    if (p->ftz_in && x.cls == CLS_SUB) x = decode(0u, t);          /* FlushSubnormal: -> +0.0 */
+    return x;
+}
+
+/* maximum exponent over the products first, first+stride, ... (count of them); returns 0 when
+ * no product takes part (count = 0, or all significands zero and skip_zero_terms set) */
+static int part_emax(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t first, uint32_t stride,
+                     uint32_t count, int ta, int tb, int *emax)
+{
+    int any = 0;
+    for (uint32_t q = 0; q < count; ++q) {
+        uint32_t k = first + q * stride;
+        dec_t x = dec_in(p, a[k], ta), y = dec_in(p, b[k], tb);
+        if (p->skip_zero_terms && (x.sig == 0 || y.sig == 0)) continue;
+        int e = x.exp + y.exp;
+        if (!any || e > *emax) *emax = e;
+        any = 1;
+    }
+    return any;
+}
+
+/* sum of the same products, each aligned to units of 2^unit with truncation toward zero */
+static i128 part_sum(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t first, uint32_t stride,
+                     uint32_t count, int ta, int tb, int unit)
+{
+    i128 S = 0;
+    for (uint32_t q = 0; q < count; ++q) {
+        uint32_t k = first + q * stride;
+        dec_t x = dec_in(p, a[k], ta), y = dec_in(p, b[k], tb);
+        u128 prod = (u128)((uint64_t)x.sig * (uint64_t)y.sig);      /* exact product of significands */
+        int e = x.exp + y.exp;                                       /* sum of exponents */
+        u128 al = align_rz(prod, e - FMT[ta].mbits - FMT[tb].mbits, unit);
+        if (x.sign ^ y.sign) S -= (i128)al; else S += (i128)al;
+    }
+    return S;
+}
+
+/* The rounded sum with the accumulator (Algorithm "TR-FDPA" steps 3-4, "GTR-FDPA" steps 4-5):
+ * T counts units of 2^unit_T (T = 0 and have_T = 0 when no product took part). */
+static uint32_t rounded_sum_with_c(const o2_params *p, int have_T, i128 T, int emax, int unit_T, dec_t dc, int special_truncation)
 {
     const int F = (int)p->frac_bits, F2 = (int)p->frac_bits2;
-    const int E = dc.exp > emax ? dc.exp : emax;
-    i128 T2 = align_rd(T, emax - F, E - F2);
+    const int Fc = p->frac_bits_acc ? (int)p->frac_bits_acc : F;
+    const int c_live = !(p->skip_zero_terms && dc.sig == 0);
+    if (!have_T && !c_live) return 0u;
+    int E;
+    if (have_T && c_live) E = dc.exp > emax ? dc.exp : emax;
+    else E = have_T ? emax : dc.exp;
     i128 sc = dc.sign ? -(i128)dc.sig : (i128)dc.sig;
-    i128 sc2 = align_rd(sc, dc.exp - 23, E - F);
-    if (special_truncation && dc.exp < E - F - 1) sc2 = 0;
-    const int Fm = F2 > F ? F2 : F;                                  /* common unit 2^(E - Fm) */
-    i128 S = T2 * ((i128)1 << (Fm - F2)) + sc2 * ((i128)1 << (Fm - F));
+    i128 sc2 = align_rd(sc, dc.exp - 23, E - Fc);
+    if (special_truncation && dc.exp < E - Fc - 1) sc2 = 0;
+    const int unit_c = E - Fc;
+    if (!have_T) { T = 0; unit_T = unit_c; }
+    i128 S; int unit;
+    if (p->f2_at_leading_bit) {
+        /* exact sum first.  If T lies far below the accumulator's unit it is first rounded down to
+         * units of 2^(unit_c - 64): rounding down in two steps equals rounding down once. */
+        if (unit_c - unit_T > 64) { T = align_rd(T, unit_T, unit_c - 64); unit_T = unit_c - 64; }
+        unit = unit_T < unit_c ? unit_T : unit_c;
+        S = T * ((i128)1 << (unit_T - unit)) + sc2 * ((i128)1 << (unit_c - unit));
+        if (S == 0) return 0u;
+        int lead = bitlen128((u128)(S < 0 ? -S : S)) - 1 + unit;
+        if (lead - F2 > unit) { S = align_rd(S, unit, lead - F2); unit = lead - F2; }
+    } else {
+        i128 T2 = align_rd(T, unit_T, E - F2);
+        unit = (E - F2) < unit_c ? (E - F2) : unit_c;
+        S = T2 * ((i128)1 << ((E - F2) - unit)) + sc2 * ((i128)1 << (unit_c - unit));
+    }
     int neg = S < 0;
-    return to_fp32(neg, (u128)(neg ? -S : S), E - Fm, 0, (int)p->out_round);
+    return to_fp32(neg, (u128)(neg ? -S : S), unit, 0, (int)p->out_round);
+}
+
+static uint32_t finish(const o2_params *p, uint32_t d)
+{
+    if (p->ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
+    if (p->zero_result_positive && (d & 0x7FFFFFFFu) == 0) d = 0u;
+    return d;
 }
 
 static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t c,
@@ -180,27 +247,21 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
 {
     const int F = (int)p->frac_bits;
     const int fa = FMT[ta].mbits, fb = FMT[tb].mbits;
-    dec_t dc = decode(c, T_FP32);
-    if (p->ftz_in && dc.cls == CLS_SUB) dc = decode(0u, T_FP32);
+    uint32_t c_mode = p->c_mode, split = p->split, trunc = p->acc_special_truncation;
+    if (c_mode == C_AFTER_RD_EVEN_ODD) { c_mode = C_AFTER_RD; split = 1; trunc = 1; }   /* GTR-FDPA by name */
+    dec_t dc = dec_in(p, c, T_FP32);
 
-    /* pass over the inputs: specials (Sec. 4.2) and e_max */
+    /* special values (Sec. 4.2) */
     int any_nan = dc.cls == CLS_NAN, pinf = 0, ninf = 0;
-    int emax = -100000, eeven = -100000, eodd = -100000;
     for (uint32_t k = 0; k < L; ++k) {
-        dec_t x = decode(a[k], ta), y = decode(b[k], tb);
-        if (p->ftz_in) { if (x.cls == CLS_SUB) x = decode(0u, ta); if (y.cls == CLS_SUB) y = decode(0u, tb); }
+        dec_t x = dec_in(p, a[k], ta), y = dec_in(p, b[k], tb);
         if (x.cls == CLS_NAN || y.cls == CLS_NAN) any_nan = 1;
         else if (x.cls == CLS_INF || y.cls == CLS_INF) {
             if (x.cls == CLS_ZERO || y.cls == CLS_ZERO) any_nan = 1;
             else if (x.sign ^ y.sign) ninf = 1; else pinf = 1;
-        } else {
-            int e = x.exp + y.exp;
-            if (e > emax) emax = e;
-            if (k & 1) { if (e > eodd) eodd = e; } else { if (e > eeven) eeven = e; }
-            if (p->c_mode >= C_AFTER_RD) {                           /* product overflow, Sec. 4.2 */
-                uint64_t prod = (uint64_t)x.sig * (uint64_t)y.sig;
-                if (prod && bitlen128((u128)prod) - 1 + e - fa - fb >= 128) { if (x.sign ^ y.sign) ninf = 1; else pinf = 1; }
-            }
+        } else if (c_mode == C_AFTER_RD) {                            /* product overflow, Sec. 4.2 */
+            uint64_t prod = (uint64_t)x.sig * (uint64_t)y.sig;
+            if (prod && bitlen128((u128)prod) - 1 + x.exp + y.exp - fa - fb >= 128) { if (x.sign ^ y.sign) ninf = 1; else pinf = 1; }
         }
     }
     if (dc.cls == CLS_INF) { if (dc.sign) ninf = 1; else pinf = 1; }
@@ -208,49 +269,50 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
     if (pinf) return 0x7F800000u;
     if (ninf) return 0xFF800000u;
 
-    if (p->c_mode == C_AFTER_RD_EVEN_ODD) {
-        i128 Te = 0, To = 0;
-        for (uint32_t k = 0; k < L; ++k) {
-            dec_t x = decode(a[k], ta), y = decode(b[k], tb);
-            if (p->ftz_in) { if (x.cls == CLS_SUB) x = decode(0u, ta); if (y.cls == CLS_SUB) y = decode(0u, tb); }
-            u128 prod = (u128)((uint64_t)x.sig * (uint64_t)y.sig);
-            int e = x.exp + y.exp;
-            i128 al = (i128)align_rz(prod, e - fa - fb, ((k & 1) ? eodd : eeven) - F);
-            if (x.sign ^ y.sign) al = -al;
-            if (k & 1) To += al; else Te += al;
+    if (c_mode == C_AFTER_RD) {
+        if (split == 0) {
+            int emax = 0;
+            int have = part_emax(p, a, b, 0, 1, L, ta, tb, &emax);
+            i128 T = have ? part_sum(p, a, b, 0, 1, L, ta, tb, emax - F) : 0;
+            return finish(p, rounded_sum_with_c(p, have, T, emax, emax - F, dc, (int)trunc));
         }
-        i128 T = align_rd(Te, eeven - F, emax - F) + align_rd(To, eodd - F, emax - F);
-        uint32_t d = rounded_sum_with_c(p, T, emax, dc, 1);
-        if (p->ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
-        return d;
+        /* two sub-groups: even / odd products (split 1) or first / second half (split 2) */
+        const int Fm = p->frac_bits_merge ? (int)p->frac_bits_merge : F;
+        uint32_t first[2] = {0, split == 1 ? 1u : L / 2}, stride = split == 1 ? 2u : 1u;
+        int e_part[2] = {0, 0}, have[2], emax = 0, any = 0;
+        i128 T_part[2] = {0, 0};
+        for (int g = 0; g < 2; ++g) {
+            have[g] = part_emax(p, a, b, first[g], stride, L / 2, ta, tb, &e_part[g]);
+            if (!have[g]) continue;
+            T_part[g] = part_sum(p, a, b, first[g], stride, L / 2, ta, tb, e_part[g] - F);
+            if (!any || e_part[g] > emax) emax = e_part[g];
+            any = 1;
+        }
+        i128 T = 0;
+        for (int g = 0; g < 2; ++g)
+            if (have[g]) T += align_rd(T_part[g], e_part[g] - F, emax - Fm);
+        return finish(p, rounded_sum_with_c(p, any, T, emax, emax - Fm, dc, (int)trunc));
     }
 
-    if (p->c_mode == C_IN_GROUP && dc.exp > emax) emax = dc.exp;
-    const int unit = emax - F;
-
-    i128 S = 0;
-    for (uint32_t k = 0; k < L; ++k) {
-        dec_t x = decode(a[k], ta), y = decode(b[k], tb);
-        if (p->ftz_in) { if (x.cls == CLS_SUB) x = decode(0u, ta); if (y.cls == CLS_SUB) y = decode(0u, tb); }
-        u128 prod = (u128)((uint64_t)x.sig * (uint64_t)y.sig);      /* exact product of significands */
-        int e = x.exp + y.exp;                                       /* sum of exponents */
-        u128 al = align_rz(prod, e - fa - fb, unit);                 /* RZ_F(s_k 2^(e_k - e_max)) */
-        if (x.sign ^ y.sign) S -= (i128)al; else S += (i128)al;
-    }
-    uint32_t d;
-    if (p->c_mode == C_IN_GROUP) {
+    int emax = 0;
+    int have = part_emax(p, a, b, 0, 1, L, ta, tb, &emax);
+    if (c_mode == C_IN_GROUP) {
+        const int c_live = !(p->skip_zero_terms && dc.sig == 0);
+        if (!have && !c_live) return 0u;
+        if (c_live && (!have || dc.exp > emax)) emax = dc.exp;
+        const int unit = emax - F;
+        i128 S = part_sum(p, a, b, 0, 1, L, ta, tb, unit);
         u128 al = align_rz((u128)dc.sig, dc.exp - 23, unit);
         if (dc.sign) S -= (i128)al; else S += (i128)al;
         int neg = S < 0;
-        d = to_fp32(neg, (u128)(neg ? -S : S), unit, 0, (int)p->out_round);
-    } else if (p->c_mode == C_AFTER_RD) {
-        d = rounded_sum_with_c(p, S, emax, dc, 0);
-    } else {
-        int neg = S < 0;
-        d = add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, (int)p->out_round);
+        return finish(p, to_fp32(neg, (u128)(neg ? -S : S), unit, 0, (int)p->out_round));
     }
-    if (p->ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
-    return d;
+    /* C_AFTER_EXACT */
+    if (!have) emax = 0;
+    const int unit = emax - F;
+    i128 S = part_sum(p, a, b, 0, 1, L, ta, tb, unit);
+    int neg = S < 0;
+    return finish(p, add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, (int)p->out_round));
 }
 
 static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out)
@@ -264,11 +326,18 @@ static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out
         int lg = 0; while ((1u << lg) < L) ++lg;
         if ((int)p->frac_bits + 2 + lg > 40) return -2;
     }
-    if (p->c_mode >= C_AFTER_RD) {      /* keep every intermediate of rounded_sum_with_c() below 2^120 */
+    if (p->c_mode >= C_AFTER_RD) {      /* keep every intermediate of the RD steps below 2^126 */
         int lg = 0; while ((1u << lg) < L) ++lg;
-        int Fm = p->frac_bits2 > p->frac_bits ? (int)p->frac_bits2 : (int)p->frac_bits;
-        if (p->frac_bits2 > 64 || Fm + 3 + lg > 100) return -2;
-        if (p->c_mode == C_AFTER_RD_EVEN_ODD && (L & 1)) return -3;
+        uint32_t fmax = p->frac_bits;
+        if (p->frac_bits2 > fmax) fmax = p->frac_bits2;
+        if (p->frac_bits_merge > fmax) fmax = p->frac_bits_merge;
+        if (p->frac_bits_acc > fmax) fmax = p->frac_bits_acc;
+        if (fmax > 48 || lg > 20) return -2;
+        uint32_t fc = p->frac_bits_acc ? p->frac_bits_acc : p->frac_bits;
+        if (p->frac_bits2 > fc + 40) return -2;                 /* see rounded_sum_with_c(), two-step rounding */
+        uint32_t split = p->c_mode == C_AFTER_RD_EVEN_ODD ? 1u : p->split;
+        if (split > 2) return -2;
+        if (split && (L & 1)) return -3;
     }
     *L_out = L;
     return 0;

@@ -96,7 +96,25 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: frac_bits2 is used by the C_AFTER_RD modes only and must be 0 otherwise");
         return MMAEMU_ERR_UNSUPPORTED;
     }
-    if (rd_mode && p->frac_bits2 > 48) { set_error("model_create: frac_bits2 %u > 48", p->frac_bits2); return MMAEMU_ERR_UNSUPPORTED; }
+    if (rd_mode && (p->frac_bits2 > 48 || p->frac_bits_merge > 48 || p->frac_bits_acc > 48)) {
+        set_error("model_create: frac_bits2 / frac_bits_merge / frac_bits_acc above 48");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if (p->split > MMAEMU_SPLIT_HALVES || p->acc_special_truncation > 1 || p->f2_at_leading_bit > 1 ||
+        p->skip_zero_terms > 1 || p->zero_result_positive > 1) {
+        set_error("model_create: enum field out of range");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (p->c_mode != MMAEMU_C_AFTER_RD &&
+        (p->split || p->acc_special_truncation || p->frac_bits_merge || p->frac_bits_acc || p->f2_at_leading_bit)) {
+        set_error("model_create: split, acc_special_truncation, frac_bits_merge, frac_bits_acc and f2_at_leading_bit "
+                  "belong to c_mode C_AFTER_RD");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if (p->frac_bits_merge && p->split == MMAEMU_SPLIT_NONE) {
+        set_error("model_create: frac_bits_merge needs a split");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
     if (p->frac_bits > 40) { set_error("model_create: frac_bits %u > 40", p->frac_bits); return MMAEMU_ERR_UNSUPPORTED; }
     if (p->group_len > (1u << 20)) { set_error("model_create: group_len %u > 2^20", p->group_len); return MMAEMU_ERR_UNSUPPORTED; }
     mmaemu_model *m = new (std::nothrow) mmaemu_model;
@@ -145,14 +163,18 @@ mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const
         set_error("emulate_mma: C_AFTER_EXACT needs frac_bits + 2 + ceil(log2 L) <= 56");
         return MMAEMU_ERR_UNSUPPORTED;
     }
-    if (mp.c_mode == MMAEMU_C_AFTER_RD || mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD) {
-        const uint32_t fm = mp.frac_bits > mp.frac_bits2 ? mp.frac_bits : mp.frac_bits2;
-        if (fm + 3 + ceil_log2(L) > 53) {
-            set_error("emulate_mma: the C_AFTER_RD modes need max(frac_bits, frac_bits2) + 3 + ceil(log2 L) <= 53");
+    const bool rd_mode = mp.c_mode == MMAEMU_C_AFTER_RD || mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD;
+    const uint32_t split = mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD ? (uint32_t)MMAEMU_SPLIT_EVEN_ODD : mp.split;
+    if (rd_mode) {
+        uint32_t fmax = mp.frac_bits > mp.frac_bits2 ? mp.frac_bits : mp.frac_bits2;
+        if (mp.frac_bits_merge > fmax) fmax = mp.frac_bits_merge;
+        if (mp.frac_bits_acc > fmax) fmax = mp.frac_bits_acc;
+        if (fmax + 3 + ceil_log2(L) > 53) {
+            set_error("emulate_mma: the C_AFTER_RD modes need max(F, F2, F_m, F_c) + 3 + ceil(log2 L) <= 53");
             return MMAEMU_ERR_UNSUPPORTED;
         }
-        if (mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD && (L & 1u)) {
-            set_error("emulate_mma: C_AFTER_RD_EVEN_ODD needs an even group length (L=%u)", L);
+        if (split != MMAEMU_SPLIT_NONE && (L & 1u)) {
+            set_error("emulate_mma: a split group needs an even group length (L=%u)", L);
             return MMAEMU_ERR_SHAPE;
         }
     }
@@ -168,7 +190,14 @@ mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const
     ma.L = L;
     ma.F = (int32_t)mp.frac_bits;
     ma.F2 = (int32_t)mp.frac_bits2;
-    ma.c_mode = mp.c_mode;
+    ma.c_mode = rd_mode ? (uint32_t)MMAEMU_C_AFTER_RD : mp.c_mode;
+    ma.split = split;
+    ma.acc_special_truncation = mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD ? 1u : mp.acc_special_truncation;
+    ma.Fm = (int32_t)(mp.frac_bits_merge ? mp.frac_bits_merge : mp.frac_bits);
+    ma.Fc = (int32_t)(mp.frac_bits_acc ? mp.frac_bits_acc : mp.frac_bits);
+    ma.f2_at_leading_bit = mp.f2_at_leading_bit;
+    ma.skip_zero_terms = mp.skip_zero_terms;
+    ma.zero_result_positive = mp.zero_result_positive;
     ma.out_round = mp.out_round;
     ma.ftz_in = mp.ftz_in;
     ma.ftz_out = mp.ftz_out;

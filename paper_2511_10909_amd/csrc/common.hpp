@@ -32,6 +32,10 @@ struct ModelArgs {
     int32_t F;           // fractional bits of the aligned terms
     int32_t F2;          // fractional bits kept of the product sum (TR-FDPA / GTR-FDPA)
     uint32_t c_mode, out_round, ftz_in, ftz_out, nan_bits;
+    // variations of the RD mode (c_mode is never C_AFTER_RD_EVEN_ODD here: the entry point rewrites it)
+    uint32_t split, acc_special_truncation;
+    int32_t Fm, Fc;      // merge and accumulator precisions, already defaulted to F
+    uint32_t f2_at_leading_bit, skip_zero_terms, zero_result_positive;
 };
 
 // error plumbing (api.hip)

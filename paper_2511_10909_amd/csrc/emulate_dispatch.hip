@@ -20,7 +20,8 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // the tiled kernels need 8-byte aligned operand arrays (four consecutive k elements are
     // loaded at once) and group sums below 2^52
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) == 0;
-    const bool tiled_mode = p.c_mode == MMAEMU_C_IN_GROUP || p.c_mode == MMAEMU_C_AFTER_EXACT;
+    const bool tiled_mode = (p.c_mode == MMAEMU_C_IN_GROUP || p.c_mode == MMAEMU_C_AFTER_EXACT) && !p.skip_zero_terms &&
+                            !p.zero_result_positive;
     if (tiled_mode && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;

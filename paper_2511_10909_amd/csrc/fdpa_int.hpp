@@ -35,31 +35,109 @@ __device__ __forceinline__ Dec decode(uint32_t bits, uint32_t ftz_in)
     return d;
 }
 
+typedef __int128 i128;
+typedef unsigned __int128 u128;
+
 // RD: v counts units of 2^lsb; the result counts units of 2^unit, rounded toward minus infinity.
-// Left shifts are bounded by the entry point's limits on F and F2.
-__device__ __forceinline__ int64_t align_rd(int64_t v, int lsb, int unit)
+// Left shifts are bounded by the entry point's limits on the precisions.
+__device__ __forceinline__ i128 align_rd(i128 v, int lsb, int unit)
 {
     const int sh = lsb - unit;
-    if (sh >= 0) return (int64_t)((uint64_t)v << sh);
-    return sh > -64 ? (v >> (-sh)) : (v >> 63);        // arithmetic shift = floor
+    if (sh >= 0) return (i128)((u128)v << sh);
+    return sh > -127 ? (v >> (-sh)) : (v >> 127);      // arithmetic shift = floor
 }
 
-// Algorithm "TR-FDPA", steps 3 and 4 (Algorithm "GTR-FDPA", steps 4 and 5): T counts units of
-// 2^(emax - F).  E = max(e_max, e_c); T' = RD_F2(T at E); s_c' = RD_F(c at E), dropped by the
-// special truncation when e_c < E - F - 1; d = rho(T' + s_c').
-__device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, int64_t T, int emax, const Dec &dc,
-                                                       bool special_truncation)
+__device__ __forceinline__ int bitlen128(u128 x)
 {
-    const int E = dc.exp > emax ? dc.exp : emax;
-    const int64_t T2 = align_rd(T, emax - p.F, E - p.F2);
-    const int64_t sc = dc.sign ? -(int64_t)dc.sig : (int64_t)dc.sig;
-    int64_t sc2 = align_rd(sc, dc.exp - 23, E - p.F);
-    if (special_truncation && dc.exp < E - p.F - 1) sc2 = 0;
-    const int Fm = p.F2 > p.F ? p.F2 : p.F;
-    const int64_t S = (int64_t)((uint64_t)T2 << (Fm - p.F2)) + (int64_t)((uint64_t)sc2 << (Fm - p.F));
+    const uint64_t hi = (uint64_t)(x >> 64), lo = (uint64_t)x;
+    return hi ? 128 - __builtin_clzll(hi) : (lo ? 64 - __builtin_clzll(lo) : 0);
+}
+
+// rho for a 128-bit magnitude: the value is first cut to 64 bits with the lost bits remembered
+// (they lie at least 40 places below the leading bit, far under the rounding position).
+__device__ __forceinline__ uint32_t round128_to_fp32(uint32_t neg, u128 mag, int lsb, uint32_t mode)
+{
+    const int bl = bitlen128(mag);
+    if (bl <= 64) return round_to_fp32(neg, (uint64_t)mag, lsb, 0, mode);
+    const int sh = bl - 64;
+    const uint32_t lost = (mag & ((((u128)1) << sh) - 1)) != 0;
+    return round_to_fp32(neg, (uint64_t)(mag >> sh), lsb + sh, lost, mode);
+}
+
+// One sub-group of products k = first, first + stride, ... (count of them): maximum exponent
+// over the terms that take part, then the sum of the terms aligned at that exponent with F
+// fractional bits, truncated toward zero.  Returns false when no term takes part.
+template <int TA, int TB>
+__device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, const typename Fmt<TB>::elem *b,
+                           uint32_t first, uint32_t stride, uint32_t count, int &emax, int64_t &T)
+{
+    constexpr int FA = Fmt<TA>::MB, FB = Fmt<TB>::MB;
+    bool any = false;
+    emax = 0;
+    for (uint32_t q = 0; q < count; ++q) {
+        const uint32_t k = first + q * stride;
+        const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
+        if (p.skip_zero_terms && (x.sig == 0 || y.sig == 0)) continue;
+        const int e = x.exp + y.exp;
+        emax = (!any || e > emax) ? e : emax;
+        any = true;
+    }
+    T = 0;
+    if (!any) return false;
+    const int unit = emax - p.F;
+    for (uint32_t q = 0; q < count; ++q) {
+        const uint32_t k = first + q * stride;
+        const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
+        const uint64_t prod = (uint64_t)(x.sig * y.sig);                    // <= 22 bits
+        const int sh = (x.exp + y.exp - FA - FB) - unit;                    // <= F
+        const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
+        T += (x.sign ^ y.sign) ? -(int64_t)al : (int64_t)al;
+    }
+    return true;
+}
+
+// Algorithm "TR-FDPA", steps 3 and 4 (Algorithm "GTR-FDPA", steps 4 and 5) and their variations:
+// T counts units of 2^unit_T.  E = max(e_max, e_c) over the terms that take part; s_c' = RD_Fc(c at E),
+// dropped by the special truncation when e_c < E - F_c - 1; then either RD_F2(T at E) + s_c', or the
+// exact T + s_c' rounded down to F2 bits below its own leading bit; d = rho of that.
+__device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, bool have_T, int64_t T64, int emax, int unit_T,
+                                                       const Dec &dc)
+{
+    const bool c_live = !(p.skip_zero_terms && dc.sig == 0);
+    if (!have_T && !c_live) return 0u;
+    const int E = (have_T && c_live) ? (dc.exp > emax ? dc.exp : emax) : (have_T ? emax : dc.exp);
+    const i128 sc = dc.sign ? -(i128)dc.sig : (i128)dc.sig;
+    i128 sc2 = align_rd(sc, dc.exp - 23, E - p.Fc);
+    if (p.acc_special_truncation && dc.exp < E - p.Fc - 1) sc2 = 0;
+    const int unit_c = E - p.Fc;
+    i128 T = have_T ? (i128)T64 : (i128)0;
+    if (!have_T) unit_T = unit_c;
+    i128 S;
+    int unit;
+    if (p.f2_at_leading_bit) {
+        // T far below the accumulator's unit is first rounded down to units of 2^(unit_c - 64):
+        // rounding down in two steps equals rounding down once
+        if (unit_c - unit_T > 64) { T = align_rd(T, unit_T, unit_c - 64); unit_T = unit_c - 64; }
+        unit = unit_T < unit_c ? unit_T : unit_c;
+        S = (i128)((u128)T << (unit_T - unit)) + (i128)((u128)sc2 << (unit_c - unit));
+        if (S == 0) return 0u;
+        const int lead = bitlen128((u128)(S < 0 ? -S : S)) - 1 + unit;
+        if (lead - p.F2 > unit) { S = align_rd(S, unit, lead - p.F2); unit = lead - p.F2; }
+    } else {
+        const i128 T2 = align_rd(T, unit_T, E - p.F2);
+        unit = (E - p.F2) < unit_c ? (E - p.F2) : unit_c;
+        S = (i128)((u128)T2 << ((E - p.F2) - unit)) + (i128)((u128)sc2 << (unit_c - unit));
+    }
     if (S == 0) return 0u;
     const uint32_t neg = S < 0;
-    return round_to_fp32(neg, (uint64_t)(neg ? -S : S), E - Fm, 0, p.out_round);
+    return round128_to_fp32(neg, (u128)(neg ? -S : S), unit, p.out_round);
+}
+
+__device__ __forceinline__ uint32_t finish_group(const ModelArgs &p, uint32_t d)
+{
+    if (p.ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
+    if (p.zero_result_positive && (d & 0x7FFFFFFFu) == 0) d = 0u;
+    return d;
 }
 
 template <int TA, int TB>
@@ -69,10 +147,8 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
     constexpr int FA = Fmt<TA>::MB, FB = Fmt<TB>::MB;
     const Dec dc = decode<MMAEMU_FP32>(c, p.ftz_in);
 
-    // pass 1: special values and the maximum exponent
+    // special values (Sec. 4.2)
     bool any_nan = dc.cls == CLS_NAN, pinf = false, ninf = false;
-    const bool rd_mode = p.c_mode == MMAEMU_C_AFTER_RD || p.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD;
-    int emax = -100000, eeven = -100000, eodd = -100000;
     for (uint32_t k = 0; k < L; ++k) {
         const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
         if (x.cls == CLS_NAN || y.cls == CLS_NAN) any_nan = true;
@@ -80,16 +156,10 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
             if (x.cls == CLS_ZERO || y.cls == CLS_ZERO) any_nan = true;      // inf * 0
             else if (x.sign ^ y.sign) ninf = true;
             else pinf = true;
-        } else {
-            const int e = x.exp + y.exp;
-            emax = e > emax ? e : emax;
-            if (k & 1u) eodd = e > eodd ? e : eodd;
-            else eeven = e > eeven ? e : eeven;
-            if (rd_mode) {                                                   // |a b| >= 2^128 is an infinity
-                const uint32_t prod = x.sig * y.sig;
-                if (prod && (31 - __builtin_clz(prod)) + e - FA - FB >= 128) {
-                    if (x.sign ^ y.sign) ninf = true; else pinf = true;
-                }
+        } else if (p.c_mode == MMAEMU_C_AFTER_RD) {                           // |a b| >= 2^128 is an infinity
+            const uint32_t prod = x.sig * y.sig;
+            if (prod && (31 - __builtin_clz(prod)) + x.exp + y.exp - FA - FB >= 128) {
+                if (x.sign ^ y.sign) ninf = true; else pinf = true;
             }
         }
     }
@@ -98,51 +168,56 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
     if (pinf) return 0x7F800000u;
     if (ninf) return 0xFF800000u;
 
-    if (p.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD) {
-        // even and odd products fused apart, each at its own maximum exponent
-        int64_t Te = 0, To = 0;
-        for (uint32_t k = 0; k < L; ++k) {
-            const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
-            const uint64_t prod = (uint64_t)(x.sig * y.sig);
-            const int sh = (x.exp + y.exp - FA - FB) - (((k & 1u) ? eodd : eeven) - p.F);
-            const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
-            const int64_t t = (x.sign ^ y.sign) ? -(int64_t)al : (int64_t)al;
-            if (k & 1u) To += t; else Te += t;
+    if (p.c_mode == MMAEMU_C_AFTER_RD) {
+        if (p.split == MMAEMU_SPLIT_NONE) {
+            int emax; int64_t T;
+            const bool have = fused_part<TA, TB>(p, a, b, 0, 1, L, emax, T);
+            return finish_group(p, rounded_sum_with_c(p, have, T, emax, emax - p.F, dc));
         }
-        const int64_t T = align_rd(Te, eeven - p.F, emax - p.F) + align_rd(To, eodd - p.F, emax - p.F);
-        uint32_t d = rounded_sum_with_c(p, T, emax, dc, true);
-        if (p.ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
-        return d;
+        // two sub-groups, each fused at its own maximum exponent, merged with RD at F_m bits
+        const uint32_t second = p.split == MMAEMU_SPLIT_EVEN_ODD ? 1u : L / 2, stride = p.split == MMAEMU_SPLIT_EVEN_ODD ? 2u : 1u;
+        int e0, e1; int64_t T0, T1;
+        const bool h0 = fused_part<TA, TB>(p, a, b, 0, stride, L / 2, e0, T0);
+        const bool h1 = fused_part<TA, TB>(p, a, b, second, stride, L / 2, e1, T1);
+        const int emax = (h0 && h1) ? (e0 > e1 ? e0 : e1) : (h0 ? e0 : e1);
+        i128 T = 0;
+        if (h0) T += align_rd((i128)T0, e0 - p.F, emax - p.Fm);
+        if (h1) T += align_rd((i128)T1, e1 - p.F, emax - p.Fm);
+        return finish_group(p, rounded_sum_with_c(p, h0 || h1, (int64_t)T, emax, emax - p.Fm, dc));
     }
 
-    if (p.c_mode == MMAEMU_C_IN_GROUP && dc.exp > emax) emax = dc.exp;
-    const int unit = emax - p.F;            // aligned terms count multiples of 2^unit
-
-    // pass 2: align, truncate toward zero, sum exactly
-    int64_t S = 0;
-    for (uint32_t k = 0; k < L; ++k) {
-        const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
-        const uint64_t prod = (uint64_t)(x.sig * y.sig);                    // <= 22 bits
-        const int sh = (x.exp + y.exp - FA - FB) - unit;                    // <= F
-        const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
-        S += (x.sign ^ y.sign) ? -(int64_t)al : (int64_t)al;
-    }
+    int emax; int64_t S;
+    bool have = fused_part<TA, TB>(p, a, b, 0, 1, L, emax, S);          // S aligned at the products' own maximum
     uint32_t d;
     if (p.c_mode == MMAEMU_C_IN_GROUP) {
+        const bool c_live = !(p.skip_zero_terms && dc.sig == 0);
+        if (!have && !c_live) return 0u;
+        if (c_live && (!have || dc.exp > emax)) {
+            // the accumulator raises the maximum: align the products again at the new exponent
+            const int unit = dc.exp - p.F;
+            S = 0;
+            for (uint32_t k = 0; k < L; ++k) {
+                const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
+                const uint64_t prod = (uint64_t)(x.sig * y.sig);
+                const int sh = (x.exp + y.exp - FA - FB) - unit;
+                const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
+                S += (x.sign ^ y.sign) ? -(int64_t)al : (int64_t)al;
+            }
+            emax = dc.exp;
+        }
+        const int unit = emax - p.F;
         const int sh = (dc.exp - 23) - unit;
         const uint64_t al = sh >= 0 ? ((uint64_t)dc.sig << sh) : (sh > -32 ? ((uint64_t)dc.sig >> (-sh)) : 0ull);
         S += dc.sign ? -(int64_t)al : (int64_t)al;
         const uint32_t neg = S < 0;
         const uint64_t mag = (uint64_t)(neg ? -S : S);
         d = mag ? round_to_fp32(neg, mag, unit, 0, p.out_round) : 0u;
-    } else if (p.c_mode == MMAEMU_C_AFTER_RD) {
-        d = rounded_sum_with_c(p, S, emax, dc, false);
-    } else {
+    } else {                                                            // C_AFTER_EXACT
+        if (!have) { emax = 0; S = 0; }
         const uint32_t neg = S < 0;
-        d = add_exact_round(neg, (uint64_t)(neg ? -S : S), unit, dc.sign, (uint64_t)dc.sig, dc.exp - 23, p.out_round);
+        d = add_exact_round(neg, (uint64_t)(neg ? -S : S), emax - p.F, dc.sign, (uint64_t)dc.sig, dc.exp - 23, p.out_round);
     }
-    if (p.ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
-    return d;
+    return finish_group(p, d);
 }
 
 

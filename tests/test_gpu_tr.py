@@ -24,7 +24,7 @@ def test_tr_gtr_random_parameters(mm, ta, tb):
         L = int(rng.choice([2, 4, 8, 16, 32, 0]))
         k = int(rng.choice([8, 16, 64])) if L == 0 else L * int(rng.integers(1, 5))
         F = int(rng.choice([0, 5, 13, 23, 24, 25, 31, 40]))
-        F2 = int(rng.choice([0, 24, 31, 31, 31, 36, 44]))
+        F2 = min(int(rng.choice([0, 24, 31, 31, 31, 36, 44])), F + 40)      # limit of the C form of the oracle
         p = ModelParams(group_len=L, frac_bits=F, frac_bits2=F2, c_mode=mode, out_round=int(rng.integers(0, 2)),
                         ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)),
                         nan_bits=0x7FFFFFFF if trial % 3 == 0 else 0x7FC00000)
@@ -108,3 +108,49 @@ def test_rd_mode_limits_are_errors(mm):
         mm.emulate_mma(h, z, z, z, z, 1, 1, 16, 1, (mm.FP16, mm.FP16, mm.FP32, mm.FP32))
     assert ei.value.status == 2          # MMAEMU_ERR_UNSUPPORTED: 48 + 3 + 4 > 53
     mm.model_destroy(h)
+
+
+# ------------------------------------------------------------------ variations of the RD mode
+from oracle.fdpa import C_IN_GROUP, C_AFTER_EXACT, SPLIT_HALVES
+
+
+@pytest.mark.parametrize("ta,tb", [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, fm.E4M3),
+                                   (fm.E4M3, fm.E4M3), (fm.E5M2, fm.E5M2), (fm.E4M3, fm.BF16)])
+def test_variations_random_parameters(mm, ta, tb):
+    rng = np.random.default_rng(1700 + 8 * ta + tb)
+    for trial in range(20):
+        L = int(rng.choice([2, 4, 8, 16, 32, 0]))
+        k = int(rng.choice([8, 16, 64])) if L == 0 else L * int(rng.integers(1, 4))
+        F = int(rng.choice([0, 5, 13, 24, 25, 40]))
+        p = ModelParams(group_len=L, frac_bits=F, frac_bits2=int(rng.choice([max(F - 3, 0), 24, 31, 36, min(F + 40, 44)])),
+                        c_mode=int(rng.choice([C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD, C_AFTER_RD])),
+                        out_round=int(rng.integers(0, 2)), ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)),
+                        skip_zero_terms=bool(rng.integers(0, 2)), zero_result_positive=bool(rng.integers(0, 2)))
+        if p.c_mode == C_AFTER_RD:
+            split = int(rng.integers(0, 3))
+            p = p.with_(split=split, acc_special_truncation=bool(rng.integers(0, 2)),
+                        frac_bits_merge=int(rng.choice([0, 13, 24, 31])) if split else 0,
+                        frac_bits_acc=int(rng.choice([0, 13, 24, 30])), f2_at_leading_bit=bool(rng.integers(0, 2)))
+            fc = p.frac_bits_acc or p.frac_bits
+            if p.frac_bits2 > fc + 40:
+                p = p.with_(frac_bits2=fc + 40)
+        else:
+            p = p.with_(frac_bits2=0)
+            if p.c_mode == C_AFTER_EXACT and p.frac_bits > 30:
+                p = p.with_(frac_bits=30)
+        nb, m, n = int(rng.integers(1, 4)), int(rng.integers(1, 24)), int(rng.integers(1, 24))
+        A = synth.random_bits(rng, (nb, m, k), ta)
+        B = synth.random_bits(rng, (nb, n, k), tb)
+        A = synth.sprinkle(rng, A, np.array([0, 1 << (A.dtype.itemsize * 8 - 1)], dtype=A.dtype), 0.2)
+        A[0, 0, :] = 0
+        lo, hi = ((90, 165) if trial % 4 < 2 else (1, 254))
+        if ta == fm.BF16 and tb == fm.BF16 and trial % 4 < 2:
+            B = synth.narrow_exponent_bits(rng, (nb, n, k), tb, 100, 150)
+        C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, lo, hi)
+        C[0, 0, 0] = 0
+        if trial % 5 == 0:
+            B = synth.sprinkle(rng, B, synth.SPECIAL_CODES[tb], 0.02)
+            C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32], 0.05)
+        want, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
+        got = gpu_emulate(mm, p, A, B, C, ta, tb)
+        assert_same(got, want, "%s %s" % (p, gpu_emulate.last_kernel))

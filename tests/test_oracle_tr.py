@@ -208,7 +208,7 @@ def test_o2_equals_rational_oracle_tr_gtr(ta, tb):
         L = int(rng.choice([2, 4, 8, 16, 0]))
         k = int(rng.choice([8, 16, 32])) if L == 0 else L * int(rng.integers(1, 4))
         F = int(rng.choice([0, 3, 13, 23, 24, 25, 31, 40]))
-        F2 = int(rng.choice([0, 24, 31, 31, 31, 36, 48]))
+        F2 = min(int(rng.choice([0, 24, 31, 31, 31, 36, 48])), F + 40)     # the C form's stated limit
         p = ModelParams(group_len=L, frac_bits=F, frac_bits2=F2, c_mode=mode, out_round=int(rng.integers(0, 2)),
                         ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)),
                         nan_bits=0x7FFFFFFF if trial % 3 == 0 else 0x7FC00000)
@@ -252,3 +252,135 @@ def test_o2_rejects_odd_group_for_gtr():
         o2lib.emulate_mma(p, A, A, np.zeros((1, 1, 1), dtype=np.uint32), fm.FP16, fm.FP16)
     with pytest.raises(ValueError):
         emulate_mma(p, A, A, np.zeros((1, 1, 1), dtype=np.uint32), fm.FP16, fm.FP16)
+
+
+# ------------------------------------------------------------------ variations beyond the paper's two algorithms
+from oracle.fdpa import SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES
+
+
+def test_gtr_by_name_is_tr_with_even_odd_split_and_special_truncation():
+    rng = np.random.default_rng(8)
+    q = GTR.with_(c_mode=C_AFTER_RD, split=SPLIT_EVEN_ODD, acc_special_truncation=True)
+    A = synth.random_bits(rng, (2, 4, 32), fm.E4M3)
+    B = synth.random_bits(rng, (2, 4, 32), fm.E5M2)
+    C = synth.narrow_exponent_bits(rng, (2, 4, 4), fm.FP32, 100, 150)
+    assert np.array_equal(emulate_mma(GTR, A, B, C, fm.E4M3, fm.E5M2), emulate_mma(q, A, B, C, fm.E4M3, fm.E5M2))
+    assert np.array_equal(o2lib.emulate_mma(GTR, A, B, C, fm.E4M3, fm.E5M2)[0], o2lib.emulate_mma(q, A, B, C, fm.E4M3, fm.E5M2)[0])
+
+
+def test_halves_split():
+    # first half: 2^13 * 2^10 (e = 23); second half: -0.25.  Same arithmetic as the even/odd case above, other partition.
+    p = GTR.with_(c_mode=C_AFTER_RD, split=SPLIT_HALVES, acc_special_truncation=True)
+    a = [2.0 ** 13] + [0.0] * 7 + [-0.25] + [0.0] * 7
+    b = [2.0 ** 10] + [0.0] * 7 + [1.0] + [0.0] * 7
+    assert bits_f32(_run(p, a, b, 0.0, L=16)) == 2.0 ** 23 - 0.5
+    # both in the first half: truncated toward zero at the shared maximum
+    assert bits_f32(_run(p, [2.0 ** 13, -0.25], [2.0 ** 10, 1.0], 0.0, L=16)) == 2.0 ** 23
+
+
+def test_separate_precisions():
+    # F = 13 for the products, F_m = F_c = 24: a product 2^-14 below the largest one of its half is dropped ...
+    p = ModelParams(group_len=16, frac_bits=13, frac_bits_merge=24, frac_bits_acc=24, frac_bits2=31, c_mode=C_AFTER_RD, split=SPLIT_HALVES)
+    assert bits_f32(_run(p, [1.0, 2.0 ** -14], [1.0, 1.0], 0.0, L=16)) == 1.0
+    assert bits_f32(_run(p, [1.0, 2.0 ** -13], [1.0, 1.0], 0.0, L=16)) == 1.0 + 2.0 ** -13
+    # ... but in the other half it is aligned at its own exponent and survives the merge at 24 bits
+    a = [1.0] + [0.0] * 7 + [2.0 ** -14] + [0.0] * 7
+    assert bits_f32(_run(p, a, [1.0] * 16, 0.0, L=16)) == 1.0 + 2.0 ** -14
+    # the accumulator keeps 24 bits: 1 + 2^-23 survives next to a product of 1
+    assert bits_f32(_run(p, [1.0], [1.0], 2.0 ** -23, L=16)) == 1.0 + 2.0 ** -23
+    # with F_c = F = 13 it does not
+    assert bits_f32(_run(p.with_(frac_bits_acc=0), [1.0], [1.0], 2.0 ** -23, L=16)) == 1.0
+
+
+def test_skip_zero_terms():
+    # 0 * 2^15 carries the exponent (1 - 15) + 15 = 1 into e_max in the literal reading; the live product
+    # (1 + 2^-10)^2 2^-8 = 2^-8 + 2^-17 + 2^-28 then loses its last bit below the unit 2^(1-24)
+    a, b = [0.0, 1.0 + 2.0 ** -10], [2.0 ** 15, 2.0 ** -8 * (1.0 + 2.0 ** -10)]
+    exact = (1 + 2.0 ** -10) ** 2 * 2.0 ** -8
+    assert bits_f32(_run(TR, a, b, 0.0)) == 2.0 ** -8 + 2.0 ** -17
+    assert bits_f32(_run(TR.with_(skip_zero_terms=True), a, b, 0.0)) == exact          # 21 significant bits: a binary32 number
+    # all products zero: the accumulator passes through, also a negative tiny one (no round-down at a foreign exponent)
+    for c in (-2.0 ** -140, 2.0 ** -140, -1.5, 0.0):
+        assert _run(TR.with_(skip_zero_terms=True), [0.0], [3.0], c) == f32_bits(c)
+    assert _run(TR, [0.0], [3.0], -2.0 ** -140) == f32_bits(-2.0 ** -37)               # literal: e_max = -14 + 1, RD_24 of c is -2^(-13-24)
+    # a zero accumulator does not set E either.  Products 2^-150 + 2^-151 with F2 = 24: the literal reading rounds the
+    # sum down at E = -126 to a multiple of 2^-150, a tie of the subnormal grid that goes to 0; skipped, E = e_max
+    # keeps 1.5 * 2^-150, which rounds up to 2^-149
+    p = ModelParams(group_len=2, frac_bits=24, frac_bits2=24, c_mode=C_AFTER_RD)
+    a2, b2 = [bf16_bits(2.0 ** -75)] * 2, [bf16_bits(2.0 ** -75), bf16_bits(2.0 ** -76)]
+    assert fdpa_group(p, a2, b2, 0, fm.BF16, fm.BF16) == 0
+    assert fdpa_group(p.with_(skip_zero_terms=True), a2, b2, 0, fm.BF16, fm.BF16) == 1
+    # exact zero stays +0.0 in every mode
+    for mode in (C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD):
+        q = ModelParams(group_len=2, frac_bits=24, frac_bits2=31, c_mode=mode, skip_zero_terms=True)
+        assert fdpa_group(q, [0, 0x8000], [0x3C00, 0x3C00], 0x80000000, fm.FP16, fm.FP16) == 0
+
+
+def test_f2_below_the_leading_bit():
+    # c = 2^30 (2 - 2^-23); products 128, 128 and 0.5 (e_max = 7): in units of 2^30, T = 2^-22 + 2^-31 and
+    # S = 2 + 2^-23 + 2^-31.  S has its leading bit one place above 2^E.  Binary32 spacing there is 2^-22, so
+    # 2 + 2^-23 is a tie.  Counted below 2^E the 2^-31 bit is kept: above the tie, rounds up.  Counted below the
+    # leading bit the unit is 2^-30: the bit is dropped and the tie goes to the even neighbour 2.
+    c = bits_f32(0x4EFFFFFF)
+    assert _run(TR, [128.0, 128.0, 0.5], [1.0, 1.0, 1.0], c) == 0x4F000001
+    assert _run(TR.with_(f2_at_leading_bit=True), [128.0, 128.0, 0.5], [1.0, 1.0, 1.0], c) == 0x4F000000
+    # one place of cancellation keeps one bit more: c = -2^30, products 2^29 - 2^6 ... : S = -(1/2 + 2^-24 ...)
+    # c = -2^30 (1 + 2^-23)... simpler: c = 2^30, products -(2^29) and -(2^-2 + 2^-3): in units of 2^30,
+    # S = 1/2 - 2^-32 - 2^-33.  Below 2^E: RD_31 of T = -(1/2 + 2^-32 + 2^-33) gives -(1/2 + 2^-31), S = 1/2 - 2^-31.
+    # Below the leading bit (2^-2 after the borrow... S < 1/2, leading bit 2^-2): unit 2^-33, S is kept exactly.
+    # Both are below 1/2 by far less than half a binary32 place (2^-26): the two anchors agree on 0x4DFFFFFF? No:
+    # 1/2 - 2^-31 and 1/2 - 2^-32 - 2^-33 both round to 1/2 (spacing below 1/2 is 2^-25).  Agreement is the point:
+    d0 = _run(TR, [-(2.0 ** 15), -0.25, -0.125], [2.0 ** 14, 1.0, 1.0], 2.0 ** 30)
+    d1 = _run(TR.with_(f2_at_leading_bit=True), [-(2.0 ** 15), -0.25, -0.125], [2.0 ** 14, 1.0, 1.0], 2.0 ** 30)
+    assert d0 == d1 == f32_bits(2.0 ** 29)
+
+
+def test_zero_result_positive():
+    p = ModelParams(group_len=1, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD)
+    a, b = [bf16_bits(-(2.0 ** -80))], [bf16_bits(2.0 ** -80)]
+    assert fdpa_group(p, a, b, 0, fm.BF16, fm.BF16) == 0x80000000
+    assert fdpa_group(p.with_(zero_result_positive=True), a, b, 0, fm.BF16, fm.BF16) == 0
+    q = ModelParams(group_len=1, frac_bits=24, ftz_out=True, zero_result_positive=True)
+    assert fdpa_group(q, [bf16_bits(-(2.0 ** -70))], [bf16_bits(2.0 ** -70)], 0, fm.BF16, fm.BF16) == 0
+
+
+@pytest.mark.parametrize("ta,tb", [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, fm.E4M3), (fm.E4M3, fm.BF16)])
+def test_o2_equals_rational_oracle_variations(ta, tb):
+    rng = np.random.default_rng(700 + 8 * ta + tb)
+    for trial in range(24):
+        L = int(rng.choice([2, 4, 8, 16, 0]))
+        k = int(rng.choice([8, 16, 32])) if L == 0 else L * int(rng.integers(1, 3))
+        F = int(rng.choice([0, 5, 13, 24, 25, 40]))
+        p = ModelParams(group_len=L, frac_bits=F, frac_bits2=int(rng.choice([max(F - 3, 0), 24, 31, 36, min(F + 40, 48)])),
+                        c_mode=int(rng.choice([C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD, C_AFTER_RD])),
+                        out_round=int(rng.integers(0, 2)), ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)),
+                        skip_zero_terms=bool(rng.integers(0, 2)), zero_result_positive=bool(rng.integers(0, 2)))
+        if p.c_mode == C_AFTER_RD:
+            p = p.with_(split=int(rng.integers(0, 3)), acc_special_truncation=bool(rng.integers(0, 2)),
+                        frac_bits_merge=int(rng.choice([0, 13, 24, 31])), frac_bits_acc=int(rng.choice([0, 13, 24, 30])),
+                        f2_at_leading_bit=bool(rng.integers(0, 2)))
+            fc = p.frac_bits_acc or p.frac_bits
+            if p.frac_bits2 > fc + 40:
+                p = p.with_(frac_bits2=fc + 40)
+        else:
+            p = p.with_(frac_bits2=0)
+            if p.c_mode == C_AFTER_EXACT and p.frac_bits > 32:
+                p = p.with_(frac_bits=32)
+        nb, m, n = 2, 3, 4
+        A = synth.random_bits(rng, (nb, m, k), ta)
+        B = synth.random_bits(rng, (nb, n, k), tb)
+        # plenty of zeros so that skip_zero_terms matters, whole zero rows included
+        A = synth.sprinkle(rng, A, np.array([0, 1 << (A.dtype.itemsize * 8 - 1)], dtype=A.dtype), 0.2)
+        A[0, 0, :] = 0
+        lo, hi = ((90, 165) if trial % 4 < 2 else (1, 254))
+        if ta == fm.BF16 and tb == fm.BF16 and trial % 4 < 2:
+            B = synth.narrow_exponent_bits(rng, (nb, n, k), tb, 100, 150)
+        C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, lo, hi)
+        C[0, 0, 0] = 0
+        C[0, 0, 1] = 0x80000000
+        if trial % 5 == 0:
+            B = synth.sprinkle(rng, B, synth.SPECIAL_CODES[tb], 0.02)
+            C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32], 0.05)
+        want = emulate_mma(p, A, B, C, ta, tb)
+        got, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
+        assert np.array_equal(got, want), (p, np.argwhere(got != want)[:3])
