@@ -230,3 +230,55 @@ def config5(n_tiles=1 << 24, chunk=1 << 16, seed=0, dev="cuda", kinds=("bf16", "
         out[kind] = dict(terms=len(CONFIG5_MODELS) * n_tiles * m * n * k, seconds=secs, kernels=kernels, stats=res,
                          agreement=[1.0 - s["n_mismatch_bits"] / max(s["n_compared"], 1) for s in res], dev=kept)
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Randomised validation of a candidate model against the native instruction (paper Sec. 3, Step 4).
+
+def validation_families(ta, tb):
+    """Input families of Step 4: common distributions, all finite bit patterns, all bit patterns (NaN and infinities
+    included: the paper calls this one the most important), and exponent ranges chosen to put the accumulator above,
+    below and anywhere relative to the products.  Each entry: (name, generator arguments for A, for B, for C)."""
+    full = {mm.FP16: (1, 30), mm.BF16: (1, 254), mm.E4M3: (0, 15), mm.E5M2: (0, 30)}
+    mid = {mm.FP16: (11, 19), mm.BF16: (120, 134), mm.E4M3: (3, 11), mm.E5M2: (11, 19)}
+
+    def ue(rng, zero=True):
+        return dict(family=mm.GEN_UNIFORM_EXP, exp_lo=rng[0], exp_hi=rng[1], exp_zero=zero)
+
+    simple = [("normal", mm.GEN_NORMAL), ("finite_bits", mm.GEN_FINITE_BITS), ("random_bits", mm.GEN_RANDOM_BITS)]
+    fams = [(name, dict(family=f), dict(family=f), dict(family=f)) for name, f in simple]
+    fams.append(("mid_exp_c_above", ue(mid[ta]), ue(mid[tb]), ue((125, 145), zero=False)))
+    fams.append(("mid_exp_c_below", ue(mid[ta]), ue(mid[tb]), ue((80, 129))))
+    fams.append(("wide_exp_c_any", ue(full[ta]), ue(full[tb]), ue((1, 254))))
+    return fams
+
+
+def validate_against_mfma(instr, model_kwargs, n_tiles=4096, seeds=(0,), dev="cuda"):
+    """Runs the native instruction `instr` (one issue per tile, k = the instruction's K) and the model on the same
+    generated tiles and compares bit for bit.  Returns {family: stats dict} plus "seconds" and "terms"."""
+    info = mm.mfma_info(instr)
+    m, n, k, ta, tb = info["m"], info["n"], info["k"], info["a"], info["b"]
+    A, B = _buf((n_tiles, m, k), ta, dev), _buf((n_tiles, n, k), tb, dev)
+    C, Dhw, D = (_buf((n_tiles, m, n), mm.FP32, dev) for _ in range(3))
+    h = mm.model_create(**model_kwargs)
+    fams = validation_families(ta, tb)
+    stats = {name: _stats_buf(dev) for name, _, _, _ in fams}
+
+    def run():
+        for name, ga, gb, gc in fams:
+            for seed in seeds:
+                mm.generate(A, ta, m * k, 0, n_tiles, seed=seed, operand=0, **ga)
+                mm.generate(B, tb, n * k, 0, n_tiles, seed=seed, operand=1, **gb)
+                mm.generate(C, mm.FP32, m * n, 0, n_tiles, seed=seed, operand=2, **gc)
+                mm.mfma_probe(instr, A, B, C, Dhw, k, n_tiles)
+                mm.emulate_mma(h, A, B, C, D, m, n, k, n_tiles, (ta, tb, mm.FP32, mm.FP32))
+                mm.compare(D, Dhw, n_tiles * m * n, stats[name])
+
+    _, secs = _timed(run)
+    kernel = mm.last_kernel()
+    mm.model_destroy(h)
+    out = {name: mm.read_stats(st) for name, st in stats.items()}
+    out["seconds"] = secs
+    out["terms"] = len(fams) * len(seeds) * n_tiles * m * n * k
+    out["kernel"] = kernel
+    return out

@@ -1,0 +1,38 @@
+"""The parameter sets in presets.GFX950_MFMA against the native v_mfma_f32_* instructions of the GPU the tests run
+on: bit-for-bit agreement on every validation family (paper Sec. 3, Step 4: randomised validation of a model against
+the MMA interface; Eq. 2).  This is not a parity test of the library (those compare with the CPU oracle): it checks a
+*model* against silicon, and it ties the oracle-checked emulation to something outside this repository."""
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2511_10909_amd import binding, configs, presets
+    return binding, configs, presets
+
+
+@pytest.mark.parametrize("instr", range(10))
+def test_gfx950_preset_reproduces_the_instruction(env, instr):
+    mm, configs, presets = env
+    res = configs.validate_against_mfma(instr, presets.GFX950_MFMA[instr], n_tiles=1024, seeds=(0, 1))
+    for fam, st in res.items():
+        if not isinstance(st, dict):
+            continue
+        assert st["n_compared"] > 0
+        assert st["n_mismatch_bits"] == 0, (instr, fam, st["n_mismatch_bits"], st["first_mismatch_index"])
+
+
+def test_paper_cdna3_models_differ_from_gfx950(env):
+    # the published CDNA3 parameter sets are close to, but not the same as, what gfx950 computes
+    mm, configs, presets = env
+    res = configs.validate_against_mfma(mm.MFMA_F32_16X16X32_FP8_FP8, dict(presets.PAPER[("cdna3", "fp8")], nan_bits=0xFFC00000),
+                                        n_tiles=512)
+    assert res["normal"]["n_mismatch_bits"] > 0
+    res = configs.validate_against_mfma(mm.MFMA_F32_32X32X8_F16, dict(presets.PAPER[("cdna3", "fp16")], nan_bits=0xFFC00000),
+                                        n_tiles=512)
+    assert res["normal"]["n_mismatch_bits"] == 0            # indistinguishable on common distributions ...
+    assert res["wide_exp_c_any"]["n_mismatch_bits"] > 0     # ... but not once zero operands carry large exponents
