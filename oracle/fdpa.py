@@ -47,7 +47,9 @@ algorithms):
   * skip_zero_terms: terms whose significand is zero take no part in any exponent maximum;
   * f2_at_leading_bit: the sum T 2^(e_max - E) + s_c' is formed exactly and then rounded down to
     F2 fractional bits counted below its own leading bit (not below 2^E);
-  * zero_result_positive: a result that rounds (or is flushed) to zero is +0.0.
+  * zero_result_positive: a result that rounds (or is flushed) to zero is +0.0;
+  * sum_drop_distance (n > 0): the counterpart of the special truncation for the product sum: T' = 0 when
+    E - e_max >= n.
 """
 from dataclasses import dataclass, replace
 from fractions import Fraction
@@ -82,6 +84,7 @@ class ModelParams:
     skip_zero_terms: bool = False
     f2_at_leading_bit: bool = False
     zero_result_positive: bool = False
+    sum_drop_distance: int = 0
 
     def with_(self, **kw):
         return replace(self, **kw)
@@ -221,6 +224,8 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb):
         sc_al = _rd_frac(dc.signed_sig * Fraction(2) ** (dc.exp - E), F_c)
         if p.acc_special_truncation and dc.exp < E - F_c - 1:
             sc_al = Fraction(0)                                   # special truncation
+        if p.sum_drop_distance and E - e_max >= p.sum_drop_distance:
+            T = Fraction(0)                                       # the product sum lies too far below the accumulator
         if p.f2_at_leading_bit:
             S = T * Fraction(2) ** (e_max - E) + sc_al
             if S != 0:

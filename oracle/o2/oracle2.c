@@ -41,6 +41,7 @@ enum { R_RNE = 0, R_RZ = 1 };
 typedef struct {
     uint32_t group_len, frac_bits, align_round, c_mode, out_round, ftz_in, ftz_out, nan_bits, frac_bits2;
     uint32_t split, acc_special_truncation, frac_bits_merge, frac_bits_acc, skip_zero_terms, f2_at_leading_bit, zero_result_positive;
+    uint32_t sum_drop_distance;
 } o2_params;
 
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
@@ -215,6 +216,7 @@ static uint32_t rounded_sum_with_c(const o2_params *p, int have_T, i128 T, int e
     i128 sc2 = align_rd(sc, dc.exp - 23, E - Fc);
     if (special_truncation && dc.exp < E - Fc - 1) sc2 = 0;
     const int unit_c = E - Fc;
+    if (have_T && p->sum_drop_distance && E - emax >= (int)p->sum_drop_distance) have_T = 0;   /* T' = 0 */
     if (!have_T) { T = 0; unit_T = unit_c; }
     i128 S; int unit;
     if (p->f2_at_leading_bit) {

@@ -250,6 +250,12 @@ def validation_families(ta, tb):
     fams.append(("mid_exp_c_above", ue(mid[ta]), ue(mid[tb]), ue((125, 145), zero=False)))
     fams.append(("mid_exp_c_below", ue(mid[ta]), ue(mid[tb]), ue((80, 129))))
     fams.append(("wide_exp_c_any", ue(full[ta]), ue(full[tb]), ue((1, 254))))
+    # every product at one exponent, the accumulator 20 to 32 binary places above it (where whole sums drop out)
+    bias = {mm.FP16: 15, mm.BF16: 127, mm.E4M3: 7, mm.E5M2: 15}
+    one = {mm.FP16: 16, mm.BF16: 128, mm.E4M3: 8, mm.E5M2: 16}
+    e_prod = (one[ta] - bias[ta]) + (one[tb] - bias[tb])
+    fams.append(("one_exp_c_far_above", ue((one[ta], one[ta]), zero=False), ue((one[tb], one[tb]), zero=False),
+                 ue((127 + e_prod + 20, 127 + e_prod + 32), zero=False)))
     return fams
 
 

@@ -106,9 +106,10 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         return MMAEMU_ERR_INVALID_ARG;
     }
     if (p->c_mode != MMAEMU_C_AFTER_RD &&
-        (p->split || p->acc_special_truncation || p->frac_bits_merge || p->frac_bits_acc || p->f2_at_leading_bit)) {
-        set_error("model_create: split, acc_special_truncation, frac_bits_merge, frac_bits_acc and f2_at_leading_bit "
-                  "belong to c_mode C_AFTER_RD");
+        (p->split || p->acc_special_truncation || p->frac_bits_merge || p->frac_bits_acc || p->f2_at_leading_bit ||
+         p->sum_drop_distance)) {
+        set_error("model_create: split, acc_special_truncation, frac_bits_merge, frac_bits_acc, f2_at_leading_bit and "
+                  "sum_drop_distance belong to c_mode C_AFTER_RD");
         return MMAEMU_ERR_UNSUPPORTED;
     }
     if (p->frac_bits_merge && p->split == MMAEMU_SPLIT_NONE) {
@@ -198,6 +199,7 @@ mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const
     ma.f2_at_leading_bit = mp.f2_at_leading_bit;
     ma.skip_zero_terms = mp.skip_zero_terms;
     ma.zero_result_positive = mp.zero_result_positive;
+    ma.sum_drop_distance = (int32_t)(mp.sum_drop_distance > 100000u ? 100000u : mp.sum_drop_distance);
     ma.out_round = mp.out_round;
     ma.ftz_in = mp.ftz_in;
     ma.ftz_out = mp.ftz_out;

@@ -36,6 +36,7 @@ struct ModelArgs {
     uint32_t split, acc_special_truncation;
     int32_t Fm, Fc;      // merge and accumulator precisions, already defaulted to F
     uint32_t f2_at_leading_bit, skip_zero_terms, zero_result_positive;
+    int32_t sum_drop_distance;
 };
 
 // error plumbing (api.hip)

@@ -98,7 +98,8 @@ __device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, 
 
 // Algorithm "TR-FDPA", steps 3 and 4 (Algorithm "GTR-FDPA", steps 4 and 5) and their variations:
 // T counts units of 2^unit_T.  E = max(e_max, e_c) over the terms that take part; s_c' = RD_Fc(c at E),
-// dropped by the special truncation when e_c < E - F_c - 1; then either RD_F2(T at E) + s_c', or the
+// dropped by the special truncation when e_c < E - F_c - 1 (and T' = 0 when E - e_max >= sum_drop_distance);
+// then either RD_F2(T at E) + s_c', or the
 // exact T + s_c' rounded down to F2 bits below its own leading bit; d = rho of that.
 __device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, bool have_T, int64_t T64, int emax, int unit_T,
                                                        const Dec &dc)
@@ -110,6 +111,7 @@ __device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, bool 
     i128 sc2 = align_rd(sc, dc.exp - 23, E - p.Fc);
     if (p.acc_special_truncation && dc.exp < E - p.Fc - 1) sc2 = 0;
     const int unit_c = E - p.Fc;
+    if (have_T && p.sum_drop_distance && E - emax >= p.sum_drop_distance) have_T = false;      // T' = 0
     i128 T = have_T ? (i128)T64 : (i128)0;
     if (!have_T) unit_T = unit_c;
     i128 S;

@@ -130,7 +130,8 @@ def test_variations_random_parameters(mm, ta, tb):
             split = int(rng.integers(0, 3))
             p = p.with_(split=split, acc_special_truncation=bool(rng.integers(0, 2)),
                         frac_bits_merge=int(rng.choice([0, 13, 24, 31])) if split else 0,
-                        frac_bits_acc=int(rng.choice([0, 13, 24, 30])), f2_at_leading_bit=bool(rng.integers(0, 2)))
+                        frac_bits_acc=int(rng.choice([0, 13, 24, 30])), f2_at_leading_bit=bool(rng.integers(0, 2)),
+                        sum_drop_distance=int(rng.choice([0, 0, 5, 20, 28])))
             fc = p.frac_bits_acc or p.frac_bits
             if p.frac_bits2 > fc + 40:
                 p = p.with_(frac_bits2=fc + 40)

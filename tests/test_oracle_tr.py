@@ -358,7 +358,8 @@ def test_o2_equals_rational_oracle_variations(ta, tb):
         if p.c_mode == C_AFTER_RD:
             p = p.with_(split=int(rng.integers(0, 3)), acc_special_truncation=bool(rng.integers(0, 2)),
                         frac_bits_merge=int(rng.choice([0, 13, 24, 31])), frac_bits_acc=int(rng.choice([0, 13, 24, 30])),
-                        f2_at_leading_bit=bool(rng.integers(0, 2)))
+                        f2_at_leading_bit=bool(rng.integers(0, 2)),
+                        sum_drop_distance=int(rng.choice([0, 0, 5, 20, 28])))
             fc = p.frac_bits_acc or p.frac_bits
             if p.frac_bits2 > fc + 40:
                 p = p.with_(frac_bits2=fc + 40)
@@ -384,3 +385,14 @@ def test_o2_equals_rational_oracle_variations(ta, tb):
         want = emulate_mma(p, A, B, C, ta, tb)
         got, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
         assert np.array_equal(got, want), (p, np.argwhere(got != want)[:3])
+
+
+def test_sum_drop_distance():
+    # eight products of 1.5 * 1.5 (e_max = 0, T = 18) next to c = 2^28: in units of binary32 places of c (2^5) T is
+    # 0.5625 places and rounds c up by one; with the drop at distance 28 the sum is ignored altogether
+    p = TR.with_(sum_drop_distance=28)
+    a = [1.5] * 8
+    assert _run(TR, a, a, 2.0 ** 28) == f32_bits(2.0 ** 28) + 1
+    assert _run(p, a, a, 2.0 ** 28) == f32_bits(2.0 ** 28)
+    assert _run(p, a, a, 2.0 ** 27) == f32_bits(2.0 ** 27 + 16)       # distance 27: kept (18 = 1.125 places of 16)
+    assert _run(p, a, a, -(2.0 ** 28)) == f32_bits(-(2.0 ** 28))
