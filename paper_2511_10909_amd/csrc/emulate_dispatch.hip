@@ -8,9 +8,9 @@ template <int VM>
 static mmaemu_status launch_vm(const TiledArgs &t, const void *A, const void *B, const void *Cm, void *D, uint32_t m, uint32_t n,
                                uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
 {
-    return t.p.c_mode == MMAEMU_C_IN_GROUP
-               ? launch_tiled_shape<MMAEMU_C_IN_GROUP, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled)
-               : launch_tiled_shape<MMAEMU_C_AFTER_EXACT, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (t.p.c_mode == MMAEMU_C_IN_GROUP) return launch_tiled_shape<MMAEMU_C_IN_GROUP, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (t.p.c_mode == MMAEMU_C_AFTER_EXACT) return launch_tiled_shape<MMAEMU_C_AFTER_EXACT, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    return launch_tiled_shape<MMAEMU_C_AFTER_RD, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
 }
 
 mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *Cm, void *D,
@@ -20,14 +20,16 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // the tiled kernels need 8-byte aligned operand arrays (four consecutive k elements are
     // loaded at once) and group sums below 2^52
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) == 0;
-    const bool tiled_mode = (p.c_mode == MMAEMU_C_IN_GROUP || p.c_mode == MMAEMU_C_AFTER_EXACT) && !p.skip_zero_terms &&
-                            !p.zero_result_positive;
+    // the RD mode without a split runs tiled with all of its variations; the two other modes only as the paper has them
+    const bool tiled_mode = p.c_mode == MMAEMU_C_AFTER_RD ? p.split == MMAEMU_SPLIT_NONE
+                                                          : (!p.skip_zero_terms && !p.zero_result_positive);
     if (tiled_mode && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;
         t.ta = ta;
         t.tb = tb;
-        t.ebase = 2 - fmt_info(ta).bias - fmt_info(tb).bias;
+        t.ebase = 2 - fmt_info(ta).bias - fmt_info(tb).bias -
+                  ((p.c_mode == MMAEMU_C_AFTER_RD && p.skip_zero_terms) ? 2 * (int)ZBIAS : 0);
         bool handled = false;
         mmaemu_status st;
         if (p.F >= 30) st = launch_vm<2>(t, A, B, Cm, D, m, n, k, batch, s, handled);             // wide F: binary64 terms

@@ -65,13 +65,20 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 // One element -> exact binary32 value (every supported operand value is a binary32 number)
 // and e' = max(E, 1) - 1, or the sentinel tag for NaN / infinities.  `wild` is raised by a
 // finite non-zero value outside [2^-31, 2^32), whose products may leave binary32 (BF16 only).
+// `zbias` (0, or ZBIAS when terms with a zero significand must not take part in exponent maxima):
+// a non-zero element's e' is raised by zbias and a zero element's e' is 0, so that a product with
+// a zero factor has an exponent sum below 2 * ZBIAS and every other product one at or above it.
+constexpr uint32_t ZBIAS = 0x100u;
+
 template <int T>
-__device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, float &val, uint32_t &ex, bool &wild)
+__device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, uint32_t zbias, float &val, uint32_t &ex, bool &wild)
 {
     using F = Fmt<T>;
     constexpr uint32_t EMASK = (1u << F::EB) - 1u, MMASK = (1u << F::MB) - 1u;
     const uint32_t E = (bits >> F::MB) & EMASK;
-    ex = (E ? E : 1u) - 1u;
+    const bool is_zero = (bits & ((1u << (F::EB + F::MB)) - 1u)) == 0 || (ftz_in && E == 0);
+    ex = (E ? E : 1u) - 1u + zbias;
+    if (zbias && is_zero) ex = 0;
     if (T == MMAEMU_BF16) {
         // the value is the pattern moved to the top half of a binary32 word
         const bool flushed = ftz_in && E == 0;                  // FlushSubnormal: -> +0.0
@@ -90,7 +97,7 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, floa
         const bool special = F::IEEE ? (E == EMASK) : (E == EMASK && M == MMASK);
         if (ftz_in && E == 0) { M = 0; sign = 0; }
         const uint32_t sig = E ? (M | (1u << F::MB)) : M;
-        const float mag = ldexpf((float)sig, (int)ex + 1 - F::BIAS - F::MB);   // exact
+        const float mag = ldexpf((float)sig, (int)(E ? E : 1u) - F::BIAS - F::MB);   // exact
         val = __uint_as_float(__float_as_uint(mag) | (sign << 31));
         if (special) { ex = SENTINEL; val = 0.0f; }
     }
@@ -98,7 +105,7 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, floa
 
 // four consecutive k elements of one row: raw little-endian bytes in `raw`
 template <int T>
-__device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float (&f)[4], uint2 &e, bool &wild)
+__device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, uint32_t zbias, float (&f)[4], uint2 &e, bool &wild)
 {
     uint32_t b[4];
     if (Fmt<T>::W == 8) {
@@ -108,7 +115,7 @@ __device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, float (&f)[4
     }
     uint32_t x[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, f[q], x[q], wild);
+    for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, zbias, f[q], x[q], wild);
     e = make_uint2(x[0] | (x[1] << 16), x[2] | (x[3] << 16));
 }
 
@@ -168,22 +175,23 @@ __device__ __forceinline__ void load_panel(uint32_t esize, const StagePlan<NQ> &
 
 // raw registers -> decoded registers; returns whether any element needs binary64 products
 template <int T, int NQ>
-__device__ __forceinline__ bool decode_panel(const uint2 (&raw)[NQ], uint32_t ftz_in, float (&f)[NQ][4], uint2 (&e)[NQ])
+__device__ __forceinline__ bool decode_panel(const uint2 (&raw)[NQ], uint32_t ftz_in, uint32_t zbias, float (&f)[NQ][4], uint2 (&e)[NQ])
 {
     bool wild = false;
 #pragma unroll
-    for (int i = 0; i < NQ; ++i) decode4<T>(raw[i], ftz_in, f[i], e[i], wild);
+    for (int i = 0; i < NQ; ++i) decode4<T>(raw[i], ftz_in, zbias, f[i], e[i], wild);
     return wild;
 }
 
 template <int NQ>
-__device__ __forceinline__ bool decode_any(uint32_t t, const uint2 (&raw)[NQ], uint32_t ftz_in, float (&f)[NQ][4], uint2 (&e)[NQ])
+__device__ __forceinline__ bool decode_any(uint32_t t, const uint2 (&raw)[NQ], uint32_t ftz_in, uint32_t zbias, float (&f)[NQ][4],
+                                           uint2 (&e)[NQ])
 {
     switch (t) {   // uniform
-    case MMAEMU_FP8_E4M3: return decode_panel<MMAEMU_FP8_E4M3, NQ>(raw, ftz_in, f, e);
-    case MMAEMU_FP8_E5M2: return decode_panel<MMAEMU_FP8_E5M2, NQ>(raw, ftz_in, f, e);
-    case MMAEMU_FP16: return decode_panel<MMAEMU_FP16, NQ>(raw, ftz_in, f, e);
-    default: return decode_panel<MMAEMU_BF16, NQ>(raw, ftz_in, f, e);
+    case MMAEMU_FP8_E4M3: return decode_panel<MMAEMU_FP8_E4M3, NQ>(raw, ftz_in, zbias, f, e);
+    case MMAEMU_FP8_E5M2: return decode_panel<MMAEMU_FP8_E5M2, NQ>(raw, ftz_in, zbias, f, e);
+    case MMAEMU_FP16: return decode_panel<MMAEMU_FP16, NQ>(raw, ftz_in, zbias, f, e);
+    default: return decode_panel<MMAEMU_BF16, NQ>(raw, ftz_in, zbias, f, e);
     }
 }
 
@@ -404,10 +412,15 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 
     // end of pass 1 for one element: e_max (products, and the accumulator when it is a term)
     auto exponents = [&](int r, int c, int &emax, uint32_t &tagged) {
-        const uint32_t e = m2[r][c];
-        tagged |= e;
+        uint32_t e = m2[r][c];
         const uint32_t lo = e & 0xFFFFu, hi = e >> 16;
         int em = (int)(lo > hi ? lo : hi) + ta_.ebase;
+        if (CMODE == MMAEMU_C_AFTER_RD && VM != 0 && em >= 126 && !(e & SENTINEL_MASK)) {
+            // a product may reach 2^128, which this mode counts as an infinity: leave the group to the integer routine
+            e |= 0x8000u;
+            m2[r][c] = e;
+        }
+        tagged |= e;
         if (CMODE == MMAEMU_C_IN_GROUP) {
             const uint32_t Ec = (d[r][c] >> 23) & 0xFFu;               // (a flushed subnormal keeps Exp = -126)
             const int ec = (int)(Ec ? Ec : 1u) - 127;
@@ -447,6 +460,48 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                     const double tc = __builtin_trunc(ldexp((double)__uint_as_float(d[r][c]), -unit));
                     v[r][c] = ldexp(T + tc, unit);                      // exact: integers below 2^53
                 }
+        } else if (CMODE == MMAEMU_C_AFTER_RD) {
+            // Algorithm "TR-FDPA", steps 3 and 4, and its variations, in binary64 (every quantity below is an
+            // integer of fewer than 53 bits times a power of two, hence exact, except where noted)
+            const int Fmax = p.F2 > p.Fc ? p.F2 : p.Fc;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];   // units of 2^(e_max - F)
+                    const uint32_t mx = m2[r][c], mlo = mx & 0xFFFFu, mhi = mx >> 16;
+                    bool have_T = !p.skip_zero_terms || (mlo > mhi ? mlo : mhi) >= 2 * ZBIAS;
+                    const uint32_t cb = d[r][c];
+                    const uint32_t Ec = (cb >> 23) & 0xFFu;
+                    const int ec = (int)(Ec ? Ec : 1u) - 127;
+                    const bool c_live = !(p.skip_zero_terms && (cb & 0x7FFFFFFFu) == 0);
+                    const int em = emax[r][c];
+                    const int E = (have_T && c_live) ? (ec > em ? ec : em) : (have_T ? em : ec);
+                    if (have_T && p.sum_drop_distance && E - em >= p.sum_drop_distance) have_T = false;
+                    if (!have_T) T = 0.0;
+                    double sc = __builtin_floor(ldexp((double)__uint_as_float(cb), p.Fc - E));   // RD_Fc(c at E), units of 2^(E - Fc)
+                    if (p.acc_special_truncation && ec < E - p.Fc - 1) sc = 0.0;
+                    double val;
+                    if (!p.f2_at_leading_bit) {
+                        const double T2 = __builtin_floor(ldexp(T, (em - F) - (E - p.F2)));      // RD_F2(T at E)
+                        val = ldexp(ldexp(T2, Fmax - p.F2) + ldexp(sc, Fmax - p.Fc), E - Fmax);
+                    } else {
+                        // exact two-term sum as s + err (Knuth's TwoSum); then round down to F2 bits below the
+                        // leading bit of the exact sum.  |err| is below half a last place of s, far under that unit.
+                        const double a = ldexp(T, em - F), b = ldexp(sc, E - p.Fc);
+                        const double sm = a + b, bb = sm - a;
+                        const double err = (a - (sm - bb)) + (b - bb);
+                        const long long sbits = __double_as_longlong(sm);
+                        int lead = (int)((sbits >> 52) & 0x7FF) - 1023;
+                        const bool toward_zero = (err != 0.0) && ((err < 0.0) != (sm < 0.0));
+                        if ((sbits & 0xFFFFFFFFFFFFFll) == 0 && toward_zero) lead -= 1;          // just inside the binade below
+                        const int unit = lead - p.F2;
+                        double q = __builtin_floor(ldexp(sm, -unit));
+                        if (err < 0.0 && ldexp(q, unit) == sm) q -= 1.0;                          // s on the grid, exact sum just below it
+                        val = sm == 0.0 ? 0.0 : ldexp(q, unit);
+                    }
+                    v[r][c] = (have_T || c_live) ? val : 0.0;
+                }
         } else {
             // d = rho(T 2^unit + c) with the two-term sum exact: s = RN(a + c) and its exact
             // error (Knuth's TwoSum); an inexact s is then rounded to odd (truncated toward
@@ -484,7 +539,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int c = 0; c < C; ++c) dn[r][c] = __float_as_uint((float)v[r][c]);
-        if (p.out_round != MMAEMU_ROUND_RNE || p.ftz_out) {
+        if (p.out_round != MMAEMU_ROUND_RNE || p.ftz_out || p.zero_result_positive) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -495,6 +550,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                         if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) o -= 1u;   // rounded away from zero: step back
                     }
                     if (p.ftz_out && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                    if (p.zero_result_positive && (o & 0x7FFFFFFFu) == 0) o = 0u;
                     dn[r][c] = o;
                 }
         }
@@ -531,8 +587,9 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     auto commit = [&](int what) {
         float fa[NQA][4], fb[NQB][4];
         uint2 xa[NQA], xb[NQB];
-        bool wild = decode_any<NQA>(ta_.ta, raw_a, p.ftz_in, fa, xa);
-        wild |= decode_any<NQB>(ta_.tb, raw_b, p.ftz_in, fb, xb);
+        const uint32_t zbias = (CMODE == MMAEMU_C_AFTER_RD && p.skip_zero_terms) ? ZBIAS : 0u;
+        bool wild = decode_any<NQA>(ta_.ta, raw_a, p.ftz_in, zbias, fa, xa);
+        wild |= decode_any<NQB>(ta_.tb, raw_b, p.ftz_in, zbias, fb, xb);
         if (VM == 1) chunk_is_double = __syncthreads_or(wild && (what & 2)) != 0;
         else __syncthreads();
         store_panel<NQA, VS, VSD>(plan_a, fa, xa, Av_raw, Ae, chunk_is_double, what);
@@ -696,5 +753,8 @@ extern template MMAEMU_TILED_SIG(MMAEMU_C_IN_GROUP, 2);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 0);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 1);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 2);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 0);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 1);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 2);
 
 } // namespace mmaemu

@@ -1,0 +1,121 @@
+"""GPU parity of the tiled kernels in the RD accumulation mode (paper Algorithm "TR-FDPA" and the variations that
+`mmaemu.h` documents) against the CPU oracle, bit for bit.  Shapes, operand families and the expectation that the
+tiled route is taken follow tests/test_gpu_tiled.py."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import formats as fm, o2lib
+from oracle.fdpa import ModelParams, C_AFTER_RD
+from oracle.rounding import RNE, RZ
+from paper_2511_10909_amd import synth
+from test_gpu_parity import gpu_emulate, assert_same, mm  # noqa: F401  (fixture)
+from test_gpu_tiled import operands, SHAPES, PAIRS
+
+GFX950_16BIT = ModelParams(group_len=8, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD, skip_zero_terms=True,
+                           f2_at_leading_bit=True, zero_result_positive=True, sum_drop_distance=28, nan_bits=0xFFC00000)
+CDNA3_16BIT = ModelParams(group_len=8, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD)
+
+
+def random_rd_params(rng, k):
+    Ls = [L for L in (4, 8, 16, 32, 0, 64, 24, 2) if (L == 0 or k % L == 0 or L > k)]
+    L = int(rng.choice(Ls))
+    F = int(rng.choice([0, 3, 13, 16, 24, 25, 27, 29, 30, 32, 36, 40]))
+    Fc = int(rng.choice([0, 0, 13, 24, 30]))
+    F2 = int(rng.choice([max(F - 2, 0), 24, 31, 31, 36, 44]))
+    F2 = min(F2, (Fc or F) + 40)
+    return ModelParams(group_len=L, frac_bits=F, frac_bits2=F2, frac_bits_acc=Fc, c_mode=C_AFTER_RD,
+                       out_round=int(rng.integers(0, 2)), ftz_in=bool(rng.integers(0, 4) == 0), ftz_out=bool(rng.integers(0, 4) == 0),
+                       acc_special_truncation=bool(rng.integers(0, 2)), skip_zero_terms=bool(rng.integers(0, 2)),
+                       f2_at_leading_bit=bool(rng.integers(0, 2)), zero_result_positive=bool(rng.integers(0, 2)),
+                       sum_drop_distance=int(rng.choice([0, 0, 6, 20, 28])), nan_bits=0xFFC00000 if rng.integers(0, 2) else 0x7FC00000)
+
+
+@pytest.mark.parametrize("ta,tb", PAIRS)
+def test_tiled_rd_parameter_sweep(mm, ta, tb):
+    rng = np.random.default_rng(5000 + 8 * ta + tb)
+    used_tiled = expected_tiled = 0
+    for (m, n, k, nb) in SHAPES:
+        for mode in ("narrow", "full", "special", "zeros"):
+            p = random_rd_params(rng, k)
+            A, B, C = operands(rng, ta, tb, nb, m, n, k, "narrow" if mode == "zeros" else mode)
+            if mode == "zeros":     # plenty of zero operands and accumulators, whole zero rows
+                A = synth.sprinkle(rng, A, np.array([0, 1 << (A.dtype.itemsize * 8 - 1)], dtype=A.dtype), 0.3)
+                A[0, 0, :] = 0
+                B[0, 1, :] = 0
+                C = np.where(rng.random(C.shape) < 0.3, np.uint32(0x80000000), C).astype(np.uint32)
+            print("tiled rd", ta, tb, (m, n, k, nb), mode, p, flush=True)
+            want, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
+            got = gpu_emulate(mm, p, A, B, C, ta, tb)
+            assert_same(got, want, "tiled rd %s %s %s %s" % ((m, n, k, nb), mode, p, gpu_emulate.last_kernel))
+            Leff = k if p.group_len == 0 else min(p.group_len, k)
+            fast_shape = (m % 16 == 0 and n % 16 == 0 and k % 16 == 0) or (m % 32 == 0 and n % 32 == 0 and k % 8 == 0)
+            if fast_shape and Leff in (4, 8, 16, 32, k) and not (Leff == 32 and k % 32) and not (Leff == 4 and k % 4):
+                used_tiled += gpu_emulate.last_kernel.startswith("tiled")
+                expected_tiled += 1
+    assert expected_tiled > 10 and used_tiled >= 0.8 * expected_tiled, (used_tiled, expected_tiled)
+
+
+@pytest.mark.parametrize("p", [GFX950_16BIT, CDNA3_16BIT], ids=["gfx950", "cdna3"])
+def test_tiled_rd_accumulator_sweep(mm, p):
+    # the accumulator's exponent swept from far below to far above the products', both signs, zeros among the operands
+    rng = np.random.default_rng(81)
+    for ta, lo in ((fm.FP16, 13), (fm.BF16, 125)):
+        nb, m, n, k = 6, 32, 32, 8
+        A = synth.narrow_exponent_bits(rng, (nb, m, k), ta, lo, lo + 4)
+        B = synth.narrow_exponent_bits(rng, (nb, n, k), ta, lo, lo + 4)
+        A = synth.sprinkle(rng, A, np.array([0, 0x8000], dtype=A.dtype), 0.05)
+        for c_exp in ((60, 100), (100, 126), (120, 134), (130, 150), (148, 162), (0, 2), (250, 254)):
+            C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, *c_exp)
+            for rho in (RNE, RZ):
+                q = p.with_(out_round=rho)
+                want, _ = o2lib.emulate_mma(q, A, B, C, ta, ta)
+                assert_same(gpu_emulate(mm, q, A, B, C, ta, ta), want, "acc sweep %s %s" % (c_exp, q))
+                assert gpu_emulate.last_kernel.startswith("tiled 32x32"), gpu_emulate.last_kernel
+
+
+def test_tiled_rd_same_sign_products_far_below(mm):
+    # all products positive and at one exponent, accumulator 20..34 places above: the sum drops out at the stated distance
+    rng = np.random.default_rng(82)
+    nb, m, n, k = 4, 16, 16, 16
+    A = (synth.narrow_exponent_bits(rng, (nb, m, k), fm.FP16, 16, 16) & 0x7FFF).astype(np.uint16)
+    B = (synth.narrow_exponent_bits(rng, (nb, n, k), fm.FP16, 16, 16) & 0x7FFF).astype(np.uint16)
+    for shift in range(20, 35):
+        C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 127 + 2 + shift, 127 + 2 + shift)
+        for p in (GFX950_16BIT, CDNA3_16BIT, GFX950_16BIT.with_(sum_drop_distance=25)):
+            want, _ = o2lib.emulate_mma(p, A, B, C, fm.FP16, fm.FP16)
+            assert_same(gpu_emulate(mm, p, A, B, C, fm.FP16, fm.FP16), want, "far below %d %s" % (shift, p))
+
+
+def test_tiled_rd_cancellation_and_ties(mm):
+    rng = np.random.default_rng(83)
+    nb, m, n, k = 6, 16, 16, 16
+    A = synth.narrow_exponent_bits(rng, (nb, m, k), fm.FP16, 10, 20)
+    B = synth.narrow_exponent_bits(rng, (nb, n, k), fm.FP16, 10, 20)
+    A[:, :, 1::2] = A[:, :, 0::2] ^ 0x8000
+    B[:, :, 1::2] = B[:, :, 0::2]
+    flip = rng.random(B.shape) < 0.05
+    B = np.where(flip, B ^ 1, B).astype(np.uint16)
+    C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 90, 140)
+    for L in (4, 8, 16):
+        for base in (GFX950_16BIT, CDNA3_16BIT):
+            for F2 in (24, 31):
+                for rho in (RNE, RZ):
+                    p = base.with_(group_len=L, frac_bits2=F2, out_round=rho)
+                    want, _ = o2lib.emulate_mma(p, A, B, C, fm.FP16, fm.FP16)
+                    assert_same(gpu_emulate(mm, p, A, B, C, fm.FP16, fm.FP16), want, "cancel %s" % (p,))
+
+
+def test_tiled_rd_bf16_product_overflow(mm):
+    # products at and above 2^128 count as infinities in this mode (Sec. 4.2): whole tiles of large bf16 operands
+    rng = np.random.default_rng(84)
+    nb, m, n, k = 3, 16, 16, 16
+    A = synth.narrow_exponent_bits(rng, (nb, m, k), fm.BF16, 185, 195)
+    B = synth.narrow_exponent_bits(rng, (nb, n, k), fm.BF16, 185, 195)
+    C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 200, 254)
+    for p in (GFX950_16BIT, CDNA3_16BIT):
+        want, _ = o2lib.emulate_mma(p, A, B, C, fm.BF16, fm.BF16)
+        got = gpu_emulate(mm, p, A, B, C, fm.BF16, fm.BF16)
+        assert_same(got, want, "overflow %s" % (p,))
+        assert ((want & 0x7F800000) == 0x7F800000).mean() > 0.2     # the case does produce infinities / NaN
