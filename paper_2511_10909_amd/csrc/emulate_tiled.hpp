@@ -226,6 +226,18 @@ struct TiledArgs {
     int32_t ebase;       // Exp = e' + ebase for a product: 2 - bias_a - bias_b
 };
 
+// start of the running kernel's argument segment, as a pointer the optimiser cannot trace back to the arguments
+__device__ __forceinline__ const void *opaque_kernarg_ptr()
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const void *kp = __builtin_amdgcn_kernarg_segment_ptr();
+    asm volatile("" : "+s"(kp));
+    return kp;
+#else
+    return nullptr;
+#endif
+}
+
 // ---- the kernel -------------------------------------------------------------------------
 // TM x TN : block of D per slot;  R x C: register block per thread;
 // KC      : k elements staged at a time;
@@ -434,7 +446,11 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         const uint64_t brow = my_tile * n + j_base + TJ * c;
         const uint8_t *a = reinterpret_cast<const uint8_t *>(A) + (arow * k + kg) * esa;
         const uint8_t *b = reinterpret_cast<const uint8_t *>(B) + (brow * k + kg) * esb;
-        return fdpa_group_raw(p, ta_.ta, ta_.tb, a, b, p.L, cin);
+        // The model parameters are fetched again here, from the kernel-argument segment (they are its first
+        // bytes), through a pointer the optimiser cannot see through: otherwise every parameter this rare path
+        // needs stays in scalar registers for the whole kernel and crowds out the hot loops' values.
+        const TiledArgs q = *reinterpret_cast<const TiledArgs *>(opaque_kernarg_ptr());
+        return fdpa_group_raw(q.p, q.ta, q.tb, a, b, q.p.L, cin);
     };
 
     // End of a group: rho of (sum of aligned terms) * 2^unit.  The value to convert is held
