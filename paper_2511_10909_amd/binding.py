@@ -65,6 +65,10 @@ ERR_STATS_BYTES = ctypes.sizeof(ErrStats)
 if not os.path.exists(LIB_PATH):
     raise ImportError("libmmaemu.so is not built (%s); run `python -m paper_2511_10909_amd.build` or "
                       "__graft_entry__.build() first -- there is no fallback path" % LIB_PATH)
+# PyTorch first: it ships its own HIP runtime, and the library must bind to that same copy (tensors and streams
+# come from it).  Loaded the other way round, the library's runtime is a second one that sees no device.
+import torch  # noqa: E402,F401
+
 _lib = ctypes.CDLL(LIB_PATH)
 
 _vp, _u32, _u64 = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64
