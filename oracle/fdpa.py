@@ -62,6 +62,7 @@ from .rounding import to_fp32, floor_log2, RNE, RZ
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 ALIGN_RZ = 0
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES = 0, 1, 2
+FAMILY_FDPA, FAMILY_FTZ_ADDMUL = 0, 1      # FAMILY_FTZ_ADDMUL: oracle/addmul.py, with P = group_len
 DEFAULT_NAN = 0x7FC00000
 NVIDIA_NAN = 0x7FFFFFFF  # Sec. 4.2: canonical NaN of T-FDPA on NVIDIA parts
 
@@ -85,6 +86,7 @@ class ModelParams:
     f2_at_leading_bit: bool = False
     zero_result_positive: bool = False
     sum_drop_distance: int = 0
+    family: int = FAMILY_FDPA
 
     def with_(self, **kw):
         return replace(self, **kw)
@@ -252,7 +254,11 @@ def group_length(p, K):
 
 
 def emulate_element(p, a_bits, b_bits, c_bits, ta, tb):
-    """Algorithm "Phi_FDPA" for one output element: chain over K/L groups."""
+    """Algorithm "Phi_FDPA" for one output element: chain over K/L groups.  (family = FAMILY_FTZ_ADDMUL:
+    Algorithm "Phi_FTZ-AddMul" with P = group_len instead.)"""
+    if p.family == FAMILY_FTZ_ADDMUL:
+        from . import addmul
+        return addmul.emulate_element(p.group_len, a_bits, b_bits, c_bits, ta, tb, p.nan_bits)
     K = len(a_bits)
     L = group_length(p, K)
     d = int(c_bits)

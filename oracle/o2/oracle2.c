@@ -42,6 +42,7 @@ typedef struct {
     uint32_t group_len, frac_bits, align_round, c_mode, out_round, ftz_in, ftz_out, nan_bits, frac_bits2;
     uint32_t split, acc_special_truncation, frac_bits_merge, frac_bits_acc, skip_zero_terms, f2_at_leading_bit, zero_result_positive;
     uint32_t sum_drop_distance;
+    uint32_t family;     /* 0: chained FDPA, 1: FTZ-AddMul with P = group_len */
 } o2_params;
 
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
@@ -317,9 +318,71 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
     return finish(p, add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, (int)p->out_round));
 }
 
+/* ---- Algorithm "Phi_FTZ-AddMul" (Sec. 4.1.1) on the host's own binary32 arithmetic -------------------------
+ * The host's float + and * are RNE-FP32 of the exact result (IEEE-754 basic operations; the file is built without
+ * contraction or extended intermediate precision), which is what Algorithm "FTZ-Add and FTZ-Mul" asks for; the
+ * flush of results below 2^-126 and the NaN encoding are applied by hand. */
+static float f_of(uint32_t b) { float f; memcpy(&f, &b, 4); return f; }
+static uint32_t b_of(float f) { uint32_t b; memcpy(&b, &f, 4); return b; }
+
+static uint32_t ftz_fix(const o2_params *p, float z)
+{
+    uint32_t b = b_of(z);
+    if ((b & 0x7FFFFFFFu) > 0x7F800000u) return p->nan_bits;
+    if ((b & 0x7F800000u) == 0) b &= 0x80000000u;           /* |z| < 2^-126: zero, sign kept */
+    return b;
+}
+
+/* operand of type t (flushed if subnormal) as a float: every FP8 / FP16 / BF16 value is a binary32 number */
+static float operand_as_float(uint32_t bits, int t)
+{
+    dec_t x = decode(bits, t);
+    if (x.cls == CLS_NAN) return NAN;
+    if (x.cls == CLS_INF) return x.sign ? -INFINITY : INFINITY;
+    if (x.cls == CLS_SUB || x.cls == CLS_ZERO) return x.cls == CLS_ZERO && x.sign ? -0.0f : 0.0f;   /* FlushSubnormal: +0.0 */
+    float v = ldexpf((float)x.sig, x.exp - FMT[t].mbits);
+    return x.sign ? -v : v;
+}
+
+static uint32_t addmul_element(const o2_params *p, const void *A, const void *B, uint32_t c,
+                               size_t arow, size_t brow, uint32_t k, int ta, int tb)
+{
+    const uint32_t P = p->group_len;
+    uint32_t d = c;
+    if ((d & 0x7F800000u) == 0 && (d & 0x007FFFFFu)) d = 0u;      /* subnormal accumulator -> +0.0 */
+    if ((d & 0x7FFFFFFFu) > 0x7F800000u) d = p->nan_bits;
+    for (uint32_t k0 = 0; k0 < k; k0 += P) {
+        uint32_t pr[4];
+        for (uint32_t l = 0; l < P; ++l) {
+            volatile float x = operand_as_float(load_elem(A, arow + k0 + l, ta), ta);
+            volatile float y = operand_as_float(load_elem(B, brow + k0 + l, tb), tb);
+            volatile float z = x * y;
+            pr[l] = ftz_fix(p, z);
+        }
+        volatile float s0 = f_of(pr[0]) + f_of(pr[1]);
+        uint32_t s = ftz_fix(p, s0);
+        if (P == 4) {
+            volatile float s1 = f_of(pr[2]) + f_of(pr[3]);
+            uint32_t s2 = ftz_fix(p, s1);
+            volatile float s3 = f_of(s) + f_of(s2);
+            s = ftz_fix(p, s3);
+        }
+        volatile float dn = f_of(d) + f_of(s);
+        d = ftz_fix(p, dn);
+    }
+    return d;
+}
+
 static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out)
 {
     if (ta < 0 || ta > T_BF16 || tb < 0 || tb > T_BF16) return -2;
+    if (p->family == 1) {
+        if (p->group_len != 2 && p->group_len != 4) return -2;
+        if (k == 0 || k > (1u << 20) || k % p->group_len) return -3;
+        *L_out = p->group_len;
+        return 0;
+    }
+    if (p->family > 1) return -2;
     if (p->align_round != 0 || p->c_mode > 3 || p->out_round > 1 || p->frac_bits > 64) return -2;
     if (k == 0 || k > (1u << 20)) return -3;
     uint32_t L = (p->group_len == 0 || p->group_len > k) ? k : p->group_len;
@@ -382,7 +445,8 @@ int o2_emulate_mma(const o2_params *p, const void *A, const void *B, const uint3
             uint64_t t = (uint64_t)r / m; uint32_t i = (uint32_t)((uint64_t)r % m);
             for (uint32_t j = 0; j < n; ++j) {
                 size_t o = ((size_t)t * m + i) * n + j;
-                D[o] = element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
+                D[o] = p->family == 1 ? addmul_element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, ta, tb)
+                                      : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
             }
         }
     }
@@ -412,7 +476,8 @@ int o2_emulate_sample(const o2_params *p, const void *A, const void *B, const ui
             uint64_t o = idx[s];
             uint64_t t = o / ((uint64_t)m * n);
             uint32_t i = (uint32_t)((o / n) % m), j = (uint32_t)(o % n);
-            D_sample[s] = element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
+            D_sample[s] = p->family == 1 ? addmul_element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, ta, tb)
+                                         : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
         }
     }
     if (threads_used) *threads_used = used;

@@ -33,10 +33,14 @@ def test_table_d00(row):
     a = [enc(-2.0 ** 13), enc(-0.5), enc(-0.25), enc(-0.125)] + [0] * (K - 4)
     b = [enc(2.0 ** 10), enc(1.0), enc(1.0), enc(1.0)] + [0] * (K - 4)
     c = f32_bits(2.0 ** 23)
-    p = ModelParams(group_len=int(lmax), frac_bits=WIDE if F == "exact" else int(F),
+    p = ModelParams(group_len=int(lmax), frac_bits=WIDE if F == "exact" else (24 if F == "-" else int(F)),
                     out_round=RZ if rho == "RZ" else RNE)
     if rho in ("TR", "GTR"):
         p = p.with_(frac_bits2=31, c_mode=C_AFTER_RD if rho == "TR" else C_AFTER_RD_EVEN_ODD)
+    if rho == "ADDMUL":
+        p = ModelParams(group_len=int(lmax), family=1)
+    if rho == "FMA":
+        p = ModelParams(group_len=1, frac_bits=24, c_mode=C_AFTER_EXACT)
     got = emulate_element(p, a, b, c, t, t)
     assert bits_f32(got) == float(want)
     if float(want) == 0.0:

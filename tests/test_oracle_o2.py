@@ -81,9 +81,13 @@ def test_o2_table_d00(row):
     b = [enc(2.0 ** 10), enc(1.0), enc(1.0), enc(1.0)] + [0] * (K - 4)
     A, B = np.array([[a]]), np.array([[b]])
     C = np.array([[[f32_bits(2.0 ** 23)]]], dtype=np.uint32)
-    p = ModelParams(group_len=int(lmax), frac_bits=64 if F == "exact" else int(F), out_round=RZ if rho == "RZ" else RNE)
+    p = ModelParams(group_len=int(lmax), frac_bits=64 if F == "exact" else (24 if F == "-" else int(F)), out_round=RZ if rho == "RZ" else RNE)
     if rho in ("TR", "GTR"):
         p = p.with_(frac_bits2=31, c_mode=C_AFTER_RD if rho == "TR" else C_AFTER_RD_EVEN_ODD)
+    if rho == "ADDMUL":
+        p = ModelParams(group_len=int(lmax), family=1)
+    if rho == "FMA":
+        p = ModelParams(group_len=1, frac_bits=24, c_mode=C_AFTER_EXACT)
     got, _ = o2lib.emulate_mma(p, A, B, C, t, t)
     assert bits_f32(got[0, 0, 0]) == float(want)
 
