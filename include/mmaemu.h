@@ -60,6 +60,7 @@ enum { MMAEMU_C_IN_GROUP = 0, MMAEMU_C_AFTER_EXACT = 1, MMAEMU_C_AFTER_RD = 2, M
 enum { MMAEMU_ROUND_RNE = 0, MMAEMU_ROUND_RZ = 1 };
 enum { MMAEMU_ALIGN_RZ = 0 };
 enum { MMAEMU_SPLIT_NONE = 0, MMAEMU_SPLIT_EVEN_ODD = 1, MMAEMU_SPLIT_HALVES = 2 };
+enum { MMAEMU_FAMILY_FDPA = 0, MMAEMU_FAMILY_FTZ_ADDMUL = 1 };
 
 /*
  * One arithmetic-behaviour model: the chained FDPA model (paper Algorithm "Phi_FDPA")
@@ -106,6 +107,17 @@ enum { MMAEMU_SPLIT_NONE = 0, MMAEMU_SPLIT_EVEN_ODD = 1, MMAEMU_SPLIT_HALVES = 2
  *          sign (Algorithm "FTZ-Add/FTZ-Mul", last line).
  * nan_bits: pattern written for every NaN result (Sec. 4.2; 0x7FFFFFFF on NVIDIA parts).
  *
+ * family = MMAEMU_FAMILY_FTZ_ADDMUL selects the other model of the paper, built from binary
+ *   operations (Algorithms "FTZ-Add and FTZ-Mul" and "Phi_FTZ-AddMul", Sec. 4.1.1): subnormal
+ *   A, B, C inputs become +0.0; every product is RNE-FP32(a b) and every sum RNE-FP32(x + y),
+ *   each flushed to a zero of its sign when below 2^-126; every P = group_len (2 or 4)
+ *   consecutive products are summed pairwise, and c and the K/P partial sums sequentially.
+ *   Only group_len and nan_bits are used; the FDPA fields must hold their defaults
+ *   (frac_bits is ignored).  K must be a multiple of P.
+ *   (A chain of fused multiply-adds, Algorithm "Phi_FMA", is group_len = 1 with
+ *   c_mode = C_AFTER_EXACT in the FDPA family: the product of two operands of at most 11
+ *   significant bits is exact.)
+ *
  * Limits: frac_bits <= 40; K <= 2^20; with C_AFTER_EXACT also
  * frac_bits + 2 + ceil(log2 L) <= 56; with the two RD modes frac_bits2, frac_bits_merge
  * and frac_bits_acc <= 48 and max(F, F2, F_m, F_c) + 3 + ceil(log2 L) <= 53.
@@ -129,6 +141,7 @@ typedef struct {
     uint32_t skip_zero_terms;        /* 0 / 1 */
     uint32_t zero_result_positive;   /* 0 / 1 */
     uint32_t sum_drop_distance;      /* C_AFTER_RD only */
+    uint32_t family;                 /* MMAEMU_FAMILY_* */
 } mmaemu_model_params;
 
 typedef struct mmaemu_model mmaemu_model; /* opaque, host memory, owned by the library */

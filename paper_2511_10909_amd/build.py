@@ -15,7 +15,7 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-I", os.path.j
           # packed-FP32 VALU forms are not to be generated on the test machines
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # the NORMAL generator is defined as a fixed sequence of IEEE operations: no fused multiply-add
-PER_FILE = {"gen.hip": ["-ffp-contract=off"]}
+PER_FILE = {"gen.hip": ["-ffp-contract=off"], "emulate_addmul.hip": ["-ffp-contract=off"]}
 
 
 def sources():

@@ -87,6 +87,19 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: enum field out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
+    if (p->family > MMAEMU_FAMILY_FTZ_ADDMUL) { set_error("model_create: family out of range"); return MMAEMU_ERR_INVALID_ARG; }
+    if (p->family == MMAEMU_FAMILY_FTZ_ADDMUL) {
+        if (p->group_len != 2 && p->group_len != 4) {
+            set_error("model_create: the FTZ-AddMul family needs group_len (P) = 2 or 4");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        if (p->align_round || p->c_mode || p->frac_bits2 || p->out_round || p->out_mant_bits != 23 || p->ftz_in || p->ftz_out ||
+            p->split || p->acc_special_truncation || p->frac_bits_merge || p->frac_bits_acc || p->f2_at_leading_bit ||
+            p->skip_zero_terms || p->zero_result_positive || p->sum_drop_distance) {
+            set_error("model_create: the FTZ-AddMul family takes group_len and nan_bits only");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+    }
     if (p->align_round != MMAEMU_ALIGN_RZ || p->out_mant_bits != 23) {
         set_error("model_create: only RZ alignment and FP32 output (out_mant_bits = 23) are supported");
         return MMAEMU_ERR_UNSUPPORTED;
@@ -158,6 +171,20 @@ mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const
         return MMAEMU_ERR_UNSUPPORTED;
     }
     const mmaemu_model_params &mp = model->params;
+    if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL) {
+        if (k % mp.group_len) { set_error("emulate_mma: k=%u is not a multiple of P=%u", k, mp.group_len); return MMAEMU_ERR_SHAPE; }
+        const uint64_t mn_ = (uint64_t)m * n;
+        if (batch && (mn_ > (1ull << 40) || batch > (1ull << 62) / mn_ || batch * mn_ > (1ull << 48))) {
+            set_error("emulate_mma: problem too large");
+            return MMAEMU_ERR_SHAPE;
+        }
+        if (batch == 0) return MMAEMU_OK;
+        if (!A || !B || !C || !D) { set_error("emulate_mma: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+        ModelArgs am = {};
+        am.L = mp.group_len;
+        am.nan_bits = mp.nan_bits;
+        return launch_emulate_addmul(am, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream);
+    }
     const uint32_t L = (mp.group_len == 0 || mp.group_len > k) ? k : mp.group_len;
     if (k % L) { set_error("emulate_mma: k=%u is not a multiple of the group length L=%u", k, L); return MMAEMU_ERR_SHAPE; }
     if (mp.c_mode == MMAEMU_C_AFTER_EXACT && mp.frac_bits + 2 + ceil_log2(L) > 56) {

@@ -57,6 +57,9 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                      uint32_t tb, hipStream_t s);
+mmaemu_status launch_emulate_addmul(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
+                                    uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
+                                    uint32_t tb, hipStream_t s);
 mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s);
 mmaemu_status launch_compare(const uint32_t *d0, const uint32_t *d1, uint64_t count, uint64_t base,
                              mmaemu_stats *st, hipStream_t s);

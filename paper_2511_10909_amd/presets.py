@@ -33,6 +33,12 @@ PAPER = {
     ("blackwell", "bf16"): _t(16, 25, mm.RZ),
     ("blackwell", "fp16"): _t(16, 25, mm.RZ),
     ("blackwell", "fp8"): _t(32, 25, mm.RZ),
+    ("cdna1", "bf16"): dict(group_len=2, frac_bits=40, out_round=mm.RNE, c_mode=mm.C_IN_GROUP),     # E-FDPA up to 40 bits
+    ("cdna1", "fp16"): dict(group_len=4, frac_bits=40, out_round=mm.RNE, c_mode=mm.C_IN_GROUP),
+    ("cdna2", "bf16"): dict(group_len=2, family=mm.FAMILY_FTZ_ADDMUL),
+    ("cdna2", "bf16_1k"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),
+    ("cdna2", "fp16"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),
+    ("fma_chain", "any"): dict(group_len=1, frac_bits=24, out_round=mm.RNE, c_mode=mm.C_AFTER_EXACT),   # Phi_FMA on <= 16-bit inputs
     ("cdna3", "bf16"): dict(group_len=8, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD),
     ("cdna3", "fp16"): dict(group_len=8, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD),
     ("cdna3", "fp8"): dict(group_len=16, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD_EVEN_ODD),
