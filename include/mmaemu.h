@@ -210,9 +210,21 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
  *                optionally multiplied by scale_target / max|z| (max over the call's
  *                elements, or per tile), rounded to binary32 then to the output format
  *                (RNE, saturating at the largest finite value)
+ *   UNIFORM      uniform on [-1, 1): (word + 0.5) * 2^-31 - 1 in binary64; scaling and casts as NORMAL
+ *   NORMAL_OUTLIERS  z + h * 10 * z', with z as NORMAL, z' the same from word stream operand + 256 and
+ *                h = 1 where the word of stream operand + 512 is below floor(0.001 * 2^32), else 0
+ *                (the DNN-like family N(0,1) + Bernoulli(0.001) N(0,100) of Sec. 3.1 Step 4, variance
+ *                100 read as standard deviation 10); scaling and casts as NORMAL
+ *   CANCELLING   adversarial sums (Sec. 3.1 Step 4, large condition numbers): an element of even index
+ *                is drawn as UNIFORM_EXP; the odd element after it repeats that draw, with the sign
+ *                flipped for operand 0 and, for the other operands, the last mantissa bit flipped
+ *                where the low 4 bits of the odd element's own word are 0.  With K even and both
+ *                operands K-contiguous the products cancel pairwise up to those perturbations.
+ *                Not defined for FP32 output.
  */
 enum { MMAEMU_GEN_ZERO = 0, MMAEMU_GEN_FINITE_BITS = 1, MMAEMU_GEN_UNIFORM_EXP = 2,
-       MMAEMU_GEN_RANDOM_BITS = 3, MMAEMU_GEN_NORMAL = 4 };
+       MMAEMU_GEN_RANDOM_BITS = 3, MMAEMU_GEN_NORMAL = 4, MMAEMU_GEN_UNIFORM = 5,
+       MMAEMU_GEN_NORMAL_OUTLIERS = 6, MMAEMU_GEN_CANCELLING = 7 };
 enum { MMAEMU_SCALE_NONE = 0, MMAEMU_SCALE_TENSOR = 1, MMAEMU_SCALE_TILE = 2 };
 
 typedef struct {
@@ -220,15 +232,15 @@ typedef struct {
     uint32_t family;
     uint64_t seed;
     uint32_t operand;        /* 0 = A, 1 = B, 2 = C: selects the word stream */
-    uint32_t exp_lo, exp_hi; /* UNIFORM_EXP */
-    uint32_t exp_zero;       /* UNIFORM_EXP */
-    uint32_t scale_scope;    /* NORMAL */
-    double scale_target;     /* NORMAL with a scale scope */
+    uint32_t exp_lo, exp_hi; /* UNIFORM_EXP, CANCELLING */
+    uint32_t exp_zero;       /* UNIFORM_EXP, CANCELLING */
+    uint32_t scale_scope;    /* NORMAL, UNIFORM, NORMAL_OUTLIERS */
+    double scale_target;     /* those three, with a scale scope */
 } mmaemu_gen_params;
 
 /* Writes n_tiles * elems_per_tile elements of type `dtype` to `out`.
  * `workspace`: device memory of at least 8 bytes, 8-byte aligned, needed (and
- * overwritten) only for NORMAL with MMAEMU_SCALE_TENSOR; may be NULL otherwise.
+ * overwritten) only for the value families with MMAEMU_SCALE_TENSOR; may be NULL otherwise.
  * Errors: INVALID_ARG, UNSUPPORTED (exponent range outside the format), SHAPE
  * (elems_per_tile = 0 or total elements >= 2^62). */
 mmaemu_status mmaemu_generate(const mmaemu_gen_params *gen, void *out, mmaemu_dtype dtype,

@@ -34,6 +34,15 @@ Families (r = first word, r1 = second word):
                 optionally multiplied by scale_target / absmax (absmax over the
                 whole call, or over each tile), rounded to binary32 (RNE), then to
                 the output format (RNE, saturating at the largest finite value).
+  UNIFORM       uniform on [-1, 1): (r + 0.5) * 2^-31 - 1 (exact in binary64); scaling and casts as NORMAL.
+  NORMAL_OUTLIERS  the DNN-like family of Sec. 3.1 Step 4, N(0,1) + Bernoulli(0.001) * N(0,100), with the
+                variance 100 read as standard deviation 10: z + h * 10 * z', z as NORMAL, z' the same
+                construction on word stream `operand + 256`, h = 1 where the word of stream
+                `operand + 512` is below floor(0.001 * 2^32) = 4294967.  Scaling and casts as NORMAL.
+  CANCELLING    adversarial sums with large condition numbers (Sec. 3.1 Step 4): an element of even index
+                is drawn as UNIFORM_EXP; the odd element after it repeats that draw -- with the sign
+                flipped for operand 0, and for the other operands with the last mantissa bit flipped
+                where the low 4 bits of the odd element's own word are zero.  Not defined for FP32.
 """
 import math
 from dataclasses import dataclass
@@ -44,6 +53,8 @@ from . import formats as fm
 from .philox import philox4x32_10
 
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
+GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING = 5, 6, 7
+VALUE_FAMILIES = (GEN_NORMAL, GEN_UNIFORM, GEN_NORMAL_OUTLIERS)
 SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
 
 
@@ -171,19 +182,35 @@ def _normal_range(gp, g0, count):
     return z[off:off + count]
 
 
+def _value_range(gp, g0, count):
+    """Unscaled binary64 values of elements g0 .. g0+count-1 for the three value families."""
+    if gp.family == GEN_UNIFORM:
+        g = np.arange(g0, g0 + count, dtype=np.uint64)
+        r = _words(gp.seed, gp.operand, g).astype(np.float64)
+        return (r + 0.5) * (1.0 / 2147483648.0) - 1.0
+    z = _normal_range(gp, g0, count)
+    if gp.family == GEN_NORMAL_OUTLIERS:
+        from dataclasses import replace
+        z2 = _normal_range(replace(gp, operand=gp.operand + 256), g0, count)
+        g = np.arange(g0, g0 + count, dtype=np.uint64)
+        hit = _words(gp.seed, gp.operand + 512, g).astype(np.uint64) < np.uint64(4294967)
+        z = np.where(hit, z + 10.0 * z2, z)
+    return z
+
+
 def normal_values(gp, elems_per_tile, first_tile, n_tiles, threads=1):
-    """Unscaled binary64 N(0,1) values of the NORMAL family, shape (n_tiles, elems_per_tile).
+    """Unscaled binary64 values of the value families (NORMAL, UNIFORM, NORMAL_OUTLIERS), shape (n_tiles, elems_per_tile).
     `threads` > 1 only splits the element range over a thread pool (numpy releases the GIL);
     every element is computed by the same operations either way."""
     g0 = first_tile * elems_per_tile
     total = n_tiles * elems_per_tile
     step = 1 << 18                                                 # cache-sized pieces
     if total <= step:
-        return _normal_range(gp, g0, total).reshape(n_tiles, elems_per_tile)
+        return _value_range(gp, g0, total).reshape(n_tiles, elems_per_tile)
     from concurrent.futures import ThreadPoolExecutor
     starts = list(range(0, total, step))
     with ThreadPoolExecutor(max_workers=max(1, threads)) as ex:
-        parts = list(ex.map(lambda s0: _normal_range(gp, g0 + s0, min(step, total - s0)), starts))
+        parts = list(ex.map(lambda s0: _value_range(gp, g0 + s0, min(step, total - s0)), starts))
     return np.concatenate(parts).reshape(n_tiles, elems_per_tile)
 
 
@@ -195,7 +222,7 @@ def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
         return np.zeros((n_tiles, elems_per_tile), dtype=np.uint32)
     g = np.arange(first_tile * elems_per_tile, first_tile * elems_per_tile + total, dtype=np.uint64)
     wpe = words_per_elem(gp, fmt_id)
-    if gp.family == GEN_NORMAL:
+    if gp.family in VALUE_FAMILIES:
         z = normal_values(gp, elems_per_tile, first_tile, n_tiles, threads)
         if gp.scale_scope == SCALE_TENSOR:
             z = z * (np.float64(gp.scale_target) / np.abs(z).max())
@@ -213,7 +240,12 @@ def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
         v = (r * np.uint64(2 * nmag)) >> np.uint64(32)
         sign = (v >= nmag).astype(np.uint64)
         out = (sign << np.uint64(f.width - 1)) | (v - sign * np.uint64(nmag))
-    elif gp.family == GEN_UNIFORM_EXP:
+    elif gp.family in (GEN_UNIFORM_EXP, GEN_CANCELLING):
+        if gp.family == GEN_CANCELLING:
+            if fmt_id == fm.FP32:
+                raise ValueError("CANCELLING is not defined for FP32")
+            r_own = r
+            r = _words(gp.seed, gp.operand, (g & ~np.uint64(1)) * np.uint64(wpe)).astype(np.uint64)   # the even partner's word
         nch = gp.exp_hi - gp.exp_lo + 1 + (1 if gp.exp_zero else 0)
         sign = r >> np.uint64(31)
         if fmt_id == fm.FP32:
@@ -229,6 +261,13 @@ def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
         else:
             E = np.uint64(gp.exp_lo) + idx
         out = (sign << np.uint64(f.width - 1)) | (E << np.uint64(f.mbits)) | mant
+        if gp.family == GEN_CANCELLING:
+            odd = (g & np.uint64(1)) == 1
+            if gp.operand == 0:
+                out = np.where(odd, out ^ np.uint64(1 << (f.width - 1)), out)
+            else:
+                flip = odd & ((r_own & np.uint64(0xF)) == 0)
+                out = np.where(flip, out ^ np.uint64(1), out)
     else:
         raise ValueError(gp.family)
     return out.astype(np.uint32).reshape(n_tiles, elems_per_tile)

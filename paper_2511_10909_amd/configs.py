@@ -245,8 +245,13 @@ def validation_families(ta, tb):
     def ue(rng, zero=True):
         return dict(family=mm.GEN_UNIFORM_EXP, exp_lo=rng[0], exp_hi=rng[1], exp_zero=zero)
 
-    simple = [("normal", mm.GEN_NORMAL), ("finite_bits", mm.GEN_FINITE_BITS), ("random_bits", mm.GEN_RANDOM_BITS)]
+    simple = [("normal", mm.GEN_NORMAL), ("uniform", mm.GEN_UNIFORM), ("normal_outliers", mm.GEN_NORMAL_OUTLIERS),
+              ("finite_bits", mm.GEN_FINITE_BITS), ("random_bits", mm.GEN_RANDOM_BITS)]
     fams = [(name, dict(family=f), dict(family=f), dict(family=f)) for name, f in simple]
+    # adversarial sums: products cancelling pairwise up to last-place perturbations, accumulator near the residue
+    canc = dict(family=mm.GEN_CANCELLING, exp_zero=False)
+    fams.append(("cancelling", dict(canc, exp_lo=mid[ta][0], exp_hi=mid[ta][1]), dict(canc, exp_lo=mid[tb][0], exp_hi=mid[tb][1]),
+                 ue((100, 135))))
     fams.append(("mid_exp_c_above", ue(mid[ta]), ue(mid[tb]), ue((125, 145), zero=False)))
     fams.append(("mid_exp_c_below", ue(mid[ta]), ue(mid[tb]), ue((80, 129))))
     fams.append(("wide_exp_c_any", ue(full[ta]), ue(full[tb]), ue((1, 254))))

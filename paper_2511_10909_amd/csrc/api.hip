@@ -260,7 +260,7 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
         set_error("generate: struct_size %u, expected %zu", g->struct_size, sizeof(mmaemu_gen_params));
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if ((uint32_t)dtype > MMAEMU_FP32 || g->family > MMAEMU_GEN_NORMAL || g->scale_scope > MMAEMU_SCALE_TILE) {
+    if ((uint32_t)dtype > MMAEMU_FP32 || g->family > MMAEMU_GEN_CANCELLING || g->scale_scope > MMAEMU_SCALE_TILE) {
         set_error("generate: enum out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
@@ -270,21 +270,26 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
         return MMAEMU_ERR_SHAPE;
     }
     const FmtInfo f = fmt_info(dtype);
-    if (g->family == MMAEMU_GEN_UNIFORM_EXP) {
+    if (g->family == MMAEMU_GEN_CANCELLING && dtype == MMAEMU_FP32) {
+        set_error("generate: CANCELLING is not defined for FP32 output");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if (g->family == MMAEMU_GEN_UNIFORM_EXP || g->family == MMAEMU_GEN_CANCELLING) {
         const uint32_t emax_field = (1u << f.ebits) - 1u;
         if (g->exp_lo > g->exp_hi || g->exp_hi > emax_field) {
             set_error("generate: exponent-field range %u..%u outside 0..%u", g->exp_lo, g->exp_hi, emax_field);
             return MMAEMU_ERR_UNSUPPORTED;
         }
     }
-    if (g->family == MMAEMU_GEN_NORMAL && g->scale_scope != MMAEMU_SCALE_NONE && !(g->scale_target > 0.0)) {
+    const bool value_family = g->family == MMAEMU_GEN_NORMAL || g->family == MMAEMU_GEN_UNIFORM || g->family == MMAEMU_GEN_NORMAL_OUTLIERS;
+    if (value_family && g->scale_scope != MMAEMU_SCALE_NONE && !(g->scale_target > 0.0)) {
         set_error("generate: scale_target must be positive");
         return MMAEMU_ERR_INVALID_ARG;
     }
     if (n_tiles == 0) return MMAEMU_OK;
     if (!out) { set_error("generate: NULL output"); return MMAEMU_ERR_INVALID_ARG; }
     if ((uintptr_t)out & (uintptr_t)(f.width / 8 - 1)) { set_error("generate: output not aligned to its element size"); return MMAEMU_ERR_INVALID_ARG; }
-    if (g->family == MMAEMU_GEN_NORMAL && g->scale_scope == MMAEMU_SCALE_TENSOR) {
+    if (value_family && g->scale_scope == MMAEMU_SCALE_TENSOR) {
         if (!workspace || ((uintptr_t)workspace & 7)) { set_error("generate: SCALE_TENSOR needs an 8-byte aligned workspace"); return MMAEMU_ERR_INVALID_ARG; }
     }
     return launch_generate(*g, out, dtype, ept, first_tile, n_tiles, workspace, (hipStream_t)hip_stream);

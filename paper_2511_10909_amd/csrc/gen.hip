@@ -51,6 +51,7 @@ __device__ __forceinline__ void block_words(const GenArgs &g, uint64_t blk, uint
 
 __device__ __forceinline__ uint32_t bits_from_word(const GenArgs &g, uint32_t r, uint32_t r1)
 {
+    // (CANCELLING draws like UNIFORM_EXP; the pairing of even and odd elements is applied by the caller)
     if (g.family == MMAEMU_GEN_RANDOM_BITS) return g.width == 32 ? r : (r & ((1u << g.width) - 1u));
     if (g.family == MMAEMU_GEN_FINITE_BITS) {
         const uint32_t v = __umulhi(r, 2u * g.nmag);
@@ -108,6 +109,13 @@ gen_bits_kernel(GenArgs g, T *out, uint64_t g0, uint64_t total, uint64_t blk0, u
     uint32_t v[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] = bits_from_word(g, w[j], 0u);
+    if (g.family == MMAEMU_GEN_CANCELLING) {
+        // element 2q+1 repeats element 2q (both live in this block): sign flipped for operand 0; for the other
+        // operands the last mantissa bit is flipped where the odd element's own word ends in four zero bits
+#pragma unroll
+        for (int j = 1; j < 4; j += 2)
+            v[j] = g.operand == 0 ? (v[j - 1] ^ (1u << (g.width - 1))) : (v[j - 1] ^ ((w[j] & 0xFu) == 0 ? 1u : 0u));
+    }
     const uint64_t e0 = 4 * blk;
     if (e0 >= g0 && e0 + 4 <= g0 + total && ((reinterpret_cast<uintptr_t>(out + (e0 - g0)) & (4 * sizeof(T) - 1)) == 0)) {
         store4<T>(out + (e0 - g0), v);
@@ -205,12 +213,29 @@ __device__ __forceinline__ void normal_pair(uint32_t r_even, uint32_t r_odd, dou
     z_odd = radius * sinphi;
 }
 
+// the four binary64 values of one Philox block, by family
 __device__ __forceinline__ void block_normals(const GenArgs &g, uint64_t blk, double z[4])
 {
     uint32_t w[4];
     block_words(g, blk, w);
+    if (g.family == MMAEMU_GEN_UNIFORM) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) z[j] = ((double)w[j] + 0.5) * (1.0 / 2147483648.0) - 1.0;      // exact
+        return;
+    }
     normal_pair(w[0], w[1], z[0], z[1]);
     normal_pair(w[2], w[3], z[2], z[3]);
+    if (g.family == MMAEMU_GEN_NORMAL_OUTLIERS) {
+        uint32_t w2[4], wh[4];
+        double z2[4];
+        philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), g.operand + 256u, 0u, g.k0, g.k1, w2);
+        philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), g.operand + 512u, 0u, g.k0, g.k1, wh);
+        normal_pair(w2[0], w2[1], z2[0], z2[1]);
+        normal_pair(w2[2], w2[3], z2[2], z2[3]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (wh[j] < 4294967u) z[j] = z[j] + 10.0 * z2[j];                                       // floor(0.001 * 2^32)
+    }
 }
 
 // binary64 -> binary32 (RNE, hardware conversion) -> output format (RNE on the integer
@@ -348,7 +373,8 @@ static mmaemu_status launch_typed(const GenArgs &ga, void *out, uint64_t ept, ui
     const uint64_t blk0 = (g0 * wpe) >> 2, nblk = (((g0 + total) * wpe - 1) >> 2) - blk0 + 1;
     const uint64_t grid = (nblk + 255) / 256;
     if (grid > 0x7FFFFFFFull) { set_error("generate: too many elements for one call"); return MMAEMU_ERR_SHAPE; }
-    if (ga.family != MMAEMU_GEN_NORMAL) {
+    const bool value_family = ga.family == MMAEMU_GEN_NORMAL || ga.family == MMAEMU_GEN_UNIFORM || ga.family == MMAEMU_GEN_NORMAL_OUTLIERS;
+    if (!value_family) {
         hipLaunchKernelGGL((gen_bits_kernel<T>), dim3((uint32_t)grid), dim3(256), 0, s, ga, (T *)out, g0, total, blk0, nblk);
     } else if (ga.scale_scope == MMAEMU_SCALE_NONE) {
         hipLaunchKernelGGL((gen_normal_kernel<T>), dim3((uint32_t)grid), dim3(256), 0, s, ga, (T *)out, g0, total, blk0, nblk,

@@ -150,6 +150,12 @@ GEN_CASES = [
     (ogen.GEN_NORMAL, fm.E4M3, dict(scale_scope=ogen.SCALE_TILE, scale_target=448.0)),
     (ogen.GEN_NORMAL, fm.E5M2, dict(scale_scope=ogen.SCALE_TILE, scale_target=57344.0)),
     (ogen.GEN_NORMAL, fm.BF16, dict(scale_scope=ogen.SCALE_TILE, scale_target=3.0)),
+    (ogen.GEN_UNIFORM, fm.FP32, {}), (ogen.GEN_UNIFORM, fm.FP16, {}),
+    (ogen.GEN_UNIFORM, fm.E4M3, dict(scale_scope=ogen.SCALE_TENSOR, scale_target=448.0)),
+    (ogen.GEN_NORMAL_OUTLIERS, fm.FP32, {}), (ogen.GEN_NORMAL_OUTLIERS, fm.BF16, {}), (ogen.GEN_NORMAL_OUTLIERS, fm.FP16, {}),
+    (ogen.GEN_NORMAL_OUTLIERS, fm.E5M2, dict(scale_scope=ogen.SCALE_TILE, scale_target=57344.0)),
+    (ogen.GEN_CANCELLING, fm.FP16, dict(exp_lo=5, exp_hi=25)), (ogen.GEN_CANCELLING, fm.BF16, dict(exp_lo=100, exp_hi=150, exp_zero=True)),
+    (ogen.GEN_CANCELLING, fm.E4M3, dict(exp_lo=0, exp_hi=14)), (ogen.GEN_CANCELLING, fm.E5M2, dict(exp_lo=1, exp_hi=30)),
 ]
 
 
@@ -158,6 +164,8 @@ def test_generate_matches_cpu_twin(mm, family, fmt, kw):
     ws = dev_empty(8)
     for ept, first, nt, seed, operand in ((256, 0, 9, 0, 0), (256, 1000003, 5, 7, 1), (1024, 17, 3, 1 << 40, 2),
                                           (37, 5, 11, 3, 0), (4096 + 2, 1, 2, 9, 1), (1, 3, 7, 2, 2)):
+        if family == ogen.GEN_CANCELLING and operand == 2:
+            operand = 1              # (the family is meant for the two multiplicands)
         gp = ogen.GenParams(family=family, seed=seed, operand=operand, **kw)
         want = ogen.generate(gp, fmt, ept, first, nt).astype(NP[fmt])
         out = dev_empty((nt, ept), NP[fmt])

@@ -87,6 +87,51 @@ def test_normal_family_moments_and_tails():
     assert abs(np.corrcoef(z[0::2], z[1::2])[0, 1]) < 4 / np.sqrt(n / 2)
 
 
+def test_uniform_family():
+    gp = gen.GenParams(family=gen.GEN_UNIFORM, seed=3, operand=1)
+    u = gen.normal_values(gp, 1 << 20, 0, 1).ravel()
+    n = u.size
+    assert u.min() >= -1.0 and u.max() < 1.0
+    assert abs(u.mean()) < 4 * np.sqrt(1 / 3 / n)
+    assert abs(u.var() - 1 / 3) < 4 * np.sqrt(4 / 45 / n)
+    # every value is (r + 0.5) 2^-31 - 1 for an integer r below 2^32
+    r = (u + 1.0) * 2147483648.0 - 0.5
+    assert np.array_equal(r, np.floor(r)) and r.max() < 2 ** 32
+
+
+def test_normal_outliers_family():
+    # Sec. 3.1 Step 4: N(0,1) + Bernoulli(0.001) * N(0,100)
+    gp = gen.GenParams(family=gen.GEN_NORMAL_OUTLIERS, seed=5, operand=0)
+    x = gen.normal_values(gp, 1 << 21, 0, 1).ravel()
+    z = gen.normal_values(gen.GenParams(family=gen.GEN_NORMAL, seed=5, operand=0), 1 << 21, 0, 1).ravel()
+    hit = x != z
+    n = x.size
+    assert abs(hit.mean() - 0.001) < 4 * np.sqrt(0.001 / n)
+    extra = (x - z)[hit] / 10.0                      # the second normal, where it was added
+    assert abs(extra.std() - 1.0) < 5 / np.sqrt(2 * hit.sum())
+    assert abs(np.corrcoef(extra, z[hit])[0, 1]) < 5 / np.sqrt(hit.sum())
+    # variance of the mixture: 1 + 0.001 * 100
+    assert abs(x.var() - 1.1) < 0.02
+
+
+def test_cancelling_family_has_large_condition_numbers():
+    # Sec. 3.1 Step 4, second input type: sum |p_k| / |sum p_k| >> 1
+    K, rows = 16, 4096
+    ga = gen.GenParams(family=gen.GEN_CANCELLING, seed=1, operand=0, exp_lo=10, exp_hi=20)
+    gb = gen.GenParams(family=gen.GEN_CANCELLING, seed=1, operand=1, exp_lo=10, exp_hi=20)
+    A = gen.generate(ga, fm.FP16, K, 0, rows).astype(np.uint16)
+    B = gen.generate(gb, fm.FP16, K, 0, rows).astype(np.uint16)
+    assert np.array_equal(A[:, 1::2], A[:, 0::2] ^ 0x8000)
+    same = B[:, 1::2] == B[:, 0::2]
+    assert np.array_equal(B[:, 1::2][~same], B[:, 0::2][~same] ^ 1)
+    assert abs((~same).mean() - 1 / 16) < 0.01
+    p = A.view(np.float16).astype(np.float64) * B.view(np.float16).astype(np.float64)
+    cond = np.abs(p).sum(axis=1) / np.maximum(np.abs(p.sum(axis=1)), 1e-300)
+    assert np.median(cond) > 1e3
+    with pytest.raises(ValueError):
+        gen.generate(ga, fm.FP32, K, 0, 1)
+
+
 def test_elementary_functions_against_libm():
     r = np.random.default_rng(1).integers(0, 1 << 32, size=20000, dtype=np.uint64).astype(np.uint32)
     want = np.log((r.astype(np.float64) + 0.5) / 2.0 ** 32)
