@@ -10,7 +10,13 @@ static mmaemu_status launch_vm(const TiledArgs &t, const void *A, const void *B,
 {
     if (t.p.c_mode == MMAEMU_C_IN_GROUP) return launch_tiled_shape<MMAEMU_C_IN_GROUP, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
     if (t.p.c_mode == MMAEMU_C_AFTER_EXACT) return launch_tiled_shape<MMAEMU_C_AFTER_EXACT, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
-    return launch_tiled_shape<MMAEMU_C_AFTER_RD, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    if (t.p.split == MMAEMU_SPLIT_NONE) return launch_tiled_shape<MMAEMU_C_AFTER_RD, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    if constexpr (VM == 0) {
+        if (t.p.split == MMAEMU_SPLIT_EVEN_ODD) return launch_tiled_shape<CM_RD_EVEN_ODD, 0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_tiled_shape<CM_RD_HALVES, 0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    }
+    handled = false;        // split groups with BF16 operands or wide F: general kernel
+    return MMAEMU_OK;
 }
 
 mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *Cm, void *D,
@@ -20,9 +26,8 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // the tiled kernels need 8-byte aligned operand arrays (four consecutive k elements are
     // loaded at once) and group sums below 2^52
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) == 0;
-    // the RD mode without a split runs tiled with all of its variations; the two other modes only as the paper has them
-    const bool tiled_mode = p.c_mode == MMAEMU_C_AFTER_RD ? p.split == MMAEMU_SPLIT_NONE
-                                                          : (!p.skip_zero_terms && !p.zero_result_positive);
+    // the RD mode runs tiled with all of its variations; the two other modes only as the paper has them
+    const bool tiled_mode = p.c_mode == MMAEMU_C_AFTER_RD || (!p.skip_zero_terms && !p.zero_result_positive);
     if (tiled_mode && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;

@@ -30,6 +30,11 @@
 //      conversion;
 //   2  wide F (30..40): binary64 values, terms truncated with v_trunc_f64 and summed in
 //      binary64 (exact below 2^53).
+// Accumulation modes (template parameter CMODE): MMAEMU_C_IN_GROUP, MMAEMU_C_AFTER_EXACT, MMAEMU_C_AFTER_RD (paper
+// Algorithm "TR-FDPA" and its variations), and the two split forms of the latter (Algorithm "GTR-FDPA"):
+// CM_RD_EVEN_ODD, where the packed exponent maxima of pass 1 already are the even and the odd maximum (even k in
+// the low halves, odd k in the high halves) and pass 2 alternates between two scales and two sums, and CM_RD_HALVES,
+// where each half of a group runs through passes 1 and 2 as a group of its own before the halves are merged.
 // NaN and infinities are tagged with an exponent sentinel; a group that meets one is
 // recomputed by the integer routine of the general kernel from the raw operands in
 // global memory.
@@ -37,6 +42,8 @@
 #include "fdpa_int.hpp"
 
 namespace mmaemu {
+
+constexpr int CM_RD_EVEN_ODD = 3, CM_RD_HALVES = 4;      // template-only values of CMODE (ModelArgs::c_mode stays C_AFTER_RD)
 
 constexpr uint32_t SENTINEL = 0x4000u;      // exponent tag of an element the fast path cannot take
 constexpr uint32_t SENTINEL_MASK = 0xC000C000u;
@@ -255,7 +262,10 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     constexpr int VS = KC + 4;                       // LDS row stride of binary32 values (floats), padded
     constexpr int VSD = KC + 2;                      // LDS row stride of binary64 values (doubles)
     constexpr int ES = KC / 2 + (KC == 16 ? 2 : 4);  // LDS row stride of packed exponents (dwords)
-    constexpr int GL = LT ? LT : KC;                 // terms per inner step
+    constexpr bool IS_RD = CMODE == MMAEMU_C_AFTER_RD || CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES;
+    static_assert(!(CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES) || (LT >= 4 && VM == 0 && NF == 0), "split groups: fixed length, binary32 values, one fold");
+    static_assert(CMODE != CM_RD_HALVES || LT >= 8, "halves of at least four terms");
+    constexpr int GL = CMODE == CM_RD_HALVES ? LT / 2 : (LT ? LT : KC);   // terms per inner step
     constexpr int FOLD = NF ? NF : GL;
     constexpr bool USE_SD = (NF != 0) || (LT == 0) || (VM == 2);   // binary64 accumulator needed
     constexpr int VBYTES_A = SLOTS * TM * (VM == 0 ? VS * 4 : VSD * 8);
@@ -309,6 +319,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 
     uint32_t m2[R][C];                                          // packed running maxima of e'
     int32_t S32[R][C];
+    int32_t S32o[CMODE == CM_RD_EVEN_ODD ? R : 1][CMODE == CM_RD_EVEN_ODD ? C : 1];   // odd products (even / odd split)
     double Sd[R][C];
     bool chunk_is_double = (VM == 2);                           // how the staged chunk's values are held
 
@@ -385,6 +396,44 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         }
     };
 
+    // pass 2 with the even / odd split: even k aligned at the even maximum into S32, odd k at the odd one into S32o
+    auto pass2eo = [&](int g, const int (&emax_e)[R][C], const int (&emax_o)[R][C]) {
+        float scale_e[R][C], scale_o[R][C];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                int se = F + 127 - emax_e[r][c], so = F + 127 - emax_o[r][c];
+                se = se < 1 ? 1 : (se > 254 ? 254 : se);
+                so = so < 1 ? 1 : (so > 254 ? 254 : so);
+                scale_e[r][c] = __uint_as_float((uint32_t)se << 23);
+                scale_o[r][c] = __uint_as_float((uint32_t)so << 23);
+            }
+#pragma unroll U2
+        for (int q = 0; q < GL; q += 4) {
+            float a[R][4], b[C][4];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float4 v = *reinterpret_cast<const float4 *>(av + TI * r * VS + g * GL + q);
+                a[r][0] = v.x; a[r][1] = v.y; a[r][2] = v.z; a[r][3] = v.w;
+            }
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const float4 v = *reinterpret_cast<const float4 *>(bv + TJ * c * VS + g * GL + q);
+                b[c][0] = v.x; b[c][1] = v.y; b[c][2] = v.z; b[c][3] = v.w;
+            }
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        if (w & 1) S32o[CMODE == CM_RD_EVEN_ODD ? r : 0][CMODE == CM_RD_EVEN_ODD ? c : 0] += (int32_t)((a[r][w] * b[c][w]) * scale_o[r][c]);
+                        else S32[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale_e[r][c]);
+                    }
+        }
+    };
+
     // pass 2, binary64 values (any finite operands; also wide F): two k per LDS read and row
     auto pass2d = [&](int g, const int (&emax)[R][C]) {
         double scale[R][C];
@@ -427,7 +476,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         uint32_t e = m2[r][c];
         const uint32_t lo = e & 0xFFFFu, hi = e >> 16;
         int em = (int)(lo > hi ? lo : hi) + ta_.ebase;
-        if (CMODE == MMAEMU_C_AFTER_RD && VM != 0 && em >= 126 && !(e & SENTINEL_MASK)) {
+        if (IS_RD && VM != 0 && em >= 126 && !(e & SENTINEL_MASK)) {
             // a product may reach 2^128, which this mode counts as an infinity: leave the group to the integer routine
             e |= 0x8000u;
             m2[r][c] = e;
@@ -453,10 +502,80 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         return fdpa_group_raw(q.p, q.ta, q.tb, a, b, q.p.L, cin);
     };
 
+    // Algorithm "TR-FDPA", steps 3 and 4 ("GTR-FDPA", steps 4 and 5), and the variations, in binary64 (every
+    // quantity is an integer of fewer than 53 bits times a power of two, hence exact, except where noted):
+    // T counts units of 2^(em - FT); returns the exact value whose conversion is the group's result.
+    auto rd_value = [&](double T, bool have_T, int em, int FT, uint32_t cb) -> double {
+        const int Fmax = p.F2 > p.Fc ? p.F2 : p.Fc;
+        const uint32_t Ec = (cb >> 23) & 0xFFu;
+        const int ec = (int)(Ec ? Ec : 1u) - 127;
+        const bool c_live = !(p.skip_zero_terms && (cb & 0x7FFFFFFFu) == 0);
+        const int E = (have_T && c_live) ? (ec > em ? ec : em) : (have_T ? em : ec);
+        if (have_T && p.sum_drop_distance && E - em >= p.sum_drop_distance) have_T = false;
+        if (!have_T) T = 0.0;
+        double sc = __builtin_floor(ldexp((double)__uint_as_float(cb), p.Fc - E));               // RD_Fc(c at E), units of 2^(E - Fc)
+        if (p.acc_special_truncation && ec < E - p.Fc - 1) sc = 0.0;
+        double val;
+        if (!p.f2_at_leading_bit) {
+            const double T2 = __builtin_floor(ldexp(T, (em - FT) - (E - p.F2)));                  // RD_F2(T at E)
+            val = ldexp(ldexp(T2, Fmax - p.F2) + ldexp(sc, Fmax - p.Fc), E - Fmax);
+        } else {
+            // exact two-term sum as s + err (Knuth's TwoSum); then round down to F2 bits below the leading bit
+            // of the exact sum.  |err| is below half a last place of s, far under that unit.
+            const double a = ldexp(T, em - FT), b = ldexp(sc, E - p.Fc);
+            const double sm = a + b, bb = sm - a;
+            const double err = (a - (sm - bb)) + (b - bb);
+            const long long sbits = __double_as_longlong(sm);
+            int lead = (int)((sbits >> 52) & 0x7FF) - 1023;
+            const bool toward_zero = (err != 0.0) && ((err < 0.0) != (sm < 0.0));
+            if ((sbits & 0xFFFFFFFFFFFFFll) == 0 && toward_zero) lead -= 1;                      // just inside the binade below
+            const int unit = lead - p.F2;
+            double q = __builtin_floor(ldexp(sm, -unit));
+            if (err < 0.0 && ldexp(q, unit) == sm) q -= 1.0;                                      // s on the grid, exact sum just below it
+            val = sm == 0.0 ? 0.0 : ldexp(q, unit);
+        }
+        return (have_T || c_live) ? val : 0.0;
+    };
+
     // End of a group: rho of (sum of aligned terms) * 2^unit.  The value to convert is held
     // in binary64, exact or rounded to odd, so that the single hardware conversion to
     // binary32 (RNE, gradual underflow, overflow to infinity) rounds correctly.
-    auto end_of_group = [&](uint32_t kg, const int (&emax)[R][C], uint32_t tagged) {
+    // conversion of the exact group values v, output rounding variants, the rare integer route, d <- result
+    auto finish_group = [&](uint32_t kg, const double (&v)[R][C], const uint32_t (&tg)[R][C], uint32_t tagged) {
+        uint32_t dn[R][C];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) dn[r][c] = __float_as_uint((float)v[r][c]);
+        if (p.out_round != MMAEMU_ROUND_RNE || p.ftz_out || p.zero_result_positive) {
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    uint32_t o = dn[r][c];
+                    if (p.out_round == MMAEMU_ROUND_RZ) {
+                        const double back = (double)__uint_as_float(o);
+                        if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) o -= 1u;   // rounded away from zero: step back
+                    }
+                    if (p.ftz_out && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                    if (p.zero_result_positive && (o & 0x7FFFFFFFu) == 0) o = 0u;
+                    dn[r][c] = o;
+                }
+        }
+        if (tagged & SENTINEL_MASK) {                                   // rare: the group met a tagged element
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if (tg[r][c] & SENTINEL_MASK) dn[r][c] = slow_group(r, c, kg, d[r][c]);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+    };
+
+    auto flush_accumulators = [&]() {
         if (p.ftz_in) {                                                 // FlushSubnormal on the accumulator
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -464,6 +583,10 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                 for (int c = 0; c < C; ++c)
                     if ((d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;
         }
+    };
+
+    auto end_of_group = [&](uint32_t kg, const int (&emax)[R][C], uint32_t tagged) {
+        flush_accumulators();
         double v[R][C];
         if (CMODE == MMAEMU_C_IN_GROUP) {
 #pragma unroll
@@ -477,46 +600,14 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                     v[r][c] = ldexp(T + tc, unit);                      // exact: integers below 2^53
                 }
         } else if (CMODE == MMAEMU_C_AFTER_RD) {
-            // Algorithm "TR-FDPA", steps 3 and 4, and its variations, in binary64 (every quantity below is an
-            // integer of fewer than 53 bits times a power of two, hence exact, except where noted)
-            const int Fmax = p.F2 > p.Fc ? p.F2 : p.Fc;
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
-                    double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];   // units of 2^(e_max - F)
+                    const double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];   // units of 2^(e_max - F)
                     const uint32_t mx = m2[r][c], mlo = mx & 0xFFFFu, mhi = mx >> 16;
-                    bool have_T = !p.skip_zero_terms || (mlo > mhi ? mlo : mhi) >= 2 * ZBIAS;
-                    const uint32_t cb = d[r][c];
-                    const uint32_t Ec = (cb >> 23) & 0xFFu;
-                    const int ec = (int)(Ec ? Ec : 1u) - 127;
-                    const bool c_live = !(p.skip_zero_terms && (cb & 0x7FFFFFFFu) == 0);
-                    const int em = emax[r][c];
-                    const int E = (have_T && c_live) ? (ec > em ? ec : em) : (have_T ? em : ec);
-                    if (have_T && p.sum_drop_distance && E - em >= p.sum_drop_distance) have_T = false;
-                    if (!have_T) T = 0.0;
-                    double sc = __builtin_floor(ldexp((double)__uint_as_float(cb), p.Fc - E));   // RD_Fc(c at E), units of 2^(E - Fc)
-                    if (p.acc_special_truncation && ec < E - p.Fc - 1) sc = 0.0;
-                    double val;
-                    if (!p.f2_at_leading_bit) {
-                        const double T2 = __builtin_floor(ldexp(T, (em - F) - (E - p.F2)));      // RD_F2(T at E)
-                        val = ldexp(ldexp(T2, Fmax - p.F2) + ldexp(sc, Fmax - p.Fc), E - Fmax);
-                    } else {
-                        // exact two-term sum as s + err (Knuth's TwoSum); then round down to F2 bits below the
-                        // leading bit of the exact sum.  |err| is below half a last place of s, far under that unit.
-                        const double a = ldexp(T, em - F), b = ldexp(sc, E - p.Fc);
-                        const double sm = a + b, bb = sm - a;
-                        const double err = (a - (sm - bb)) + (b - bb);
-                        const long long sbits = __double_as_longlong(sm);
-                        int lead = (int)((sbits >> 52) & 0x7FF) - 1023;
-                        const bool toward_zero = (err != 0.0) && ((err < 0.0) != (sm < 0.0));
-                        if ((sbits & 0xFFFFFFFFFFFFFll) == 0 && toward_zero) lead -= 1;          // just inside the binade below
-                        const int unit = lead - p.F2;
-                        double q = __builtin_floor(ldexp(sm, -unit));
-                        if (err < 0.0 && ldexp(q, unit) == sm) q -= 1.0;                          // s on the grid, exact sum just below it
-                        val = sm == 0.0 ? 0.0 : ldexp(q, unit);
-                    }
-                    v[r][c] = (have_T || c_live) ? val : 0.0;
+                    const bool have_T = !p.skip_zero_terms || (mlo > mhi ? mlo : mhi) >= 2 * ZBIAS;
+                    v[r][c] = rd_value(T, have_T, emax[r][c], F, d[r][c]);
                 }
         } else {
             // d = rho(T 2^unit + c) with the two-term sum exact: s = RN(a + c) and its exact
@@ -550,44 +641,45 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                         }
             }
         }
-        uint32_t dn[R][C];
+        finish_group(kg, v, m2, tagged);
+    };
+
+    // End of a split group (Algorithm "GTR-FDPA", steps 3 to 5): the two sub-group sums T0, T1 (units of 2^(e - F) at
+    // their own maxima e0, e1; h0, h1: whether any term took part) are rounded down to F_m bits at the larger maximum
+    // and added; then as TR-FDPA.
+    auto end_of_split_group = [&](uint32_t kg, const double (&T0)[R][C], const int (&e0)[R][C], const uint32_t (&x0)[R][C],
+                                  const double (&T1)[R][C], const int (&e1)[R][C], const uint32_t (&x1)[R][C], bool halves,
+                                  uint32_t tagged) {
+        flush_accumulators();
+        double v[R][C];
+        uint32_t tg[R][C];
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) dn[r][c] = __float_as_uint((float)v[r][c]);
-        if (p.out_round != MMAEMU_ROUND_RNE || p.ftz_out || p.zero_result_positive) {
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    uint32_t o = dn[r][c];
-                    if (p.out_round == MMAEMU_ROUND_RZ) {
-                        const double back = (double)__uint_as_float(o);
-                        if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) o -= 1u;   // rounded away from zero: step back
-                    }
-                    if (p.ftz_out && (o & 0x7F800000u) == 0) o &= 0x80000000u;
-                    if (p.zero_result_positive && (o & 0x7FFFFFFFu) == 0) o = 0u;
-                    dn[r][c] = o;
-                }
-        }
-        if (tagged & SENTINEL_MASK) {                                   // rare: the group met a tagged element
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (m2[r][c] & SENTINEL_MASK) dn[r][c] = slow_group(r, c, kg, d[r][c]);
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+            for (int c = 0; c < C; ++c) {
+                // x0 / x1: the packed exponent maxima the sub-sums came from (both halves of the word for a half
+                // group, the low / high half for the even / odd split)
+                const uint32_t m0 = halves ? ((x0[r][c] & 0xFFFFu) > (x0[r][c] >> 16) ? (x0[r][c] & 0xFFFFu) : (x0[r][c] >> 16)) : (x0[r][c] & 0xFFFFu);
+                const uint32_t m1 = halves ? ((x1[r][c] & 0xFFFFu) > (x1[r][c] >> 16) ? (x1[r][c] & 0xFFFFu) : (x1[r][c] >> 16)) : (x1[r][c] >> 16);
+                const bool h0 = !p.skip_zero_terms || m0 >= 2 * ZBIAS, h1 = !p.skip_zero_terms || m1 >= 2 * ZBIAS;
+                const int em = (h0 && h1) ? (e0[r][c] > e1[r][c] ? e0[r][c] : e1[r][c]) : (h0 ? e0[r][c] : e1[r][c]);
+                double T = 0.0;
+                if (h0) T += __builtin_floor(ldexp(T0[r][c], (e0[r][c] - F) - (em - p.Fm)));
+                if (h1) T += __builtin_floor(ldexp(T1[r][c], (e1[r][c] - F) - (em - p.Fm)));
+                v[r][c] = rd_value(T, h0 || h1, em, p.Fm, d[r][c]);
+                tg[r][c] = x0[r][c] | x1[r][c];
+            }
+        finish_group(kg, v, tg, tagged);
     };
 
     auto reset_group = [&]() {
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) { m2[r][c] = 0; S32[r][c] = 0; Sd[r][c] = 0.0; }
+            for (int c = 0; c < C; ++c) {
+                m2[r][c] = 0; S32[r][c] = 0; Sd[r][c] = 0.0;
+                if (CMODE == CM_RD_EVEN_ODD) S32o[CMODE == CM_RD_EVEN_ODD ? r : 0][CMODE == CM_RD_EVEN_ODD ? c : 0] = 0;
+            }
     };
 
     // Staging is split in two: `prefetch` issues the global loads of a chunk (they complete
@@ -603,7 +695,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     auto commit = [&](int what) {
         float fa[NQA][4], fb[NQB][4];
         uint2 xa[NQA], xb[NQB];
-        const uint32_t zbias = (CMODE == MMAEMU_C_AFTER_RD && p.skip_zero_terms) ? ZBIAS : 0u;
+        const uint32_t zbias = (IS_RD && p.skip_zero_terms) ? ZBIAS : 0u;
         bool wild = decode_any<NQA>(ta_.ta, raw_a, p.ftz_in, zbias, fa, xa);
         wild |= decode_any<NQB>(ta_.tb, raw_b, p.ftz_in, zbias, fb, xb);
         if (VM == 1) chunk_is_double = __syncthreads_or(wild && (what & 2)) != 0;
@@ -625,17 +717,71 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         for (uint32_t k0 = 0; k0 < k; k0 += KC) {
             commit(3);
             if (k0 + KC < k) prefetch(k0 + KC);
+            if constexpr (CMODE == CM_RD_EVEN_ODD) {
 #pragma unroll 1
-            for (int g = 0; g < KC / GL; ++g) {
-                reset_group();
-                pass1(g);
-                int emax[R][C]; uint32_t tagged = 0;
+                for (int g = 0; g < KC / GL; ++g) {
+                    reset_group();
+                    pass1(g);
+                    int ee[R][C], eo[R][C]; uint32_t tagged = 0;
 #pragma unroll
-                for (int r = 0; r < R; ++r)
+                    for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], tagged);
-                pass2(g, emax);
-                end_of_group(k0 + g * GL, emax, tagged);
+                        for (int c = 0; c < C; ++c) {
+                            ee[r][c] = (int)(m2[r][c] & 0xFFFFu) + ta_.ebase;      // even k sit in the low halves
+                            eo[r][c] = (int)(m2[r][c] >> 16) + ta_.ebase;
+                            tagged |= m2[r][c];
+                        }
+                    pass2eo(g, ee, eo);
+                    double Te[R][C], To[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) { Te[r][c] = (double)S32[r][c]; To[r][c] = (double)S32o[CMODE == CM_RD_EVEN_ODD ? r : 0][CMODE == CM_RD_EVEN_ODD ? c : 0]; }
+                    end_of_split_group(k0 + g * GL, Te, ee, m2, To, eo, m2, false, tagged);
+                }
+            } else if constexpr (CMODE == CM_RD_HALVES) {
+#pragma unroll 1
+                for (int g = 0; g < KC / LT; ++g) {
+                    double T0[R][C]; int e0[R][C]; uint32_t x0[R][C];
+                    int emax[R][C]; uint32_t tagged = 0;
+                    reset_group();
+                    pass1(2 * g);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], tagged);
+                    pass2f(2 * g, emax);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) { T0[r][c] = (double)S32[r][c]; e0[r][c] = emax[r][c]; x0[r][c] = m2[r][c]; }
+                    reset_group();
+                    pass1(2 * g + 1);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], tagged);
+                    pass2f(2 * g + 1, emax);
+                    double T1[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) T1[r][c] = (double)S32[r][c];
+                    end_of_split_group(k0 + g * LT, T0, e0, x0, T1, emax, m2, true, tagged);
+                }
+            } else {
+#pragma unroll 1
+                for (int g = 0; g < KC / GL; ++g) {
+                    reset_group();
+                    pass1(g);
+                    int emax[R][C]; uint32_t tagged = 0;
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) exponents(r, c, emax[r][c], tagged);
+                    pass2(g, emax);
+                    end_of_group(k0 + g * GL, emax, tagged);
+                }
             }
         }
     } else {
@@ -703,6 +849,8 @@ static mmaemu_status launch_fold(const TiledArgs &ta, const void *A, const void 
 {
     if constexpr (VM == 2) {
         return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0, VM>(ta, A, B, Cm, D, m, n, k, batch, s);   // terms summed in binary64
+    } else if constexpr (CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES) {
+        return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0, VM>(ta, A, B, Cm, D, m, n, k, batch, s);   // (the caller checked the 32-bit sums)
     } else {
         constexpr int GL = LT ? LT : KC;
         const uint64_t term = 1ull << (ta.p.F + 2);             // |aligned term| < 2^(F+2)
@@ -718,6 +866,20 @@ static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B,
 {
     handled = true;
     const uint32_t L = ta.p.L;
+    if constexpr (CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES) {
+        // split groups: fixed lengths only, and half a group's aligned terms must fit one 32-bit sum
+        if ((uint64_t)(L / 2) << (ta.p.F + 2) <= (1ull << 31)) {
+            if (L == 8) return launch_fold<TM, TN, R, C, KC, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+            if constexpr (KC >= 16) {
+                if (L == 16) return launch_fold<TM, TN, R, C, KC, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+            }
+            if constexpr (KC >= 32) {
+                if (L == 32) return launch_fold<TM, TN, R, C, KC, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+            }
+        }
+        handled = false;
+        return MMAEMU_OK;
+    } else {
     if (L == 4) return launch_fold<TM, TN, R, C, KC, 4, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     if (L == 8) return launch_fold<TM, TN, R, C, KC, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     if constexpr (KC >= 16) {
@@ -729,6 +891,7 @@ static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B,
     if (L % KC == 0) return launch_fold<TM, TN, R, C, KC, 0, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     handled = false;
     return MMAEMU_OK;
+    }
 }
 
 template <int CMODE, int VM>
@@ -772,5 +935,7 @@ extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 2);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 0);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 1);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 2);
+extern template MMAEMU_TILED_SIG(CM_RD_EVEN_ODD, 0);
+extern template MMAEMU_TILED_SIG(CM_RD_HALVES, 0);
 
 } // namespace mmaemu
