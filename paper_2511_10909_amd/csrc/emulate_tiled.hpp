@@ -900,23 +900,26 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
 {
     handled = false;
     const uint64_t outputs = batch * m * n;
-    // whole small tiles of a batch (binary64 values need twice the LDS: fewer tiles per workgroup)
+    // whole small tiles of a batch (binary64 values need twice the LDS: fewer tiles per workgroup; half groups keep
+    // a second set of sums and maxima per output: smaller register blocks)
+    constexpr bool BIG_BLOCKS = VM == 0 && CMODE != CM_RD_HALVES;
+    constexpr bool BIG_BLOCKS_OK = CMODE != CM_RD_HALVES;
     if (m == 16 && n == 16 && k % 16 == 0) {
-        if constexpr (VM == 0) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        if constexpr (BIG_BLOCKS) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
         else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     }
     if (m == 32 && n == 32 && k % 8 == 0 && k % 32 != 0)
         return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     // blocks of a larger problem: 4x4 register blocks once there are enough outputs to fill
     // the chip with them (256 CUs x 4 SIMDs x 2 waves x 64 lanes x 16), 2x2 blocks otherwise
-    if (m % 64 == 0 && n % 64 == 0 && k % 32 == 0 && outputs >= (1ull << 21))
+    if (BIG_BLOCKS_OK && m % 64 == 0 && n % 64 == 0 && k % 32 == 0 && outputs >= (1ull << 21))
         return launch_L<64, 64, 4, 4, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 32 == 0 && n % 32 == 0 && k % 32 == 0)
         return launch_L<32, 32, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
         return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) {
-        if constexpr (VM == 0) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        if constexpr (BIG_BLOCKS) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
         else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     }
     return MMAEMU_OK;
