@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 INT32_VALU_PEAK = 256 * 4 * 16 * 2.4e9      # lane-instructions / s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
 ALGO_OPS_PER_TERM = 8                       # accounting floor of INT32 VALU instructions per MAC term
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (scaled by a copy kernel
+# of known size; see profiles/emulate_tiled_bf16_gemm1024_hbm_counters.md).  Valid only for the kernel variant and
+# problem size it was measured on: any other variant reports null.
+MEASURED_TRAFFIC = {("tiled 32x32 r2x2 kc=32 L=8 c_mode=1 fold=0 vm=1", 1024): (11362.5 * 2.00 + 4096.0) * 1024.0}
 
 
 def parse():
@@ -160,7 +164,7 @@ def main():
             "peak": INT32_VALU_PEAK / 1e12,
             "unit": "T INT32 lane-instr/s (8 algorithmic instr per MAC term)",
             "frac": achieved / INT32_VALU_PEAK,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC.get((kernels[dom_name], args.size)),
         },
     }
     mm.model_destroy(chained)
