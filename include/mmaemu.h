@@ -101,6 +101,8 @@ enum { MMAEMU_FAMILY_FDPA = 0, MMAEMU_FAMILY_FTZ_ADDMUL = 1 };
  *   zero_result_positive   a result that rounds or is flushed to zero is +0.0
  * out_round: rho = RNE-FP32 or RZ-FP32 (Table "Conversion functions"); overflow gives
  *   infinity (RNE) or the largest finite value (RZ); an exact-zero sum gives +0.0.
+ *   out_mant_bits = 13 with out_round = RZ is RZ-E8M13 of the same table: binary32 with the
+ *   low 10 mantissa bits cut toward zero (D still holds binary32 patterns).
  * ftz_in : subnormal A, B and C inputs are replaced by +0.0 first (Algorithm
  *          "Phi_FTZ-AddMul", FlushSubnormal).
  * ftz_out: after every group's conversion, |d| < 2^-126 becomes zero of the same
@@ -130,7 +132,7 @@ typedef struct {
     uint32_t c_mode;
     uint32_t frac_bits2;    /* F2 (the two RD modes); must be 0 in the other modes */
     uint32_t out_round;
-    uint32_t out_mant_bits; /* 23 (FP32 output); other values reserved */
+    uint32_t out_mant_bits; /* 23 (FP32 output) or 13 (E8M13, RZ only) */
     uint32_t ftz_in, ftz_out;
     uint32_t nan_bits;
     uint32_t split;                  /* MMAEMU_SPLIT_*; C_AFTER_RD only */

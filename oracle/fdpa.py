@@ -20,6 +20,7 @@ Follows the paper's Sec. 4.1.3:
                             maximum and added; then as TR-FDPA, with the accumulator's
                             term dropped when e_c < E - F - 1.
   * Sec. 4.2, last paragraph: in TR-FDPA a product of magnitude >= 2^128 overflows to infinity.
+  * Table "Conversion functions": RNE-FP32, RZ-FP32 and RZ-E8M13 (out_mant_bits = 13).
   * Algorithm "FTZ-Add/Mul": output flush  |z| < 2^-126 -> zero of the same sign.
   * Algorithm "Phi_FTZ-AddMul" (its FlushSubnormal lines): input subnormals -> +0.0.
 
@@ -75,6 +76,7 @@ class ModelParams:
     align_round: int = ALIGN_RZ
     c_mode: int = C_IN_GROUP
     out_round: int = RNE        # rho: RNE-FP32 or RZ-FP32
+    out_mant_bits: int = 23     # 13 with out_round = RZ: rho = RZ-E8M13 (binary32 with 13 mantissa bits)
     ftz_in: bool = False
     ftz_out: bool = False
     nan_bits: int = DEFAULT_NAN
@@ -239,8 +241,15 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb):
     else:
         raise ValueError(p.c_mode)
 
-    # Step 3: convert
-    d = _flush_out(p, to_fp32(V, p.out_round))
+    # Step 3: convert (Table "Conversion functions")
+    d = to_fp32(V, p.out_round)
+    if p.out_mant_bits == 13:
+        if p.out_round != RZ:
+            raise ValueError("E8M13 is defined with round-to-zero only")
+        d &= 0xFFFFFC00                  # RZ to 13 mantissa bits = RZ to 23 bits, then the low 10 bits cut (also toward zero)
+    elif p.out_mant_bits != 23:
+        raise ValueError("out_mant_bits must be 23 or 13")
+    d = _flush_out(p, d)
     if p.zero_result_positive and (d & 0x7FFFFFFF) == 0:
         d = 0
     return d

@@ -37,6 +37,7 @@ struct ModelArgs {
     int32_t Fm, Fc;      // merge and accumulator precisions, already defaulted to F
     uint32_t f2_at_leading_bit, skip_zero_terms, zero_result_positive;
     int32_t sum_drop_distance;
+    uint32_t out_mask;   // 0xFFFFFFFF, or 0xFFFFFC00 for the E8M13 output conversion
 };
 
 // error plumbing (api.hip)

@@ -137,6 +137,7 @@ __device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, bool 
 
 __device__ __forceinline__ uint32_t finish_group(const ModelArgs &p, uint32_t d)
 {
+    d &= p.out_mask;                                     // RZ-E8M13: low mantissa bits cut (toward zero, like RZ itself)
     if (p.ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
     if (p.zero_result_positive && (d & 0x7FFFFFFFu) == 0) d = 0u;
     return d;

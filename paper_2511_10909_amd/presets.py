@@ -28,6 +28,8 @@ PAPER = {
     ("ampere", "fp16"): _t(8, 24, mm.RZ),
     ("ada", "bf16"): _t(8, 24, mm.RZ),
     ("ada", "fp16"): _t(8, 24, mm.RZ),
+    ("ada", "fp8"): dict(_t(16, 13, mm.RZ), out_mant_bits=13),          # rho = RZ-E8M13
+    ("hopper", "fp8"): dict(_t(32, 13, mm.RZ), out_mant_bits=13),
     ("hopper", "bf16"): _t(16, 25, mm.RZ),
     ("hopper", "fp16"): _t(16, 25, mm.RZ),
     ("blackwell", "bf16"): _t(16, 25, mm.RZ),

@@ -33,7 +33,7 @@ def gpu_emulate(mm, p, A, B, C, ta, tb):
                         acc_special_truncation=p.acc_special_truncation, frac_bits_merge=p.frac_bits_merge,
                         frac_bits_acc=p.frac_bits_acc, f2_at_leading_bit=p.f2_at_leading_bit,
                         skip_zero_terms=p.skip_zero_terms, zero_result_positive=p.zero_result_positive,
-                        sum_drop_distance=p.sum_drop_distance, family=p.family)
+                        sum_drop_distance=p.sum_drop_distance, family=p.family, out_mant_bits=p.out_mant_bits)
     try:
         dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(np.uint32))
         dD = dev_empty((nb, m, n), np.uint32)
@@ -73,6 +73,8 @@ def test_emulate_random_parameters(mm, ta, tb):
         p = ModelParams(group_len=L, frac_bits=F, c_mode=int(rng.integers(0, 2)), out_round=int(rng.integers(0, 2)),
                         ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)),
                         nan_bits=0x7FFFFFFF if trial % 3 == 0 else 0x7FC00000)
+        if p.out_round == RZ and trial % 2:
+            p = p.with_(out_mant_bits=13)
         if p.c_mode == C_AFTER_EXACT and F > 30:
             p = p.with_(frac_bits=30)       # limit of the C oracle for this mode
         m, n = int(rng.integers(1, 40)), int(rng.integers(1, 40))

@@ -391,3 +391,26 @@ def test_group_length_rules():
         emulate_element(p, [one] * 12, [one] * 12, 0, fm.FP16, fm.FP16)   # K % L != 0 is rejected
     # L = min(K, L_max)
     assert bits_f32(emulate_element(ModelParams(group_len=64), [one] * 16, [one] * 16, 0, fm.FP16, fm.FP16)) == 16.0
+
+
+def test_rz_e8m13_conversion():
+    # Table "Conversion functions": RZ-E8M13 keeps 13 mantissa bits, toward zero
+    from oracle.rounding import RZ as _RZ
+    p = ModelParams(group_len=2, frac_bits=30, out_round=_RZ, out_mant_bits=13)
+    one = fp16_bits(1.0)
+    # 1 + 2^-13 + 2^-14: the 2^-14 part is cut; negative likewise toward zero
+    a, b = [one, fp16_bits(2.0 ** -13 + 2.0 ** -14)], [one, one]
+    assert bits_f32(fdpa_group(p, a, b, 0, fm.FP16, fm.FP16)) == 1.0 + 2.0 ** -13
+    a = [fp16_bits(-1.0), fp16_bits(-(2.0 ** -13 + 2.0 ** -14))]
+    assert bits_f32(fdpa_group(p, a, b, 0, fm.FP16, fm.FP16)) == -(1.0 + 2.0 ** -13)
+    # every result has its low 10 bits clear, and equals the RZ-FP32 result cut there
+    rng = np.random.default_rng(2)
+    for _ in range(200):
+        a = synth.random_bits(rng, 2, fm.FP16).tolist()
+        b = synth.random_bits(rng, 2, fm.FP16).tolist()
+        c = int(synth.narrow_exponent_bits(rng, 1, fm.FP32, 100, 150)[0])
+        d13 = fdpa_group(p, a, b, c, fm.FP16, fm.FP16)
+        d23 = fdpa_group(p.with_(out_mant_bits=23), a, b, c, fm.FP16, fm.FP16)
+        assert d13 == d23 & 0xFFFFFC00
+    with pytest.raises(ValueError):
+        fdpa_group(p.with_(out_round=RNE), a, b, c, fm.FP16, fm.FP16)

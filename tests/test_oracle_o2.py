@@ -41,6 +41,8 @@ def test_o2_equals_rational_oracle_random(ta, tb):
                         nan_bits=0x7FFFFFFF if trial % 3 == 0 else 0x7FC00000)
         if p.c_mode == C_AFTER_EXACT and p.frac_bits > 32:
             p = p.with_(frac_bits=32)
+        if p.out_round == RZ and trial % 2:
+            p = p.with_(out_mant_bits=13)
         # accumulators near the products' range half of the time, anywhere otherwise
         c_exp = (90, 165) if trial % 2 else None
         A, B, C = _case(rng, ta, tb, 2, 3, 4, k, special_frac=0.02 if trial % 4 == 0 else 0.0, c_exp=c_exp)
