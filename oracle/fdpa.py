@@ -21,6 +21,10 @@ Follows the paper's Sec. 4.1.3:
                             term dropped when e_c < E - F - 1.
   * Sec. 4.2, last paragraph: in TR-FDPA a product of magnitude >= 2^128 overflows to infinity.
   * Table "Conversion functions": RNE-FP32, RZ-FP32 and RZ-E8M13 (out_mant_bits = 13).
+  * Algorithm "ST-FDPA"   : T-FDPA on block-scaled operands: every product also takes Exp(alpha) + Exp(beta)
+                            of its block's E8M0 scales (value 2^(x - 127), pattern 0xFF is NaN) into e_k.
+                            Here the scales are optional arguments of every accumulation mode, one pair per
+                            `block` consecutive k.
   * Algorithm "FTZ-Add/Mul": output flush  |z| < 2^-126 -> zero of the same sign.
   * Algorithm "Phi_FTZ-AddMul" (its FlushSubnormal lines): input subnormals -> +0.0.
 
@@ -109,14 +113,14 @@ def _rd_frac(x, F):
     return Fraction(n, 1 << F)
 
 
-def _specials(p, da, db, dc):
+def _specials(p, da, db, dc, scale_exp=None):
     """Sec. 4.2.  Returns output bits if the group's result is NaN or infinite, else None."""
     if dc.cls == fm.NAN or any(x.cls == fm.NAN for x in da) or any(x.cls == fm.NAN for x in db):
         return p.nan_bits
     pos_inf = neg_inf = False
-    for x, y in zip(da, db):
+    for k, (x, y) in enumerate(zip(da, db)):
         if p.c_mode in (C_AFTER_RD, C_AFTER_RD_EVEN_ODD) and x.finite and y.finite \
-                and abs(x.value * y.value) >= Fraction(2) ** 128:
+                and abs(x.value * y.value) * Fraction(2) ** (scale_exp[k] if scale_exp is not None else 0) >= Fraction(2) ** 128:
             # TR-FDPA: the multiplication result overflows to infinity
             if x.sign ^ y.sign:
                 neg_inf = True
@@ -150,10 +154,13 @@ def _flush_out(p, d):
     return d
 
 
-def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb):
-    """One FDPA operation on L = len(a_bits) products and the accumulator c (FP32 bits)."""
+def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None):
+    """One FDPA operation on L = len(a_bits) products and the accumulator c (FP32 bits).  scale_exp: None, or per
+    product the sum Exp(alpha) + Exp(beta) of its block scales (Algorithm "ST-FDPA"; None entries mean a NaN scale)."""
     L = len(a_bits)
     assert len(b_bits) == L and L >= 1
+    if scale_exp is not None and any(x is None for x in scale_exp):
+        return p.nan_bits                              # a NaN scale factor
     if p.c_mode == C_AFTER_RD_EVEN_ODD:       # the paper's GTR-FDPA, by name
         p = p.with_(c_mode=C_AFTER_RD, split=SPLIT_EVEN_ODD, acc_special_truncation=True)
     if p.align_round != ALIGN_RZ:
@@ -167,13 +174,15 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb):
     db = [fm.decode(x, tb) for x in b_bits]
     dc = fm.decode(c_bits, fm.FP32)
 
-    sp = _specials(p, da, db, dc)
+    sp = _specials(p, da, db, dc, scale_exp)
     if sp is not None:
         return sp
 
     # Step 1: exact products
     s = [da[k].signed_sig * db[k].signed_sig for k in range(L)]
     e = [da[k].exp + db[k].exp for k in range(L)]
+    if scale_exp is not None:
+        e = [e[k] + scale_exp[k] for k in range(L)]    # ST-FDPA: + Exp(alpha) + Exp(beta)
 
     if p.c_mode == C_IN_GROUP:
         # Step 2: truncated fused sum of L+1 terms
@@ -262,23 +271,34 @@ def group_length(p, K):
     return L
 
 
-def emulate_element(p, a_bits, b_bits, c_bits, ta, tb):
+def emulate_element(p, a_bits, b_bits, c_bits, ta, tb, sa=None, sb=None, block=32):
     """Algorithm "Phi_FDPA" for one output element: chain over K/L groups.  (family = FAMILY_FTZ_ADDMUL:
-    Algorithm "Phi_FTZ-AddMul" with P = group_len instead.)"""
+    Algorithm "Phi_FTZ-AddMul" with P = group_len instead.)  sa, sb: E8M0 scale bytes of this row of A and of B,
+    one per `block` consecutive k (both or neither)."""
     if p.family == FAMILY_FTZ_ADDMUL:
+        if sa is not None:
+            raise ValueError("block scales belong to the FDPA family")
         from . import addmul
         return addmul.emulate_element(p.group_len, a_bits, b_bits, c_bits, ta, tb, p.nan_bits)
     K = len(a_bits)
     L = group_length(p, K)
+    scale_exp = None
+    if sa is not None:
+        if K % block or len(sa) != K // block or len(sb) != K // block:
+            raise ValueError("one scale per block of %d" % block)
+        scale_exp = [None if (int(sa[k // block]) == 0xFF or int(sb[k // block]) == 0xFF)
+                     else (int(sa[k // block]) - 127) + (int(sb[k // block]) - 127) for k in range(K)]
     d = int(c_bits)
     for k in range(0, K, L):
-        d = fdpa_group(p, [int(x) for x in a_bits[k:k + L]], [int(x) for x in b_bits[k:k + L]], d, ta, tb)
+        d = fdpa_group(p, [int(x) for x in a_bits[k:k + L]], [int(x) for x in b_bits[k:k + L]], d, ta, tb,
+                       None if scale_exp is None else scale_exp[k:k + L])
     return d
 
 
-def emulate_mma(p, A, B, C, ta, tb):
+def emulate_mma(p, A, B, C, ta, tb, SA=None, SB=None, block=32):
     """A[batch][m][k], B[batch][n][k] (both K-contiguous), C[batch][m][n] as raw bit
-    patterns (any integer dtype); returns D[batch][m][n] as uint32 FP32 bits."""
+    patterns (any integer dtype); returns D[batch][m][n] as uint32 FP32 bits.
+    SA[batch][m][k/block], SB[batch][n][k/block]: optional E8M0 block scales (Algorithm "ST-FDPA")."""
     A = np.asarray(A)
     B = np.asarray(B)
     C = np.asarray(C)
@@ -292,7 +312,11 @@ def emulate_mma(p, A, B, C, ta, tb):
         for i in range(m):
             ai = A[t, i].tolist()
             for j in range(n):
-                D[t, i, j] = emulate_element(p, ai, B[t, j].tolist(), int(C[t, i, j]), ta, tb)
+                if SA is None:
+                    D[t, i, j] = emulate_element(p, ai, B[t, j].tolist(), int(C[t, i, j]), ta, tb)
+                else:
+                    D[t, i, j] = emulate_element(p, ai, B[t, j].tolist(), int(C[t, i, j]), ta, tb,
+                                                 np.asarray(SA)[t, i].tolist(), np.asarray(SB)[t, j].tolist(), block)
     return D
 
 

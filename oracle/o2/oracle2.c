@@ -172,7 +172,7 @@ static dec_t dec_in(const o2_params *p, uint32_t bits, int t)
 
 /* maximum exponent over the products first, first+stride, ... (count of them); returns 0 when
  * no product takes part (count = 0, or all significands zero and skip_zero_terms set) */
-static int part_emax(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t first, uint32_t stride,
+static int part_emax(const o2_params *p, const uint32_t *a, const uint32_t *b, const int *se, uint32_t first, uint32_t stride,
                      uint32_t count, int ta, int tb, int *emax)
 {
     int any = 0;
@@ -180,7 +180,7 @@ static int part_emax(const o2_params *p, const uint32_t *a, const uint32_t *b, u
         uint32_t k = first + q * stride;
         dec_t x = dec_in(p, a[k], ta), y = dec_in(p, b[k], tb);
         if (p->skip_zero_terms && (x.sig == 0 || y.sig == 0)) continue;
-        int e = x.exp + y.exp;
+        int e = x.exp + y.exp + (se ? se[k] : 0);               /* ST-FDPA: + Exp(alpha) + Exp(beta) */
         if (!any || e > *emax) *emax = e;
         any = 1;
     }
@@ -188,7 +188,7 @@ static int part_emax(const o2_params *p, const uint32_t *a, const uint32_t *b, u
 }
 
 /* sum of the same products, each aligned to units of 2^unit with truncation toward zero */
-static i128 part_sum(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t first, uint32_t stride,
+static i128 part_sum(const o2_params *p, const uint32_t *a, const uint32_t *b, const int *se, uint32_t first, uint32_t stride,
                      uint32_t count, int ta, int tb, int unit)
 {
     i128 S = 0;
@@ -196,7 +196,7 @@ static i128 part_sum(const o2_params *p, const uint32_t *a, const uint32_t *b, u
         uint32_t k = first + q * stride;
         dec_t x = dec_in(p, a[k], ta), y = dec_in(p, b[k], tb);
         u128 prod = (u128)((uint64_t)x.sig * (uint64_t)y.sig);      /* exact product of significands */
-        int e = x.exp + y.exp;                                       /* sum of exponents */
+        int e = x.exp + y.exp + (se ? se[k] : 0);                    /* sum of exponents (and of the scales') */
         u128 al = align_rz(prod, e - FMT[ta].mbits - FMT[tb].mbits, unit);
         if (x.sign ^ y.sign) S -= (i128)al; else S += (i128)al;
     }
@@ -247,9 +247,12 @@ static uint32_t finish(const o2_params *p, uint32_t d)
     return d;
 }
 
-static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t *b, uint32_t c,
+#define SCALE_NAN (-100000)          /* entry of the scale-exponent array for a NaN scale (E8M0 pattern 0xFF) */
+
+static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t *b, const int *se, uint32_t c,
                            uint32_t L, int ta, int tb)
 {
+    if (se) for (uint32_t k = 0; k < L; ++k) if (se[k] == SCALE_NAN) return p->nan_bits;
     const int F = (int)p->frac_bits;
     const int fa = FMT[ta].mbits, fb = FMT[tb].mbits;
     uint32_t c_mode = p->c_mode, split = p->split, trunc = p->acc_special_truncation;
@@ -266,7 +269,7 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
             else if (x.sign ^ y.sign) ninf = 1; else pinf = 1;
         } else if (c_mode == C_AFTER_RD) {                            /* product overflow, Sec. 4.2 */
             uint64_t prod = (uint64_t)x.sig * (uint64_t)y.sig;
-            if (prod && bitlen128((u128)prod) - 1 + x.exp + y.exp - fa - fb >= 128) { if (x.sign ^ y.sign) ninf = 1; else pinf = 1; }
+            if (prod && bitlen128((u128)prod) - 1 + x.exp + y.exp + (se ? se[k] : 0) - fa - fb >= 128) { if (x.sign ^ y.sign) ninf = 1; else pinf = 1; }
         }
     }
     if (dc.cls == CLS_INF) { if (dc.sign) ninf = 1; else pinf = 1; }
@@ -277,8 +280,8 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
     if (c_mode == C_AFTER_RD) {
         if (split == 0) {
             int emax = 0;
-            int have = part_emax(p, a, b, 0, 1, L, ta, tb, &emax);
-            i128 T = have ? part_sum(p, a, b, 0, 1, L, ta, tb, emax - F) : 0;
+            int have = part_emax(p, a, b, se, 0, 1, L, ta, tb, &emax);
+            i128 T = have ? part_sum(p, a, b, se, 0, 1, L, ta, tb, emax - F) : 0;
             return finish(p, rounded_sum_with_c(p, have, T, emax, emax - F, dc, (int)trunc));
         }
         /* two sub-groups: even / odd products (split 1) or first / second half (split 2) */
@@ -287,9 +290,9 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
         int e_part[2] = {0, 0}, have[2], emax = 0, any = 0;
         i128 T_part[2] = {0, 0};
         for (int g = 0; g < 2; ++g) {
-            have[g] = part_emax(p, a, b, first[g], stride, L / 2, ta, tb, &e_part[g]);
+            have[g] = part_emax(p, a, b, se, first[g], stride, L / 2, ta, tb, &e_part[g]);
             if (!have[g]) continue;
-            T_part[g] = part_sum(p, a, b, first[g], stride, L / 2, ta, tb, e_part[g] - F);
+            T_part[g] = part_sum(p, a, b, se, first[g], stride, L / 2, ta, tb, e_part[g] - F);
             if (!any || e_part[g] > emax) emax = e_part[g];
             any = 1;
         }
@@ -300,13 +303,13 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
     }
 
     int emax = 0;
-    int have = part_emax(p, a, b, 0, 1, L, ta, tb, &emax);
+    int have = part_emax(p, a, b, se, 0, 1, L, ta, tb, &emax);
     if (c_mode == C_IN_GROUP) {
         const int c_live = !(p->skip_zero_terms && dc.sig == 0);
         if (!have && !c_live) return 0u;
         if (c_live && (!have || dc.exp > emax)) emax = dc.exp;
         const int unit = emax - F;
-        i128 S = part_sum(p, a, b, 0, 1, L, ta, tb, unit);
+        i128 S = part_sum(p, a, b, se, 0, 1, L, ta, tb, unit);
         u128 al = align_rz((u128)dc.sig, dc.exp - 23, unit);
         if (dc.sign) S -= (i128)al; else S += (i128)al;
         int neg = S < 0;
@@ -315,7 +318,7 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
     /* C_AFTER_EXACT */
     if (!have) emax = 0;
     const int unit = emax - F;
-    i128 S = part_sum(p, a, b, 0, 1, L, ta, tb, unit);
+    i128 S = part_sum(p, a, b, se, 0, 1, L, ta, tb, unit);
     int neg = S < 0;
     return finish(p, add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, (int)p->out_round));
 }
@@ -411,36 +414,46 @@ static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out
     return 0;
 }
 
+/* block scales of the call (NULL pointers: none): SA[rows of A][k / block], SB[rows of B][k / block], E8M0 bytes */
+typedef struct { const uint8_t *sa, *sb; uint32_t block; } scales_t;
+static const scales_t NO_SCALES = {0, 0, 1};
+
 static uint32_t element(const o2_params *p, const void *A, const void *B, uint32_t c,
                         size_t arow, size_t brow, uint32_t k, uint32_t L, int ta, int tb,
-                        uint32_t *abuf, uint32_t *bbuf)
+                        uint32_t *abuf, uint32_t *bbuf, int *sebuf, scales_t sc)
 {
     uint32_t d = c;
     for (uint32_t k0 = 0; k0 < k; k0 += L) {
         for (uint32_t q = 0; q < L; ++q) {
             abuf[q] = load_elem(A, arow + k0 + q, ta);
             bbuf[q] = load_elem(B, brow + k0 + q, tb);
+            if (sc.sa) {
+                uint32_t xa = sc.sa[(arow / k) * (k / sc.block) + (k0 + q) / sc.block];
+                uint32_t xb = sc.sb[(brow / k) * (k / sc.block) + (k0 + q) / sc.block];
+                sebuf[q] = (xa == 0xFF || xb == 0xFF) ? SCALE_NAN : ((int)xa - 127) + ((int)xb - 127);
+            }
         }
-        d = fdpa_group(p, abuf, bbuf, d, L, ta, tb);
+        d = fdpa_group(p, abuf, bbuf, sc.sa ? sebuf : 0, d, L, ta, tb);
     }
     return d;
 }
 
 /* D[b][i][j] for A[b][m][k], B[b][n][k], C[b][m][n].  Returns 0, or a negative code
  * (-2 unsupported parameter, -3 bad shape).  *threads_used receives the team size. */
-int o2_emulate_mma(const o2_params *p, const void *A, const void *B, const uint32_t *C, uint32_t *D,
-                   uint32_t m, uint32_t n, uint32_t k, uint64_t batch, int ta, int tb,
-                   int nthreads, int *threads_used)
+static int emulate_mma_impl(const o2_params *p, const void *A, const void *B, const uint32_t *C, uint32_t *D,
+                            uint32_t m, uint32_t n, uint32_t k, uint64_t batch, int ta, int tb,
+                            int nthreads, int *threads_used, scales_t sc)
 {
     uint32_t L;
     int rc = check(p, k, ta, tb, &L);
     if (rc) return rc;
+    if (sc.sa && (p->family != 0 || sc.block == 0 || k % sc.block)) return -3;
     if (nthreads > 0) omp_set_num_threads(nthreads);
     int used = 1;
     int64_t rows = (int64_t)batch * m;
 #pragma omp parallel
     {
-        uint32_t abuf[L], bbuf[L];
+        uint32_t abuf[L], bbuf[L]; int sebuf[L];
 #pragma omp single
         used = omp_get_num_threads();
 #pragma omp for schedule(dynamic, 4)
@@ -449,12 +462,30 @@ int o2_emulate_mma(const o2_params *p, const void *A, const void *B, const uint3
             for (uint32_t j = 0; j < n; ++j) {
                 size_t o = ((size_t)t * m + i) * n + j;
                 D[o] = p->family == 1 ? addmul_element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, ta, tb)
-                                      : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
+                                      : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf, sebuf, sc);
             }
         }
     }
     if (threads_used) *threads_used = used;
     return 0;
+}
+
+int o2_emulate_mma(const o2_params *p, const void *A, const void *B, const uint32_t *C, uint32_t *D,
+                   uint32_t m, uint32_t n, uint32_t k, uint64_t batch, int ta, int tb,
+                   int nthreads, int *threads_used)
+{
+    return emulate_mma_impl(p, A, B, C, D, m, n, k, batch, ta, tb, nthreads, threads_used, NO_SCALES);
+}
+
+/* Algorithm "ST-FDPA": the same with E8M0 block scales SA[batch][m][k / block], SB[batch][n][k / block]. */
+int o2_emulate_mma_scaled(const o2_params *p, const void *A, const void *B, const uint32_t *C, uint32_t *D,
+                          const uint8_t *SA, const uint8_t *SB, uint32_t block,
+                          uint32_t m, uint32_t n, uint32_t k, uint64_t batch, int ta, int tb,
+                          int nthreads, int *threads_used)
+{
+    scales_t sc = {SA, SB, block};
+    if (!SA || !SB) return -3;
+    return emulate_mma_impl(p, A, B, C, D, m, n, k, batch, ta, tb, nthreads, threads_used, sc);
 }
 
 /* The same, only at the flattened output indices idx[0..count) (index = (b*m + i)*n + j). */
@@ -471,7 +502,7 @@ int o2_emulate_sample(const o2_params *p, const void *A, const void *B, const ui
     int used = 1;
 #pragma omp parallel
     {
-        uint32_t abuf[L], bbuf[L];
+        uint32_t abuf[L], bbuf[L]; int sebuf[L]; const scales_t sc = NO_SCALES;
 #pragma omp single
         used = omp_get_num_threads();
 #pragma omp for schedule(dynamic, 16)
@@ -480,7 +511,7 @@ int o2_emulate_sample(const o2_params *p, const void *A, const void *B, const ui
             uint64_t t = o / ((uint64_t)m * n);
             uint32_t i = (uint32_t)((o / n) % m), j = (uint32_t)(o % n);
             D_sample[s] = p->family == 1 ? addmul_element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, ta, tb)
-                                         : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf);
+                                         : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf, sebuf, sc);
         }
     }
     if (threads_used) *threads_used = used;

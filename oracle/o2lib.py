@@ -74,6 +74,22 @@ def emulate_mma(p, A, B, C, ta, tb, nthreads=0):
     return D, used.value
 
 
+def emulate_mma_scaled(p, A, B, C, SA, SB, block, ta, tb, nthreads=0):
+    """Algorithm "ST-FDPA": as emulate_mma with E8M0 block scales SA[batch][m][k/block], SB[batch][n][k/block]."""
+    A, B, C, nb, m, n, k = _prep(A, B, C, ta, tb)
+    SA = np.ascontiguousarray(np.asarray(SA).astype(np.uint8, copy=False)).reshape(nb, m, k // block)
+    SB = np.ascontiguousarray(np.asarray(SB).astype(np.uint8, copy=False)).reshape(nb, n, k // block)
+    D = np.empty((nb, m, n), dtype=np.uint32)
+    used = ctypes.c_int(0)
+    pp = _params(p)
+    rc = _load().o2_emulate_mma_scaled(ctypes.byref(pp), _vp(A), _vp(B), _vp(C), _vp(D), _vp(SA), _vp(SB), ctypes.c_uint32(block),
+                                       ctypes.c_uint32(m), ctypes.c_uint32(n), ctypes.c_uint32(k),
+                                       ctypes.c_uint64(nb), ta, tb, nthreads, ctypes.byref(used))
+    if rc:
+        raise ValueError("o2_emulate_mma_scaled failed: %d" % rc)
+    return D, used.value
+
+
 def emulate_sample(p, A, B, C, idx, ta, tb, nthreads=0):
     """D at flattened indices idx (index = (b*m + i)*n + j)."""
     A, B, C, nb, m, n, k = _prep(A, B, C, ta, tb)
