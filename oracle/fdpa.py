@@ -51,10 +51,12 @@ algorithms):
   * acc_special_truncation: the special truncation of GTR-FDPA as a switch of its own;
   * skip_zero_terms: terms whose significand is zero take no part in any exponent maximum;
   * f2_at_leading_bit: the sum T 2^(e_max - E) + s_c' is formed exactly and then rounded down to
-    F2 fractional bits counted below its own leading bit (not below 2^E);
+    F2 fractional bits counted below its own leading bit (not below 2^E), or below 2^-126 for a smaller sum;
   * zero_result_positive: a result that rounds (or is flushed) to zero is +0.0;
   * sum_drop_distance (n > 0): the counterpart of the special truncation for the product sum: T' = 0 when
-    E - e_max >= n.
+    E - e_max >= n;
+  * wide_products: a product of magnitude 2^128 or more keeps its value instead of counting as an infinity
+    (overflow then happens only where a group's sum is converted).
 """
 from dataclasses import dataclass, replace
 from fractions import Fraction
@@ -92,6 +94,7 @@ class ModelParams:
     f2_at_leading_bit: bool = False
     zero_result_positive: bool = False
     sum_drop_distance: int = 0
+    wide_products: bool = False
     family: int = FAMILY_FDPA
 
     def with_(self, **kw):
@@ -119,7 +122,7 @@ def _specials(p, da, db, dc, scale_exp=None):
         return p.nan_bits
     pos_inf = neg_inf = False
     for k, (x, y) in enumerate(zip(da, db)):
-        if p.c_mode in (C_AFTER_RD, C_AFTER_RD_EVEN_ODD) and x.finite and y.finite \
+        if p.c_mode in (C_AFTER_RD, C_AFTER_RD_EVEN_ODD) and not p.wide_products and x.finite and y.finite \
                 and abs(x.value * y.value) * Fraction(2) ** (scale_exp[k] if scale_exp is not None else 0) >= Fraction(2) ** 128:
             # TR-FDPA: the multiplication result overflows to infinity
             if x.sign ^ y.sign:
@@ -242,7 +245,7 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None):
         if p.f2_at_leading_bit:
             S = T * Fraction(2) ** (e_max - E) + sc_al
             if S != 0:
-                lead = floor_log2(abs(S))
+                lead = max(floor_log2(abs(S)), -126 - E)          # S counts units of 2^E; binary32's smallest normal exponent
                 S = _rd_frac(S * Fraction(2) ** (-lead), F2) * Fraction(2) ** lead
         else:
             S = _rd_frac(T * Fraction(2) ** (e_max - E), F2) + sc_al

@@ -44,6 +44,7 @@ typedef struct {
     uint32_t sum_drop_distance;
     uint32_t family;     /* 0: chained FDPA, 1: FTZ-AddMul with P = group_len */
     uint32_t out_mant_bits; /* 23, or 13 (RZ-E8M13, with out_round = RZ) */
+    uint32_t wide_products; /* RD mode: no infinity from a single product of magnitude >= 2^128 */
 } o2_params;
 
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
@@ -229,6 +230,7 @@ static uint32_t rounded_sum_with_c(const o2_params *p, int have_T, i128 T, int e
         S = T * ((i128)1 << (unit_T - unit)) + sc2 * ((i128)1 << (unit_c - unit));
         if (S == 0) return 0u;
         int lead = bitlen128((u128)(S < 0 ? -S : S)) - 1 + unit;
+        if (lead < -126) lead = -126;                     /* no lower than binary32's smallest normal exponent */
         if (lead - F2 > unit) { S = align_rd(S, unit, lead - F2); unit = lead - F2; }
     } else {
         i128 T2 = align_rd(T, unit_T, E - F2);
@@ -267,7 +269,7 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
         else if (x.cls == CLS_INF || y.cls == CLS_INF) {
             if (x.cls == CLS_ZERO || y.cls == CLS_ZERO) any_nan = 1;
             else if (x.sign ^ y.sign) ninf = 1; else pinf = 1;
-        } else if (c_mode == C_AFTER_RD) {                            /* product overflow, Sec. 4.2 */
+        } else if (c_mode == C_AFTER_RD && !p->wide_products) {       /* product overflow, Sec. 4.2 */
             uint64_t prod = (uint64_t)x.sig * (uint64_t)y.sig;
             if (prod && bitlen128((u128)prod) - 1 + x.exp + y.exp + (se ? se[k] : 0) - fa - fb >= 128) { if (x.sign ^ y.sign) ninf = 1; else pinf = 1; }
         }

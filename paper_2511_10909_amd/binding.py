@@ -20,6 +20,8 @@ SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
 (MFMA_F32_16X16X16_F16, MFMA_F32_16X16X16_BF16, MFMA_F32_32X32X8_F16, MFMA_F32_32X32X8_BF16,
  MFMA_F32_16X16X32_F16, MFMA_F32_16X16X32_BF16, MFMA_F32_16X16X32_FP8_FP8, MFMA_F32_16X16X32_FP8_BF8,
  MFMA_F32_16X16X32_BF8_FP8, MFMA_F32_16X16X32_BF8_BF8) = range(10)
+(MFMA_SCALE_F32_16X16X128_FP8_FP8, MFMA_SCALE_F32_16X16X128_FP8_BF8, MFMA_SCALE_F32_16X16X128_BF8_FP8,
+ MFMA_SCALE_F32_16X16X128_BF8_BF8) = range(10, 14)
 ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4}
 NO_MISMATCH = (1 << 64) - 1
 
@@ -35,7 +37,7 @@ class ModelParams(ctypes.Structure):
                 ("struct_size", "group_len", "frac_bits", "align_round", "c_mode", "frac_bits2", "out_round",
                  "out_mant_bits", "ftz_in", "ftz_out", "nan_bits", "split", "acc_special_truncation",
                  "frac_bits_merge", "frac_bits_acc", "f2_at_leading_bit", "skip_zero_terms", "zero_result_positive",
-                 "sum_drop_distance", "family")]
+                 "sum_drop_distance", "family", "wide_products")]
 
 
 class Dtypes(ctypes.Structure):
@@ -83,11 +85,13 @@ _lib.mmaemu_model_create.argtypes = [ctypes.POINTER(ModelParams), ctypes.POINTER
 _lib.mmaemu_model_destroy.argtypes = [_vp]
 _lib.mmaemu_model_get_params.argtypes = [_vp, ctypes.POINTER(ModelParams)]
 _lib.mmaemu_emulate_mma.argtypes = [_vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u64, Dtypes, _vp]
+_lib.mmaemu_emulate_mma_scaled.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _u64, Dtypes, _vp]
 _lib.mmaemu_stats_reset.argtypes = [_vp, _vp]
 _lib.mmaemu_compare.argtypes = [_vp, _vp, _u64, _u64, ctypes.c_int, _vp, _vp]
 _lib.mmaemu_generate.argtypes = [ctypes.POINTER(GenParams), _vp, ctypes.c_int, _u64, _u64, _u64, _vp, _vp]
 _lib.mmaemu_mfma_info.argtypes = [ctypes.c_int] + [ctypes.POINTER(_u32)] * 3 + [ctypes.POINTER(ctypes.c_int)] * 2
 _lib.mmaemu_mfma_probe.argtypes = [ctypes.c_int, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
+_lib.mmaemu_mfma_probe_scaled.argtypes = [ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
 _lib.mmaemu_err_stats_reset.argtypes = [_vp, _vp]
 _lib.mmaemu_exact_dot_sample.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, Dtypes, _u64, _vp, _vp]
 
@@ -135,11 +139,11 @@ def model_create(group_len=0, frac_bits=24, c_mode=C_IN_GROUP, out_round=RNE, ft
                  nan_bits=0x7FC00000, align_round=0, frac_bits2=0, out_mant_bits=23, struct_size=None,
                  split=SPLIT_NONE, acc_special_truncation=False, frac_bits_merge=0, frac_bits_acc=0,
                  f2_at_leading_bit=False, skip_zero_terms=False, zero_result_positive=False, sum_drop_distance=0,
-                 family=FAMILY_FDPA):
+                 family=FAMILY_FDPA, wide_products=False):
     p = ModelParams(ctypes.sizeof(ModelParams) if struct_size is None else struct_size, group_len, frac_bits,
                     align_round, c_mode, frac_bits2, out_round, out_mant_bits, int(ftz_in), int(ftz_out), nan_bits,
                     split, int(acc_special_truncation), frac_bits_merge, frac_bits_acc, int(f2_at_leading_bit),
-                    int(skip_zero_terms), int(zero_result_positive), sum_drop_distance, family)
+                    int(skip_zero_terms), int(zero_result_positive), sum_drop_distance, family, int(wide_products))
     h = _vp()
     _check(_lib.mmaemu_model_create(ctypes.byref(p), ctypes.byref(h)))
     return h
@@ -158,6 +162,12 @@ def model_get_params(model):
 def emulate_mma(model, A, B, C, D, m, n, k, batch, dtypes, stream=None):
     dt = dtypes if isinstance(dtypes, Dtypes) else Dtypes(*dtypes)
     _check(_lib.mmaemu_emulate_mma(model, _ptr(A), _ptr(B), _ptr(C), _ptr(D), m, n, k, batch, dt, _stream(stream)))
+
+
+def emulate_mma_scaled(model, A, B, C, D, SA, SB, block, m, n, k, batch, dtypes, stream=None):
+    dt = dtypes if isinstance(dtypes, Dtypes) else Dtypes(*dtypes)
+    _check(_lib.mmaemu_emulate_mma_scaled(model, _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(SA), _ptr(SB), block, m, n, k, batch, dt,
+                                          _stream(stream)))
 
 
 def stats_reset(dev_stats, stream=None):
@@ -185,6 +195,10 @@ def mfma_info(instr):
 
 def mfma_probe(instr, A, B, C, D, k, batch, stream=None):
     _check(_lib.mmaemu_mfma_probe(instr, _ptr(A), _ptr(B), _ptr(C), _ptr(D), k, batch, _stream(stream)))
+
+
+def mfma_probe_scaled(instr, A, B, C, D, SA, SB, k, batch, stream=None):
+    _check(_lib.mmaemu_mfma_probe_scaled(instr, _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(SA), _ptr(SB), k, batch, _stream(stream)))
 
 
 def err_stats_reset(dev_err, stream=None):

@@ -27,7 +27,10 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // loaded at once) and group sums below 2^52
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) == 0;
     // the RD mode runs tiled with all of its variations; the two other modes only as the paper has them
-    const bool tiled_mode = p.c_mode == MMAEMU_C_AFTER_RD || (!p.skip_zero_terms && !p.zero_result_positive);
+    // (the tiled kernels tag BF16 products of 2^128 and more as infinities: without that rule such products need
+    // the general kernel's integer range)
+    const bool wide_bf16 = p.wide_products && (ta == MMAEMU_BF16 || tb == MMAEMU_BF16);
+    const bool tiled_mode = (p.c_mode == MMAEMU_C_AFTER_RD && !wide_bf16) || (p.c_mode != MMAEMU_C_AFTER_RD && !p.skip_zero_terms && !p.zero_result_positive);
     if (tiled_mode && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;

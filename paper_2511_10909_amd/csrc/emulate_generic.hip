@@ -16,7 +16,8 @@ template <int TA, int TB>
 __global__ void __launch_bounds__(256)
 emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A,
                        const typename Fmt<TB>::elem *__restrict__ B, const uint32_t *C, uint32_t *D,
-                       uint32_t m, uint32_t n, uint32_t k, uint64_t total)
+                       uint32_t m, uint32_t n, uint32_t k, uint64_t total, const uint8_t *__restrict__ SA,
+                       const uint8_t *__restrict__ SB, uint32_t block)
 {
     const uint64_t mn = (uint64_t)m * n;
     for (uint64_t o = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total;
@@ -27,31 +28,41 @@ emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A
         const typename Fmt<TA>::elem *a = A + (t * m + i) * (uint64_t)k;
         const typename Fmt<TB>::elem *b = B + (t * n + j) * (uint64_t)k;
         uint32_t d = C[o];
-        for (uint32_t k0 = 0; k0 < k; k0 += p.L) d = fdpa_group<TA, TB>(p, a + k0, b + k0, p.L, d);
+        ScaleRef sr = no_scales();
+        if (SA) {                                   // Algorithm "ST-FDPA": this row's and this column's block scales
+            sr.sa = SA + (t * m + i) * (uint64_t)(k / block);
+            sr.sb = SB + (t * n + j) * (uint64_t)(k / block);
+            sr.block = block;
+        }
+        for (uint32_t k0 = 0; k0 < k; k0 += p.L) {
+            sr.k0 = k0;
+            d = fdpa_group<TA, TB>(p, a + k0, b + k0, p.L, d, sr);
+        }
         D[o] = d;
     }
 }
 
 template <int TA, int TB>
 static mmaemu_status launch_t(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
-                              uint32_t m, uint32_t n, uint32_t k, uint64_t batch, hipStream_t s)
+                              uint32_t m, uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, const uint8_t *SA,
+                              const uint8_t *SB, uint32_t block)
 {
     const uint64_t total = batch * m * n;
     uint64_t blocks = (total + 255) / 256;
     if (blocks > (1ull << 22)) blocks = 1ull << 22;     // grid-stride beyond that
     hipLaunchKernelGGL((emulate_generic_kernel<TA, TB>), dim3((uint32_t)blocks), dim3(256), 0, s, p,
                        (const typename Fmt<TA>::elem *)A, (const typename Fmt<TB>::elem *)B,
-                       (const uint32_t *)C, (uint32_t *)D, m, n, k, total);
+                       (const uint32_t *)C, (uint32_t *)D, m, n, k, total, SA, SB, block);
     MMAEMU_HIP(hipGetLastError());
-    set_last_kernel("general");
+    set_last_kernel(SA ? "general, block-scaled" : "general");
     return MMAEMU_OK;
 }
 
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
-                                     uint32_t tb, hipStream_t s)
+                                     uint32_t tb, hipStream_t s, const uint8_t *SA, const uint8_t *SB, uint32_t block)
 {
-#define CASE(X, Y) if (ta == X && tb == Y) return launch_t<X, Y>(p, A, B, C, D, m, n, k, batch, s)
+#define CASE(X, Y) if (ta == X && tb == Y) return launch_t<X, Y>(p, A, B, C, D, m, n, k, batch, s, SA, SB, block)
     CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3); CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2);
     CASE(MMAEMU_FP8_E4M3, MMAEMU_FP16);     CASE(MMAEMU_FP8_E4M3, MMAEMU_BF16);
     CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3); CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2);

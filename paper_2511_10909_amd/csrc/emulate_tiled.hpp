@@ -529,6 +529,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
             int lead = (int)((sbits >> 52) & 0x7FF) - 1023;
             const bool toward_zero = (err != 0.0) && ((err < 0.0) != (sm < 0.0));
             if ((sbits & 0xFFFFFFFFFFFFFll) == 0 && toward_zero) lead -= 1;                      // just inside the binade below
+            lead = lead < -126 ? -126 : lead;                                                     // binary32's smallest normal exponent
             const int unit = lead - p.F2;
             double q = __builtin_floor(ldexp(sm, -unit));
             if (err < 0.0 && ldexp(q, unit) == sm) q -= 1.0;                                      // s on the grid, exact sum just below it

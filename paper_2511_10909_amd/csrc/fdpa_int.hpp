@@ -64,11 +64,26 @@ __device__ __forceinline__ uint32_t round128_to_fp32(uint32_t neg, u128 mag, int
     return round_to_fp32(neg, (uint64_t)(mag >> sh), lsb + sh, lost, mode);
 }
 
+// E8M0 block scales of one row of A and one row of B (Algorithm "ST-FDPA"): sa[q], sb[q] scale the products
+// q * block .. (q + 1) * block - 1 of the row; null pointers mean no scaling.  k0 is the group's first k.
+struct ScaleRef {
+    const uint8_t *sa, *sb;
+    uint32_t block, k0;
+};
+__device__ __forceinline__ ScaleRef no_scales() { return ScaleRef{nullptr, nullptr, 1u, 0u}; }
+// Exp(alpha) + Exp(beta) for product k of the group (0 without scales)
+__device__ __forceinline__ int scale_exp(const ScaleRef &sr, uint32_t k)
+{
+    if (!sr.sa) return 0;
+    const uint32_t q = (sr.k0 + k) / sr.block;
+    return (int)sr.sa[q] + (int)sr.sb[q] - 254;
+}
+
 // One sub-group of products k = first, first + stride, ... (count of them): maximum exponent
 // over the terms that take part, then the sum of the terms aligned at that exponent with F
 // fractional bits, truncated toward zero.  Returns false when no term takes part.
 template <int TA, int TB>
-__device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, const typename Fmt<TB>::elem *b,
+__device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, const typename Fmt<TB>::elem *b, const ScaleRef &sr,
                            uint32_t first, uint32_t stride, uint32_t count, int &emax, int64_t &T)
 {
     constexpr int FA = Fmt<TA>::MB, FB = Fmt<TB>::MB;
@@ -78,7 +93,7 @@ __device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, 
         const uint32_t k = first + q * stride;
         const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
         if (p.skip_zero_terms && (x.sig == 0 || y.sig == 0)) continue;
-        const int e = x.exp + y.exp;
+        const int e = x.exp + y.exp + scale_exp(sr, k);
         emax = (!any || e > emax) ? e : emax;
         any = true;
     }
@@ -89,7 +104,7 @@ __device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, 
         const uint32_t k = first + q * stride;
         const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
         const uint64_t prod = (uint64_t)(x.sig * y.sig);                    // <= 22 bits
-        const int sh = (x.exp + y.exp - FA - FB) - unit;                    // <= F
+        const int sh = (x.exp + y.exp + scale_exp(sr, k) - FA - FB) - unit; // <= F
         const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
         T += (x.sign ^ y.sign) ? -(int64_t)al : (int64_t)al;
     }
@@ -123,7 +138,8 @@ __device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, bool 
         unit = unit_T < unit_c ? unit_T : unit_c;
         S = (i128)((u128)T << (unit_T - unit)) + (i128)((u128)sc2 << (unit_c - unit));
         if (S == 0) return 0u;
-        const int lead = bitlen128((u128)(S < 0 ? -S : S)) - 1 + unit;
+        int lead = bitlen128((u128)(S < 0 ? -S : S)) - 1 + unit;
+        lead = lead < -126 ? -126 : lead;                  // no lower than binary32's smallest normal exponent
         if (lead - p.F2 > unit) { S = align_rd(S, unit, lead - p.F2); unit = lead - p.F2; }
     } else {
         const i128 T2 = align_rd(T, unit_T, E - p.F2);
@@ -145,10 +161,14 @@ __device__ __forceinline__ uint32_t finish_group(const ModelArgs &p, uint32_t d)
 
 template <int TA, int TB>
 __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem *a,
-                               const typename Fmt<TB>::elem *b, uint32_t L, uint32_t c)
+                               const typename Fmt<TB>::elem *b, uint32_t L, uint32_t c, const ScaleRef &sr)
 {
     constexpr int FA = Fmt<TA>::MB, FB = Fmt<TB>::MB;
     const Dec dc = decode<MMAEMU_FP32>(c, p.ftz_in);
+    if (sr.sa) {                                                              // a NaN scale factor (E8M0 pattern 0xFF)
+        for (uint32_t q = sr.k0 / sr.block; q <= (sr.k0 + L - 1) / sr.block; ++q)
+            if (sr.sa[q] == 0xFFu || sr.sb[q] == 0xFFu) return p.nan_bits;
+    }
 
     // special values (Sec. 4.2)
     bool any_nan = dc.cls == CLS_NAN, pinf = false, ninf = false;
@@ -159,9 +179,9 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
             if (x.cls == CLS_ZERO || y.cls == CLS_ZERO) any_nan = true;      // inf * 0
             else if (x.sign ^ y.sign) ninf = true;
             else pinf = true;
-        } else if (p.c_mode == MMAEMU_C_AFTER_RD) {                           // |a b| >= 2^128 is an infinity
+        } else if (p.c_mode == MMAEMU_C_AFTER_RD && !p.wide_products) {       // |a b| >= 2^128 is an infinity
             const uint32_t prod = x.sig * y.sig;
-            if (prod && (31 - __builtin_clz(prod)) + x.exp + y.exp - FA - FB >= 128) {
+            if (prod && (31 - __builtin_clz(prod)) + x.exp + y.exp + scale_exp(sr, k) - FA - FB >= 128) {
                 if (x.sign ^ y.sign) ninf = true; else pinf = true;
             }
         }
@@ -174,14 +194,14 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
     if (p.c_mode == MMAEMU_C_AFTER_RD) {
         if (p.split == MMAEMU_SPLIT_NONE) {
             int emax; int64_t T;
-            const bool have = fused_part<TA, TB>(p, a, b, 0, 1, L, emax, T);
+            const bool have = fused_part<TA, TB>(p, a, b, sr, 0, 1, L, emax, T);
             return finish_group(p, rounded_sum_with_c(p, have, T, emax, emax - p.F, dc));
         }
         // two sub-groups, each fused at its own maximum exponent, merged with RD at F_m bits
         const uint32_t second = p.split == MMAEMU_SPLIT_EVEN_ODD ? 1u : L / 2, stride = p.split == MMAEMU_SPLIT_EVEN_ODD ? 2u : 1u;
         int e0, e1; int64_t T0, T1;
-        const bool h0 = fused_part<TA, TB>(p, a, b, 0, stride, L / 2, e0, T0);
-        const bool h1 = fused_part<TA, TB>(p, a, b, second, stride, L / 2, e1, T1);
+        const bool h0 = fused_part<TA, TB>(p, a, b, sr, 0, stride, L / 2, e0, T0);
+        const bool h1 = fused_part<TA, TB>(p, a, b, sr, second, stride, L / 2, e1, T1);
         const int emax = (h0 && h1) ? (e0 > e1 ? e0 : e1) : (h0 ? e0 : e1);
         i128 T = 0;
         if (h0) T += align_rd((i128)T0, e0 - p.F, emax - p.Fm);
@@ -190,7 +210,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
     }
 
     int emax; int64_t S;
-    bool have = fused_part<TA, TB>(p, a, b, 0, 1, L, emax, S);          // S aligned at the products' own maximum
+    bool have = fused_part<TA, TB>(p, a, b, sr, 0, 1, L, emax, S);          // S aligned at the products' own maximum
     uint32_t d;
     if (p.c_mode == MMAEMU_C_IN_GROUP) {
         const bool c_live = !(p.skip_zero_terms && dc.sig == 0);
@@ -202,7 +222,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
             for (uint32_t k = 0; k < L; ++k) {
                 const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
                 const uint64_t prod = (uint64_t)(x.sig * y.sig);
-                const int sh = (x.exp + y.exp - FA - FB) - unit;
+                const int sh = (x.exp + y.exp + scale_exp(sr, k) - FA - FB) - unit;
                 const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
                 S += (x.sign ^ y.sign) ? -(int64_t)al : (int64_t)al;
             }
@@ -232,7 +252,7 @@ __device__ __noinline__ uint32_t fdpa_group_raw(ModelArgs p, uint32_t ta, uint32
 #define MMAEMU_CASE(X, Y)                                                                             \
     if (ta == X && tb == Y)                                                                           \
         return fdpa_group<X, Y>(p, reinterpret_cast<const typename Fmt<X>::elem *>(a),                \
-                                reinterpret_cast<const typename Fmt<Y>::elem *>(b), L, c)
+                                reinterpret_cast<const typename Fmt<Y>::elem *>(b), L, c, no_scales())
     MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2);
     MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP16);     MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_BF16);
     MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2);
@@ -243,7 +263,7 @@ __device__ __noinline__ uint32_t fdpa_group_raw(ModelArgs p, uint32_t ta, uint32
     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP16);
 #undef MMAEMU_CASE
     return fdpa_group<MMAEMU_BF16, MMAEMU_BF16>(p, reinterpret_cast<const uint16_t *>(a),
-                                                reinterpret_cast<const uint16_t *>(b), L, c);
+                                                reinterpret_cast<const uint16_t *>(b), L, c, no_scales());
 }
 
 } // namespace mmaemu

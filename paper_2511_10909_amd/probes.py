@@ -406,6 +406,21 @@ def hardware(instr):
     return H(info["m"], info["n"], info["k"], info["a"], info["b"])
 
 
+def hardware_scaled(instr, scale_a=127, scale_b=127):
+    """The block-scaled native instruction `instr` (an MFMA_SCALE_* id) with every E8M0 scale of A set to the code
+    `scale_a` and of B to `scale_b` (127 = 2^0): the same probes then read its summation structure."""
+    import torch
+    from . import binding as mm
+    info = mm.mfma_info(instr)
+
+    class H(_LibraryInterface):
+        def _run(self, dA, dB, dC, dD, nb):
+            sa = torch.full((nb * self.m * (self.k // 32),), scale_a, dtype=torch.uint8, device=dA.device)
+            sb = torch.full((nb * self.n * (self.k // 32),), scale_b, dtype=torch.uint8, device=dA.device)
+            mm.mfma_probe_scaled(instr, dA, dB, dC, dD, sa, sb, self.k, nb)
+    return H(info["m"], info["n"], info["k"], info["a"], info["b"])
+
+
 def model(model_kwargs, m, n, k, ta, tb):
     """A parameterised model evaluated by the library on m x n x k tiles."""
     from . import binding as mm

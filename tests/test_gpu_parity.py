@@ -33,7 +33,8 @@ def gpu_emulate(mm, p, A, B, C, ta, tb):
                         acc_special_truncation=p.acc_special_truncation, frac_bits_merge=p.frac_bits_merge,
                         frac_bits_acc=p.frac_bits_acc, f2_at_leading_bit=p.f2_at_leading_bit,
                         skip_zero_terms=p.skip_zero_terms, zero_result_positive=p.zero_result_positive,
-                        sum_drop_distance=p.sum_drop_distance, family=p.family, out_mant_bits=p.out_mant_bits)
+                        sum_drop_distance=p.sum_drop_distance, family=p.family, out_mant_bits=p.out_mant_bits,
+                        wide_products=p.wide_products)
     try:
         dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(np.uint32))
         dD = dev_empty((nb, m, n), np.uint32)
