@@ -49,7 +49,8 @@ algorithms):
     (the paper uses F);  frac_bits_acc (F_c): fractional bits of the accumulator's RD rounding
     and of the special-truncation threshold (the paper uses F);
   * acc_special_truncation: the special truncation of GTR-FDPA as a switch of its own;
-  * skip_zero_terms: terms whose significand is zero take no part in any exponent maximum;
+  * skip_zero_terms: products whose significand is zero take no part in any exponent maximum (the accumulator
+    always does; a zero accumulator has the exponent of the subnormals, -126);
   * f2_at_leading_bit: the sum T 2^(e_max - E) + s_c' is formed exactly and then rounded down to
     F2 fractional bits counted below its own leading bit (not below 2^E), or below 2^-126 for a smaller sum;
   * zero_result_positive: a result that rounds (or is flushed) to zero is +0.0;
@@ -191,9 +192,7 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None):
         # Step 2: truncated fused sum of L+1 terms
         s.append(dc.signed_sig)
         e.append(dc.exp)
-        live = [e[k] for k in range(L + 1) if not (p.skip_zero_terms and s[k] == 0)]
-        if not live:
-            return 0                                              # every term is zero: +0.0
+        live = [e[k] for k in range(L + 1) if k == L or not (p.skip_zero_terms and s[k] == 0)]   # the accumulator always takes part
         e_max = max(live)
         s_al = [_rz_frac(s[k] * Fraction(2) ** (e[k] - e_max), F) for k in range(L + 1)]
         S = sum(s_al, Fraction(0))
@@ -231,10 +230,8 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None):
             e_max = max(e_part for e_part, _ in sums)
             T = sum((_rd_frac(T_part * Fraction(2) ** (e_part - e_max), F_m) for e_part, T_part in sums), Fraction(0))
         # rounded sum with the accumulator
-        c_live = not (p.skip_zero_terms and dc.signed_sig == 0)
-        if e_max is None and not c_live:
-            return 0                                              # nothing to add: +0.0
-        E = max(([e_max] if e_max is not None else []) + ([dc.exp] if c_live else []))
+        # (the accumulator always takes part, a zero one with the exponent of the subnormals, -126)
+        E = max(([e_max] if e_max is not None else []) + [dc.exp])
         if e_max is None:
             e_max = E
         sc_al = _rd_frac(dc.signed_sig * Fraction(2) ** (dc.exp - E), F_c)

@@ -214,8 +214,35 @@ def normal_values(gp, elems_per_tile, first_tile, n_tiles, threads=1):
     return np.concatenate(parts).reshape(n_tiles, elems_per_tile)
 
 
+E8M0 = 5       # block-scale codes: one byte, 2^(code - 127), no sign and no mantissa
+
+
+def _generate_scale_codes(gp, elems_per_tile, first_tile, n_tiles):
+    """E8M0 codes from the bit-pattern families: all zero, the low byte of the element's word, or a code drawn
+    uniformly from exp_lo .. exp_hi (plus code 0 with exp_zero) with the word's low 31 bits as the selector."""
+    total = n_tiles * elems_per_tile
+    if gp.family == GEN_ZERO:
+        return np.zeros((n_tiles, elems_per_tile), dtype=np.uint32)
+    g = np.arange(first_tile * elems_per_tile, first_tile * elems_per_tile + total, dtype=np.uint64)
+    r = _words(gp.seed, gp.operand, g).astype(np.uint64)
+    if gp.family == GEN_RANDOM_BITS:
+        out = r & np.uint64(0xFF)
+    elif gp.family == GEN_UNIFORM_EXP:
+        nch = gp.exp_hi - gp.exp_lo + 1 + (1 if gp.exp_zero else 0)
+        idx = ((r & np.uint64(0x7FFFFFFF)) * np.uint64(nch)) >> np.uint64(31)
+        if gp.exp_zero:
+            out = np.where(idx == 0, np.uint64(0), np.uint64(gp.exp_lo) + idx - np.uint64(1))
+        else:
+            out = np.uint64(gp.exp_lo) + idx
+    else:
+        raise ValueError("scale codes come from ZERO, RANDOM_BITS and UNIFORM_EXP only")
+    return out.astype(np.uint32).reshape(n_tiles, elems_per_tile)
+
+
 def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
     """Raw bit patterns (uint32 array, shape (n_tiles, elems_per_tile)) of one operand."""
+    if fmt_id == E8M0:
+        return _generate_scale_codes(gp, elems_per_tile, first_tile, n_tiles)
     f = fm.FORMATS[fmt_id]
     total = n_tiles * elems_per_tile
     if gp.family == GEN_ZERO:

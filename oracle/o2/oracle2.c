@@ -210,11 +210,8 @@ static uint32_t rounded_sum_with_c(const o2_params *p, int have_T, i128 T, int e
 {
     const int F = (int)p->frac_bits, F2 = (int)p->frac_bits2;
     const int Fc = p->frac_bits_acc ? (int)p->frac_bits_acc : F;
-    const int c_live = !(p->skip_zero_terms && dc.sig == 0);
-    if (!have_T && !c_live) return 0u;
-    int E;
-    if (have_T && c_live) E = dc.exp > emax ? dc.exp : emax;
-    else E = have_T ? emax : dc.exp;
+    /* the accumulator always takes part, a zero one with the exponent of the subnormals, -126 */
+    const int E = (have_T && emax > dc.exp) ? emax : dc.exp;
     i128 sc = dc.sign ? -(i128)dc.sig : (i128)dc.sig;
     i128 sc2 = align_rd(sc, dc.exp - 23, E - Fc);
     if (special_truncation && dc.exp < E - Fc - 1) sc2 = 0;
@@ -307,9 +304,7 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
     int emax = 0;
     int have = part_emax(p, a, b, se, 0, 1, L, ta, tb, &emax);
     if (c_mode == C_IN_GROUP) {
-        const int c_live = !(p->skip_zero_terms && dc.sig == 0);
-        if (!have && !c_live) return 0u;
-        if (c_live && (!have || dc.exp > emax)) emax = dc.exp;
+        if (!have || dc.exp > emax) emax = dc.exp;       /* the accumulator always takes part */
         const int unit = emax - F;
         i128 S = part_sum(p, a, b, se, 0, 1, L, ta, tb, unit);
         u128 al = align_rz((u128)dc.sig, dc.exp - 23, unit);

@@ -261,7 +261,54 @@ def validation_families(ta, tb):
     e_prod = (one[ta] - bias[ta]) + (one[tb] - bias[tb])
     fams.append(("one_exp_c_far_above", ue((one[ta], one[ta]), zero=False), ue((one[tb], one[tb]), zero=False),
                  ue((127 + e_prod + 20, 127 + e_prod + 32), zero=False)))
+    if ta == mm.BF16 and tb == mm.BF16:
+        # products around the bottom of binary32's subnormal range, with a zero and with a subnormal accumulator
+        tiny = ue((46, 52))
+        fams.append(("tiny_products_c_zero", tiny, tiny, dict(family=mm.GEN_ZERO)))
+        fams.append(("tiny_products_c_subnormal", tiny, tiny, ue((0, 2))))
     return fams
+
+
+# ranges of E8M0 scale codes for the block-scaled instructions: (name, lowest code, highest code, zero accumulator)
+SCALE_RANGES = [("unit", 127, 127, False), ("narrow", 120, 134, False), ("wide", 60, 190, False), ("all_codes", 0, 255, False),
+                ("low", 0, 70, False), ("low_c_zero", 30, 70, True)]
+
+
+def validate_scaled_against_mfma(instr, model_kwargs, n_tiles=1024, seeds=(0,), dev="cuda"):
+    """The same loop for a block-scaled native instruction (MFMA_SCALE_* ids; one E8M0 scale per row and 32 values of
+    k): every input family under every range of scale codes in SCALE_RANGES.  Returns {(range, family): stats dict}
+    plus "seconds", "terms" and "kernel"."""
+    info = mm.mfma_info(instr)
+    m, n, k, ta, tb = info["m"], info["n"], info["k"], info["a"], info["b"]
+    nblk = k // 32
+    A, B = _buf((n_tiles, m, k), ta, dev), _buf((n_tiles, n, k), tb, dev)
+    SA, SB = _buf((n_tiles, m, nblk), mm.E8M0, dev), _buf((n_tiles, n, nblk), mm.E8M0, dev)
+    C, Dhw, D = (_buf((n_tiles, m, n), mm.FP32, dev) for _ in range(3))
+    h = mm.model_create(**model_kwargs)
+    fams = validation_families(ta, tb)
+    stats = {(rname, name): _stats_buf(dev) for rname, _, _, _ in SCALE_RANGES for name, _, _, _ in fams}
+
+    def run():
+        for rname, lo, hi, c_zero in SCALE_RANGES:
+            for name, ga, gb, gc in fams:
+                for seed in seeds:
+                    mm.generate(A, ta, m * k, 0, n_tiles, seed=seed, operand=0, **ga)
+                    mm.generate(B, tb, n * k, 0, n_tiles, seed=seed, operand=1, **gb)
+                    mm.generate(C, mm.FP32, m * n, 0, n_tiles, seed=seed, operand=2, **(dict(family=mm.GEN_ZERO) if c_zero else gc))
+                    mm.generate(SA, mm.E8M0, m * nblk, 0, n_tiles, family=mm.GEN_UNIFORM_EXP, seed=seed, operand=3, exp_lo=lo, exp_hi=hi)
+                    mm.generate(SB, mm.E8M0, n * nblk, 0, n_tiles, family=mm.GEN_UNIFORM_EXP, seed=seed, operand=4, exp_lo=lo, exp_hi=hi)
+                    mm.mfma_probe_scaled(instr, A, B, C, Dhw, SA, SB, k, n_tiles)
+                    mm.emulate_mma_scaled(h, A, B, C, D, SA, SB, 32, m, n, k, n_tiles, (ta, tb, mm.FP32, mm.FP32))
+                    mm.compare(D, Dhw, n_tiles * m * n, stats[(rname, name)])
+
+    _, secs = _timed(run)
+    kernel = mm.last_kernel()
+    mm.model_destroy(h)
+    out = {key: mm.read_stats(st) for key, st in stats.items()}
+    out["seconds"] = secs
+    out["terms"] = len(SCALE_RANGES) * len(fams) * len(seeds) * n_tiles * m * n * k
+    out["kernel"] = kernel
+    return out
 
 
 def validate_against_mfma(instr, model_kwargs, n_tiles=4096, seeds=(0,), dev="cuda"):

@@ -283,9 +283,14 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
         set_error("generate: struct_size %u, expected %zu", g->struct_size, sizeof(mmaemu_gen_params));
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if ((uint32_t)dtype > MMAEMU_FP32 || g->family > MMAEMU_GEN_CANCELLING || g->scale_scope > MMAEMU_SCALE_TILE) {
+    if ((uint32_t)dtype > MMAEMU_E8M0 || g->family > MMAEMU_GEN_CANCELLING || g->scale_scope > MMAEMU_SCALE_TILE) {
         set_error("generate: enum out of range");
         return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (dtype == MMAEMU_E8M0 && g->family != MMAEMU_GEN_ZERO && g->family != MMAEMU_GEN_RANDOM_BITS &&
+        g->family != MMAEMU_GEN_UNIFORM_EXP) {
+        set_error("generate: scale codes (E8M0) come from the ZERO, RANDOM_BITS and UNIFORM_EXP families only");
+        return MMAEMU_ERR_UNSUPPORTED;
     }
     if (ept == 0) { set_error("generate: elems_per_tile = 0"); return MMAEMU_ERR_SHAPE; }
     if (n_tiles > (1ull << 62) / ept || first_tile > (1ull << 62) / ept || (first_tile + n_tiles) > (1ull << 62) / ept) {

@@ -22,6 +22,7 @@ inline FmtInfo fmt_info(uint32_t t)
     case MMAEMU_FP8_E5M2: return {5, 2, 15, 8, true};
     case MMAEMU_FP16: return {5, 10, 15, 16, true};
     case MMAEMU_BF16: return {8, 7, 127, 16, true};
+    case MMAEMU_E8M0: return {8, 0, 127, 8, false};
     default: return {8, 23, 127, 32, true};
     }
 }

@@ -509,8 +509,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         const int Fmax = p.F2 > p.Fc ? p.F2 : p.Fc;
         const uint32_t Ec = (cb >> 23) & 0xFFu;
         const int ec = (int)(Ec ? Ec : 1u) - 127;
-        const bool c_live = !(p.skip_zero_terms && (cb & 0x7FFFFFFFu) == 0);
-        const int E = (have_T && c_live) ? (ec > em ? ec : em) : (have_T ? em : ec);
+        const int E = have_T ? (ec > em ? ec : em) : ec;           // the accumulator always takes part
         if (have_T && p.sum_drop_distance && E - em >= p.sum_drop_distance) have_T = false;
         if (!have_T) T = 0.0;
         double sc = __builtin_floor(ldexp((double)__uint_as_float(cb), p.Fc - E));               // RD_Fc(c at E), units of 2^(E - Fc)
@@ -535,7 +534,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
             if (err < 0.0 && ldexp(q, unit) == sm) q -= 1.0;                                      // s on the grid, exact sum just below it
             val = sm == 0.0 ? 0.0 : ldexp(q, unit);
         }
-        return (have_T || c_live) ? val : 0.0;
+        return val;
     };
 
     // End of a group: rho of (sum of aligned terms) * 2^unit.  The value to convert is held

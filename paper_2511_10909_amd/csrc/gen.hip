@@ -58,8 +58,8 @@ __device__ __forceinline__ uint32_t bits_from_word(const GenArgs &g, uint32_t r,
         const uint32_t sign = v >= g.nmag;
         return (sign << (g.width - 1)) | (v - sign * g.nmag);
     }
-    // UNIFORM_EXP
-    const uint32_t sign = r >> 31;
+    // UNIFORM_EXP (scale codes have no sign bit)
+    const uint32_t sign = g.dtype == MMAEMU_E8M0 ? 0u : (r >> 31);
     uint32_t idx, mant;
     if (g.fp32_two_words) {
         idx = (uint32_t)(((uint64_t)(r & 0x7FFFFFFFu) * g.nchoices) >> 31);

@@ -9,7 +9,7 @@ E4M3, E5M2, FP16, BF16, FP32 = 0, 1, 2, 3, 4
 WIDTH = {E4M3: 8, E5M2: 8, FP16: 16, BF16: 16, FP32: 32}
 EBITS = {E4M3: 4, E5M2: 5, FP16: 5, BF16: 8, FP32: 8}
 MBITS = {E4M3: 3, E5M2: 2, FP16: 10, BF16: 7, FP32: 23}
-NP_DTYPE = {E4M3: np.uint8, E5M2: np.uint8, FP16: np.uint16, BF16: np.uint16, FP32: np.uint32}
+NP_DTYPE = {E4M3: np.uint8, E5M2: np.uint8, FP16: np.uint16, BF16: np.uint16, FP32: np.uint32, 5: np.uint8}   # 5: E8M0 scale codes
 
 
 def _is_special(bits, t):

@@ -159,6 +159,8 @@ GEN_CASES = [
     (ogen.GEN_NORMAL_OUTLIERS, fm.E5M2, dict(scale_scope=ogen.SCALE_TILE, scale_target=57344.0)),
     (ogen.GEN_CANCELLING, fm.FP16, dict(exp_lo=5, exp_hi=25)), (ogen.GEN_CANCELLING, fm.BF16, dict(exp_lo=100, exp_hi=150, exp_zero=True)),
     (ogen.GEN_CANCELLING, fm.E4M3, dict(exp_lo=0, exp_hi=14)), (ogen.GEN_CANCELLING, fm.E5M2, dict(exp_lo=1, exp_hi=30)),
+    (ogen.GEN_UNIFORM_EXP, ogen.E8M0, dict(exp_lo=60, exp_hi=190)), (ogen.GEN_UNIFORM_EXP, ogen.E8M0, dict(exp_lo=0, exp_hi=255, exp_zero=True)),
+    (ogen.GEN_RANDOM_BITS, ogen.E8M0, {}), (ogen.GEN_ZERO, ogen.E8M0, {}),
 ]
 
 

@@ -211,3 +211,23 @@ def test_ordered_distance_matches_float_neighbours():
     up = np.nextafter(x, np.float32(np.inf))
     d = np.abs(stats.ordered_key(x.view(np.uint32)) - stats.ordered_key(up.view(np.uint32)))
     assert (d == 1).all()
+
+
+def test_scale_code_generation():
+    # E8M0 codes: UNIFORM_EXP draws every code of the range about equally often and nothing else; RANDOM_BITS gives
+    # all 256 codes; chunks compose
+    from oracle import gen as ogen
+    gp = ogen.GenParams(family=ogen.GEN_UNIFORM_EXP, seed=5, operand=3, exp_lo=120, exp_hi=134)
+    x = ogen.generate(gp, ogen.E8M0, 64, 0, 512).ravel()
+    counts = np.bincount(x, minlength=256)
+    assert counts[:120].sum() == 0 and counts[135:].sum() == 0
+    assert counts[120:135].min() > 0.8 * x.size / 15 and counts[120:135].max() < 1.2 * x.size / 15
+    gz = ogen.GenParams(family=ogen.GEN_UNIFORM_EXP, seed=5, operand=3, exp_lo=200, exp_hi=203, exp_zero=True)
+    assert set(np.unique(ogen.generate(gz, ogen.E8M0, 64, 0, 64))) == {0, 200, 201, 202, 203}
+    gr = ogen.GenParams(family=ogen.GEN_RANDOM_BITS, seed=1, operand=4)
+    r = ogen.generate(gr, ogen.E8M0, 256, 0, 256)
+    assert len(np.unique(r)) == 256 and r.max() == 255
+    assert np.array_equal(ogen.generate(gr, ogen.E8M0, 256, 100, 7), r[100:107])
+    assert not ogen.generate(ogen.GenParams(family=ogen.GEN_ZERO), ogen.E8M0, 16, 0, 4).any()
+    with pytest.raises(ValueError):
+        ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL), ogen.E8M0, 16, 0, 4)

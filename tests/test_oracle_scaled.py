@@ -175,16 +175,26 @@ def test_leading_bit_rounding_stops_at_smallest_normal_exponent():
     a = [e4m3(1.0), e4m3(1.0)] + [0] * 6
     b = [e4m3(1.0), e4m3(1.0)] + [0] * 6
     # 2^-150 + 2^-158: half a last place of the subnormal grid and a little more.  Below the leading bit 31 bits would
-    # keep the little more (result 2^-149); the rounding position 2^-157 does not, and the tie goes to even (zero)
+    # keep the little more (result 2^-149); the rounding position 2^-157 does not, and the tie goes to even (zero).
+    # (Without the leading-bit rule the position is 2^(E - 31) with E = -126, the zero accumulator's exponent: the same.)
     se = [-150, -158] + [0] * 6
     assert fdpa_group(p, a, b, 0, fm.E4M3, fm.E4M3, scale_exp=se) == 0
-    assert fdpa_group(p.with_(f2_at_leading_bit=False), a, b, 0, fm.E4M3, fm.E4M3, scale_exp=se) == 1
+    assert fdpa_group(p.with_(f2_at_leading_bit=False), a, b, 0, fm.E4M3, fm.E4M3, scale_exp=se) == 0
     # 2^-150 + 2^-157 is kept: above the tie
     assert fdpa_group(p, a, b, 0, fm.E4M3, fm.E4M3, scale_exp=[-150, -157] + [0] * 6) == 1
     # negative: -(3 2^-150) + 2^-158 = -1.5 ulp + a little: rounded down to -1.5 ulp first, tie to even: -2 ulp
     a[0] = e4m3(-1.5)
     assert fdpa_group(p, a, b, 0, fm.E4M3, fm.E4M3, scale_exp=[-149, -158] + [0] * 6) == 0x80000002
-    assert fdpa_group(p.with_(f2_at_leading_bit=False), a, b, 0, fm.E4M3, fm.E4M3, scale_exp=[-149, -158] + [0] * 6) == 0x80000001
+    assert fdpa_group(p.with_(f2_at_leading_bit=False), a, b, 0, fm.E4M3, fm.E4M3, scale_exp=[-149, -158] + [0] * 6) == 0x80000002
+    # a zero accumulator takes part with the exponent -126: a product sum 28 or more binary places below it is dropped
+    q = p.with_(sum_drop_distance=28)
+    a16, b16 = [e4m3(1.25)] * 8, [e4m3(1.0)] * 8
+    assert fdpa_group(q, a16, b16, 0, fm.E4M3, fm.E4M3, scale_exp=[-153] * 8) == 1        # 10 * 2^-153 = 0.625 of 2^-149
+    assert fdpa_group(q, a16, b16, 0, fm.E4M3, fm.E4M3, scale_exp=[-154] * 8) == 0
+    assert fdpa_group(p, a16, b16, 0, fm.E4M3, fm.E4M3, scale_exp=[-154] * 8) == 0        # 0.3125: rounds to zero anyway
+    a16, b16 = [e4m3(1.75)] * 8, [e4m3(1.5)] * 8                                         # 21 * 2^-154 = 0.65625 of 2^-149
+    assert fdpa_group(p, a16, b16, 0, fm.E4M3, fm.E4M3, scale_exp=[-154] * 8) == 1
+    assert fdpa_group(q, a16, b16, 0, fm.E4M3, fm.E4M3, scale_exp=[-154] * 8) == 0
     # results of 2^-126 and more are untouched by the floor
     assert fdpa_group(p, a, b, 0, fm.E4M3, fm.E4M3, scale_exp=[-100, -135] + [0] * 6) == \
         fdpa_group(p.with_(f2_at_leading_bit=False, frac_bits2=40), a, b, 0, fm.E4M3, fm.E4M3, scale_exp=[-100, -135] + [0] * 6)

@@ -303,13 +303,14 @@ def test_skip_zero_terms():
     for c in (-2.0 ** -140, 2.0 ** -140, -1.5, 0.0):
         assert _run(TR.with_(skip_zero_terms=True), [0.0], [3.0], c) == f32_bits(c)
     assert _run(TR, [0.0], [3.0], -2.0 ** -140) == f32_bits(-2.0 ** -37)               # literal: e_max = -14 + 1, RD_24 of c is -2^(-13-24)
-    # a zero accumulator does not set E either.  Products 2^-150 + 2^-151 with F2 = 24: the literal reading rounds the
-    # sum down at E = -126 to a multiple of 2^-150, a tie of the subnormal grid that goes to 0; skipped, E = e_max
-    # keeps 1.5 * 2^-150, which rounds up to 2^-149
+    # a zero accumulator still sets E (only products are skipped): it has the exponent of the subnormals.  Products
+    # 2^-150 + 2^-151 with F2 = 24: the sum is rounded down at E = -126 to a multiple of 2^-150, a tie of the subnormal
+    # grid that goes to 0, with and without the switch (E = e_max would keep 1.5 * 2^-150, which rounds up to 2^-149)
     p = ModelParams(group_len=2, frac_bits=24, frac_bits2=24, c_mode=C_AFTER_RD)
     a2, b2 = [bf16_bits(2.0 ** -75)] * 2, [bf16_bits(2.0 ** -75), bf16_bits(2.0 ** -76)]
     assert fdpa_group(p, a2, b2, 0, fm.BF16, fm.BF16) == 0
-    assert fdpa_group(p.with_(skip_zero_terms=True), a2, b2, 0, fm.BF16, fm.BF16) == 1
+    assert fdpa_group(p.with_(skip_zero_terms=True), a2, b2, 0, fm.BF16, fm.BF16) == 0
+    assert fdpa_group(p.with_(skip_zero_terms=True, frac_bits2=25), a2, b2, 0, fm.BF16, fm.BF16) == 1
     # exact zero stays +0.0 in every mode
     for mode in (C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD):
         q = ModelParams(group_len=2, frac_bits=24, frac_bits2=31, c_mode=mode, skip_zero_terms=True)
