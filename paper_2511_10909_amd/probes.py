@@ -421,6 +421,23 @@ def hardware_scaled(instr, scale_a=127, scale_b=127):
     return H(info["m"], info["n"], info["k"], info["a"], info["b"])
 
 
+def model_scaled(model_kwargs, m, n, k, ta, tb, scale_a=127, scale_b=127, block=32):
+    """A parameterised model on m x n x k tiles with every E8M0 block scale of A set to `scale_a`, of B to `scale_b`."""
+    import torch
+    from . import binding as mm
+
+    class M(_LibraryInterface):
+        def _run(self, dA, dB, dC, dD, nb):
+            sa = torch.full((nb * self.m * (self.k // block),), scale_a, dtype=torch.uint8, device=dA.device)
+            sb = torch.full((nb * self.n * (self.k // block),), scale_b, dtype=torch.uint8, device=dA.device)
+            h = mm.model_create(**model_kwargs)
+            try:
+                mm.emulate_mma_scaled(h, dA, dB, dC, dD, sa, sb, block, self.m, self.n, self.k, nb, (self.ta, self.tb, mm.FP32, mm.FP32))
+            finally:
+                mm.model_destroy(h)
+    return M(m, n, k, ta, tb)
+
+
 def model(model_kwargs, m, n, k, ta, tb):
     """A parameterised model evaluated by the library on m x n x k tiles."""
     from . import binding as mm

@@ -14,11 +14,16 @@ def env():
     return binding, presets, probes
 
 
-@pytest.mark.parametrize("instr", range(10))
-def test_probes_agree_between_instruction_and_model(env, instr):
+@pytest.mark.parametrize("instr,scales", [(i, None) for i in range(10)] + [(10, (127, 127)), (11, (100, 154)), (12, (150, 104)), (13, (127, 127))])
+def test_probes_agree_between_instruction_and_model(env, instr, scales):
     mm, presets, probes = env
-    hw = probes.hardware(instr)
-    md = probes.model(presets.GFX950_MFMA[instr], hw.m, hw.n, hw.k, hw.ta, hw.tb)
+    if scales is None:
+        hw = probes.hardware(instr)
+        md = probes.model(presets.GFX950_MFMA[instr], hw.m, hw.n, hw.k, hw.ta, hw.tb)
+    else:       # the block-scaled instruction, all scales of A and of B at one code each (the two cancel: the probes
+                # build products and accumulator on one scale)
+        hw = probes.hardware_scaled(instr, *scales)
+        md = probes.model_scaled(presets.GFX950_MFMA[instr], hw.m, hw.n, hw.k, hw.ta, hw.tb, *scales)
     assert probes.independence(hw, trials=16)
     assert probes.independence(md, trials=16)
     t_hw, t_md = probes.summation_table(hw), probes.summation_table(md)
