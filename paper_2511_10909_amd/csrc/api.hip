@@ -236,8 +236,10 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     ma.ftz_in = mp.ftz_in;
     ma.ftz_out = mp.ftz_out;
     ma.nan_bits = mp.nan_bits;
-    if (SA) return launch_emulate_generic(ma, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream, SA, SB, block);
-    return launch_emulate(ma, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream);
+    ma.flags = (ma.out_round == MMAEMU_ROUND_RZ ? FL_RZ : 0u) | (ma.ftz_out ? FL_FTZ_OUT : 0u) | (ma.zero_result_positive ? FL_ZERO_POSITIVE : 0u) |
+               (ma.ftz_in ? FL_FTZ_IN : 0u) | (ma.acc_special_truncation ? FL_SPECIAL_TRUNC : 0u) | (ma.f2_at_leading_bit ? FL_F2_LEADING : 0u) |
+               (ma.skip_zero_terms ? FL_SKIP_ZERO : 0u) | (ma.wide_products ? FL_WIDE_PRODUCTS : 0u);
+    return launch_emulate(ma, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream, SA, SB, block);
 }
 
 mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const void *B, const void *C, void *D,

@@ -27,6 +27,11 @@ inline FmtInfo fmt_info(uint32_t t)
     }
 }
 
+enum : uint32_t {
+    FL_RZ = 1u, FL_FTZ_OUT = 2u, FL_ZERO_POSITIVE = 4u, FL_FTZ_IN = 8u, FL_SPECIAL_TRUNC = 16u, FL_F2_LEADING = 32u,
+    FL_SKIP_ZERO = 64u, FL_WIDE_PRODUCTS = 128u
+};
+
 // Model parameters as the kernels take them (by value).
 struct ModelArgs {
     uint32_t L;          // group length actually used: min(K, L_max)
@@ -39,6 +44,7 @@ struct ModelArgs {
     uint32_t f2_at_leading_bit, skip_zero_terms, zero_result_positive, wide_products;
     int32_t sum_drop_distance;
     uint32_t out_mask;   // 0xFFFFFFFF, or 0xFFFFFC00 for the E8M13 output conversion
+    uint32_t flags;      // the switches above once more, one FL_* bit each (the tiled kernels test these)
 };
 
 // error plumbing (api.hip)
@@ -53,9 +59,10 @@ mmaemu_status hip_fail(hipError_t e, const char *what);
 
 // launchers implemented in the kernel translation units; all validate nothing (the
 // entry points do) and return the launch status
+// SA / SB: E8M0 block scales (device), or null for the unscaled operation
 mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                              uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb,
-                             hipStream_t s);
+                             hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr, uint32_t block = 1);
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                      uint32_t tb, hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr,

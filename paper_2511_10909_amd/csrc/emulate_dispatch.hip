@@ -15,13 +15,17 @@ static mmaemu_status launch_vm(const TiledArgs &t, const void *A, const void *B,
         if (t.p.split == MMAEMU_SPLIT_EVEN_ODD) return launch_tiled_shape<CM_RD_EVEN_ODD, 0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         return launch_tiled_shape<CM_RD_HALVES, 0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
     }
+    if constexpr (VM == 3) {
+        if (t.p.split == MMAEMU_SPLIT_EVEN_ODD) return launch_tiled_shape<CM_RD_EVEN_ODD, 3>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_tiled_shape<CM_RD_HALVES, 3>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    }
     handled = false;        // split groups with BF16 operands or wide F: general kernel
     return MMAEMU_OK;
 }
 
 mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *Cm, void *D,
                              uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb,
-                             hipStream_t s)
+                             hipStream_t s, const uint8_t *SA, const uint8_t *SB, uint32_t block)
 {
     // the tiled kernels need 8-byte aligned operand arrays (four consecutive k elements are
     // loaded at once) and group sums below 2^52
@@ -31,21 +35,29 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // the general kernel's integer range)
     const bool wide_bf16 = p.wide_products && (ta == MMAEMU_BF16 || tb == MMAEMU_BF16);
     const bool tiled_mode = (p.c_mode == MMAEMU_C_AFTER_RD && !wide_bf16) || (p.c_mode != MMAEMU_C_AFTER_RD && !p.skip_zero_terms && !p.zero_result_positive);
-    if (tiled_mode && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
+    // block scales run tiled when every group lies inside one block (all of its products then share one scale
+    // exponent) and the values stay binary32 (FP8 / FP16 operands, F below 30)
+    const bool scaled = SA != nullptr;
+    const bool scaled_ok = !scaled || (block % p.L == 0 && ta != MMAEMU_BF16 && tb != MMAEMU_BF16 && p.F < 30);
+    if (tiled_mode && scaled_ok && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;
         t.ta = ta;
         t.tb = tb;
+        t.sa = SA;
+        t.sb = SB;
+        t.block = block;
         t.ebase = 2 - fmt_info(ta).bias - fmt_info(tb).bias -
                   ((p.c_mode == MMAEMU_C_AFTER_RD && p.skip_zero_terms) ? 2 * (int)ZBIAS : 0);
         bool handled = false;
         mmaemu_status st;
-        if (p.F >= 30) st = launch_vm<2>(t, A, B, Cm, D, m, n, k, batch, s, handled);             // wide F: binary64 terms
+        if (scaled) st = launch_vm<3>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        else if (p.F >= 30) st = launch_vm<2>(t, A, B, Cm, D, m, n, k, batch, s, handled);             // wide F: binary64 terms
         else if (ta == MMAEMU_BF16 || tb == MMAEMU_BF16) st = launch_vm<1>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         else st = launch_vm<0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         if (handled) return st;
     }
-    return launch_emulate_generic(p, A, B, Cm, D, m, n, k, batch, ta, tb, s);
+    return launch_emulate_generic(p, A, B, Cm, D, m, n, k, batch, ta, tb, s, SA, SB, scaled ? block : 1u);
 }
 
 } // namespace mmaemu

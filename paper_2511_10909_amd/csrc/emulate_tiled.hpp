@@ -29,7 +29,10 @@
 //      alignment exact for any finite operands), still truncating with the float->int
 //      conversion;
 //   2  wide F (30..40): binary64 values, terms truncated with v_trunc_f64 and summed in
-//      binary64 (exact below 2^53).
+//      binary64 (exact below 2^53);
+//   3  mode 0 with E8M0 block scales (Algorithm "ST-FDPA") whose blocks hold whole groups: all products of a group
+//      then share one scale exponent s, the aligned terms are those of the unscaled group, and s only moves the
+//      group's maximum exponent (and with it everything the accumulator meets).
 // Accumulation modes (template parameter CMODE): MMAEMU_C_IN_GROUP, MMAEMU_C_AFTER_EXACT, MMAEMU_C_AFTER_RD (paper
 // Algorithm "TR-FDPA" and its variations), and the two split forms of the latter (Algorithm "GTR-FDPA"):
 // CM_RD_EVEN_ODD, where the packed exponent maxima of pass 1 already are the even and the odd maximum (even k in
@@ -231,6 +234,9 @@ struct TiledArgs {
     ModelArgs p;
     uint32_t ta, tb;
     int32_t ebase;       // Exp = e' + ebase for a product: 2 - bias_a - bias_b
+    // value mode 3: E8M0 codes SA[batch][m][k / block], SB[batch][n][k / block]; block is a multiple of the group length
+    const uint8_t *sa, *sb;
+    uint32_t block;
 };
 
 // start of the running kernel's argument segment, as a pointer the optimiser cannot trace back to the arguments
@@ -251,14 +257,17 @@ __device__ __forceinline__ const void *opaque_kernarg_ptr()
 // LT      : group length if it divides KC, 0 if a group spans whole chunks (L % KC == 0);
 // NF      : terms summed in 32 bits between folds into binary64 (0: once per group/chunk);
 // VM      : value mode (see the head of this file).
-template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF, int VM>
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF, int VM_>
 __global__ void __launch_bounds__(256)
 emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm,
                      uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nitems, uint32_t bm_count,
                      uint32_t bn_count, uint32_t xcd_remap)
 {
+    constexpr bool SC = VM_ == 3;                     // block scales
+    constexpr int VM = SC ? 0 : VM_;                  // how values are held
     constexpr int TI = TM / R, TJ = TN / C, TPS = TI * TJ, SLOTS = 256 / TPS;
     static_assert(TPS * SLOTS == 256, "thread layout");
+    static_assert(!SC || LT != 0, "scaled groups have a fixed length");
     constexpr int VS = KC + 4;                       // LDS row stride of binary32 values (floats), padded
     constexpr int VSD = KC + 2;                      // LDS row stride of binary64 values (doubles)
     constexpr int ES = KC / 2 + (KC == 16 ? 2 : 4);  // LDS row stride of packed exponents (dwords)
@@ -279,6 +288,16 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 
     const ModelArgs &p = ta_.p;
     const int F = p.F;
+    const uint32_t fl = p.flags;                      // the model's switches, one bit each (one scalar register)
+    // The group epilogues test the switches on a copy that is made opaque each time: otherwise every test is
+    // hoisted out of the loops as a wave-wide mask (two scalar registers apiece, live across the hot loops).
+    uint32_t fe = fl;
+    auto refresh_switches = [&]() {
+#if defined(__HIP_DEVICE_COMPILE__)
+        fe = fl;
+        asm volatile("" : "+s"(fe));
+#endif
+    };
     const uint32_t tid = threadIdx.x, slot = tid / TPS, ti = (tid % TPS) / TJ, tj = tid % TJ;
 
     // workgroup -> items.  Consecutive workgroup ids go to different XCDs (8 of them, each
@@ -318,6 +337,20 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     const uint32_t *be = Be + (slot * TN + tj) * ES;
 
     uint32_t m2[R][C];                                          // packed running maxima of e'
+    // block scales: the codes of this thread's rows and columns for the group at hand, and per element
+    // s = Exp(alpha) + Exp(beta), which the group's maximum exponent carries and pass 2 must leave out again
+    uint32_t sca[SC ? R : 1], scb[SC ? C : 1];
+    int sadj[SC ? R : 1][SC ? C : 1];
+    auto load_scales = [&](uint32_t kg) {
+        if constexpr (SC) {
+            const TiledArgs q = *reinterpret_cast<const TiledArgs *>(opaque_kernarg_ptr());
+            const uint32_t nblk = k / q.block, qb = kg / q.block;
+#pragma unroll
+            for (int r = 0; r < R; ++r) sca[r] = q.sa[(my_tile * m + i_base + TI * r) * (uint64_t)nblk + qb];
+#pragma unroll
+            for (int c = 0; c < C; ++c) scb[c] = q.sb[(my_tile * n + j_base + TJ * c) * (uint64_t)nblk + qb];
+        }
+    };
     int32_t S32[R][C];
     int32_t S32o[CMODE == CM_RD_EVEN_ODD ? R : 1][CMODE == CM_RD_EVEN_ODD ? C : 1];   // odd products (even / odd split)
     double Sd[R][C];
@@ -368,6 +401,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 #pragma unroll
             for (int c = 0; c < C; ++c) {
                 int se = F + 127 - emax[r][c];                         // biased exponent of 2^(F - e_max)
+                if constexpr (SC) se += sadj[r][c];                    // (values are unscaled: e_max without s)
                 se = se < 1 ? 1 : (se > 254 ? 254 : se);               // the clamps never change a truncated term
                 scale[r][c] = __uint_as_float((uint32_t)se << 23);
             }
@@ -403,7 +437,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                int se = F + 127 - emax_e[r][c], so = F + 127 - emax_o[r][c];
+                int se = F + 127 - emax_e[r][c], so = F + 127 - emax_o[r][c];     // (unscaled maxima, also with block scales)
                 se = se < 1 ? 1 : (se > 254 ? 254 : se);
                 so = so < 1 ? 1 : (so > 254 ? 254 : so);
                 scale_e[r][c] = __uint_as_float((uint32_t)se << 23);
@@ -476,8 +510,17 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         uint32_t e = m2[r][c];
         const uint32_t lo = e & 0xFFFFu, hi = e >> 16;
         int em = (int)(lo > hi ? lo : hi) + ta_.ebase;
-        if (IS_RD && VM != 0 && em >= 126 && !(e & SENTINEL_MASK)) {
-            // a product may reach 2^128, which this mode counts as an infinity: leave the group to the integer routine
+        bool to_slow = IS_RD && VM != 0 && em >= 126;
+        if constexpr (SC) {
+            const int s = (int)sca[r] + (int)scb[c] - 254;
+            sadj[r][c] = s;
+            em += s;
+            // a NaN scale; or a product that may reach 2^128 where that counts as an infinity
+            to_slow = sca[r] == 0xFFu || scb[c] == 0xFFu || (IS_RD && !(fl & FL_WIDE_PRODUCTS) && em >= 126);
+        }
+        if (to_slow && !(e & SENTINEL_MASK)) {
+            // (without scales: a product may reach 2^128, which this mode counts as an infinity) leave the group
+            // to the integer routine
             e |= 0x8000u;
             m2[r][c] = e;
         }
@@ -499,7 +542,13 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         // bytes), through a pointer the optimiser cannot see through: otherwise every parameter this rare path
         // needs stays in scalar registers for the whole kernel and crowds out the hot loops' values.
         const TiledArgs q = *reinterpret_cast<const TiledArgs *>(opaque_kernarg_ptr());
-        return fdpa_group_raw(q.p, q.ta, q.tb, a, b, q.p.L, cin);
+        ScaleRef sr = no_scales();
+        if constexpr (SC) {
+            const uint32_t nblk = k / q.block;
+            sr = ScaleRef{q.sa + arow * nblk, q.sb + brow * nblk, q.block, kg};
+        }
+        if constexpr (!SC) return fdpa_group_raw_unscaled(q.p, q.ta, q.tb, a, b, q.p.L, cin);   // (fewer arguments: none on the stack)
+        else return fdpa_group_raw(q.p, q.ta, q.tb, a, b, q.p.L, cin, sr);
     };
 
     // Algorithm "TR-FDPA", steps 3 and 4 ("GTR-FDPA", steps 4 and 5), and the variations, in binary64 (every
@@ -513,9 +562,9 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         if (have_T && p.sum_drop_distance && E - em >= p.sum_drop_distance) have_T = false;
         if (!have_T) T = 0.0;
         double sc = __builtin_floor(ldexp((double)__uint_as_float(cb), p.Fc - E));               // RD_Fc(c at E), units of 2^(E - Fc)
-        if (p.acc_special_truncation && ec < E - p.Fc - 1) sc = 0.0;
+        if ((fe & FL_SPECIAL_TRUNC) && ec < E - p.Fc - 1 && Ec != 0xFFu) sc = 0.0;             // (an infinite or NaN accumulator stays)
         double val;
-        if (!p.f2_at_leading_bit) {
+        if (!(fe & FL_F2_LEADING)) {
             const double T2 = __builtin_floor(ldexp(T, (em - FT) - (E - p.F2)));                  // RD_F2(T at E)
             val = ldexp(ldexp(T2, Fmax - p.F2) + ldexp(sc, Fmax - p.Fc), E - Fmax);
         } else {
@@ -547,19 +596,19 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int c = 0; c < C; ++c) dn[r][c] = __float_as_uint((float)v[r][c]);
-        if (p.out_round != MMAEMU_ROUND_RNE || p.ftz_out || p.zero_result_positive) {
+        if ((fe & (FL_RZ | FL_FTZ_OUT | FL_ZERO_POSITIVE))) {
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
                     uint32_t o = dn[r][c];
-                    if (p.out_round == MMAEMU_ROUND_RZ) {
+                    if ((fe & FL_RZ)) {
                         const double back = (double)__uint_as_float(o);
                         if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) o -= 1u;   // rounded away from zero: step back
                         o &= p.out_mask;                                               // RZ-E8M13 cuts further, still toward zero
                     }
-                    if (p.ftz_out && (o & 0x7F800000u) == 0) o &= 0x80000000u;
-                    if (p.zero_result_positive && (o & 0x7FFFFFFFu) == 0) o = 0u;
+                    if ((fe & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                    if ((fe & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
                     dn[r][c] = o;
                 }
         }
@@ -577,7 +626,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     };
 
     auto flush_accumulators = [&]() {
-        if (p.ftz_in) {                                                 // FlushSubnormal on the accumulator
+        if ((fe & FL_FTZ_IN)) {                                                 // FlushSubnormal on the accumulator
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -587,6 +636,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     };
 
     auto end_of_group = [&](uint32_t kg, const int (&emax)[R][C], uint32_t tagged) {
+        refresh_switches();
         flush_accumulators();
         double v[R][C];
         if (CMODE == MMAEMU_C_IN_GROUP) {
@@ -607,7 +657,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                 for (int c = 0; c < C; ++c) {
                     const double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];   // units of 2^(e_max - F)
                     const uint32_t mx = m2[r][c], mlo = mx & 0xFFFFu, mhi = mx >> 16;
-                    const bool have_T = !p.skip_zero_terms || (mlo > mhi ? mlo : mhi) >= 2 * ZBIAS;
+                    const bool have_T = !(fe & FL_SKIP_ZERO) || (mlo > mhi ? mlo : mhi) >= 2 * ZBIAS;
                     v[r][c] = rd_value(T, have_T, emax[r][c], F, d[r][c]);
                 }
         } else {
@@ -651,6 +701,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     auto end_of_split_group = [&](uint32_t kg, const double (&T0)[R][C], const int (&e0)[R][C], const uint32_t (&x0)[R][C],
                                   const double (&T1)[R][C], const int (&e1)[R][C], const uint32_t (&x1)[R][C], bool halves,
                                   uint32_t tagged) {
+        refresh_switches();
         flush_accumulators();
         double v[R][C];
         uint32_t tg[R][C];
@@ -662,7 +713,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                 // group, the low / high half for the even / odd split)
                 const uint32_t m0 = halves ? ((x0[r][c] & 0xFFFFu) > (x0[r][c] >> 16) ? (x0[r][c] & 0xFFFFu) : (x0[r][c] >> 16)) : (x0[r][c] & 0xFFFFu);
                 const uint32_t m1 = halves ? ((x1[r][c] & 0xFFFFu) > (x1[r][c] >> 16) ? (x1[r][c] & 0xFFFFu) : (x1[r][c] >> 16)) : (x1[r][c] >> 16);
-                const bool h0 = !p.skip_zero_terms || m0 >= 2 * ZBIAS, h1 = !p.skip_zero_terms || m1 >= 2 * ZBIAS;
+                const bool h0 = !(fe & FL_SKIP_ZERO) || m0 >= 2 * ZBIAS, h1 = !(fe & FL_SKIP_ZERO) || m1 >= 2 * ZBIAS;
                 const int em = (h0 && h1) ? (e0[r][c] > e1[r][c] ? e0[r][c] : e1[r][c]) : (h0 ? e0[r][c] : e1[r][c]);
                 double T = 0.0;
                 if (h0) T += __builtin_floor(ldexp(T0[r][c], (e0[r][c] - F) - (em - p.Fm)));
@@ -696,9 +747,9 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     auto commit = [&](int what) {
         float fa[NQA][4], fb[NQB][4];
         uint2 xa[NQA], xb[NQB];
-        const uint32_t zbias = (IS_RD && p.skip_zero_terms) ? ZBIAS : 0u;
-        bool wild = decode_any<NQA>(ta_.ta, raw_a, p.ftz_in, zbias, fa, xa);
-        wild |= decode_any<NQB>(ta_.tb, raw_b, p.ftz_in, zbias, fb, xb);
+        const uint32_t zbias = (IS_RD && (fl & FL_SKIP_ZERO)) ? ZBIAS : 0u;
+        bool wild = decode_any<NQA>(ta_.ta, raw_a, fl & FL_FTZ_IN, zbias, fa, xa);
+        wild |= decode_any<NQB>(ta_.tb, raw_b, fl & FL_FTZ_IN, zbias, fb, xb);
         if (VM == 1) chunk_is_double = __syncthreads_or(wild && (what & 2)) != 0;
         else __syncthreads();
         store_panel<NQA, VS, VSD>(plan_a, fa, xa, Av_raw, Ae, chunk_is_double, what);
@@ -722,6 +773,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 #pragma unroll 1
                 for (int g = 0; g < KC / GL; ++g) {
                     reset_group();
+                    load_scales(k0 + g * GL);
                     pass1(g);
                     int ee[R][C], eo[R][C]; uint32_t tagged = 0;
 #pragma unroll
@@ -733,6 +785,21 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                             tagged |= m2[r][c];
                         }
                     pass2eo(g, ee, eo);
+                    if constexpr (SC) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                const int s = (int)sca[r] + (int)scb[c] - 254;
+                                ee[r][c] += s;
+                                eo[r][c] += s;
+                                const int em = ee[r][c] > eo[r][c] ? ee[r][c] : eo[r][c];
+                                if ((sca[r] == 0xFFu || scb[c] == 0xFFu || (!(fl & FL_WIDE_PRODUCTS) && em >= 126)) && !(m2[r][c] & SENTINEL_MASK)) {
+                                    m2[r][c] |= 0x8000u;
+                                    tagged |= 0x8000u;
+                                }
+                            }
+                    }
                     double Te[R][C], To[R][C];
 #pragma unroll
                     for (int r = 0; r < R; ++r)
@@ -746,6 +813,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                     double T0[R][C]; int e0[R][C]; uint32_t x0[R][C];
                     int emax[R][C]; uint32_t tagged = 0;
                     reset_group();
+                    load_scales(k0 + g * LT);
                     pass1(2 * g);
 #pragma unroll
                     for (int r = 0; r < R; ++r)
@@ -774,6 +842,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 #pragma unroll 1
                 for (int g = 0; g < KC / GL; ++g) {
                     reset_group();
+                    load_scales(k0 + g * GL);
                     pass1(g);
                     int emax[R][C]; uint32_t tagged = 0;
 #pragma unroll
@@ -889,7 +958,9 @@ static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B,
     if constexpr (KC >= 32) {
         if (L == 32) return launch_fold<TM, TN, R, C, KC, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     }
-    if (L % KC == 0) return launch_fold<TM, TN, R, C, KC, 0, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if constexpr (VM != 3) {        // (a scaled group lies inside one chunk)
+        if (L % KC == 0) return launch_fold<TM, TN, R, C, KC, 0, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+    }
     handled = false;
     return MMAEMU_OK;
     }
@@ -903,7 +974,7 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
     const uint64_t outputs = batch * m * n;
     // whole small tiles of a batch (binary64 values need twice the LDS: fewer tiles per workgroup; half groups keep
     // a second set of sums and maxima per output: smaller register blocks)
-    constexpr bool BIG_BLOCKS = VM == 0 && CMODE != CM_RD_HALVES;
+    constexpr bool BIG_BLOCKS = (VM == 0 || VM == 3) && CMODE != CM_RD_HALVES;
     constexpr bool BIG_BLOCKS_OK = CMODE != CM_RD_HALVES;
     if (m == 16 && n == 16 && k % 16 == 0) {
         if constexpr (BIG_BLOCKS) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
@@ -941,5 +1012,10 @@ extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 1);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 2);
 extern template MMAEMU_TILED_SIG(CM_RD_EVEN_ODD, 0);
 extern template MMAEMU_TILED_SIG(CM_RD_HALVES, 0);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_IN_GROUP, 3);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 3);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 3);
+extern template MMAEMU_TILED_SIG(CM_RD_EVEN_ODD, 3);
+extern template MMAEMU_TILED_SIG(CM_RD_HALVES, 3);
 
 } // namespace mmaemu

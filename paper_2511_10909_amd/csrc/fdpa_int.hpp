@@ -244,6 +244,27 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
 // run-time operand types (used where a template per type pair is not worth its code size)
 // (parameters by value: a reference would force the caller to keep a copy of them in scratch memory)
 __device__ __noinline__ uint32_t fdpa_group_raw(ModelArgs p, uint32_t ta, uint32_t tb, const void *a, const void *b,
+                                                uint32_t L, uint32_t c, ScaleRef sr)
+{
+#define MMAEMU_CASE(X, Y)                                                                             \
+    if (ta == X && tb == Y)                                                                           \
+        return fdpa_group<X, Y>(p, reinterpret_cast<const typename Fmt<X>::elem *>(a),                \
+                                reinterpret_cast<const typename Fmt<Y>::elem *>(b), L, c, sr)
+    MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2);
+    MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP16);     MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_BF16);
+    MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2);
+    MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP16);     MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_BF16);
+    MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP8_E5M2);
+    MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP16);         MMAEMU_CASE(MMAEMU_FP16, MMAEMU_BF16);
+    MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E5M2);
+    MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP16);
+#undef MMAEMU_CASE
+    return fdpa_group<MMAEMU_BF16, MMAEMU_BF16>(p, reinterpret_cast<const uint16_t *>(a),
+                                                reinterpret_cast<const uint16_t *>(b), L, c, sr);
+}
+
+// the same without block scales
+__device__ __noinline__ uint32_t fdpa_group_raw_unscaled(ModelArgs p, uint32_t ta, uint32_t tb, const void *a, const void *b,
                                                 uint32_t L, uint32_t c)
 {
 #define MMAEMU_CASE(X, Y)                                                                             \

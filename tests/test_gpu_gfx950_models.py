@@ -44,7 +44,7 @@ def test_gfx950_preset_reproduces_the_block_scaled_instruction(env, instr):
     # family under every range of scale codes (unit, narrow, wide, all codes with NaN, and the bottom of binary32)
     mm, configs, presets = env
     res = configs.validate_scaled_against_mfma(instr, presets.GFX950_MFMA[instr], n_tiles=256)
-    assert res["kernel"].startswith("general, block-scaled")
+    assert res["kernel"].startswith("tiled") and "vm=3" in res["kernel"]
     for key, st in res.items():
         if not isinstance(st, dict):
             continue

@@ -62,6 +62,60 @@ def test_scaled_emulation_matches_oracle(mm, ta, tb):
         assert mm.last_kernel().startswith("general, block-scaled")
 
 
+TILED_SHAPES = [(3, 16, 16, 64), (2, 32, 32, 64), (1, 64, 64, 128), (5, 16, 16, 128), (1, 64, 128, 32), (1, 2048, 1024, 32)]
+
+
+@pytest.mark.parametrize("ta,tb", [(fm.E4M3, fm.E4M3), (fm.E5M2, fm.E4M3), (fm.E4M3, fm.FP16), (fm.FP16, fm.FP16)])
+def test_scaled_tiled_kernels_match_oracle(mm, ta, tb):
+    # groups inside one block of scales: the tiled kernels (value mode 3), every accumulation mode and split
+    rng = np.random.default_rng(5100 + 8 * ta + tb)
+    for trial in range(18):
+        nb, m, n, k = TILED_SHAPES[trial % len(TILED_SHAPES)]
+        if m * n * k * nb > (1 << 24) and trial >= len(TILED_SHAPES):
+            nb, m, n, k = 2, 32, 32, 64
+        block = int(rng.choice([b for b in (16, 32, 64) if k % b == 0]))
+        L = int(rng.choice([x for x in (4, 8, 16, 32) if block % x == 0 and x <= m]))     # (16 x 16 tiles are staged 16 k at a time)
+        mode = [C_IN_GROUP, C_AFTER_RD, C_AFTER_RD, C_AFTER_EXACT][trial % 4]
+        F = int(rng.choice([13, 24, 25]))
+        p = ModelParams(group_len=L, frac_bits=F, c_mode=mode, out_round=int(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)))
+        if mode == C_AFTER_RD:
+            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 3)) if L >= 8 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
+                        acc_special_truncation=bool(rng.integers(0, 2)), sum_drop_distance=int(rng.choice([0, 28])),
+                        wide_products=bool(rng.integers(0, 2)), skip_zero_terms=bool(rng.integers(0, 2)),
+                        zero_result_positive=bool(rng.integers(0, 2)))
+            if p.split:
+                p = p.with_(frac_bits_merge=int(rng.choice([0, 24])), frac_bits_acc=int(rng.choice([0, 24])))
+        A = synth.random_bits(rng, (nb, m, k), ta)
+        B = synth.random_bits(rng, (nb, n, k), tb)
+        if trial % 3 == 0:          # zeros with large exponents next to them, no specials: the fast route throughout
+            A = synth.narrow_exponent_bits(rng, (nb, m, k), ta, 1, 14)
+            A[rng.random(A.shape) < 0.2] = 0
+        lo, hi = [(115, 140), (30, 225), (0, 256)][trial % 3]
+        C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, max(1, lo + lo - 127 - 30), min(254, hi + hi - 127 + 30))
+        SA = rng.integers(lo, hi, size=(nb, m, k // block)).astype(np.uint8)
+        SB = rng.integers(lo, hi, size=(nb, n, k // block)).astype(np.uint8)
+        want, _ = o2lib.emulate_mma_scaled(p, A, B, C, SA, SB, block, ta, tb)
+        print("scaled tiled", trial, (nb, m, n, k), block, p, flush=True)
+        got = gpu_emulate_scaled(mm, p, A, B, C, SA, SB, block, ta, tb)
+        assert mm.last_kernel().startswith("tiled") and "vm=3" in mm.last_kernel(), mm.last_kernel()
+        assert_same(got, want, "scaled tiled %s block %d" % (p, block))
+        assert len(np.unique(want)) > want.size // 64
+
+
+def test_scaled_groups_across_blocks_use_the_general_kernel(mm):
+    rng = np.random.default_rng(8)
+    p = ModelParams(group_len=32, frac_bits=24)
+    A = synth.random_bits(rng, (1, 32, 64), fm.E4M3)
+    B = synth.random_bits(rng, (1, 32, 64), fm.E4M3)
+    C = synth.narrow_exponent_bits(rng, (1, 32, 32), fm.FP32, 100, 150)
+    SA = rng.integers(110, 140, size=(1, 32, 4)).astype(np.uint8)
+    SB = rng.integers(110, 140, size=(1, 32, 4)).astype(np.uint8)
+    want, _ = o2lib.emulate_mma_scaled(p, A, B, C, SA, SB, 16, fm.E4M3, fm.E4M3)
+    got = gpu_emulate_scaled(mm, p, A, B, C, SA, SB, 16, fm.E4M3, fm.E4M3)
+    assert mm.last_kernel().startswith("general, block-scaled")
+    assert_same(got, want, "group of two blocks")
+
+
 def test_wide_products_without_scales(mm):
     # BF16 products far beyond 2^128 that keep their value: the general kernel's integer range, not the tiled kernels
     from test_gpu_parity import gpu_emulate
