@@ -20,7 +20,9 @@ Follows the paper's Sec. 4.1.3:
                             maximum and added; then as TR-FDPA, with the accumulator's
                             term dropped when e_c < E - F - 1.
   * Sec. 4.2, last paragraph: in TR-FDPA a product of magnitude >= 2^128 overflows to infinity.
-  * Table "Conversion functions": RNE-FP32, RZ-FP32 and RZ-E8M13 (out_mant_bits = 13).
+  * Table "Conversion functions": RNE-FP32, RZ-FP32 and RZ-E8M13 (out_mant_bits = 13); RNE-FP16 when the accumulator
+    and the output are FP16 (argument tc = FP16 of the functions below: c and d are then binary16 patterns, the
+    NaN pattern is the low half of nan_bits; Algorithm "T-FDPA" with F_C = FP16, not defined for the RD modes).
   * Algorithm "ST-FDPA"   : T-FDPA on block-scaled operands: every product also takes Exp(alpha) + Exp(beta)
                             of its block's E8M0 scales (value 2^(x - 127), pattern 0xFF is NaN) into e_k.
                             Here the scales are optional arguments of every accumulation mode, one pair per
@@ -65,7 +67,7 @@ from fractions import Fraction
 import numpy as np
 
 from . import formats as fm
-from .rounding import to_fp32, floor_log2, RNE, RZ
+from .rounding import to_fp32, to_fp16, floor_log2, RNE, RZ
 
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 ALIGN_RZ = 0
@@ -117,10 +119,14 @@ def _rd_frac(x, F):
     return Fraction(n, 1 << F)
 
 
-def _specials(p, da, db, dc, scale_exp=None):
+def _nan(p, tc):
+    return p.nan_bits if tc == fm.FP32 else p.nan_bits & 0xFFFF
+
+
+def _specials(p, da, db, dc, scale_exp=None, tc=fm.FP32):
     """Sec. 4.2.  Returns output bits if the group's result is NaN or infinite, else None."""
     if dc.cls == fm.NAN or any(x.cls == fm.NAN for x in da) or any(x.cls == fm.NAN for x in db):
-        return p.nan_bits
+        return _nan(p, tc)
     pos_inf = neg_inf = False
     for k, (x, y) in enumerate(zip(da, db)):
         if p.c_mode in (C_AFTER_RD, C_AFTER_RD_EVEN_ODD) and not p.wide_products and x.finite and y.finite \
@@ -133,7 +139,7 @@ def _specials(p, da, db, dc, scale_exp=None):
         elif x.cls == fm.INF or y.cls == fm.INF:
             other = y if x.cls == fm.INF else x
             if other.cls == fm.ZERO:
-                return p.nan_bits                      # inf * 0
+                return _nan(p, tc)                     # inf * 0
             if x.sign ^ y.sign:
                 neg_inf = True
             else:
@@ -144,27 +150,31 @@ def _specials(p, da, db, dc, scale_exp=None):
         else:
             pos_inf = True
     if pos_inf and neg_inf:
-        return p.nan_bits                              # +inf + -inf
+        return _nan(p, tc)                             # +inf + -inf
     if pos_inf:
-        return 0x7F800000
+        return 0x7F800000 if tc == fm.FP32 else 0x7C00
     if neg_inf:
-        return 0xFF800000
+        return 0xFF800000 if tc == fm.FP32 else 0xFC00
     return None
 
 
-def _flush_out(p, d):
-    if p.ftz_out and (d & 0x7F800000) == 0:
-        return d & 0x80000000
+def _flush_out(p, d, tc=fm.FP32):
+    if tc == fm.FP32:
+        if p.ftz_out and (d & 0x7F800000) == 0:
+            return d & 0x80000000
+    elif p.ftz_out and (d & 0x7C00) == 0:
+        return d & 0x8000
     return d
 
 
-def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None):
-    """One FDPA operation on L = len(a_bits) products and the accumulator c (FP32 bits).  scale_exp: None, or per
+def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None, tc=fm.FP32):
+    """One FDPA operation on L = len(a_bits) products and the accumulator c (bits of type tc: FP32 or FP16; the
+    result has the same type).  scale_exp: None, or per
     product the sum Exp(alpha) + Exp(beta) of its block scales (Algorithm "ST-FDPA"; None entries mean a NaN scale)."""
     L = len(a_bits)
     assert len(b_bits) == L and L >= 1
     if scale_exp is not None and any(x is None for x in scale_exp):
-        return p.nan_bits                              # a NaN scale factor
+        return _nan(p, tc)                             # a NaN scale factor
     if p.c_mode == C_AFTER_RD_EVEN_ODD:       # the paper's GTR-FDPA, by name
         p = p.with_(c_mode=C_AFTER_RD, split=SPLIT_EVEN_ODD, acc_special_truncation=True)
     if p.align_round != ALIGN_RZ:
@@ -173,12 +183,16 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None):
     if p.ftz_in:
         a_bits = [fm.flush_subnormal(x, ta) for x in a_bits]
         b_bits = [fm.flush_subnormal(x, tb) for x in b_bits]
-        c_bits = fm.flush_subnormal(c_bits, fm.FP32)
+        c_bits = fm.flush_subnormal(c_bits, tc)
     da = [fm.decode(x, ta) for x in a_bits]
     db = [fm.decode(x, tb) for x in b_bits]
-    dc = fm.decode(c_bits, fm.FP32)
+    dc = fm.decode(c_bits, tc)
+    if tc not in (fm.FP32, fm.FP16):
+        raise ValueError("the accumulator is FP32 or FP16")
+    if tc == fm.FP16 and (p.c_mode in (C_AFTER_RD, C_AFTER_RD_EVEN_ODD) or p.out_mant_bits != 23):
+        raise ValueError("FP16 accumulators go with the T-FDPA modes and the plain conversion only")
 
-    sp = _specials(p, da, db, dc, scale_exp)
+    sp = _specials(p, da, db, dc, scale_exp, tc)
     if sp is not None:
         return sp
 
@@ -251,15 +265,15 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None):
         raise ValueError(p.c_mode)
 
     # Step 3: convert (Table "Conversion functions")
-    d = to_fp32(V, p.out_round)
+    d = to_fp32(V, p.out_round) if tc == fm.FP32 else to_fp16(V, p.out_round)
     if p.out_mant_bits == 13:
         if p.out_round != RZ:
             raise ValueError("E8M13 is defined with round-to-zero only")
         d &= 0xFFFFFC00                  # RZ to 13 mantissa bits = RZ to 23 bits, then the low 10 bits cut (also toward zero)
     elif p.out_mant_bits != 23:
         raise ValueError("out_mant_bits must be 23 or 13")
-    d = _flush_out(p, d)
-    if p.zero_result_positive and (d & 0x7FFFFFFF) == 0:
+    d = _flush_out(p, d, tc)
+    if p.zero_result_positive and (d & (0x7FFFFFFF if tc == fm.FP32 else 0x7FFF)) == 0:
         d = 0
     return d
 
@@ -271,13 +285,13 @@ def group_length(p, K):
     return L
 
 
-def emulate_element(p, a_bits, b_bits, c_bits, ta, tb, sa=None, sb=None, block=32):
+def emulate_element(p, a_bits, b_bits, c_bits, ta, tb, sa=None, sb=None, block=32, tc=fm.FP32):
     """Algorithm "Phi_FDPA" for one output element: chain over K/L groups.  (family = FAMILY_FTZ_ADDMUL:
     Algorithm "Phi_FTZ-AddMul" with P = group_len instead.)  sa, sb: E8M0 scale bytes of this row of A and of B,
     one per `block` consecutive k (both or neither)."""
     if p.family == FAMILY_FTZ_ADDMUL:
-        if sa is not None:
-            raise ValueError("block scales belong to the FDPA family")
+        if sa is not None or tc != fm.FP32:
+            raise ValueError("block scales and FP16 accumulators belong to the FDPA family")
         from . import addmul
         return addmul.emulate_element(p.group_len, a_bits, b_bits, c_bits, ta, tb, p.nan_bits)
     K = len(a_bits)
@@ -291,13 +305,13 @@ def emulate_element(p, a_bits, b_bits, c_bits, ta, tb, sa=None, sb=None, block=3
     d = int(c_bits)
     for k in range(0, K, L):
         d = fdpa_group(p, [int(x) for x in a_bits[k:k + L]], [int(x) for x in b_bits[k:k + L]], d, ta, tb,
-                       None if scale_exp is None else scale_exp[k:k + L])
+                       None if scale_exp is None else scale_exp[k:k + L], tc)
     return d
 
 
-def emulate_mma(p, A, B, C, ta, tb, SA=None, SB=None, block=32):
+def emulate_mma(p, A, B, C, ta, tb, SA=None, SB=None, block=32, tc=fm.FP32):
     """A[batch][m][k], B[batch][n][k] (both K-contiguous), C[batch][m][n] as raw bit
-    patterns (any integer dtype); returns D[batch][m][n] as uint32 FP32 bits.
+    patterns (any integer dtype); returns D[batch][m][n] as uint32 holding FP32 bits (FP16 bits for tc = FP16).
     SA[batch][m][k/block], SB[batch][n][k/block]: optional E8M0 block scales (Algorithm "ST-FDPA")."""
     A = np.asarray(A)
     B = np.asarray(B)
@@ -313,10 +327,10 @@ def emulate_mma(p, A, B, C, ta, tb, SA=None, SB=None, block=32):
             ai = A[t, i].tolist()
             for j in range(n):
                 if SA is None:
-                    D[t, i, j] = emulate_element(p, ai, B[t, j].tolist(), int(C[t, i, j]), ta, tb)
+                    D[t, i, j] = emulate_element(p, ai, B[t, j].tolist(), int(C[t, i, j]), ta, tb, tc=tc)
                 else:
                     D[t, i, j] = emulate_element(p, ai, B[t, j].tolist(), int(C[t, i, j]), ta, tb,
-                                                 np.asarray(SA)[t, i].tolist(), np.asarray(SB)[t, j].tolist(), block)
+                                                 np.asarray(SA)[t, i].tolist(), np.asarray(SB)[t, j].tolist(), block, tc)
     return D
 
 

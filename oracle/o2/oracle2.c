@@ -45,6 +45,7 @@ typedef struct {
     uint32_t family;     /* 0: chained FDPA, 1: FTZ-AddMul with P = group_len */
     uint32_t out_mant_bits; /* 23, or 13 (RZ-E8M13, with out_round = RZ) */
     uint32_t wide_products; /* RD mode: no infinity from a single product of magnitude >= 2^128 */
+    uint32_t acc_fp16;      /* accumulator and output are binary16 patterns (rho = RNE-FP16 / RZ-FP16); T-FDPA modes only */
 } o2_params;
 
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
@@ -89,14 +90,14 @@ static int bitlen128(u128 x)
 /* rho: round (-1)^neg * mag * 2^lsb to binary32.  `sticky` says the true magnitude is
  * a little more (sticky > 0) or less (sticky < 0) than mag * 2^lsb, by less than one
  * unit of 2^lsb; the caller guarantees the unit is far below any rounding boundary. */
-static uint32_t to_fp32(int neg, u128 mag, int lsb, int sticky, int mode)
+static uint32_t to_bin(int neg, u128 mag, int lsb, int sticky, int mode, int mb, int emin, int emax)
 {
     if (mag == 0) return 0u; /* exact zero -> +0.0 */
     if (sticky < 0) { mag -= 1; sticky = 1; } /* value in (mag-1, mag) units: floor is mag-1, remainder non-zero */
     int bl = bitlen128(mag);
     int e = bl - 1 + lsb;               /* floor(log2 |value|) */
-    int eg = e < -126 ? -126 : e;       /* exponent of the grid */
-    int qexp = eg - 23;                 /* weight of the last place */
+    int eg = e < emin ? emin : e;       /* exponent of the grid */
+    int qexp = eg - mb;                 /* weight of the last place */
     int sh = qexp - lsb;                /* drop `sh` low bits of mag (if positive) */
     u128 n; int half = 0, rest = sticky != 0;
     if (sh <= 0) {
@@ -111,20 +112,28 @@ static uint32_t to_fp32(int neg, u128 mag, int lsb, int sticky, int mode)
         rest |= (rem & (h - 1)) != 0;
     }
     if (mode == R_RNE && half && (rest || (n & 1))) n += 1;
-    if (n == ((u128)1 << 24)) { n >>= 1; eg += 1; }
+    if (n == ((u128)1 << (mb + 1))) { n >>= 1; eg += 1; }
     uint32_t out;
-    if (eg > 127) out = (mode == R_RNE) ? 0x7F800000u : 0x7F7FFFFFu;
-    else if (n < ((u128)1 << 23)) out = (uint32_t)n;           /* subnormal / zero, eg == -126 */
-    else out = ((uint32_t)(eg + 127) << 23) | ((uint32_t)n & 0x7FFFFFu);
-    return ((uint32_t)neg << 31) | out;
+    const uint32_t inf = (uint32_t)(2 * emax + 1) << mb;                 /* exponent field all ones */
+    if (eg > emax) out = (mode == R_RNE) ? inf : inf - 1u;
+    else if (n < ((u128)1 << mb)) out = (uint32_t)n;           /* subnormal / zero, eg == emin */
+    else out = ((uint32_t)(eg + emax) << mb) | ((uint32_t)n & ((1u << mb) - 1u));
+    return ((uint32_t)neg << (mb == 23 ? 31 : 15)) | out;
+}
+
+static uint32_t to_fp32(int neg, u128 mag, int lsb, int sticky, int mode) { return to_bin(neg, mag, lsb, sticky, mode, 23, -126, 127); }
+/* rho of the model: binary32, or binary16 when the accumulator and the output are FP16 */
+static uint32_t rho(const o2_params *p, int neg, u128 mag, int lsb, int sticky)
+{
+    return p->acc_fp16 ? to_bin(neg, mag, lsb, sticky, (int)p->out_round, 10, -14, 15) : to_fp32(neg, mag, lsb, sticky, (int)p->out_round);
 }
 
 /* exact x + y with x = sx*mx*2^lx, y likewise, then rho */
-static uint32_t add_exact_round(int sx, u128 mx, int lx, int sy, u128 my, int ly, int mode)
+static uint32_t add_exact_round(int sx, u128 mx, int lx, int sy, u128 my, int ly, const o2_params *p)
 {
     if (mx == 0 && my == 0) return 0u;
-    if (mx == 0) return to_fp32(sy, my, ly, 0, mode);
-    if (my == 0) return to_fp32(sx, mx, lx, 0, mode);
+    if (mx == 0) return rho(p, sy, my, ly, 0);
+    if (my == 0) return rho(p, sx, mx, lx, 0);
     if (lx < ly) { /* make x the one with the larger last-place exponent */
         int ts = sx; sx = sy; sy = ts; u128 tm = mx; mx = my; my = tm; int tl = lx; lx = ly; ly = tl;
     }
@@ -135,14 +144,14 @@ static uint32_t add_exact_round(int sx, u128 mx, int lx, int sy, u128 my, int ly
         i128 v = (i128)(mx << d) * (sx ? -1 : 1) + (i128)my * (sy ? -1 : 1);
         if (v == 0) return 0u;
         int neg = v < 0;
-        return to_fp32(neg, (u128)(neg ? -v : v), ly, 0, mode);
+        return rho(p, neg, (u128)(neg ? -v : v), ly, 0);
     }
     /* |y| < 2^(lx - 26): y lies more than 26 binary places below x's last place, while
      * binary32 rounding boundaries of x + y are multiples of 2^(lx - 25) or coarser;
      * so y only decides on which side of x the sum falls */
     u128 big = mx << 60;
     int st = (sx == sy) ? 1 : -1;
-    return to_fp32(sx, big, lx - 60, st, mode);
+    return rho(p, sx, big, lx - 60, st);
 }
 
 /* align magnitude `mag` (units 2^lsb) to units 2^(unit) with truncation toward zero */
@@ -240,6 +249,11 @@ static uint32_t rounded_sum_with_c(const o2_params *p, int have_T, i128 T, int e
 
 static uint32_t finish(const o2_params *p, uint32_t d)
 {
+    if (p->acc_fp16) {
+        if (p->ftz_out && (d & 0x7C00u) == 0) d &= 0x8000u;
+        if (p->zero_result_positive && (d & 0x7FFFu) == 0) d = 0u;
+        return d;
+    }
     if (p->out_mant_bits == 13) d &= 0xFFFFFC00u;         /* RZ-E8M13: the low 10 mantissa bits cut, toward zero */
     if (p->ftz_out && (d & 0x7F800000u) == 0) d &= 0x80000000u;
     if (p->zero_result_positive && (d & 0x7FFFFFFFu) == 0) d = 0u;
@@ -248,15 +262,28 @@ static uint32_t finish(const o2_params *p, uint32_t d)
 
 #define SCALE_NAN (-100000)          /* entry of the scale-exponent array for a NaN scale (E8M0 pattern 0xFF) */
 
+/* the NaN pattern of the output type (binary16: the low half of nan_bits) */
+static uint32_t nan_out(const o2_params *p) { return p->acc_fp16 ? (p->nan_bits & 0xFFFFu) : p->nan_bits; }
+
+/* the accumulator as sign, Exp and a 24-bit significand (value = sig 2^(exp - 23)); a binary16 accumulator keeps its own
+ * exponent range (Exp = -14 for zero and subnormals) and its 11-bit significand is moved up by 13 places */
+static dec_t dec_acc(const o2_params *p, uint32_t c)
+{
+    if (!p->acc_fp16) return dec_in(p, c, T_FP32);
+    dec_t d = dec_in(p, c & 0xFFFFu, T_FP16);
+    d.sig <<= 13;
+    return d;
+}
+
 static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t *b, const int *se, uint32_t c,
                            uint32_t L, int ta, int tb)
 {
-    if (se) for (uint32_t k = 0; k < L; ++k) if (se[k] == SCALE_NAN) return p->nan_bits;
+    if (se) for (uint32_t k = 0; k < L; ++k) if (se[k] == SCALE_NAN) return nan_out(p);
     const int F = (int)p->frac_bits;
     const int fa = FMT[ta].mbits, fb = FMT[tb].mbits;
     uint32_t c_mode = p->c_mode, split = p->split, trunc = p->acc_special_truncation;
     if (c_mode == C_AFTER_RD_EVEN_ODD) { c_mode = C_AFTER_RD; split = 1; trunc = 1; }   /* GTR-FDPA by name */
-    dec_t dc = dec_in(p, c, T_FP32);
+    dec_t dc = dec_acc(p, c);
 
     /* special values (Sec. 4.2) */
     int any_nan = dc.cls == CLS_NAN, pinf = 0, ninf = 0;
@@ -272,9 +299,9 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
         }
     }
     if (dc.cls == CLS_INF) { if (dc.sign) ninf = 1; else pinf = 1; }
-    if (any_nan || (pinf && ninf)) return p->nan_bits;
-    if (pinf) return 0x7F800000u;
-    if (ninf) return 0xFF800000u;
+    if (any_nan || (pinf && ninf)) return nan_out(p);
+    if (pinf) return p->acc_fp16 ? 0x7C00u : 0x7F800000u;
+    if (ninf) return p->acc_fp16 ? 0xFC00u : 0xFF800000u;
 
     if (c_mode == C_AFTER_RD) {
         if (split == 0) {
@@ -310,14 +337,14 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
         u128 al = align_rz((u128)dc.sig, dc.exp - 23, unit);
         if (dc.sign) S -= (i128)al; else S += (i128)al;
         int neg = S < 0;
-        return finish(p, to_fp32(neg, (u128)(neg ? -S : S), unit, 0, (int)p->out_round));
+        return finish(p, rho(p, neg, (u128)(neg ? -S : S), unit, 0));
     }
     /* C_AFTER_EXACT */
     if (!have) emax = 0;
     const int unit = emax - F;
     i128 S = part_sum(p, a, b, se, 0, 1, L, ta, tb, unit);
     int neg = S < 0;
-    return finish(p, add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, (int)p->out_round));
+    return finish(p, add_exact_round(neg, (u128)(neg ? -S : S), unit, dc.sign, (u128)dc.sig, dc.exp - 23, p));
 }
 
 /* ---- Algorithm "Phi_FTZ-AddMul" (Sec. 4.1.1) on the host's own binary32 arithmetic -------------------------
@@ -379,12 +406,14 @@ static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out
 {
     if (ta < 0 || ta > T_BF16 || tb < 0 || tb > T_BF16) return -2;
     if (p->family == 1) {
+        if (p->acc_fp16) return -2;
         if (p->group_len != 2 && p->group_len != 4) return -2;
         if (k == 0 || k > (1u << 20) || k % p->group_len) return -3;
         *L_out = p->group_len;
         return 0;
     }
     if (p->family > 1) return -2;
+    if (p->acc_fp16 && (p->c_mode >= C_AFTER_RD || p->out_mant_bits != 23)) return -2;
     if (p->out_mant_bits != 23 && !(p->out_mant_bits == 13 && p->out_round == R_RZ)) return -2;
     if (p->align_round != 0 || p->c_mode > 3 || p->out_round > 1 || p->frac_bits > 64) return -2;
     if (k == 0 || k > (1u << 20)) return -3;

@@ -23,7 +23,7 @@ class O2Params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
                 ("group_len", "frac_bits", "align_round", "c_mode", "out_round", "ftz_in", "ftz_out", "nan_bits", "frac_bits2", "split", "acc_special_truncation",
                  "frac_bits_merge", "frac_bits_acc", "skip_zero_terms", "f2_at_leading_bit", "zero_result_positive",
-                 "sum_drop_distance", "family", "out_mant_bits", "wide_products")]
+                 "sum_drop_distance", "family", "out_mant_bits", "wide_products", "acc_fp16")]
 
 
 def _load():
@@ -34,11 +34,12 @@ def _load():
     return _lib
 
 
-def _params(p):
+def _params(p, tc=fm.FP32):
     return O2Params(p.group_len, p.frac_bits, p.align_round, p.c_mode, p.out_round,
                     int(p.ftz_in), int(p.ftz_out), p.nan_bits, p.frac_bits2, p.split, int(p.acc_special_truncation),
                     p.frac_bits_merge, p.frac_bits_acc, int(p.skip_zero_terms), int(p.f2_at_leading_bit),
-                    int(p.zero_result_positive), p.sum_drop_distance, p.family, p.out_mant_bits, int(p.wide_products))
+                    int(p.zero_result_positive), p.sum_drop_distance, p.family, p.out_mant_bits, int(p.wide_products),
+                    1 if tc == fm.FP16 else 0)
 
 
 _NP = {fm.E4M3: np.uint8, fm.E5M2: np.uint8, fm.FP16: np.uint16, fm.BF16: np.uint16, fm.FP32: np.uint32}
@@ -60,12 +61,12 @@ def _vp(a):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
-def emulate_mma(p, A, B, C, ta, tb, nthreads=0):
-    """Same contract as oracle.fdpa.emulate_mma; returns (D, threads_used)."""
+def emulate_mma(p, A, B, C, ta, tb, nthreads=0, tc=fm.FP32):
+    """Same contract as oracle.fdpa.emulate_mma (tc = FP16: C and D hold binary16 patterns); returns (D, threads_used)."""
     A, B, C, nb, m, n, k = _prep(A, B, C, ta, tb)
     D = np.empty((nb, m, n), dtype=np.uint32)
     used = ctypes.c_int(0)
-    pp = _params(p)
+    pp = _params(p, tc)
     rc = _load().o2_emulate_mma(ctypes.byref(pp), _vp(A), _vp(B), _vp(C), _vp(D),
                                 ctypes.c_uint32(m), ctypes.c_uint32(n), ctypes.c_uint32(k),
                                 ctypes.c_uint64(nb), ta, tb, nthreads, ctypes.byref(used))
@@ -74,14 +75,14 @@ def emulate_mma(p, A, B, C, ta, tb, nthreads=0):
     return D, used.value
 
 
-def emulate_mma_scaled(p, A, B, C, SA, SB, block, ta, tb, nthreads=0):
+def emulate_mma_scaled(p, A, B, C, SA, SB, block, ta, tb, nthreads=0, tc=fm.FP32):
     """Algorithm "ST-FDPA": as emulate_mma with E8M0 block scales SA[batch][m][k/block], SB[batch][n][k/block]."""
     A, B, C, nb, m, n, k = _prep(A, B, C, ta, tb)
     SA = np.ascontiguousarray(np.asarray(SA).astype(np.uint8, copy=False)).reshape(nb, m, k // block)
     SB = np.ascontiguousarray(np.asarray(SB).astype(np.uint8, copy=False)).reshape(nb, n, k // block)
     D = np.empty((nb, m, n), dtype=np.uint32)
     used = ctypes.c_int(0)
-    pp = _params(p)
+    pp = _params(p, tc)
     rc = _load().o2_emulate_mma_scaled(ctypes.byref(pp), _vp(A), _vp(B), _vp(C), _vp(D), _vp(SA), _vp(SB), ctypes.c_uint32(block),
                                        ctypes.c_uint32(m), ctypes.c_uint32(n), ctypes.c_uint32(k),
                                        ctypes.c_uint64(nb), ta, tb, nthreads, ctypes.byref(used))

@@ -64,6 +64,37 @@ def to_fp32(v, mode):
     return (sign << 31) | mag
 
 
+def to_fp16(v, mode):
+    """Round the exact rational v to binary16 bits under `mode`: RNE-FP16 of the paper's table (RZ likewise, by
+    analogy with RZ-FP32).  Same rules as to_fp32 on the binary16 grid: 10 mantissa bits, exponents -14 .. 15,
+    gradual underflow, overflow to infinity (RNE) or to the largest finite value (RZ), exact zero -> +0.0."""
+    v = Fraction(v)
+    if v == 0:
+        return 0
+    sign = 1 if v < 0 else 0
+    a = -v if sign else v
+    e = max(floor_log2(a), -14)
+    q = a / Fraction(2) ** (e - 10)
+    n = q.numerator // q.denominator
+    rem = q - n
+    if mode == RNE:
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (n & 1)):
+            n += 1
+    elif mode != RZ:
+        raise ValueError(mode)
+    if n == (1 << 11):
+        n >>= 1
+        e += 1
+    if e > 15:
+        mag = 0x7C00 if mode == RNE else 0x7BFF
+    elif n < (1 << 10):
+        assert e == -14
+        mag = n
+    else:
+        mag = ((e + 15) << 10) | (n - (1 << 10))
+    return (sign << 15) | mag
+
+
 def rne_fp32(v):
     return to_fp32(v, RNE)
 
