@@ -56,7 +56,10 @@ typedef enum {
 } mmaemu_dtype;
 
 typedef struct {
-    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16}; c = d = FP32 */
+    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16}; c = d = FP32, or c = d = FP16
+                            (Algorithm "T-FDPA" with F_C = FP16: the accumulator is decoded as binary16, Exp >= -14,
+                            rho is RNE-FP16 of Table "Conversion functions" (RZ likewise), both flushes use 2^-14, the
+                            NaN pattern is the low half of nan_bits; c_mode C_IN_GROUP or C_AFTER_EXACT only) */
 } mmaemu_dtypes;
 
 enum { MMAEMU_C_IN_GROUP = 0, MMAEMU_C_AFTER_EXACT = 1, MMAEMU_C_AFTER_RD = 2, MMAEMU_C_AFTER_RD_EVEN_ODD = 3 };
@@ -180,7 +183,8 @@ mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const
  * SB[batch][n][k / block] (device, one byte each) hold E8M0 scale factors, value 2^(x - 127), 0xFF = NaN.
  * Every product of block q of a row takes Exp(alpha_q) + Exp(beta_q) on top of its exponent sum, in every
  * accumulation mode of the FDPA family; a NaN scale makes the group's result NaN.  k must be a multiple of
- * block.  Runs in the general kernel.
+ * block.  (Runs in the tiled kernels when block is a multiple of the group length and the operands are FP8 or
+ * FP16, else in the general kernel.)
  * Errors: as mmaemu_emulate_mma; SHAPE (block = 0 or k % block != 0), INVALID_ARG (NULL scales),
  *         UNSUPPORTED (FTZ-AddMul family).
  */

@@ -168,11 +168,16 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         set_error("emulate_mma: dtype out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if (!is_ab_type(dt.a) || !is_ab_type(dt.b) || dt.c != MMAEMU_FP32 || dt.d != MMAEMU_FP32) {
-        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16} and c = d = FP32");
+    const bool acc16 = dt.c == MMAEMU_FP16 && dt.d == MMAEMU_FP16;
+    if (!is_ab_type(dt.a) || !is_ab_type(dt.b) || !((dt.c == MMAEMU_FP32 && dt.d == MMAEMU_FP32) || acc16)) {
+        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16} and c = d = FP32 or c = d = FP16");
         return MMAEMU_ERR_UNSUPPORTED;
     }
     const mmaemu_model_params &mp = model->params;
+    if (acc16 && (mp.family != MMAEMU_FAMILY_FDPA || mp.c_mode > MMAEMU_C_AFTER_EXACT || mp.out_mant_bits != 23)) {
+        set_error("emulate_mma: FP16 accumulators go with c_mode C_IN_GROUP or C_AFTER_EXACT and the plain conversion");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
     if (SA && mp.family != MMAEMU_FAMILY_FDPA) { set_error("emulate_mma_scaled: block scales belong to the FDPA family"); return MMAEMU_ERR_UNSUPPORTED; }
     if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL) {
         if (k % mp.group_len) { set_error("emulate_mma: k=%u is not a multiple of P=%u", k, mp.group_len); return MMAEMU_ERR_SHAPE; }
@@ -236,7 +241,9 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     ma.ftz_in = mp.ftz_in;
     ma.ftz_out = mp.ftz_out;
     ma.nan_bits = mp.nan_bits;
-    ma.flags = (ma.out_round == MMAEMU_ROUND_RZ ? FL_RZ : 0u) | (ma.ftz_out ? FL_FTZ_OUT : 0u) | (ma.zero_result_positive ? FL_ZERO_POSITIVE : 0u) |
+    ma.nan16 = mp.nan_bits & 0xFFFFu;
+    if (acc16) ma.nan_bits = 0x7FC00000u;             // inside the kernels the accumulator is a binary32 pattern
+    ma.flags = (acc16 ? FL_ACC16 : 0u) | (ma.out_round == MMAEMU_ROUND_RZ ? FL_RZ : 0u) | (ma.ftz_out ? FL_FTZ_OUT : 0u) | (ma.zero_result_positive ? FL_ZERO_POSITIVE : 0u) |
                (ma.ftz_in ? FL_FTZ_IN : 0u) | (ma.acc_special_truncation ? FL_SPECIAL_TRUNC : 0u) | (ma.f2_at_leading_bit ? FL_F2_LEADING : 0u) |
                (ma.skip_zero_terms ? FL_SKIP_ZERO : 0u) | (ma.wide_products ? FL_WIDE_PRODUCTS : 0u);
     return launch_emulate(ma, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream, SA, SB, block);

@@ -29,7 +29,8 @@ inline FmtInfo fmt_info(uint32_t t)
 
 enum : uint32_t {
     FL_RZ = 1u, FL_FTZ_OUT = 2u, FL_ZERO_POSITIVE = 4u, FL_FTZ_IN = 8u, FL_SPECIAL_TRUNC = 16u, FL_F2_LEADING = 32u,
-    FL_SKIP_ZERO = 64u, FL_WIDE_PRODUCTS = 128u
+    FL_SKIP_ZERO = 64u, FL_WIDE_PRODUCTS = 128u,
+    FL_ACC16 = 256u      // accumulator and output are binary16 (C and D hold 16-bit patterns)
 };
 
 // Model parameters as the kernels take them (by value).
@@ -45,6 +46,9 @@ struct ModelArgs {
     int32_t sum_drop_distance;
     uint32_t out_mask;   // 0xFFFFFFFF, or 0xFFFFFC00 for the E8M13 output conversion
     uint32_t flags;      // the switches above once more, one FL_* bit each (the tiled kernels test these)
+    // FL_ACC16: inside the kernels a binary16 accumulator travels as the binary32 pattern of the same value (every
+    // binary16 number is one); nan_bits is then a binary32 quiet NaN and nan16 the pattern written to D for it
+    uint32_t nan16;
 };
 
 // error plumbing (api.hip)
@@ -118,15 +122,68 @@ __device__ __forceinline__ uint32_t round_to_fp32(uint32_t neg, uint64_t mag, in
     return (neg << 31) | out;
 }
 
+// The same onto the binary16 grid (10 mantissa bits, exponents -14 .. 15: rho = RNE-FP16 of the paper's table, or its
+// RZ counterpart); the result is returned as the binary32 pattern of that binary16 number.
+__device__ __forceinline__ uint32_t round_to_fp16_as_fp32(uint32_t neg, uint64_t mag, int lsb, uint32_t sticky, uint32_t mode)
+{
+    const int bl = 64 - __builtin_clzll(mag);
+    const int e = bl - 1 + lsb;
+    int eg = e < -14 ? -14 : e;
+    const int sh = eg - 10 - lsb;
+    uint64_t n;
+    uint32_t half = 0, rest = sticky;
+    if (sh <= 0) {
+        n = mag << (-sh);
+    } else if (sh >= 64) {
+        n = 0;
+        if (sh == 64) { half = (uint32_t)(mag >> 63); rest |= (mag << 1) != 0; }
+        else rest |= 1u;
+    } else {
+        n = mag >> sh;
+        half = (uint32_t)(mag >> (sh - 1)) & 1u;
+        rest |= (mag & ((1ull << (sh - 1)) - 1ull)) != 0;
+    }
+    if (mode == MMAEMU_ROUND_RNE && half && (rest || (n & 1ull))) n += 1;
+    if (n == (1ull << 11)) { n >>= 1; eg += 1; }
+    uint32_t out;
+    if (eg > 15) out = (mode == MMAEMU_ROUND_RNE) ? 0x7F800000u : 0x477FE000u;       // infinity, or 65504
+    else if (n == 0) out = 0u;
+    else {
+        const int nb = 32 - __builtin_clz((uint32_t)n);                              // n < 2^11: value n 2^(eg - 10)
+        out = ((uint32_t)(eg - 10 + nb - 1 + 127) << 23) | (((uint32_t)n << (24 - nb)) & 0x7FFFFFu);
+    }
+    return (neg << 31) | out;
+}
+__device__ __forceinline__ uint32_t round_out(bool acc16, uint32_t neg, uint64_t mag, int lsb, uint32_t sticky, uint32_t mode)
+{
+    return acc16 ? round_to_fp16_as_fp32(neg, mag, lsb, sticky, mode) : round_to_fp32(neg, mag, lsb, sticky, mode);
+}
+
+// binary16 pattern <-> the binary32 pattern of the same value
+__device__ __forceinline__ uint32_t half_bits_to_float_bits(uint32_t h)
+{
+    _Float16 x;
+    const uint16_t hb = (uint16_t)h;
+    __builtin_memcpy(&x, &hb, 2);
+    return __float_as_uint((float)x);                     // exact; NaN stays NaN
+}
+__device__ __forceinline__ uint32_t float_bits_to_half_bits(uint32_t f)      // f holds a binary16 number (or inf / NaN)
+{
+    const _Float16 x = (_Float16)__uint_as_float(f);
+    uint16_t hb;
+    __builtin_memcpy(&hb, &x, 2);
+    return hb;
+}
+
 // rho(x + y) with the two-term sum exact: x = (-1)^sx mx 2^lx, y likewise; magnitudes
 // below 2^60.  Both are left-justified to bit 62; the smaller is shifted down with the
 // lost bits remembered, which happens only when the gap exceeds 3 places, i.e. when at
 // most one leading bit can cancel, so the remembered bits stay below the rounding place.
-__device__ __forceinline__ uint32_t add_exact_round(uint32_t sx, uint64_t mx, int lx, uint32_t sy, uint64_t my, int ly, uint32_t mode)
+__device__ __forceinline__ uint32_t add_exact_round(uint32_t sx, uint64_t mx, int lx, uint32_t sy, uint64_t my, int ly, uint32_t mode, bool acc16 = false)
 {
     if (mx == 0 && my == 0) return 0u;
-    if (mx == 0) return round_to_fp32(sy, my, ly, 0, mode);
-    if (my == 0) return round_to_fp32(sx, mx, lx, 0, mode);
+    if (mx == 0) return round_out(acc16, sy, my, ly, 0, mode);
+    if (my == 0) return round_out(acc16, sx, mx, lx, 0, mode);
     int nx = __builtin_clzll(mx) - 1, ny = __builtin_clzll(my) - 1;
     mx <<= nx; lx -= nx;
     my <<= ny; ly -= ny;
@@ -143,7 +200,7 @@ __device__ __forceinline__ uint32_t add_exact_round(uint32_t sx, uint64_t mx, in
     if (sx == sy) r = mx + ys;             // true sum in [r, r+1)
     else r = mx - ys - lost;               // true difference in (r, r+1) when lost, == r otherwise
     if (r == 0 && !lost) return 0u;        // exact cancellation -> +0.0
-    return round_to_fp32(sx, r, lx, lost, mode);
+    return round_out(acc16, sx, r, lx, lost, mode);
 }
 
 #endif // __HIPCC__

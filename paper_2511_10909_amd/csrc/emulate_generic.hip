@@ -27,7 +27,9 @@ emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A
         const uint32_t i = r / n, j = r - i * n;
         const typename Fmt<TA>::elem *a = A + (t * m + i) * (uint64_t)k;
         const typename Fmt<TB>::elem *b = B + (t * n + j) * (uint64_t)k;
-        uint32_t d = C[o];
+        const bool acc16 = (p.flags & FL_ACC16) != 0;
+        uint32_t d = acc16 ? half_bits_to_float_bits(reinterpret_cast<const uint16_t *>(C)[o]) : C[o];
+        if (acc16 && (d & 0x7FFFFFFFu) > 0x7F800000u) d = p.nan_bits;
         ScaleRef sr = no_scales();
         if (SA) {                                   // Algorithm "ST-FDPA": this row's and this column's block scales
             sr.sa = SA + (t * m + i) * (uint64_t)(k / block);
@@ -38,7 +40,8 @@ emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A
             sr.k0 = k0;
             d = fdpa_group<TA, TB>(p, a + k0, b + k0, p.L, d, sr);
         }
-        D[o] = d;
+        if (acc16) reinterpret_cast<uint16_t *>(D)[o] = (uint16_t)((d & 0x7FFFFFFFu) > 0x7F800000u ? p.nan16 : float_bits_to_half_bits(d));
+        else D[o] = d;
     }
 }
 

@@ -291,6 +291,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     const uint32_t fl = p.flags;                      // the model's switches, one bit each (one scalar register)
     // The group epilogues test the switches on a copy that is made opaque each time: otherwise every test is
     // hoisted out of the loops as a wave-wide mask (two scalar registers apiece, live across the hot loops).
+    const int ec_floor = (fl & FL_ACC16) ? -14 : -126;          // smallest Exp of the accumulator's type
     uint32_t fe = fl;
     auto refresh_switches = [&]() {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -327,7 +328,10 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 #pragma unroll
     for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int c = 0; c < C; ++c) d[r][c] = Cm[d_off + (uint64_t)(TI * r) * n + TJ * c];
+        for (int c = 0; c < C; ++c) {
+            const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
+            d[r][c] = (fl & FL_ACC16) ? half_bits_to_float_bits(reinterpret_cast<const uint16_t *>(Cm)[o]) : Cm[o];
+        }
 
     const float *av = reinterpret_cast<const float *>(Av_raw) + (slot * TM + ti) * VS;
     const float *bv = reinterpret_cast<const float *>(Bv_raw) + (slot * TN + tj) * VS;
@@ -527,7 +531,8 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         tagged |= e;
         if (CMODE == MMAEMU_C_IN_GROUP) {
             const uint32_t Ec = (d[r][c] >> 23) & 0xFFu;               // (a flushed subnormal keeps Exp = -126)
-            const int ec = (int)(Ec ? Ec : 1u) - 127;
+            int ec = (int)(Ec ? Ec : 1u) - 127;
+            ec = ec > ec_floor ? ec : ec_floor;                        // (a binary16 accumulator: Exp >= -14)
             em = ec > em ? ec : em;
         }
         emax = em;
@@ -596,21 +601,48 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int c = 0; c < C; ++c) dn[r][c] = __float_as_uint((float)v[r][c]);
-        if ((fe & (FL_RZ | FL_FTZ_OUT | FL_ZERO_POSITIVE))) {
+        if ((fe & (FL_ACC16 | FL_RZ | FL_FTZ_OUT | FL_ZERO_POSITIVE))) {       // (one test on the common path: none of them)
+            if ((fe & FL_ACC16)) {
+                // rho onto the binary16 grid: the value is first brought to binary32 rounded to odd (24 bits, far more than
+                // binary16's 11 plus a guard bit), then one hardware conversion gives RNE-FP16 with gradual underflow and
+                // overflow; RZ steps back where that rounded away from zero.  The accumulator keeps travelling as the
+                // binary32 pattern of the binary16 result.
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    uint32_t o = dn[r][c];
-                    if ((fe & FL_RZ)) {
-                        const double back = (double)__uint_as_float(o);
-                        if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) o -= 1u;   // rounded away from zero: step back
-                        o &= p.out_mask;                                               // RZ-E8M13 cuts further, still toward zero
+                    for (int c = 0; c < C; ++c) {
+                        uint32_t fb = dn[r][c];
+                        const double back = (double)__uint_as_float(fb);
+                        if (back != v[r][c]) {                                             // inexact (a NaN stays a NaN through this)
+                            if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) fb -= 1u;
+                            fb |= 1u;
+                        }
+                        uint32_t hb = float_bits_to_half_bits(fb);
+                        if ((fe & FL_RZ) && (hb & 0x7FFFu) <= 0x7C00u) {
+                            const double hv = (double)__uint_as_float(half_bits_to_float_bits(hb));
+                            if (__builtin_fabs(hv) > __builtin_fabs(v[r][c])) hb -= 1u;
+                        }
+                        uint32_t o = half_bits_to_float_bits(hb);
+                        if ((fe & FL_FTZ_OUT) && (o & 0x7F800000u) < (113u << 23)) o &= 0x80000000u;   // |d| < 2^-14
+                        if ((fe & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
+                        dn[r][c] = o;
                     }
-                    if ((fe & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
-                    if ((fe & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
-                    dn[r][c] = o;
-                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        uint32_t o = dn[r][c];
+                        if ((fe & FL_RZ)) {
+                            const double back = (double)__uint_as_float(o);
+                            if (__builtin_fabs(back) > __builtin_fabs(v[r][c])) o -= 1u;   // rounded away from zero: step back
+                            o &= p.out_mask;                                               // RZ-E8M13 cuts further, still toward zero
+                        }
+                        if ((fe & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                        if ((fe & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
+                        dn[r][c] = o;
+                    }
+            }
         }
         if (tagged & SENTINEL_MASK) {                                   // rare: the group met a tagged element
 #pragma unroll
@@ -627,11 +659,12 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 
     auto flush_accumulators = [&]() {
         if ((fe & FL_FTZ_IN)) {                                                 // FlushSubnormal on the accumulator
+            const uint32_t first_normal = (fe & FL_ACC16) ? (113u << 23) : (1u << 23);  // 2^-14 for binary16, 2^-126
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int c = 0; c < C; ++c)
-                    if ((d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;
+                    if ((d[r][c] & 0x7F800000u) < first_normal) d[r][c] = 0;
         }
     };
 
@@ -888,7 +921,11 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) D[d_off + (uint64_t)(TI * r) * n + TJ * c] = d[r][c];
+            for (int c = 0; c < C; ++c) {
+                const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
+                if (fl & FL_ACC16) reinterpret_cast<uint16_t *>(D)[o] = (uint16_t)(d[r][c] == p.nan_bits ? p.nan16 : float_bits_to_half_bits(d[r][c]));
+                else D[o] = d[r][c];
+            }
     }
 }
 

@@ -25,7 +25,7 @@ PAIRS = [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, f
          (fm.E4M3, fm.E4M3), (fm.E5M2, fm.E5M2), (fm.FP16, fm.BF16), (fm.E4M3, fm.FP16), (fm.BF16, fm.E5M2)]
 
 
-def gpu_emulate(mm, p, A, B, C, ta, tb):
+def gpu_emulate(mm, p, A, B, C, ta, tb, tc=fm.FP32):
     nb, m, k = A.shape
     n = B.shape[1]
     h = mm.model_create(group_len=p.group_len, frac_bits=p.frac_bits, frac_bits2=p.frac_bits2, c_mode=p.c_mode, out_round=p.out_round,
@@ -36,11 +36,11 @@ def gpu_emulate(mm, p, A, B, C, ta, tb):
                         sum_drop_distance=p.sum_drop_distance, family=p.family, out_mant_bits=p.out_mant_bits,
                         wide_products=p.wide_products)
     try:
-        dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(np.uint32))
-        dD = dev_empty((nb, m, n), np.uint32)
-        mm.emulate_mma(h, dA, dB, dC, dD, m, n, k, nb, (ta, tb, fm.FP32, fm.FP32))
+        dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(NP[tc]))
+        dD = dev_empty((nb, m, n), NP[tc])
+        mm.emulate_mma(h, dA, dB, dC, dD, m, n, k, nb, (ta, tb, tc, tc))
         gpu_emulate.last_kernel = mm.last_kernel()
-        return to_host(dD, np.uint32)
+        return to_host(dD, NP[tc]).astype(np.uint32)
     finally:
         mm.model_destroy(h)
 
