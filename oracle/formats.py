@@ -15,12 +15,15 @@ and nothing is renormalised.
 
 FP8 flavours are the OCP ones: E4M3 has no infinity and a single NaN mantissa
 (S.1111.111), its largest finite value is 448; E5M2 is IEEE-like with
-largest finite value 57344.
+largest finite value 57344.  FP6 (E2M3, E3M2) and FP4 (E2M1) are the OCP
+microscaling element formats: every code is a finite number (no infinity, no
+NaN); codes are held one per byte in their low 6 / 4 bits, higher bits ignored.
 """
 from dataclasses import dataclass
 from fractions import Fraction
 
 E4M3, E5M2, FP16, BF16, FP32 = 0, 1, 2, 3, 4
+E2M3, E3M2, E2M1 = 6, 7, 8          # (5 is the E8M0 scale code, which is no operand type)
 
 
 @dataclass(frozen=True)
@@ -30,6 +33,7 @@ class Format:
     mbits: int
     bias: int
     ieee_specials: bool  # True: exponent field all-ones = Inf/NaN.  False: E4M3 rule.
+    no_specials: bool = False   # every code is finite (FP6, FP4)
 
     @property
     def width(self):
@@ -46,6 +50,9 @@ FORMATS = {
     FP16: Format("fp16", 5, 10, 15, True),
     BF16: Format("bf16", 8, 7, 127, True),
     FP32: Format("fp32", 8, 23, 127, True),
+    E2M3: Format("e2m3", 2, 3, 1, False, True),
+    E3M2: Format("e3m2", 3, 2, 3, False, True),
+    E2M1: Format("e2m1", 2, 1, 1, False, True),
 }
 
 ZERO, SUBNORMAL, NORMAL, INF, NAN = "zero", "subnormal", "normal", "inf", "nan"
@@ -82,7 +89,7 @@ def decode(bits, fmt_id):
     M = bits & ((1 << f.mbits) - 1)
     if f.ieee_specials and E == f.emax_field:
         return Decoded(INF if M == 0 else NAN, sign, 0, 0, f.mbits)
-    if not f.ieee_specials and E == f.emax_field and M == (1 << f.mbits) - 1:
+    if not f.ieee_specials and not f.no_specials and E == f.emax_field and M == (1 << f.mbits) - 1:
         return Decoded(NAN, sign, 0, 0, f.mbits)
     if E == 0:
         return Decoded(ZERO if M == 0 else SUBNORMAL, sign, 1 - f.bias, M, f.mbits)

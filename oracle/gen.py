@@ -81,6 +81,8 @@ def _words(seed, operand, w):
 
 
 def _n_finite_magnitudes(f):
+    if f.no_specials:
+        return (f.emax_field + 1) << f.mbits
     return (f.emax_field << f.mbits) if f.ieee_specials else ((f.emax_field + 1) << f.mbits) - 1
 
 

@@ -33,7 +33,7 @@
 typedef __int128 i128;
 typedef unsigned __int128 u128;
 
-enum { T_E4M3 = 0, T_E5M2 = 1, T_FP16 = 2, T_BF16 = 3, T_FP32 = 4 };
+enum { T_E4M3 = 0, T_E5M2 = 1, T_FP16 = 2, T_BF16 = 3, T_FP32 = 4, T_E8M0 = 5, T_E2M3 = 6, T_E3M2 = 7, T_E2M1 = 8 };
 enum { CLS_ZERO, CLS_SUB, CLS_NORMAL, CLS_INF, CLS_NAN };
 enum { C_IN_GROUP = 0, C_AFTER_EXACT = 1, C_AFTER_RD = 2, C_AFTER_RD_EVEN_ODD = 3 };
 enum { R_RNE = 0, R_RZ = 1 };
@@ -48,9 +48,11 @@ typedef struct {
     uint32_t acc_fp16;      /* accumulator and output are binary16 patterns (rho = RNE-FP16 / RZ-FP16); T-FDPA modes only */
 } o2_params;
 
+/* ieee: 1 = exponent field all ones is Inf / NaN, 0 = the E4M3 rule (one NaN code), 2 = every code finite (FP6, FP4) */
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
-static const fmt_t FMT[5] = {
-    {4, 3, 7, 0}, {5, 2, 15, 1}, {5, 10, 15, 1}, {8, 7, 127, 1}, {8, 23, 127, 1}};
+static const fmt_t FMT[9] = {
+    {4, 3, 7, 0}, {5, 2, 15, 1}, {5, 10, 15, 1}, {8, 7, 127, 1}, {8, 23, 127, 1}, {8, 0, 127, 2},
+    {2, 3, 1, 2}, {3, 2, 3, 2}, {2, 1, 1, 2}};
 
 typedef struct { int cls, sign, exp; uint32_t sig; } dec_t;
 
@@ -63,8 +65,8 @@ static dec_t decode(uint32_t bits, int t)
     uint32_t M = bits & ((1u << f.mbits) - 1u);
     d.sign = (bits >> (f.ebits + f.mbits)) & 1u;
     d.exp = 0; d.sig = 0;
-    if (f.ieee && E == emask) { d.cls = M ? CLS_NAN : CLS_INF; return d; }
-    if (!f.ieee && E == emask && M == ((1u << f.mbits) - 1u)) { d.cls = CLS_NAN; return d; }
+    if (f.ieee == 1 && E == emask) { d.cls = M ? CLS_NAN : CLS_INF; return d; }
+    if (f.ieee == 0 && E == emask && M == ((1u << f.mbits) - 1u)) { d.cls = CLS_NAN; return d; }
     if (E == 0) { d.cls = M ? CLS_SUB : CLS_ZERO; d.exp = 1 - f.bias; d.sig = M; return d; }
     d.cls = CLS_NORMAL; d.exp = (int)E - f.bias; d.sig = (1u << f.mbits) | M;
     return d;
@@ -73,7 +75,7 @@ static dec_t decode(uint32_t bits, int t)
 static uint32_t load_elem(const void *p, size_t i, int t)
 {
     switch (t) {
-    case T_E4M3: case T_E5M2: return ((const uint8_t *)p)[i];
+    case T_E4M3: case T_E5M2: case T_E2M3: case T_E3M2: case T_E2M1: return ((const uint8_t *)p)[i];
     case T_FP16: case T_BF16: return ((const uint16_t *)p)[i];
     default: return ((const uint32_t *)p)[i];
     }
@@ -404,7 +406,7 @@ static uint32_t addmul_element(const o2_params *p, const void *A, const void *B,
 
 static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out)
 {
-    if (ta < 0 || ta > T_BF16 || tb < 0 || tb > T_BF16) return -2;
+    if (ta < 0 || tb < 0 || ta > T_E2M1 || tb > T_E2M1 || ta == T_FP32 || tb == T_FP32 || ta == T_E8M0 || tb == T_E8M0) return -2;
     if (p->family == 1) {
         if (p->acc_fp16) return -2;
         if (p->group_len != 2 && p->group_len != 4) return -2;
