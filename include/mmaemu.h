@@ -50,13 +50,20 @@ typedef enum {
     MMAEMU_FP16 = 2,
     MMAEMU_BF16 = 3,
     MMAEMU_FP32 = 4,
-    MMAEMU_E8M0 = 5 /* block-scale codes (Algorithm "ST-FDPA"): one byte, 2^(code - 127), 0xFF = NaN; no sign, no
-                       mantissa.  Only mmaemu_generate takes it (families ZERO, RANDOM_BITS, UNIFORM_EXP, where the
-                       "exponent field" is the whole code). */
+    MMAEMU_E8M0 = 5, /* block-scale codes (Algorithm "ST-FDPA"): one byte, 2^(code - 127), 0xFF = NaN; no sign, no
+                        mantissa.  Only mmaemu_generate takes it (families ZERO, RANDOM_BITS, UNIFORM_EXP, where the
+                        "exponent field" is the whole code). */
+    /* FP6 and FP4 operands (element formats of the OCP microscaling specification; Require lines of Algorithms
+     * "T-FDPA" and "ST-FDPA"): every code is a finite number; one code per byte in its low 6 / 4 bits (sign on top),
+     * higher bits ignored on input and written as zero by mmaemu_generate. */
+    MMAEMU_FP6_E2M3 = 6, /* bias 1, largest 7.5 */
+    MMAEMU_FP6_E3M2 = 7, /* bias 3, largest 28 */
+    MMAEMU_FP4_E2M1 = 8  /* bias 1, largest 6 */
 } mmaemu_dtype;
 
 typedef struct {
-    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16}; c = d = FP32, or c = d = FP16
+    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1} (the FP6 / FP4 types
+                            pair with each other and with the FP8 types); c = d = FP32, or c = d = FP16
                             (Algorithm "T-FDPA" with F_C = FP16: the accumulator is decoded as binary16, Exp >= -14,
                             rho is RNE-FP16 of Table "Conversion functions" (RZ likewise), both flushes use 2^-14, the
                             NaN pattern is the low half of nan_bits; c_mode C_IN_GROUP or C_AFTER_EXACT only) */

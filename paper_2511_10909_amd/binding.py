@@ -10,6 +10,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmmaemu.so")
 
 E4M3, E5M2, FP16, BF16, FP32, E8M0 = 0, 1, 2, 3, 4, 5
+E2M3, E3M2, E2M1 = 6, 7, 8                      # FP6 and FP4 operands, one code per byte
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 RNE, RZ = 0, 1
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES = 0, 1, 2
@@ -22,7 +23,7 @@ SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
  MFMA_F32_16X16X32_BF8_FP8, MFMA_F32_16X16X32_BF8_BF8) = range(10)
 (MFMA_SCALE_F32_16X16X128_FP8_FP8, MFMA_SCALE_F32_16X16X128_FP8_BF8, MFMA_SCALE_F32_16X16X128_BF8_FP8,
  MFMA_SCALE_F32_16X16X128_BF8_BF8) = range(10, 14)
-ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1}
+ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1}
 NO_MISMATCH = (1 << 64) - 1
 
 

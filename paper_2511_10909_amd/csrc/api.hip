@@ -41,7 +41,7 @@ mmaemu_status hip_fail(hipError_t e, const char *what)
     return MMAEMU_ERR_HIP;
 }
 
-static bool is_ab_type(uint32_t t) { return t <= MMAEMU_BF16; }
+static bool is_ab_type(uint32_t t) { return t <= MMAEMU_BF16 || is_narrow_type(t); }
 
 static uint32_t ceil_log2(uint32_t x)
 {
@@ -164,13 +164,17 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     if (!model || model->magic != MODEL_MAGIC) { set_error("emulate_mma: bad model handle"); return MMAEMU_ERR_INVALID_ARG; }
     if (m == 0 || n == 0 || k == 0) { set_error("emulate_mma: zero dimension (m=%u n=%u k=%u)", m, n, k); return MMAEMU_ERR_SHAPE; }
     if (k > (1u << 20)) { set_error("emulate_mma: k=%u > 2^20", k); return MMAEMU_ERR_SHAPE; }
-    if (dt.a > MMAEMU_FP32 || dt.b > MMAEMU_FP32 || dt.c > MMAEMU_FP32 || dt.d > MMAEMU_FP32) {
+    if (dt.a > MMAEMU_FP4_E2M1 || dt.b > MMAEMU_FP4_E2M1 || dt.c > MMAEMU_FP32 || dt.d > MMAEMU_FP32) {
         set_error("emulate_mma: dtype out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
     const bool acc16 = dt.c == MMAEMU_FP16 && dt.d == MMAEMU_FP16;
     if (!is_ab_type(dt.a) || !is_ab_type(dt.b) || !((dt.c == MMAEMU_FP32 && dt.d == MMAEMU_FP32) || acc16)) {
-        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16} and c = d = FP32 or c = d = FP16");
+        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1} and c = d = FP32 or c = d = FP16");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if ((is_narrow_type(dt.a) && !is_byte_type(dt.b)) || (is_narrow_type(dt.b) && !is_byte_type(dt.a))) {
+        set_error("emulate_mma: FP6 / FP4 operands pair with FP6, FP4 and FP8 operands only");
         return MMAEMU_ERR_UNSUPPORTED;
     }
     const mmaemu_model_params &mp = model->params;
@@ -179,6 +183,10 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         return MMAEMU_ERR_UNSUPPORTED;
     }
     if (SA && mp.family != MMAEMU_FAMILY_FDPA) { set_error("emulate_mma_scaled: block scales belong to the FDPA family"); return MMAEMU_ERR_UNSUPPORTED; }
+    if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL && (is_narrow_type(dt.a) || is_narrow_type(dt.b))) {
+        set_error("emulate_mma: the FTZ-AddMul family takes FP8, FP16 and BF16 operands");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
     if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL) {
         if (k % mp.group_len) { set_error("emulate_mma: k=%u is not a multiple of P=%u", k, mp.group_len); return MMAEMU_ERR_SHAPE; }
         const uint64_t mn_ = (uint64_t)m * n;
@@ -292,7 +300,7 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
         set_error("generate: struct_size %u, expected %zu", g->struct_size, sizeof(mmaemu_gen_params));
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if ((uint32_t)dtype > MMAEMU_E8M0 || g->family > MMAEMU_GEN_CANCELLING || g->scale_scope > MMAEMU_SCALE_TILE) {
+    if ((uint32_t)dtype > MMAEMU_FP4_E2M1 || g->family > MMAEMU_GEN_CANCELLING || g->scale_scope > MMAEMU_SCALE_TILE) {
         set_error("generate: enum out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }

@@ -8,24 +8,34 @@ namespace mmaemu {
 
 // Operand encodings (OCP FP8, IEEE binary16, bfloat16, binary32).
 template <int T> struct Fmt;
-template <> struct Fmt<MMAEMU_FP8_E4M3> { static constexpr int EB = 4, MB = 3, BIAS = 7, W = 8; static constexpr bool IEEE = false; using elem = uint8_t; };
-template <> struct Fmt<MMAEMU_FP8_E5M2> { static constexpr int EB = 5, MB = 2, BIAS = 15, W = 8; static constexpr bool IEEE = true; using elem = uint8_t; };
-template <> struct Fmt<MMAEMU_FP16> { static constexpr int EB = 5, MB = 10, BIAS = 15, W = 16; static constexpr bool IEEE = true; using elem = uint16_t; };
-template <> struct Fmt<MMAEMU_BF16> { static constexpr int EB = 8, MB = 7, BIAS = 127, W = 16; static constexpr bool IEEE = true; using elem = uint16_t; };
-template <> struct Fmt<MMAEMU_FP32> { static constexpr int EB = 8, MB = 23, BIAS = 127, W = 32; static constexpr bool IEEE = true; using elem = uint32_t; };
+// W: storage width; IEEE: exponent field all ones is Inf / NaN; NOSPEC: every code is finite (else, without IEEE, the
+// E4M3 rule: one NaN code)
+template <> struct Fmt<MMAEMU_FP8_E4M3> { static constexpr int EB = 4, MB = 3, BIAS = 7, W = 8; static constexpr bool IEEE = false, NOSPEC = false; using elem = uint8_t; };
+template <> struct Fmt<MMAEMU_FP8_E5M2> { static constexpr int EB = 5, MB = 2, BIAS = 15, W = 8; static constexpr bool IEEE = true, NOSPEC = false; using elem = uint8_t; };
+template <> struct Fmt<MMAEMU_FP16> { static constexpr int EB = 5, MB = 10, BIAS = 15, W = 16; static constexpr bool IEEE = true, NOSPEC = false; using elem = uint16_t; };
+template <> struct Fmt<MMAEMU_BF16> { static constexpr int EB = 8, MB = 7, BIAS = 127, W = 16; static constexpr bool IEEE = true, NOSPEC = false; using elem = uint16_t; };
+template <> struct Fmt<MMAEMU_FP32> { static constexpr int EB = 8, MB = 23, BIAS = 127, W = 32; static constexpr bool IEEE = true, NOSPEC = false; using elem = uint32_t; };
+template <> struct Fmt<MMAEMU_FP6_E2M3> { static constexpr int EB = 2, MB = 3, BIAS = 1, W = 8; static constexpr bool IEEE = false, NOSPEC = true; using elem = uint8_t; };
+template <> struct Fmt<MMAEMU_FP6_E3M2> { static constexpr int EB = 3, MB = 2, BIAS = 3, W = 8; static constexpr bool IEEE = false, NOSPEC = true; using elem = uint8_t; };
+template <> struct Fmt<MMAEMU_FP4_E2M1> { static constexpr int EB = 2, MB = 1, BIAS = 1, W = 8; static constexpr bool IEEE = false, NOSPEC = true; using elem = uint8_t; };
 
-struct FmtInfo { int ebits, mbits, bias, width; bool ieee; };
+struct FmtInfo { int ebits, mbits, bias, width; bool ieee, nospec; };      // width: storage bits
 inline FmtInfo fmt_info(uint32_t t)
 {
     switch (t) {
-    case MMAEMU_FP8_E4M3: return {4, 3, 7, 8, false};
-    case MMAEMU_FP8_E5M2: return {5, 2, 15, 8, true};
-    case MMAEMU_FP16: return {5, 10, 15, 16, true};
-    case MMAEMU_BF16: return {8, 7, 127, 16, true};
-    case MMAEMU_E8M0: return {8, 0, 127, 8, false};
-    default: return {8, 23, 127, 32, true};
+    case MMAEMU_FP8_E4M3: return {4, 3, 7, 8, false, false};
+    case MMAEMU_FP8_E5M2: return {5, 2, 15, 8, true, false};
+    case MMAEMU_FP16: return {5, 10, 15, 16, true, false};
+    case MMAEMU_BF16: return {8, 7, 127, 16, true, false};
+    case MMAEMU_E8M0: return {8, 0, 127, 8, false, true};
+    case MMAEMU_FP6_E2M3: return {2, 3, 1, 8, false, true};
+    case MMAEMU_FP6_E3M2: return {3, 2, 3, 8, false, true};
+    case MMAEMU_FP4_E2M1: return {2, 1, 1, 8, false, true};
+    default: return {8, 23, 127, 32, true, false};
     }
 }
+inline bool is_narrow_type(uint32_t t) { return t == MMAEMU_FP6_E2M3 || t == MMAEMU_FP6_E3M2 || t == MMAEMU_FP4_E2M1; }   // FP6 / FP4
+inline bool is_byte_type(uint32_t t) { return t <= MMAEMU_FP8_E5M2 || is_narrow_type(t); }
 
 enum : uint32_t {
     FL_RZ = 1u, FL_FTZ_OUT = 2u, FL_ZERO_POSITIVE = 4u, FL_FTZ_IN = 8u, FL_SPECIAL_TRUNC = 16u, FL_F2_LEADING = 32u,

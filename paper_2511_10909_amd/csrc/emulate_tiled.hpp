@@ -103,8 +103,8 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, uint
         if (ftz_in && E == 0) val = 0.0f;
         if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
     } else {
-        uint32_t M = bits & MMASK, sign = (bits >> 7) & 1u;
-        const bool special = F::IEEE ? (E == EMASK) : (E == EMASK && M == MMASK);
+        uint32_t M = bits & MMASK, sign = (bits >> (F::EB + F::MB)) & 1u;
+        const bool special = F::IEEE ? (E == EMASK) : (!F::NOSPEC && E == EMASK && M == MMASK);
         if (ftz_in && E == 0) { M = 0; sign = 0; }
         const uint32_t sig = E ? (M | (1u << F::MB)) : M;
         const float mag = ldexpf((float)sig, (int)(E ? E : 1u) - F::BIAS - F::MB);   // exact
@@ -201,6 +201,9 @@ __device__ __forceinline__ bool decode_any(uint32_t t, const uint2 (&raw)[NQ], u
     case MMAEMU_FP8_E4M3: return decode_panel<MMAEMU_FP8_E4M3, NQ>(raw, ftz_in, zbias, f, e);
     case MMAEMU_FP8_E5M2: return decode_panel<MMAEMU_FP8_E5M2, NQ>(raw, ftz_in, zbias, f, e);
     case MMAEMU_FP16: return decode_panel<MMAEMU_FP16, NQ>(raw, ftz_in, zbias, f, e);
+    case MMAEMU_FP6_E2M3: return decode_panel<MMAEMU_FP6_E2M3, NQ>(raw, ftz_in, zbias, f, e);
+    case MMAEMU_FP6_E3M2: return decode_panel<MMAEMU_FP6_E3M2, NQ>(raw, ftz_in, zbias, f, e);
+    case MMAEMU_FP4_E2M1: return decode_panel<MMAEMU_FP4_E2M1, NQ>(raw, ftz_in, zbias, f, e);
     default: return decode_panel<MMAEMU_BF16, NQ>(raw, ftz_in, zbias, f, e);
     }
 }
@@ -308,7 +311,8 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     if (xcd_remap) wg = (wg & 7u) * (gridDim.x >> 3) + (wg >> 3);
     const uint64_t item0 = (uint64_t)wg * SLOTS;
     constexpr int NQA = (SLOTS * TM * (KC / 4) + 255) / 256, NQB = (SLOTS * TN * (KC / 4) + 255) / 256;
-    const uint32_t esa = ta_.ta <= MMAEMU_FP8_E5M2 ? 1u : 2u, esb = ta_.tb <= MMAEMU_FP8_E5M2 ? 1u : 2u;
+    const uint32_t esa = (ta_.ta <= MMAEMU_FP8_E5M2 || ta_.ta >= MMAEMU_FP6_E2M3) ? 1u : 2u;      // bytes per element
+    const uint32_t esb = (ta_.tb <= MMAEMU_FP8_E5M2 || ta_.tb >= MMAEMU_FP6_E2M3) ? 1u : 2u;
     StagePlan<NQA> plan_a;
     StagePlan<NQB> plan_b;
     make_plan<TM, KC, SLOTS, VS, ES, true, NQA>(plan_a, A, esa, item0, nitems, bm_count, bn_count, m, k);

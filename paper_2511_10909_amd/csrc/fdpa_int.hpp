@@ -28,7 +28,7 @@ __device__ __forceinline__ Dec decode(uint32_t bits, uint32_t ftz_in)
     d.cls = E ? CLS_NORMAL : (M ? CLS_SUB : CLS_ZERO);
     if (F::IEEE) {
         if (E == EMASK) d.cls = M ? CLS_NAN : CLS_INF;
-    } else {
+    } else if (!F::NOSPEC) {
         if (E == EMASK && M == MMASK) d.cls = CLS_NAN;
     }
     if (ftz_in && d.cls == CLS_SUB) { d.cls = CLS_ZERO; d.sig = 0; d.sign = 0; }   // FlushSubnormal: -> +0.0
@@ -280,6 +280,12 @@ __device__ __noinline__ uint32_t fdpa_group_raw(ModelArgs p, uint32_t ta, uint32
     MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP16);         MMAEMU_CASE(MMAEMU_FP16, MMAEMU_BF16);
     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E5M2);
     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP16);
+#define MMAEMU_NARROW_ROW(X) MMAEMU_CASE(X, MMAEMU_FP8_E4M3); MMAEMU_CASE(X, MMAEMU_FP8_E5M2); MMAEMU_CASE(X, MMAEMU_FP6_E2M3); MMAEMU_CASE(X, MMAEMU_FP6_E3M2); MMAEMU_CASE(X, MMAEMU_FP4_E2M1)
+#define MMAEMU_NARROW_COL(Y) MMAEMU_CASE(MMAEMU_FP8_E4M3, Y); MMAEMU_CASE(MMAEMU_FP8_E5M2, Y)
+    MMAEMU_NARROW_ROW(MMAEMU_FP6_E2M3); MMAEMU_NARROW_ROW(MMAEMU_FP6_E3M2); MMAEMU_NARROW_ROW(MMAEMU_FP4_E2M1);
+    MMAEMU_NARROW_COL(MMAEMU_FP6_E2M3); MMAEMU_NARROW_COL(MMAEMU_FP6_E3M2); MMAEMU_NARROW_COL(MMAEMU_FP4_E2M1);
+#undef MMAEMU_NARROW_ROW
+#undef MMAEMU_NARROW_COL
 #undef MMAEMU_CASE
     return fdpa_group<MMAEMU_BF16, MMAEMU_BF16>(p, reinterpret_cast<const uint16_t *>(a),
                                                 reinterpret_cast<const uint16_t *>(b), L, c, sr);
@@ -301,6 +307,12 @@ __device__ __noinline__ uint32_t fdpa_group_raw_unscaled(ModelArgs p, uint32_t t
     MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP16);         MMAEMU_CASE(MMAEMU_FP16, MMAEMU_BF16);
     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E5M2);
     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP16);
+#define MMAEMU_NARROW_ROW(X) MMAEMU_CASE(X, MMAEMU_FP8_E4M3); MMAEMU_CASE(X, MMAEMU_FP8_E5M2); MMAEMU_CASE(X, MMAEMU_FP6_E2M3); MMAEMU_CASE(X, MMAEMU_FP6_E3M2); MMAEMU_CASE(X, MMAEMU_FP4_E2M1)
+#define MMAEMU_NARROW_COL(Y) MMAEMU_CASE(MMAEMU_FP8_E4M3, Y); MMAEMU_CASE(MMAEMU_FP8_E5M2, Y)
+    MMAEMU_NARROW_ROW(MMAEMU_FP6_E2M3); MMAEMU_NARROW_ROW(MMAEMU_FP6_E3M2); MMAEMU_NARROW_ROW(MMAEMU_FP4_E2M1);
+    MMAEMU_NARROW_COL(MMAEMU_FP6_E2M3); MMAEMU_NARROW_COL(MMAEMU_FP6_E3M2); MMAEMU_NARROW_COL(MMAEMU_FP4_E2M1);
+#undef MMAEMU_NARROW_ROW
+#undef MMAEMU_NARROW_COL
 #undef MMAEMU_CASE
     return fdpa_group<MMAEMU_BF16, MMAEMU_BF16>(p, reinterpret_cast<const uint16_t *>(a),
                                                 reinterpret_cast<const uint16_t *>(b), L, c, no_scales());

@@ -33,7 +33,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 struct GenArgs {
     uint32_t family, operand, k0, k1;
-    uint32_t width, mbits, nmag;          // output format; nmag = number of finite magnitudes
+    uint32_t width, mbits, nmag;          // output format (width: bits of a code, sign on top); nmag = number of finite magnitudes
     uint32_t exp_lo, nchoices, exp_zero;  // UNIFORM_EXP
     uint32_t fp32_two_words;              // UNIFORM_EXP with FP32 output
     uint32_t bias, max_code;              // NORMAL: target format
@@ -416,10 +416,10 @@ mmaemu_status launch_generate(const mmaemu_gen_params &gp, void *out, uint32_t d
     ga.operand = gp.operand;
     ga.k0 = (uint32_t)gp.seed;
     ga.k1 = (uint32_t)(gp.seed >> 32);
-    ga.width = (uint32_t)f.width;
+    ga.width = dtype == MMAEMU_E8M0 ? 8u : (uint32_t)(1 + f.ebits + f.mbits);
     ga.mbits = (uint32_t)f.mbits;
     const uint32_t emax_field = (1u << f.ebits) - 1u;
-    ga.nmag = f.ieee ? (emax_field << f.mbits) : (((emax_field + 1u) << f.mbits) - 1u);
+    ga.nmag = f.ieee ? (emax_field << f.mbits) : (((emax_field + 1u) << f.mbits) - (f.nospec ? 0u : 1u));
     ga.exp_lo = gp.exp_lo;
     ga.exp_zero = gp.exp_zero ? 1u : 0u;
     ga.nchoices = gp.exp_hi - gp.exp_lo + 1u + ga.exp_zero;

@@ -161,6 +161,14 @@ GEN_CASES = [
     (ogen.GEN_CANCELLING, fm.E4M3, dict(exp_lo=0, exp_hi=14)), (ogen.GEN_CANCELLING, fm.E5M2, dict(exp_lo=1, exp_hi=30)),
     (ogen.GEN_UNIFORM_EXP, ogen.E8M0, dict(exp_lo=60, exp_hi=190)), (ogen.GEN_UNIFORM_EXP, ogen.E8M0, dict(exp_lo=0, exp_hi=255, exp_zero=True)),
     (ogen.GEN_RANDOM_BITS, ogen.E8M0, {}), (ogen.GEN_ZERO, ogen.E8M0, {}),
+    (ogen.GEN_FINITE_BITS, fm.E2M1, {}), (ogen.GEN_FINITE_BITS, fm.E2M3, {}), (ogen.GEN_FINITE_BITS, fm.E3M2, {}),
+    (ogen.GEN_RANDOM_BITS, fm.E2M1, {}), (ogen.GEN_RANDOM_BITS, fm.E3M2, {}),
+    (ogen.GEN_UNIFORM_EXP, fm.E2M1, dict(exp_lo=0, exp_hi=3)), (ogen.GEN_UNIFORM_EXP, fm.E2M3, dict(exp_lo=1, exp_hi=3, exp_zero=True)),
+    (ogen.GEN_UNIFORM_EXP, fm.E3M2, dict(exp_lo=0, exp_hi=7)),
+    (ogen.GEN_NORMAL, fm.E2M1, dict(scale_scope=ogen.SCALE_TILE, scale_target=6.0)), (ogen.GEN_NORMAL, fm.E2M3, {}),
+    (ogen.GEN_NORMAL, fm.E3M2, dict(scale_scope=ogen.SCALE_TENSOR, scale_target=28.0)),
+    (ogen.GEN_CANCELLING, fm.E2M1, dict(exp_lo=0, exp_hi=3)), (ogen.GEN_CANCELLING, fm.E3M2, dict(exp_lo=1, exp_hi=6)),
+    (ogen.GEN_ZERO, fm.E2M1, {}),
 ]
 
 

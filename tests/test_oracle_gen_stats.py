@@ -231,3 +231,25 @@ def test_scale_code_generation():
     assert not ogen.generate(ogen.GenParams(family=ogen.GEN_ZERO), ogen.E8M0, 16, 0, 4).any()
     with pytest.raises(ValueError):
         ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL), ogen.E8M0, 16, 0, 4)
+
+
+def test_fp6_fp4_generation():
+    # FP6 / FP4 codes stay inside their 6 / 4 bits; FINITE_BITS reaches every code; NORMAL saturates at the largest
+    # finite value and rounds to nearest (checked against the decoded values)
+    from oracle import gen as ogen
+    for t, width in ((fm.E2M1, 4), (fm.E2M3, 6), (fm.E3M2, 6)):
+        x = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=3, operand=0), t, 64, 0, 64).ravel()
+        assert x.max() < (1 << width) and len(np.unique(x)) == (1 << width)
+        z = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=3, operand=1), t, 256, 0, 16).ravel()
+        assert z.max() < (1 << width)
+        vals = np.array([float(fm.decode(int(c), t).value) for c in range(1 << width)])
+        zs = ogen.normal_values(ogen.GenParams(family=ogen.GEN_NORMAL, seed=3, operand=1), 256, 0, 16).ravel()
+        got = vals[z]
+        big = float(vals.max())
+        want_mag = np.minimum(np.abs(zs.astype(np.float32).astype(np.float64)), big)
+        # nearest representable magnitude (ties aside): the error is at most half the local spacing
+        grid = np.sort(np.unique(np.abs(vals)))
+        nearest = grid[np.abs(grid[None, :] - want_mag[:, None]).argmin(axis=1)]
+        tie = np.isclose(np.abs(np.abs(got) - want_mag), np.abs(nearest - want_mag))
+        assert np.all((np.abs(got) == nearest) | tie)
+        assert np.all((np.sign(got) == np.sign(zs)) | (got == 0))
