@@ -300,12 +300,15 @@ typedef enum {
     MMAEMU_MFMA_F32_16X16X32_FP8_BF8 = 7, /* A E4M3, B E5M2 */
     MMAEMU_MFMA_F32_16X16X32_BF8_FP8 = 8, /* A E5M2, B E4M3 */
     MMAEMU_MFMA_F32_16X16X32_BF8_BF8 = 9, /* A E5M2, B E5M2 */
-    /* v_mfma_scale_f32_16x16x128_f8f6f4 with 8-bit operand formats: only through mmaemu_mfma_probe_scaled */
+    /* v_mfma_scale_f32_16x16x128_f8f6f4, only through mmaemu_mfma_probe_scaled: id = BASE + 5 fa + fb with the operand
+     * formats fa (A) and fb (B) numbered as the instruction numbers them: 0 E4M3, 1 E5M2, 2 E2M3, 3 E3M2, 4 E2M1 */
+    MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE = 10,
     MMAEMU_MFMA_SCALE_F32_16X16X128_FP8_FP8 = 10,
     MMAEMU_MFMA_SCALE_F32_16X16X128_FP8_BF8 = 11,
-    MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_FP8 = 12,
-    MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_BF8 = 13,
-    MMAEMU_MFMA_COUNT = 14
+    MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_FP8 = 15,
+    MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_BF8 = 16,
+    MMAEMU_MFMA_SCALE_F32_16X16X128_FP4_FP4 = 34,
+    MMAEMU_MFMA_COUNT = 35
 } mmaemu_mfma_instr;
 
 /* Shape and operand types of an instruction (host-side query). */

@@ -312,20 +312,22 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
             i128 T = have ? part_sum(p, a, b, se, 0, 1, L, ta, tb, emax - F) : 0;
             return finish(p, rounded_sum_with_c(p, have, T, emax, emax - F, dc, (int)trunc));
         }
-        /* two sub-groups: even / odd products (split 1) or first / second half (split 2) */
+        /* sub-groups: even / odd products (split 1), first / second half (split 2), or the four quarters (split 3) */
         const int Fm = p->frac_bits_merge ? (int)p->frac_bits_merge : F;
-        uint32_t first[2] = {0, split == 1 ? 1u : L / 2}, stride = split == 1 ? 2u : 1u;
-        int e_part[2] = {0, 0}, have[2], emax = 0, any = 0;
-        i128 T_part[2] = {0, 0};
-        for (int g = 0; g < 2; ++g) {
-            have[g] = part_emax(p, a, b, se, first[g], stride, L / 2, ta, tb, &e_part[g]);
+        const int np_ = split == 3 ? 4 : 2;
+        const uint32_t len = L / (uint32_t)np_, stride = split == 1 ? 2u : 1u;
+        int e_part[4] = {0, 0, 0, 0}, have[4] = {0, 0, 0, 0}, emax = 0, any = 0;
+        i128 T_part[4] = {0, 0, 0, 0};
+        for (int g = 0; g < np_; ++g) {
+            const uint32_t first = split == 1 ? (uint32_t)g : (uint32_t)g * len;
+            have[g] = part_emax(p, a, b, se, first, stride, len, ta, tb, &e_part[g]);
             if (!have[g]) continue;
-            T_part[g] = part_sum(p, a, b, se, first[g], stride, L / 2, ta, tb, e_part[g] - F);
+            T_part[g] = part_sum(p, a, b, se, first, stride, len, ta, tb, e_part[g] - F);
             if (!any || e_part[g] > emax) emax = e_part[g];
             any = 1;
         }
         i128 T = 0;
-        for (int g = 0; g < 2; ++g)
+        for (int g = 0; g < np_; ++g)
             if (have[g]) T += align_rd(T_part[g], e_part[g] - F, emax - Fm);
         return finish(p, rounded_sum_with_c(p, any, T, emax, emax - Fm, dc, (int)trunc));
     }
@@ -435,8 +437,8 @@ static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out
         uint32_t fc = p->frac_bits_acc ? p->frac_bits_acc : p->frac_bits;
         if (p->frac_bits2 > fc + 40) return -2;                 /* see rounded_sum_with_c(), two-step rounding */
         uint32_t split = p->c_mode == C_AFTER_RD_EVEN_ODD ? 1u : p->split;
-        if (split > 2) return -2;
-        if (split && (L & 1)) return -3;
+        if (split > 3) return -2;
+        if ((split && (L & 1)) || (split == 3 && (L & 3))) return -3;
     }
     *L_out = L;
     return 0;

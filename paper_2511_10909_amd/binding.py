@@ -21,8 +21,20 @@ SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
 (MFMA_F32_16X16X16_F16, MFMA_F32_16X16X16_BF16, MFMA_F32_32X32X8_F16, MFMA_F32_32X32X8_BF16,
  MFMA_F32_16X16X32_F16, MFMA_F32_16X16X32_BF16, MFMA_F32_16X16X32_FP8_FP8, MFMA_F32_16X16X32_FP8_BF8,
  MFMA_F32_16X16X32_BF8_FP8, MFMA_F32_16X16X32_BF8_BF8) = range(10)
-(MFMA_SCALE_F32_16X16X128_FP8_FP8, MFMA_SCALE_F32_16X16X128_FP8_BF8, MFMA_SCALE_F32_16X16X128_BF8_FP8,
- MFMA_SCALE_F32_16X16X128_BF8_BF8) = range(10, 14)
+# v_mfma_scale_f32_16x16x128_f8f6f4: id = base + 5 fa + fb, formats numbered 0 E4M3, 1 E5M2, 2 E2M3, 3 E3M2, 4 E2M1
+MFMA_SCALE_BASE = 10
+MFMA_SCALE_FORMATS = (0, 1, 6, 7, 8)            # dtype ids in the instruction's numbering
+
+
+def mfma_scale_id(ta, tb):
+    """Instruction id of the block-scaled MFMA with operand types ta (A) and tb (B)."""
+    return MFMA_SCALE_BASE + 5 * MFMA_SCALE_FORMATS.index(ta) + MFMA_SCALE_FORMATS.index(tb)
+
+
+MFMA_SCALE_F32_16X16X128_FP8_FP8, MFMA_SCALE_F32_16X16X128_FP8_BF8 = 10, 11
+MFMA_SCALE_F32_16X16X128_BF8_FP8, MFMA_SCALE_F32_16X16X128_BF8_BF8 = 15, 16
+MFMA_SCALE_FP8_IDS = (10, 11, 15, 16)
+MFMA_SCALE_IDS = tuple(range(10, 35))
 ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1}
 NO_MISMATCH = (1 << 64) - 1
 

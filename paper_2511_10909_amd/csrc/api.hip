@@ -343,14 +343,22 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
 mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n, uint32_t *k_native, mmaemu_dtype *a,
                                mmaemu_dtype *b)
 {
-    static const struct { uint32_t m, n, k; mmaemu_dtype a, b; } T[MMAEMU_MFMA_COUNT] = {
+    if ((uint32_t)instr >= MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE && (uint32_t)instr < MMAEMU_MFMA_COUNT) {
+        static const mmaemu_dtype F[5] = {MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2, MMAEMU_FP6_E2M3, MMAEMU_FP6_E3M2, MMAEMU_FP4_E2M1};
+        const uint32_t q = (uint32_t)instr - MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE;
+        if (m) *m = 16;
+        if (n) *n = 16;
+        if (k_native) *k_native = 128;
+        if (a) *a = F[q / 5];
+        if (b) *b = F[q % 5];
+        return MMAEMU_OK;
+    }
+    static const struct { uint32_t m, n, k; mmaemu_dtype a, b; } T[10] = {
         {16, 16, 16, MMAEMU_FP16, MMAEMU_FP16},         {16, 16, 16, MMAEMU_BF16, MMAEMU_BF16},
         {32, 32, 8, MMAEMU_FP16, MMAEMU_FP16},          {32, 32, 8, MMAEMU_BF16, MMAEMU_BF16},
         {16, 16, 32, MMAEMU_FP16, MMAEMU_FP16},         {16, 16, 32, MMAEMU_BF16, MMAEMU_BF16},
         {16, 16, 32, MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3}, {16, 16, 32, MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2},
-        {16, 16, 32, MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3}, {16, 16, 32, MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2},
-        {16, 16, 128, MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3}, {16, 16, 128, MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2},
-        {16, 16, 128, MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3}, {16, 16, 128, MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2}};
+        {16, 16, 32, MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3}, {16, 16, 32, MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2}};
     if ((uint32_t)instr >= MMAEMU_MFMA_COUNT) { set_error("mfma_info: unknown instruction %u", (uint32_t)instr); return MMAEMU_ERR_INVALID_ARG; }
     if (m) *m = T[instr].m;
     if (n) *n = T[instr].n;

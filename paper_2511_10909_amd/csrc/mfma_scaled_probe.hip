@@ -1,12 +1,15 @@
-// Native-instruction probe for the block-scaled MFMA of gfx950, v_mfma_scale_f32_16x16x128_f8f6f4 with FP8 (E4M3)
-// or BF8 (E5M2) operands: the device under test for Algorithm "ST-FDPA" (paper Sec. 4.1.3).  One wavefront issues
-// exactly one instruction per tile.
+// Native-instruction probe for the block-scaled MFMA of gfx950, v_mfma_scale_f32_16x16x128_f8f6f4, with every
+// pairing of its operand formats (FP8 E4M3, BF8 E5M2, FP6 E2M3, BF6 E3M2, FP4 E2M1): the device under test for
+// Algorithm "ST-FDPA" (paper Sec. 4.1.3).  One wavefront issues exactly one instruction per tile.
 //
-// Register layout (wave64), l = lane, g = l / 16, found with one-hot operands and distinct scales: A row i = l % 16;
-// dwords 0..3 hold k = 16 g + 0..15 and dwords 4..7 hold k = 64 + 16 g + 0..15, bytes in k order (same for B with
-// column j); the scale operand of lane l carries, in its byte 0, the E8M0 scale of row l % 16 and of the block
-// k = 32 g .. 32 g + 31; C/D column j = l % 16, rows i = 4 g + r, r = 0..3.  k positions at or beyond the caller's k
-// are fed as zeros with scale 2^0.
+// Register layout (wave64), l = lane, g = l / 16; found with one-hot operands and distinct scales on raw registers,
+// then fixed by exact small-integer tests.  Row (A) or column (B) l % 16 in every format.
+//   8-bit formats: dwords 0..3 hold k = 16 g + 0..15 and dwords 4..7 hold k = 64 + 16 g + 0..15, bytes in k order;
+//   6-bit and 4-bit formats: the lane holds k = 32 g + 0..31, codes packed back to back from bit 0 (six dwords for
+//     FP6, four for FP4; the remaining dwords are ignored);
+//   scales: the scale operand of lane l carries, in its byte 0, the E8M0 code of row l % 16 and block k = 32 g .. 32 g + 31;
+//   C/D: column j = l % 16, rows i = 4 g + r, r = 0..3.
+// In memory FP6 / FP4 codes sit one per byte.  k positions at or beyond the caller's k are fed as zeros with scale 2^0.
 #include "common.hpp"
 
 namespace mmaemu {
@@ -14,7 +17,42 @@ namespace mmaemu {
 typedef int v8i32 __attribute__((ext_vector_type(8)));
 typedef float v4f32s __attribute__((ext_vector_type(4)));
 
-template <int FA, int FB>          // operand formats as the instruction encodes them: 0 = E4M3, 1 = E5M2
+// operand registers of one lane from a row of one-code-per-byte elements; FMT as the instruction numbers the formats
+template <int FMT>
+__device__ __forceinline__ v8i32 load_operand(const uint8_t *row, uint32_t k, uint32_t g)
+{
+    v8i32 r;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) r[q] = 0;
+    if (FMT <= 1) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const uint32_t k0 = 64 * h + 16 * g;
+            if (k0 < k) {        // k is a multiple of 32, so the sixteen positions are inside together
+                const uint32_t *p = reinterpret_cast<const uint32_t *>(row + k0);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) r[4 * h + q] = (int)p[q];
+            }
+        }
+    } else if (32 * g < k) {
+        constexpr int BITS = FMT == 4 ? 4 : 6;
+        constexpr uint32_t MASK = (1u << BITS) - 1u;
+        const uint32_t *p = reinterpret_cast<const uint32_t *>(row + 32 * g);
+        uint32_t regs[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int e = 0; e < 32; ++e) {
+            const uint32_t code = (p[e / 4] >> (8 * (e % 4))) & MASK;
+            const int bit = e * BITS, w = bit / 32, o = bit % 32;
+            regs[w] |= code << o;
+            if (o + BITS > 32) regs[w + 1] |= code >> (32 - o);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r[q] = (int)regs[q];
+    }
+    return r;
+}
+
+template <int FA, int FB>
 __global__ void __launch_bounds__(256)
 mfma_scaled_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const float *C, float *D,
                          const uint8_t *__restrict__ SA, const uint8_t *__restrict__ SB, uint32_t k, uint64_t batch)
@@ -25,20 +63,9 @@ mfma_scaled_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restric
     const uint32_t nblk = k / 32;
     for (uint64_t t = wave; t < batch; t += nwaves) {
         const uint32_t rc = lane % 16, blk = lane / 16;
-        v8i32 a, b;
+        const v8i32 a = load_operand<FA>(A + (t * 16 + rc) * (uint64_t)k, k, blk);
+        const v8i32 b = load_operand<FB>(B + (t * 16 + rc) * (uint64_t)k, k, blk);
         int sa = 127, sb = 127;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) { a[q] = 0; b[q] = 0; }
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const uint32_t k0 = 64 * h + 16 * blk;
-            if (k0 < k) {        // k is a multiple of 32, so the sixteen positions are inside together
-                const uint32_t *pa = reinterpret_cast<const uint32_t *>(A + (t * 16 + rc) * (uint64_t)k + k0);
-                const uint32_t *pb = reinterpret_cast<const uint32_t *>(B + (t * 16 + rc) * (uint64_t)k + k0);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) { a[4 * h + q] = (int)pa[q]; b[4 * h + q] = (int)pb[q]; }
-            }
-        }
         if (blk < nblk) {
             sa = SA[(t * 16 + rc) * (uint64_t)nblk + blk];
             sb = SB[(t * 16 + rc) * (uint64_t)nblk + blk];
@@ -70,15 +97,20 @@ static mmaemu_status launch_f(const void *A, const void *B, const void *C, void 
 mmaemu_status launch_mfma_probe_scaled(uint32_t instr, const void *A, const void *B, const void *C, void *D,
                                        const void *SA, const void *SB, uint32_t k, uint64_t batch, hipStream_t s)
 {
-    switch (instr) {
-    case MMAEMU_MFMA_SCALE_F32_16X16X128_FP8_FP8: return launch_f<0, 0>(A, B, C, D, SA, SB, k, batch, s);
-    case MMAEMU_MFMA_SCALE_F32_16X16X128_FP8_BF8: return launch_f<0, 1>(A, B, C, D, SA, SB, k, batch, s);
-    case MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_FP8: return launch_f<1, 0>(A, B, C, D, SA, SB, k, batch, s);
-    case MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_BF8: return launch_f<1, 1>(A, B, C, D, SA, SB, k, batch, s);
+    const uint32_t q = instr - MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE;
+#define MMAEMU_ROW(X)                                                                                   \
+    case 5 * X + 0: return launch_f<X, 0>(A, B, C, D, SA, SB, k, batch, s);                             \
+    case 5 * X + 1: return launch_f<X, 1>(A, B, C, D, SA, SB, k, batch, s);                             \
+    case 5 * X + 2: return launch_f<X, 2>(A, B, C, D, SA, SB, k, batch, s);                             \
+    case 5 * X + 3: return launch_f<X, 3>(A, B, C, D, SA, SB, k, batch, s);                             \
+    case 5 * X + 4: return launch_f<X, 4>(A, B, C, D, SA, SB, k, batch, s)
+    switch (q) {
+        MMAEMU_ROW(0); MMAEMU_ROW(1); MMAEMU_ROW(2); MMAEMU_ROW(3); MMAEMU_ROW(4);
     default:
         set_error("unknown scaled mfma instruction %u", instr);
         return MMAEMU_ERR_INVALID_ARG;
     }
+#undef MMAEMU_ROW
 }
 
 } // namespace mmaemu

@@ -154,7 +154,7 @@ def test_scaled_argument_errors(mm):
     mm.model_destroy(h)
 
 
-@pytest.mark.parametrize("instr", range(10, 14))
+@pytest.mark.parametrize("instr", range(10, 35))
 def test_scaled_mfma_register_layout(mm, instr):
     # small-integer operands and scales of 2^-4 .. 2^4: every arithmetic is exact, so any mistake in the operand,
     # scale or result register layout shows, whatever the instruction does inside

@@ -79,7 +79,7 @@ def test_o2_matches_oracle_on_fp6_fp4(ta, tb):
         p = ModelParams(group_len=L, frac_bits=int(rng.choice([6, 13, 25])), c_mode=mode, out_round=int(rng.integers(0, 2)),
                         skip_zero_terms=bool(rng.integers(0, 2)))
         if mode == C_AFTER_RD:
-            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 3)), f2_at_leading_bit=bool(rng.integers(0, 2)))
+            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 4 if (L or k) % 4 == 0 else 3)), f2_at_leading_bit=bool(rng.integers(0, 2)))
         nb, m, n, k = 2, 3, 3, 32
         A = rng.integers(0, 1 << fm.FORMATS[ta].width, size=(nb, m, k)).astype(np.uint8)
         B = rng.integers(0, 1 << fm.FORMATS[tb].width, size=(nb, n, k)).astype(np.uint8)

@@ -89,7 +89,7 @@ def test_o2_equals_rational_form_with_scales(ta, tb):
         p = ModelParams(group_len=L, frac_bits=int(rng.choice([8, 13, 24, 25, 30])), c_mode=mode, out_round=int(rng.integers(0, 2)),
                         skip_zero_terms=bool(rng.integers(0, 2)))
         if mode == C_AFTER_RD:
-            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 3)) if (L or k) % 2 == 0 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
+            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 4 if (L or k) % 4 == 0 else 3)) if (L or k) % 2 == 0 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
                         acc_special_truncation=bool(rng.integers(0, 2)), sum_drop_distance=int(rng.choice([0, 28])))
         nb, m, n = 2, 3, 4
         A = synth.random_bits(rng, (nb, m, k), ta)
@@ -148,7 +148,7 @@ def test_wide_products_o2_matches_oracle():
         L = int(rng.choice([2, 4, 8]))
         k = 16
         p = ModelParams(group_len=L, frac_bits=int(rng.choice([13, 24])), frac_bits2=31, c_mode=C_AFTER_RD, wide_products=True,
-                        split=int(rng.integers(0, 3)), skip_zero_terms=bool(rng.integers(0, 2)), out_round=int(rng.integers(0, 2)),
+                        split=int(rng.integers(0, 4 if (L or k) % 4 == 0 else 3)), skip_zero_terms=bool(rng.integers(0, 2)), out_round=int(rng.integers(0, 2)),
                         f2_at_leading_bit=bool(rng.integers(0, 2)), acc_special_truncation=bool(rng.integers(0, 2)))
         nb, m, n = 2, 3, 3
         if ta == fm.BF16:
@@ -204,8 +204,9 @@ def test_tiny_range_o2_matches_oracle():
     rng = np.random.default_rng(91)
     for trial in range(30):
         ta, tb = [(fm.E4M3, fm.E4M3), (fm.E5M2, fm.E4M3), (fm.BF16, fm.BF16)][trial % 3]
-        p = ModelParams(group_len=int(rng.choice([2, 8, 16])), frac_bits=int(rng.choice([13, 24])), frac_bits2=31, c_mode=C_AFTER_RD,
-                        wide_products=True, split=int(rng.integers(0, 3)), skip_zero_terms=bool(rng.integers(0, 2)),
+        L = int(rng.choice([2, 8, 16]))
+        p = ModelParams(group_len=L, frac_bits=int(rng.choice([13, 24])), frac_bits2=31, c_mode=C_AFTER_RD,
+                        wide_products=True, split=int(rng.integers(0, 4 if L % 4 == 0 else 3)), skip_zero_terms=bool(rng.integers(0, 2)),
                         f2_at_leading_bit=True, frac_bits_acc=24, frac_bits_merge=24 if trial % 2 else 0, zero_result_positive=bool(rng.integers(0, 2)))
         if p.frac_bits_merge and p.split == 0:
             p = p.with_(frac_bits_merge=0)

@@ -357,7 +357,7 @@ def test_o2_equals_rational_oracle_variations(ta, tb):
                         out_round=int(rng.integers(0, 2)), ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)),
                         skip_zero_terms=bool(rng.integers(0, 2)), zero_result_positive=bool(rng.integers(0, 2)))
         if p.c_mode == C_AFTER_RD:
-            p = p.with_(split=int(rng.integers(0, 3)), acc_special_truncation=bool(rng.integers(0, 2)),
+            p = p.with_(split=int(rng.integers(0, 4 if (L or k) % 4 == 0 else 3)), acc_special_truncation=bool(rng.integers(0, 2)),
                         frac_bits_merge=int(rng.choice([0, 13, 24, 31])), frac_bits_acc=int(rng.choice([0, 13, 24, 30])),
                         f2_at_leading_bit=bool(rng.integers(0, 2)),
                         sum_drop_distance=int(rng.choice([0, 0, 5, 20, 28])))
@@ -397,3 +397,26 @@ def test_sum_drop_distance():
     assert _run(p, a, a, 2.0 ** 28) == f32_bits(2.0 ** 28)
     assert _run(p, a, a, 2.0 ** 27) == f32_bits(2.0 ** 27 + 16)       # distance 27: kept (18 = 1.125 places of 16)
     assert _run(p, a, a, -(2.0 ** 28)) == f32_bits(-(2.0 ** 28))
+
+
+def test_split_into_quarters():
+    # four sub-groups of two products each (L = 8), F = 4 inside a sub-group, 24 bits across.  Products (value, by
+    # construction): quarter 0: 1 and 2^-5 (the small one lies below the unit 2^-4 of its own quarter: cut);
+    # quarter 1: 2^-5 alone with 0: kept, its quarter's maximum is its own exponent; merged at the overall maximum
+    # with 24 bits it survives: 1 + 2^-5.  As halves of four the small product of quarter 1 would share the maximum
+    # 2^0 of quarter 0 and be cut as well: 1.
+    from oracle.fdpa import SPLIT_QUARTERS, SPLIT_HALVES
+    p = ModelParams(group_len=8, frac_bits=4, frac_bits2=31, c_mode=C_AFTER_RD, frac_bits_merge=24, frac_bits_acc=24,
+                    split=SPLIT_QUARTERS, skip_zero_terms=True)
+    a = [1.0, 2.0 ** -5, 2.0 ** -5, 0.0, 0.0, 0.0, 0.0, 0.0]
+    b = [1.0] * 8
+    assert bits_f32(_run(p, a, b, 0.0, L=8)) == 1.0 + 2.0 ** -5
+    assert bits_f32(_run(p.with_(split=SPLIT_HALVES), a, b, 0.0, L=8)) == 1.0
+    # quarters with one product each are a plain sum rounded down at 24 bits: every term kept
+    q = p.with_(group_len=4)
+    assert bits_f32(_run(q, [1.0, 2.0 ** -5, 2.0 ** -9, 2.0 ** -13], [1.0] * 4, 0.0, L=4)) == 1.0 + 2.0 ** -5 + 2.0 ** -9 + 2.0 ** -13
+    # the merge rounds every quarter down: -2^-30 in a quarter of its own next to 1 becomes -2^-24, and the sum
+    # 1 - 2^-24 is a binary32 number
+    assert bits_f32(_run(q, [1.0, -2.0 ** -12, 0.0, 0.0], [2.0 ** 0, 2.0 ** -14], 0.0, L=4)) == 1.0 - 2.0 ** -24
+    with pytest.raises(ValueError):
+        _run(p.with_(group_len=6), [1.0] * 6, [1.0] * 6, 0.0, L=6)
