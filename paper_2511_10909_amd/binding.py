@@ -13,7 +13,7 @@ E4M3, E5M2, FP16, BF16, FP32, E8M0 = 0, 1, 2, 3, 4, 5
 E2M3, E3M2, E2M1 = 6, 7, 8                      # FP6 and FP4 operands, one code per byte
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 RNE, RZ = 0, 1
-SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES = 0, 1, 2
+SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
 FAMILY_FDPA, FAMILY_FTZ_ADDMUL = 0, 1
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
 GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING = 5, 6, 7

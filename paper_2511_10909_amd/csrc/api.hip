@@ -114,7 +114,7 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: frac_bits2 / frac_bits_merge / frac_bits_acc above 48");
         return MMAEMU_ERR_UNSUPPORTED;
     }
-    if (p->split > MMAEMU_SPLIT_HALVES || p->acc_special_truncation > 1 || p->f2_at_leading_bit > 1 ||
+    if (p->split > MMAEMU_SPLIT_QUARTERS || p->acc_special_truncation > 1 || p->f2_at_leading_bit > 1 ||
         p->skip_zero_terms > 1 || p->zero_result_positive > 1 || p->wide_products > 1) {
         set_error("model_create: enum field out of range");
         return MMAEMU_ERR_INVALID_ARG;
@@ -217,8 +217,8 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
             set_error("emulate_mma: the C_AFTER_RD modes need max(F, F2, F_m, F_c) + 3 + ceil(log2 L) <= 53");
             return MMAEMU_ERR_UNSUPPORTED;
         }
-        if (split != MMAEMU_SPLIT_NONE && (L & 1u)) {
-            set_error("emulate_mma: a split group needs an even group length (L=%u)", L);
+        if ((split != MMAEMU_SPLIT_NONE && (L & 1u)) || (split == MMAEMU_SPLIT_QUARTERS && (L & 3u))) {
+            set_error("emulate_mma: a split group needs an even group length, quarters a multiple of 4 (L=%u)", L);
             return MMAEMU_ERR_SHAPE;
         }
     }

@@ -11,13 +11,10 @@ static mmaemu_status launch_vm(const TiledArgs &t, const void *A, const void *B,
     if (t.p.c_mode == MMAEMU_C_IN_GROUP) return launch_tiled_shape<MMAEMU_C_IN_GROUP, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
     if (t.p.c_mode == MMAEMU_C_AFTER_EXACT) return launch_tiled_shape<MMAEMU_C_AFTER_EXACT, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
     if (t.p.split == MMAEMU_SPLIT_NONE) return launch_tiled_shape<MMAEMU_C_AFTER_RD, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
-    if constexpr (VM == 0) {
-        if (t.p.split == MMAEMU_SPLIT_EVEN_ODD) return launch_tiled_shape<CM_RD_EVEN_ODD, 0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
-        return launch_tiled_shape<CM_RD_HALVES, 0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
-    }
-    if constexpr (VM == 3) {
-        if (t.p.split == MMAEMU_SPLIT_EVEN_ODD) return launch_tiled_shape<CM_RD_EVEN_ODD, 3>(t, A, B, Cm, D, m, n, k, batch, s, handled);
-        return launch_tiled_shape<CM_RD_HALVES, 3>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+    if constexpr (VM == 0 || VM == 3) {
+        if (t.p.split == MMAEMU_SPLIT_EVEN_ODD) return launch_tiled_shape<CM_RD_EVEN_ODD, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        if (t.p.split == MMAEMU_SPLIT_HALVES) return launch_tiled_shape<CM_RD_HALVES, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_tiled_shape<CM_RD_QUARTERS, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
     }
     handled = false;        // split groups with BF16 operands or wide F: general kernel
     return MMAEMU_OK;

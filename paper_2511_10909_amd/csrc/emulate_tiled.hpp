@@ -37,7 +37,9 @@
 // Algorithm "TR-FDPA" and its variations), and the two split forms of the latter (Algorithm "GTR-FDPA"):
 // CM_RD_EVEN_ODD, where the packed exponent maxima of pass 1 already are the even and the odd maximum (even k in
 // the low halves, odd k in the high halves) and pass 2 alternates between two scales and two sums, and CM_RD_HALVES,
-// where each half of a group runs through passes 1 and 2 as a group of its own before the halves are merged.
+// where each half of a group runs through passes 1 and 2 as a group of its own before the halves are merged, and
+// CM_RD_QUARTERS, where pass 1 runs over the four quarters first (their maxima and the largest of them), then pass 2
+// quarter by quarter, each sum rounded down into the merged sum as soon as it is complete.
 // NaN and infinities are tagged with an exponent sentinel; a group that meets one is
 // recomputed by the integer routine of the general kernel from the raw operands in
 // global memory.
@@ -46,7 +48,7 @@
 
 namespace mmaemu {
 
-constexpr int CM_RD_EVEN_ODD = 3, CM_RD_HALVES = 4;      // template-only values of CMODE (ModelArgs::c_mode stays C_AFTER_RD)
+constexpr int CM_RD_EVEN_ODD = 3, CM_RD_HALVES = 4, CM_RD_QUARTERS = 5;   // template-only values of CMODE (ModelArgs::c_mode stays C_AFTER_RD)
 
 constexpr uint32_t SENTINEL = 0x4000u;      // exponent tag of an element the fast path cannot take
 constexpr uint32_t SENTINEL_MASK = 0xC000C000u;
@@ -274,10 +276,11 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     constexpr int VS = KC + 4;                       // LDS row stride of binary32 values (floats), padded
     constexpr int VSD = KC + 2;                      // LDS row stride of binary64 values (doubles)
     constexpr int ES = KC / 2 + (KC == 16 ? 2 : 4);  // LDS row stride of packed exponents (dwords)
-    constexpr bool IS_RD = CMODE == MMAEMU_C_AFTER_RD || CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES;
-    static_assert(!(CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES) || (LT >= 4 && VM == 0 && NF == 0), "split groups: fixed length, binary32 values, one fold");
+    constexpr bool IS_RD = CMODE == MMAEMU_C_AFTER_RD || CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES || CMODE == CM_RD_QUARTERS;
+    static_assert(!(CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES || CMODE == CM_RD_QUARTERS) || (LT >= 4 && VM == 0 && NF == 0), "split groups: fixed length, binary32 values, one fold");
     static_assert(CMODE != CM_RD_HALVES || LT >= 8, "halves of at least four terms");
-    constexpr int GL = CMODE == CM_RD_HALVES ? LT / 2 : (LT ? LT : KC);   // terms per inner step
+    static_assert(CMODE != CM_RD_QUARTERS || LT >= 16, "quarters of at least four terms");
+    constexpr int GL = CMODE == CM_RD_HALVES ? LT / 2 : CMODE == CM_RD_QUARTERS ? LT / 4 : (LT ? LT : KC);   // terms per inner step
     constexpr int FOLD = NF ? NF : GL;
     constexpr bool USE_SD = (NF != 0) || (LT == 0) || (VM == 2);   // binary64 accumulator needed
     constexpr int VBYTES_A = SLOTS * TM * (VM == 0 ? VS * 4 : VSD * 8);
@@ -875,6 +878,70 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                         for (int c = 0; c < C; ++c) T1[r][c] = (double)S32[r][c];
                     end_of_split_group(k0 + g * LT, T0, e0, x0, T1, emax, m2, true, tagged);
                 }
+            } else if constexpr (CMODE == CM_RD_QUARTERS) {
+#pragma unroll 1
+                for (int g = 0; g < KC / LT; ++g) {
+                    int ep[4][R][C]; uint32_t tg[R][C], have[R][C], tagged = 0;
+                    refresh_switches();
+                    load_scales(k0 + g * LT);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) { tg[r][c] = 0; have[r][c] = 0; }
+                    // pass 1 over the four quarters: their maxima, and which of them hold a live product
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        reset_group();
+                        pass1(4 * g + q);
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                exponents(r, c, ep[q][r][c], tagged);
+                                const uint32_t x = m2[r][c], mx = (x & 0xFFFFu) > (x >> 16) ? (x & 0xFFFFu) : (x >> 16);
+                                tg[r][c] |= x;
+                                if (!(fe & FL_SKIP_ZERO) || mx >= 2 * ZBIAS) have[r][c] |= 1u << q;
+                            }
+                    }
+                    int em[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            int e = ep[0][r][c]; bool any = (have[r][c] & 1u) != 0;
+#pragma unroll
+                            for (int q = 1; q < 4; ++q)
+                                if ((have[r][c] >> q) & 1u) { e = (!any || ep[q][r][c] > e) ? ep[q][r][c] : e; any = true; }
+                            em[r][c] = e;
+                        }
+                    // pass 2 quarter by quarter; each sum is rounded down to F_m bits at the largest maximum and added
+                    double Tm[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) Tm[r][c] = 0.0;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) S32[r][c] = 0;
+                        pass2f(4 * g + q, ep[q]);
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c)
+                                if ((have[r][c] >> q) & 1u)
+                                    Tm[r][c] += __builtin_floor(ldexp((double)S32[r][c], (ep[q][r][c] - F) - (em[r][c] - p.Fm)));
+                    }
+                    flush_accumulators();
+                    double v[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) v[r][c] = rd_value(Tm[r][c], have[r][c] != 0, em[r][c], p.Fm, d[r][c]);
+                    finish_group(k0 + g * LT, v, tg, tagged);
+                }
             } else {
 #pragma unroll 1
                 for (int g = 0; g < KC / GL; ++g) {
@@ -960,7 +1027,7 @@ static mmaemu_status launch_fold(const TiledArgs &ta, const void *A, const void 
 {
     if constexpr (VM == 2) {
         return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0, VM>(ta, A, B, Cm, D, m, n, k, batch, s);   // terms summed in binary64
-    } else if constexpr (CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES) {
+    } else if constexpr (CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES || CMODE == CM_RD_QUARTERS) {
         return launch_cfg<TM, TN, R, C, KC, LT, CMODE, 0, VM>(ta, A, B, Cm, D, m, n, k, batch, s);   // (the caller checked the 32-bit sums)
     } else {
         constexpr int GL = LT ? LT : KC;
@@ -977,10 +1044,12 @@ static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B,
 {
     handled = true;
     const uint32_t L = ta.p.L;
-    if constexpr (CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES) {
+    if constexpr (CMODE == CM_RD_EVEN_ODD || CMODE == CM_RD_HALVES || CMODE == CM_RD_QUARTERS) {
         // split groups: fixed lengths only, and half a group's aligned terms must fit one 32-bit sum
         if ((uint64_t)(L / 2) << (ta.p.F + 2) <= (1ull << 31)) {
-            if (L == 8) return launch_fold<TM, TN, R, C, KC, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+            if constexpr (CMODE != CM_RD_QUARTERS) {
+                if (L == 8) return launch_fold<TM, TN, R, C, KC, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+            }
             if constexpr (KC >= 16) {
                 if (L == 16) return launch_fold<TM, TN, R, C, KC, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
             }
@@ -1015,8 +1084,12 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
     const uint64_t outputs = batch * m * n;
     // whole small tiles of a batch (binary64 values need twice the LDS: fewer tiles per workgroup; half groups keep
     // a second set of sums and maxima per output: smaller register blocks)
-    constexpr bool BIG_BLOCKS = (VM == 0 || VM == 3) && CMODE != CM_RD_HALVES;
-    constexpr bool BIG_BLOCKS_OK = CMODE != CM_RD_HALVES;
+    constexpr bool BIG_BLOCKS = (VM == 0 || VM == 3) && CMODE != CM_RD_HALVES && CMODE != CM_RD_QUARTERS;
+    constexpr bool BIG_BLOCKS_OK = CMODE != CM_RD_HALVES && CMODE != CM_RD_QUARTERS;
+    if constexpr (CMODE == CM_RD_QUARTERS) {
+        // (groups of 32 on 16 x 16 tiles: staged 32 k at a time)
+        if (m == 16 && n == 16 && k % 32 == 0 && ta.p.L == 32) return launch_L<16, 16, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    }
     if (m == 16 && n == 16 && k % 16 == 0) {
         if constexpr (BIG_BLOCKS) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
         else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
@@ -1058,5 +1131,7 @@ extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 3);
 extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 3);
 extern template MMAEMU_TILED_SIG(CM_RD_EVEN_ODD, 3);
 extern template MMAEMU_TILED_SIG(CM_RD_HALVES, 3);
+extern template MMAEMU_TILED_SIG(CM_RD_QUARTERS, 0);
+extern template MMAEMU_TILED_SIG(CM_RD_QUARTERS, 3);
 
 } // namespace mmaemu

@@ -20,7 +20,7 @@ def _params(rng, L, trial):
     p = ModelParams(group_len=L, frac_bits=int(rng.choice([5, 13, 24, 25])), c_mode=mode, out_round=int(rng.integers(0, 2)),
                     ftz_in=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)))
     if mode == C_AFTER_RD:
-        p = p.with_(frac_bits2=31, split=int(rng.integers(0, 3)) if L >= 8 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
+        p = p.with_(frac_bits2=31, split=int(rng.integers(0, 4 if L >= 16 else 3)) if L >= 8 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
                     acc_special_truncation=bool(rng.integers(0, 2)), skip_zero_terms=bool(rng.integers(0, 2)),
                     zero_result_positive=bool(rng.integers(0, 2)), sum_drop_distance=int(rng.choice([0, 28])))
     return p

@@ -42,7 +42,7 @@ def test_scaled_emulation_matches_oracle(mm, ta, tb):
         p = ModelParams(group_len=L, frac_bits=int(rng.choice([8, 13, 24, 25, 30])), c_mode=mode, out_round=int(rng.integers(0, 2)),
                         skip_zero_terms=bool(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)))
         if mode == C_AFTER_RD:
-            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 3)) if (L or k) % 2 == 0 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
+            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 4 if (L or k) % 4 == 0 else 3)) if (L or k) % 2 == 0 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
                         acc_special_truncation=bool(rng.integers(0, 2)), sum_drop_distance=int(rng.choice([0, 28])),
                         wide_products=bool(rng.integers(0, 2)))
         nb, m, n = int(rng.integers(1, 4)), int(rng.integers(1, 20)), int(rng.integers(1, 20))
@@ -79,7 +79,7 @@ def test_scaled_tiled_kernels_match_oracle(mm, ta, tb):
         F = int(rng.choice([13, 24, 25]))
         p = ModelParams(group_len=L, frac_bits=F, c_mode=mode, out_round=int(rng.integers(0, 2)), ftz_out=bool(rng.integers(0, 2)))
         if mode == C_AFTER_RD:
-            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 3)) if L >= 8 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
+            p = p.with_(frac_bits2=31, split=int(rng.integers(0, 4 if L >= 16 else 3)) if L >= 8 else 0, f2_at_leading_bit=bool(rng.integers(0, 2)),
                         acc_special_truncation=bool(rng.integers(0, 2)), sum_drop_distance=int(rng.choice([0, 28])),
                         wide_products=bool(rng.integers(0, 2)), skip_zero_terms=bool(rng.integers(0, 2)),
                         zero_result_positive=bool(rng.integers(0, 2)))
