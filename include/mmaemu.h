@@ -309,7 +309,13 @@ typedef enum {
     MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_FP8 = 15,
     MMAEMU_MFMA_SCALE_F32_16X16X128_BF8_BF8 = 16,
     MMAEMU_MFMA_SCALE_F32_16X16X128_FP4_FP4 = 34,
-    MMAEMU_MFMA_COUNT = 35
+    MMAEMU_MFMA_F32_32X32X16_F16 = 35,
+    MMAEMU_MFMA_F32_32X32X16_BF16 = 36,
+    MMAEMU_MFMA_F32_32X32X16_FP8_FP8 = 37,
+    MMAEMU_MFMA_F32_32X32X16_FP8_BF8 = 38,
+    MMAEMU_MFMA_F32_32X32X16_BF8_FP8 = 39,
+    MMAEMU_MFMA_F32_32X32X16_BF8_BF8 = 40,
+    MMAEMU_MFMA_COUNT = 41
 } mmaemu_mfma_instr;
 
 /* Shape and operand types of an instruction (host-side query). */

@@ -6,7 +6,7 @@
 // Register layouts (wave64), l = lane:
 //   16x16xK : A row  i = l % 16, k = (K/4) * (l / 16) + 0 .. K/4-1   (same for B with column j)
 //             C/D column j = l % 16, rows i = 4 * (l / 16) + r, r = 0..3
-//   32x32x8 : A row  i = l % 32, k = 4 * (l / 32) + 0..3             (same for B with column j)
+//   32x32xK : A row  i = l % 32, k = (K/2) * (l / 32) + 0 .. K/2-1   (same for B with column j)
 //             C/D column j = l % 32, rows i = 8 * (r / 4) + 4 * (l / 32) + r % 4, r = 0..15
 // k positions at or beyond the caller's k are fed as zeros.
 #include "common.hpp"
@@ -35,6 +35,12 @@ DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_FP8_FP8, 16, 16, 32, 1);
 DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_FP8_BF8, 16, 16, 32, 1);
 DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_BF8_FP8, 16, 16, 32, 1);
 DEF_INSTR(MMAEMU_MFMA_F32_16X16X32_BF8_BF8, 16, 16, 32, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_F16, 32, 32, 16, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_BF16, 32, 32, 16, 2);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_FP8_FP8, 32, 32, 16, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_FP8_BF8, 32, 32, 16, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_BF8_FP8, 32, 32, 16, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_BF8_BF8, 32, 32, 16, 1);
 #undef DEF_INSTR
 
 // gather this lane's K/4 (16-wide) or 4 (32-wide) consecutive k elements of one row,
@@ -59,7 +65,7 @@ mfma_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, 
                   uint32_t k, uint64_t batch)
 {
     using I = Instr<INSTR>;
-    constexpr int KL = (I::M == 16) ? I::K / 4 : 4;       // k elements per lane
+    constexpr int KL = (I::M == 16) ? I::K / 4 : I::K / 2;  // k elements per lane
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const uint64_t nwaves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
@@ -115,6 +121,25 @@ mfma_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, 
                 v4f16 a, b;
                 __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
                 acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, acc, 0, 0, 0);
+            } else if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X16_F16) {
+                v8f16 a, b;
+                __builtin_memcpy(&a, ra, 16); __builtin_memcpy(&b, rb, 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc, 0, 0, 0);
+            } else if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X16_BF16) {
+                v8bf16 a, b;
+                __builtin_memcpy(&a, ra, 16); __builtin_memcpy(&b, rb, 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+            } else if constexpr (I::ELEM_BYTES == 1) {
+                long a, b;
+                __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+                if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X16_FP8_FP8)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b, acc, 0, 0, 0);
+                else if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X16_FP8_BF8)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_fp8_bf8(a, b, acc, 0, 0, 0);
+                else if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X16_BF8_FP8)
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf8_fp8(a, b, acc, 0, 0, 0);
+                else
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf8_bf8(a, b, acc, 0, 0, 0);
             } else {
                 v4i16 a, b;
                 __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
@@ -153,6 +178,12 @@ mmaemu_status launch_mfma_probe(uint32_t instr, const void *A, const void *B, co
         CASE(MMAEMU_MFMA_F32_16X16X32_FP8_BF8);
         CASE(MMAEMU_MFMA_F32_16X16X32_BF8_FP8);
         CASE(MMAEMU_MFMA_F32_16X16X32_BF8_BF8);
+        CASE(MMAEMU_MFMA_F32_32X32X16_F16);
+        CASE(MMAEMU_MFMA_F32_32X32X16_BF16);
+        CASE(MMAEMU_MFMA_F32_32X32X16_FP8_FP8);
+        CASE(MMAEMU_MFMA_F32_32X32X16_FP8_BF8);
+        CASE(MMAEMU_MFMA_F32_32X32X16_BF8_FP8);
+        CASE(MMAEMU_MFMA_F32_32X32X16_BF8_BF8);
 #undef CASE
     default:
         set_error("unknown mfma instruction %u", instr);

@@ -15,7 +15,7 @@ def env():
     return binding, configs, presets
 
 
-@pytest.mark.parametrize("instr", range(10))
+@pytest.mark.parametrize("instr", list(range(10)) + list(range(35, 41)))
 def test_gfx950_preset_reproduces_the_instruction(env, instr):
     mm, configs, presets = env
     res = configs.validate_against_mfma(instr, presets.GFX950_MFMA[instr], n_tiles=1024, seeds=(0, 1))

@@ -224,7 +224,9 @@ def test_compare_matches_oracle(mm):
 
 MFMA_TYPES = {0: (fm.FP16, fm.FP16), 1: (fm.BF16, fm.BF16), 2: (fm.FP16, fm.FP16), 3: (fm.BF16, fm.BF16),
               4: (fm.FP16, fm.FP16), 5: (fm.BF16, fm.BF16), 6: (fm.E4M3, fm.E4M3), 7: (fm.E4M3, fm.E5M2),
-              8: (fm.E5M2, fm.E4M3), 9: (fm.E5M2, fm.E5M2)}
+              8: (fm.E5M2, fm.E4M3), 9: (fm.E5M2, fm.E5M2),
+              35: (fm.FP16, fm.FP16), 36: (fm.BF16, fm.BF16), 37: (fm.E4M3, fm.E4M3), 38: (fm.E4M3, fm.E5M2),
+              39: (fm.E5M2, fm.E4M3), 40: (fm.E5M2, fm.E5M2)}
 
 
 def _small_int_codes(rng, shape, t):
@@ -241,7 +243,7 @@ def _small_int_codes(rng, shape, t):
     return out.astype(NP[t]), vals
 
 
-@pytest.mark.parametrize("instr", range(10))
+@pytest.mark.parametrize("instr", sorted(MFMA_TYPES))
 def test_mfma_probe_register_layout(mm, instr):
     # with small-integer operands every arithmetic is exact, so D = A B^T + C exactly whatever the
     # instruction's internal behaviour: any mistake in the operand/result register layout shows
