@@ -518,6 +518,85 @@ int o2_emulate_mma_scaled(const o2_params *p, const void *A, const void *B, cons
     return emulate_mma_impl(p, A, B, C, D, m, n, k, batch, ta, tb, nthreads, threads_used, sc);
 }
 
+/* ---- Algorithm "GST-FDPA" (Sec. 4.1.3): FP4 operands, one scale factor pair per k_block elements, exact dot product
+ * per group of G products, truncated fused sum of the L / G group terms and the accumulator.  Integer form: an FP4
+ * value is sig * 2^(exp - 1) with sig in 0..3, so a product counts units of 2^-2; a scale significand counts units of
+ * 2^-3 (UE4M3; E8M0's 1.0 is 8 of them), so s_g counts units of 2^-8. */
+typedef struct { uint32_t L, G, k_block, F, out_round, scale_format, nan_bits; } gst_params;
+
+static int gst_scale(uint32_t code, uint32_t fmt, int *sig8, int *exp)
+{
+    code &= 0xFFu;
+    if (fmt == 0) { if (code == 0xFF) return 0; *sig8 = 8; *exp = (int)code - 127; return 1; }
+    dec_t d = decode(code & 0x7Fu, T_E4M3);
+    if (d.cls == CLS_NAN) return 0;
+    *sig8 = (int)d.sig; *exp = d.exp;
+    return 1;
+}
+
+static uint32_t gst_group_op(const gst_params *g, const uint8_t *a, const uint8_t *b, uint32_t c, const uint8_t *al, const uint8_t *be)
+{
+    dec_t dc = decode(c, T_FP32);
+    if (dc.cls == CLS_NAN) return g->nan_bits;
+    const uint32_t ng = g->L / g->G;
+    int64_t s[65]; int e[65];
+    for (uint32_t q = 0; q < ng; ++q) {
+        int sa, ea, sb, eb;
+        const uint32_t blk = q * g->G / g->k_block;
+        if (!gst_scale(al[blk], g->scale_format, &sa, &ea) || !gst_scale(be[blk], g->scale_format, &sb, &eb)) return g->nan_bits;
+        int64_t p = 0;
+        for (uint32_t k = q * g->G; k < (q + 1) * g->G; ++k) {
+            dec_t x = decode(a[k], T_E2M1), y = decode(b[k], T_E2M1);
+            int64_t t = (int64_t)(x.sig * y.sig) << (x.exp + y.exp);          /* units of 2^-2 */
+            p += (x.sign ^ y.sign) ? -t : t;
+        }
+        s[q] = p * sa * sb;                                                   /* units of 2^-8 */
+        e[q] = ea + eb;
+    }
+    if (dc.cls == CLS_INF) return dc.sign ? 0xFF800000u : 0x7F800000u;
+    int emax = dc.exp;
+    for (uint32_t q = 0; q < ng; ++q) if (e[q] > emax) emax = e[q];
+    const int F = (int)g->F;
+    i128 S = 0;
+    for (uint32_t q = 0; q < ng; ++q) {
+        u128 mag = (u128)(s[q] < 0 ? -s[q] : s[q]);
+        u128 al_ = align_rz(mag, e[q] - 8, emax - F);
+        if (s[q] < 0) S -= (i128)al_; else S += (i128)al_;
+    }
+    u128 ac = align_rz((u128)dc.sig, dc.exp - 23, emax - F);
+    if (dc.sign) S -= (i128)ac; else S += (i128)ac;
+    int neg = S < 0;
+    return to_fp32(neg, (u128)(neg ? -S : S), emax - F, 0, (int)g->out_round);
+}
+
+/* D = Phi_GST-FDPA(A, B, C): A[batch][m][k], B[batch][n][k] FP4 codes (one per byte), SA[batch][m][k / k_block],
+ * SB[batch][n][k / k_block].  Returns 0, -2 (parameter) or -3 (shape). */
+int o2_emulate_gst(const gst_params *g, const uint8_t *A, const uint8_t *B, const uint32_t *C, uint32_t *D,
+                   const uint8_t *SA, const uint8_t *SB, uint32_t m, uint32_t n, uint32_t k, uint64_t batch, int nthreads)
+{
+    gst_params p = *g;
+    if (p.L == 0 || p.L > k) p.L = k;
+    if (p.G == 0 || p.k_block == 0 || p.F > 64 || p.out_round > 1 || p.scale_format > 1) return -2;
+    if (k == 0 || k % p.L || p.L % p.k_block || p.k_block % p.G || p.L / p.G > 64) return -3;
+    if (nthreads > 0) omp_set_num_threads(nthreads);
+    const uint32_t nblk = k / p.k_block;
+    int64_t rows = (int64_t)batch * m;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t r = 0; r < rows; ++r) {
+        uint64_t t = (uint64_t)r / m; uint32_t i = (uint32_t)((uint64_t)r % m);
+        for (uint32_t j = 0; j < n; ++j) {
+            size_t o = ((size_t)t * m + i) * n + j;
+            const uint8_t *a = A + ((size_t)t * m + i) * k, *b = B + ((size_t)t * n + j) * k;
+            const uint8_t *al = SA + ((size_t)t * m + i) * nblk, *be = SB + ((size_t)t * n + j) * nblk;
+            uint32_t d = C[o];
+            for (uint32_t k0 = 0; k0 < k; k0 += p.L)
+                d = gst_group_op(&p, a + k0, b + k0, d, al + k0 / p.k_block, be + k0 / p.k_block);
+            D[o] = d;
+        }
+    }
+    return 0;
+}
+
 /* The same, only at the flattened output indices idx[0..count) (index = (b*m + i)*n + j). */
 int o2_emulate_sample(const o2_params *p, const void *A, const void *B, const uint32_t *C,
                       const uint64_t *idx, uint64_t count, uint32_t *D_sample,

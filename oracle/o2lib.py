@@ -124,3 +124,28 @@ def exact_dot_stats(A, B, D, ta, tb, stride):
     return dict(n_samples=int(io[0]), n_equal_rne=int(io[1]), n_above=int(io[2]), n_below=int(io[3]),
                 ulp_hist=[int(x) for x in io[4:38]], sum_abs_err=float(do[0]), max_abs_err=float(do[1]),
                 sum_rel_err=float(do[2]), max_rel_err=float(do[3]), sum_signed_err=float(do[4]))
+
+
+class GstParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_uint32) for n in ("L", "G", "k_block", "F", "out_round", "scale_format", "nan_bits")]
+
+
+def emulate_gst(A, B, C, SA, SB, L, G, k_block, F, out_round, scale_format, nan_bits=0x7FFFFFFF, nthreads=0):
+    """Algorithm "GST-FDPA" chained over K / L operations: FP4 codes A[batch][m][k], B[batch][n][k] (one per byte),
+    scale codes SA[batch][m][k / k_block], SB[batch][n][k / k_block]; returns D as uint32 FP32 bits."""
+    A = np.ascontiguousarray(np.asarray(A).astype(np.uint8, copy=False))
+    B = np.ascontiguousarray(np.asarray(B).astype(np.uint8, copy=False))
+    C = np.ascontiguousarray(np.asarray(C).astype(np.uint32, copy=False))
+    if A.ndim == 2:
+        A, B, C = A[None], B[None], C[None]
+    nb, m, k = A.shape
+    n = B.shape[1]
+    SA = np.ascontiguousarray(np.asarray(SA).astype(np.uint8, copy=False)).reshape(nb, m, k // k_block)
+    SB = np.ascontiguousarray(np.asarray(SB).astype(np.uint8, copy=False)).reshape(nb, n, k // k_block)
+    D = np.empty((nb, m, n), dtype=np.uint32)
+    g = GstParams(L, G, k_block, F, out_round, scale_format, nan_bits)
+    rc = _load().o2_emulate_gst(ctypes.byref(g), _vp(A), _vp(B), _vp(C), _vp(D), _vp(SA), _vp(SB), ctypes.c_uint32(m), ctypes.c_uint32(n),
+                                ctypes.c_uint32(k), ctypes.c_uint64(nb), nthreads)
+    if rc:
+        raise ValueError("o2_emulate_gst failed: %d" % rc)
+    return D
