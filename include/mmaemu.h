@@ -73,7 +73,8 @@ enum { MMAEMU_C_IN_GROUP = 0, MMAEMU_C_AFTER_EXACT = 1, MMAEMU_C_AFTER_RD = 2, M
 enum { MMAEMU_ROUND_RNE = 0, MMAEMU_ROUND_RZ = 1 };
 enum { MMAEMU_ALIGN_RZ = 0 };
 enum { MMAEMU_SPLIT_NONE = 0, MMAEMU_SPLIT_EVEN_ODD = 1, MMAEMU_SPLIT_HALVES = 2, MMAEMU_SPLIT_QUARTERS = 3 };
-enum { MMAEMU_FAMILY_FDPA = 0, MMAEMU_FAMILY_FTZ_ADDMUL = 1 };
+enum { MMAEMU_FAMILY_FDPA = 0, MMAEMU_FAMILY_FTZ_ADDMUL = 1, MMAEMU_FAMILY_GST_FDPA = 2 };
+enum { MMAEMU_SCALE_FORMAT_E8M0 = 0, MMAEMU_SCALE_FORMAT_UE4M3 = 1 };
 
 /*
  * One arithmetic-behaviour model: the chained FDPA model (paper Algorithm "Phi_FDPA")
@@ -138,6 +139,17 @@ enum { MMAEMU_FAMILY_FDPA = 0, MMAEMU_FAMILY_FTZ_ADDMUL = 1 };
  *   c_mode = C_AFTER_EXACT in the FDPA family: the product of two operands of at most 11
  *   significant bits is exact.)
  *
+ * family = MMAEMU_FAMILY_GST_FDPA is Algorithm "GST-FDPA" (Sec. 4.1.3), through mmaemu_emulate_mma_scaled only, FP4 (E2M1)
+ *   operands on both sides: per operation of L = group_len products, every gst_group (G) consecutive products form an
+ *   exact dot product p_g; s_g = p_g * SignedSig(alpha) * SignedSig(beta), e_g = Exp(alpha) + Exp(beta) with the
+ *   scale factors of the group's block (`block` of the call is K_block, a multiple of G and a divisor of L); the
+ *   L / G terms and the accumulator are aligned at their maximum exponent, truncated toward zero to frac_bits
+ *   fractional bits and summed; rho as above.  scale_format: E8M0 (significand 1, Exp = code - 127, 0xFF NaN) or
+ *   UE4M3, NVFP4's unsigned E4M3 (E4M3 decoding of the low seven bits, 0x7F NaN, the top bit ignored).  A NaN scale
+ *   or accumulator gives nan_bits.  Uses group_len, gst_group, frac_bits, out_round, nan_bits, scale_format; every
+ *   other field must hold its default.  (Table "GST-FDPA parameter selection": L = 64, G = 16, F = 35, RZ-FP32,
+ *   K_block = 32 for MXFP4 and 16 for NVFP4.)  L / G <= 64.
+ *
  * Limits: frac_bits <= 40; K <= 2^20; with C_AFTER_EXACT also
  * frac_bits + 2 + ceil(log2 L) <= 56; with the two RD modes frac_bits2, frac_bits_merge
  * and frac_bits_acc <= 48 and max(F, F2, F_m, F_c) + 3 + ceil(log2 L) <= 53.
@@ -163,6 +175,8 @@ typedef struct {
     uint32_t sum_drop_distance;      /* C_AFTER_RD only */
     uint32_t family;                 /* MMAEMU_FAMILY_* */
     uint32_t wide_products;          /* 0 / 1; C_AFTER_RD only */
+    uint32_t gst_group;              /* G; MMAEMU_FAMILY_GST_FDPA only */
+    uint32_t scale_format;           /* MMAEMU_SCALE_FORMAT_*; MMAEMU_FAMILY_GST_FDPA only */
 } mmaemu_model_params;
 
 typedef struct mmaemu_model mmaemu_model; /* opaque, host memory, owned by the library */

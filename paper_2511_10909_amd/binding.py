@@ -14,7 +14,8 @@ E2M3, E3M2, E2M1 = 6, 7, 8                      # FP6 and FP4 operands, one code
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 RNE, RZ = 0, 1
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
-FAMILY_FDPA, FAMILY_FTZ_ADDMUL = 0, 1
+FAMILY_FDPA, FAMILY_FTZ_ADDMUL, FAMILY_GST_FDPA = 0, 1, 2
+SCALE_FORMAT_E8M0, SCALE_FORMAT_UE4M3 = 0, 1
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
 GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING = 5, 6, 7
 SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
@@ -53,7 +54,7 @@ class ModelParams(ctypes.Structure):
                 ("struct_size", "group_len", "frac_bits", "align_round", "c_mode", "frac_bits2", "out_round",
                  "out_mant_bits", "ftz_in", "ftz_out", "nan_bits", "split", "acc_special_truncation",
                  "frac_bits_merge", "frac_bits_acc", "f2_at_leading_bit", "skip_zero_terms", "zero_result_positive",
-                 "sum_drop_distance", "family", "wide_products")]
+                 "sum_drop_distance", "family", "wide_products", "gst_group", "scale_format")]
 
 
 class Dtypes(ctypes.Structure):
@@ -155,11 +156,11 @@ def model_create(group_len=0, frac_bits=24, c_mode=C_IN_GROUP, out_round=RNE, ft
                  nan_bits=0x7FC00000, align_round=0, frac_bits2=0, out_mant_bits=23, struct_size=None,
                  split=SPLIT_NONE, acc_special_truncation=False, frac_bits_merge=0, frac_bits_acc=0,
                  f2_at_leading_bit=False, skip_zero_terms=False, zero_result_positive=False, sum_drop_distance=0,
-                 family=FAMILY_FDPA, wide_products=False):
+                 family=FAMILY_FDPA, wide_products=False, gst_group=0, scale_format=0):
     p = ModelParams(ctypes.sizeof(ModelParams) if struct_size is None else struct_size, group_len, frac_bits,
                     align_round, c_mode, frac_bits2, out_round, out_mant_bits, int(ftz_in), int(ftz_out), nan_bits,
                     split, int(acc_special_truncation), frac_bits_merge, frac_bits_acc, int(f2_at_leading_bit),
-                    int(skip_zero_terms), int(zero_result_positive), sum_drop_distance, family, int(wide_products))
+                    int(skip_zero_terms), int(zero_result_positive), sum_drop_distance, family, int(wide_products), gst_group, scale_format)
     h = _vp()
     _check(_lib.mmaemu_model_create(ctypes.byref(p), ctypes.byref(h)))
     return h

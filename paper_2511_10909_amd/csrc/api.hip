@@ -87,7 +87,24 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: enum field out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if (p->family > MMAEMU_FAMILY_FTZ_ADDMUL) { set_error("model_create: family out of range"); return MMAEMU_ERR_INVALID_ARG; }
+    if (p->family > MMAEMU_FAMILY_GST_FDPA) { set_error("model_create: family out of range"); return MMAEMU_ERR_INVALID_ARG; }
+    if (p->family != MMAEMU_FAMILY_GST_FDPA && (p->gst_group || p->scale_format)) {
+        set_error("model_create: gst_group and scale_format belong to the GST-FDPA family");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if (p->family == MMAEMU_FAMILY_GST_FDPA) {
+        if (p->scale_format > MMAEMU_SCALE_FORMAT_UE4M3) { set_error("model_create: scale_format out of range"); return MMAEMU_ERR_INVALID_ARG; }
+        if (p->gst_group == 0 || p->gst_group > 64 || (p->group_len && (p->group_len % p->gst_group || p->group_len / p->gst_group > 64))) {
+            set_error("model_create: GST-FDPA needs 1 <= gst_group <= 64 dividing group_len, at most 64 groups per operation");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        if (p->c_mode || p->frac_bits2 || p->out_mant_bits != 23 || p->ftz_in || p->ftz_out || p->split || p->acc_special_truncation ||
+            p->frac_bits_merge || p->frac_bits_acc || p->f2_at_leading_bit || p->skip_zero_terms || p->zero_result_positive ||
+            p->sum_drop_distance || p->wide_products) {
+            set_error("model_create: the GST-FDPA family takes group_len, gst_group, frac_bits, out_round, nan_bits and scale_format only");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+    }
     if (p->family == MMAEMU_FAMILY_FTZ_ADDMUL) {
         if (p->group_len != 2 && p->group_len != 4) {
             set_error("model_create: the FTZ-AddMul family needs group_len (P) = 2 or 4");
@@ -182,7 +199,23 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         set_error("emulate_mma: FP16 accumulators go with c_mode C_IN_GROUP or C_AFTER_EXACT and the plain conversion");
         return MMAEMU_ERR_UNSUPPORTED;
     }
-    if (SA && mp.family != MMAEMU_FAMILY_FDPA) { set_error("emulate_mma_scaled: block scales belong to the FDPA family"); return MMAEMU_ERR_UNSUPPORTED; }
+    if (SA && mp.family == MMAEMU_FAMILY_FTZ_ADDMUL) { set_error("emulate_mma_scaled: block scales belong to the FDPA families"); return MMAEMU_ERR_UNSUPPORTED; }
+    if (mp.family == MMAEMU_FAMILY_GST_FDPA) {
+        if (batch == 0) return MMAEMU_OK;
+        if (!SA) { set_error("emulate_mma: the GST-FDPA family needs scale factors (mmaemu_emulate_mma_scaled)"); return MMAEMU_ERR_UNSUPPORTED; }
+        if (dt.a != MMAEMU_FP4_E2M1 || dt.b != MMAEMU_FP4_E2M1 || acc16) { set_error("emulate_mma: GST-FDPA takes FP4 operands and FP32 accumulators"); return MMAEMU_ERR_UNSUPPORTED; }
+        const uint32_t Lg = (mp.group_len == 0 || mp.group_len > k) ? k : mp.group_len;
+        if (k % Lg || Lg % block || block % mp.gst_group || Lg / mp.gst_group > 64) {
+            set_error("emulate_mma: GST-FDPA needs k %% L = 0, L %% block = 0, block %% G = 0 and L / G <= 64 (k=%u L=%u block=%u G=%u)", k, Lg, block, mp.gst_group);
+            return MMAEMU_ERR_SHAPE;
+        }
+        const uint64_t mn_ = (uint64_t)m * n;
+        if (batch && (mn_ > (1ull << 40) || batch > (1ull << 62) / mn_ || batch * mn_ > (1ull << 48))) { set_error("emulate_mma: problem too large"); return MMAEMU_ERR_SHAPE; }
+        if (batch == 0) return MMAEMU_OK;
+        if (!A || !B || !C || !D) { set_error("emulate_mma: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+        const GstArgs ga = {Lg, mp.gst_group, block, mp.frac_bits, mp.out_round, mp.scale_format, mp.nan_bits};
+        return launch_emulate_gst(ga, A, B, C, D, SA, SB, m, n, k, batch, (hipStream_t)hip_stream);
+    }
     if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL && (is_narrow_type(dt.a) || is_narrow_type(dt.b))) {
         set_error("emulate_mma: the FTZ-AddMul family takes FP8, FP16 and BF16 operands");
         return MMAEMU_ERR_UNSUPPORTED;

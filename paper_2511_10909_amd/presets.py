@@ -52,6 +52,15 @@ def _h(L, F):
     return dict(group_len=L, frac_bits=F, out_round=mm.RNE, c_mode=mm.C_IN_GROUP, nan_bits=0x7FFF)
 
 
+# Table "GST-FDPA parameter selection" (Blackwell and RTX Blackwell, FP4 operands): pass the scale codes to
+# emulate_mma_scaled with block = 32 (MXFP4, E8M0 scales) or 16 (NVFP4, UE4M3 scales)
+PAPER_GST = {
+    ("blackwell", "mxfp4"): dict(family=mm.FAMILY_GST_FDPA, group_len=64, gst_group=16, frac_bits=35, out_round=mm.RZ, nan_bits=NVIDIA_NAN,
+                                 scale_format=mm.SCALE_FORMAT_E8M0),
+    ("blackwell", "nvfp4"): dict(family=mm.FAMILY_GST_FDPA, group_len=64, gst_group=16, frac_bits=35, out_round=mm.RZ, nan_bits=NVIDIA_NAN,
+                                 scale_format=mm.SCALE_FORMAT_UE4M3),
+}
+
 PAPER_FP16_OUT = {
     ("volta", "fp16"): _h(4, 23), ("turing", "fp16"): _h(8, 24), ("ampere", "fp16"): _h(8, 24), ("ada", "fp16"): _h(8, 24),
     ("ada", "fp8"): _h(16, 13), ("hopper", "fp16"): _h(16, 25), ("hopper", "fp8"): _h(32, 13),
