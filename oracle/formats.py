@@ -24,6 +24,7 @@ from fractions import Fraction
 
 E4M3, E5M2, FP16, BF16, FP32 = 0, 1, 2, 3, 4
 E2M3, E3M2, E2M1 = 6, 7, 8          # (5 is the E8M0 scale code, which is no operand type)
+TF32 = 9                            # a binary32 word whose low 13 mantissa bits are ignored (8 exponent, 10 mantissa bits)
 
 
 @dataclass(frozen=True)
@@ -34,6 +35,7 @@ class Format:
     bias: int
     ieee_specials: bool  # True: exponent field all-ones = Inf/NaN.  False: E4M3 rule.
     no_specials: bool = False   # every code is finite (FP6, FP4)
+    storage_shift: int = 0      # the code sits this many bits above bit 0 of its storage word (TF32: 13)
 
     @property
     def width(self):
@@ -53,6 +55,7 @@ FORMATS = {
     E2M3: Format("e2m3", 2, 3, 1, False, True),
     E3M2: Format("e3m2", 3, 2, 3, False, True),
     E2M1: Format("e2m1", 2, 1, 1, False, True),
+    TF32: Format("tf32", 8, 10, 127, True, False, 13),
 }
 
 ZERO, SUBNORMAL, NORMAL, INF, NAN = "zero", "subnormal", "normal", "inf", "nan"
@@ -83,7 +86,7 @@ class Decoded:
 
 def decode(bits, fmt_id):
     f = FORMATS[fmt_id]
-    bits = int(bits) & ((1 << f.width) - 1)
+    bits = (int(bits) >> f.storage_shift) & ((1 << f.width) - 1)
     sign = bits >> (f.ebits + f.mbits)
     E = (bits >> f.mbits) & f.emax_field
     M = bits & ((1 << f.mbits) - 1)
@@ -98,4 +101,4 @@ def decode(bits, fmt_id):
 
 def flush_subnormal(bits, fmt_id):
     """Input flush (Algorithm "Phi_FTZ-AddMul", FlushSubnormal): subnormal -> +0.0."""
-    return 0 if decode(bits, fmt_id).cls == SUBNORMAL else int(bits)
+    return 0 if decode(bits, fmt_id).cls == SUBNORMAL else int(bits)          # (a zero word is +0.0 in every format)

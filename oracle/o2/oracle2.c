@@ -33,7 +33,7 @@
 typedef __int128 i128;
 typedef unsigned __int128 u128;
 
-enum { T_E4M3 = 0, T_E5M2 = 1, T_FP16 = 2, T_BF16 = 3, T_FP32 = 4, T_E8M0 = 5, T_E2M3 = 6, T_E3M2 = 7, T_E2M1 = 8 };
+enum { T_E4M3 = 0, T_E5M2 = 1, T_FP16 = 2, T_BF16 = 3, T_FP32 = 4, T_E8M0 = 5, T_E2M3 = 6, T_E3M2 = 7, T_E2M1 = 8, T_TF32 = 9 };
 enum { CLS_ZERO, CLS_SUB, CLS_NORMAL, CLS_INF, CLS_NAN };
 enum { C_IN_GROUP = 0, C_AFTER_EXACT = 1, C_AFTER_RD = 2, C_AFTER_RD_EVEN_ODD = 3 };
 enum { R_RNE = 0, R_RZ = 1 };
@@ -50,9 +50,9 @@ typedef struct {
 
 /* ieee: 1 = exponent field all ones is Inf / NaN, 0 = the E4M3 rule (one NaN code), 2 = every code finite (FP6, FP4) */
 typedef struct { int ebits, mbits, bias, ieee; } fmt_t;
-static const fmt_t FMT[9] = {
+static const fmt_t FMT[10] = {
     {4, 3, 7, 0}, {5, 2, 15, 1}, {5, 10, 15, 1}, {8, 7, 127, 1}, {8, 23, 127, 1}, {8, 0, 127, 2},
-    {2, 3, 1, 2}, {3, 2, 3, 2}, {2, 1, 1, 2}};
+    {2, 3, 1, 2}, {3, 2, 3, 2}, {2, 1, 1, 2}, {8, 10, 127, 1}};      /* TF32: the top 19 bits of a binary32 word */
 
 typedef struct { int cls, sign, exp; uint32_t sig; } dec_t;
 
@@ -77,6 +77,7 @@ static uint32_t load_elem(const void *p, size_t i, int t)
     switch (t) {
     case T_E4M3: case T_E5M2: case T_E2M3: case T_E3M2: case T_E2M1: return ((const uint8_t *)p)[i];
     case T_FP16: case T_BF16: return ((const uint16_t *)p)[i];
+    case T_TF32: return ((const uint32_t *)p)[i] >> 13;       /* the low 13 mantissa bits are ignored */
     default: return ((const uint32_t *)p)[i];
     }
 }
@@ -408,7 +409,7 @@ static uint32_t addmul_element(const o2_params *p, const void *A, const void *B,
 
 static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out)
 {
-    if (ta < 0 || tb < 0 || ta > T_E2M1 || tb > T_E2M1 || ta == T_FP32 || tb == T_FP32 || ta == T_E8M0 || tb == T_E8M0) return -2;
+    if (ta < 0 || tb < 0 || ta > T_TF32 || tb > T_TF32 || ta == T_FP32 || tb == T_FP32 || ta == T_E8M0 || tb == T_E8M0) return -2;
     if (p->family == 1) {
         if (p->acc_fp16) return -2;
         if (p->group_len != 2 && p->group_len != 4) return -2;

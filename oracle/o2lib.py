@@ -43,7 +43,7 @@ def _params(p, tc=fm.FP32):
 
 
 _NP = {fm.E4M3: np.uint8, fm.E5M2: np.uint8, fm.FP16: np.uint16, fm.BF16: np.uint16, fm.FP32: np.uint32,
-       fm.E2M3: np.uint8, fm.E3M2: np.uint8, fm.E2M1: np.uint8}
+       fm.E2M3: np.uint8, fm.E3M2: np.uint8, fm.E2M1: np.uint8, fm.TF32: np.uint32}
 
 
 def _prep(A, B, C, ta, tb):

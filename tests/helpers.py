@@ -29,4 +29,4 @@ def e5m2_bits(x):
     return b >> 8
 
 
-ENCODERS = {"fp16": fp16_bits, "bf16": bf16_bits, "e5m2": e5m2_bits}
+ENCODERS = {"fp16": fp16_bits, "bf16": bf16_bits, "e5m2": e5m2_bits, "tf32": f32_bits}     # (a TF32 operand is a binary32 word)

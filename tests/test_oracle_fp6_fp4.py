@@ -96,3 +96,38 @@ def test_o2_matches_oracle_on_fp6_fp4(ta, tb):
         want = emulate_mma(p, A, B, C, ta, tb, SA, SB, 32)
         got, _ = o2lib.emulate_mma_scaled(p, A, B, C, SA, SB, 32, ta, tb)
         assert np.array_equal(got, want), (trial, p)
+
+
+def test_tf32_operands_ignore_the_low_13_bits():
+    # TF32 (Require lines of Algorithms "T-FDPA" and "TR-FDPA"): a binary32 word of which the sign, the 8 exponent bits
+    # and the top 10 mantissa bits count.  Values with 11 significant bits behave like FP16 values of the same
+    # significand; the low 13 bits change nothing; specials are those of binary32.
+    rng = np.random.default_rng(12)
+    p = ModelParams(group_len=4, frac_bits=24, out_round=RZ)
+    for _ in range(200):
+        x = synth.narrow_exponent_bits(rng, 8, fm.FP16, 5, 25)
+        xf = x.astype(np.uint16).view(np.float16).astype(np.float32).view(np.uint32)          # the same values as binary32 words
+        a16, b16, a32, b32 = x[:4].tolist(), x[4:].tolist(), xf[:4].tolist(), xf[4:].tolist()
+        c = int(synth.narrow_exponent_bits(rng, 1, fm.FP32, 110, 140)[0])
+        want = fdpa_group(p, a16, b16, c, fm.FP16, fm.FP16)
+        assert fdpa_group(p, a32, b32, c, fm.TF32, fm.TF32) == want
+        noisy = [int(v) | int(rng.integers(0, 1 << 13)) for v in a32]
+        assert fdpa_group(p, noisy, b32, c, fm.TF32, fm.TF32) == want
+    assert fm.decode(0x7F800000, fm.TF32).cls == fm.INF and fm.decode(0x7F802000, fm.TF32).cls == fm.NAN
+    assert fm.decode(0x7F801FFF, fm.TF32).cls == fm.INF                 # a NaN payload only in the ignored bits reads as infinity
+    assert fm.decode(0x00002000, fm.TF32).cls == fm.SUBNORMAL and fm.decode(0x00001FFF, fm.TF32).cls == fm.ZERO
+    # C form = rational form
+    for trial in range(10):
+        q = ModelParams(group_len=int(rng.choice([2, 4, 8])), frac_bits=int(rng.choice([13, 24, 25])), out_round=int(rng.integers(0, 2)),
+                        c_mode=int(rng.choice([C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD])))
+        if q.c_mode == C_AFTER_RD:
+            q = q.with_(frac_bits2=31)
+        A = synth.random_bits(rng, (2, 3, 16), fm.FP32, finite=(trial % 2 == 0))
+        B = synth.random_bits(rng, (2, 3, 16), fm.FP32)
+        if trial % 3:
+            A = synth.narrow_exponent_bits(rng, (2, 3, 16), fm.FP32, 100, 150)
+            B = synth.narrow_exponent_bits(rng, (2, 3, 16), fm.FP32, 100, 150)
+        C = synth.narrow_exponent_bits(rng, (2, 3, 3), fm.FP32, 80, 170)
+        want = emulate_mma(q, A, B, C, fm.TF32, fm.TF32)
+        got, _ = o2lib.emulate_mma(q, A, B, C, fm.TF32, fm.TF32)
+        assert np.array_equal(got, want), (trial, q)

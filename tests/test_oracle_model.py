@@ -15,7 +15,7 @@ from helpers import f32_bits, bits_f32, ENCODERS, fp16_bits, bf16_bits
 from paper_2511_10909_amd import synth
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
-FMT_ID = {"fp16": fm.FP16, "bf16": fm.BF16, "e5m2": fm.E5M2}
+FMT_ID = {"fp16": fm.FP16, "bf16": fm.BF16, "e5m2": fm.E5M2, "tf32": fm.TF32}
 WIDE = 700   # more fractional bits than any pair of supported operands can span
 
 
