@@ -58,12 +58,17 @@ typedef enum {
      * higher bits ignored on input and written as zero by mmaemu_generate. */
     MMAEMU_FP6_E2M3 = 6, /* bias 1, largest 7.5 */
     MMAEMU_FP6_E3M2 = 7, /* bias 3, largest 28 */
-    MMAEMU_FP4_E2M1 = 8  /* bias 1, largest 6 */
+    MMAEMU_FP4_E2M1 = 8, /* bias 1, largest 6 */
+    /* TF32 operands (Require lines of Algorithms "T-FDPA" and "TR-FDPA"): one binary32 word per element, of which the
+     * sign, the 8 exponent bits and the top 10 mantissa bits count; the low 13 bits are ignored on input (a NaN whose
+     * payload lies only there reads as an infinity).  Pairs with itself only; mmaemu_generate does not take it
+     * (every MMAEMU_FP32 stream is a TF32 stream). */
+    MMAEMU_TF32 = 9
 } mmaemu_dtype;
 
 typedef struct {
-    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1} (the FP6 / FP4 types
-                            pair with each other and with the FP8 types); c = d = FP32, or c = d = FP16
+    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1, TF32} (the FP6 / FP4
+                            types pair with each other and with the FP8 types, TF32 with itself); c = d = FP32, or c = d = FP16
                             (Algorithm "T-FDPA" with F_C = FP16: the accumulator is decoded as binary16, Exp >= -14,
                             rho is RNE-FP16 of Table "Conversion functions" (RZ likewise), both flushes use 2^-14, the
                             NaN pattern is the low half of nan_bits; c_mode C_IN_GROUP or C_AFTER_EXACT only) */

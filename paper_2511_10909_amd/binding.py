@@ -11,6 +11,7 @@ LIB_PATH = os.path.join(_PKG, "libmmaemu.so")
 
 E4M3, E5M2, FP16, BF16, FP32, E8M0 = 0, 1, 2, 3, 4, 5
 E2M3, E3M2, E2M1 = 6, 7, 8                      # FP6 and FP4 operands, one code per byte
+TF32 = 9                                        # binary32 words whose low 13 mantissa bits are ignored
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 RNE, RZ = 0, 1
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
@@ -39,7 +40,7 @@ MFMA_SCALE_IDS = tuple(range(10, 35))
 (MFMA_F32_32X32X16_F16, MFMA_F32_32X32X16_BF16, MFMA_F32_32X32X16_FP8_FP8, MFMA_F32_32X32X16_FP8_BF8,
  MFMA_F32_32X32X16_BF8_FP8, MFMA_F32_32X32X16_BF8_BF8) = range(35, 41)
 MFMA_UNSCALED_IDS = tuple(range(10)) + tuple(range(35, 41))
-ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1}
+ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1, TF32: 4}
 NO_MISMATCH = (1 << 64) - 1
 
 

@@ -41,7 +41,7 @@ mmaemu_status hip_fail(hipError_t e, const char *what)
     return MMAEMU_ERR_HIP;
 }
 
-static bool is_ab_type(uint32_t t) { return t <= MMAEMU_BF16 || is_narrow_type(t); }
+static bool is_ab_type(uint32_t t) { return t <= MMAEMU_BF16 || is_narrow_type(t) || t == MMAEMU_TF32; }
 
 static uint32_t ceil_log2(uint32_t x)
 {
@@ -181,13 +181,17 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     if (!model || model->magic != MODEL_MAGIC) { set_error("emulate_mma: bad model handle"); return MMAEMU_ERR_INVALID_ARG; }
     if (m == 0 || n == 0 || k == 0) { set_error("emulate_mma: zero dimension (m=%u n=%u k=%u)", m, n, k); return MMAEMU_ERR_SHAPE; }
     if (k > (1u << 20)) { set_error("emulate_mma: k=%u > 2^20", k); return MMAEMU_ERR_SHAPE; }
-    if (dt.a > MMAEMU_FP4_E2M1 || dt.b > MMAEMU_FP4_E2M1 || dt.c > MMAEMU_FP32 || dt.d > MMAEMU_FP32) {
+    if (dt.a > MMAEMU_TF32 || dt.b > MMAEMU_TF32 || dt.c > MMAEMU_FP32 || dt.d > MMAEMU_FP32) {
         set_error("emulate_mma: dtype out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
     const bool acc16 = dt.c == MMAEMU_FP16 && dt.d == MMAEMU_FP16;
     if (!is_ab_type(dt.a) || !is_ab_type(dt.b) || !((dt.c == MMAEMU_FP32 && dt.d == MMAEMU_FP32) || acc16)) {
-        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1} and c = d = FP32 or c = d = FP16");
+        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1, TF32} and c = d = FP32 or c = d = FP16");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if ((dt.a == MMAEMU_TF32) != (dt.b == MMAEMU_TF32)) {
+        set_error("emulate_mma: TF32 operands pair with TF32 operands only");
         return MMAEMU_ERR_UNSUPPORTED;
     }
     if ((is_narrow_type(dt.a) && !is_byte_type(dt.b)) || (is_narrow_type(dt.b) && !is_byte_type(dt.a))) {
@@ -216,7 +220,7 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         const GstArgs ga = {Lg, mp.gst_group, block, mp.frac_bits, mp.out_round, mp.scale_format, mp.nan_bits};
         return launch_emulate_gst(ga, A, B, C, D, SA, SB, m, n, k, batch, (hipStream_t)hip_stream);
     }
-    if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL && (is_narrow_type(dt.a) || is_narrow_type(dt.b))) {
+    if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL && (is_narrow_type(dt.a) || is_narrow_type(dt.b) || dt.a == MMAEMU_TF32)) {
         set_error("emulate_mma: the FTZ-AddMul family takes FP8, FP16 and BF16 operands");
         return MMAEMU_ERR_UNSUPPORTED;
     }
@@ -333,6 +337,7 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
         set_error("generate: struct_size %u, expected %zu", g->struct_size, sizeof(mmaemu_gen_params));
         return MMAEMU_ERR_INVALID_ARG;
     }
+    if (dtype == MMAEMU_TF32) { set_error("generate: TF32 streams are FP32 streams (generate MMAEMU_FP32)"); return MMAEMU_ERR_UNSUPPORTED; }
     if ((uint32_t)dtype > MMAEMU_FP4_E2M1 || g->family > MMAEMU_GEN_CANCELLING || g->scale_scope > MMAEMU_SCALE_TILE) {
         set_error("generate: enum out of range");
         return MMAEMU_ERR_INVALID_ARG;

@@ -17,6 +17,7 @@ template <> struct Fmt<MMAEMU_BF16> { static constexpr int EB = 8, MB = 7, BIAS 
 template <> struct Fmt<MMAEMU_FP32> { static constexpr int EB = 8, MB = 23, BIAS = 127, W = 32; static constexpr bool IEEE = true, NOSPEC = false; using elem = uint32_t; };
 template <> struct Fmt<MMAEMU_FP6_E2M3> { static constexpr int EB = 2, MB = 3, BIAS = 1, W = 8; static constexpr bool IEEE = false, NOSPEC = true; using elem = uint8_t; };
 template <> struct Fmt<MMAEMU_FP6_E3M2> { static constexpr int EB = 3, MB = 2, BIAS = 3, W = 8; static constexpr bool IEEE = false, NOSPEC = true; using elem = uint8_t; };
+template <> struct Fmt<MMAEMU_TF32> { static constexpr int EB = 8, MB = 10, BIAS = 127, W = 32; static constexpr bool IEEE = true, NOSPEC = false; using elem = uint32_t; };   // fields after dropping the low 13 bits
 template <> struct Fmt<MMAEMU_FP4_E2M1> { static constexpr int EB = 2, MB = 1, BIAS = 1, W = 8; static constexpr bool IEEE = false, NOSPEC = true; using elem = uint8_t; };
 
 struct FmtInfo { int ebits, mbits, bias, width; bool ieee, nospec; };      // width: storage bits
@@ -31,6 +32,7 @@ inline FmtInfo fmt_info(uint32_t t)
     case MMAEMU_FP6_E2M3: return {2, 3, 1, 8, false, true};
     case MMAEMU_FP6_E3M2: return {3, 2, 3, 8, false, true};
     case MMAEMU_FP4_E2M1: return {2, 1, 1, 8, false, true};
+    case MMAEMU_TF32: return {8, 10, 127, 32, true, false};
     default: return {8, 23, 127, 32, true, false};
     }
 }

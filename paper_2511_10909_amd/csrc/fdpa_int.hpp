@@ -20,6 +20,7 @@ __device__ __forceinline__ Dec decode(uint32_t bits, uint32_t ftz_in)
 {
     using F = Fmt<T>;
     constexpr uint32_t EMASK = (1u << F::EB) - 1u, MMASK = (1u << F::MB) - 1u;
+    if (T == MMAEMU_TF32) bits >>= 13;                  // the low 13 mantissa bits of the binary32 word do not count
     const uint32_t E = (bits >> F::MB) & EMASK, M = bits & MMASK;
     Dec d;
     d.sign = (bits >> (F::EB + F::MB)) & 1u;

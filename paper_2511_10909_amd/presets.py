@@ -1,7 +1,7 @@
 """Named parameter sets for `binding.model_create` (data only).
 
 PAPER: the rows of the paper's Tables "T-FDPA and ST-FDPA parameter selection" and "TR-FDPA and GTR-FDPA
-parameter selection" that this library's operand and output types cover (FP8 / FP16 / BF16 inputs, FP32
+parameter selection" that this library's operand and output types cover (FP8 / FP16 / BF16 / TF32 inputs, FP32
 output, rho in {RNE-FP32, RZ-FP32}); NaN encoding per Sec. 4.2.
 
 GFX950_MFMA: parameter sets found with this library by the paper's own method (candidate models against the
@@ -24,6 +24,10 @@ PAPER = {
     # architecture, input type (output FP32)
     ("volta", "fp16"): _t(4, 23, mm.RZ),
     ("turing", "fp16"): _t(8, 24, mm.RZ),
+    ("ampere", "tf32"): _t(4, 24, mm.RZ),
+    ("ada", "tf32"): _t(4, 24, mm.RZ),
+    ("hopper", "tf32"): _t(8, 25, mm.RZ),
+    ("blackwell", "tf32"): _t(8, 25, mm.RZ),
     ("ampere", "bf16"): _t(8, 24, mm.RZ),
     ("ampere", "fp16"): _t(8, 24, mm.RZ),
     ("ada", "bf16"): _t(8, 24, mm.RZ),
@@ -41,6 +45,7 @@ PAPER = {
     ("cdna2", "bf16_1k"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),
     ("cdna2", "fp16"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),
     ("fma_chain", "any"): dict(group_len=1, frac_bits=24, out_round=mm.RNE, c_mode=mm.C_AFTER_EXACT),   # Phi_FMA on <= 16-bit inputs
+    ("cdna3", "tf32"): dict(group_len=4, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD),
     ("cdna3", "bf16"): dict(group_len=8, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD),
     ("cdna3", "fp16"): dict(group_len=8, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD),
     ("cdna3", "fp8"): dict(group_len=16, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD_EVEN_ODD),

@@ -7,11 +7,12 @@ import numpy as np
 
 E4M3, E5M2, FP16, BF16, FP32 = 0, 1, 2, 3, 4
 E2M3, E3M2, E2M1 = 6, 7, 8                      # FP6 and FP4: one code per byte, in its low bits
-WIDTH = {E4M3: 8, E5M2: 8, FP16: 16, BF16: 16, FP32: 32, E2M3: 6, E3M2: 6, E2M1: 4}     # bits of a code, sign on top
-EBITS = {E4M3: 4, E5M2: 5, FP16: 5, BF16: 8, FP32: 8, E2M3: 2, E3M2: 3, E2M1: 2}
-MBITS = {E4M3: 3, E5M2: 2, FP16: 10, BF16: 7, FP32: 23, E2M3: 3, E3M2: 2, E2M1: 1}
+TF32 = 9                                        # whole binary32 words (the low 13 bits are drawn too: the models ignore them)
+WIDTH = {E4M3: 8, E5M2: 8, FP16: 16, BF16: 16, FP32: 32, E2M3: 6, E3M2: 6, E2M1: 4, TF32: 32}     # bits of a code, sign on top
+EBITS = {E4M3: 4, E5M2: 5, FP16: 5, BF16: 8, FP32: 8, E2M3: 2, E3M2: 3, E2M1: 2, TF32: 8}
+MBITS = {E4M3: 3, E5M2: 2, FP16: 10, BF16: 7, FP32: 23, E2M3: 3, E3M2: 2, E2M1: 1, TF32: 23}
 NP_DTYPE = {E4M3: np.uint8, E5M2: np.uint8, FP16: np.uint16, BF16: np.uint16, FP32: np.uint32, 5: np.uint8,   # 5: E8M0 scale codes
-            E2M3: np.uint8, E3M2: np.uint8, E2M1: np.uint8}
+            E2M3: np.uint8, E3M2: np.uint8, E2M1: np.uint8, TF32: np.uint32}
 
 
 def _is_special(bits, t):
@@ -56,5 +57,6 @@ SPECIAL_CODES = {
     FP16: [0x7C00, 0xFC00, 0x7E00, 0x0000, 0x8000, 0x7BFF, 0x0001],
     BF16: [0x7F80, 0xFF80, 0x7FC0, 0x0000, 0x8000, 0x7F7F, 0x0001],
     FP32: [0x7F800000, 0xFF800000, 0x7FC00000, 0, 0x80000000, 0x7F7FFFFF, 1],
+    TF32: [0x7F800000, 0xFF800000, 0x7FC00000, 0x7F802000, 0x7F801FFF, 0, 0x80000000, 0x7F7FFFFF, 0x00002000, 0x00001FFF],
     E2M3: [0x00, 0x20, 0x1F, 0x3F, 0x01], E3M2: [0x00, 0x20, 0x1F, 0x3F, 0x01], E2M1: [0x0, 0x8, 0x7, 0xF, 0x1],
 }
