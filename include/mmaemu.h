@@ -228,7 +228,8 @@ mmaemu_status mmaemu_emulate_mma_scaled(const mmaemu_model *model, const void *A
  *   ulp_hist[i]      distance in [2^(i-1), 2^i), i = 1..32
  *   ulp_hist[33]     exactly one of the two values is NaN
  * Ordered-integer distance: key(b) = b if the sign bit is clear, else -(b & 0x7FFFFFFF);
- * distance = |key(x) - key(y)|.
+ * distance = |key(x) - key(y)|.  For FP16 outputs the same on 16-bit patterns (sign bit 0x8000, NaN above 0x7C00;
+ * only buckets 0..16 and 33 can fill).
  */
 typedef struct {
     uint64_t n_compared;
@@ -241,8 +242,9 @@ typedef struct {
 
 /* Sets *dev_stats to the empty state (all zero, first_mismatch_index = UINT64_MAX). */
 mmaemu_status mmaemu_stats_reset(mmaemu_stats *dev_stats, void *hip_stream);
-/* Accumulates the comparison of D0[0..count) with D1[0..count) (FP32 bit patterns; `d`
- * must be MMAEMU_FP32).  count = 0 is a no-op. */
+/* Accumulates the comparison of D0[0..count) with D1[0..count): FP32 bit patterns (`d` = MMAEMU_FP32) or FP16 bit
+ * patterns (`d` = MMAEMU_FP16, the outputs of models run with c = d = FP16); other types: MMAEMU_ERR_UNSUPPORTED.
+ * Pointers aligned to the element size.  count = 0 is a no-op. */
 mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uint64_t index_base,
                              mmaemu_dtype d, mmaemu_stats *dev_stats, void *hip_stream);
 

@@ -15,7 +15,7 @@ build's own definition:
 
 Ordered-integer distance: map FP32 bits b to key(b) = b if the sign bit is clear,
 else -(b & 0x7FFFFFFF); the distance is |key(x) - key(y)| (so +0 and -0 coincide
-and adjacent floats are at distance 1).
+and adjacent floats are at distance 1).  FP16 outputs: the same on 16-bit patterns.
 """
 import numpy as np
 
@@ -23,14 +23,15 @@ NO_MISMATCH = (1 << 64) - 1
 N_BUCKETS = 34
 
 
-def ordered_key(bits):
+def ordered_key(bits, width=32):
     b = np.asarray(bits, dtype=np.uint32).astype(np.int64)
-    return np.where(b & 0x80000000, -(b & 0x7FFFFFFF), b)
+    sign = 1 << (width - 1)
+    return np.where(b & sign, -(b & (sign - 1)), b)
 
 
-def is_nan(bits):
+def is_nan(bits, width=32):
     b = np.asarray(bits, dtype=np.uint32)
-    return (b & 0x7FFFFFFF) > 0x7F800000
+    return (b & ((1 << (width - 1)) - 1)) > (0x7F800000 if width == 32 else 0x7C00)
 
 
 def empty_stats():
@@ -38,8 +39,9 @@ def empty_stats():
                 first_mismatch_index=NO_MISMATCH, max_ulp_dist=0, ulp_hist=[0] * N_BUCKETS)
 
 
-def compare(d0, d1, stats=None, index_base=0):
-    """Accumulate the comparison of two FP32 bit arrays into `stats` (a dict)."""
+def compare(d0, d1, stats=None, index_base=0, width=32):
+    """Accumulate the comparison of two FP32 (width 32) or FP16 (width 16) bit arrays into `stats` (a dict)."""
+    assert width in (32, 16)
     st = empty_stats() if stats is None else stats
     x = np.asarray(d0, dtype=np.uint32).ravel()
     y = np.asarray(d1, dtype=np.uint32).ravel()
@@ -47,7 +49,7 @@ def compare(d0, d1, stats=None, index_base=0):
     st["n_compared"] += int(x.size)
     diff = x != y
     st["n_mismatch_bits"] += int(diff.sum())
-    nx, ny = is_nan(x), is_nan(y)
+    nx, ny = is_nan(x, width), is_nan(y, width)
     st["n_mismatch_nan_equiv"] += int((diff & nx & ny).sum())
     if diff.any():
         st["first_mismatch_index"] = min(st["first_mismatch_index"], index_base + int(np.argmax(diff)))
@@ -56,7 +58,7 @@ def compare(d0, d1, stats=None, index_base=0):
     st["ulp_hist"][33] += int(one_nan.sum())
     st["ulp_hist"][0] += int(both_nan.sum())
     num = ~(nx | ny)
-    dist = np.abs(ordered_key(x[num]) - ordered_key(y[num]))
+    dist = np.abs(ordered_key(x[num], width) - ordered_key(y[num], width))
     if dist.size:
         st["max_ulp_dist"] = max(st["max_ulp_dist"], int(dist.max()))
         # bucket = bit length of the distance

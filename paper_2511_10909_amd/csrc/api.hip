@@ -320,13 +320,14 @@ mmaemu_status mmaemu_stats_reset(mmaemu_stats *st, void *hip_stream)
 mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uint64_t index_base, mmaemu_dtype d,
                              mmaemu_stats *st, void *hip_stream)
 {
-    if (d != MMAEMU_FP32) { set_error("compare: only FP32 outputs"); return MMAEMU_ERR_UNSUPPORTED; }
+    if (d != MMAEMU_FP32 && d != MMAEMU_FP16) { set_error("compare: FP32 or FP16 outputs"); return MMAEMU_ERR_UNSUPPORTED; }
+    const uintptr_t amask = d == MMAEMU_FP32 ? 3 : 1;
     if (!st) { set_error("compare: NULL stats"); return MMAEMU_ERR_INVALID_ARG; }
     if (count == 0) return MMAEMU_OK;
     if (!D0 || !D1) { set_error("compare: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
-    if (((uintptr_t)D0 | (uintptr_t)D1) & 3) { set_error("compare: pointers must be 4-byte aligned"); return MMAEMU_ERR_INVALID_ARG; }
+    if (((uintptr_t)D0 | (uintptr_t)D1) & amask) { set_error("compare: pointers must be aligned to the element size"); return MMAEMU_ERR_INVALID_ARG; }
     if (count > (1ull << 48)) { set_error("compare: count too large"); return MMAEMU_ERR_SHAPE; }
-    return launch_compare((const uint32_t *)D0, (const uint32_t *)D1, count, index_base, st, (hipStream_t)hip_stream);
+    return launch_compare(D0, D1, count, index_base, d == MMAEMU_FP16, st, (hipStream_t)hip_stream);
 }
 
 mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtype dtype, uint64_t ept,

@@ -91,7 +91,7 @@ struct GstArgs { uint32_t L, G, block, F, out_round, scale_format, nan_bits; };
 mmaemu_status launch_emulate_gst(const GstArgs &g, const void *A, const void *B, const void *C, void *D, const uint8_t *SA,
                                  const uint8_t *SB, uint32_t m, uint32_t n, uint32_t k, uint64_t batch, hipStream_t s);
 mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s);
-mmaemu_status launch_compare(const uint32_t *d0, const uint32_t *d1, uint64_t count, uint64_t base,
+mmaemu_status launch_compare(const void *d0, const void *d1, uint64_t count, uint64_t base, bool half,
                              mmaemu_stats *st, hipStream_t s);
 mmaemu_status launch_generate(const mmaemu_gen_params &g, void *out, uint32_t dtype, uint64_t ept,
                               uint64_t first_tile, uint64_t n_tiles, void *workspace, hipStream_t s);

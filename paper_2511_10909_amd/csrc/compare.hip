@@ -1,7 +1,7 @@
-// Bitwise comparison of two FP32 outputs with mismatch statistics (paper Eq. 2 and
+// Bitwise comparison of two FP32 (or two FP16) outputs with mismatch statistics (paper Eq. 2 and
 // Sec. 3.1 Step 4: the model must reproduce the interface bit by bit).
 //
-// HBM-bound: 8 bytes read per compared pair.  Each lane handles four consecutive
+// HBM-bound: 8 (4) bytes read per compared pair.  Each lane handles four (eight) consecutive
 // elements (one 128-bit load per input).  The histogram is kept in LDS in 32 copies per
 // bucket (copy = lane mod 32), so that lanes counting the same bucket do not serialise
 // on one address; counters are flushed with one global atomic per non-zero counter per
@@ -17,9 +17,11 @@ __global__ void stats_reset_kernel(mmaemu_stats *st)
     if (i < sizeof(mmaemu_stats) / 8) w[i] = (i == 3) ? ~0ull : 0ull;   // word 3: first_mismatch_index
 }
 
-__device__ __forceinline__ int64_t ordered_key(uint32_t b)
+// W = 32: binary32 patterns; W = 16: binary16 patterns (widened to 32 bits by the caller of one_pair)
+template <int W> __device__ __forceinline__ int64_t ordered_key(uint32_t b)
 {
-    return (b & 0x80000000u) ? -(int64_t)(b & 0x7FFFFFFFu) : (int64_t)b;
+    constexpr uint32_t SIGN = 1u << (W - 1);
+    return (b & SIGN) ? -(int64_t)(b & (SIGN - 1u)) : (int64_t)b;
 }
 
 struct Local {
@@ -27,9 +29,11 @@ struct Local {
     uint64_t first, maxd;
 };
 
+template <int W>
 __device__ __forceinline__ void one_pair(uint32_t x, uint32_t y, uint64_t idx, Local &lc, uint32_t *hist)
 {
-    const bool nx = (x & 0x7FFFFFFFu) > 0x7F800000u, ny = (y & 0x7FFFFFFFu) > 0x7F800000u;
+    constexpr uint32_t MAG = (1u << (W - 1)) - 1u, INF = W == 32 ? 0x7F800000u : 0x7C00u;
+    const bool nx = (x & MAG) > INF, ny = (y & MAG) > INF;
     uint32_t bucket;
     if (x != y) {
         lc.mism += 1;
@@ -39,7 +43,7 @@ __device__ __forceinline__ void one_pair(uint32_t x, uint32_t y, uint64_t idx, L
         bucket = (nx && ny) ? 0u : 33u;
         if (nx && ny && x != y) lc.nan_equiv += 1;
     } else {
-        const int64_t kx = ordered_key(x), ky = ordered_key(y);
+        const int64_t kx = ordered_key<W>(x), ky = ordered_key<W>(y);
         const uint64_t dist = (uint64_t)(kx > ky ? kx - ky : ky - kx);
         lc.maxd = dist > lc.maxd ? dist : lc.maxd;
         bucket = dist ? 64u - (uint32_t)__builtin_clzll(dist) : 0u;
@@ -47,54 +51,53 @@ __device__ __forceinline__ void one_pair(uint32_t x, uint32_t y, uint64_t idx, L
     if (bucket) atomicAdd(&hist[bucket * 32u + (threadIdx.x & 31u)], 1u);   // bucket 0 is derived from the total
 }
 
-__global__ void __launch_bounds__(256)
-compare_kernel(const uint32_t *__restrict__ d0, const uint32_t *__restrict__ d1, uint64_t count,
-               uint64_t base, mmaemu_stats *st)
+// the 128 / W elements of one 128-bit load from each input, first element index i0
+template <int W>
+__device__ __forceinline__ void one_vector(const uint4 &x, const uint4 &y, uint64_t i0, Local &lc, uint32_t *hist)
 {
+    const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        if (W == 32) {
+            one_pair<W>(xs[w], ys[w], i0 + w, lc, hist);
+        } else {
+            one_pair<W>(xs[w] & 0xFFFFu, ys[w] & 0xFFFFu, i0 + 2 * w, lc, hist);
+            one_pair<W>(xs[w] >> 16, ys[w] >> 16, i0 + 2 * w + 1, lc, hist);
+        }
+    }
+}
+
+template <int W, typename T>
+__global__ void __launch_bounds__(1024)
+compare_kernel(const T *__restrict__ d0, const T *__restrict__ d1, uint64_t count, uint64_t base, mmaemu_stats *st)
+{
+    constexpr uint32_t EPV = 128 / W;                    // elements per 128-bit load
     __shared__ uint32_t hist[34 * 32];
     __shared__ uint32_t s_mism, s_nan;
-    __shared__ unsigned long long s_first, s_maxd, s_count;
+    __shared__ unsigned long long s_first, s_maxd;
     for (uint32_t i = threadIdx.x; i < 34 * 32; i += blockDim.x) hist[i] = 0;
-    if (threadIdx.x == 0) { s_mism = 0; s_nan = 0; s_first = ~0ull; s_maxd = 0; s_count = 0; }
+    if (threadIdx.x == 0) { s_mism = 0; s_nan = 0; s_first = ~0ull; s_maxd = 0; }
     __syncthreads();
 
     Local lc = {0, 0, ~0ull, 0};
-    const uint64_t nvec = count / 4;
+    const uint64_t nvec = count / EPV;
     const bool aligned = ((reinterpret_cast<uintptr_t>(d0) | reinterpret_cast<uintptr_t>(d1)) & 15) == 0;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    uint64_t handled = 0;        // elements this thread looked at
     if (aligned) {
         const uint4 *v0 = reinterpret_cast<const uint4 *>(d0), *v1 = reinterpret_cast<const uint4 *>(d1);
         uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
         for (; v + stride < nvec; v += 2 * stride) {               // two independent 128-bit loads per input in flight
             const uint4 x0 = v0[v], y0 = v1[v], x1 = v0[v + stride], y1 = v1[v + stride];
-            const uint64_t i0 = base + 4 * v, i1 = base + 4 * (v + stride);
-            one_pair(x0.x, y0.x, i0, lc, hist); one_pair(x0.y, y0.y, i0 + 1, lc, hist);
-            one_pair(x0.z, y0.z, i0 + 2, lc, hist); one_pair(x0.w, y0.w, i0 + 3, lc, hist);
-            one_pair(x1.x, y1.x, i1, lc, hist); one_pair(x1.y, y1.y, i1 + 1, lc, hist);
-            one_pair(x1.z, y1.z, i1 + 2, lc, hist); one_pair(x1.w, y1.w, i1 + 3, lc, hist);
-            handled += 8;
+            one_vector<W>(x0, y0, base + EPV * v, lc, hist);
+            one_vector<W>(x1, y1, base + EPV * (v + stride), lc, hist);
         }
-        for (; v < nvec; v += stride) {
-            const uint4 x = v0[v], y = v1[v];
-            const uint64_t i0 = base + 4 * v;
-            one_pair(x.x, y.x, i0, lc, hist);
-            one_pair(x.y, y.y, i0 + 1, lc, hist);
-            one_pair(x.z, y.z, i0 + 2, lc, hist);
-            one_pair(x.w, y.w, i0 + 3, lc, hist);
-            handled += 4;
-        }
-        for (uint64_t i = 4 * nvec + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-            one_pair(d0[i], d1[i], base + i, lc, hist);
-            handled += 1;
-        }
+        for (; v < nvec; v += stride) one_vector<W>(v0[v], v1[v], base + EPV * v, lc, hist);
+        for (uint64_t i = EPV * nvec + (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
+            one_pair<W>(d0[i], d1[i], base + i, lc, hist);
     } else {
-        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) {
-            one_pair(d0[i], d1[i], base + i, lc, hist);
-            handled += 1;
-        }
+        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
+            one_pair<W>(d0[i], d1[i], base + i, lc, hist);
     }
-    if (handled) atomicAdd(&s_count, (unsigned long long)handled);
     if (lc.mism) {
         atomicAdd(&s_mism, lc.mism);
         atomicMin(&s_first, (unsigned long long)lc.first);
@@ -113,13 +116,11 @@ compare_kernel(const uint32_t *__restrict__ d0, const uint32_t *__restrict__ d1,
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        const unsigned long long mine = s_count;
         uint32_t nonzero = 0;
         for (int b = 1; b < 34; ++b) nonzero += tot[b];
         // n_compared and bucket 0 are known up front: workgroup 0 adds the whole count once,
         // every workgroup takes its non-zero buckets back out of bucket 0 (sums are modular,
         // so the order does not matter); equal inputs then cost no further atomics at all
-        (void)mine;
         if (blockIdx.x == 0) {
             atomicAdd(&g[0], (unsigned long long)count);
             atomicAdd(&g[5 + 0], (unsigned long long)count);
@@ -141,16 +142,22 @@ mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s)
     return MMAEMU_OK;
 }
 
-mmaemu_status launch_compare(const uint32_t *d0, const uint32_t *d1, uint64_t count, uint64_t base,
+mmaemu_status launch_compare(const void *d0, const void *d1, uint64_t count, uint64_t base, bool half,
                              mmaemu_stats *st, hipStream_t s)
 {
     // Few, fat workgroups: every workgroup ends with up to ~40 global atomics on the same
-    // few addresses, and those serialise across the chip, so a workgroup should cover at
-    // least 32K pairs (128 per thread) before it pays for them.
-    uint64_t blocks = (count + 32767) / 32768;
+    // few addresses, and those serialise across the chip (measured: ~40-80 ns per workgroup), so a
+    // workgroup covers at least 16K pairs before it pays for them; 1024 threads each, so that a
+    // workgroup has 16 waves' worth of loads in flight (a small comparison is latency-bound).
+    uint64_t blocks = (count + 16383) / 16384;
     if (blocks < 1) blocks = 1;
-    if (blocks > 512) blocks = 512;                 // measured: ~40-80 ns of serialised atomics per workgroup
-    hipLaunchKernelGGL(compare_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, d0, d1, count, base, st);
+    if (blocks > 512) blocks = 512;
+    if (half)
+        hipLaunchKernelGGL((compare_kernel<16, uint16_t>), dim3((uint32_t)blocks), dim3(1024), 0, s, (const uint16_t *)d0,
+                           (const uint16_t *)d1, count, base, st);
+    else
+        hipLaunchKernelGGL((compare_kernel<32, uint32_t>), dim3((uint32_t)blocks), dim3(1024), 0, s, (const uint32_t *)d0,
+                           (const uint32_t *)d1, count, base, st);
     MMAEMU_HIP(hipGetLastError());
     return MMAEMU_OK;
 }

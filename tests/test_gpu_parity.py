@@ -223,6 +223,29 @@ def test_compare_matches_oracle(mm):
     assert mm.read_stats(st) == ostats.empty_stats()
 
 
+def test_compare_fp16_outputs_matches_oracle(mm):
+    rng = np.random.default_rng(81)
+    for count, misalign in ((1, 0), (7, 0), (1000, 0), (100003, 0), (4099, 1), (4099, 3), (1 << 20, 0)):
+        x = synth.random_bits(rng, count + misalign, fm.FP16, finite=False)
+        y = x.copy()
+        flip = rng.random(count + misalign) < 0.3
+        y[flip] ^= (np.uint16(1) << rng.integers(0, 16, size=int(flip.sum())).astype(np.uint16))
+        y[rng.random(count + misalign) < 0.01] = 0x7E01
+        x[rng.random(count + misalign) < 0.01] = 0x7E00
+        dx, dy = to_dev(x), to_dev(y)
+        st = dev_empty(mm.STATS_BYTES)
+        mm.stats_reset(st)
+        mm.compare(dx[misalign:], dy[misalign:], count, st, index_base=10, d=mm.FP16)
+        want = ostats.compare(x[misalign:], y[misalign:], index_base=10, width=16)
+        assert mm.read_stats(st) == want, (count, misalign)
+        mm.compare(dx[misalign:], dx[misalign:], count, st, index_base=10 + count, d=mm.FP16)
+        want = ostats.compare(x[misalign:], x[misalign:], stats=want, index_base=10 + count, width=16)
+        assert mm.read_stats(st) == want
+    with pytest.raises(mm.MmaemuError) as ei:
+        mm.compare(dx, dy, 4, st, d=mm.BF16)
+    assert ei.value.status == 2
+
+
 MFMA_TYPES = {0: (fm.FP16, fm.FP16), 1: (fm.BF16, fm.BF16), 2: (fm.FP16, fm.FP16), 3: (fm.BF16, fm.BF16),
               4: (fm.FP16, fm.FP16), 5: (fm.BF16, fm.BF16), 6: (fm.E4M3, fm.E4M3), 7: (fm.E4M3, fm.E5M2),
               8: (fm.E5M2, fm.E4M3), 9: (fm.E5M2, fm.E5M2),

@@ -253,3 +253,23 @@ def test_fp6_fp4_generation():
         tie = np.isclose(np.abs(np.abs(got) - want_mag), np.abs(nearest - want_mag))
         assert np.all((np.abs(got) == nearest) | tie)
         assert np.all((np.sign(got) == np.sign(zs)) | (got == 0))
+
+
+def test_compare_stats_fp16_patterns():
+    # the same definition on binary16 patterns (outputs of the models with FP16 accumulators): hand-counted
+    one = 0x3C00
+    d0 = np.array([one, one, one, 0x0000, 0x7E00, 0x7E00, one, 0x0001, 0x7BFF, 0x7C00], dtype=np.uint16)
+    d1 = np.array([one, one + 1, one + 5, 0x8000, 0x7E01, one, 0x7FFF, 0x8001, 0xFBFF, 0x7BFF], dtype=np.uint16)
+    st = stats.compare(d0, d1, index_base=7, width=16)
+    assert st["n_compared"] == 10 and st["n_mismatch_bits"] == 9 and st["n_mismatch_nan_equiv"] == 1
+    assert st["first_mismatch_index"] == 8
+    h = st["ulp_hist"]
+    assert h[0] == 3 and h[1] == 2 and h[2] == 1 and h[3] == 1 and h[33] == 2      # (inf vs largest finite: distance 1)
+    assert h[16] == 1 and st["max_ulp_dist"] == 2 * 0x7BFF and sum(h) == 10
+    # neighbours in binary16 are at distance 1, across zero too
+    x = np.array([1.0, -1.0, 6e-8, 0.0, -6e-8, 65504.0], dtype=np.float16)
+    up = np.nextafter(x, np.float16(np.inf))
+    d = np.abs(stats.ordered_key(x.view(np.uint16), 16) - stats.ordered_key(up.view(np.uint16), 16))
+    assert (d == 1).all()
+    # a 16-bit pattern is never taken for a binary32 one: 0x7E00 is a NaN at width 16 and a small number at width 32
+    assert stats.is_nan(np.array([0x7E00]), 16)[0] and not stats.is_nan(np.array([0x7E00]), 32)[0]
