@@ -38,7 +38,7 @@ emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A
         }
         for (uint32_t k0 = 0; k0 < k; k0 += p.L) {
             sr.k0 = k0;
-            d = fdpa_group<TA, TB>(p, a + k0, b + k0, p.L, d, sr);
+            d = fdpa_group(p, StaticFmt<TA>{}, StaticFmt<TB>{}, a + k0, b + k0, p.L, d, sr);
         }
         if (acc16) reinterpret_cast<uint16_t *>(D)[o] = (uint16_t)((d & 0x7FFFFFFFu) > 0x7F800000u ? p.nan16 : float_bits_to_half_bits(d));
         else D[o] = d;

@@ -15,26 +15,67 @@ struct Dec {
     int cls;
 };
 
-template <int T>
-__device__ __forceinline__ Dec decode(uint32_t bits, uint32_t ftz_in)
+// An operand format as this routine sees it.  StaticFmt<T>: every property a compile-time constant (the general kernel:
+// one instantiation per type pair).  DynFmt: the properties are run-time values (the tiled kernels' rare fall-back: one
+// instantiation for every type pair, an order of magnitude less code).
+template <int T> struct StaticFmt {
+    __device__ __forceinline__ constexpr int eb() const { return Fmt<T>::EB; }
+    __device__ __forceinline__ constexpr int mb() const { return Fmt<T>::MB; }
+    __device__ __forceinline__ constexpr int bias() const { return Fmt<T>::BIAS; }
+    __device__ __forceinline__ constexpr bool ieee() const { return Fmt<T>::IEEE; }
+    __device__ __forceinline__ constexpr bool nospec() const { return Fmt<T>::NOSPEC; }
+    __device__ __forceinline__ constexpr int shift() const { return T == MMAEMU_TF32 ? 13 : 0; }   // surplus low bits of the word
+    __device__ __forceinline__ uint32_t load(const void *p, uint32_t k) const { return static_cast<const typename Fmt<T>::elem *>(p)[k]; }
+};
+struct DynFmt {
+    int eb_, mb_, bias_, width_;
+    bool ieee_, nospec_;
+    __device__ __forceinline__ int eb() const { return eb_; }
+    __device__ __forceinline__ int mb() const { return mb_; }
+    __device__ __forceinline__ int bias() const { return bias_; }
+    __device__ __forceinline__ bool ieee() const { return ieee_; }
+    __device__ __forceinline__ bool nospec() const { return nospec_; }
+    __device__ __forceinline__ constexpr int shift() const { return 0; }                            // (TF32 never comes this way)
+    __device__ __forceinline__ uint32_t load(const void *p, uint32_t k) const
+    {
+        return width_ == 8 ? static_cast<const uint8_t *>(p)[k] : (width_ == 16 ? static_cast<const uint16_t *>(p)[k] : static_cast<const uint32_t *>(p)[k]);
+    }
+};
+__device__ __forceinline__ DynFmt dyn_fmt(uint32_t t)
 {
-    using F = Fmt<T>;
-    constexpr uint32_t EMASK = (1u << F::EB) - 1u, MMASK = (1u << F::MB) - 1u;
-    if (T == MMAEMU_TF32) bits >>= 13;                  // the low 13 mantissa bits of the binary32 word do not count
-    const uint32_t E = (bits >> F::MB) & EMASK, M = bits & MMASK;
+    switch (t) {
+    case MMAEMU_FP8_E4M3: return DynFmt{4, 3, 7, 8, false, false};
+    case MMAEMU_FP8_E5M2: return DynFmt{5, 2, 15, 8, true, false};
+    case MMAEMU_FP16: return DynFmt{5, 10, 15, 16, true, false};
+    case MMAEMU_FP6_E2M3: return DynFmt{2, 3, 1, 8, false, true};
+    case MMAEMU_FP6_E3M2: return DynFmt{3, 2, 3, 8, false, true};
+    case MMAEMU_FP4_E2M1: return DynFmt{2, 1, 1, 8, false, true};
+    default: return DynFmt{8, 7, 127, 16, true, false};                                             // BF16
+    }
+}
+
+template <class FT>
+__device__ __forceinline__ Dec decode_as(const FT &f, uint32_t bits, uint32_t ftz_in)
+{
+    const uint32_t EMASK = (1u << f.eb()) - 1u, MMASK = (1u << f.mb()) - 1u;
+    bits >>= f.shift();
+    const uint32_t E = (bits >> f.mb()) & EMASK, M = bits & MMASK;
     Dec d;
-    d.sign = (bits >> (F::EB + F::MB)) & 1u;
-    d.exp = (E ? (int)E : 1) - F::BIAS;
-    d.sig = E ? (M | (1u << F::MB)) : M;
+    d.sign = (bits >> (f.eb() + f.mb())) & 1u;
+    d.exp = (E ? (int)E : 1) - f.bias();
+    d.sig = E ? (M | (1u << f.mb())) : M;
     d.cls = E ? CLS_NORMAL : (M ? CLS_SUB : CLS_ZERO);
-    if (F::IEEE) {
+    if (f.ieee()) {
         if (E == EMASK) d.cls = M ? CLS_NAN : CLS_INF;
-    } else if (!F::NOSPEC) {
-        if (E == EMASK && M == MMASK) d.cls = CLS_NAN;
+    } else if (!f.nospec()) {
+        if (E == EMASK && M == MMASK) d.cls = CLS_NAN;                             // the E4M3 rule: one NaN code
     }
     if (ftz_in && d.cls == CLS_SUB) { d.cls = CLS_ZERO; d.sig = 0; d.sign = 0; }   // FlushSubnormal: -> +0.0
     return d;
 }
+
+template <int T>
+__device__ __forceinline__ Dec decode(uint32_t bits, uint32_t ftz_in) { return decode_as(StaticFmt<T>{}, bits, ftz_in); }
 
 typedef __int128 i128;
 typedef unsigned __int128 u128;
@@ -83,16 +124,16 @@ __device__ __forceinline__ int scale_exp(const ScaleRef &sr, uint32_t k)
 // One sub-group of products k = first, first + stride, ... (count of them): maximum exponent
 // over the terms that take part, then the sum of the terms aligned at that exponent with F
 // fractional bits, truncated toward zero.  Returns false when no term takes part.
-template <int TA, int TB>
-__device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, const typename Fmt<TB>::elem *b, const ScaleRef &sr,
+template <class FTA, class FTB>
+__device__ bool fused_part(const ModelArgs &p, const FTA &fa, const FTB &fb, const void *a, const void *b, const ScaleRef &sr,
                            uint32_t first, uint32_t stride, uint32_t count, int &emax, int64_t &T)
 {
-    constexpr int FA = Fmt<TA>::MB, FB = Fmt<TB>::MB;
+    const int FA = fa.mb(), FB = fb.mb();
     bool any = false;
     emax = 0;
     for (uint32_t q = 0; q < count; ++q) {
         const uint32_t k = first + q * stride;
-        const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
+        const Dec x = decode_as(fa, fa.load(a, k), p.ftz_in), y = decode_as(fb, fb.load(b, k), p.ftz_in);
         if (p.skip_zero_terms && (x.sig == 0 || y.sig == 0)) continue;
         const int e = x.exp + y.exp + scale_exp(sr, k);
         emax = (!any || e > emax) ? e : emax;
@@ -103,7 +144,7 @@ __device__ bool fused_part(const ModelArgs &p, const typename Fmt<TA>::elem *a, 
     const int unit = emax - p.F;
     for (uint32_t q = 0; q < count; ++q) {
         const uint32_t k = first + q * stride;
-        const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
+        const Dec x = decode_as(fa, fa.load(a, k), p.ftz_in), y = decode_as(fb, fb.load(b, k), p.ftz_in);
         const uint64_t prod = (uint64_t)(x.sig * y.sig);                    // <= 22 bits
         const int sh = (x.exp + y.exp + scale_exp(sr, k) - FA - FB) - unit; // <= F
         const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
@@ -180,11 +221,11 @@ __device__ __forceinline__ uint32_t finish_group(const ModelArgs &p, uint32_t d)
     return d;
 }
 
-template <int TA, int TB>
-__device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem *a,
-                               const typename Fmt<TB>::elem *b, uint32_t L, uint32_t c, const ScaleRef &sr)
+template <class FTA, class FTB>
+__device__ uint32_t fdpa_group(const ModelArgs &p, const FTA &fa, const FTB &fb, const void *a, const void *b, uint32_t L,
+                               uint32_t c, const ScaleRef &sr)
 {
-    constexpr int FA = Fmt<TA>::MB, FB = Fmt<TB>::MB;
+    const int FA = fa.mb(), FB = fb.mb();
     const Dec dc = decode_acc(p, c);
     const bool acc16 = (p.flags & FL_ACC16) != 0;
     if (sr.sa) {                                                              // a NaN scale factor (E8M0 pattern 0xFF)
@@ -195,7 +236,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
     // special values (Sec. 4.2)
     bool any_nan = dc.cls == CLS_NAN, pinf = false, ninf = false;
     for (uint32_t k = 0; k < L; ++k) {
-        const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
+        const Dec x = decode_as(fa, fa.load(a, k), p.ftz_in), y = decode_as(fb, fb.load(b, k), p.ftz_in);
         if (x.cls == CLS_NAN || y.cls == CLS_NAN) any_nan = true;
         else if (x.cls == CLS_INF || y.cls == CLS_INF) {
             if (x.cls == CLS_ZERO || y.cls == CLS_ZERO) any_nan = true;      // inf * 0
@@ -216,7 +257,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
     if (p.c_mode == MMAEMU_C_AFTER_RD) {
         if (p.split == MMAEMU_SPLIT_NONE) {
             int emax; int64_t T;
-            const bool have = fused_part<TA, TB>(p, a, b, sr, 0, 1, L, emax, T);
+            const bool have = fused_part(p, fa, fb, a, b, sr, 0, 1, L, emax, T);
             return finish_group(p, rounded_sum_with_c(p, have, T, emax, emax - p.F, dc));
         }
         // two or four sub-groups, each fused at its own maximum exponent, merged with RD at F_m bits
@@ -225,7 +266,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
         int ep[4] = {0, 0, 0, 0}, emax = 0; int64_t Tp[4] = {0, 0, 0, 0}; bool hp[4] = {false, false, false, false}, any = false;
         for (int g = 0; g < np_; ++g) {
             const uint32_t first = p.split == MMAEMU_SPLIT_EVEN_ODD ? (uint32_t)g : (uint32_t)g * len;
-            hp[g] = fused_part<TA, TB>(p, a, b, sr, first, stride, len, ep[g], Tp[g]);
+            hp[g] = fused_part(p, fa, fb, a, b, sr, first, stride, len, ep[g], Tp[g]);
             if (hp[g] && (!any || ep[g] > emax)) emax = ep[g];
             any |= hp[g];
         }
@@ -236,7 +277,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
     }
 
     int emax; int64_t S;
-    bool have = fused_part<TA, TB>(p, a, b, sr, 0, 1, L, emax, S);          // S aligned at the products' own maximum
+    bool have = fused_part(p, fa, fb, a, b, sr, 0, 1, L, emax, S);          // S aligned at the products' own maximum
     uint32_t d;
     if (p.c_mode == MMAEMU_C_IN_GROUP) {
         if (!have || dc.exp > emax) {
@@ -244,7 +285,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
             const int unit = dc.exp - p.F;
             S = 0;
             for (uint32_t k = 0; k < L; ++k) {
-                const Dec x = decode<TA>(a[k], p.ftz_in), y = decode<TB>(b[k], p.ftz_in);
+                const Dec x = decode_as(fa, fa.load(a, k), p.ftz_in), y = decode_as(fb, fb.load(b, k), p.ftz_in);
                 const uint64_t prod = (uint64_t)(x.sig * y.sig);
                 const int sh = (x.exp + y.exp + scale_exp(sr, k) - FA - FB) - unit;
                 const uint64_t al = sh >= 0 ? (prod << sh) : (sh > -32 ? (prod >> (-sh)) : 0ull);
@@ -268,59 +309,19 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const typename Fmt<TA>::elem 
 }
 
 
-// run-time operand types (used where a template per type pair is not worth its code size)
+// run-time operand types: the tiled kernels' fall-back (a template per type pair there multiplied the code size)
 // (parameters by value: a reference would force the caller to keep a copy of them in scratch memory)
 __device__ __noinline__ uint32_t fdpa_group_raw(ModelArgs p, uint32_t ta, uint32_t tb, const void *a, const void *b,
                                                 uint32_t L, uint32_t c, ScaleRef sr)
 {
-#define MMAEMU_CASE(X, Y)                                                                             \
-    if (ta == X && tb == Y)                                                                           \
-        return fdpa_group<X, Y>(p, reinterpret_cast<const typename Fmt<X>::elem *>(a),                \
-                                reinterpret_cast<const typename Fmt<Y>::elem *>(b), L, c, sr)
-    MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP16);     MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_BF16);
-    MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP16);     MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_BF16);
-    MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP16);         MMAEMU_CASE(MMAEMU_FP16, MMAEMU_BF16);
-    MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP16);
-#define MMAEMU_NARROW_ROW(X) MMAEMU_CASE(X, MMAEMU_FP8_E4M3); MMAEMU_CASE(X, MMAEMU_FP8_E5M2); MMAEMU_CASE(X, MMAEMU_FP6_E2M3); MMAEMU_CASE(X, MMAEMU_FP6_E3M2); MMAEMU_CASE(X, MMAEMU_FP4_E2M1)
-#define MMAEMU_NARROW_COL(Y) MMAEMU_CASE(MMAEMU_FP8_E4M3, Y); MMAEMU_CASE(MMAEMU_FP8_E5M2, Y)
-    MMAEMU_NARROW_ROW(MMAEMU_FP6_E2M3); MMAEMU_NARROW_ROW(MMAEMU_FP6_E3M2); MMAEMU_NARROW_ROW(MMAEMU_FP4_E2M1);
-    MMAEMU_NARROW_COL(MMAEMU_FP6_E2M3); MMAEMU_NARROW_COL(MMAEMU_FP6_E3M2); MMAEMU_NARROW_COL(MMAEMU_FP4_E2M1);
-#undef MMAEMU_NARROW_ROW
-#undef MMAEMU_NARROW_COL
-#undef MMAEMU_CASE
-    return fdpa_group<MMAEMU_BF16, MMAEMU_BF16>(p, reinterpret_cast<const uint16_t *>(a),
-                                                reinterpret_cast<const uint16_t *>(b), L, c, sr);
+    return fdpa_group(p, dyn_fmt(ta), dyn_fmt(tb), a, b, L, c, sr);
 }
 
 // the same without block scales
 __device__ __noinline__ uint32_t fdpa_group_raw_unscaled(ModelArgs p, uint32_t ta, uint32_t tb, const void *a, const void *b,
-                                                uint32_t L, uint32_t c)
+                                                         uint32_t L, uint32_t c)
 {
-#define MMAEMU_CASE(X, Y)                                                                             \
-    if (ta == X && tb == Y)                                                                           \
-        return fdpa_group<X, Y>(p, reinterpret_cast<const typename Fmt<X>::elem *>(a),                \
-                                reinterpret_cast<const typename Fmt<Y>::elem *>(b), L, c, no_scales())
-    MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_FP16);     MMAEMU_CASE(MMAEMU_FP8_E4M3, MMAEMU_BF16);
-    MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3); MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_FP16);     MMAEMU_CASE(MMAEMU_FP8_E5M2, MMAEMU_BF16);
-    MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_FP16, MMAEMU_FP16);         MMAEMU_CASE(MMAEMU_FP16, MMAEMU_BF16);
-    MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E4M3);     MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP8_E5M2);
-    MMAEMU_CASE(MMAEMU_BF16, MMAEMU_FP16);
-#define MMAEMU_NARROW_ROW(X) MMAEMU_CASE(X, MMAEMU_FP8_E4M3); MMAEMU_CASE(X, MMAEMU_FP8_E5M2); MMAEMU_CASE(X, MMAEMU_FP6_E2M3); MMAEMU_CASE(X, MMAEMU_FP6_E3M2); MMAEMU_CASE(X, MMAEMU_FP4_E2M1)
-#define MMAEMU_NARROW_COL(Y) MMAEMU_CASE(MMAEMU_FP8_E4M3, Y); MMAEMU_CASE(MMAEMU_FP8_E5M2, Y)
-    MMAEMU_NARROW_ROW(MMAEMU_FP6_E2M3); MMAEMU_NARROW_ROW(MMAEMU_FP6_E3M2); MMAEMU_NARROW_ROW(MMAEMU_FP4_E2M1);
-    MMAEMU_NARROW_COL(MMAEMU_FP6_E2M3); MMAEMU_NARROW_COL(MMAEMU_FP6_E3M2); MMAEMU_NARROW_COL(MMAEMU_FP4_E2M1);
-#undef MMAEMU_NARROW_ROW
-#undef MMAEMU_NARROW_COL
-#undef MMAEMU_CASE
-    return fdpa_group<MMAEMU_BF16, MMAEMU_BF16>(p, reinterpret_cast<const uint16_t *>(a),
-                                                reinterpret_cast<const uint16_t *>(b), L, c, no_scales());
+    return fdpa_group(p, dyn_fmt(ta), dyn_fmt(tb), a, b, L, c, no_scales());
 }
 
 } // namespace mmaemu
