@@ -142,8 +142,8 @@ static uint32_t add_exact_round(int sx, u128 mx, int lx, int sy, u128 my, int ly
     }
     int d = lx - ly;
     if (bitlen128(my) + 26 > d) {
-        /* the terms overlap or nearly do: both magnitudes have at most 40 bits (checked
-         * by the caller), so d < 66 and the exact sum fits 128 bits */
+        /* the terms overlap or nearly do: both magnitudes have at most 50 bits (checked
+         * by the caller), so d < 76 and the exact sum fits 127 bits */
         i128 v = (i128)(mx << d) * (sx ? -1 : 1) + (i128)my * (sy ? -1 : 1);
         if (v == 0) return 0u;
         int neg = v < 0;
@@ -409,7 +409,7 @@ static uint32_t addmul_element(const o2_params *p, const void *A, const void *B,
 
 static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out)
 {
-    if (ta < 0 || tb < 0 || ta > T_TF32 || tb > T_TF32 || ta == T_FP32 || tb == T_FP32 || ta == T_E8M0 || tb == T_E8M0) return -2;
+    if (ta < 0 || tb < 0 || ta > T_TF32 || tb > T_TF32 || ta == T_E8M0 || tb == T_E8M0) return -2;
     if (p->family == 1) {
         if (p->acc_fp16) return -2;
         if (p->group_len != 2 && p->group_len != 4) return -2;
@@ -424,9 +424,9 @@ static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out
     if (k == 0 || k > (1u << 20)) return -3;
     uint32_t L = (p->group_len == 0 || p->group_len > k) ? k : p->group_len;
     if (k % L) return -3;
-    if (p->c_mode == C_AFTER_EXACT) {   /* add_exact_round() needs magnitudes of at most 40 bits */
+    if (p->c_mode == C_AFTER_EXACT) {   /* add_exact_round() needs magnitudes of at most 50 bits */
         int lg = 0; while ((1u << lg) < L) ++lg;
-        if ((int)p->frac_bits + 2 + lg > 40) return -2;
+        if ((int)p->frac_bits + 2 + lg > 50) return -2;
     }
     if (p->c_mode >= C_AFTER_RD) {      /* keep every intermediate of the RD steps below 2^126 */
         int lg = 0; while ((1u << lg) < L) ++lg;
