@@ -67,8 +67,9 @@ typedef enum {
 } mmaemu_dtype;
 
 typedef struct {
-    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1, TF32} (the FP6 / FP4
-                            types pair with each other and with the FP8 types, TF32 with itself); c = d = FP32, or c = d = FP16
+    uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16, FP32, E2M3, E3M2, E2M1, TF32} (the FP6 /
+                            FP4 types pair with each other and with the FP8 types, TF32 and FP32 each with itself; TF32
+                            and FP32 operands and frac_bits above 40 run in the general kernel); c = d = FP32, or c = d = FP16
                             (Algorithm "T-FDPA" with F_C = FP16: the accumulator is decoded as binary16, Exp >= -14,
                             rho is RNE-FP16 of Table "Conversion functions" (RZ likewise), both flushes use 2^-14, the
                             NaN pattern is the low half of nan_bits; c_mode C_IN_GROUP or C_AFTER_EXACT only) */
@@ -336,7 +337,10 @@ typedef enum {
     MMAEMU_MFMA_F32_32X32X16_FP8_BF8 = 38,
     MMAEMU_MFMA_F32_32X32X16_BF8_FP8 = 39,
     MMAEMU_MFMA_F32_32X32X16_BF8_BF8 = 40,
-    MMAEMU_MFMA_COUNT = 41
+    /* FP32 operands (the paper's FP32 instructions are chains of FMAs, Sec. 4.1.2) */
+    MMAEMU_MFMA_F32_16X16X4_F32 = 41,
+    MMAEMU_MFMA_F32_32X32X2_F32 = 42,
+    MMAEMU_MFMA_COUNT = 43
 } mmaemu_mfma_instr;
 
 /* Shape and operand types of an instruction (host-side query). */

@@ -39,7 +39,8 @@ MFMA_SCALE_FP8_IDS = (10, 11, 15, 16)
 MFMA_SCALE_IDS = tuple(range(10, 35))
 (MFMA_F32_32X32X16_F16, MFMA_F32_32X32X16_BF16, MFMA_F32_32X32X16_FP8_FP8, MFMA_F32_32X32X16_FP8_BF8,
  MFMA_F32_32X32X16_BF8_FP8, MFMA_F32_32X32X16_BF8_BF8) = range(35, 41)
-MFMA_UNSCALED_IDS = tuple(range(10)) + tuple(range(35, 41))
+MFMA_F32_16X16X4_F32, MFMA_F32_32X32X2_F32 = 41, 42
+MFMA_UNSCALED_IDS = tuple(range(10)) + tuple(range(35, 43))
 ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1, TF32: 4}
 NO_MISMATCH = (1 << 64) - 1
 

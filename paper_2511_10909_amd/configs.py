@@ -239,8 +239,8 @@ def validation_families(ta, tb):
     """Input families of Step 4: common distributions, all finite bit patterns, all bit patterns (NaN and infinities
     included: the paper calls this one the most important), and exponent ranges chosen to put the accumulator above,
     below and anywhere relative to the products.  Each entry: (name, generator arguments for A, for B, for C)."""
-    full = {mm.FP16: (1, 30), mm.BF16: (1, 254), mm.E4M3: (0, 15), mm.E5M2: (0, 30), mm.E2M3: (0, 3), mm.E3M2: (0, 7), mm.E2M1: (0, 3)}
-    mid = {mm.FP16: (11, 19), mm.BF16: (120, 134), mm.E4M3: (3, 11), mm.E5M2: (11, 19), mm.E2M3: (1, 2), mm.E3M2: (2, 5), mm.E2M1: (1, 2)}
+    full = {mm.FP32: (1, 254), mm.FP16: (1, 30), mm.BF16: (1, 254), mm.E4M3: (0, 15), mm.E5M2: (0, 30), mm.E2M3: (0, 3), mm.E3M2: (0, 7), mm.E2M1: (0, 3)}
+    mid = {mm.FP32: (120, 134), mm.FP16: (11, 19), mm.BF16: (120, 134), mm.E4M3: (3, 11), mm.E5M2: (11, 19), mm.E2M3: (1, 2), mm.E3M2: (2, 5), mm.E2M1: (1, 2)}
 
     def ue(rng, zero=True):
         return dict(family=mm.GEN_UNIFORM_EXP, exp_lo=rng[0], exp_hi=rng[1], exp_zero=zero)
@@ -250,18 +250,19 @@ def validation_families(ta, tb):
     fams = [(name, dict(family=f), dict(family=f), dict(family=f)) for name, f in simple]
     # adversarial sums: products cancelling pairwise up to last-place perturbations, accumulator near the residue
     canc = dict(family=mm.GEN_CANCELLING, exp_zero=False)
-    fams.append(("cancelling", dict(canc, exp_lo=mid[ta][0], exp_hi=mid[ta][1]), dict(canc, exp_lo=mid[tb][0], exp_hi=mid[tb][1]),
-                 ue((100, 135))))
+    if ta != mm.FP32:       # (the generator does not build cancelling pairs of FP32 values)
+        fams.append(("cancelling", dict(canc, exp_lo=mid[ta][0], exp_hi=mid[ta][1]), dict(canc, exp_lo=mid[tb][0], exp_hi=mid[tb][1]),
+                     ue((100, 135))))
     fams.append(("mid_exp_c_above", ue(mid[ta]), ue(mid[tb]), ue((125, 145), zero=False)))
     fams.append(("mid_exp_c_below", ue(mid[ta]), ue(mid[tb]), ue((80, 129))))
     fams.append(("wide_exp_c_any", ue(full[ta]), ue(full[tb]), ue((1, 254))))
     # every product at one exponent, the accumulator 20 to 32 binary places above it (where whole sums drop out)
-    bias = {mm.FP16: 15, mm.BF16: 127, mm.E4M3: 7, mm.E5M2: 15, mm.E2M3: 1, mm.E3M2: 3, mm.E2M1: 1}
-    one = {mm.FP16: 16, mm.BF16: 128, mm.E4M3: 8, mm.E5M2: 16, mm.E2M3: 2, mm.E3M2: 4, mm.E2M1: 2}
+    bias = {mm.FP32: 127, mm.FP16: 15, mm.BF16: 127, mm.E4M3: 7, mm.E5M2: 15, mm.E2M3: 1, mm.E3M2: 3, mm.E2M1: 1}
+    one = {mm.FP32: 128, mm.FP16: 16, mm.BF16: 128, mm.E4M3: 8, mm.E5M2: 16, mm.E2M3: 2, mm.E3M2: 4, mm.E2M1: 2}
     e_prod = (one[ta] - bias[ta]) + (one[tb] - bias[tb])
     fams.append(("one_exp_c_far_above", ue((one[ta], one[ta]), zero=False), ue((one[tb], one[tb]), zero=False),
                  ue((127 + e_prod + 20, 127 + e_prod + 32), zero=False)))
-    if ta == mm.BF16 and tb == mm.BF16:
+    if ta == tb and ta in (mm.BF16, mm.FP32):
         # products around the bottom of binary32's subnormal range, with a zero and with a subnormal accumulator
         tiny = ue((46, 52))
         fams.append(("tiny_products_c_zero", tiny, tiny, dict(family=mm.GEN_ZERO)))

@@ -41,7 +41,8 @@ mmaemu_status hip_fail(hipError_t e, const char *what)
     return MMAEMU_ERR_HIP;
 }
 
-static bool is_ab_type(uint32_t t) { return t <= MMAEMU_BF16 || is_narrow_type(t) || t == MMAEMU_TF32; }
+static bool is_ab_type(uint32_t t) { return t <= MMAEMU_FP32 || is_narrow_type(t) || t == MMAEMU_TF32; }
+static bool is_word_type(uint32_t t) { return t == MMAEMU_TF32 || t == MMAEMU_FP32; }      // operands held in 32-bit words
 
 static uint32_t ceil_log2(uint32_t x)
 {
@@ -147,7 +148,10 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: frac_bits_merge needs a split");
         return MMAEMU_ERR_UNSUPPORTED;
     }
-    if (p->frac_bits > 40) { set_error("model_create: frac_bits %u > 40", p->frac_bits); return MMAEMU_ERR_UNSUPPORTED; }
+    if (p->frac_bits > (rd_mode ? 40u : 48u)) {
+        set_error("model_create: frac_bits %u > %u", p->frac_bits, rd_mode ? 40u : 48u);
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
     if (p->group_len > (1u << 20)) { set_error("model_create: group_len %u > 2^20", p->group_len); return MMAEMU_ERR_UNSUPPORTED; }
     mmaemu_model *m = new (std::nothrow) mmaemu_model;
     if (!m) { set_error("model_create: allocation failed"); return MMAEMU_ERR_NOMEM; }
@@ -187,11 +191,11 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     }
     const bool acc16 = dt.c == MMAEMU_FP16 && dt.d == MMAEMU_FP16;
     if (!is_ab_type(dt.a) || !is_ab_type(dt.b) || !((dt.c == MMAEMU_FP32 && dt.d == MMAEMU_FP32) || acc16)) {
-        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16, E2M3, E3M2, E2M1, TF32} and c = d = FP32 or c = d = FP16");
+        set_error("emulate_mma: supported types are a, b in {E4M3, E5M2, FP16, BF16, FP32, E2M3, E3M2, E2M1, TF32} and c = d = FP32 or c = d = FP16");
         return MMAEMU_ERR_UNSUPPORTED;
     }
-    if ((dt.a == MMAEMU_TF32) != (dt.b == MMAEMU_TF32)) {
-        set_error("emulate_mma: TF32 operands pair with TF32 operands only");
+    if ((is_word_type(dt.a) || is_word_type(dt.b)) && dt.a != dt.b) {
+        set_error("emulate_mma: TF32 operands pair with TF32 operands only, FP32 with FP32");
         return MMAEMU_ERR_UNSUPPORTED;
     }
     if ((is_narrow_type(dt.a) && !is_byte_type(dt.b)) || (is_narrow_type(dt.b) && !is_byte_type(dt.a))) {
@@ -220,7 +224,7 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         const GstArgs ga = {Lg, mp.gst_group, block, mp.frac_bits, mp.out_round, mp.scale_format, mp.nan_bits};
         return launch_emulate_gst(ga, A, B, C, D, SA, SB, m, n, k, batch, (hipStream_t)hip_stream);
     }
-    if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL && (is_narrow_type(dt.a) || is_narrow_type(dt.b) || dt.a == MMAEMU_TF32)) {
+    if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL && (is_narrow_type(dt.a) || is_narrow_type(dt.b) || is_word_type(dt.a))) {
         set_error("emulate_mma: the FTZ-AddMul family takes FP8, FP16 and BF16 operands");
         return MMAEMU_ERR_UNSUPPORTED;
     }
@@ -240,6 +244,10 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     }
     const uint32_t L = (mp.group_len == 0 || mp.group_len > k) ? k : mp.group_len;
     if (k % L) { set_error("emulate_mma: k=%u is not a multiple of the group length L=%u", k, L); return MMAEMU_ERR_SHAPE; }
+    if (mp.c_mode == MMAEMU_C_IN_GROUP && mp.frac_bits + 3 + ceil_log2(L) > 63) {      // the fused sum is a 64-bit integer
+        set_error("emulate_mma: C_IN_GROUP needs frac_bits + 3 + ceil(log2 L) <= 63");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
     if (mp.c_mode == MMAEMU_C_AFTER_EXACT && mp.frac_bits + 2 + ceil_log2(L) > 56) {
         set_error("emulate_mma: C_AFTER_EXACT needs frac_bits + 2 + ceil(log2 L) <= 56");
         return MMAEMU_ERR_UNSUPPORTED;
@@ -382,7 +390,16 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
 mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n, uint32_t *k_native, mmaemu_dtype *a,
                                mmaemu_dtype *b)
 {
-    if ((uint32_t)instr >= MMAEMU_MFMA_F32_32X32X16_F16 && (uint32_t)instr < MMAEMU_MFMA_COUNT) {
+    if ((uint32_t)instr == MMAEMU_MFMA_F32_16X16X4_F32 || (uint32_t)instr == MMAEMU_MFMA_F32_32X32X2_F32) {
+        const bool small = (uint32_t)instr == MMAEMU_MFMA_F32_16X16X4_F32;
+        if (m) *m = small ? 16 : 32;
+        if (n) *n = small ? 16 : 32;
+        if (k_native) *k_native = small ? 4 : 2;
+        if (a) *a = MMAEMU_FP32;
+        if (b) *b = MMAEMU_FP32;
+        return MMAEMU_OK;
+    }
+    if ((uint32_t)instr >= MMAEMU_MFMA_F32_32X32X16_F16 && (uint32_t)instr <= MMAEMU_MFMA_F32_32X32X16_BF8_BF8) {
         static const mmaemu_dtype T2[6][2] = {{MMAEMU_FP16, MMAEMU_FP16}, {MMAEMU_BF16, MMAEMU_BF16}, {MMAEMU_FP8_E4M3, MMAEMU_FP8_E4M3},
                                               {MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2}, {MMAEMU_FP8_E5M2, MMAEMU_FP8_E4M3}, {MMAEMU_FP8_E5M2, MMAEMU_FP8_E5M2}};
         const uint32_t q = (uint32_t)instr - MMAEMU_MFMA_F32_32X32X16_F16;

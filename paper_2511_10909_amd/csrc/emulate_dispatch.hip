@@ -36,7 +36,8 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // exponent) and the values stay binary32 (FP8 / FP16 operands, F below 30)
     const bool scaled = SA != nullptr;
     const bool scaled_ok = !scaled || (block % p.L == 0 && ta != MMAEMU_BF16 && tb != MMAEMU_BF16 && p.F < 30);
-    const bool tiled_types = ta != MMAEMU_TF32;     // TF32 operands (binary32 words) run in the general kernel only
+    // TF32 and FP32 operands (binary32 words) run in the general kernel only, and so does F above 40
+    const bool tiled_types = ta != MMAEMU_TF32 && ta != MMAEMU_FP32 && p.F <= 40;
     if (tiled_mode && tiled_types && scaled_ok && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;

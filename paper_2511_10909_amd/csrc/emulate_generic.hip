@@ -74,7 +74,7 @@ mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const vo
     CASE(MMAEMU_FP16, MMAEMU_FP16);         CASE(MMAEMU_FP16, MMAEMU_BF16);
     CASE(MMAEMU_BF16, MMAEMU_FP8_E4M3);     CASE(MMAEMU_BF16, MMAEMU_FP8_E5M2);
     CASE(MMAEMU_BF16, MMAEMU_FP16);         CASE(MMAEMU_BF16, MMAEMU_BF16);
-    CASE(MMAEMU_TF32, MMAEMU_TF32);
+    CASE(MMAEMU_TF32, MMAEMU_TF32);         CASE(MMAEMU_FP32, MMAEMU_FP32);
     // FP6 / FP4 with each other and with FP8
 #define NARROW_ROW(X) CASE(X, MMAEMU_FP8_E4M3); CASE(X, MMAEMU_FP8_E5M2); CASE(X, MMAEMU_FP6_E2M3); CASE(X, MMAEMU_FP6_E3M2); CASE(X, MMAEMU_FP4_E2M1)
 #define NARROW_COL(Y) CASE(MMAEMU_FP8_E4M3, Y); CASE(MMAEMU_FP8_E5M2, Y)

@@ -4,6 +4,7 @@
 // of the emulation entry point straight into the instruction's register layout.
 //
 // Register layouts (wave64), l = lane:
+//   (the FP32 instructions 16x16x4 and 32x32x2 hold one element per lane: K/4 = 1, K/2 = 1)
 //   16x16xK : A row  i = l % 16, k = (K/4) * (l / 16) + 0 .. K/4-1   (same for B with column j)
 //             C/D column j = l % 16, rows i = 4 * (l / 16) + r, r = 0..3
 //   32x32xK : A row  i = l % 32, k = (K/2) * (l / 32) + 0 .. K/2-1   (same for B with column j)
@@ -41,6 +42,8 @@ DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_FP8_FP8, 32, 32, 16, 1);
 DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_FP8_BF8, 32, 32, 16, 1);
 DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_BF8_FP8, 32, 32, 16, 1);
 DEF_INSTR(MMAEMU_MFMA_F32_32X32X16_BF8_BF8, 32, 32, 16, 1);
+DEF_INSTR(MMAEMU_MFMA_F32_16X16X4_F32, 16, 16, 4, 4);
+DEF_INSTR(MMAEMU_MFMA_F32_32X32X2_F32, 32, 32, 2, 4);
 #undef DEF_INSTR
 
 // gather this lane's K/4 (16-wide) or 4 (32-wide) consecutive k elements of one row,
@@ -53,7 +56,7 @@ __device__ __forceinline__ void load_row_slice(const uint8_t *row, uint32_t k0, 
     for (int q = 0; q < NELEM; ++q) {
         const uint32_t kk = k0 + q;
         uint32_t v = 0;
-        if (kk < k) v = (EB == 1) ? row[kk] : reinterpret_cast<const uint16_t *>(row)[kk];
+        if (kk < k) v = (EB == 1) ? row[kk] : (EB == 2 ? reinterpret_cast<const uint16_t *>(row)[kk] : reinterpret_cast<const uint32_t *>(row)[kk]);
         const int bit = q * EB * 8;
         out[bit / 32] |= v << (bit % 32);
     }
@@ -82,7 +85,9 @@ mfma_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, 
             v4f32 acc;
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[r] = c[(i0 + r) * 16 + j];
-            if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X16_F16) {
+            if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X4_F32) {
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(ra[0]), __uint_as_float(rb[0]), acc, 0, 0, 0);
+            } else if constexpr (INSTR == MMAEMU_MFMA_F32_16X16X16_F16) {
                 v4f16 a, b;
                 __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
                 acc = __builtin_amdgcn_mfma_f32_16x16x16f16(a, b, acc, 0, 0, 0);
@@ -117,7 +122,9 @@ mfma_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, 
             v16f32 acc;
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[r] = c[(8 * (r / 4) + ib + r % 4) * 32 + j];
-            if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X8_F16) {
+            if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X2_F32) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(ra[0]), __uint_as_float(rb[0]), acc, 0, 0, 0);
+            } else if constexpr (INSTR == MMAEMU_MFMA_F32_32X32X8_F16) {
                 v4f16 a, b;
                 __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
                 acc = __builtin_amdgcn_mfma_f32_32x32x8f16(a, b, acc, 0, 0, 0);
@@ -184,6 +191,8 @@ mmaemu_status launch_mfma_probe(uint32_t instr, const void *A, const void *B, co
         CASE(MMAEMU_MFMA_F32_32X32X16_FP8_BF8);
         CASE(MMAEMU_MFMA_F32_32X32X16_BF8_FP8);
         CASE(MMAEMU_MFMA_F32_32X32X16_BF8_BF8);
+        CASE(MMAEMU_MFMA_F32_16X16X4_F32);
+        CASE(MMAEMU_MFMA_F32_32X32X2_F32);
 #undef CASE
     default:
         set_error("unknown mfma instruction %u", instr);

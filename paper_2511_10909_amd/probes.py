@@ -387,8 +387,8 @@ class _LibraryInterface:
         tdt = {1: torch.uint8, 2: torch.int16, 4: torch.int32}
         nb = A.shape[0]
         dev = "cuda"
-        dA = torch.from_numpy(np.ascontiguousarray(A).view({1: np.uint8, 2: np.int16}[A.dtype.itemsize])).to(dev)
-        dB = torch.from_numpy(np.ascontiguousarray(B).view({1: np.uint8, 2: np.int16}[B.dtype.itemsize])).to(dev)
+        dA = torch.from_numpy(np.ascontiguousarray(A).view({1: np.uint8, 2: np.int16, 4: np.int32}[A.dtype.itemsize])).to(dev)
+        dB = torch.from_numpy(np.ascontiguousarray(B).view({1: np.uint8, 2: np.int16, 4: np.int32}[B.dtype.itemsize])).to(dev)
         dC = torch.from_numpy(np.ascontiguousarray(C).view(np.int32)).to(dev)
         dD = torch.empty_like(dC)
         self._run(dA, dB, dC, dD, nb)

@@ -51,7 +51,7 @@ def test_host_side_validation_needs_no_gpu():
     assert mm.model_get_params(h)["group_len"] == 8
     mm.model_destroy(h)
     mm.model_destroy(None)
-    for kw, status in ((dict(frac_bits=41), 2), (dict(out_round=2), 1), (dict(c_mode=5), 1), (dict(align_round=1), 2),
+    for kw, status in ((dict(frac_bits=49), 2), (dict(frac_bits=41, frac_bits2=31, c_mode=2), 2), (dict(out_round=2), 1), (dict(c_mode=5), 1), (dict(align_round=1), 2),
                        (dict(out_mant_bits=13), 2), (dict(out_mant_bits=10, out_round=1), 2), (dict(frac_bits2=31), 2), (dict(c_mode=2, frac_bits2=49), 2), (dict(split=1), 2), (dict(c_mode=2, split=4), 1),
                        (dict(c_mode=3, frac_bits2=31, frac_bits_acc=24), 2), (dict(c_mode=2, frac_bits_merge=24), 2), (dict(skip_zero_terms=2), 1), (dict(family=3), 1), (dict(family=2), 2), (dict(family=1, group_len=8), 2), (dict(family=1, group_len=4, ftz_out=True), 2), (dict(struct_size=40), 1), (dict(group_len=(1 << 20) + 1), 2)):
         with pytest.raises(mm.MmaemuError) as ei:
