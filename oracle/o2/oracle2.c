@@ -29,6 +29,7 @@
 #include <string.h>
 #include <math.h>
 #include <omp.h>
+#include <stdlib.h>
 
 typedef __int128 i128;
 typedef unsigned __int128 u128;
@@ -482,13 +483,21 @@ static int emulate_mma_impl(const o2_params *p, const void *A, const void *B, co
     if (nthreads > 0) omp_set_num_threads(nthreads);
     int used = 1;
     int64_t rows = (int64_t)batch * m;
+    int nomem = 0;
 #pragma omp parallel
     {
-        uint32_t abuf[L], bbuf[L]; int sebuf[L];
+        /* one group's operands per thread, on the heap: L goes up to 2^20, far beyond a thread's stack */
+        uint32_t *abuf = malloc((size_t)L * 4), *bbuf = malloc((size_t)L * 4); int *sebuf = malloc((size_t)L * sizeof(int));
+        if (!abuf || !bbuf || !sebuf) {
+#pragma omp atomic write
+            nomem = 1;
+        }
+#pragma omp barrier
 #pragma omp single
         used = omp_get_num_threads();
 #pragma omp for schedule(dynamic, 4)
         for (int64_t r = 0; r < rows; ++r) {
+            if (nomem) continue;
             uint64_t t = (uint64_t)r / m; uint32_t i = (uint32_t)((uint64_t)r % m);
             for (uint32_t j = 0; j < n; ++j) {
                 size_t o = ((size_t)t * m + i) * n + j;
@@ -496,9 +505,10 @@ static int emulate_mma_impl(const o2_params *p, const void *A, const void *B, co
                                       : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf, sebuf, sc);
             }
         }
+        free(abuf); free(bbuf); free(sebuf);
     }
     if (threads_used) *threads_used = used;
-    return 0;
+    return nomem ? -4 : 0;
 }
 
 int o2_emulate_mma(const o2_params *p, const void *A, const void *B, const uint32_t *C, uint32_t *D,
@@ -610,22 +620,31 @@ int o2_emulate_sample(const o2_params *p, const void *A, const void *B, const ui
     for (uint64_t s = 0; s < count; ++s) if (idx[s] >= batch * m * n) return -3;
     if (nthreads > 0) omp_set_num_threads(nthreads);
     int used = 1;
+    int nomem = 0;
 #pragma omp parallel
     {
-        uint32_t abuf[L], bbuf[L]; int sebuf[L]; const scales_t sc = NO_SCALES;
+        uint32_t *abuf = malloc((size_t)L * 4), *bbuf = malloc((size_t)L * 4); int *sebuf = malloc((size_t)L * sizeof(int));
+        const scales_t sc = NO_SCALES;
+        if (!abuf || !bbuf || !sebuf) {
+#pragma omp atomic write
+            nomem = 1;
+        }
+#pragma omp barrier
 #pragma omp single
         used = omp_get_num_threads();
 #pragma omp for schedule(dynamic, 16)
         for (int64_t s = 0; s < (int64_t)count; ++s) {
+            if (nomem) continue;
             uint64_t o = idx[s];
             uint64_t t = o / ((uint64_t)m * n);
             uint32_t i = (uint32_t)((o / n) % m), j = (uint32_t)(o % n);
             D_sample[s] = p->family == 1 ? addmul_element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, ta, tb)
                                          : element(p, A, B, C[o], ((size_t)t * m + i) * k, ((size_t)t * n + j) * k, k, L, ta, tb, abuf, bbuf, sebuf, sc);
         }
+        free(abuf); free(bbuf); free(sebuf);
     }
     if (threads_used) *threads_used = used;
-    return 0;
+    return nomem ? -4 : 0;
 }
 
 /* Exact dot products (C = 0) and the error of D against them, at flattened indices

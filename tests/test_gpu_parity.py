@@ -317,3 +317,26 @@ def test_exact_dot_sample_matches_oracle(mm):
             assert got[key] == want[key], key
         for key in ("sum_abs_err", "max_abs_err", "sum_rel_err", "max_rel_err", "sum_signed_err"):
             assert got[key] == pytest.approx(want[key], rel=1e-9, abs=1e-300), key
+
+
+@pytest.mark.parametrize("ta,tb,L,cm", [(fm.FP16, fm.FP16, 0, C_IN_GROUP), (fm.BF16, fm.BF16, 8, C_AFTER_EXACT), (fm.E4M3, fm.E5M2, 32, C_IN_GROUP),
+                                        (fm.FP16, fm.FP16, 1 << 20, C_AFTER_EXACT)])
+def test_emulate_longest_dot_products(mm, ta, tb, L, cm):
+    # k at the entry point's limit (2^20), one group spanning all of it and chains of short groups; k one above: refused
+    rng = np.random.default_rng(77 + L % 97)
+    k = 1 << 20
+    A = synth.narrow_exponent_bits(rng, (1, 3, k), ta, *((12, 18) if ta != fm.BF16 else (120, 134)))
+    B = synth.narrow_exponent_bits(rng, (1, 2, k), tb, *((12, 18) if tb != fm.BF16 else (120, 134)))
+    if ta == fm.E4M3:
+        A, B = synth.random_bits(rng, (1, 3, k), ta), synth.random_bits(rng, (1, 2, k), tb)
+    C = synth.narrow_exponent_bits(rng, (1, 3, 2), fm.FP32, 120, 140)
+    p = ModelParams(group_len=L, frac_bits=24, c_mode=cm)
+    want, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
+    got = gpu_emulate(mm, p, A, B, C, ta, tb)
+    assert_same(got, want, "k = 2^20, L = %d" % L)
+    h = mm.model_create(group_len=1)
+    x = dev_empty(64)
+    with pytest.raises(mm.MmaemuError) as ei:
+        mm.emulate_mma(h, x, x, x, x, 1, 1, k + 1, 1, (ta, tb, fm.FP32, fm.FP32))
+    assert ei.value.status == 3
+    mm.model_destroy(h)

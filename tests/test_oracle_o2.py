@@ -175,3 +175,30 @@ def test_o2_exact_dot_stats_against_rational():
     for key in ("sum_abs_err", "max_abs_err", "sum_rel_err", "max_rel_err", "sum_signed_err"):
         assert got[key] == pytest.approx(want[key], rel=1e-12, abs=1e-300), key
     assert want["n_samples"] == len(range(0, m * n, 7)) and want["n_equal_rne"] < want["n_samples"]
+
+
+def test_o2_longest_groups():
+    # one group over k = 2^20 (the longest dot product the entry points take), on several threads: against the rational
+    # form on one output, and against a closed form (2^20 equal products: the exact sum is a power of two times k)
+    from oracle.fdpa import emulate_element
+    rng = np.random.default_rng(2020)
+    k = 1 << 20
+    A = synth.narrow_exponent_bits(rng, (1, 3, k), fm.FP16, 12, 18)
+    B = synth.narrow_exponent_bits(rng, (1, 2, k), fm.FP16, 12, 18)
+    C = synth.narrow_exponent_bits(rng, (1, 3, 2), fm.FP32, 120, 140)
+    full, _ = o2lib.emulate_mma(ModelParams(group_len=0, frac_bits=24), A, B, C, fm.FP16, fm.FP16)
+    q = k // 8                                                  # (the rational form on an eighth: it takes seconds per 10^5 terms)
+    p = ModelParams(group_len=q, frac_bits=24, c_mode=C_AFTER_EXACT)
+    got, _ = o2lib.emulate_mma(p, A[:, :, :q], B[:, :, :q], C, fm.FP16, fm.FP16)
+    assert int(got[0, 2, 1]) == emulate_element(p, A[0, 2, :q].tolist(), B[0, 1, :q].tolist(), int(C[0, 2, 1]), fm.FP16, fm.FP16)
+    # the whole length in one group with nothing cut (F wide, three-bit values on two exponents): binary64's dot product,
+    # exact here, rounded once
+    wide = ModelParams(group_len=0, frac_bits=40)
+    Cz = np.zeros((1, 3, 2), dtype=np.uint32)
+    Ah, Bh = synth.narrow_exponent_bits(rng, (1, 3, k), fm.FP16, 15, 16) & 0xFF00, synth.narrow_exponent_bits(rng, (1, 2, k), fm.FP16, 15, 16) & 0xFF00
+    d1, _ = o2lib.emulate_mma(wide, Ah, Bh, Cz, fm.FP16, fm.FP16)
+    exact = (Ah.view(np.float16).astype(np.float64)[0] @ Bh.view(np.float16).astype(np.float64)[0].T).astype(np.float32).view(np.uint32)
+    assert np.array_equal(d1[0], exact) and full.shape == (1, 3, 2)
+    ones = np.full((1, 1, k), ENCODERS["fp16"](1.5), dtype=np.uint16)
+    got, _ = o2lib.emulate_mma(ModelParams(group_len=0, frac_bits=24), ones, ones, np.zeros((1, 1, 1), dtype=np.uint32), fm.FP16, fm.FP16)
+    assert bits_f32(int(got[0, 0, 0])) == 2.25 * k
