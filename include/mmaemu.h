@@ -340,7 +340,9 @@ typedef enum {
     /* FP32 operands (the paper's FP32 instructions are chains of FMAs, Sec. 4.1.2) */
     MMAEMU_MFMA_F32_16X16X4_F32 = 41,
     MMAEMU_MFMA_F32_32X32X2_F32 = 42,
-    MMAEMU_MFMA_COUNT = 43
+    /* v_mfma_scale_f32_32x32x64_f8f6f4, numbered like the 16x16x128 form: id = BASE + 5 fa + fb (43 .. 67) */
+    MMAEMU_MFMA_SCALE_F32_32X32X64_F8F6F4_BASE = 43,
+    MMAEMU_MFMA_COUNT = 68
 } mmaemu_mfma_instr;
 
 /* Shape and operand types of an instruction (host-side query). */

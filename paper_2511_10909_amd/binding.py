@@ -28,15 +28,19 @@ MFMA_SCALE_BASE = 10
 MFMA_SCALE_FORMATS = (0, 1, 6, 7, 8)            # dtype ids in the instruction's numbering
 
 
-def mfma_scale_id(ta, tb):
-    """Instruction id of the block-scaled MFMA with operand types ta (A) and tb (B)."""
-    return MFMA_SCALE_BASE + 5 * MFMA_SCALE_FORMATS.index(ta) + MFMA_SCALE_FORMATS.index(tb)
+MFMA_SCALE32_BASE = 43                          # v_mfma_scale_f32_32x32x64_f8f6f4, numbered the same way
+
+
+def mfma_scale_id(ta, tb, m=16):
+    """Instruction id of the block-scaled MFMA (m = 16: 16x16x128, m = 32: 32x32x64) with operand types ta (A) and tb (B)."""
+    return (MFMA_SCALE_BASE if m == 16 else MFMA_SCALE32_BASE) + 5 * MFMA_SCALE_FORMATS.index(ta) + MFMA_SCALE_FORMATS.index(tb)
 
 
 MFMA_SCALE_F32_16X16X128_FP8_FP8, MFMA_SCALE_F32_16X16X128_FP8_BF8 = 10, 11
 MFMA_SCALE_F32_16X16X128_BF8_FP8, MFMA_SCALE_F32_16X16X128_BF8_BF8 = 15, 16
 MFMA_SCALE_FP8_IDS = (10, 11, 15, 16)
 MFMA_SCALE_IDS = tuple(range(10, 35))
+MFMA_SCALE32_IDS = tuple(range(43, 68))
 (MFMA_F32_32X32X16_F16, MFMA_F32_32X32X16_BF16, MFMA_F32_32X32X16_FP8_FP8, MFMA_F32_32X32X16_FP8_BF8,
  MFMA_F32_32X32X16_BF8_FP8, MFMA_F32_32X32X16_BF8_BF8) = range(35, 41)
 MFMA_F32_16X16X4_F32, MFMA_F32_32X32X2_F32 = 41, 42

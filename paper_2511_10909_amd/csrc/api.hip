@@ -387,6 +387,13 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
     return launch_generate(*g, out, dtype, ept, first_tile, n_tiles, workspace, (hipStream_t)hip_stream);
 }
 
+// the block-scaled instructions: 16x16x128 (25 ids) and 32x32x64 (25 ids)
+static bool is_scaled_instr(uint32_t i)
+{
+    return (i >= MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE && i < MMAEMU_MFMA_F32_32X32X16_F16) ||
+           (i >= MMAEMU_MFMA_SCALE_F32_32X32X64_F8F6F4_BASE && i < MMAEMU_MFMA_COUNT);
+}
+
 mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n, uint32_t *k_native, mmaemu_dtype *a,
                                mmaemu_dtype *b)
 {
@@ -410,12 +417,13 @@ mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n
         if (b) *b = T2[q][1];
         return MMAEMU_OK;
     }
-    if ((uint32_t)instr >= MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE && (uint32_t)instr < MMAEMU_MFMA_F32_32X32X16_F16) {
+    if (is_scaled_instr((uint32_t)instr)) {
         static const mmaemu_dtype F[5] = {MMAEMU_FP8_E4M3, MMAEMU_FP8_E5M2, MMAEMU_FP6_E2M3, MMAEMU_FP6_E3M2, MMAEMU_FP4_E2M1};
-        const uint32_t q = (uint32_t)instr - MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE;
-        if (m) *m = 16;
-        if (n) *n = 16;
-        if (k_native) *k_native = 128;
+        const bool big = (uint32_t)instr >= MMAEMU_MFMA_SCALE_F32_32X32X64_F8F6F4_BASE;
+        const uint32_t q = (uint32_t)instr - (big ? MMAEMU_MFMA_SCALE_F32_32X32X64_F8F6F4_BASE : MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE);
+        if (m) *m = big ? 32 : 16;
+        if (n) *n = big ? 32 : 16;
+        if (k_native) *k_native = big ? 64 : 128;
         if (a) *a = F[q / 5];
         if (b) *b = F[q % 5];
         return MMAEMU_OK;
@@ -442,7 +450,7 @@ mmaemu_status mmaemu_mfma_probe(mmaemu_mfma_instr instr, const void *A, const vo
     mmaemu_dtype ta, tb;
     mmaemu_status st = mmaemu_mfma_info(instr, &m, &n, &kn, &ta, &tb);
     if (st != MMAEMU_OK) return st;
-    if (instr >= MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE && instr < MMAEMU_MFMA_F32_32X32X16_F16) { set_error("mfma_probe: a block-scaled instruction needs mfma_probe_scaled"); return MMAEMU_ERR_INVALID_ARG; }
+    if (is_scaled_instr((uint32_t)instr)) { set_error("mfma_probe: a block-scaled instruction needs mfma_probe_scaled"); return MMAEMU_ERR_INVALID_ARG; }
     if (k == 0 || k > kn) { set_error("mfma_probe: k=%u outside 1..%u", k, kn); return MMAEMU_ERR_SHAPE; }
     if (batch > (1ull << 40)) { set_error("mfma_probe: batch too large"); return MMAEMU_ERR_SHAPE; }
     if (batch == 0) return MMAEMU_OK;
@@ -461,7 +469,7 @@ mmaemu_status mmaemu_mfma_probe_scaled(mmaemu_mfma_instr instr, const void *A, c
     uint32_t m, n, kn;
     mmaemu_status st = mmaemu_mfma_info(instr, &m, &n, &kn, nullptr, nullptr);
     if (st != MMAEMU_OK) return st;
-    if (instr < MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE || instr >= MMAEMU_MFMA_F32_32X32X16_F16) { set_error("mfma_probe_scaled: not a block-scaled instruction"); return MMAEMU_ERR_INVALID_ARG; }
+    if (!is_scaled_instr((uint32_t)instr)) { set_error("mfma_probe_scaled: not a block-scaled instruction"); return MMAEMU_ERR_INVALID_ARG; }
     if (k == 0 || k > kn || k % 32) { set_error("mfma_probe_scaled: k=%u must be a multiple of 32 up to %u", k, kn); return MMAEMU_ERR_SHAPE; }
     if (batch > (1ull << 40)) { set_error("mfma_probe_scaled: batch too large"); return MMAEMU_ERR_SHAPE; }
     if (batch == 0) return MMAEMU_OK;

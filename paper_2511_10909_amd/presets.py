@@ -108,3 +108,5 @@ for _ta in mm.MFMA_SCALE_FORMATS:
     for _tb in mm.MFMA_SCALE_FORMATS:
         _both_narrow = _ta >= mm.E2M3 and _tb >= mm.E2M3
         GFX950_MFMA[mm.mfma_scale_id(_ta, _tb)] = _GFX950_NARROW_SCALED if _both_narrow else _GFX950_FP8_SCALED
+        # v_mfma_scale_f32_32x32x64_f8f6f4: the same arithmetic over K = 64
+        GFX950_MFMA[mm.mfma_scale_id(_ta, _tb, 32)] = _GFX950_NARROW_SCALED if _both_narrow else _GFX950_FP8_SCALED

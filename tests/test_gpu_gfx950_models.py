@@ -59,12 +59,13 @@ def test_paper_cdna3_models_differ_from_gfx950(env):
     assert res["wide_exp_c_any"]["n_mismatch_bits"] > 0     # ... but not once zero operands carry large exponents
 
 
-@pytest.mark.parametrize("instr", range(10, 35))
+@pytest.mark.parametrize("instr", list(range(10, 35)) + list(range(43, 68)))
 def test_gfx950_preset_reproduces_the_block_scaled_instruction(env, instr):
-    # Algorithm "ST-FDPA" on the FP8 instructions' structure, against v_mfma_scale_f32_16x16x128_f8f6f4: every input
+    # Algorithm "ST-FDPA" on the FP8 instructions' structure, against v_mfma_scale_f32_16x16x128_f8f6f4 (ids 10 .. 34)
+    # and v_mfma_scale_f32_32x32x64_f8f6f4 (ids 43 .. 67): every input
     # family under every range of scale codes (unit, narrow, wide, all codes with NaN, and the bottom of binary32)
     mm, configs, presets = env
-    res = configs.validate_scaled_against_mfma(instr, presets.GFX950_MFMA[instr], n_tiles=256)
+    res = configs.validate_scaled_against_mfma(instr, presets.GFX950_MFMA[instr], n_tiles=256 if instr < 43 else 64)
     assert res["kernel"].startswith("tiled") and "vm=3" in res["kernel"]
     for key, st in res.items():
         if not isinstance(st, dict):

@@ -14,7 +14,7 @@ def env():
     return binding, presets, probes
 
 
-@pytest.mark.parametrize("instr,scales", [(i, None) for i in list(range(10)) + [35, 36, 37, 40]] + [(10, (127, 127)), (11, (100, 154)), (15, (150, 104)), (16, (127, 127))])
+@pytest.mark.parametrize("instr,scales", [(i, None) for i in list(range(10)) + [35, 36, 37, 40]] + [(10, (127, 127)), (11, (100, 154)), (15, (150, 104)), (16, (127, 127)), (43, (127, 127)), (49, (110, 144))])
 def test_probes_agree_between_instruction_and_model(env, instr, scales):
     mm, presets, probes = env
     if scales is None:

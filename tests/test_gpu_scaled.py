@@ -154,28 +154,29 @@ def test_scaled_argument_errors(mm):
     mm.model_destroy(h)
 
 
-@pytest.mark.parametrize("instr", range(10, 35))
+@pytest.mark.parametrize("instr", list(range(10, 35)) + list(range(43, 68)))
 def test_scaled_mfma_register_layout(mm, instr):
     # small-integer operands and scales of 2^-4 .. 2^4: every arithmetic is exact, so any mistake in the operand,
     # scale or result register layout shows, whatever the instruction does inside
     info = mm.mfma_info(instr)
     ta, tb = info["a"], info["b"]
-    assert (info["m"], info["n"], info["k"]) == (16, 16, 128)
+    M = info["m"]
+    assert (info["m"], info["n"], info["k"]) == ((16, 16, 128) if instr < 43 else (32, 32, 64))
     rng = np.random.default_rng(instr)
-    for k in (128, 64, 32):
+    for k in ((128, 64, 32) if M == 16 else (64, 32)):
         nb = 9
-        A, av = _small_int_codes(rng, (nb, 16, k), ta)
-        B, bv = _small_int_codes(rng, (nb, 16, k), tb)
-        SA = rng.integers(123, 132, size=(nb, 16, k // 32)).astype(np.uint8)
-        SB = rng.integers(123, 132, size=(nb, 16, k // 32)).astype(np.uint8)
-        cv = rng.integers(-100, 100, size=(nb, 16, 16))
+        A, av = _small_int_codes(rng, (nb, M, k), ta)
+        B, bv = _small_int_codes(rng, (nb, M, k), tb)
+        SA = rng.integers(123, 132, size=(nb, M, k // 32)).astype(np.uint8)
+        SB = rng.integers(123, 132, size=(nb, M, k // 32)).astype(np.uint8)
+        cv = rng.integers(-100, 100, size=(nb, M, M))
         C = cv.astype(np.float32).view(np.uint32)
         want = cv.astype(np.float64)
         for q in range(k // 32):
             blockdot = np.einsum("bik,bjk->bij", av[:, :, 32 * q:32 * q + 32], bv[:, :, 32 * q:32 * q + 32]).astype(np.float64)
             want = want + blockdot * 2.0 ** (SA[:, :, q].astype(np.int64)[:, :, None] + SB[:, :, q].astype(np.int64)[:, None, :] - 254)
         want = want.astype(np.float32).view(np.uint32)
-        dD = dev_empty((nb, 16, 16), np.uint32)
+        dD = dev_empty((nb, M, M), np.uint32)
         print("scaled mfma", instr, k, flush=True)
         mm.mfma_probe_scaled(instr, to_dev(A), to_dev(B), to_dev(C), dD, to_dev(SA), to_dev(SB), k, nb)
         got = to_host(dD, np.uint32)
