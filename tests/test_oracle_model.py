@@ -414,3 +414,48 @@ def test_rz_e8m13_conversion():
         assert d13 == d23 & 0xFFFFFC00
     with pytest.raises(ValueError):
         fdpa_group(p.with_(out_round=RNE), a, b, c, fm.FP16, fm.FP16)
+
+
+# ---------------------------------------------------------------- invariants of the fused sum (Algorithm "T-FDPA")
+@pytest.mark.parametrize("cm", [C_IN_GROUP, C_AFTER_EXACT])
+def test_order_inside_a_group_does_not_matter_but_groups_do(cm):
+    # every term of a group is aligned to the same maximum and the integer sum is exact: permuting the products of a
+    # group changes nothing; moving a product to another group of the chain generally does
+    rng = np.random.default_rng(41)
+    p = ModelParams(group_len=8, frac_bits=13, c_mode=cm, out_round=RZ)
+    moved = 0
+    for _ in range(60):
+        A = synth.narrow_exponent_bits(rng, (1, 4, 16), fm.FP16, 8, 22)
+        B = synth.narrow_exponent_bits(rng, (1, 3, 16), fm.FP16, 8, 22)
+        C = synth.narrow_exponent_bits(rng, (1, 4, 3), fm.FP32, 110, 140)
+        want, _ = o2lib_emulate(p, A, B, C)
+        perm = np.concatenate([rng.permutation(8), 8 + rng.permutation(8)])
+        got, _ = o2lib_emulate(p, A[:, :, perm], B[:, :, perm], C)
+        assert np.array_equal(got, want)
+        swap = np.arange(16); swap[[0, 8]] = swap[[8, 0]]
+        other, _ = o2lib_emulate(p, A[:, :, swap], B[:, :, swap], C)
+        moved += int((other != want).sum())
+    assert moved > 0
+
+
+def test_scaling_by_a_power_of_two_shifts_the_result():
+    # Exp enters only through differences to e_max and through the final scale: A * 2^s and C * 2^s give D * 2^s
+    # bit for bit while nothing leaves the normal ranges
+    rng = np.random.default_rng(42)
+    for trial in range(40):
+        p = ModelParams(group_len=int(rng.choice([4, 8])), frac_bits=int(rng.choice([13, 24])), out_round=int(rng.integers(0, 2)),
+                        c_mode=int(rng.integers(0, 2)))
+        A = synth.narrow_exponent_bits(rng, (1, 3, 8), fm.BF16, 110, 140)
+        B = synth.narrow_exponent_bits(rng, (1, 3, 8), fm.BF16, 110, 140)
+        C = synth.narrow_exponent_bits(rng, (1, 3, 3), fm.FP32, 100, 150)
+        s = int(rng.integers(-20, 21))
+        want, _ = o2lib_emulate(p, A, B, C, ta=fm.BF16)
+        got, _ = o2lib_emulate(p, (A.astype(np.int64) + (s << 7)).astype(np.uint16), B, (C.astype(np.int64) + (s << 23)).astype(np.uint32), ta=fm.BF16)
+        nz = (want & 0x7FFFFFFF) != 0
+        assert np.array_equal(got[nz].astype(np.int64), want[nz].astype(np.int64) + (s << 23)), trial
+        assert not (got[~nz] & 0x7FFFFFFF).any()
+
+
+def o2lib_emulate(p, A, B, C, ta=fm.FP16):
+    from oracle import o2lib
+    return o2lib.emulate_mma(p, A, B, C, ta, ta)
