@@ -256,6 +256,92 @@ __device__ __forceinline__ const void *opaque_kernarg_ptr()
 #endif
 }
 
+// ---- special values of a thread's register block, from the raw operands ---------------------
+// A group that holds a NaN or an infinity (operand or accumulator) has a NaN or an infinity for its result (Sec. 4.2),
+// and which one follows from the classes and signs of the operands alone.  For the tagged outputs of one thread's
+// R x C block this routine classifies each row of A and of B once per group into bit masks over k (NaN, infinity,
+// zero, sign) and applies the rules to the masks: no value is decoded, and a row shared by several outputs is read
+// once.  Outputs it cannot settle (no special operand after all: the group was tagged for another reason; or an
+// infinity where the model's overflow rule or a NaN scale factor may still turn it into NaN) are left to the integer
+// routine.  Kept out of line so that its registers do not count against the hot loops.  (The model's parameters come
+// in as arguments: the kernel-argument segment pointer is null inside a called function.)
+template <int N> struct BlockVals { uint32_t v[N]; uint32_t settled; };      // settled: bit r * C + c
+
+struct RowMasks { uint64_t nan, inf, zero, sign; };
+
+__device__ __forceinline__ RowMasks classify_row(const DynFmt &f, const void *row, uint32_t len, uint32_t ftz_in)
+{
+    const uint32_t MAG = (1u << (f.eb() + f.mb())) - 1u, EXPM = ((1u << f.eb()) - 1u) << f.mb();
+    RowMasks r = {0ull, 0ull, 0ull, 0ull};
+    for (uint32_t k = 0; k < len; ++k) {
+        const uint32_t bits = f.load(row, k), mag = bits & MAG;
+        const uint64_t bit = 1ull << k;
+        if (f.ieee()) {
+            if (mag > EXPM) r.nan |= bit;
+            if (mag == EXPM) r.inf |= bit;
+        } else if (!f.nospec()) {
+            if (mag == MAG) r.nan |= bit;                                     // the E4M3 rule: one NaN code, no infinity
+        }
+        if (ftz_in ? (mag & EXPM) == 0 : mag == 0) r.zero |= bit;            // (FlushSubnormal: a subnormal counts as zero)
+        if ((bits >> (f.eb() + f.mb())) & 1u) r.sign |= bit;
+    }
+    return r;
+}
+
+// inf_final: an infinity stands (nothing else can still make it NaN: no product-overflow rule, which adds infinities
+// of its own, and no scale factors, of which a NaN one overrides)
+template <int R, int C, int TI, int TJ>
+__device__ __noinline__ BlockVals<R * C> special_block(const void *A, const void *B, uint64_t arow0, uint64_t brow0, uint32_t k,
+                                                       uint32_t kg, BlockVals<R * C> cin, uint32_t tagged, uint32_t ta, uint32_t tb,
+                                                       uint32_t L, uint32_t ftz_in, uint32_t nan_bits, bool inf_final)
+{
+    const DynFmt fa = dyn_fmt(ta), fb = dyn_fmt(tb);
+    const uint32_t esa = (uint32_t)fa.width_ / 8u, esb = (uint32_t)fb.width_ / 8u;
+    uint32_t any_nan = 0, pinf = 0, ninf = 0;                                 // one bit per output
+    uint32_t rows = 0, cols = 0;                                              // rows of A / of B that a tagged output needs
+#pragma unroll
+    for (int i = 0; i < R * C; ++i)
+        if ((tagged >> i) & 1u) { rows |= 1u << (i / C); cols |= 1u << (i % C); }
+    for (uint32_t k0 = 0; k0 < L; k0 += 64u) {
+        const uint32_t len = L - k0 < 64u ? L - k0 : 64u;
+        RowMasks mb[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            mb[c] = RowMasks{0ull, 0ull, 0ull, 0ull};
+            if ((cols >> c) & 1u)
+                mb[c] = classify_row(fb, reinterpret_cast<const uint8_t *>(B) + ((brow0 + (uint64_t)(TJ * c)) * k + kg + k0) * esb, len, ftz_in);
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (!((rows >> r) & 1u)) continue;
+            const RowMasks ma = classify_row(fa, reinterpret_cast<const uint8_t *>(A) + ((arow0 + (uint64_t)(TI * r)) * k + kg + k0) * esa, len, ftz_in);
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const uint64_t nanp = ma.nan | mb[c].nan | (ma.inf & mb[c].zero) | (mb[c].inf & ma.zero);
+                const uint64_t infp = (ma.inf | mb[c].inf) & ~nanp, neg = ma.sign ^ mb[c].sign;
+                const uint32_t bit = 1u << (r * C + c);
+                if (nanp) any_nan |= bit;
+                if (infp & ~neg) pinf |= bit;
+                if (infp & neg) ninf |= bit;
+            }
+        }
+    }
+    BlockVals<R * C> out;
+    out.settled = 0;
+#pragma unroll
+    for (int i = 0; i < R * C; ++i) {
+        out.v[i] = 0;
+        if (!((tagged >> i) & 1u)) continue;
+        const uint32_t c = cin.v[i], bit = 1u << i;
+        bool n = (any_nan & bit) != 0, p = (pinf & bit) != 0, m = (ninf & bit) != 0;
+        if ((c & 0x7FFFFFFFu) > 0x7F800000u) n = true;
+        else if ((c & 0x7FFFFFFFu) == 0x7F800000u) { if (c >> 31) m = true; else p = true; }
+        if (n || (p && m)) { out.v[i] = nan_bits; out.settled |= bit; }
+        else if ((p || m) && inf_final) { out.v[i] = p ? 0x7F800000u : 0xFF800000u; out.settled |= bit; }
+    }
+    return out;
+}
+
 // ---- the kernel -------------------------------------------------------------------------
 // TM x TN : block of D per slot;  R x C: register block per thread;
 // KC      : k elements staged at a time;
@@ -652,11 +738,30 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
             }
         }
         if (tagged & SENTINEL_MASK) {                                   // rare: the group met a tagged element
+            BlockVals<R * C> cin;
+            uint32_t tm = 0;
+#pragma unroll
+            for (int i = 0; i < R * C; ++i) cin.v[i] = 0;
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int c = 0; c < C; ++c)
-                    if (tg[r][c] & SENTINEL_MASK) dn[r][c] = slow_group(r, c, kg, d[r][c]);
+                    if (tg[r][c] & SENTINEL_MASK) {
+                        cin.v[r * C + c] = d[r][c];
+                        tm |= 1u << (r * C + c);
+                    }
+            // NaN and infinity results first, for the whole block at once; then the integer routine for what is left
+            // (the model parameters are fetched from the kernel-argument segment here, as in slow_group)
+            const TiledArgs q = *reinterpret_cast<const TiledArgs *>(opaque_kernarg_ptr());
+            const bool inf_final = !SC && (q.p.c_mode != MMAEMU_C_AFTER_RD || q.p.wide_products);
+            const BlockVals<R * C> sp = special_block<R, C, TI, TJ>(A, B, my_tile * m + i_base, my_tile * n + j_base, k, kg, cin, tm, q.ta, q.tb,
+                                                                    q.p.L, q.p.ftz_in, q.p.nan_bits, inf_final);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+                    if (tg[r][c] & SENTINEL_MASK)
+                        dn[r][c] = ((sp.settled >> (r * C + c)) & 1u) ? sp.v[r * C + c] : slow_group(r, c, kg, d[r][c]);
         }
 #pragma unroll
         for (int r = 0; r < R; ++r)
