@@ -100,6 +100,7 @@ class ModelParams:
     sum_drop_distance: int = 0
     wide_products: bool = False
     family: int = FAMILY_FDPA
+    nan_propagate: bool = False  # FP32 operands only: a NaN result carries an operand's payload (see _specials)
 
     def with_(self, **kw):
         return replace(self, **kw)
@@ -124,9 +125,28 @@ def _nan(p, tc):
     return p.nan_bits if tc == fm.FP32 else p.nan_bits & 0xFFFF
 
 
-def _specials(p, da, db, dc, scale_exp=None, tc=fm.FP32):
-    """Sec. 4.2.  Returns output bits if the group's result is NaN or infinite, else None."""
-    if dc.cls == fm.NAN or any(x.cls == fm.NAN for x in da) or any(x.cls == fm.NAN for x in db):
+def _specials(p, da, db, dc, scale_exp=None, tc=fm.FP32, raw=None):
+    """Sec. 4.2.  Returns output bits if the group's result is NaN or infinite, else None.
+
+    With `nan_propagate` (raw = the bit patterns (a, b, c); FP32 operands and accumulator) a NaN result is not the one
+    pattern `nan_bits` but follows the rule of a fused multiply-add unit that passes payloads on, in this order: the
+    first NaN operand in the order a_0, b_0, a_1, b_1, ..., made quiet (mantissa bit 22 set, everything else kept); else,
+    if some product is infinity times zero, `nan_bits`; else a NaN accumulator, made quiet; else (infinities of both
+    signs) `nan_bits`.  The paper's models write one pattern; this variation is what the FP32 instructions of gfx950
+    were seen to do (one product per step)."""
+    if p.nan_propagate:
+        a_raw, b_raw, c_raw = raw
+        for k in range(len(da)):
+            if da[k].cls == fm.NAN:
+                return a_raw[k] | 0x00400000
+            if db[k].cls == fm.NAN:
+                return b_raw[k] | 0x00400000
+        for x, y in zip(da, db):
+            if (x.cls == fm.INF and y.cls == fm.ZERO) or (y.cls == fm.INF and x.cls == fm.ZERO):
+                return _nan(p, tc)
+        if dc.cls == fm.NAN:
+            return c_raw | 0x00400000
+    elif dc.cls == fm.NAN or any(x.cls == fm.NAN for x in da) or any(x.cls == fm.NAN for x in db):
         return _nan(p, tc)
     pos_inf = neg_inf = False
     for k, (x, y) in enumerate(zip(da, db)):
@@ -193,7 +213,9 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None, tc=fm.FP32):
     if tc == fm.FP16 and (p.c_mode in (C_AFTER_RD, C_AFTER_RD_EVEN_ODD) or p.out_mant_bits != 23):
         raise ValueError("FP16 accumulators go with the T-FDPA modes and the plain conversion only")
 
-    sp = _specials(p, da, db, dc, scale_exp, tc)
+    if p.nan_propagate and not (ta == tb == tc == fm.FP32):
+        raise ValueError("nan_propagate is defined for FP32 operands and accumulators")
+    sp = _specials(p, da, db, dc, scale_exp, tc, raw=(a_bits, b_bits, c_bits))
     if sp is not None:
         return sp
 

@@ -47,6 +47,9 @@ typedef struct {
     uint32_t out_mant_bits; /* 23, or 13 (RZ-E8M13, with out_round = RZ) */
     uint32_t wide_products; /* RD mode: no infinity from a single product of magnitude >= 2^128 */
     uint32_t acc_fp16;      /* accumulator and output are binary16 patterns (rho = RNE-FP16 / RZ-FP16); T-FDPA modes only */
+    uint32_t nan_propagate; /* FP32 operands: a NaN result carries a payload (first NaN operand in the order a_0, b_0, a_1, ...,
+                               made quiet; else nan_bits for infinity times zero; else a NaN accumulator, made quiet; else
+                               nan_bits for infinities of both signs) */
 } o2_params;
 
 /* ieee: 1 = exponent field all ones is Inf / NaN, 0 = the E4M3 rule (one NaN code), 2 = every code finite (FP6, FP4) */
@@ -289,6 +292,17 @@ static uint32_t fdpa_group(const o2_params *p, const uint32_t *a, const uint32_t
     if (c_mode == C_AFTER_RD_EVEN_ODD) { c_mode = C_AFTER_RD; split = 1; trunc = 1; }   /* GTR-FDPA by name */
     dec_t dc = dec_acc(p, c);
 
+    if (p->nan_propagate) {      /* payload rule, in its order of precedence; what it leaves goes on below */
+        for (uint32_t k = 0; k < L; ++k) {
+            if (dec_in(p, a[k], ta).cls == CLS_NAN) return a[k] | 0x00400000u;
+            if (dec_in(p, b[k], tb).cls == CLS_NAN) return b[k] | 0x00400000u;
+        }
+        for (uint32_t k = 0; k < L; ++k) {
+            dec_t x = dec_in(p, a[k], ta), y = dec_in(p, b[k], tb);
+            if ((x.cls == CLS_INF && y.cls == CLS_ZERO) || (y.cls == CLS_INF && x.cls == CLS_ZERO)) return nan_out(p);
+        }
+        if (dc.cls == CLS_NAN) return c | 0x00400000u;
+    }
     /* special values (Sec. 4.2) */
     int any_nan = dc.cls == CLS_NAN, pinf = 0, ninf = 0;
     for (uint32_t k = 0; k < L; ++k) {
@@ -420,6 +434,7 @@ static int check(const o2_params *p, uint32_t k, int ta, int tb, uint32_t *L_out
     }
     if (p->family > 1) return -2;
     if (p->acc_fp16 && (p->c_mode >= C_AFTER_RD || p->out_mant_bits != 23)) return -2;
+    if (p->nan_propagate && (ta != T_FP32 || tb != T_FP32 || p->acc_fp16)) return -2;
     if (p->out_mant_bits != 23 && !(p->out_mant_bits == 13 && p->out_round == R_RZ)) return -2;
     if (p->align_round != 0 || p->c_mode > 3 || p->out_round > 1 || p->frac_bits > 64) return -2;
     if (k == 0 || k > (1u << 20)) return -3;

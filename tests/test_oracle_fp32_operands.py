@@ -132,3 +132,63 @@ def test_c_form_equals_rational_form_on_fp32_operands():
         want = emulate_mma(p, A, B, C, fm.FP32, fm.FP32)
         got, _ = o2lib.emulate_mma(p, A, B, C, fm.FP32, fm.FP32)
         assert np.array_equal(got, want), (trial, p)
+
+
+def test_nan_payload_rule():
+    # the variation `nan_propagate`: which NaN comes out of a chain of FMAs that pass payloads on.  Cases written out
+    # from the rule's order of precedence (a, then b, then an invalid product, then the accumulator, then infinities of
+    # both signs), step by step along the chain.
+    one, inf, ninf, zero = f32_bits(1.0), 0x7F800000, 0xFF800000, 0
+    qa, qb, qc, qd = 0x7FC00AAA, 0xFFC00BBB, 0x7FC00CCC, 0x7FC00DDD
+    sa, sc = 0x7F800AAA, 0x7F800CCC                                   # signalling: come out quiet, payload kept
+    gen = 0xFFC00000
+    p = FMA.with_(nan_propagate=True, nan_bits=gen)
+    cases = [
+        (([qa, one, one, one], [one] * 4, one), qa),
+        (([one] * 4, [one, qb, one, one], one), qb),
+        (([one] * 4, [one] * 4, qc), qc),
+        (([qa, one, one, one], [qb, one, one, one], one), qa),       # a before b in one step
+        (([qa, one, one, one], [one] * 4, qc), qa),                  # a before the accumulator
+        (([one] * 4, [qb, one, one, one], qc), qb),                  # b before the accumulator
+        (([one, qa, one, one], [qb, one, one, one], one), qa),       # the later step's operand over the running NaN
+        (([qa, one, one, one], [one, qb, one, one], one), qb),
+        (([qa, qd, one, one], [one] * 4, one), qd),
+        (([sa, one, one, one], [one] * 4, one), qa),
+        (([one] * 4, [one] * 4, sc), qc),
+        (([inf, one, one, one], [zero, one, one, one], one), gen),   # infinity times zero: the model's own pattern
+        (([inf, one, one, one], [zero, one, one, one], qc), gen),    # ... also over a NaN accumulator
+        (([inf, one, one, one], [one] * 4, ninf), gen),              # infinities of both signs
+        (([inf, qa, one, one], [zero, one, one, one], one), qa),     # a later operand NaN over the generated one
+        (([qa, inf, one, one], [one, zero, one, one], one), gen),    # a later invalid product over the running NaN
+        (([inf, one, one, one], [one] * 4, one), inf),               # no NaN at all: unchanged
+    ]
+    A = np.array([c[0][0] for c in cases], dtype=np.uint32).reshape(len(cases), 1, 4)
+    B = np.array([c[0][1] for c in cases], dtype=np.uint32).reshape(len(cases), 1, 4)
+    C = np.array([c[0][2] for c in cases], dtype=np.uint32).reshape(len(cases), 1, 1)
+    got2, _ = o2lib.emulate_mma(p, A, B, C, fm.FP32, fm.FP32)
+    for i, ((a, b, c), want) in enumerate(cases):
+        assert emulate_element(p, a, b, c, fm.FP32, fm.FP32) == want, (i, hex(emulate_element(p, a, b, c, fm.FP32, fm.FP32)), hex(want))
+        assert int(got2[i, 0, 0]) == want, (i, hex(int(got2[i, 0, 0])), hex(want))
+    # inside one group of several products the order is a_0, b_0, a_1, b_1, ...
+    g = ModelParams(group_len=4, frac_bits=24, nan_propagate=True, nan_bits=gen)
+    assert emulate_element(g, [one, qa, one, one], [qb, one, one, one], one, fm.FP32, fm.FP32) == qb
+    assert emulate_element(g, [one, qa, one, one], [one, one, qb, one], qc, fm.FP32, fm.FP32) == qa
+    assert emulate_element(g, [inf, one, one, one], [zero, one, one, one], qc, fm.FP32, fm.FP32) == gen
+    # without the variation: one pattern whatever the operands hold; numbers are the same either way
+    assert emulate_element(FMA.with_(nan_bits=gen), [qa, one, one, one], [one] * 4, one, fm.FP32, fm.FP32) == gen
+    rng = np.random.default_rng(91)
+    A = synth.random_bits(rng, (3, 4, 8), fm.FP32, finite=False)
+    B = synth.random_bits(rng, (3, 5, 8), fm.FP32, finite=False)
+    C = synth.random_bits(rng, (3, 4, 5), fm.FP32, finite=False)
+    A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[fm.FP32] + [qa, sa], 0.05)
+    B = synth.sprinkle(rng, B, synth.SPECIAL_CODES[fm.FP32] + [qb], 0.05)
+    for q in (p, g, g.with_(group_len=2, c_mode=C_AFTER_RD, frac_bits2=31)):
+        with_rule = emulate_mma(q, A, B, C, fm.FP32, fm.FP32)
+        plain = emulate_mma(q.with_(nan_propagate=False), A, B, C, fm.FP32, fm.FP32)
+        isnan = (plain & 0x7FFFFFFF) > 0x7F800000
+        assert np.array_equal(with_rule[~isnan], plain[~isnan]) and ((with_rule[isnan] & 0x7FFFFFFF) > 0x7F800000).all()
+        assert isnan.any() and (with_rule[isnan] != plain[isnan]).any()
+        got, _ = o2lib.emulate_mma(q, A, B, C, fm.FP32, fm.FP32)
+        assert np.array_equal(got, with_rule)
+    with pytest.raises(ValueError):
+        emulate_element(p, [0x7E00], [0x3C00], one, fm.FP16, fm.FP16)
