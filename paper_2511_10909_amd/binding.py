@@ -60,7 +60,7 @@ class ModelParams(ctypes.Structure):
                 ("struct_size", "group_len", "frac_bits", "align_round", "c_mode", "frac_bits2", "out_round",
                  "out_mant_bits", "ftz_in", "ftz_out", "nan_bits", "split", "acc_special_truncation",
                  "frac_bits_merge", "frac_bits_acc", "f2_at_leading_bit", "skip_zero_terms", "zero_result_positive",
-                 "sum_drop_distance", "family", "wide_products", "gst_group", "scale_format")]
+                 "sum_drop_distance", "family", "wide_products", "gst_group", "scale_format", "nan_propagate")]
 
 
 class Dtypes(ctypes.Structure):
@@ -162,11 +162,12 @@ def model_create(group_len=0, frac_bits=24, c_mode=C_IN_GROUP, out_round=RNE, ft
                  nan_bits=0x7FC00000, align_round=0, frac_bits2=0, out_mant_bits=23, struct_size=None,
                  split=SPLIT_NONE, acc_special_truncation=False, frac_bits_merge=0, frac_bits_acc=0,
                  f2_at_leading_bit=False, skip_zero_terms=False, zero_result_positive=False, sum_drop_distance=0,
-                 family=FAMILY_FDPA, wide_products=False, gst_group=0, scale_format=0):
+                 family=FAMILY_FDPA, wide_products=False, gst_group=0, scale_format=0, nan_propagate=False):
     p = ModelParams(ctypes.sizeof(ModelParams) if struct_size is None else struct_size, group_len, frac_bits,
                     align_round, c_mode, frac_bits2, out_round, out_mant_bits, int(ftz_in), int(ftz_out), nan_bits,
                     split, int(acc_special_truncation), frac_bits_merge, frac_bits_acc, int(f2_at_leading_bit),
-                    int(skip_zero_terms), int(zero_result_positive), sum_drop_distance, family, int(wide_products), gst_group, scale_format)
+                    int(skip_zero_terms), int(zero_result_positive), sum_drop_distance, family, int(wide_products), gst_group, scale_format,
+                    int(nan_propagate))
     h = _vp()
     _check(_lib.mmaemu_model_create(ctypes.byref(p), ctypes.byref(h)))
     return h

@@ -89,6 +89,11 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         return MMAEMU_ERR_INVALID_ARG;
     }
     if (p->family > MMAEMU_FAMILY_GST_FDPA) { set_error("model_create: family out of range"); return MMAEMU_ERR_INVALID_ARG; }
+    if (p->nan_propagate > 1) { set_error("model_create: nan_propagate must be 0 or 1"); return MMAEMU_ERR_INVALID_ARG; }
+    if (p->nan_propagate && p->family != MMAEMU_FAMILY_FDPA) {
+        set_error("model_create: nan_propagate belongs to the FDPA family");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
     if (p->family != MMAEMU_FAMILY_GST_FDPA && (p->gst_group || p->scale_format)) {
         set_error("model_create: gst_group and scale_format belong to the GST-FDPA family");
         return MMAEMU_ERR_UNSUPPORTED;
@@ -203,6 +208,10 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         return MMAEMU_ERR_UNSUPPORTED;
     }
     const mmaemu_model_params &mp = model->params;
+    if (mp.nan_propagate && !(dt.a == MMAEMU_FP32 && dt.b == MMAEMU_FP32 && dt.c == MMAEMU_FP32)) {
+        set_error("emulate_mma: nan_propagate is defined for FP32 operands and accumulators");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
     if (acc16 && (mp.family != MMAEMU_FAMILY_FDPA || mp.c_mode > MMAEMU_C_AFTER_EXACT || mp.out_mant_bits != 23)) {
         set_error("emulate_mma: FP16 accumulators go with c_mode C_IN_GROUP or C_AFTER_EXACT and the plain conversion");
         return MMAEMU_ERR_UNSUPPORTED;
@@ -298,7 +307,7 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     if (acc16) ma.nan_bits = 0x7FC00000u;             // inside the kernels the accumulator is a binary32 pattern
     ma.flags = (acc16 ? FL_ACC16 : 0u) | (ma.out_round == MMAEMU_ROUND_RZ ? FL_RZ : 0u) | (ma.ftz_out ? FL_FTZ_OUT : 0u) | (ma.zero_result_positive ? FL_ZERO_POSITIVE : 0u) |
                (ma.ftz_in ? FL_FTZ_IN : 0u) | (ma.acc_special_truncation ? FL_SPECIAL_TRUNC : 0u) | (ma.f2_at_leading_bit ? FL_F2_LEADING : 0u) |
-               (ma.skip_zero_terms ? FL_SKIP_ZERO : 0u) | (ma.wide_products ? FL_WIDE_PRODUCTS : 0u);
+               (ma.skip_zero_terms ? FL_SKIP_ZERO : 0u) | (ma.wide_products ? FL_WIDE_PRODUCTS : 0u) | (mp.nan_propagate ? FL_NAN_PROPAGATE : 0u);
     return launch_emulate(ma, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream, SA, SB, block);
 }
 

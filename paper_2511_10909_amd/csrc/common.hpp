@@ -42,7 +42,8 @@ inline bool is_byte_type(uint32_t t) { return t <= MMAEMU_FP8_E5M2 || is_narrow_
 enum : uint32_t {
     FL_RZ = 1u, FL_FTZ_OUT = 2u, FL_ZERO_POSITIVE = 4u, FL_FTZ_IN = 8u, FL_SPECIAL_TRUNC = 16u, FL_F2_LEADING = 32u,
     FL_SKIP_ZERO = 64u, FL_WIDE_PRODUCTS = 128u,
-    FL_ACC16 = 256u      // accumulator and output are binary16 (C and D hold 16-bit patterns)
+    FL_ACC16 = 256u,     // accumulator and output are binary16 (C and D hold 16-bit patterns)
+    FL_NAN_PROPAGATE = 512u   // FP32 operands: a NaN result carries an operand's payload (general kernel only)
 };
 
 // Model parameters as the kernels take them (by value).

@@ -240,6 +240,20 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const FTA &fa, const FTB &fb,
             if (sr.sa[q] == 0xFFu || sr.sb[q] == 0xFFu) return p.nan_bits;
     }
 
+    if (p.flags & FL_NAN_PROPAGATE) {
+        // the payload variation, in its order of precedence (FP32 operands: the element is the binary32 pattern);
+        // what it leaves is handled below as usual
+        for (uint32_t k = 0; k < L; ++k) {
+            const uint32_t xa = fa.load(a, k), xb = fb.load(b, k);
+            if (decode_as(fa, xa, p.ftz_in).cls == CLS_NAN) return xa | 0x00400000u;
+            if (decode_as(fb, xb, p.ftz_in).cls == CLS_NAN) return xb | 0x00400000u;
+        }
+        for (uint32_t k = 0; k < L; ++k) {
+            const Dec x = decode_as(fa, fa.load(a, k), p.ftz_in), y = decode_as(fb, fb.load(b, k), p.ftz_in);
+            if ((x.cls == CLS_INF && y.cls == CLS_ZERO) || (y.cls == CLS_INF && x.cls == CLS_ZERO)) return p.nan_bits;
+        }
+        if (dc.cls == CLS_NAN) return c | 0x00400000u;
+    }
     // special values (Sec. 4.2)
     bool any_nan = dc.cls == CLS_NAN, pinf = false, ninf = false;
     for (uint32_t k = 0; k < L; ++k) {

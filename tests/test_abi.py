@@ -40,7 +40,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_sizes_match_binding():
     from paper_2511_10909_amd import binding as mm
-    assert ctypes.sizeof(mm.ModelParams) == 92
+    assert ctypes.sizeof(mm.ModelParams) == 96
     assert ctypes.sizeof(mm.Stats) == 8 * 39
     assert ctypes.sizeof(mm.ErrStats) == 8 * 44
     assert ctypes.sizeof(mm.GenParams) == 48

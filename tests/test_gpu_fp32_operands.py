@@ -99,3 +99,37 @@ def test_fp32_argument_errors(mm):
     with pytest.raises(mm.MmaemuError) as ei:
         mm.model_create(group_len=4, frac_bits=44, frac_bits2=31, c_mode=mm.C_AFTER_RD)       # the RD modes stop at 40
     assert ei.value.status == 2
+
+
+def test_nan_payload_rule_matches_oracle(mm):
+    # `nan_propagate`: NaN results carry payloads (first NaN operand in the order a_0, b_0, a_1, ..., made quiet; the
+    # model's own pattern for invalid products; then the accumulator)
+    rng = np.random.default_rng(4103)
+    qa, sa, qb = 0x7FC00AAA, 0x7F800AAA, 0xFFC00BBB
+    for trial in range(8):
+        L = int(rng.choice([1, 1, 2, 4]))
+        k = L * int(rng.integers(1, 5))
+        cm = C_AFTER_EXACT if L == 1 else int(rng.choice([C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD]))
+        p = ModelParams(group_len=L, frac_bits=46 if (L == 1) else 24, c_mode=cm, nan_bits=0xFFC00000, nan_propagate=True,
+                        ftz_in=bool(trial % 2))
+        if cm == C_AFTER_RD:
+            p = p.with_(frac_bits2=31)
+        nb, m, n = 3, int(rng.integers(1, 24)), int(rng.integers(1, 24))
+        A = synth.random_bits(rng, (nb, m, k), fm.FP32, finite=False)
+        B = synth.random_bits(rng, (nb, n, k), fm.FP32, finite=False)
+        C = synth.random_bits(rng, (nb, m, n), fm.FP32, finite=False)
+        A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[fm.FP32] + [qa, sa], 0.06)
+        B = synth.sprinkle(rng, B, synth.SPECIAL_CODES[fm.FP32] + [qb], 0.06)
+        C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32] + [0x7FC00CCC], 0.06)
+        print("case", trial, p, (nb, m, n, k), flush=True)
+        want, _ = o2lib.emulate_mma(p, A, B, C, fm.FP32, fm.FP32)
+        got = gpu_emulate(mm, p, A, B, C, fm.FP32, fm.FP32)
+        assert_same(got, want, "payload rule, trial %d" % trial)
+        assert ((want & 0x7FFFFFFF) > 0x7F800000).any() and (want != o2lib.emulate_mma(p.with_(nan_propagate=False), A, B, C, fm.FP32, fm.FP32)[0]).any()
+    h = mm.model_create(group_len=1, frac_bits=24, c_mode=mm.C_AFTER_EXACT, nan_propagate=True)
+    from gpu_utils import dev_empty
+    x = dev_empty(4096)
+    with pytest.raises(mm.MmaemuError) as ei:
+        mm.emulate_mma(h, x, x, x, x, 4, 4, 4, 1, (mm.BF16, mm.BF16, mm.FP32, mm.FP32))           # FP32 operands only
+    assert ei.value.status == 2
+    mm.model_destroy(h)
