@@ -351,7 +351,19 @@ typedef enum {
     MMAEMU_MFMA_F32_32X32X2_F32 = 42,
     /* v_mfma_scale_f32_32x32x64_f8f6f4, numbered like the 16x16x128 form: id = BASE + 5 fa + fb (43 .. 67) */
     MMAEMU_MFMA_SCALE_F32_32X32X64_F8F6F4_BASE = 43,
-    MMAEMU_MFMA_COUNT = 68
+    /* multi-block forms: one issue computes 64 / m independent m x m x k products (2, 4 or 16 "blocks").  Through
+     * mmaemu_mfma_probe a block is a tile: tiles 0 .. 64/m - 1 go through the first issue, and so on; the blocks of a
+     * last, partial issue beyond `batch` are fed zeros and not stored. */
+    MMAEMU_MFMA_F32_32X32X4_2B_F16 = 68,
+    MMAEMU_MFMA_F32_16X16X4_4B_F16 = 69,
+    MMAEMU_MFMA_F32_4X4X4_16B_F16 = 70,
+    MMAEMU_MFMA_F32_32X32X4_2B_BF16 = 71, /* the _1k forms (four BF16 values per lane) */
+    MMAEMU_MFMA_F32_16X16X4_4B_BF16 = 72,
+    MMAEMU_MFMA_F32_4X4X4_16B_BF16 = 73,
+    MMAEMU_MFMA_F32_32X32X1_2B_F32 = 74,
+    MMAEMU_MFMA_F32_16X16X1_4B_F32 = 75,
+    MMAEMU_MFMA_F32_4X4X1_16B_F32 = 76,
+    MMAEMU_MFMA_COUNT = 77
 } mmaemu_mfma_instr;
 
 /* Shape and operand types of an instruction (host-side query). */

@@ -44,7 +44,9 @@ MFMA_SCALE32_IDS = tuple(range(43, 68))
 (MFMA_F32_32X32X16_F16, MFMA_F32_32X32X16_BF16, MFMA_F32_32X32X16_FP8_FP8, MFMA_F32_32X32X16_FP8_BF8,
  MFMA_F32_32X32X16_BF8_FP8, MFMA_F32_32X32X16_BF8_BF8) = range(35, 41)
 MFMA_F32_16X16X4_F32, MFMA_F32_32X32X2_F32 = 41, 42
-MFMA_UNSCALED_IDS = tuple(range(10)) + tuple(range(35, 43))
+# multi-block forms (one issue = 64 / m tiles): 32x32x4_2b, 16x16x4_4b, 4x4x4_16b for FP16 and BF16; 32x32x1_2b, 16x16x1_4b, 4x4x1_16b for FP32
+MFMA_MULTIBLOCK_F16_IDS, MFMA_MULTIBLOCK_BF16_IDS, MFMA_MULTIBLOCK_F32_IDS = (68, 69, 70), (71, 72, 73), (74, 75, 76)
+MFMA_UNSCALED_IDS = tuple(range(10)) + tuple(range(35, 43)) + tuple(range(68, 77))
 ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1, TF32: 4}
 NO_MISMATCH = (1 << 64) - 1
 

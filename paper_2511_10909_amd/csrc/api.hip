@@ -400,12 +400,22 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
 static bool is_scaled_instr(uint32_t i)
 {
     return (i >= MMAEMU_MFMA_SCALE_F32_16X16X128_F8F6F4_BASE && i < MMAEMU_MFMA_F32_32X32X16_F16) ||
-           (i >= MMAEMU_MFMA_SCALE_F32_32X32X64_F8F6F4_BASE && i < MMAEMU_MFMA_COUNT);
+           (i >= MMAEMU_MFMA_SCALE_F32_32X32X64_F8F6F4_BASE && i < MMAEMU_MFMA_F32_32X32X4_2B_F16);
 }
 
 mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n, uint32_t *k_native, mmaemu_dtype *a,
                                mmaemu_dtype *b)
 {
+    if ((uint32_t)instr >= MMAEMU_MFMA_F32_32X32X4_2B_F16 && (uint32_t)instr < MMAEMU_MFMA_COUNT) {     // multi-block forms
+        const uint32_t q = (uint32_t)instr - MMAEMU_MFMA_F32_32X32X4_2B_F16, shape = q % 3, type = q / 3;
+        const uint32_t mm_ = shape == 0 ? 32u : (shape == 1 ? 16u : 4u);
+        if (m) *m = mm_;
+        if (n) *n = mm_;
+        if (k_native) *k_native = type == 2 ? 1u : 4u;
+        if (a) *a = type == 0 ? MMAEMU_FP16 : (type == 1 ? MMAEMU_BF16 : MMAEMU_FP32);
+        if (b) *b = type == 0 ? MMAEMU_FP16 : (type == 1 ? MMAEMU_BF16 : MMAEMU_FP32);
+        return MMAEMU_OK;
+    }
     if ((uint32_t)instr == MMAEMU_MFMA_F32_16X16X4_F32 || (uint32_t)instr == MMAEMU_MFMA_F32_32X32X2_F32) {
         const bool small = (uint32_t)instr == MMAEMU_MFMA_F32_16X16X4_F32;
         if (m) *m = small ? 16 : 32;

@@ -158,6 +158,81 @@ mfma_probe_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, 
     }
 }
 
+// ---- multi-block forms: one issue computes NB = 64 / M independent M x M x K products; a block is a tile ----------
+// Register layout (found from the single-block forms by analogy, then fixed by exact small-integer tests), l = lane:
+//   A: row i = l % M of block l / M, its K elements in k order (same for B with column j);
+//   C/D register r:  M = 32: block r / 16, row 8 ((r % 16) / 4) + 4 (l / 32) + r % 4, column l % 32;
+//                    M = 16: block r / 4,  row 4 (l / 16) + r % 4,                   column l % 16;
+//                    M = 4:  block l / 4,  row r,                                     column l % 4.
+typedef float v32f32 __attribute__((ext_vector_type(32)));
+
+template <int M, int TYPE>      // TYPE 0: FP16, 1: BF16 (_1k), 2: FP32
+__global__ void __launch_bounds__(256)
+mfma_multiblock_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const float *C, float *D, uint32_t k, uint64_t batch)
+{
+    constexpr int NB = 64 / M, KN = TYPE == 2 ? 1 : 4, EB = TYPE == 2 ? 4 : 2, NR = M * M * NB / 64;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const uint64_t nwaves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    const uint64_t issues = (batch + NB - 1) / NB;
+    for (uint64_t w = wave; w < issues; w += nwaves) {
+        const uint64_t t0 = w * NB;
+        const uint32_t rc = lane % M;
+        const uint64_t ta = t0 + lane / M;                      // the tile whose row of A / column of B this lane holds
+        uint32_t ra[4] = {0u, 0u, 0u, 0u}, rb[4] = {0u, 0u, 0u, 0u};
+        if (ta < batch) {
+            load_row_slice<KN, EB>(A + ((ta * M + rc) * (uint64_t)k) * EB, 0, k, ra);
+            load_row_slice<KN, EB>(B + ((ta * M + rc) * (uint64_t)k) * EB, 0, k, rb);
+        }
+        typedef float vacc __attribute__((ext_vector_type(NR)));
+        vacc acc;
+        uint64_t tile[NR]; uint32_t off[NR];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            uint32_t bb, ii, jj;
+            if (M == 32) { bb = r / 16; ii = 8 * ((r % 16) / 4) + 4 * (lane / 32) + r % 4; jj = lane % 32; }
+            else if (M == 16) { bb = r / 4; ii = 4 * (lane / 16) + r % 4; jj = lane % 16; }
+            else { bb = lane / 4; ii = r; jj = lane % 4; }
+            tile[r] = t0 + bb;
+            off[r] = ii * M + jj;
+            acc[r] = tile[r] < batch ? C[tile[r] * (uint64_t)(M * M) + off[r]] : 0.0f;
+        }
+        if constexpr (TYPE == 2) {
+            const float a = __uint_as_float(ra[0]), b = __uint_as_float(rb[0]);
+            if constexpr (M == 32) acc = __builtin_amdgcn_mfma_f32_32x32x1f32(a, b, acc, 0, 0, 0);
+            else if constexpr (M == 16) acc = __builtin_amdgcn_mfma_f32_16x16x1f32(a, b, acc, 0, 0, 0);
+            else acc = __builtin_amdgcn_mfma_f32_4x4x1f32(a, b, acc, 0, 0, 0);
+        } else if constexpr (TYPE == 0) {
+            v4f16 a, b;
+            __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+            if constexpr (M == 32) acc = __builtin_amdgcn_mfma_f32_32x32x4f16(a, b, acc, 0, 0, 0);
+            else if constexpr (M == 16) acc = __builtin_amdgcn_mfma_f32_16x16x4f16(a, b, acc, 0, 0, 0);
+            else acc = __builtin_amdgcn_mfma_f32_4x4x4f16(a, b, acc, 0, 0, 0);
+        } else {
+            v4i16 a, b;
+            __builtin_memcpy(&a, ra, 8); __builtin_memcpy(&b, rb, 8);
+            if constexpr (M == 32) acc = __builtin_amdgcn_mfma_f32_32x32x4bf16_1k(a, b, acc, 0, 0, 0);
+            else if constexpr (M == 16) acc = __builtin_amdgcn_mfma_f32_16x16x4bf16_1k(a, b, acc, 0, 0, 0);
+            else acc = __builtin_amdgcn_mfma_f32_4x4x4bf16_1k(a, b, acc, 0, 0, 0);
+        }
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+            if (tile[r] < batch) D[tile[r] * (uint64_t)(M * M) + off[r]] = acc[r];
+    }
+}
+
+template <int M, int TYPE>
+static mmaemu_status launch_mb(const void *A, const void *B, const void *C, void *D, uint32_t k, uint64_t batch, hipStream_t s)
+{
+    const uint64_t issues = (batch + 64 / M - 1) / (64 / M);
+    uint64_t blocks = (issues + 3) / 4;                  // 4 wavefronts (issues) per workgroup
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL((mfma_multiblock_kernel<M, TYPE>), dim3((uint32_t)blocks), dim3(256), 0, s, (const uint8_t *)A,
+                       (const uint8_t *)B, (const float *)C, (float *)D, k, batch);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
 template <int INSTR>
 static mmaemu_status launch_i(const void *A, const void *B, const void *C, void *D, uint32_t k, uint64_t batch,
                               hipStream_t s)
@@ -194,6 +269,15 @@ mmaemu_status launch_mfma_probe(uint32_t instr, const void *A, const void *B, co
         CASE(MMAEMU_MFMA_F32_16X16X4_F32);
         CASE(MMAEMU_MFMA_F32_32X32X2_F32);
 #undef CASE
+    case MMAEMU_MFMA_F32_32X32X4_2B_F16: return launch_mb<32, 0>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_16X16X4_4B_F16: return launch_mb<16, 0>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_4X4X4_16B_F16: return launch_mb<4, 0>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_32X32X4_2B_BF16: return launch_mb<32, 1>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_16X16X4_4B_BF16: return launch_mb<16, 1>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_4X4X4_16B_BF16: return launch_mb<4, 1>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_32X32X1_2B_F32: return launch_mb<32, 2>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_16X16X1_4B_F32: return launch_mb<16, 2>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F32_4X4X1_16B_F32: return launch_mb<4, 2>(A, B, C, D, k, batch, s);
     default:
         set_error("unknown mfma instruction %u", instr);
         return MMAEMU_ERR_INVALID_ARG;

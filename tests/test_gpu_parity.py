@@ -250,7 +250,10 @@ MFMA_TYPES = {0: (fm.FP16, fm.FP16), 1: (fm.BF16, fm.BF16), 2: (fm.FP16, fm.FP16
               4: (fm.FP16, fm.FP16), 5: (fm.BF16, fm.BF16), 6: (fm.E4M3, fm.E4M3), 7: (fm.E4M3, fm.E5M2),
               8: (fm.E5M2, fm.E4M3), 9: (fm.E5M2, fm.E5M2),
               35: (fm.FP16, fm.FP16), 36: (fm.BF16, fm.BF16), 37: (fm.E4M3, fm.E4M3), 38: (fm.E4M3, fm.E5M2),
-              39: (fm.E5M2, fm.E4M3), 40: (fm.E5M2, fm.E5M2)}
+              39: (fm.E5M2, fm.E4M3), 40: (fm.E5M2, fm.E5M2), 41: (fm.FP32, fm.FP32), 42: (fm.FP32, fm.FP32),
+              # multi-block forms (2, 4 or 16 tiles per issue; seven tiles: the last issue is a partial one)
+              68: (fm.FP16, fm.FP16), 69: (fm.FP16, fm.FP16), 70: (fm.FP16, fm.FP16), 71: (fm.BF16, fm.BF16), 72: (fm.BF16, fm.BF16),
+              73: (fm.BF16, fm.BF16), 74: (fm.FP32, fm.FP32), 75: (fm.FP32, fm.FP32), 76: (fm.FP32, fm.FP32)}
 
 
 def _small_int_codes(rng, shape, t):
@@ -276,8 +279,8 @@ def test_mfma_probe_register_layout(mm, instr):
     assert (info["a"], info["b"]) == (ta, tb)
     M, N, KN = info["m"], info["n"], info["k"]
     rng = np.random.default_rng(instr)
-    for k in (KN, KN // 2, 3):
-        nb = 7
+    for k in sorted({q for q in (KN, KN // 2, 3) if 1 <= q <= KN}):
+        nb = 7 if instr < 68 else 37
         A, av = _small_int_codes(rng, (nb, M, k), ta)
         B, bv = _small_int_codes(rng, (nb, N, k), tb)
         cv = rng.integers(-100, 100, size=(nb, M, N))
