@@ -1,13 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path: generate -> emulate (two models) -> compare, on one MI355X.
 
-Workload (the second configuration of the build's baseline list): bf16 A/B, fp32 C/D GEMM with
+Workload: bf16 A/B, fp32 C/D GEMM with
 m = n = k = 1024; A, B ~ N(0,1) cast to bf16, C = 0; model 0 accumulates in fused groups of 8
 products, each group added to the running fp32 sum with RNE (c_mode = C_AFTER_EXACT, F = 24);
 model 1 is the fully fused model of the same shape (L = K = 1024, F = 24, RNE); the step ends
 with the bitwise comparison of the two outputs.  One step = 2 * 1024^3 emulated MAC terms.
 
-Prints ONE JSON line.  `--gpus N` with N > 1 is refused: this build is single-GPU.
+Prints ONE JSON line.  `--gpus N` with N > 1 is refused: the library runs on one GPU.
 """
 import argparse
 import json
@@ -69,8 +69,8 @@ def cpu_baseline(size, target_seconds):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (tiles and D elements are independent; see DESIGN.md for how "
-              "the path would shard); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        print("bench.py: this benchmark runs on ONE GPU (tiles and D elements are independent, so the path would shard by "
+              "tile range); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():

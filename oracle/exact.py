@@ -5,7 +5,7 @@ Methodology after the paper's accuracy study (Sec. 6.2.4: deviation
 delta = D_model - D_real of a model's output from the real result), with the real
 result taken as the exact rational c + sum_k a_k b_k rather than an FP64 product.
 
-Sampling rule (this build's definition): flattened output index i*n + j is sampled
+Sampling rule (this library's definition): flattened output index i*n + j is sampled
 when it is a multiple of `stride`.
 
 Per sample, with R = RNE-FP32(exact):

@@ -3,7 +3,7 @@ Test infrastructure: see oracle/__init__.py.
 
 The paper's randomized validation (Sec. 3.1, Step 4) draws inputs from common
 distributions and from random bit streams; it fixes no generator.  This file is
-this build's definition, stated so that an integer-exact twin can exist on the
+this library's definition, stated so that an integer-exact twin can exist on the
 device:
 
 Random words.  Element with global index g = (first_tile + t) * elems_per_tile + e

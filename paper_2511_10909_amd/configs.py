@@ -2,8 +2,7 @@
 computation inside the library).  Each runner returns a dict of results; tensors it leaves
 on the device are returned under "dev" so that tests can check them against the CPU oracle.
 
-Workloads (synthetic stand-ins for the randomized validation of the paper's Sec. 3.1 Step 4;
-recipes in DESIGN.md):
+Workloads (synthetic stand-ins for the randomized validation of the paper's Sec. 3.1 Step 4):
   config1  10,000 fp16 16x16x16 tiles, uniform finite bit patterns, C ~ N(0,1); F = 27, L = 16,
            RNE against RZ output
   config2  bf16 1024^3 GEMM, N(0,1) operands, C = 0; groups of 8 added exactly to the running
