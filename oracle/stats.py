@@ -2,7 +2,7 @@
 
 The paper's requirement is bit-for-bit equality of model and interface outputs
 (Eq. 2, and Step 4 of Sec. 3.1).  The statistics kept per comparison are this
-build's own definition:
+library's own definition:
 
   n_compared            number of element pairs
   n_mismatch_bits       pairs whose 32-bit patterns differ
