@@ -806,10 +806,12 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                     v[r][c] = rd_value(T, have_T, emax[r][c], F, d[r][c]);
                 }
         } else {
-            // d = rho(T 2^unit + c) with the two-term sum exact: s = RN(a + c) and its exact
-            // error (Knuth's TwoSum); an inexact s is then rounded to odd (truncated toward
-            // zero, last bit set), which the conversion below cannot tell from the exact sum
-            double err[R][C];
+            // d = rho(T 2^unit + c) with the two-term sum exact.  s = RN(a + c) is that sum unless it was rounded, and
+            // it was not exactly when bb = RN(s - a) equals c and RN(s - bb) equals a: the difference of s and the
+            // larger of the two operands is always representable, so one of the two tests compares exact
+            // quantities and the other then does as well.  Only an inexact s (rare: the operands lie more than 29
+            // binary places apart) needs its error term (Knuth's TwoSum); it is then rounded to odd (truncated
+            // toward zero, last bit set), which the conversion below cannot tell from the exact sum.
             bool inexact = false;
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -820,21 +822,26 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                     const double cd = (double)__uint_as_float(d[r][c]);
                     const double s = a + cd;
                     const double bb = s - a;
-                    err[r][c] = (a - (s - bb)) + (cd - bb);
                     v[r][c] = s;
-                    inexact |= __builtin_fabs(err[r][c]) > 0.0;        // false for NaN (infinite operands)
+                    inexact |= (bb != cd) || ((s - bb) != a);          // (true for NaN: infinite operands)
                 }
             if (inexact) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int c = 0; c < C; ++c)
-                        if (__builtin_fabs(err[r][c]) > 0.0) {
-                            long long sb = __double_as_longlong(v[r][c]);
-                            const bool toward_zero = (err[r][c] < 0.0) != (v[r][c] < 0.0);   // true value nearer zero
+                    for (int c = 0; c < C; ++c) {
+                        const double T = USE_SD ? Sd[r][c] + (double)S32[r][c] : (double)S32[r][c];
+                        const double a = ldexp(T, emax[r][c] - F);
+                        const double cd = (double)__uint_as_float(d[r][c]);
+                        const double s = v[r][c], bb = s - a;
+                        const double err = (a - (s - bb)) + (cd - bb);
+                        if (__builtin_fabs(err) > 0.0) {                // (false for NaN)
+                            long long sb = __double_as_longlong(s);
+                            const bool toward_zero = (err < 0.0) != (s < 0.0);               // true value nearer zero
                             sb -= toward_zero ? 1 : 0;
                             v[r][c] = __longlong_as_double(sb | 1ll);
                         }
+                    }
             }
         }
         finish_group(kg, v, m2, tagged);
