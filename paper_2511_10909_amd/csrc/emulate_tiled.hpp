@@ -1055,7 +1055,11 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                     finish_group(k0 + g * LT, v, tg, tagged);
                 }
             } else {
-#pragma unroll 1
+                // (the groups of a chunk unrolled for the 2 x 2 kernels of the T-FDPA modes: their LDS addresses become
+                // immediate offsets, -3.5 % on the headline kernel; the 4 x 4 kernels' bodies are too large for that to
+                // pay, and some RD kernels lose a wave of occupancy to it)
+                constexpr int GU = (R * C <= 4 && KC / GL <= 4 && CMODE != MMAEMU_C_AFTER_RD) ? KC / GL : 1;
+#pragma unroll GU
                 for (int g = 0; g < KC / GL; ++g) {
                     reset_group();
                     load_scales(k0 + g * GL);
