@@ -23,7 +23,7 @@ ALGO_OPS_PER_TERM = 8                       # accounting floor of INT32 VALU ins
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (scaled by a copy kernel
 # of known size; see profiles/emulate_tiled_bf16_gemm1024_hbm_counters.md).  Valid only for the kernel variant and
 # problem size it was measured on: any other variant reports null.
-MEASURED_TRAFFIC = {("tiled 32x32 r2x2 kc=32 L=8 c_mode=1 fold=0 vm=1", 1024): (11394.0 * 2.00 + 4096.0) * 1024.0}
+MEASURED_TRAFFIC = {("tiled 32x32 r2x2 kc=32 L=8 c_mode=1 fold=0 vm=1", 1024): (11487.0 * 2.00 + 4096.0) * 1024.0}
 
 
 def parse():
