@@ -12,6 +12,7 @@ fdpa.py      the model: chained fused-dot-product-add with truncated alignment
              (paper Sec. 4.1.3, Algorithms "Phi_FDPA", "E-FDPA", "T-FDPA"), special
              values (Sec. 4.2), input/output subnormal flush (Algorithms
              "FTZ-Add/FTZ-Mul" and "Phi_FTZ-AddMul")
+fma.py       the model built from the standard fused multiply-add (Sec. 4.1.2, Algorithms "FMA", "Phi_FMA")
 exact.py     exact rational dot products and error statistics
 stats.py     bitwise comparison statistics (Eq. 2 of the paper: Phi(A,B,C) == interface(A,B,C))
 philox.py    Philox-4x32-10 counter-based generator (Salmon et al., SC'11)
