@@ -79,7 +79,7 @@ enum { MMAEMU_C_IN_GROUP = 0, MMAEMU_C_AFTER_EXACT = 1, MMAEMU_C_AFTER_RD = 2, M
 enum { MMAEMU_ROUND_RNE = 0, MMAEMU_ROUND_RZ = 1 };
 enum { MMAEMU_ALIGN_RZ = 0 };
 enum { MMAEMU_SPLIT_NONE = 0, MMAEMU_SPLIT_EVEN_ODD = 1, MMAEMU_SPLIT_HALVES = 2, MMAEMU_SPLIT_QUARTERS = 3 };
-enum { MMAEMU_FAMILY_FDPA = 0, MMAEMU_FAMILY_FTZ_ADDMUL = 1, MMAEMU_FAMILY_GST_FDPA = 2 };
+enum { MMAEMU_FAMILY_FDPA = 0, MMAEMU_FAMILY_FTZ_ADDMUL = 1, MMAEMU_FAMILY_GST_FDPA = 2, MMAEMU_FAMILY_FMA = 3 };
 enum { MMAEMU_SCALE_FORMAT_E8M0 = 0, MMAEMU_SCALE_FORMAT_UE4M3 = 1 };
 
 /*
@@ -141,9 +141,16 @@ enum { MMAEMU_SCALE_FORMAT_E8M0 = 0, MMAEMU_SCALE_FORMAT_UE4M3 = 1 };
  *   consecutive products are summed pairwise, and c and the K/P partial sums sequentially.
  *   Only group_len and nan_bits are used; the FDPA fields must hold their defaults
  *   (frac_bits is ignored).  K must be a multiple of P.
- *   (A chain of fused multiply-adds, Algorithm "Phi_FMA", is group_len = 1 with
- *   c_mode = C_AFTER_EXACT in the FDPA family: the product of two operands of at most 11
- *   significant bits is exact.)
+ *
+ * family = MMAEMU_FAMILY_FMA is Algorithm "Phi_FMA" (Sec. 4.1.2) on FP32 operands and accumulators: d <- c, then
+ *   d <- FMA(a_k, b_k, d) for k = 0 .. K - 1 in order, each step the standard fused multiply-add of Algorithm "FMA":
+ *   a b + d as if to infinite precision, rounded once to binary32, ties to even; subnormal inputs and results kept;
+ *   overflow gives infinity.  The sign of an exact zero is IEEE-754's: +0.0, except that a zero product and a zero
+ *   accumulator of the same sign keep that sign.  Special values as in Sec. 4.2 (every NaN result is nan_bits), or with
+ *   nan_propagate the payload rule described at that field, applied per step.  Uses nan_bits and nan_propagate only;
+ *   group_len must be 0 or 1 and every other field must hold its default (frac_bits is ignored).
+ *   (The FDPA family with group_len = 1, c_mode = C_AFTER_EXACT and frac_bits wide enough for the whole product, 46
+ *   for FP32 operands, computes the same chain except for that sign: there an exact zero is always +0.0.)
  *
  * family = MMAEMU_FAMILY_GST_FDPA is Algorithm "GST-FDPA" (Sec. 4.1.3), through mmaemu_emulate_mma_scaled only, FP4 (E2M1)
  *   operands on both sides: per operation of L = group_len products, every gst_group (G) consecutive products form an
@@ -184,8 +191,8 @@ typedef struct {
     uint32_t gst_group;              /* G; MMAEMU_FAMILY_GST_FDPA only */
     uint32_t scale_format;           /* MMAEMU_SCALE_FORMAT_*; MMAEMU_FAMILY_GST_FDPA only */
     uint32_t nan_propagate;          /* 0 / 1.  Variation of the special-value rules (Sec. 4.2) for FP32 operands with an
-                                        FP32 accumulator (MMAEMU_FAMILY_FDPA; other types: MMAEMU_ERR_UNSUPPORTED at
-                                        the call): a NaN result is not the one pattern nan_bits but, in this order of
+                                        FP32 accumulator (MMAEMU_FAMILY_FDPA and MMAEMU_FAMILY_FMA; other types:
+                                        MMAEMU_ERR_UNSUPPORTED at the call): a NaN result is not the one pattern nan_bits but, in this order of
                                         precedence, the first NaN operand in the order a_0, b_0, a_1, b_1, ... of the
                                         group, made quiet (mantissa bit 22 set, sign and payload kept); else nan_bits
                                         if some product is infinity times zero; else a NaN accumulator, made quiet;
@@ -207,9 +214,10 @@ mmaemu_status mmaemu_model_get_params(const mmaemu_model *model, mmaemu_model_pa
 /*
  * D = Phi_model(A, B, C) for `batch` independent m x n x k tiles (paper Eq. 1 / Eq. 3:
  * every d_ij is an independent dot-product-accumulate).  D may alias C; D may not
- * overlap A or B.  batch = 0 is a no-op.
+ * overlap A or B.  Pointers aligned to their element size (the tiled kernels are taken when A and B are
+ * 8-byte aligned).  batch = 0 is a no-op.
  * Errors: SHAPE (m, n or k zero; k > 2^20; k % L != 0; m*n or batch*m*n overflow),
- *         UNSUPPORTED (dtype combination), INVALID_ARG, HIP.
+ *         UNSUPPORTED (dtype combination), INVALID_ARG (NULL or misaligned pointer, bad handle), HIP.
  */
 mmaemu_status mmaemu_emulate_mma(const mmaemu_model *model, const void *A, const void *B,
                                  const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,

@@ -15,7 +15,7 @@ TF32 = 9                                        # binary32 words whose low 13 ma
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
 RNE, RZ = 0, 1
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
-FAMILY_FDPA, FAMILY_FTZ_ADDMUL, FAMILY_GST_FDPA = 0, 1, 2
+FAMILY_FDPA, FAMILY_FTZ_ADDMUL, FAMILY_GST_FDPA, FAMILY_FMA = 0, 1, 2, 3
 SCALE_FORMAT_E8M0, SCALE_FORMAT_UE4M3 = 0, 1
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
 GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING = 5, 6, 7

@@ -88,10 +88,10 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: enum field out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if (p->family > MMAEMU_FAMILY_GST_FDPA) { set_error("model_create: family out of range"); return MMAEMU_ERR_INVALID_ARG; }
+    if (p->family > MMAEMU_FAMILY_FMA) { set_error("model_create: family out of range"); return MMAEMU_ERR_INVALID_ARG; }
     if (p->nan_propagate > 1) { set_error("model_create: nan_propagate must be 0 or 1"); return MMAEMU_ERR_INVALID_ARG; }
-    if (p->nan_propagate && p->family != MMAEMU_FAMILY_FDPA) {
-        set_error("model_create: nan_propagate belongs to the FDPA family");
+    if (p->nan_propagate && p->family != MMAEMU_FAMILY_FDPA && p->family != MMAEMU_FAMILY_FMA) {
+        set_error("model_create: nan_propagate belongs to the FDPA and FMA families");
         return MMAEMU_ERR_UNSUPPORTED;
     }
     if (p->family != MMAEMU_FAMILY_GST_FDPA && (p->gst_group || p->scale_format)) {
@@ -120,6 +120,14 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
             p->split || p->acc_special_truncation || p->frac_bits_merge || p->frac_bits_acc || p->f2_at_leading_bit ||
             p->skip_zero_terms || p->zero_result_positive || p->sum_drop_distance || p->wide_products) {
             set_error("model_create: the FTZ-AddMul family takes group_len and nan_bits only");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+    }
+    if (p->family == MMAEMU_FAMILY_FMA) {
+        if (p->group_len > 1 || p->align_round || p->c_mode || p->frac_bits2 || p->out_round || p->out_mant_bits != 23 || p->ftz_in ||
+            p->ftz_out || p->split || p->acc_special_truncation || p->frac_bits_merge || p->frac_bits_acc || p->f2_at_leading_bit ||
+            p->skip_zero_terms || p->zero_result_positive || p->sum_drop_distance || p->wide_products) {
+            set_error("model_create: the FMA family takes nan_bits and nan_propagate only (group_len 0 or 1)");
             return MMAEMU_ERR_UNSUPPORTED;
         }
     }
@@ -216,6 +224,11 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         set_error("emulate_mma: FP16 accumulators go with c_mode C_IN_GROUP or C_AFTER_EXACT and the plain conversion");
         return MMAEMU_ERR_UNSUPPORTED;
     }
+    const uintptr_t ab_mask = (uintptr_t)(fmt_info(dt.a).width / 8 - 1) | (uintptr_t)(fmt_info(dt.b).width / 8 - 1);
+    if ((((uintptr_t)A | (uintptr_t)B) & ab_mask) || (((uintptr_t)C | (uintptr_t)D) & (acc16 ? 1u : 3u))) {
+        set_error("emulate_mma: pointers must be aligned to their element size");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
     if (SA && mp.family == MMAEMU_FAMILY_FTZ_ADDMUL) { set_error("emulate_mma_scaled: block scales belong to the FDPA families"); return MMAEMU_ERR_UNSUPPORTED; }
     if (mp.family == MMAEMU_FAMILY_GST_FDPA) {
         if (batch == 0) return MMAEMU_OK;
@@ -232,6 +245,21 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         if (!A || !B || !C || !D) { set_error("emulate_mma: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
         const GstArgs ga = {Lg, mp.gst_group, block, mp.frac_bits, mp.out_round, mp.scale_format, mp.nan_bits};
         return launch_emulate_gst(ga, A, B, C, D, SA, SB, m, n, k, batch, (hipStream_t)hip_stream);
+    }
+    if (mp.family == MMAEMU_FAMILY_FMA) {
+        if (SA) { set_error("emulate_mma_scaled: block scales belong to the FDPA families"); return MMAEMU_ERR_UNSUPPORTED; }
+        if (dt.a != MMAEMU_FP32 || dt.b != MMAEMU_FP32 || dt.c != MMAEMU_FP32 || dt.d != MMAEMU_FP32) {
+            set_error("emulate_mma: the FMA family takes FP32 operands and accumulators");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        const uint64_t mn_ = (uint64_t)m * n;
+        if (batch && (mn_ > (1ull << 40) || batch > (1ull << 62) / mn_ || batch * mn_ > (1ull << 48))) {
+            set_error("emulate_mma: problem too large");
+            return MMAEMU_ERR_SHAPE;
+        }
+        if (batch == 0) return MMAEMU_OK;
+        if (!A || !B || !C || !D) { set_error("emulate_mma: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+        return launch_emulate_fma(A, B, C, D, m, n, k, batch, mp.nan_bits, mp.nan_propagate != 0, (hipStream_t)hip_stream);
     }
     if (mp.family == MMAEMU_FAMILY_FTZ_ADDMUL && (is_narrow_type(dt.a) || is_narrow_type(dt.b) || is_word_type(dt.a))) {
         set_error("emulate_mma: the FTZ-AddMul family takes FP8, FP16 and BF16 operands");

@@ -87,6 +87,9 @@ mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const vo
 mmaemu_status launch_emulate_addmul(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                     uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                     uint32_t tb, hipStream_t s);
+// Algorithm "Phi_FMA": binary32 operands and accumulators, a chain of fused multiply-adds in k order
+mmaemu_status launch_emulate_fma(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                                 uint64_t batch, uint32_t nan_bits, bool nan_propagate, hipStream_t s);
 // Algorithm "GST-FDPA": FP4 operands, scale codes SA / SB per `block` elements (L, G, F, rho, NaN pattern, scale format)
 struct GstArgs { uint32_t L, G, block, F, out_round, scale_format, nan_bits; };
 mmaemu_status launch_emulate_gst(const GstArgs &g, const void *A, const void *B, const void *C, void *D, const uint8_t *SA,

@@ -1,0 +1,115 @@
+// The model built from the standard fused multiply-add (paper Sec. 4.1.2): Algorithm "Phi_FMA" around Algorithm
+// "FMA", binary32 operands and accumulators.  One thread per output element runs the chain d <- FMA(a_k, b_k, d) in
+// k order.
+//
+// The device's v_fma_f32 is IEEE-754's fusedMultiplyAdd (a b + d exact, one rounding to nearest-even, gradual
+// underflow, the standard's signs of zero; this library is compiled with binary32 subnormals kept), which is the
+// operation Algorithm "FMA" states, so each step is one instruction.  What the instruction leaves open is the NaN it
+// returns: whenever a step's result is a NaN the model's own rule replaces it (Sec. 4.2: one pattern nan_bits, or the
+// payload rule of the nan_propagate variation).
+//
+// HBM-bound on instruction-shaped tiles: a 16x16x4 tile reads 2.5 KiB and writes 1 KiB for 1024 terms.  Large problems
+// are walked in 16x16 blocks of D so that a wavefront shares 4 rows of A and 16 rows of B in the caches.
+#include "common.hpp"
+
+namespace mmaemu {
+
+__device__ __forceinline__ bool is_nan32(uint32_t b) { return (b & 0x7FFFFFFFu) > 0x7F800000u; }
+__device__ __forceinline__ bool is_inf32(uint32_t b) { return (b & 0x7FFFFFFFu) == 0x7F800000u; }
+__device__ __forceinline__ bool is_zero32(uint32_t b) { return (b & 0x7FFFFFFFu) == 0u; }
+
+template <bool PROPAGATE>
+__device__ __forceinline__ uint32_t fma_step(uint32_t x, uint32_t y, uint32_t d, uint32_t nan_bits)
+{
+    uint32_t r = __float_as_uint(__builtin_fmaf(__uint_as_float(x), __uint_as_float(y), __uint_as_float(d)));
+    if (is_nan32(r)) {                       // a NaN operand, infinity times zero, or infinities of both signs
+        r = nan_bits;
+        if (PROPAGATE) {
+            if (is_nan32(x)) r = x | 0x00400000u;
+            else if (is_nan32(y)) r = y | 0x00400000u;
+            else if ((is_inf32(x) && is_zero32(y)) || (is_inf32(y) && is_zero32(x))) r = nan_bits;
+            else if (is_nan32(d)) r = d | 0x00400000u;
+        }
+    }
+    return r;
+}
+
+// BLOCKED: m and n are multiples of 16 and a workgroup owns one 16x16 block of D; otherwise outputs are taken in
+// row-major order, 256 per workgroup.  VEC: k is a multiple of 4 and the rows of A and B are 16-byte aligned.
+template <bool PROPAGATE, bool BLOCKED, bool VEC>
+__global__ void __launch_bounds__(256)
+emulate_fma_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B, const uint32_t *C, uint32_t *D, uint32_t m,
+                   uint32_t n, uint32_t k, uint64_t total, uint64_t nblocks, uint32_t nan_bits)
+{
+    const uint64_t mn = (uint64_t)m * n;
+    for (uint64_t w = blockIdx.x; w < nblocks; w += gridDim.x) {
+        uint64_t t;
+        uint32_t i, j;
+        if (BLOCKED) {
+            const uint32_t bpr = n / 16u;
+            const uint64_t bpt = (uint64_t)(m / 16u) * bpr;
+            t = w / bpt;
+            const uint32_t r = (uint32_t)(w - t * bpt);
+            i = 16u * (r / bpr) + threadIdx.x / 16u;
+            j = 16u * (r % bpr) + threadIdx.x % 16u;
+        } else {
+            const uint64_t o = w * 256u + threadIdx.x;
+            if (o >= total) continue;
+            t = o / mn;
+            const uint32_t r = (uint32_t)(o - t * mn);
+            i = r / n;
+            j = r - i * n;
+        }
+        const uint64_t o = t * mn + (uint64_t)i * n + j;
+        const uint32_t *a = A + (t * m + i) * (uint64_t)k;
+        const uint32_t *b = B + (t * n + j) * (uint64_t)k;
+        uint32_t d = C[o];
+        if (VEC) {
+            for (uint32_t k0 = 0; k0 < k; k0 += 4) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(a + k0), y = *reinterpret_cast<const uint4 *>(b + k0);
+                d = fma_step<PROPAGATE>(x.x, y.x, d, nan_bits);
+                d = fma_step<PROPAGATE>(x.y, y.y, d, nan_bits);
+                d = fma_step<PROPAGATE>(x.z, y.z, d, nan_bits);
+                d = fma_step<PROPAGATE>(x.w, y.w, d, nan_bits);
+            }
+        } else {
+            for (uint32_t kk = 0; kk < k; ++kk) d = fma_step<PROPAGATE>(a[kk], b[kk], d, nan_bits);
+        }
+        D[o] = d;
+    }
+}
+
+template <bool PROPAGATE, bool BLOCKED, bool VEC>
+static mmaemu_status launch_v(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                              uint64_t batch, uint32_t nan_bits, hipStream_t s)
+{
+    const uint64_t total = batch * m * n;
+    const uint64_t nblocks = (total + 255) / 256;         // (blocked: total is a multiple of 256)
+    const uint64_t grid = nblocks < (1ull << 22) ? nblocks : (1ull << 22);
+    hipLaunchKernelGGL((emulate_fma_kernel<PROPAGATE, BLOCKED, VEC>), dim3((uint32_t)grid), dim3(256), 0, s, (const uint32_t *)A,
+                       (const uint32_t *)B, (const uint32_t *)C, (uint32_t *)D, m, n, k, total, nblocks, nan_bits);
+    MMAEMU_HIP(hipGetLastError());
+    set_last_kernel("fma chain%s%s%s", PROPAGATE ? ", payloads" : "", BLOCKED ? ", 16x16 blocks" : "", VEC ? ", 128-bit loads" : "");
+    return MMAEMU_OK;
+}
+
+template <bool PROPAGATE>
+static mmaemu_status launch_p(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                              uint64_t batch, uint32_t nan_bits, hipStream_t s)
+{
+    const bool blocked = m % 16 == 0 && n % 16 == 0;
+    const bool vec = k % 4 == 0 && ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0;
+    if (blocked && vec) return launch_v<PROPAGATE, true, true>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    if (blocked) return launch_v<PROPAGATE, true, false>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    if (vec) return launch_v<PROPAGATE, false, true>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    return launch_v<PROPAGATE, false, false>(A, B, C, D, m, n, k, batch, nan_bits, s);
+}
+
+mmaemu_status launch_emulate_fma(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                                 uint64_t batch, uint32_t nan_bits, bool nan_propagate, hipStream_t s)
+{
+    if (nan_propagate) return launch_p<true>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    return launch_p<false>(A, B, C, D, m, n, k, batch, nan_bits, s);
+}
+
+} // namespace mmaemu

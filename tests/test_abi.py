@@ -54,7 +54,7 @@ def test_host_side_validation_needs_no_gpu():
     mm.model_destroy(None)
     for kw, status in ((dict(frac_bits=49), 2), (dict(frac_bits=41, frac_bits2=31, c_mode=2), 2), (dict(out_round=2), 1), (dict(c_mode=5), 1), (dict(align_round=1), 2),
                        (dict(out_mant_bits=13), 2), (dict(out_mant_bits=10, out_round=1), 2), (dict(frac_bits2=31), 2), (dict(c_mode=2, frac_bits2=49), 2), (dict(split=1), 2), (dict(c_mode=2, split=4), 1),
-                       (dict(c_mode=3, frac_bits2=31, frac_bits_acc=24), 2), (dict(c_mode=2, frac_bits_merge=24), 2), (dict(skip_zero_terms=2), 1), (dict(family=3), 1), (dict(family=2), 2), (dict(family=1, group_len=8), 2), (dict(family=1, group_len=4, ftz_out=True), 2), (dict(struct_size=40), 1), (dict(group_len=(1 << 20) + 1), 2)):
+                       (dict(c_mode=3, frac_bits2=31, frac_bits_acc=24), 2), (dict(c_mode=2, frac_bits_merge=24), 2), (dict(skip_zero_terms=2), 1), (dict(family=4), 1), (dict(family=2), 2), (dict(family=1, group_len=8), 2), (dict(family=1, group_len=4, ftz_out=True), 2), (dict(struct_size=40), 1), (dict(group_len=(1 << 20) + 1), 2)):
         with pytest.raises(mm.MmaemuError) as ei:
             mm.model_create(**kw)
         assert ei.value.status == status, kw
@@ -68,3 +68,50 @@ def test_host_side_validation_needs_no_gpu():
     assert info == dict(m=16, n=16, k=32, a=mm.E4M3, b=mm.E5M2)
     with pytest.raises(mm.MmaemuError):
         mm.mfma_info(99)
+
+
+def test_emulate_rejects_bad_arguments_before_any_gpu_call():
+    """Every check of mmaemu_emulate_mma's arguments runs on the host: fake addresses never reach a kernel."""
+    from paper_2511_10909_amd import binding as mm
+    h = mm.model_create(group_len=8, frac_bits=24)
+    dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
+    ok = 0x1000
+    cases = [
+        (dict(A=ok + 1), 1),          # FP16 operand at an odd address
+        (dict(C=ok + 2), 1),          # FP32 accumulator off a 4-byte boundary
+        (dict(D=ok + 1), 1),
+        (dict(A=None), 1),
+        (dict(k=12), 3),              # k is not a multiple of the group length
+        (dict(m=0), 3),
+        (dict(k=(1 << 20) + 8), 3),
+    ]
+    for change, status in cases:
+        a = dict(A=ok, B=ok, C=ok, D=ok, m=16, n=16, k=16, batch=1)
+        a.update(change)
+        with pytest.raises(mm.MmaemuError) as ei:
+            mm.emulate_mma(h, a["A"], a["B"], a["C"], a["D"], a["m"], a["n"], a["k"], a["batch"], dt, stream=0)
+        assert ei.value.status == status, (change, mm.last_error())
+    # batch = 0 is a no-op whatever the pointers are
+    mm.emulate_mma(h, None, None, None, None, 16, 16, 16, 0, dt, stream=0)
+    with pytest.raises(mm.MmaemuError) as ei:
+        mm.emulate_mma(h, ok, ok, ok, ok, 16, 16, 16, 1, (mm.TF32, mm.FP16, mm.FP32, mm.FP32), stream=0)
+    assert ei.value.status == 2
+    mm.model_destroy(h)
+
+
+def test_fma_family_argument_checks():
+    from paper_2511_10909_amd import binding as mm
+    for kw in (dict(group_len=2), dict(ftz_in=True), dict(out_round=mm.RZ), dict(c_mode=mm.C_AFTER_EXACT), dict(out_mant_bits=13, out_round=mm.RZ)):
+        with pytest.raises(mm.MmaemuError) as ei:
+            mm.model_create(family=mm.FAMILY_FMA, **kw)
+        assert ei.value.status == 2, kw
+    h = mm.model_create(family=mm.FAMILY_FMA, group_len=1)
+    ok = 0x1000
+    for dt in ((mm.BF16, mm.BF16, mm.FP32, mm.FP32), (mm.TF32, mm.TF32, mm.FP32, mm.FP32), (mm.FP32, mm.FP32, mm.FP16, mm.FP16)):
+        with pytest.raises(mm.MmaemuError) as ei:
+            mm.emulate_mma(h, ok, ok, ok, ok, 16, 16, 4, 1, dt, stream=0)
+        assert ei.value.status == 2, dt
+    with pytest.raises(mm.MmaemuError):
+        mm.emulate_mma_scaled(h, ok, ok, ok, ok, ok, ok, 4, 16, 16, 4, 1, (mm.FP32,) * 4, stream=0)
+    mm.emulate_mma(h, None, None, None, None, 16, 16, 4, 0, (mm.FP32,) * 4, stream=0)     # batch = 0: no-op
+    mm.model_destroy(h)
