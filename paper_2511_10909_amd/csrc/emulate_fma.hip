@@ -8,7 +8,7 @@
 // returns: whenever a step's result is a NaN the model's own rule replaces it (Sec. 4.2: one pattern nan_bits, or the
 // payload rule of the nan_propagate variation).
 //
-// HBM-bound on instruction-shaped tiles: a 16x16x4 tile reads 2.5 KiB and writes 1 KiB for 1024 terms.  Large problems
+// HBM-bound on instruction-shaped tiles: a 16x16x4 tile reads 1.5 KiB and writes 1 KiB for 1024 terms.  Large problems
 // are walked in 16x16 blocks of D so that a wavefront shares 4 rows of A and 16 rows of B in the caches.
 #include "common.hpp"
 
@@ -35,8 +35,9 @@ __device__ __forceinline__ uint32_t fma_step(uint32_t x, uint32_t y, uint32_t d,
 }
 
 // BLOCKED: m and n are multiples of 16 and a workgroup owns one 16x16 block of D; otherwise outputs are taken in
-// row-major order, 256 per workgroup.  VEC: k is a multiple of 4 and the rows of A and B are 16-byte aligned.
-template <bool PROPAGATE, bool BLOCKED, bool VEC>
+// row-major order, 256 per workgroup.  VEC = 4 (2): k is a multiple of 4 (2) and the rows of A and B are 16-byte (8-byte)
+// aligned, so that four (two) consecutive k come with one load.
+template <bool PROPAGATE, bool BLOCKED, int VEC>
 __global__ void __launch_bounds__(256)
 emulate_fma_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B, const uint32_t *C, uint32_t *D, uint32_t m,
                    uint32_t n, uint32_t k, uint64_t total, uint64_t nblocks, uint32_t nan_bits)
@@ -64,13 +65,19 @@ emulate_fma_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ 
         const uint32_t *a = A + (t * m + i) * (uint64_t)k;
         const uint32_t *b = B + (t * n + j) * (uint64_t)k;
         uint32_t d = C[o];
-        if (VEC) {
+        if (VEC == 4) {
             for (uint32_t k0 = 0; k0 < k; k0 += 4) {
                 const uint4 x = *reinterpret_cast<const uint4 *>(a + k0), y = *reinterpret_cast<const uint4 *>(b + k0);
                 d = fma_step<PROPAGATE>(x.x, y.x, d, nan_bits);
                 d = fma_step<PROPAGATE>(x.y, y.y, d, nan_bits);
                 d = fma_step<PROPAGATE>(x.z, y.z, d, nan_bits);
                 d = fma_step<PROPAGATE>(x.w, y.w, d, nan_bits);
+            }
+        } else if (VEC == 2) {
+            for (uint32_t k0 = 0; k0 < k; k0 += 2) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(a + k0), y = *reinterpret_cast<const uint2 *>(b + k0);
+                d = fma_step<PROPAGATE>(x.x, y.x, d, nan_bits);
+                d = fma_step<PROPAGATE>(x.y, y.y, d, nan_bits);
             }
         } else {
             for (uint32_t kk = 0; kk < k; ++kk) d = fma_step<PROPAGATE>(a[kk], b[kk], d, nan_bits);
@@ -79,17 +86,18 @@ emulate_fma_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ 
     }
 }
 
-template <bool PROPAGATE, bool BLOCKED, bool VEC>
+template <bool PROPAGATE, bool BLOCKED, int VEC>
 static mmaemu_status launch_v(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
                               uint64_t batch, uint32_t nan_bits, hipStream_t s)
 {
     const uint64_t total = batch * m * n;
     const uint64_t nblocks = (total + 255) / 256;         // (blocked: total is a multiple of 256)
-    const uint64_t grid = nblocks < (1ull << 22) ? nblocks : (1ull << 22);
+    const uint64_t grid = nblocks < 16384 ? nblocks : 16384;             // (grid-stride beyond that)
     hipLaunchKernelGGL((emulate_fma_kernel<PROPAGATE, BLOCKED, VEC>), dim3((uint32_t)grid), dim3(256), 0, s, (const uint32_t *)A,
                        (const uint32_t *)B, (const uint32_t *)C, (uint32_t *)D, m, n, k, total, nblocks, nan_bits);
     MMAEMU_HIP(hipGetLastError());
-    set_last_kernel("fma chain%s%s%s", PROPAGATE ? ", payloads" : "", BLOCKED ? ", 16x16 blocks" : "", VEC ? ", 128-bit loads" : "");
+    set_last_kernel("fma chain%s%s%s", PROPAGATE ? ", payloads" : "", BLOCKED ? ", 16x16 blocks" : "",
+                    VEC == 4 ? ", 128-bit loads" : (VEC == 2 ? ", 64-bit loads" : ""));
     return MMAEMU_OK;
 }
 
@@ -98,11 +106,16 @@ static mmaemu_status launch_p(const void *A, const void *B, const void *C, void 
                               uint64_t batch, uint32_t nan_bits, hipStream_t s)
 {
     const bool blocked = m % 16 == 0 && n % 16 == 0;
-    const bool vec = k % 4 == 0 && ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0;
-    if (blocked && vec) return launch_v<PROPAGATE, true, true>(A, B, C, D, m, n, k, batch, nan_bits, s);
-    if (blocked) return launch_v<PROPAGATE, true, false>(A, B, C, D, m, n, k, batch, nan_bits, s);
-    if (vec) return launch_v<PROPAGATE, false, true>(A, B, C, D, m, n, k, batch, nan_bits, s);
-    return launch_v<PROPAGATE, false, false>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B);
+    const int vec = (k % 4 == 0 && (addr & 15) == 0) ? 4 : ((k % 2 == 0 && (addr & 7) == 0) ? 2 : 1);
+    if (blocked) {
+        if (vec == 4) return launch_v<PROPAGATE, true, 4>(A, B, C, D, m, n, k, batch, nan_bits, s);
+        if (vec == 2) return launch_v<PROPAGATE, true, 2>(A, B, C, D, m, n, k, batch, nan_bits, s);
+        return launch_v<PROPAGATE, true, 1>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    }
+    if (vec == 4) return launch_v<PROPAGATE, false, 4>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    if (vec == 2) return launch_v<PROPAGATE, false, 2>(A, B, C, D, m, n, k, batch, nan_bits, s);
+    return launch_v<PROPAGATE, false, 1>(A, B, C, D, m, n, k, batch, nan_bits, s);
 }
 
 mmaemu_status launch_emulate_fma(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,

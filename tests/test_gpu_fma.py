@@ -44,12 +44,14 @@ def zero_case(rng, nb, m, n, k):
 
 SHAPES = [  # (tiles, m, n, k, offset_words, expected kernel variant)
     (6, 16, 16, 4, 0, "fma chain, 16x16 blocks, 128-bit loads"),
-    (2, 32, 32, 2, 0, "fma chain, 16x16 blocks"),
+    (2, 32, 32, 2, 0, "fma chain, 16x16 blocks, 64-bit loads"),
     (3, 32, 32, 1, 0, "fma chain, 16x16 blocks"),
     (40, 4, 4, 1, 0, "fma chain"),
     (3, 5, 7, 3, 0, "fma chain"),
     (2, 9, 13, 8, 0, "fma chain, 128-bit loads"),
-    (2, 16, 16, 8, 1, "fma chain, 16x16 blocks"),            # rows off the 16-byte alignment
+    (2, 16, 16, 8, 1, "fma chain, 16x16 blocks"),            # rows off the 8-byte alignment
+    (2, 16, 16, 8, 2, "fma chain, 16x16 blocks, 64-bit loads"),      # rows 8-byte but not 16-byte aligned
+    (5, 3, 6, 6, 0, "fma chain, 64-bit loads"),
     (1, 48, 32, 20, 0, "fma chain, 16x16 blocks, 128-bit loads"),
 ]
 
