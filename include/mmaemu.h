@@ -296,10 +296,14 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
  *                where the low 4 bits of the odd element's own word are 0.  With K even and both
  *                operands K-contiguous the products cancel pairwise up to those perturbations.
  *                Not defined for FP32 output.
+ *   SIGNED_ZEROS one of eight equally likely values picked by the top three bits of the word: sign = bit 29;
+ *                bits 31..30 = 0 or 1: zero, 2: 1.0, 3: the smallest subnormal.  Exact zeros of both signs next to
+ *                the values that produce them (sums of zeros, which random streams of wide formats never reach).
+ *                Not defined for scale codes.
  */
 enum { MMAEMU_GEN_ZERO = 0, MMAEMU_GEN_FINITE_BITS = 1, MMAEMU_GEN_UNIFORM_EXP = 2,
        MMAEMU_GEN_RANDOM_BITS = 3, MMAEMU_GEN_NORMAL = 4, MMAEMU_GEN_UNIFORM = 5,
-       MMAEMU_GEN_NORMAL_OUTLIERS = 6, MMAEMU_GEN_CANCELLING = 7 };
+       MMAEMU_GEN_NORMAL_OUTLIERS = 6, MMAEMU_GEN_CANCELLING = 7, MMAEMU_GEN_SIGNED_ZEROS = 8 };
 enum { MMAEMU_SCALE_NONE = 0, MMAEMU_SCALE_TENSOR = 1, MMAEMU_SCALE_TILE = 2 };
 
 typedef struct {

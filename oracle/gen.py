@@ -24,6 +24,9 @@ Families (r = first word, r1 = second word):
                 sel = bits m..30 of r (nsel = 31 - m) -- for FP32: sel = r & 0x7FFFFFFF,
                 nsel = 31 and the mantissa comes from r1; mantissa = low m bits.
   RANDOM_BITS   the low `width` bits of r (NaN and infinities included).
+  SIGNED_ZEROS  one of eight equally likely values picked by the top three bits of r: sign = bit 29, magnitude by
+                bits 31..30: 0 and 1 -> zero, 2 -> 1.0 (exponent field = bias, mantissa 0), 3 -> the smallest
+                subnormal (code 1).  Exact zeros of both signs next to the values that produce them.
   NORMAL        Box-Muller on word pairs (elements 2i, 2i+1 of the flattened
                 operand share (r_2i, r_2i+1)):  u1 = (r_2i + 0.5) / 2^32,
                 phi = 2 pi r_2i+1 / 2^32 (+ half a step), radius = sqrt(-2 ln u1);
@@ -53,7 +56,7 @@ from . import formats as fm
 from .philox import philox4x32_10
 
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
-GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING = 5, 6, 7
+GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING, GEN_SIGNED_ZEROS = 5, 6, 7, 8
 VALUE_FAMILIES = (GEN_NORMAL, GEN_UNIFORM, GEN_NORMAL_OUTLIERS)
 SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
 
@@ -297,6 +300,10 @@ def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
             else:
                 flip = odd & ((r_own & np.uint64(0xF)) == 0)
                 out = np.where(flip, out ^ np.uint64(1), out)
+    elif gp.family == GEN_SIGNED_ZEROS:
+        sign, kind = (r >> np.uint64(29)) & np.uint64(1), r >> np.uint64(30)
+        mag = np.where(kind == 2, np.uint64(f.bias << f.mbits), np.where(kind == 3, np.uint64(1), np.uint64(0)))
+        out = (sign << np.uint64(f.width - 1)) | mag
     else:
         raise ValueError(gp.family)
     return out.astype(np.uint32).reshape(n_tiles, elems_per_tile)

@@ -18,7 +18,7 @@ SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
 FAMILY_FDPA, FAMILY_FTZ_ADDMUL, FAMILY_GST_FDPA, FAMILY_FMA = 0, 1, 2, 3
 SCALE_FORMAT_E8M0, SCALE_FORMAT_UE4M3 = 0, 1
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
-GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING = 5, 6, 7
+GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING, GEN_SIGNED_ZEROS = 5, 6, 7, 8
 SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
 (MFMA_F32_16X16X16_F16, MFMA_F32_16X16X16_BF16, MFMA_F32_32X32X8_F16, MFMA_F32_32X32X8_BF16,
  MFMA_F32_16X16X32_F16, MFMA_F32_16X16X32_BF16, MFMA_F32_16X16X32_FP8_FP8, MFMA_F32_16X16X32_FP8_BF8,

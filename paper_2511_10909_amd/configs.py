@@ -252,6 +252,9 @@ def validation_families(ta, tb):
     if ta != mm.FP32:       # (the generator does not build cancelling pairs of FP32 values)
         fams.append(("cancelling", dict(canc, exp_lo=mid[ta][0], exp_hi=mid[ta][1]), dict(canc, exp_lo=mid[tb][0], exp_hi=mid[tb][1]),
                      ue((100, 135))))
+    # zeros of both signs, +-1 and the smallest subnormals: exact zeros from zeros, whose sign a model must get right
+    zs = dict(family=mm.GEN_SIGNED_ZEROS)
+    fams.append(("signed_zeros", zs, zs, zs))
     fams.append(("mid_exp_c_above", ue(mid[ta]), ue(mid[tb]), ue((125, 145), zero=False)))
     fams.append(("mid_exp_c_below", ue(mid[ta]), ue(mid[tb]), ue((80, 129))))
     fams.append(("wide_exp_c_any", ue(full[ta]), ue(full[tb]), ue((1, 254))))

@@ -384,7 +384,7 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
         return MMAEMU_ERR_INVALID_ARG;
     }
     if (dtype == MMAEMU_TF32) { set_error("generate: TF32 streams are FP32 streams (generate MMAEMU_FP32)"); return MMAEMU_ERR_UNSUPPORTED; }
-    if ((uint32_t)dtype > MMAEMU_FP4_E2M1 || g->family > MMAEMU_GEN_CANCELLING || g->scale_scope > MMAEMU_SCALE_TILE) {
+    if ((uint32_t)dtype > MMAEMU_FP4_E2M1 || g->family > MMAEMU_GEN_SIGNED_ZEROS || g->scale_scope > MMAEMU_SCALE_TILE) {
         set_error("generate: enum out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }

@@ -58,6 +58,11 @@ __device__ __forceinline__ uint32_t bits_from_word(const GenArgs &g, uint32_t r,
         const uint32_t sign = v >= g.nmag;
         return (sign << (g.width - 1)) | (v - sign * g.nmag);
     }
+    if (g.family == MMAEMU_GEN_SIGNED_ZEROS) {
+        const uint32_t kind = r >> 30, sign = (r >> 29) & 1u;
+        const uint32_t mag = kind == 2u ? (g.bias << g.mbits) : (kind == 3u ? 1u : 0u);
+        return (sign << (g.width - 1)) | mag;
+    }
     // UNIFORM_EXP (scale codes have no sign bit)
     const uint32_t sign = g.dtype == MMAEMU_E8M0 ? 0u : (r >> 31);
     uint32_t idx, mant;

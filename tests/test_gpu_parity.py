@@ -170,6 +170,9 @@ GEN_CASES = [
     (ogen.GEN_NORMAL, fm.E3M2, dict(scale_scope=ogen.SCALE_TENSOR, scale_target=28.0)),
     (ogen.GEN_CANCELLING, fm.E2M1, dict(exp_lo=0, exp_hi=3)), (ogen.GEN_CANCELLING, fm.E3M2, dict(exp_lo=1, exp_hi=6)),
     (ogen.GEN_ZERO, fm.E2M1, {}),
+    (ogen.GEN_SIGNED_ZEROS, fm.FP32, {}), (ogen.GEN_SIGNED_ZEROS, fm.FP16, {}), (ogen.GEN_SIGNED_ZEROS, fm.BF16, {}),
+    (ogen.GEN_SIGNED_ZEROS, fm.E4M3, {}), (ogen.GEN_SIGNED_ZEROS, fm.E5M2, {}), (ogen.GEN_SIGNED_ZEROS, fm.E2M3, {}),
+    (ogen.GEN_SIGNED_ZEROS, fm.E3M2, {}), (ogen.GEN_SIGNED_ZEROS, fm.E2M1, {}),
 ]
 
 

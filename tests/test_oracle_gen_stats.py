@@ -274,3 +274,22 @@ def test_compare_stats_fp16_patterns():
     assert (d == 1).all()
     # a 16-bit pattern is never taken for a binary32 one: 0x7E00 is a NaN at width 16 and a small number at width 32
     assert stats.is_nan(np.array([0x7E00]), 16)[0] and not stats.is_nan(np.array([0x7E00]), 32)[0]
+
+
+@pytest.mark.parametrize("fmt,one,neg", [(fm.FP32, 0x3F800000, 0x80000000), (fm.FP16, 0x3C00, 0x8000), (fm.BF16, 0x3F80, 0x8000),
+                                         (fm.E4M3, 0x38, 0x80), (fm.E5M2, 0x3C, 0x80), (fm.E2M3, 0x08, 0x20), (fm.E3M2, 0x0C, 0x20),
+                                         (fm.E2M1, 0x2, 0x8)])
+def test_signed_zeros_family(fmt, one, neg):
+    # eight equally likely values: +-0 twice, +-1.0, +- the smallest subnormal; 1.0 written out per format
+    gp = gen.GenParams(family=gen.GEN_SIGNED_ZEROS, seed=5, operand=1)
+    x = gen.generate(gp, fmt, 4096, 3, 4).ravel()
+    values, counts = np.unique(x, return_counts=True)
+    assert set(values.tolist()) == {0, neg, one, one | neg, 1, 1 | neg}
+    freq = dict(zip(values.tolist(), (counts / x.size).tolist()))
+    for v, p in ((0, 0.25), (neg, 0.25), (one, 0.125), (one | neg, 0.125), (1, 0.125), (1 | neg, 0.125)):
+        assert abs(freq[v] - p) < 0.02, (hex(v), freq[v])
+    assert fm.decode(one, fmt).value == 1 and fm.decode(one | neg, fmt).value == -1
+    assert fm.decode(1, fmt).cls == fm.SUBNORMAL and fm.decode(neg, fmt).cls == fm.ZERO and fm.decode(neg, fmt).sign == 1
+    # chunk independence, like every family
+    y = gen.generate(gp, fmt, 4096, 5, 1).ravel()
+    assert np.array_equal(y, x[2 * 4096:3 * 4096])
