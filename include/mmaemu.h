@@ -215,7 +215,7 @@ mmaemu_status mmaemu_model_get_params(const mmaemu_model *model, mmaemu_model_pa
  * D = Phi_model(A, B, C) for `batch` independent m x n x k tiles (paper Eq. 1 / Eq. 3:
  * every d_ij is an independent dot-product-accumulate).  D may alias C; D may not
  * overlap A or B.  Pointers aligned to their element size (the tiled kernels are taken when A and B are
- * 8-byte aligned).  batch = 0 is a no-op.
+ * 8-byte aligned, 16-byte for TF32).  batch = 0 is a no-op.
  * Errors: SHAPE (m, n or k zero; k > 2^20; k % L != 0; m*n or batch*m*n overflow),
  *         UNSUPPORTED (dtype combination), INVALID_ARG (NULL or misaligned pointer, bad handle), HIP.
  */

@@ -16,7 +16,7 @@ static mmaemu_status launch_vm(const TiledArgs &t, const void *A, const void *B,
         if (t.p.split == MMAEMU_SPLIT_HALVES) return launch_tiled_shape<CM_RD_HALVES, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         return launch_tiled_shape<CM_RD_QUARTERS, VM>(t, A, B, Cm, D, m, n, k, batch, s, handled);
     }
-    handled = false;        // split groups with BF16 operands or wide F: general kernel
+    handled = false;        // split groups with BF16 or TF32 operands or wide F: general kernel
     return MMAEMU_OK;
 }
 
@@ -28,16 +28,19 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // loaded at once) and group sums below 2^52
     const bool aligned = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) == 0;
     // the RD mode runs tiled with all of its variations; the two other modes only as the paper has them
-    // (the tiled kernels tag BF16 products of 2^128 and more as infinities: without that rule such products need
+    // (the tiled kernels tag BF16 and TF32 products of 2^128 and more as infinities: without that rule such products need
     // the general kernel's integer range)
-    const bool wide_bf16 = p.wide_products && (ta == MMAEMU_BF16 || tb == MMAEMU_BF16);
+    const bool wide_bf16 = p.wide_products && (ta == MMAEMU_BF16 || tb == MMAEMU_BF16 || ta == MMAEMU_TF32);
     const bool tiled_mode = (p.c_mode == MMAEMU_C_AFTER_RD && !wide_bf16) || (p.c_mode != MMAEMU_C_AFTER_RD && !p.skip_zero_terms && !p.zero_result_positive);
     // block scales run tiled when every group lies inside one block (all of its products then share one scale
     // exponent) and the values stay binary32 (FP8 / FP16 operands, F below 30)
     const bool scaled = SA != nullptr;
-    const bool scaled_ok = !scaled || (block % p.L == 0 && ta != MMAEMU_BF16 && tb != MMAEMU_BF16 && p.F < 30);
-    // TF32 and FP32 operands (binary32 words) run in the general kernel only, and so does F above 40
-    const bool tiled_types = ta != MMAEMU_TF32 && ta != MMAEMU_FP32 && p.F <= 40;
+    const bool tf32 = ta == MMAEMU_TF32;                                  // (pairs with itself only)
+    const bool scaled_ok = !scaled || (block % p.L == 0 && ta != MMAEMU_BF16 && tb != MMAEMU_BF16 && !tf32 && p.F < 30);
+    // FP32 operands run in the general kernel only, and so does F above 40; TF32 operands (four to a 128-bit load) run
+    // tiled with binary32 values, i.e. F below 30, from 16-byte aligned arrays
+    const bool aligned16 = ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0;
+    const bool tiled_types = ta != MMAEMU_FP32 && p.F <= 40 && (!tf32 || (p.F < 30 && aligned16));
     if (tiled_mode && tiled_types && scaled_ok && aligned && (uint64_t)p.L <= (1ull << (50 - p.F))) {
         TiledArgs t;
         t.p = p;
@@ -51,6 +54,7 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
         bool handled = false;
         mmaemu_status st;
         if (scaled) st = launch_vm<3>(t, A, B, Cm, D, m, n, k, batch, s, handled);
+        else if (tf32) st = launch_vm<4>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         else if (p.F >= 30) st = launch_vm<2>(t, A, B, Cm, D, m, n, k, batch, s, handled);             // wide F: binary64 terms
         else if (ta == MMAEMU_BF16 || tb == MMAEMU_BF16) st = launch_vm<1>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         else st = launch_vm<0>(t, A, B, Cm, D, m, n, k, batch, s, handled);

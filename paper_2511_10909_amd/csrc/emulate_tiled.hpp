@@ -33,6 +33,8 @@
 //   3  mode 0 with E8M0 block scales (Algorithm "ST-FDPA") whose blocks hold whole groups: all products of a group
 //      then share one scale exponent s, the aligned terms are those of the unscaled group, and s only moves the
 //      group's maximum exponent (and with it everything the accumulator meets).
+//   4  mode 1 for TF32 operands (binary32 words whose low 13 mantissa bits do not count): the same exponent range as
+//      BF16 with 11-bit significands, so products still fit binary32 exactly; elements arrive four to a 128-bit load.
 // Accumulation modes (template parameter CMODE): MMAEMU_C_IN_GROUP, MMAEMU_C_AFTER_EXACT, MMAEMU_C_AFTER_RD (paper
 // Algorithm "TR-FDPA" and its variations), and the two split forms of the latter (Algorithm "GTR-FDPA"):
 // CM_RD_EVEN_ODD, where the packed exponent maxima of pass 1 already are the even and the odd maximum (even k in
@@ -45,6 +47,8 @@
 // global memory.
 #pragma once
 #include "fdpa_int.hpp"
+
+#include <type_traits>
 
 namespace mmaemu {
 
@@ -97,6 +101,12 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, uint
         val = __uint_as_float(flushed ? 0u : bits << 16);
         if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
         else wild |= !flushed && (bits & 0x7FFFu) != 0 && (E - 96u) > 62u;
+    } else if (T == MMAEMU_TF32) {
+        // (bits: the word without its 13 surplus bits) the value is the pattern moved back into place
+        const bool flushed = ftz_in && E == 0;
+        val = __uint_as_float(flushed ? 0u : bits << 13);
+        if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
+        else wild |= !flushed && (bits & 0x3FFFFu) != 0 && (E - 96u) > 62u;
     } else if (T == MMAEMU_FP16) {
         _Float16 h;
         const uint16_t hb = (uint16_t)bits;
@@ -125,6 +135,17 @@ __device__ __forceinline__ void decode4(uint2 raw, uint32_t ftz_in, uint32_t zbi
     } else {
         b[0] = raw.x & 0xFFFFu; b[1] = raw.x >> 16; b[2] = raw.y & 0xFFFFu; b[3] = raw.y >> 16;
     }
+    uint32_t x[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, zbias, f[q], x[q], wild);
+    e = make_uint2(x[0] | (x[1] << 16), x[2] | (x[3] << 16));
+}
+
+// the same for elements held in 32-bit words (TF32)
+template <int T>
+__device__ __forceinline__ void decode4(uint4 raw, uint32_t ftz_in, uint32_t zbias, float (&f)[4], uint2 &e, bool &wild)
+{
+    const uint32_t b[4] = {raw.x >> 13, raw.y >> 13, raw.z >> 13, raw.w >> 13};
     uint32_t x[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) decode_elem<T>(b[q], ftz_in, zbias, f[q], x[q], wild);
@@ -185,9 +206,17 @@ __device__ __forceinline__ void load_panel(uint32_t esize, const StagePlan<NQ> &
     }
 }
 
+template <int NQ>
+__device__ __forceinline__ void load_panel(uint32_t esize, const StagePlan<NQ> &pl, uint32_t k0, uint4 (&raw)[NQ])
+{
+#pragma unroll
+    for (int i = 0; i < NQ; ++i)
+        raw[i] = *reinterpret_cast<const uint4 *>(pl.src[i] + (uint64_t)(k0 + pl.kq4[i]) * esize);    // (esize = 4)
+}
+
 // raw registers -> decoded registers; returns whether any element needs binary64 products
-template <int T, int NQ>
-__device__ __forceinline__ bool decode_panel(const uint2 (&raw)[NQ], uint32_t ftz_in, uint32_t zbias, float (&f)[NQ][4], uint2 (&e)[NQ])
+template <int T, int NQ, typename RAW>
+__device__ __forceinline__ bool decode_panel(const RAW (&raw)[NQ], uint32_t ftz_in, uint32_t zbias, float (&f)[NQ][4], uint2 (&e)[NQ])
 {
     bool wild = false;
 #pragma unroll
@@ -208,6 +237,12 @@ __device__ __forceinline__ bool decode_any(uint32_t t, const uint2 (&raw)[NQ], u
     case MMAEMU_FP4_E2M1: return decode_panel<MMAEMU_FP4_E2M1, NQ>(raw, ftz_in, zbias, f, e);
     default: return decode_panel<MMAEMU_BF16, NQ>(raw, ftz_in, zbias, f, e);
     }
+}
+template <int NQ>
+__device__ __forceinline__ bool decode_any(uint32_t, const uint4 (&raw)[NQ], uint32_t ftz_in, uint32_t zbias, float (&f)[NQ][4],
+                                           uint2 (&e)[NQ])
+{
+    return decode_panel<MMAEMU_TF32, NQ>(raw, ftz_in, zbias, f, e);
 }
 
 // decoded registers -> LDS.  `as_double`: values are written as binary64 (row stride VSD
@@ -355,7 +390,8 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                      uint32_t bn_count, uint32_t xcd_remap)
 {
     constexpr bool SC = VM_ == 3;                     // block scales
-    constexpr int VM = SC ? 0 : VM_;                  // how values are held
+    constexpr bool WIDE = VM_ == 4;                   // elements in 32-bit words (TF32)
+    constexpr int VM = SC ? 0 : (WIDE ? 1 : VM_);     // how values are held
     constexpr int TI = TM / R, TJ = TN / C, TPS = TI * TJ, SLOTS = 256 / TPS;
     static_assert(TPS * SLOTS == 256, "thread layout");
     static_assert(!SC || LT != 0, "scaled groups have a fixed length");
@@ -400,8 +436,8 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     if (xcd_remap) wg = (wg & 7u) * (gridDim.x >> 3) + (wg >> 3);
     const uint64_t item0 = (uint64_t)wg * SLOTS;
     constexpr int NQA = (SLOTS * TM * (KC / 4) + 255) / 256, NQB = (SLOTS * TN * (KC / 4) + 255) / 256;
-    const uint32_t esa = (ta_.ta <= MMAEMU_FP8_E5M2 || ta_.ta >= MMAEMU_FP6_E2M3) ? 1u : 2u;      // bytes per element
-    const uint32_t esb = (ta_.tb <= MMAEMU_FP8_E5M2 || ta_.tb >= MMAEMU_FP6_E2M3) ? 1u : 2u;
+    const uint32_t esa = WIDE ? 4u : ((ta_.ta <= MMAEMU_FP8_E5M2 || ta_.ta >= MMAEMU_FP6_E2M3) ? 1u : 2u);      // bytes per element
+    const uint32_t esb = WIDE ? 4u : ((ta_.tb <= MMAEMU_FP8_E5M2 || ta_.tb >= MMAEMU_FP6_E2M3) ? 1u : 2u);
     StagePlan<NQA> plan_a;
     StagePlan<NQB> plan_b;
     make_plan<TM, KC, SLOTS, VS, ES, true, NQA>(plan_a, A, esa, item0, nitems, bm_count, bn_count, m, k);
@@ -891,7 +927,8 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
     // WHAT bit 0: exponents, bit 1: values.  Elements are decoded into registers first; in the adaptive mode the workgroup then agrees (through the barrier
     // that also protects the previous chunk's readers) on whether any of them needs
     // binary64, and the values go to LDS in that form.
-    uint2 raw_a[NQA], raw_b[NQB];                               // the next chunk's operands, in flight
+    typedef typename std::conditional<WIDE, uint4, uint2>::type Raw;
+    Raw raw_a[NQA], raw_b[NQB];                                 // the next chunk's operands, in flight
     auto prefetch = [&](uint32_t k0) {
         load_panel<NQA>(esa, plan_a, k0, raw_a);
         load_panel<NQB>(esb, plan_b, k0, raw_b);
@@ -1210,6 +1247,10 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
         if constexpr (BIG_BLOCKS) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
         else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     }
+    if constexpr (VM == 4) {
+        // (the TF32 instructions' own shape, 16 x 16 x 8)
+        if (m == 16 && n == 16 && k % 8 == 0) return launch_L<16, 16, 2, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    }
     if (m == 32 && n == 32 && k % 8 == 0 && k % 32 != 0)
         return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     // blocks of a larger problem: 4x4 register blocks once there are enough outputs to fill
@@ -1249,5 +1290,8 @@ extern template MMAEMU_TILED_SIG(CM_RD_EVEN_ODD, 3);
 extern template MMAEMU_TILED_SIG(CM_RD_HALVES, 3);
 extern template MMAEMU_TILED_SIG(CM_RD_QUARTERS, 0);
 extern template MMAEMU_TILED_SIG(CM_RD_QUARTERS, 3);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_IN_GROUP, 4);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 4);
+extern template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_RD, 4);
 
 } // namespace mmaemu

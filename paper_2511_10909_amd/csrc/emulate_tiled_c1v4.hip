@@ -1,0 +1,6 @@
+// Tiled emulation kernels: accumulation mode MMAEMU_C_AFTER_EXACT, value mode 4 (TF32 operands; see emulate_tiled.hpp).
+#include "emulate_tiled.hpp"
+
+namespace mmaemu {
+template MMAEMU_TILED_SIG(MMAEMU_C_AFTER_EXACT, 4);
+} // namespace mmaemu

@@ -35,10 +35,11 @@ struct DynFmt {
     __device__ __forceinline__ int bias() const { return bias_; }
     __device__ __forceinline__ bool ieee() const { return ieee_; }
     __device__ __forceinline__ bool nospec() const { return nospec_; }
-    __device__ __forceinline__ constexpr int shift() const { return 0; }                            // (TF32 never comes this way)
+    __device__ __forceinline__ constexpr int shift() const { return 0; }                            // (TF32: dropped at the load)
     __device__ __forceinline__ uint32_t load(const void *p, uint32_t k) const
     {
-        return width_ == 8 ? static_cast<const uint8_t *>(p)[k] : (width_ == 16 ? static_cast<const uint16_t *>(p)[k] : static_cast<const uint32_t *>(p)[k]);
+        // 32-bit words are TF32 here (FP32 operands never take the tiled kernels): the 13 surplus bits go at once
+        return width_ == 8 ? static_cast<const uint8_t *>(p)[k] : (width_ == 16 ? static_cast<const uint16_t *>(p)[k] : static_cast<const uint32_t *>(p)[k] >> 13);
     }
 };
 __device__ __forceinline__ DynFmt dyn_fmt(uint32_t t)
@@ -50,6 +51,7 @@ __device__ __forceinline__ DynFmt dyn_fmt(uint32_t t)
     case MMAEMU_FP6_E2M3: return DynFmt{2, 3, 1, 8, false, true};
     case MMAEMU_FP6_E3M2: return DynFmt{3, 2, 3, 8, false, true};
     case MMAEMU_FP4_E2M1: return DynFmt{2, 1, 1, 8, false, true};
+    case MMAEMU_TF32: return DynFmt{8, 10, 127, 32, true, false};
     default: return DynFmt{8, 7, 127, 16, true, false};                                             // BF16
     }
 }
