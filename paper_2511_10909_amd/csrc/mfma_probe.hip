@@ -52,6 +52,22 @@ template <int NELEM, int EB>
 __device__ __forceinline__ void load_row_slice(const uint8_t *row, uint32_t k0, uint32_t k, uint32_t out[4])
 {
     out[0] = out[1] = out[2] = out[3] = 0u;
+    // the whole slice inside the row and naturally aligned: one load (the bytes land as the loop below packs them)
+    constexpr int SLICE = NELEM * EB;
+    static_assert(SLICE == 4 || SLICE == 8 || SLICE == 16, "slice of 4, 8 or 16 bytes");
+    const uint8_t *p = row + (size_t)k0 * EB;
+    if (k0 + NELEM <= k && (reinterpret_cast<uintptr_t>(p) & (SLICE - 1)) == 0) {
+        if (SLICE == 16) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(p);
+            out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+        } else if (SLICE == 8) {
+            const uint2 v = *reinterpret_cast<const uint2 *>(p);
+            out[0] = v.x; out[1] = v.y;
+        } else {
+            out[0] = *reinterpret_cast<const uint32_t *>(p);
+        }
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < NELEM; ++q) {
         const uint32_t kk = k0 + q;
