@@ -98,12 +98,23 @@ compare_kernel(const T *__restrict__ d0, const T *__restrict__ d1, uint64_t coun
         for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
             one_pair<W>(d0[i], d1[i], base + i, lc, hist);
     }
-    if (lc.mism) {
-        atomicAdd(&s_mism, lc.mism);
-        atomicMin(&s_first, (unsigned long long)lc.first);
+    // one set of LDS atomics per wavefront, not per lane: 64 lanes on one address take 64 turns
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        lc.mism += __shfl_xor(lc.mism, o);
+        lc.nan_equiv += __shfl_xor(lc.nan_equiv, o);
+        const unsigned long long f = __shfl_xor((unsigned long long)lc.first, o), d = __shfl_xor((unsigned long long)lc.maxd, o);
+        lc.first = f < lc.first ? f : lc.first;
+        lc.maxd = d > lc.maxd ? d : lc.maxd;
     }
-    if (lc.nan_equiv) atomicAdd(&s_nan, lc.nan_equiv);
-    if (lc.maxd) atomicMax(&s_maxd, (unsigned long long)lc.maxd);
+    if ((threadIdx.x & 63u) == 0) {
+        if (lc.mism) {
+            atomicAdd(&s_mism, lc.mism);
+            atomicMin(&s_first, (unsigned long long)lc.first);
+        }
+        if (lc.nan_equiv) atomicAdd(&s_nan, lc.nan_equiv);
+        if (lc.maxd) atomicMax(&s_maxd, (unsigned long long)lc.maxd);
+    }
     __syncthreads();
 
     unsigned long long *g = reinterpret_cast<unsigned long long *>(st);
