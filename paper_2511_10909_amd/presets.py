@@ -44,8 +44,8 @@ PAPER = {
     ("cdna2", "bf16"): dict(group_len=2, family=mm.FAMILY_FTZ_ADDMUL),
     ("cdna2", "bf16_1k"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),
     ("cdna2", "fp16"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),
-    ("fma_chain", "any"): dict(group_len=1, frac_bits=24, out_round=mm.RNE, c_mode=mm.C_AFTER_EXACT),   # Phi_FMA on <= 16-bit inputs
-    ("fma_chain", "fp32"): dict(group_len=1, frac_bits=46, out_round=mm.RNE, c_mode=mm.C_AFTER_EXACT),  # Phi_FMA on FP32 inputs (48-bit products)
+    ("fma_chain", "any"): dict(group_len=1, frac_bits=24, out_round=mm.RNE, c_mode=mm.C_AFTER_EXACT),   # the chain of Phi_FMA inside the FDPA family, <= 16-bit inputs (an exact zero is always +0.0 there)
+    ("fma_chain", "fp32"): dict(group_len=1, frac_bits=46, out_round=mm.RNE, c_mode=mm.C_AFTER_EXACT),  # the same on FP32 inputs (48-bit products)
     ("fma", "fp32"): dict(family=mm.FAMILY_FMA),            # Phi_FMA itself (Algorithms "FMA", "Phi_FMA"): IEEE-754 signs of zero
     ("cdna3", "tf32"): dict(group_len=4, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD),
     ("cdna3", "bf16"): dict(group_len=8, frac_bits=24, frac_bits2=31, out_round=mm.RNE, c_mode=mm.C_AFTER_RD),
