@@ -343,3 +343,37 @@ def validate_against_mfma(instr, model_kwargs, n_tiles=4096, seeds=(0,), dev="cu
     out["terms"] = len(fams) * len(seeds) * n_tiles * m * n * k
     out["kernel"] = kernel
     return out
+
+
+def _report(argv=None):
+    """`python -m paper_2511_10909_amd.configs`: the five workloads end to end, one table row each."""
+    import argparse
+    ap = argparse.ArgumentParser(description="run the five benchmark workloads end to end and print their rates")
+    ap.add_argument("--tiles4", type=int, default=1 << 22, help="tiles of workload 4 (the full workload has 2^26)")
+    ap.add_argument("--tiles5", type=int, default=1 << 20, help="tiles of workload 5 per operand type (the full workload has 2^24)")
+    ap.add_argument("--size3", type=int, default=4096, help="m = n = k of workload 3")
+    args = ap.parse_args(argv)
+    config1(n_tiles=256)                                  # (first call: library load and allocator warm-up)
+
+    def row(name, r, note=""):
+        print("| %s | %.3g | %.3f | %.3g | %s |" % (name, r["terms"], 1e3 * r["seconds"], r["terms"] / r["seconds"], note), flush=True)
+
+    print("| workload | MAC terms | ms | terms/s end to end | |\n|---|---|---|---|---|")
+    r = config1()
+    row("1: fp16 16x16x16, 10 000 tiles, RNE against RZ", r, "%d of %d outputs differ" % (r["stats"]["n_mismatch_bits"], r["stats"]["n_compared"]))
+    config2()
+    r = config2()
+    row("2: bf16 1024^3, chained against fused", r, "%d of %d outputs differ" % (r["stats"]["n_mismatch_bits"], r["stats"]["n_compared"]))
+    r = config3(size=args.size3)
+    row("3: e4m3 x e5m2 %d^3, exact dots on 1 %% of D" % args.size3, r)
+    r = config4(n_tiles=args.tiles4)
+    row("4: fp16 32x32x8, %d tiles, three flush variants" % args.tiles4, r,
+        ", ".join("%s: %d differ" % (name, st["n_mismatch_bits"]) for name, st in r["stats"].items()))
+    r = config5(n_tiles=args.tiles5)
+    for kind, v in r.items():
+        row("5 (%s): 16x16x16, %d tiles, 16 models against the native MFMA" % (kind, args.tiles5), v,
+            "agreement %.4f .. %.4f" % (min(v["agreement"]), max(v["agreement"])))
+
+
+if __name__ == "__main__":
+    _report()
