@@ -108,3 +108,43 @@ def test_fma_family_on_a_gemm_shape_sampled(mm):
         assert int(got[0, i, j]) == ofma.emulate_element(A[0, i].tolist(), B[0, j].tolist(), int(C[0, i, j])), (i, j)
     chain = ModelParams(group_len=1, frac_bits=46, c_mode=C_AFTER_EXACT, out_round=RNE)
     assert_same(got, gpu_emulate(mm, chain, A, B, C, fm.FP32, fm.FP32), "gemm shape")
+
+
+@pytest.mark.parametrize("shape", [(1, 64, 64, 64), (2, 128, 64, 80), (1, 64, 192, 128)])
+def test_fma_family_lds_tiled_kernel(mm, shape):
+    # large shapes go through LDS in 64 x 64 blocks: equal, element by element, to the simple kernel (taken when the
+    # operands are off their 16-byte alignment), and to the oracle on sampled outputs and on every NaN output
+    nb, m, n, k = shape
+    rng = np.random.default_rng(5500 + m + n + k)
+    for trial in range(5):
+        print("case", shape, trial, flush=True)
+        A, B, C = zero_case(rng, nb, m, n, k) if trial == 4 else fp32_case(rng, nb, m, n, k, trial)
+        if trial == 1:          # a few NaN / infinite operands only: most outputs stay finite, some chains meet a NaN late
+            A, B, C = fp32_case(rng, nb, m, n, k, 2)
+            A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[fm.FP32], 0.002)
+            B = synth.sprinkle(rng, B, synth.SPECIAL_CODES[fm.FP32], 0.002)
+        for propagate, nan_bits in ((False, 0x7FC00000), (True, 0xFFC00000)):
+            got = gpu_fma(mm, A, B, C, nan_bits=nan_bits, nan_propagate=propagate)
+            assert gpu_fma.last_kernel == "fma chain%s, 64x64 blocks through LDS" % (", payloads" if propagate else ""), gpu_fma.last_kernel
+            simple = gpu_fma(mm, A, B, C, nan_bits=nan_bits, nan_propagate=propagate, offset_words=1)
+            assert "16x16 blocks" in gpu_fma.last_kernel
+            assert_same(got, simple, "tiled against simple %s trial %d propagate %d" % (shape, trial, propagate))
+            nan = np.argwhere((got & 0x7FFFFFFF) > 0x7F800000)[:150]
+            picks = [tuple(x) for x in nan] + [(int(rng.integers(0, nb)), int(rng.integers(0, m)), int(rng.integers(0, n))) for _ in range(60)]
+            for t, i, j in picks:
+                want = ofma.emulate_element(A[t, i].tolist(), B[t, j].tolist(), int(C[t, i, j]), nan_bits=nan_bits, nan_propagate=propagate)
+                assert int(got[t, i, j]) == want, (shape, trial, propagate, (t, i, j), hex(int(got[t, i, j])), hex(want))
+
+
+def test_fma_family_lds_tiled_kernel_in_place(mm):
+    # D may alias C
+    rng = np.random.default_rng(5600)
+    nb, m, n, k = 1, 64, 128, 64
+    A, B, C = fp32_case(rng, nb, m, n, k, 1)
+    want = gpu_fma(mm, A, B, C, nan_bits=0xFFC00000, nan_propagate=True)
+    h = mm.model_create(family=mm.FAMILY_FMA, nan_bits=0xFFC00000, nan_propagate=True)
+    dA, dB, dC = to_dev(A), to_dev(B), to_dev(C)
+    mm.emulate_mma(h, dA, dB, dC, dC, m, n, k, nb, (mm.FP32,) * 4)
+    assert "through LDS" in mm.last_kernel()
+    mm.model_destroy(h)
+    assert_same(to_host(dC, np.uint32), want, "in place")
