@@ -87,78 +87,111 @@ emulate_fma_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ 
     }
 }
 
-// Large problems: a workgroup owns a 64 x 64 block of D, a thread a 4 x 4 block of it; A and B go through LDS sixteen k
-// at a time, transposed so that a thread reads its four rows (columns) with one 128-bit load.  Every output still runs
-// its own chain d <- fma(a_k, b_k, d) in k order.  A NaN is sticky in such a chain, so the loop carries no test: an
-// output that ends as a NaN is the model's one pattern, or, under the payload rule (where the step that produced it
-// matters), is run again step by step from global memory.  m and n multiples of 64, k of 16, rows 16-byte aligned.
-constexpr int FT = 64, FK = 16, FPAD = 4;
+// Large problems: a workgroup owns a 64 x 64 (NT = 1) or 128 x 128 (NT = 2) block of D, a thread NT x NT sub-blocks of
+// 4 x 4 outputs, 64 apart; A and B go through LDS sixteen k at a time, transposed so that a thread reads four rows
+// (columns) with one 128-bit load.  Every output still runs its own chain d <- fma(a_k, b_k, d) in k order.  A NaN is
+// sticky in such a chain, so the loop carries no test: an output that ends as a NaN is the model's one pattern, or, under
+// the payload rule (where the step that produced it matters), is run again step by step from global memory.  m and n
+// multiples of the block, k of 16, rows 16-byte aligned.
+constexpr int FK = 16, FPAD = 4;
 
-template <bool PROPAGATE>
+template <bool PROPAGATE, int NT>
 __global__ void __launch_bounds__(256)
 emulate_fma_tiled_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B, const uint32_t *C, uint32_t *D, uint32_t m,
                          uint32_t n, uint32_t k, uint32_t nan_bits)
 {
+    constexpr int FT = 64 * NT;
     __shared__ __attribute__((aligned(16))) float As[FK][FT + FPAD];
     __shared__ __attribute__((aligned(16))) float Bs[FK][FT + FPAD];
     const uint32_t bn = n / FT, bpt = (m / FT) * bn;
     const uint32_t t = blockIdx.x / bpt, r0 = blockIdx.x % bpt;
     const uint32_t i0 = FT * (r0 / bn), j0 = FT * (r0 % bn);
     const uint32_t tid = threadIdx.x, ty = tid / 16u, tx = tid % 16u;
-    const uint32_t lrow = tid / 4u, lk = 4u * (tid % 4u);                    // this thread's part of a staged panel
+    const uint32_t lrow = tid / 4u, lk = 4u * (tid % 4u);                    // this thread's part of a staged panel (+ 64 q)
     const uint32_t *a_src = A + ((uint64_t)t * m + i0 + lrow) * k + lk;
     const uint32_t *b_src = B + ((uint64_t)t * n + j0 + lrow) * k + lk;
-    const uint64_t d0 = ((uint64_t)t * m + i0 + 4u * ty) * n + j0 + 4u * tx;    // + r * n + c
+    // output (hr, r, hc, c): row i0 + 64 hr + 4 ty + r, column j0 + 64 hc + 4 tx + c
+    const uint64_t d0 = ((uint64_t)t * m + i0 + 4u * ty) * n + j0 + 4u * tx;
 
-    float acc[4][4];
+    float acc[NT][4][NT][4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const uint4 c4 = *reinterpret_cast<const uint4 *>(C + d0 + (uint64_t)r * n);
-        acc[r][0] = __uint_as_float(c4.x); acc[r][1] = __uint_as_float(c4.y);
-        acc[r][2] = __uint_as_float(c4.z); acc[r][3] = __uint_as_float(c4.w);
+    for (int hr = 0; hr < NT; ++hr)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int hc = 0; hc < NT; ++hc) {
+                const uint4 c4 = *reinterpret_cast<const uint4 *>(C + d0 + (uint64_t)(64 * hr + r) * n + 64 * hc);
+                acc[hr][r][hc][0] = __uint_as_float(c4.x); acc[hr][r][hc][1] = __uint_as_float(c4.y);
+                acc[hr][r][hc][2] = __uint_as_float(c4.z); acc[hr][r][hc][3] = __uint_as_float(c4.w);
+            }
+    uint4 pa[NT], pb[NT];
+#pragma unroll
+    for (int q = 0; q < NT; ++q) {
+        pa[q] = *reinterpret_cast<const uint4 *>(a_src + (uint64_t)(64 * q) * k);
+        pb[q] = *reinterpret_cast<const uint4 *>(b_src + (uint64_t)(64 * q) * k);
     }
-    uint4 pa = *reinterpret_cast<const uint4 *>(a_src), pb = *reinterpret_cast<const uint4 *>(b_src);
     for (uint32_t k0 = 0; k0 < k; k0 += FK) {
         __syncthreads();                                                     // the previous panel's readers are done
-        As[lk + 0][lrow] = __uint_as_float(pa.x); As[lk + 1][lrow] = __uint_as_float(pa.y);
-        As[lk + 2][lrow] = __uint_as_float(pa.z); As[lk + 3][lrow] = __uint_as_float(pa.w);
-        Bs[lk + 0][lrow] = __uint_as_float(pb.x); Bs[lk + 1][lrow] = __uint_as_float(pb.y);
-        Bs[lk + 2][lrow] = __uint_as_float(pb.z); Bs[lk + 3][lrow] = __uint_as_float(pb.w);
+#pragma unroll
+        for (int q = 0; q < NT; ++q) {
+            const uint32_t row = lrow + 64u * q;
+            As[lk + 0][row] = __uint_as_float(pa[q].x); As[lk + 1][row] = __uint_as_float(pa[q].y);
+            As[lk + 2][row] = __uint_as_float(pa[q].z); As[lk + 3][row] = __uint_as_float(pa[q].w);
+            Bs[lk + 0][row] = __uint_as_float(pb[q].x); Bs[lk + 1][row] = __uint_as_float(pb[q].y);
+            Bs[lk + 2][row] = __uint_as_float(pb[q].z); Bs[lk + 3][row] = __uint_as_float(pb[q].w);
+        }
         __syncthreads();
         if (k0 + FK < k) {                                                   // next panel in flight during the arithmetic
-            pa = *reinterpret_cast<const uint4 *>(a_src + k0 + FK);
-            pb = *reinterpret_cast<const uint4 *>(b_src + k0 + FK);
+#pragma unroll
+            for (int q = 0; q < NT; ++q) {
+                pa[q] = *reinterpret_cast<const uint4 *>(a_src + (uint64_t)(64 * q) * k + k0 + FK);
+                pb[q] = *reinterpret_cast<const uint4 *>(b_src + (uint64_t)(64 * q) * k + k0 + FK);
+            }
         }
 #pragma unroll
         for (int kk = 0; kk < FK; ++kk) {
-            const float4 av = *reinterpret_cast<const float4 *>(&As[kk][4u * ty]);
-            const float4 bv = *reinterpret_cast<const float4 *>(&Bs[kk][4u * tx]);
-            const float a[4] = {av.x, av.y, av.z, av.w}, b[4] = {bv.x, bv.y, bv.z, bv.w};
+            float a[NT][4], b[NT][4];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int c = 0; c < 4; ++c) acc[r][c] = __builtin_fmaf(a[r], b[c], acc[r][c]);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        uint32_t out[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            out[c] = __float_as_uint(acc[r][c]);
-            if (is_nan32(out[c])) {
-                out[c] = nan_bits;
-                if (PROPAGATE) {
-                    const uint32_t *a = A + ((uint64_t)t * m + i0 + 4u * ty + r) * k;
-                    const uint32_t *b = B + ((uint64_t)t * n + j0 + 4u * tx + c) * k;
-                    uint32_t d = C[d0 + (uint64_t)r * n + c];
-                    for (uint32_t kk = 0; kk < k; ++kk) d = fma_step<true>(a[kk], b[kk], d, nan_bits);
-                    out[c] = d;
-                }
+            for (int h = 0; h < NT; ++h) {
+                const float4 av = *reinterpret_cast<const float4 *>(&As[kk][64 * h + 4u * ty]);
+                const float4 bv = *reinterpret_cast<const float4 *>(&Bs[kk][64 * h + 4u * tx]);
+                a[h][0] = av.x; a[h][1] = av.y; a[h][2] = av.z; a[h][3] = av.w;
+                b[h][0] = bv.x; b[h][1] = bv.y; b[h][2] = bv.z; b[h][3] = bv.w;
             }
+#pragma unroll
+            for (int hr = 0; hr < NT; ++hr)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int hc = 0; hc < NT; ++hc)
+#pragma unroll
+                        for (int c = 0; c < 4; ++c) acc[hr][r][hc][c] = __builtin_fmaf(a[hr][r], b[hc][c], acc[hr][r][hc][c]);
         }
-        *reinterpret_cast<uint4 *>(D + d0 + (uint64_t)r * n) = make_uint4(out[0], out[1], out[2], out[3]);
     }
+#pragma unroll
+    for (int hr = 0; hr < NT; ++hr)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int hc = 0; hc < NT; ++hc) {
+                const uint64_t o = d0 + (uint64_t)(64 * hr + r) * n + 64 * hc;
+                uint32_t out[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    out[c] = __float_as_uint(acc[hr][r][hc][c]);
+                    if (is_nan32(out[c])) {
+                        out[c] = nan_bits;
+                        if (PROPAGATE) {
+                            const uint32_t *a = A + ((uint64_t)t * m + i0 + 64u * hr + 4u * ty + r) * k;
+                            const uint32_t *b = B + ((uint64_t)t * n + j0 + 64u * hc + 4u * tx + c) * k;
+                            uint32_t d = C[o + c];
+                            for (uint32_t kk = 0; kk < k; ++kk) d = fma_step<true>(a[kk], b[kk], d, nan_bits);
+                            out[c] = d;
+                        }
+                    }
+                }
+                *reinterpret_cast<uint4 *>(D + o) = make_uint4(out[0], out[1], out[2], out[3]);
+            }
 }
 
 template <bool PROPAGATE, bool BLOCKED, int VEC>
@@ -183,14 +216,23 @@ static mmaemu_status launch_p(const void *A, const void *B, const void *C, void 
     const bool blocked = m % 16 == 0 && n % 16 == 0;
     const uintptr_t addr = reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B);
     const uintptr_t addr_cd = reinterpret_cast<uintptr_t>(C) | reinterpret_cast<uintptr_t>(D);
-    const uint64_t tiles = batch * (m / FT) * (n / FT);
-    if (m % FT == 0 && n % FT == 0 && k % FK == 0 && k >= 4 * FK && ((addr | addr_cd) & 15) == 0 && tiles <= 0x7FFFFFFFull) {
+    if (m % 64 == 0 && n % 64 == 0 && k % FK == 0 && k >= 4 * FK && ((addr | addr_cd) & 15) == 0) {
         // (D may alias C: a thread reads exactly the elements of C it later writes)
-        hipLaunchKernelGGL((emulate_fma_tiled_kernel<PROPAGATE>), dim3((uint32_t)tiles), dim3(256), 0, s, (const uint32_t *)A,
-                           (const uint32_t *)B, (const uint32_t *)C, (uint32_t *)D, m, n, k, nan_bits);
-        MMAEMU_HIP(hipGetLastError());
-        set_last_kernel("fma chain%s, 64x64 blocks through LDS", PROPAGATE ? ", payloads" : "");
-        return MMAEMU_OK;
+        const uint64_t tiles64 = batch * (m / 64) * (n / 64), tiles128 = batch * (m / 128) * (n / 128);
+        if (m % 128 == 0 && n % 128 == 0 && tiles128 >= 512 && tiles128 <= 0x7FFFFFFFull) {      // two workgroups per CU and more
+            hipLaunchKernelGGL((emulate_fma_tiled_kernel<PROPAGATE, 2>), dim3((uint32_t)tiles128), dim3(256), 0, s, (const uint32_t *)A,
+                               (const uint32_t *)B, (const uint32_t *)C, (uint32_t *)D, m, n, k, nan_bits);
+            MMAEMU_HIP(hipGetLastError());
+            set_last_kernel("fma chain%s, 128x128 blocks through LDS", PROPAGATE ? ", payloads" : "");
+            return MMAEMU_OK;
+        }
+        if (tiles64 <= 0x7FFFFFFFull) {
+            hipLaunchKernelGGL((emulate_fma_tiled_kernel<PROPAGATE, 1>), dim3((uint32_t)tiles64), dim3(256), 0, s, (const uint32_t *)A,
+                               (const uint32_t *)B, (const uint32_t *)C, (uint32_t *)D, m, n, k, nan_bits);
+            MMAEMU_HIP(hipGetLastError());
+            set_last_kernel("fma chain%s, 64x64 blocks through LDS", PROPAGATE ? ", payloads" : "");
+            return MMAEMU_OK;
+        }
     }
     const int vec = (k % 4 == 0 && (addr & 15) == 0) ? 4 : ((k % 2 == 0 && (addr & 7) == 0) ? 2 : 1);
     if (blocked) {

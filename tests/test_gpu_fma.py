@@ -110,13 +110,14 @@ def test_fma_family_on_a_gemm_shape_sampled(mm):
     assert_same(got, gpu_emulate(mm, chain, A, B, C, fm.FP32, fm.FP32), "gemm shape")
 
 
-@pytest.mark.parametrize("shape", [(1, 64, 64, 64), (2, 128, 64, 80), (1, 64, 192, 128)])
+@pytest.mark.parametrize("shape", [(1, 64, 64, 64), (2, 128, 64, 80), (1, 64, 192, 128), (512, 128, 128, 64), (130, 256, 128, 80)])
 def test_fma_family_lds_tiled_kernel(mm, shape):
     # large shapes go through LDS in 64 x 64 blocks: equal, element by element, to the simple kernel (taken when the
     # operands are off their 16-byte alignment), and to the oracle on sampled outputs and on every NaN output
     nb, m, n, k = shape
     rng = np.random.default_rng(5500 + m + n + k)
-    for trial in range(5):
+    big = m % 128 == 0 and n % 128 == 0 and nb * (m // 128) * (n // 128) >= 512          # 128 x 128 blocks
+    for trial in ((1, 4) if big else range(5)):
         print("case", shape, trial, flush=True)
         A, B, C = zero_case(rng, nb, m, n, k) if trial == 4 else fp32_case(rng, nb, m, n, k, trial)
         if trial == 1:          # a few NaN / infinite operands only: most outputs stay finite, some chains meet a NaN late
@@ -125,7 +126,7 @@ def test_fma_family_lds_tiled_kernel(mm, shape):
             B = synth.sprinkle(rng, B, synth.SPECIAL_CODES[fm.FP32], 0.002)
         for propagate, nan_bits in ((False, 0x7FC00000), (True, 0xFFC00000)):
             got = gpu_fma(mm, A, B, C, nan_bits=nan_bits, nan_propagate=propagate)
-            assert gpu_fma.last_kernel == "fma chain%s, 64x64 blocks through LDS" % (", payloads" if propagate else ""), gpu_fma.last_kernel
+            assert gpu_fma.last_kernel == "fma chain%s, %s blocks through LDS" % (", payloads" if propagate else "", "128x128" if big else "64x64"), gpu_fma.last_kernel
             simple = gpu_fma(mm, A, B, C, nan_bits=nan_bits, nan_propagate=propagate, offset_words=1)
             assert "16x16 blocks" in gpu_fma.last_kernel
             assert_same(got, simple, "tiled against simple %s trial %d propagate %d" % (shape, trial, propagate))
