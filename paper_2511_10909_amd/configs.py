@@ -373,6 +373,12 @@ def _report(argv=None):
     for kind, v in r.items():
         row("5 (%s): 16x16x16, %d tiles, 16 models against the native MFMA" % (kind, args.tiles5), v,
             "agreement %.4f .. %.4f" % (min(v["agreement"]), max(v["agreement"])))
+    # beside the five: the validation loop of Sec. 3.1 Step 4 on one FP16 and one FP32 instruction of this GPU
+    from . import presets
+    for instr, name in ((mm.MFMA_F32_32X32X8_F16, "v_mfma_f32_32x32x8_f16"), (mm.MFMA_F32_16X16X4_F32, "v_mfma_f32_16x16x4_f32")):
+        r = validate_against_mfma(instr, presets.GFX950_MFMA[instr], n_tiles=1 << 16, seeds=(0, 1))
+        bad = sum(st["n_mismatch_bits"] for st in r.values() if isinstance(st, dict))
+        row("validation of the fitted model against %s, 2^16 tiles, every input family, two seeds" % name, r, "%d outputs differ; %s" % (bad, r["kernel"]))
 
 
 if __name__ == "__main__":
