@@ -219,3 +219,13 @@ def test_config5_closed_loop(cfg, mm):
         for a in res["agreement"]:
             assert 0.0 <= a <= 1.0
         assert Dhw.shape == (chunk, 16, 16)
+
+
+def test_config1_replayed_from_a_hip_graph_gives_the_same_statistics():
+    from paper_2511_10909_amd import configs
+    eager = configs.config1(n_tiles=300)
+    graph = configs.config1(n_tiles=300, use_graph=True)
+    assert graph["stats"] == eager["stats"] and graph["stats"]["n_compared"] == 300 * 256
+    import torch
+    for name in ("D0", "D1"):
+        assert torch.equal(graph["dev"][name], eager["dev"][name])
