@@ -367,6 +367,34 @@ gen_normal_tile_kernel(GenArgs g, T *out, uint64_t ept, uint64_t first_tile, uin
     }
 }
 
+// SCALE_TILE for tiles of at most 256 elements that start on a Philox block (elements per tile a multiple of 4): one
+// wavefront per tile, the maximum by lane shuffles, no LDS and no barrier.  Same values, same scale, same casts.
+template <typename T>
+__global__ void __launch_bounds__(256)
+gen_normal_tile_wave_kernel(GenArgs g, T *out, uint64_t ept, uint64_t first_tile, uint64_t n_tiles)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const uint64_t nwaves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    const uint64_t g_call0 = first_tile * ept;
+    const uint32_t nblk = (uint32_t)(ept / 4);
+    for (uint64_t tile = wave; tile < n_tiles; tile += nwaves) {
+        const uint64_t lo = (first_tile + tile) * ept, hi = lo + ept, blk_lo = lo >> 2;
+        double z[4] = {0.0, 0.0, 0.0, 0.0}, mx = 0.0;
+        if (lane < nblk) {
+            block_normals(g, blk_lo + lane, z);
+            mx = block_absmax(z, blk_lo + lane, lo, hi);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double other = __shfl_xor(mx, o);
+            mx = other > mx ? other : mx;
+        }
+        const double scale = g.scale_target / mx;
+        if (lane < nblk) write_block<T>(g, out + (lo - g_call0), blk_lo + lane, z, scale, true, lo, ept);
+    }
+}
+
 // ---- host side ------------------------------------------------------------------------
 
 template <typename T>
@@ -391,6 +419,10 @@ static mmaemu_status launch_typed(const GenArgs &ga, void *out, uint64_t ept, ui
                            (unsigned long long *)workspace);
         hipLaunchKernelGGL((gen_normal_kernel<T>), dim3((uint32_t)grid), dim3(256), 0, s, ga, (T *)out, g0, total, blk0, nblk,
                            (const double *)workspace);
+    } else if (ept % 4 == 0 && ept <= 256) {
+        const uint64_t wgrid = (n_tiles + 3) / 4 > (1ull << 20) ? (1ull << 20) : (n_tiles + 3) / 4;
+        hipLaunchKernelGGL((gen_normal_tile_wave_kernel<T>), dim3((uint32_t)wgrid), dim3(256), 0, s, ga, (T *)out, ept, first_tile,
+                           n_tiles);
     } else {
         const uint64_t per_tile_blocks = (ept + 3) / 4 + 1;
         uint32_t threads = per_tile_blocks <= 64 ? 64 : per_tile_blocks <= 128 ? 128 : 256;
