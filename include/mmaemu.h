@@ -327,6 +327,20 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *gen, void *out, mmaemu_dt
                               void *workspace, void *hip_stream);
 
 /*
+ * mmaemu_generate for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without `workspace`, same output
+ * bit for bit.  The eight bytes that per-tensor scaling needs come out of a 256-byte array that is part of the
+ * library's image (one copy per GPU, held until the process ends); the call allocates and frees nothing.  At most
+ * MMAEMU_GENERATE_NOALLOC_MAX_ELEMS (2^40) elements per call: more is MMAEMU_ERR_SHAPE.  Every call on a GPU uses
+ * that GPU's one array, and the call clears what it needs first, so calls that may overlap on one GPU (different
+ * streams, no ordering between them) race on it: order them, or use mmaemu_generate with a workspace of their own.
+ */
+#define MMAEMU_GENERATE_NOALLOC_MAX_ELEMS (1ull << 40)
+mmaemu_status mmaemu_generate_noalloc(const mmaemu_gen_params *gen, void *out, mmaemu_dtype dtype,
+                                      uint64_t elems_per_tile, uint64_t first_tile, uint64_t n_tiles,
+                                      void *hip_stream);
+
+/*
  * Native-instruction probe: the device under test of the closed loop (paper Sec. 3.3:
  * instruction-level MMA interfaces through intrinsics).  Runs one real v_mfma
  * instruction per tile on the same operand layout as mmaemu_emulate_mma:

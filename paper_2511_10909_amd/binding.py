@@ -114,6 +114,7 @@ _lib.mmaemu_emulate_mma_scaled.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u
 _lib.mmaemu_stats_reset.argtypes = [_vp, _vp]
 _lib.mmaemu_compare.argtypes = [_vp, _vp, _u64, _u64, ctypes.c_int, _vp, _vp]
 _lib.mmaemu_generate.argtypes = [ctypes.POINTER(GenParams), _vp, ctypes.c_int, _u64, _u64, _u64, _vp, _vp]
+_lib.mmaemu_generate_noalloc.argtypes = [ctypes.POINTER(GenParams), _vp, ctypes.c_int, _u64, _u64, _u64, _vp]
 _lib.mmaemu_mfma_info.argtypes = [ctypes.c_int] + [ctypes.POINTER(_u32)] * 3 + [ctypes.POINTER(ctypes.c_int)] * 2
 _lib.mmaemu_mfma_probe.argtypes = [ctypes.c_int, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
 _lib.mmaemu_mfma_probe_scaled.argtypes = [ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
@@ -210,6 +211,12 @@ def generate(out, dtype, elems_per_tile, first_tile, n_tiles, family, seed=0, op
                   exp_lo, exp_hi, int(exp_zero), scale_scope, scale_target)
     _check(_lib.mmaemu_generate(ctypes.byref(g), _ptr(out), dtype, elems_per_tile, first_tile, n_tiles,
                                 _ptr(workspace), _stream(stream)))
+
+
+def generate_noalloc(out, dtype, elems_per_tile, first_tile, n_tiles, family, seed=0, operand=0, exp_lo=0, exp_hi=0,
+                     exp_zero=False, scale_scope=SCALE_NONE, scale_target=1.0, stream=None):
+    g = GenParams(ctypes.sizeof(GenParams), family, seed, operand, exp_lo, exp_hi, int(exp_zero), scale_scope, scale_target)
+    _check(_lib.mmaemu_generate_noalloc(ctypes.byref(g), _ptr(out), dtype, elems_per_tile, first_tile, n_tiles, _stream(stream)))
 
 
 def mfma_info(instr):

@@ -375,9 +375,11 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
     return launch_compare(D0, D1, count, index_base, d == MMAEMU_FP16, st, (hipStream_t)hip_stream);
 }
 
-mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtype dtype, uint64_t ept,
-                              uint64_t first_tile, uint64_t n_tiles, void *workspace, void *hip_stream)
+// argument checks shared by mmaemu_generate and mmaemu_generate_noalloc; *run = false: valid, nothing to do
+static mmaemu_status generate_check(const mmaemu_gen_params *g, void *out, mmaemu_dtype dtype, uint64_t ept,
+                                    uint64_t first_tile, uint64_t n_tiles, bool *run)
 {
+    *run = false;
     if (!g) { set_error("generate: NULL params"); return MMAEMU_ERR_INVALID_ARG; }
     if (g->struct_size != sizeof(mmaemu_gen_params)) {
         set_error("generate: struct_size %u, expected %zu", g->struct_size, sizeof(mmaemu_gen_params));
@@ -418,10 +420,36 @@ mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtyp
     if (n_tiles == 0) return MMAEMU_OK;
     if (!out) { set_error("generate: NULL output"); return MMAEMU_ERR_INVALID_ARG; }
     if ((uintptr_t)out & (uintptr_t)(f.width / 8 - 1)) { set_error("generate: output not aligned to its element size"); return MMAEMU_ERR_INVALID_ARG; }
+    *run = true;
+    return MMAEMU_OK;
+}
+
+mmaemu_status mmaemu_generate(const mmaemu_gen_params *g, void *out, mmaemu_dtype dtype, uint64_t ept,
+                              uint64_t first_tile, uint64_t n_tiles, void *workspace, void *hip_stream)
+{
+    bool run;
+    const mmaemu_status st = generate_check(g, out, dtype, ept, first_tile, n_tiles, &run);
+    if (st != MMAEMU_OK || !run) return st;
+    const bool value_family = g->family == MMAEMU_GEN_NORMAL || g->family == MMAEMU_GEN_UNIFORM || g->family == MMAEMU_GEN_NORMAL_OUTLIERS;
     if (value_family && g->scale_scope == MMAEMU_SCALE_TENSOR) {
         if (!workspace || ((uintptr_t)workspace & 7)) { set_error("generate: SCALE_TENSOR needs an 8-byte aligned workspace"); return MMAEMU_ERR_INVALID_ARG; }
     }
     return launch_generate(*g, out, dtype, ept, first_tile, n_tiles, workspace, (hipStream_t)hip_stream);
+}
+
+mmaemu_status mmaemu_generate_noalloc(const mmaemu_gen_params *g, void *out, mmaemu_dtype dtype, uint64_t ept,
+                                      uint64_t first_tile, uint64_t n_tiles, void *hip_stream)
+{
+    bool run;
+    const mmaemu_status st = generate_check(g, out, dtype, ept, first_tile, n_tiles, &run);
+    if (st != MMAEMU_OK) return st;
+    if (ept && n_tiles > MMAEMU_GENERATE_NOALLOC_MAX_ELEMS / ept) {
+        set_error("generate_noalloc: %llu tiles of %llu elements exceed the limit of 2^40 elements per call",
+                  (unsigned long long)n_tiles, (unsigned long long)ept);
+        return MMAEMU_ERR_SHAPE;
+    }
+    if (!run) return MMAEMU_OK;
+    return launch_generate_noalloc(*g, out, dtype, ept, first_tile, n_tiles, (hipStream_t)hip_stream);
 }
 
 // the block-scaled instructions: 16x16x128 (25 ids) and 32x32x64 (25 ids)

@@ -99,6 +99,9 @@ mmaemu_status launch_compare(const void *d0, const void *d1, uint64_t count, uin
                              mmaemu_stats *st, hipStream_t s);
 mmaemu_status launch_generate(const mmaemu_gen_params &g, void *out, uint32_t dtype, uint64_t ept,
                               uint64_t first_tile, uint64_t n_tiles, void *workspace, hipStream_t s);
+// the same with the running maximum of the per-tensor scaling in the library's own static device array
+mmaemu_status launch_generate_noalloc(const mmaemu_gen_params &g, void *out, uint32_t dtype, uint64_t ept,
+                                      uint64_t first_tile, uint64_t n_tiles, hipStream_t s);
 mmaemu_status launch_mfma_probe(uint32_t instr, const void *A, const void *B, const void *C, void *D,
                                 uint32_t k, uint64_t batch, hipStream_t s);
 mmaemu_status launch_mfma_probe_scaled(uint32_t instr, const void *A, const void *B, const void *C, void *D,

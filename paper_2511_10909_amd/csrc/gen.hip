@@ -11,6 +11,8 @@
 // multiply-add anywhere would change the bits.
 #include "common.hpp"
 
+#include <mutex>
+
 namespace mmaemu {
 
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -471,6 +473,42 @@ mmaemu_status launch_generate(const mmaemu_gen_params &gp, void *out, uint32_t d
     case 16: return launch_typed<uint16_t>(ga, out, ept, first_tile, n_tiles, workspace, s);
     default: return launch_typed<uint32_t>(ga, out, ept, first_tile, n_tiles, workspace, s);
     }
+}
+
+// ---- the variant for callers that cannot allocate -----------------------------------------
+// The per-tensor scaling needs eight bytes of device memory for the running maximum.  Here they come out of an
+// array that is part of the library's image: every GPU the library runs on holds its own copy at its own address
+// until the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address it
+// returns (looked up once per device, with that device current) is what kernels and fills get.
+static __device__ __align__(256) unsigned char scratch[256];
+
+static constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[MAX_DEVICES];          // per device, null until the first call on it
+
+static mmaemu_status scratch_for_current_device(void **out)
+{
+    int dev = -1;
+    MMAEMU_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) { set_error("generate_noalloc: device ordinal %d outside 0..%d", dev, MAX_DEVICES - 1); return MMAEMU_ERR_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        MMAEMU_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { set_error("generate_noalloc: the scratch array has no device address"); return MMAEMU_ERR_HIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return MMAEMU_OK;
+}
+
+mmaemu_status launch_generate_noalloc(const mmaemu_gen_params &gp, void *out, uint32_t dtype, uint64_t ept,
+                                      uint64_t first_tile, uint64_t n_tiles, hipStream_t s)
+{
+    void *ws = nullptr;
+    const mmaemu_status st = scratch_for_current_device(&ws);
+    if (st != MMAEMU_OK) return st;
+    return launch_generate(gp, out, dtype, ept, first_tile, n_tiles, ws, s);      // (its first kernel clears the maximum)
 }
 
 } // namespace mmaemu
