@@ -267,6 +267,36 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
                              mmaemu_dtype d, mmaemu_stats *dev_stats, void *hip_stream);
 
 /*
+ * The closed loop on several candidate models at once (paper Sec. 3.1 Step 4: a candidate Phi is run on random inputs and
+ * compared bit by bit with the interface, Eq. 2; here n_models candidates share one pass over the inputs).  For every
+ * model i: D_i = Phi_i(A, B, C) as mmaemu_emulate_mma computes it, compared with the reference as mmaemu_compare does,
+ * the result accumulated into dev_stats[i] (device array of n_models structs; first_mismatch_index counts from
+ * index_base).  The reference is Dref[batch][m][n] (device, FP32 patterns: typically the native instruction's
+ * output), or, when Dref is NULL, the output of models[0] (whose own row then reports no mismatch).
+ * D_out: NULL, or device memory for n_models * batch * m * n FP32 patterns; model i's outputs are then also written
+ * at D_out + i * batch * m * n.  D_out must not overlap A, B, C or Dref.
+ * Models of the FDPA family with c_mode C_IN_GROUP, no variation switches, frac_bits <= 40 and group length 4, 8 or
+ * 16, on 16 x 16 x 16 or 32 x 32 x 8 tiles with 8-byte aligned A and B of 8- or 16-bit types, run in kernels that stage
+ * and decode the operands once for up to 16 models of equal group length and keep every output in registers: D
+ * reaches memory only on request.  Any other model runs through mmaemu_emulate_mma and mmaemu_compare and needs
+ * D_out, as does a reference taken from models[0] when the models do not all fit one such launch.
+ * At most MMAEMU_COMPARE_MANY_MAX models per call.  batch = 0 is a no-op.
+ * Errors: as mmaemu_emulate_mma; UNSUPPORTED (FP16 accumulators; D_out needed but NULL), INVALID_ARG (n_models, NULL).
+ */
+#define MMAEMU_COMPARE_MANY_MAX 64
+mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uint32_t n_models, const void *A,
+                                          const void *B, const void *C, const void *Dref, void *D_out, uint32_t m,
+                                          uint32_t n, uint32_t k, uint64_t batch, mmaemu_dtypes dtypes,
+                                          uint64_t index_base, mmaemu_stats *dev_stats, void *hip_stream);
+
+/* Host-side query, for reports and for callers that want one launch per call: class_of_model[i] (host array of
+ * n_models) receives a non-negative number that is equal for models which mmaemu_emulate_compare_many runs in common
+ * launches on this problem (given 8-byte aligned A and B), or -1 for a model that goes through mmaemu_emulate_mma and
+ * mmaemu_compare there. */
+mmaemu_status mmaemu_compare_many_classes(const mmaemu_model *const *models, uint32_t n_models, uint32_t m, uint32_t n,
+                                          uint32_t k, mmaemu_dtypes dtypes, int32_t *class_of_model);
+
+/*
  * Synthetic operand generation (the input families of Sec. 3.1 Step 4: common
  * distributions and random bit streams).  Counter-based: element g (global index
  * (first_tile + t) * elems_per_tile + e) of operand `operand` owns words

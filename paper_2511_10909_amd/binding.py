@@ -111,6 +111,8 @@ _lib.mmaemu_model_destroy.argtypes = [_vp]
 _lib.mmaemu_model_get_params.argtypes = [_vp, ctypes.POINTER(ModelParams)]
 _lib.mmaemu_emulate_mma.argtypes = [_vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u64, Dtypes, _vp]
 _lib.mmaemu_emulate_mma_scaled.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u32, _u64, Dtypes, _vp]
+_lib.mmaemu_emulate_compare_many.argtypes = [ctypes.POINTER(_vp), _u32, _vp, _vp, _vp, _vp, _vp, _u32, _u32, _u32, _u64, Dtypes, _u64, _vp, _vp]
+_lib.mmaemu_compare_many_classes.argtypes = [ctypes.POINTER(_vp), _u32, _u32, _u32, _u32, Dtypes, ctypes.POINTER(ctypes.c_int32)]
 _lib.mmaemu_stats_reset.argtypes = [_vp, _vp]
 _lib.mmaemu_compare.argtypes = [_vp, _vp, _u64, _u64, ctypes.c_int, _vp, _vp]
 _lib.mmaemu_generate.argtypes = [ctypes.POINTER(GenParams), _vp, ctypes.c_int, _u64, _u64, _u64, _vp, _vp]
@@ -197,6 +199,23 @@ def emulate_mma_scaled(model, A, B, C, D, SA, SB, block, m, n, k, batch, dtypes,
                                           _stream(stream)))
 
 
+def emulate_compare_many(models, A, B, C, Dref, D_out, m, n, k, batch, dtypes, dev_stats, index_base=0, stream=None):
+    """dev_stats: device memory for len(models) statistics structs (a uint8 tensor of len(models) * STATS_BYTES)."""
+    dt = dtypes if isinstance(dtypes, Dtypes) else Dtypes(*dtypes)
+    arr = (_vp * len(models))(*[h if isinstance(h, _vp) else _vp(h) for h in models])
+    _check(_lib.mmaemu_emulate_compare_many(arr, len(models), _ptr(A), _ptr(B), _ptr(C), _ptr(Dref), _ptr(D_out), m, n, k, batch, dt,
+                                            index_base, _ptr(dev_stats), _stream(stream)))
+
+
+def compare_many_classes(models, m, n, k, dtypes):
+    """Per model, the class under which emulate_compare_many launches it (equal numbers share launches), -1 if it runs unfused."""
+    dt = dtypes if isinstance(dtypes, Dtypes) else Dtypes(*dtypes)
+    arr = (_vp * len(models))(*[h if isinstance(h, _vp) else _vp(h) for h in models])
+    out = (ctypes.c_int32 * len(models))()
+    _check(_lib.mmaemu_compare_many_classes(arr, len(models), m, n, k, dt, out))
+    return list(out)
+
+
 def stats_reset(dev_stats, stream=None):
     _check(_lib.mmaemu_stats_reset(_ptr(dev_stats), _stream(stream)))
 
@@ -258,6 +277,12 @@ def _unpack(struct_type, dev_tensor):
 def read_stats(dev_stats):
     """Synchronising copy of a device mmaemu_stats (a uint8 tensor of STATS_BYTES) to a dict."""
     return _unpack(Stats, dev_stats)
+
+
+def read_stats_array(dev_stats, count):
+    """The same for an array of `count` structs (a uint8 tensor of count * STATS_BYTES): a list of dicts."""
+    flat = dev_stats.reshape(-1)
+    return [_unpack(Stats, flat[i * STATS_BYTES:(i + 1) * STATS_BYTES]) for i in range(count)]
 
 
 def read_err_stats(dev_err):

@@ -14,6 +14,7 @@ Workloads (synthetic stand-ins for the randomized validation of the paper's Sec.
   config5  closed-loop scan: 16 parameter sets x {bf16, fp8} 16x16x16 tiles against the native
            MFMA instruction
 """
+import bisect
 import time
 
 import torch
@@ -158,38 +159,80 @@ def config4_generate(A, B, C, first_tile, n_tiles, seed=0):
                 exp_hi=158, exp_zero=True)
 
 
-def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk=False):
+def _stats_array(count, dev):
+    st = torch.empty(count * mm.STATS_BYTES, dtype=torch.uint8, device=dev)
+    for i in range(count):
+        mm.stats_reset(st[i * mm.STATS_BYTES:])
+    return st
+
+
+class _Sampler:
+    """Keeps the operands and outputs of chosen tiles of a streamed run (device-side copies, no synchronisation)."""
+
+    def __init__(self, tiles):
+        self.tiles = sorted(int(t) for t in (tiles if tiles is not None else ()))
+        self.kept = []
+
+    def in_chunk(self, t0, nt):
+        lo, hi = bisect.bisect_left(self.tiles, t0), bisect.bisect_left(self.tiles, t0 + nt)
+        return [t - t0 for t in self.tiles[lo:hi]]
+
+    def take(self, t0, local, **tensors):
+        idx = torch.tensor(local, dtype=torch.int64, device=next(iter(tensors.values())).device)
+        rec = {name: (t.index_select(1, idx) if name == "D" else t.index_select(0, idx)) for name, t in tensors.items()}
+        rec["tiles"] = [t0 + i for i in local]
+        self.kept.append(rec)
+
+
+def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk=False, fused=True, sample_tiles=None):
+    """`fused`: the three variants share one pass over each chunk (mmaemu_emulate_compare_many, the no-flush variant's
+    outputs as the reference, D never written); otherwise one emulation and one comparison per variant.
+    `keep_first_chunk` / `sample_tiles`: operands and all three outputs of the first chunk / of the given tiles are
+    kept (those chunks also write D) and returned under "dev" / "samples"."""
     m = n = 32
     k = 8
     dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
     chunk = min(chunk, n_tiles)
+    nv = len(CONFIG4_VARIANTS)
     A, B = _buf((chunk, m, k), mm.FP16, dev), _buf((chunk, n, k), mm.FP16, dev)
     C = _buf((chunk, m, n), mm.FP32, dev)
-    Ds = [_buf((chunk, m, n), mm.FP32, dev) for _ in CONFIG4_VARIANTS]
-    stats = [_stats_buf(dev) for _ in CONFIG4_VARIANTS]
+    Dall = _buf((nv, chunk, m, n), mm.FP32, dev) if (not fused or keep_first_chunk or sample_tiles is not None) else None
+    stats = _stats_array(nv, dev)
     models = [mm.model_create(group_len=8, frac_bits=24, out_round=mm.RNE, **kw) for _, kw in CONFIG4_VARIANTS]
     kept = {}
+    sampler = _Sampler(sample_tiles)
 
     def run():
         kern = None
         for t0 in range(0, n_tiles, chunk):
             nt = min(chunk, n_tiles - t0)
             config4_generate(A, B, C, t0, nt, seed)
-            for h, D in zip(models, Ds):
-                mm.emulate_mma(h, A, B, C, D, m, n, k, nt, dt)
-            kern = mm.last_kernel()
-            for st, D in zip(stats, Ds):
-                mm.compare(D, Ds[0], nt * m * n, st, index_base=t0 * m * n)
-            if keep_first_chunk and t0 == 0:
-                torch.cuda.synchronize()
-                kept.update(A=A.clone(), B=B.clone(), C=C.clone(), D=[D.clone() for D in Ds])
+            local = sampler.in_chunk(t0, nt)
+            keep = keep_first_chunk and t0 == 0
+            want_d = (not fused) or keep or bool(local)
+            # ([variant][tile][m][n] for this chunk's tile count: the layout mmaemu_emulate_compare_many writes)
+            dump = Dall.reshape(-1)[: nv * nt * m * n].view(nv, nt, m, n) if want_d else None
+            if fused:
+                mm.emulate_compare_many(models, A, B, C, None, dump, m, n, k, nt, dt, stats, index_base=t0 * m * n)
+                kern = mm.last_kernel()
+            else:
+                for i, h in enumerate(models):
+                    mm.emulate_mma(h, A, B, C, dump[i], m, n, k, nt, dt)
+                kern = mm.last_kernel()
+                for i in range(nv):
+                    mm.compare(dump[i], dump[0], nt * m * n, stats[i * mm.STATS_BYTES:], index_base=t0 * m * n)
+            if keep:
+                kept.update(A=A.clone(), B=B.clone(), C=C.clone(), D=[dump[i].clone() for i in range(nv)])
+            if local:
+                sampler.take(t0, local, A=A[:nt], B=B[:nt], C=C[:nt], D=dump)
         return kern
 
     kernel, secs = _timed(run)
     for h in models:
         mm.model_destroy(h)
-    return dict(terms=3 * n_tiles * m * n * k, seconds=secs, kernel=kernel,
-                stats={name: mm.read_stats(st) for (name, _), st in zip(CONFIG4_VARIANTS, stats)}, dev=kept)
+    res = mm.read_stats_array(stats, nv)
+    return dict(terms=nv * n_tiles * m * n * k, seconds=secs, kernel=kernel,
+                stats={name: st for (name, _), st in zip(CONFIG4_VARIANTS, res)}, dev=kept, samples=sampler.kept)
 
 
 # (F, L_max, output rounding, flush both ways)
@@ -213,46 +256,108 @@ def config5_generate(kind, A, B, C, first_tile, n_tiles, seed=0):
     mm.generate(C, mm.FP32, 256, first_tile, n_tiles, mm.GEN_NORMAL, seed=seed, operand=2)
 
 
-def config5(n_tiles=1 << 24, chunk=1 << 16, seed=0, dev="cuda", kinds=("bf16", "fp8"), keep_first_chunk=False):
-    m = n = k = 16
+class ClosedLoopScan:
+    """Workload 5 for one operand type: the sixteen parameter sets over chunks of generated 16x16x16 tiles, each chunk
+    also run through the native MFMA instruction, per-set statistics of model against instruction.
+
+    `fused`: one mmaemu_emulate_compare_many call per class of sets that share launches (the statistics are formed
+    inside the emulation kernels); otherwise one mmaemu_emulate_mma and one mmaemu_compare per set.  `timer`, if given,
+    is called as timer(name, fn) around every emulation launch of a chunk whose index is a multiple of `time_every`
+    (it must run fn); bench.py uses it for HIP events."""
+
+    def __init__(self, kind, chunk=1 << 16, seed=0, dev="cuda", fused=True, with_dump=False):
+        self.kind, self.chunk, self.seed, self.fused = kind, chunk, seed, fused
+        self.ta, self.tb = (mm.BF16, mm.BF16) if kind == "bf16" else (mm.E4M3, mm.E5M2)
+        self.instr = mm.MFMA_F32_16X16X16_BF16 if kind == "bf16" else mm.MFMA_F32_16X16X32_FP8_BF8
+        self.dt = (self.ta, self.tb, mm.FP32, mm.FP32)
+        nm = len(CONFIG5_MODELS)
+        self.A, self.B = _buf((chunk, 16, 16), self.ta, dev), _buf((chunk, 16, 16), self.tb, dev)
+        self.C, self.Dhw = _buf((chunk, 16, 16), mm.FP32, dev), _buf((chunk, 16, 16), mm.FP32, dev)
+        self.D1 = None if fused else _buf((chunk, 16, 16), mm.FP32, dev)
+        self.Dall = _buf((nm, chunk, 16, 16), mm.FP32, dev) if with_dump else None
+        self.stats = _stats_array(nm, dev)
+        self.models = [mm.model_create(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(ftz), ftz_out=bool(ftz))
+                       for F, L, rho, ftz in CONFIG5_MODELS]
+        cls = mm.compare_many_classes(self.models, 16, 16, 16, self.dt)
+        self.groups = []                                   # lists of set indices; one launch each when fused
+        for c in sorted(set(cls)):
+            members = [i for i, x in enumerate(cls) if x == c]
+            self.groups.extend([[i] for i in members] if c < 0 else [members])
+        # the statistics array is laid out group by group, so that every group's structs are consecutive
+        order = [i for g in self.groups for i in g]
+        self.pos = {i: q for q, i in enumerate(order)}
+        self.kernels = {}
+
+    def close(self):
+        for h in self.models:
+            mm.model_destroy(h)
+        self.models = []
+
+    def reset(self):
+        for i in range(len(CONFIG5_MODELS)):
+            mm.stats_reset(self.stats[i * mm.STATS_BYTES:])
+
+    def _slot(self, i):
+        return self.stats[self.pos[i] * mm.STATS_BYTES:]
+
+    def chunk_step(self, t0, nt, dump=False, timer=None):
+        """Generate tiles t0 .. t0 + nt - 1, run the instruction and every set, accumulate the statistics.
+        `dump`: every set's outputs of this chunk are also written to self.Dall[set]."""
+        A, B, C, Dhw = self.A, self.B, self.C, self.Dhw
+        config5_generate(self.kind, A, B, C, t0, nt, self.seed)
+        mm.mfma_probe(self.instr, A, B, C, Dhw, 16, nt)              # fp8: k positions 16..31 are fed as zeros
+        run = (lambda name, terms, fn: fn()) if timer is None else timer
+        if self.fused and not dump:
+            for gi, members in enumerate(self.groups):
+                hs = [self.models[i] for i in members]
+                run("group %d" % gi, len(members) * nt * 4096,
+                    lambda: mm.emulate_compare_many(hs, A, B, C, Dhw, None, 16, 16, 16, nt, self.dt, self._slot(members[0]), index_base=t0 * 256))
+                self.kernels.setdefault(gi, mm.last_kernel())
+        elif self.fused:
+            for i, h in enumerate(self.models):                      # (a set's dump area is its own slice of Dall)
+                mm.emulate_compare_many([h], A, B, C, Dhw, self.Dall[i, :nt], 16, 16, 16, nt, self.dt, self._slot(i), index_base=t0 * 256)
+        else:
+            for i, h in enumerate(self.models):
+                D = self.Dall[i, :nt] if dump else self.D1
+                run("set %d" % i, nt * 4096, lambda: mm.emulate_mma(h, A, B, C, D, 16, 16, 16, nt, self.dt))
+                self.kernels.setdefault(i, mm.last_kernel())
+                mm.compare(D, Dhw, nt * 256, self._slot(i), index_base=t0 * 256)
+
+    def read(self):
+        """Per-set statistics, a list of dicts in the order of CONFIG5_MODELS."""
+        res = mm.read_stats_array(self.stats, len(CONFIG5_MODELS))
+        return [res[self.pos[i]] for i in range(len(CONFIG5_MODELS))]
+
+
+def config5(n_tiles=1 << 24, chunk=1 << 16, seed=0, dev="cuda", kinds=("bf16", "fp8"), keep_first_chunk=False, fused=True,
+            sample_tiles=None):
     out = {}
     for kind in kinds:
-        ta, tb = (mm.BF16, mm.BF16) if kind == "bf16" else (mm.E4M3, mm.E5M2)
-        instr = mm.MFMA_F32_16X16X16_BF16 if kind == "bf16" else mm.MFMA_F32_16X16X32_FP8_BF8
-        dt = (ta, tb, mm.FP32, mm.FP32)
         ch = min(chunk, n_tiles)
-        A, B = _buf((ch, m, k), ta, dev), _buf((ch, n, k), tb, dev)
-        C, Dhw, D = (_buf((ch, m, n), mm.FP32, dev) for _ in range(3))
-        stats = [_stats_buf(dev) for _ in CONFIG5_MODELS]
-        models = [mm.model_create(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(ftz), ftz_out=bool(ftz))
-                  for F, L, rho, ftz in CONFIG5_MODELS]
+        need_dump = keep_first_chunk or sample_tiles is not None
+        scan = ClosedLoopScan(kind, ch, seed, dev, fused, with_dump=need_dump)
         kept = {}
-        kernels = []
+        sampler = _Sampler(sample_tiles)
 
         def run():
             for t0 in range(0, n_tiles, ch):
                 nt = min(ch, n_tiles - t0)
-                config5_generate(kind, A, B, C, t0, nt, seed)
-                mm.mfma_probe(instr, A, B, C, Dhw, k, nt)          # fp8: k positions 16..31 are fed as zeros
+                local = sampler.in_chunk(t0, nt)
                 keep = keep_first_chunk and t0 == 0
+                scan.chunk_step(t0, nt, dump=bool(keep or local))
                 if keep:
-                    torch.cuda.synchronize()
-                    kept.update(A=A.clone(), B=B.clone(), C=C.clone(), Dhw=Dhw.clone(), D=[])
-                for i, (h, st) in enumerate(zip(models, stats)):
-                    mm.emulate_mma(h, A, B, C, D, m, n, k, nt, dt)
-                    if t0 == 0:
-                        kernels.append(mm.last_kernel())
-                    mm.compare(D, Dhw, nt * m * n, st, index_base=t0 * m * n)
-                    if keep:
-                        torch.cuda.synchronize()
-                        kept["D"].append(D.clone())
+                    kept.update(A=scan.A.clone(), B=scan.B.clone(), C=scan.C.clone(), Dhw=scan.Dhw.clone(),
+                                D=[scan.Dall[i, :nt].clone() for i in range(len(CONFIG5_MODELS))])
+                if local:
+                    sampler.take(t0, local, A=scan.A[:nt], B=scan.B[:nt], C=scan.C[:nt], Dhw=scan.Dhw[:nt], D=scan.Dall[:, :nt])
 
         _, secs = _timed(run)
-        for h in models:
-            mm.model_destroy(h)
-        res = [mm.read_stats(st) for st in stats]
-        out[kind] = dict(terms=len(CONFIG5_MODELS) * n_tiles * m * n * k, seconds=secs, kernels=kernels, stats=res,
-                         agreement=[1.0 - s["n_mismatch_bits"] / max(s["n_compared"], 1) for s in res], dev=kept)
+        res = scan.read()
+        kernels = [scan.kernels[key] for key in sorted(scan.kernels)]
+        scan.close()
+        out[kind] = dict(terms=len(CONFIG5_MODELS) * n_tiles * 256 * 16, seconds=secs, kernels=kernels, stats=res,
+                         agreement=[1.0 - s["n_mismatch_bits"] / max(s["n_compared"], 1) for s in res], dev=kept,
+                         samples=sampler.kept)
     return out
 
 
@@ -374,8 +479,9 @@ def _report(argv=None):
     """`python -m paper_2511_10909_amd.configs`: the five workloads end to end, one table row each."""
     import argparse
     ap = argparse.ArgumentParser(description="run the five benchmark workloads end to end and print their rates")
-    ap.add_argument("--tiles4", type=int, default=1 << 22, help="tiles of workload 4 (the full workload has 2^26)")
-    ap.add_argument("--tiles5", type=int, default=1 << 20, help="tiles of workload 5 per operand type (the full workload has 2^24)")
+    ap.add_argument("--tiles4", type=int, default=1 << 26, help="tiles of workload 4 (the workload as stated: 2^26)")
+    ap.add_argument("--tiles5", type=int, default=1 << 24, help="tiles of workload 5 per operand type (as stated: 2^24)")
+    ap.add_argument("--unfused", action="store_true", help="workloads 4 and 5 with one emulation and one comparison per model")
     ap.add_argument("--size3", type=int, default=4096, help="m = n = k of workload 3")
     args = ap.parse_args(argv)
     config1(n_tiles=256)                                  # (first call: library load and allocator warm-up)
@@ -393,10 +499,10 @@ def _report(argv=None):
     row("2: bf16 1024^3, chained against fused", r, "%d of %d outputs differ" % (r["stats"]["n_mismatch_bits"], r["stats"]["n_compared"]))
     r = config3(size=args.size3)
     row("3: e4m3 x e5m2 %d^3, exact dots on 1 %% of D" % args.size3, r)
-    r = config4(n_tiles=args.tiles4)
+    r = config4(n_tiles=args.tiles4, fused=not args.unfused)
     row("4: fp16 32x32x8, %d tiles, three flush variants" % args.tiles4, r,
         ", ".join("%s: %d differ" % (name, st["n_mismatch_bits"]) for name, st in r["stats"].items()))
-    r = config5(n_tiles=args.tiles5)
+    r = config5(n_tiles=args.tiles5, fused=not args.unfused)
     for kind, v in r.items():
         row("5 (%s): 16x16x16, %d tiles, 16 models against the native MFMA" % (kind, args.tiles5), v,
             "agreement %.4f .. %.4f" % (min(v["agreement"]), max(v["agreement"])))

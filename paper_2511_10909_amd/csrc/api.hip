@@ -190,6 +190,61 @@ mmaemu_status mmaemu_model_get_params(const mmaemu_model *m, mmaemu_model_params
     return MMAEMU_OK;
 }
 
+// The FDPA family's parameters as the kernels take them, for a problem with k products per output (checks that depend
+// on k and on the accumulator's type included).
+static mmaemu_status fdpa_model_args(const mmaemu_model_params &mp, uint32_t k, bool acc16, ModelArgs &ma)
+{
+    const uint32_t L = (mp.group_len == 0 || mp.group_len > k) ? k : mp.group_len;
+    if (k % L) { set_error("emulate_mma: k=%u is not a multiple of the group length L=%u", k, L); return MMAEMU_ERR_SHAPE; }
+    if (mp.c_mode == MMAEMU_C_IN_GROUP && mp.frac_bits + 3 + ceil_log2(L) > 63) {      // the fused sum is a 64-bit integer
+        set_error("emulate_mma: C_IN_GROUP needs frac_bits + 3 + ceil(log2 L) <= 63");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    if (mp.c_mode == MMAEMU_C_AFTER_EXACT && mp.frac_bits + 2 + ceil_log2(L) > 56) {
+        set_error("emulate_mma: C_AFTER_EXACT needs frac_bits + 2 + ceil(log2 L) <= 56");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    const bool rd_mode = mp.c_mode == MMAEMU_C_AFTER_RD || mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD;
+    const uint32_t split = mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD ? (uint32_t)MMAEMU_SPLIT_EVEN_ODD : mp.split;
+    if (rd_mode) {
+        uint32_t fmax = mp.frac_bits > mp.frac_bits2 ? mp.frac_bits : mp.frac_bits2;
+        if (mp.frac_bits_merge > fmax) fmax = mp.frac_bits_merge;
+        if (mp.frac_bits_acc > fmax) fmax = mp.frac_bits_acc;
+        if (fmax + 3 + ceil_log2(L) > 53) {
+            set_error("emulate_mma: the C_AFTER_RD modes need max(F, F2, F_m, F_c) + 3 + ceil(log2 L) <= 53");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        if ((split != MMAEMU_SPLIT_NONE && (L & 1u)) || (split == MMAEMU_SPLIT_QUARTERS && (L & 3u))) {
+            set_error("emulate_mma: a split group needs an even group length, quarters a multiple of 4 (L=%u)", L);
+            return MMAEMU_ERR_SHAPE;
+        }
+    }
+    ma.L = L;
+    ma.F = (int32_t)mp.frac_bits;
+    ma.F2 = (int32_t)mp.frac_bits2;
+    ma.c_mode = rd_mode ? (uint32_t)MMAEMU_C_AFTER_RD : mp.c_mode;
+    ma.split = split;
+    ma.acc_special_truncation = mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD ? 1u : mp.acc_special_truncation;
+    ma.Fm = (int32_t)(mp.frac_bits_merge ? mp.frac_bits_merge : mp.frac_bits);
+    ma.Fc = (int32_t)(mp.frac_bits_acc ? mp.frac_bits_acc : mp.frac_bits);
+    ma.f2_at_leading_bit = mp.f2_at_leading_bit;
+    ma.skip_zero_terms = mp.skip_zero_terms;
+    ma.zero_result_positive = mp.zero_result_positive;
+    ma.wide_products = mp.wide_products;
+    ma.sum_drop_distance = (int32_t)(mp.sum_drop_distance > 100000u ? 100000u : mp.sum_drop_distance);
+    ma.out_round = mp.out_round;
+    ma.out_mask = mp.out_mant_bits == 13 ? 0xFFFFFC00u : 0xFFFFFFFFu;
+    ma.ftz_in = mp.ftz_in;
+    ma.ftz_out = mp.ftz_out;
+    ma.nan_bits = mp.nan_bits;
+    ma.nan16 = mp.nan_bits & 0xFFFFu;
+    if (acc16) ma.nan_bits = 0x7FC00000u;             // inside the kernels the accumulator is a binary32 pattern
+    ma.flags = (acc16 ? FL_ACC16 : 0u) | (ma.out_round == MMAEMU_ROUND_RZ ? FL_RZ : 0u) | (ma.ftz_out ? FL_FTZ_OUT : 0u) | (ma.zero_result_positive ? FL_ZERO_POSITIVE : 0u) |
+               (ma.ftz_in ? FL_FTZ_IN : 0u) | (ma.acc_special_truncation ? FL_SPECIAL_TRUNC : 0u) | (ma.f2_at_leading_bit ? FL_F2_LEADING : 0u) |
+               (ma.skip_zero_terms ? FL_SKIP_ZERO : 0u) | (ma.wide_products ? FL_WIDE_PRODUCTS : 0u) | (mp.nan_propagate ? FL_NAN_PROPAGATE : 0u);
+    return MMAEMU_OK;
+}
+
 static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, const void *B, const void *C, void *D,
                                   const uint8_t *SA, const uint8_t *SB, uint32_t block,
                                   uint32_t m, uint32_t n, uint32_t k, uint64_t batch, mmaemu_dtypes dt,
@@ -279,30 +334,10 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
         am.nan_bits = mp.nan_bits;
         return launch_emulate_addmul(am, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream);
     }
-    const uint32_t L = (mp.group_len == 0 || mp.group_len > k) ? k : mp.group_len;
-    if (k % L) { set_error("emulate_mma: k=%u is not a multiple of the group length L=%u", k, L); return MMAEMU_ERR_SHAPE; }
-    if (mp.c_mode == MMAEMU_C_IN_GROUP && mp.frac_bits + 3 + ceil_log2(L) > 63) {      // the fused sum is a 64-bit integer
-        set_error("emulate_mma: C_IN_GROUP needs frac_bits + 3 + ceil(log2 L) <= 63");
-        return MMAEMU_ERR_UNSUPPORTED;
-    }
-    if (mp.c_mode == MMAEMU_C_AFTER_EXACT && mp.frac_bits + 2 + ceil_log2(L) > 56) {
-        set_error("emulate_mma: C_AFTER_EXACT needs frac_bits + 2 + ceil(log2 L) <= 56");
-        return MMAEMU_ERR_UNSUPPORTED;
-    }
-    const bool rd_mode = mp.c_mode == MMAEMU_C_AFTER_RD || mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD;
-    const uint32_t split = mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD ? (uint32_t)MMAEMU_SPLIT_EVEN_ODD : mp.split;
-    if (rd_mode) {
-        uint32_t fmax = mp.frac_bits > mp.frac_bits2 ? mp.frac_bits : mp.frac_bits2;
-        if (mp.frac_bits_merge > fmax) fmax = mp.frac_bits_merge;
-        if (mp.frac_bits_acc > fmax) fmax = mp.frac_bits_acc;
-        if (fmax + 3 + ceil_log2(L) > 53) {
-            set_error("emulate_mma: the C_AFTER_RD modes need max(F, F2, F_m, F_c) + 3 + ceil(log2 L) <= 53");
-            return MMAEMU_ERR_UNSUPPORTED;
-        }
-        if ((split != MMAEMU_SPLIT_NONE && (L & 1u)) || (split == MMAEMU_SPLIT_QUARTERS && (L & 3u))) {
-            set_error("emulate_mma: a split group needs an even group length, quarters a multiple of 4 (L=%u)", L);
-            return MMAEMU_ERR_SHAPE;
-        }
+    ModelArgs ma;
+    {
+        const mmaemu_status st = fdpa_model_args(mp, k, acc16, ma);
+        if (st != MMAEMU_OK) return st;
     }
     const uint64_t mn = (uint64_t)m * n;
     if (batch && (mn > (1ull << 40) || batch > (1ull << 62) / mn || batch * mn > (1ull << 48) ||
@@ -312,30 +347,6 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     }
     if (batch == 0) return MMAEMU_OK;
     if (!A || !B || !C || !D) { set_error("emulate_mma: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
-    ModelArgs ma;
-    ma.L = L;
-    ma.F = (int32_t)mp.frac_bits;
-    ma.F2 = (int32_t)mp.frac_bits2;
-    ma.c_mode = rd_mode ? (uint32_t)MMAEMU_C_AFTER_RD : mp.c_mode;
-    ma.split = split;
-    ma.acc_special_truncation = mp.c_mode == MMAEMU_C_AFTER_RD_EVEN_ODD ? 1u : mp.acc_special_truncation;
-    ma.Fm = (int32_t)(mp.frac_bits_merge ? mp.frac_bits_merge : mp.frac_bits);
-    ma.Fc = (int32_t)(mp.frac_bits_acc ? mp.frac_bits_acc : mp.frac_bits);
-    ma.f2_at_leading_bit = mp.f2_at_leading_bit;
-    ma.skip_zero_terms = mp.skip_zero_terms;
-    ma.zero_result_positive = mp.zero_result_positive;
-    ma.wide_products = mp.wide_products;
-    ma.sum_drop_distance = (int32_t)(mp.sum_drop_distance > 100000u ? 100000u : mp.sum_drop_distance);
-    ma.out_round = mp.out_round;
-    ma.out_mask = mp.out_mant_bits == 13 ? 0xFFFFFC00u : 0xFFFFFFFFu;
-    ma.ftz_in = mp.ftz_in;
-    ma.ftz_out = mp.ftz_out;
-    ma.nan_bits = mp.nan_bits;
-    ma.nan16 = mp.nan_bits & 0xFFFFu;
-    if (acc16) ma.nan_bits = 0x7FC00000u;             // inside the kernels the accumulator is a binary32 pattern
-    ma.flags = (acc16 ? FL_ACC16 : 0u) | (ma.out_round == MMAEMU_ROUND_RZ ? FL_RZ : 0u) | (ma.ftz_out ? FL_FTZ_OUT : 0u) | (ma.zero_result_positive ? FL_ZERO_POSITIVE : 0u) |
-               (ma.ftz_in ? FL_FTZ_IN : 0u) | (ma.acc_special_truncation ? FL_SPECIAL_TRUNC : 0u) | (ma.f2_at_leading_bit ? FL_F2_LEADING : 0u) |
-               (ma.skip_zero_terms ? FL_SKIP_ZERO : 0u) | (ma.wide_products ? FL_WIDE_PRODUCTS : 0u) | (mp.nan_propagate ? FL_NAN_PROPAGATE : 0u);
     return launch_emulate(ma, A, B, C, D, m, n, k, batch, dt.a, dt.b, (hipStream_t)hip_stream, SA, SB, block);
 }
 
@@ -354,6 +365,156 @@ mmaemu_status mmaemu_emulate_mma_scaled(const mmaemu_model *model, const void *A
     if (batch && (!SA || !SB)) { set_error("emulate_mma_scaled: NULL scale pointer"); return MMAEMU_ERR_INVALID_ARG; }
     if (batch == 0) return emulate_impl(model, A, B, C, D, nullptr, nullptr, 1, m, n, k, batch, dt, hip_stream);
     return emulate_impl(model, A, B, C, D, (const uint8_t *)SA, (const uint8_t *)SB, block, m, n, k, batch, dt, hip_stream);
+}
+
+// class of a model in the multi-model kernels: models of equal class share launches; negative: not taken there
+static mmaemu_status many_class(const mmaemu_model_params &mp, const void *A, const void *B, uint32_t m, uint32_t n, uint32_t k,
+                                mmaemu_dtypes dt, ModelArgs &p, bool &fused, int &vm, int &nf)
+{
+    fused = false;
+    vm = nf = 0;
+    if (mp.family == MMAEMU_FAMILY_FDPA && is_ab_type(dt.a) && is_ab_type(dt.b)) {
+        const mmaemu_status st = fdpa_model_args(mp, k, false, p);
+        if (st != MMAEMU_OK) return st;
+        fused = multi_class(p, dt.a, dt.b, m, n, k, A, B, vm, nf);
+    }
+    return MMAEMU_OK;
+}
+
+mmaemu_status mmaemu_compare_many_classes(const mmaemu_model *const *models, uint32_t n_models, uint32_t m, uint32_t n,
+                                          uint32_t k, mmaemu_dtypes dt, int32_t *class_of_model)
+{
+    if (!models || !class_of_model || n_models == 0 || n_models > MMAEMU_COMPARE_MANY_MAX) {
+        set_error("compare_many_classes: 1 to %u models and an output array", (unsigned)MMAEMU_COMPARE_MANY_MAX);
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (m == 0 || n == 0 || k == 0) { set_error("compare_many_classes: zero dimension"); return MMAEMU_ERR_SHAPE; }
+    if (dt.a > MMAEMU_TF32 || dt.b > MMAEMU_TF32) { set_error("compare_many_classes: dtype out of range"); return MMAEMU_ERR_INVALID_ARG; }
+    for (uint32_t i = 0; i < n_models; ++i) {
+        if (!models[i] || models[i]->magic != MODEL_MAGIC) { set_error("compare_many_classes: bad model handle at %u", i); return MMAEMU_ERR_INVALID_ARG; }
+        ModelArgs p;
+        bool fused;
+        int vm, nf;
+        const mmaemu_status st = many_class(models[i]->params, nullptr, nullptr, m, n, k, dt, p, fused, vm, nf);
+        if (st != MMAEMU_OK) return st;
+        class_of_model[i] = fused ? (int32_t)(((uint32_t)vm << 16) | ((uint32_t)nf << 8) | p.L) : -1;
+    }
+    return MMAEMU_OK;
+}
+
+mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uint32_t n_models, const void *A, const void *B,
+                                          const void *C, const void *Dref, void *D_out, uint32_t m, uint32_t n, uint32_t k,
+                                          uint64_t batch, mmaemu_dtypes dt, uint64_t index_base, mmaemu_stats *dev_stats,
+                                          void *hip_stream)
+{
+    if (!models || n_models == 0 || n_models > MMAEMU_COMPARE_MANY_MAX) {
+        set_error("emulate_compare_many: 1 to %u models", (unsigned)MMAEMU_COMPARE_MANY_MAX);
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    for (uint32_t i = 0; i < n_models; ++i)
+        if (!models[i] || models[i]->magic != MODEL_MAGIC) { set_error("emulate_compare_many: bad model handle at %u", i); return MMAEMU_ERR_INVALID_ARG; }
+    if (!dev_stats) { set_error("emulate_compare_many: NULL statistics array"); return MMAEMU_ERR_INVALID_ARG; }
+    if (m == 0 || n == 0 || k == 0) { set_error("emulate_compare_many: zero dimension (m=%u n=%u k=%u)", m, n, k); return MMAEMU_ERR_SHAPE; }
+    if (dt.c != MMAEMU_FP32 || dt.d != MMAEMU_FP32) { set_error("emulate_compare_many: FP32 accumulators and outputs"); return MMAEMU_ERR_UNSUPPORTED; }
+    if (dt.a > MMAEMU_TF32 || dt.b > MMAEMU_TF32) { set_error("emulate_compare_many: dtype out of range"); return MMAEMU_ERR_INVALID_ARG; }
+    const uint64_t mn = (uint64_t)m * n;
+    if (batch && (mn > (1ull << 40) || batch > (1ull << 48) / mn)) { set_error("emulate_compare_many: problem too large"); return MMAEMU_ERR_SHAPE; }
+    if (batch == 0) return MMAEMU_OK;
+    if (!A || !B || !C) { set_error("emulate_compare_many: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+    if (((uintptr_t)C | (uintptr_t)Dref | (uintptr_t)D_out | (uintptr_t)dev_stats) & 3u) {
+        set_error("emulate_compare_many: C, Dref, D_out and the statistics must be 4-byte aligned");
+        return MMAEMU_ERR_INVALID_ARG;
+    }
+    const uint64_t count = batch * mn;
+    hipStream_t s = (hipStream_t)hip_stream;
+    uint32_t *dout = static_cast<uint32_t *>(D_out);
+
+    // which models the multi-model kernels take, and in which variant
+    struct Item { ModelArgs p; bool fused, done; int vm, nf; };
+    Item items[MMAEMU_COMPARE_MANY_MAX];
+    bool all_one = n_models <= (uint32_t)MULTI_MAX;
+    for (uint32_t i = 0; i < n_models; ++i) {
+        Item &it = items[i];
+        it.fused = false;
+        it.done = false;
+        it.vm = it.nf = 0;
+        const mmaemu_status cst = many_class(models[i]->params, A, B, m, n, k, dt, it.p, it.fused, it.vm, it.nf);
+        if (cst != MMAEMU_OK) return cst;
+        // (within a launch the models that flush subnormal inputs come last; a leading reference model that flushes
+        // can therefore share its launch with flushing models only)
+        all_one = all_one && it.fused && it.vm == items[0].vm && it.nf == items[0].nf && it.p.L == items[0].p.L &&
+                  !(items[0].p.ftz_in && !it.p.ftz_in);
+    }
+    bool any_unfused = false;
+    for (uint32_t i = 0; i < n_models; ++i) any_unfused = any_unfused || !items[i].fused;
+    if (!dout && (any_unfused || (!Dref && !all_one))) {
+        set_error("emulate_compare_many: this set of models does not run in one launch (or needs the general kernel): D_out is required");
+        return MMAEMU_ERR_UNSUPPORTED;
+    }
+    const uint32_t *ref = static_cast<const uint32_t *>(Dref);
+
+    // fused launch of `first` (if not UINT32_MAX: it leads the launch and is the reference) and every model of its
+    // class not yet run; at most MULTI_MAX per launch, FlushSubnormal sets last so that the operands are staged twice at most
+    auto run_class = [&](uint32_t lead, int vm, int nf, uint32_t L, bool ref_is_first) -> mmaemu_status {
+        for (;;) {
+            MultiLaunch ml = {};
+            ml.L = L; ml.vm = vm; ml.nf = nf;
+            ml.ref_is_first = ref_is_first;
+            ml.dref = ref;
+            ml.dout = dout;
+            ml.out_stride = count;
+            ml.index_base = index_base;
+            ml.stats = dev_stats;
+            if (ref_is_first) { ml.slot[0] = lead; ml.models[0] = items[lead].p; ml.count = 1; items[lead].done = true; }
+            for (int pass = (ref_is_first && items[lead].p.ftz_in) ? 1 : 0; pass < 2; ++pass)
+                for (uint32_t i = 0; i < n_models && ml.count < (uint32_t)MULTI_MAX; ++i) {
+                    Item &it = items[i];
+                    if (it.done || !it.fused || it.vm != vm || it.nf != nf || it.p.L != L || (int)(it.p.ftz_in != 0) != pass) continue;
+                    ml.slot[ml.count] = i;
+                    ml.models[ml.count] = it.p;
+                    ml.count += 1;
+                    it.done = true;
+                }
+            if (ml.count == 0) return MMAEMU_OK;
+            const mmaemu_status st = launch_multi(ml, A, B, C, m, n, k, batch, dt.a, dt.b, s);
+            if (st != MMAEMU_OK) return st;
+            if (ref_is_first) {                    // what is left of the class compares with the first model's stored outputs
+                ref_is_first = false;
+                ref = dout;                        // (slot 0; null only when nothing is left)
+                if (!ref) return MMAEMU_OK;
+            }
+        }
+    };
+
+    if (!ref) {
+        // the reference is model 0's output: it runs first
+        if (items[0].fused) {
+            const mmaemu_status st = run_class(0, items[0].vm, items[0].nf, items[0].p.L, true);
+            if (st != MMAEMU_OK) return st;
+        } else {
+            mmaemu_status st = emulate_impl(models[0], A, B, C, dout, nullptr, nullptr, 1, m, n, k, batch, dt, hip_stream);
+            if (st != MMAEMU_OK) return st;
+            st = launch_compare(dout, dout, count, index_base, false, dev_stats, s);
+            if (st != MMAEMU_OK) return st;
+            items[0].done = true;
+        }
+        ref = dout;
+    }
+    for (uint32_t i = 0; i < n_models; ++i) {
+        if (items[i].done) continue;
+        if (items[i].fused) {
+            const mmaemu_status st = run_class(UINT32_MAX, items[i].vm, items[i].nf, items[i].p.L, false);
+            if (st != MMAEMU_OK) return st;
+        } else {
+            uint32_t *Di = dout + (uint64_t)i * count;
+            mmaemu_status st = emulate_impl(models[i], A, B, C, Di, nullptr, nullptr, 1, m, n, k, batch, dt, hip_stream);
+            if (st != MMAEMU_OK) return st;
+            st = launch_compare(Di, ref, count, index_base, false, dev_stats + i, s);
+            if (st != MMAEMU_OK) return st;
+            items[i].done = true;
+        }
+    }
+    return MMAEMU_OK;
 }
 
 mmaemu_status mmaemu_stats_reset(mmaemu_stats *st, void *hip_stream)

@@ -80,6 +80,26 @@ mmaemu_status hip_fail(hipError_t e, const char *what);
 mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                              uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb,
                              hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr, uint32_t block = 1);
+// Several models over the same operands, each compared with a reference inside the kernel (the closed-loop scan).
+// multi_class: whether the multi-model kernels take a model on this problem, and which kernel variant it needs there;
+// models of one variant and one group length share a launch of at most MULTI_MAX models.
+constexpr int MULTI_MAX = 16;
+struct MultiLaunch {
+    uint32_t count;
+    uint32_t slot[MULTI_MAX];          // place of each model in the caller's arrays (D_out, statistics)
+    ModelArgs models[MULTI_MAX];
+    uint32_t L;                        // the common group length, and the variant as multi_class names it
+    int vm, nf;
+    bool ref_is_first;                 // the first model's outputs are the reference (dref is not read)
+    const uint32_t *dref;
+    uint32_t *dout;                    // null, or the start of the caller's output array
+    uint64_t out_stride, index_base;
+    mmaemu_stats *stats;               // the start of the caller's statistics array
+};
+bool multi_class(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B,
+                 int &vm, int &nf);
+mmaemu_status launch_multi(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
+                           uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                      uint32_t tb, hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr,

@@ -1,0 +1,192 @@
+"""mmaemu_emulate_compare_many (several models per pass, compared with a reference inside the kernel) against the CPU
+oracle: every model's outputs (written on request) bit for bit, and every model's statistics equal to the oracle's
+comparison of the oracle's outputs with the same reference."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import formats as fm, o2lib, stats as ostats
+from oracle.fdpa import ModelParams, emulate_mma as o1_emulate, C_AFTER_RD
+from oracle.rounding import RNE, RZ
+from paper_2511_10909_amd import synth
+from gpu_utils import to_dev, dev_empty, to_host
+from test_gpu_parity import assert_same, mm, make_case, NP  # noqa: F401
+
+# the sixteen parameter sets of the closed-loop scan: (F, L_max, output rounding, both flushes)
+SETS16 = [(16, 4, RNE, 0), (16, 8, RZ, 1), (16, 16, RNE, 1), (16, 64, RZ, 0), (20, 4, RZ, 1), (20, 8, RNE, 0), (20, 16, RZ, 0),
+          (20, 32, RNE, 1), (24, 4, RNE, 1), (24, 8, RZ, 0), (24, 16, RNE, 0), (24, 32, RZ, 1), (28, 8, RNE, 1), (32, 4, RZ, 0),
+          (32, 16, RZ, 1), (32, 64, RNE, 0)]
+
+
+def _handles(mm, plist):
+    return [mm.model_create(group_len=p.group_len, frac_bits=p.frac_bits, frac_bits2=p.frac_bits2, c_mode=p.c_mode, out_round=p.out_round,
+                            ftz_in=p.ftz_in, ftz_out=p.ftz_out, nan_bits=p.nan_bits, out_mant_bits=p.out_mant_bits) for p in plist]
+
+
+def run_many(mm, plist, A, B, C, ta, tb, ref=None, dump=True, index_base=0, stats=None):
+    """Returns (list of statistics dicts, dumped outputs [n_models][nb][m][n] or None, kernel name)."""
+    import torch
+    nb, m, k = A.shape
+    n = B.shape[1]
+    hs = _handles(mm, plist)
+    try:
+        dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(np.uint32))
+        dR = None if ref is None else to_dev(ref.astype(np.uint32))
+        dD = dev_empty((len(plist), nb, m, n), np.uint32) if dump else None
+        if dump:
+            dD.fill_(0x5A5A5A5A)
+        if stats is None:
+            stats = torch.empty(len(plist) * mm.STATS_BYTES, dtype=torch.uint8, device="cuda")
+            for i in range(len(plist)):
+                mm.stats_reset(stats[i * mm.STATS_BYTES:])
+        mm.emulate_compare_many(hs, dA, dB, dC, dR, dD, m, n, k, nb, (ta, tb, fm.FP32, fm.FP32), stats, index_base=index_base)
+        kern = mm.last_kernel()
+        out = to_host(dD, np.uint32) if dump else None
+        return mm.read_stats_array(stats, len(plist)), out, kern, stats
+    finally:
+        for h in hs:
+            mm.model_destroy(h)
+
+
+def oracle_outputs(plist, A, B, C, ta, tb):
+    return [o2lib.emulate_mma(p, A, B, C, ta, tb)[0] for p in plist]
+
+
+def sets16():
+    return [ModelParams(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(z), ftz_out=bool(z)) for F, L, rho, z in SETS16]
+
+
+@pytest.mark.parametrize("ta,tb", [(fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.FP16, fm.FP16)])
+def test_sixteen_sets_against_a_reference_array(mm, ta, tb):
+    rng = np.random.default_rng(100 + ta)
+    nb = 301                                                    # not a multiple of the tiles per workgroup (16 and 4)
+    A, B, C = make_case(rng, ta, tb, nb, 16, 16, 16, c_exp=(100, 140))
+    if ta == fm.BF16:                                           # half the tiles inside binary32's comfortable range, half anywhere
+        A[: nb // 2] = synth.narrow_exponent_bits(rng, (nb // 2, 16, 16), ta, 110, 140)
+        B[: nb // 2] = synth.narrow_exponent_bits(rng, (nb // 2, 16, 16), tb, 110, 140)
+    plist = sets16()
+    want = oracle_outputs(plist, A, B, C, ta, tb)
+    # a reference that agrees with set 10 mostly: some entries moved by a few places, some NaNs of two patterns, a -0
+    ref = want[10].copy()
+    flat = ref.reshape(-1)
+    idx = rng.choice(flat.size, size=flat.size // 50, replace=False)
+    flat[idx] += rng.integers(1, 200, size=idx.size).astype(np.uint32)
+    flat[rng.choice(flat.size, size=40, replace=False)] = 0x7FC00000
+    flat[rng.choice(flat.size, size=40, replace=False)] = 0xFFC00001
+    flat[rng.choice(flat.size, size=10, replace=False)] = 0x80000000
+    got_stats, got_D, kern, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, index_base=5_000_000_000)
+    assert kern.startswith("multi"), kern
+    for i, p in enumerate(plist):
+        assert_same(got_D[i], want[i], "set %d %s" % (i, p))
+        assert got_stats[i] == ostats.compare(want[i], ref, index_base=5_000_000_000), (i, p)
+
+
+def test_sets_without_dump_give_the_same_statistics_and_accumulate(mm):
+    rng = np.random.default_rng(7)
+    ta, tb = fm.E4M3, fm.E5M2
+    A, B, C = make_case(rng, ta, tb, 128, 16, 16, 16, c_exp=(110, 135))
+    plist = sets16()
+    want = oracle_outputs(plist, A, B, C, ta, tb)
+    ref = want[3]
+    st1, _, kern, dev = run_many(mm, plist, A, B, C, ta, tb, ref=ref, dump=False)
+    assert kern.startswith("multi")
+    expect = [ostats.compare(w, ref) for w in want]
+    assert st1 == expect
+    # second call on the same device structs: counters add up, the first index stays
+    st2, _, _, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, dump=False, index_base=1 << 33, stats=dev)
+    for i, w in enumerate(want):
+        assert st2[i] == ostats.compare(w, ref, stats=ostats.compare(w, ref), index_base=1 << 33), i
+
+
+@pytest.mark.parametrize("lead_flushes", [False, True])
+def test_first_model_as_reference_flush_variants(mm, lead_flushes):
+    """Subnormal stress shape: fp16 32x32x8 tiles, exponent fields over the whole range; no reference array, the
+    first model's outputs are the reference and never leave the kernel."""
+    rng = np.random.default_rng(11)
+    nb = 77
+    A = synth.narrow_exponent_bits(rng, (nb, 32, 8), fm.FP16, 0, 30)
+    B = synth.narrow_exponent_bits(rng, (nb, 32, 8), fm.FP16, 0, 30)
+    C = synth.narrow_exponent_bits(rng, (nb, 32, 32), fm.FP32, 79, 158)
+    C[rng.random(C.shape) < 0.1] &= 0x807FFFFF                  # zeros and subnormals
+    plist = [ModelParams(group_len=8, frac_bits=24), ModelParams(group_len=8, frac_bits=24, ftz_in=True),
+             ModelParams(group_len=8, frac_bits=24, ftz_out=True)]
+    if lead_flushes:
+        plist = [plist[1], plist[0], plist[2]]
+    want = oracle_outputs(plist, A, B, C, fm.FP16, fm.FP16)
+    if not lead_flushes:
+        st, _, kern, _ = run_many(mm, plist, A, B, C, fm.FP16, fm.FP16, ref=None, dump=False)
+        assert kern.startswith("multi x3"), kern
+        assert st == [ostats.compare(w, want[0]) for w in want]
+        assert st[0]["n_mismatch_bits"] == 0 and st[1]["n_mismatch_bits"] > 0
+    else:
+        # the flushing set leads: the others cannot share its launch, so the call needs D_out
+        with pytest.raises(mm.MmaemuError) as ei:
+            run_many(mm, plist, A, B, C, fm.FP16, fm.FP16, ref=None, dump=False)
+        assert ei.value.status == 2 and "D_out" in mm.last_error()
+    st, D, kern, _ = run_many(mm, plist, A, B, C, fm.FP16, fm.FP16, ref=None, dump=True)
+    for i in range(3):
+        assert_same(D[i], want[i], "variant %d" % i)
+    assert st == [ostats.compare(w, want[0]) for w in want]
+
+
+def test_special_values_and_wide_bf16_inside_the_fused_kernels(mm):
+    rng = np.random.default_rng(21)
+    for ta, tb in ((fm.BF16, fm.BF16), (fm.E5M2, fm.E5M2), (fm.FP16, fm.E4M3)):
+        A, B, C = make_case(rng, ta, tb, 65, 16, 16, 16, special_frac=0.02)
+        A2 = synth.random_bits(rng, A.shape, ta, finite=False)   # all bit patterns in a third of the tiles
+        A[:20] = A2[:20]
+        plist = [ModelParams(group_len=8, frac_bits=24, nan_bits=0x7FFFFFFF), ModelParams(group_len=8, frac_bits=20, out_round=RZ, ftz_in=True),
+                 ModelParams(group_len=8, frac_bits=16, ftz_out=True, out_round=RZ, out_mant_bits=13)]
+        want = oracle_outputs(plist, A, B, C, ta, tb)
+        ref = want[0]
+        st, D, kern, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref)
+        assert kern.startswith("multi")
+        for i in range(3):
+            assert_same(D[i], want[i], "types %s set %d" % ((ta, tb), i))
+            assert st[i] == ostats.compare(want[i], ref)
+    # the rational form of the oracle on the first tiles of one case
+    A, B, C = make_case(rng, fm.BF16, fm.BF16, 3, 16, 16, 16, c_exp=(100, 140))
+    plist = sets16()
+    st, D, _, _ = run_many(mm, plist, A, B, C, fm.BF16, fm.BF16, ref=C)
+    for i, p in enumerate(plist):
+        assert_same(D[i], o1_emulate(p, A, B, C, fm.BF16, fm.BF16), "rational oracle, set %d" % i)
+
+
+def test_models_outside_the_fused_kernels_fall_back(mm):
+    """A TR-FDPA set and a ragged shape run through the ordinary kernels; statistics and outputs are the same."""
+    rng = np.random.default_rng(31)
+    A, B, C = make_case(rng, fm.FP16, fm.FP16, 40, 16, 16, 16, c_exp=(100, 140))
+    plist = [ModelParams(group_len=8, frac_bits=24), ModelParams(group_len=8, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD),
+             ModelParams(group_len=16, frac_bits=27, out_round=RZ), ModelParams(group_len=2, frac_bits=24)]
+    want = oracle_outputs(plist, A, B, C, fm.FP16, fm.FP16)
+    for ref in (None, want[2]):
+        st, D, _, _ = run_many(mm, plist, A, B, C, fm.FP16, fm.FP16, ref=ref)
+        base = want[0] if ref is None else ref
+        for i in range(len(plist)):
+            assert_same(D[i], want[i], "set %d" % i)
+            assert st[i] == ostats.compare(want[i], base), i
+    with pytest.raises(mm.MmaemuError) as ei:
+        run_many(mm, plist, A, B, C, fm.FP16, fm.FP16, ref=want[2], dump=False)
+    assert ei.value.status == 2
+    # a shape the fused kernels do not take (20 x 20 x 8)
+    A, B, C = make_case(rng, fm.FP16, fm.FP16, 9, 20, 20, 8, c_exp=(100, 140))
+    want = oracle_outputs(plist[:1], A, B, C, fm.FP16, fm.FP16)
+    st, D, _, _ = run_many(mm, plist[:1], A, B, C, fm.FP16, fm.FP16, ref=C)
+    assert_same(D[0], want[0], "ragged shape")
+    assert st[0] == ostats.compare(want[0], C)
+
+
+def test_argument_checks(mm):
+    h = mm.model_create(group_len=8, frac_bits=24)
+    ok = 0x1000
+    dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
+    for kw, status in ((dict(models=[]), 1), (dict(stats=None), 1), (dict(m=0), 3), (dict(dt=(mm.FP16, mm.FP16, mm.FP16, mm.FP16)), 2),
+                       (dict(A=None), 1), (dict(C=ok + 2), 1), (dict(models=[h] * 65), 1)):
+        a = dict(models=[h], A=ok, B=ok, C=ok, Dref=ok, D_out=None, m=16, n=16, k=16, batch=4, dt=dt, stats=ok)
+        a.update(kw)
+        with pytest.raises(mm.MmaemuError) as ei:
+            mm.emulate_compare_many(a["models"], a["A"], a["B"], a["C"], a["Dref"], a["D_out"], a["m"], a["n"], a["k"], a["batch"], a["dt"], a["stats"], stream=0)
+        assert ei.value.status == status, (kw, mm.last_error())
+    mm.emulate_compare_many([h], None, None, None, None, None, 16, 16, 16, 0, dt, ok, stream=0)       # no tiles: nothing to do
+    mm.model_destroy(h)
