@@ -1,11 +1,13 @@
 #!/usr/bin/env python3
-"""Benchmark of the hot path: generate -> emulate (two models) -> compare, on one MI355X.
+"""Benchmark of the hot path on one MI355X: the closed-loop scan (the largest of the five workloads).
 
-Workload: bf16 A/B, fp32 C/D GEMM with
-m = n = k = 1024; A, B ~ N(0,1) cast to bf16, C = 0; model 0 accumulates in fused groups of 8
-products, each group added to the running fp32 sum with RNE (c_mode = C_AFTER_EXACT, F = 24);
-model 1 is the fully fused model of the same shape (L = K = 1024, F = 24, RNE); the step ends
-with the bitwise comparison of the two outputs.  One step = 2 * 1024^3 emulated MAC terms.
+One step = the whole scan: for each operand type (bf16 x bf16, e4m3 x e5m2), 2^24 random 16x16x16 tiles in chunks of
+2^16: generate A, B, C on the device, run every tile through the native MFMA instruction, evaluate the sixteen
+parameter sets (fused dot-product-add models of internal width 16..32, group length 4..16, RNE / RZ, flushes on / off)
+and accumulate each set's bitwise comparison statistics against the instruction's output.  With the default fused
+path the sets of one group length share a launch (mmaemu_emulate_compare_many): the operands are staged and decoded
+once per chunk and group of sets, every output is compared in registers, D never reaches memory.  `--unfused` runs one
+mmaemu_emulate_mma and one mmaemu_compare per set instead.
 
 Prints ONE JSON line.  `--gpus N` with N > 1 is refused: the library runs on one GPU.
 """
@@ -20,19 +22,24 @@ sys.path.insert(0, ROOT)
 
 INT32_VALU_PEAK = 256 * 4 * 16 * 2.4e9      # lane-instructions / s: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
 ALGO_OPS_PER_TERM = 8                       # accounting floor of INT32 VALU instructions per MAC term
-# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters (scaled by a copy kernel
-# of known size; see profiles/emulate_tiled_bf16_gemm1024_hbm_counters.md).  Valid only for the kernel variant and
-# problem size it was measured on: any other variant reports null.
-MEASURED_TRAFFIC = {("tiled 32x32 r2x2 kc=32 L=8 c_mode=1 fold=0 vm=1", 1024): (11487.0 * 2.00 + 4096.0) * 1024.0}
+# Counter figures of the emulation kernels, from rocprofv3 --pmc runs of this program (see the named files under profiles/):
+# vector-ALU lane-instructions per MAC term (SQ_INSTS_VALU x 64 / terms) and HBM bytes per launch (FETCH_SIZE + WRITE_SIZE,
+# scaled by a copy kernel of known size).  Keyed by the kernel's name: a kernel that has changed since reports null.
+COUNTERS = {}
+COUNTERS_SOURCE = None
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--size", type=int, default=1024, help="m = n = k of the GEMM-shaped workload")
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--tiles", type=int, default=1 << 24, help="tiles per operand type (the workload as stated: 2^24)")
+    ap.add_argument("--chunk", type=int, default=1 << 16, help="tiles generated and evaluated at a time")
+    ap.add_argument("--unfused", action="store_true", help="one emulation launch and one comparison launch per parameter set")
+    ap.add_argument("--time-every", type=int, default=16, help="HIP events around the emulation launches of every n-th chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the one-off runs of workloads 1-4 after the timed region")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region, run 5 plain device copies of 64 MiB (a kernel of known traffic, "
                          "to scale FETCH_SIZE / WRITE_SIZE counters collected under rocprofv3 --pmc)")
@@ -40,30 +47,29 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(size, target_seconds):
-    """The C form of the CPU oracle, as it stands, timed on a bounded sample of the same workload:
-    whole rows of D (all n columns, both models) on inputs from the oracle's own generator twin."""
+def cpu_baseline(target_seconds):
+    """The C form of the CPU oracle, as it stands, timed on a bounded sample of the same workload: the first tiles of
+    the bf16 half of the scan (inputs from the oracle's own generator twin), all sixteen parameter sets."""
     import numpy as np
     from oracle import o2lib, gen as ogen, formats as fm
-    from oracle.fdpa import ModelParams, C_AFTER_EXACT
-    m = n = k = size
-    A = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=0), fm.BF16, m * k, 0, 1).reshape(m, k)
-    B = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=1), fm.BF16, n * k, 0, 1).reshape(n, k)
-    models = [ModelParams(group_len=8, frac_bits=24, c_mode=C_AFTER_EXACT), ModelParams(group_len=0, frac_bits=24)]
-    rows, used, elapsed, terms = 2, 1, 0.0, 0
+    from oracle.fdpa import ModelParams
+    from paper_2511_10909_amd.configs import CONFIG5_MODELS
+    models = [ModelParams(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(z), ftz_out=bool(z)) for F, L, rho, z in CONFIG5_MODELS]
+    nt, used, elapsed, terms = 1 << 10, 1, 0.0, 0
     while True:
-        rows = min(rows, m)
-        Cz = np.zeros((1, rows, n), dtype=np.uint32)
+        A = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=0), fm.BF16, 256, 0, nt).reshape(nt, 16, 16)
+        B = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=1), fm.BF16, 256, 0, nt).reshape(nt, 16, 16)
+        C = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=2), fm.FP32, 256, 0, nt, threads=8).reshape(nt, 16, 16)
         t0 = time.perf_counter()
         for p in models:
-            _, used = o2lib.emulate_mma(p, A[None, :rows], B[None], Cz, fm.BF16, fm.BF16)
+            _, used = o2lib.emulate_mma(p, A, B, C, fm.BF16, fm.BF16)
         elapsed = time.perf_counter() - t0
-        terms = 2 * rows * n * k
-        if elapsed >= 0.5 * target_seconds or rows == m:
+        terms = len(models) * nt * 4096
+        if elapsed >= 0.5 * target_seconds or nt >= (1 << 20):
             break
-        rows = int(min(m, max(rows * 2, rows * target_seconds / max(elapsed, 1e-3) * 0.9)))
+        nt = int(min(1 << 20, max(nt * 2, nt * target_seconds / max(elapsed, 1e-3) * 0.9)))
     return dict(value=terms / elapsed, unit="terms/s", cores=used, kind="oracle",
-                sample="rows 0..%d of D (all %d columns, both models): %d terms in %.2f s" % (rows - 1, n, terms, elapsed))
+                sample="tiles 0..%d of the bf16 half, all 16 parameter sets (emulation only): %d terms in %.2f s" % (nt - 1, terms, elapsed))
 
 
 def main():
@@ -76,38 +82,30 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    from paper_2511_10909_amd import binding as mm
+    from paper_2511_10909_amd import binding as mm, configs
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    m = n = k = args.size
-    dt = (mm.BF16, mm.BF16, mm.FP32, mm.FP32)
-    A = torch.empty((m, k), dtype=torch.int16, device=dev)
-    B = torch.empty((n, k), dtype=torch.int16, device=dev)
-    C = torch.empty((m, n), dtype=torch.int32, device=dev)
-    D0 = torch.empty((m, n), dtype=torch.int32, device=dev)
-    D1 = torch.empty((m, n), dtype=torch.int32, device=dev)
-    stats = torch.empty(mm.STATS_BYTES, dtype=torch.uint8, device=dev)
-    chained = mm.model_create(group_len=8, frac_bits=24, c_mode=mm.C_AFTER_EXACT, out_round=mm.RNE)
-    fused = mm.model_create(group_len=0, frac_bits=24, c_mode=mm.C_IN_GROUP, out_round=mm.RNE)
-    kernels = {}
+    n_tiles, chunk = args.tiles, min(args.chunk, args.tiles)
+    fused = not args.unfused
+    scans = [configs.ClosedLoopScan(kind, chunk, 0, "cuda", fused) for kind in ("bf16", "fp8")]
+    n_sets = len(configs.CONFIG5_MODELS)
+    timed = []                      # (kernel key, terms, start event, end event) of the emulation launches that carry events
 
-    def step(events=None):
-        mm.generate(A, mm.BF16, m * k, 0, 1, mm.GEN_NORMAL, seed=0, operand=0)
-        mm.generate(B, mm.BF16, n * k, 0, 1, mm.GEN_NORMAL, seed=0, operand=1)
-        mm.generate(C, mm.FP32, m * n, 0, 1, mm.GEN_ZERO, seed=0, operand=2)
-        mm.stats_reset(stats)
-        if events is not None:
-            events[0].record()
-        mm.emulate_mma(chained, A, B, C, D0, m, n, k, 1, dt)
-        kernels["chained"] = mm.last_kernel()
-        if events is not None:
-            events[1].record()
-        mm.emulate_mma(fused, A, B, C, D1, m, n, k, 1, dt)
-        kernels["fused"] = mm.last_kernel()
-        if events is not None:
-            events[2].record()
-        mm.compare(D0, D1, m * n, stats)
+    def step(collect):
+        for scan in scans:
+            scan.reset()
+            for ci, t0 in enumerate(range(0, n_tiles, chunk)):
+                nt = min(chunk, n_tiles - t0)
+                timer = None
+                if collect and ci % args.time_every == 0:
+                    def timer(name, terms, fn, scan=scan):
+                        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                        e0.record()
+                        fn()
+                        e1.record()
+                        timed.append(((scan.kind, name), terms, e0, e1))
+                scan.chunk_step(t0, nt, timer=timer)
 
     if args.copy_calibration:
         src = torch.arange(16 * 1024 * 1024, dtype=torch.int32, device=dev)       # 64 MiB read + 64 MiB written
@@ -116,23 +114,38 @@ def main():
             torch.add(src, 1, out=dst)                                             # one elementwise kernel per call
         torch.cuda.synchronize()
     for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+        step(False)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(evs[i])
+    for _ in range(args.steps):
+        step(True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
-    terms_per_model = m * n * k
-    terms_per_step = 2 * terms_per_model
-    t_chained = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps * 1e-3
-    t_fused = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps * 1e-3
-    dom_name, dom_t = ("chained", t_chained) if t_chained >= t_fused else ("fused", t_fused)
-    achieved = ALGO_OPS_PER_TERM * terms_per_model / dom_t
-    st = mm.read_stats(stats)
+    terms_per_step = 2 * n_sets * n_tiles * 4096
+    # per emulation kernel: average launch duration and the fraction of the accounting roofline it reaches
+    per = {}
+    for key, terms, e0, e1 in timed:
+        d = per.setdefault(key, dict(launches=0, ms=0.0, terms=0))
+        d["launches"] += 1
+        d["ms"] += e0.elapsed_time(e1)
+        d["terms"] += terms
+    kernels = {}
+    for (kind, name), d in per.items():
+        scan = scans[0] if kind == "bf16" else scans[1]
+        idx = int(name.split()[1])
+        kname = scan.kernels.get(idx, "?")
+        kernels["%s %s: %s" % (kind, name, kname)] = dict(
+            launches_timed=d["launches"], avg_ms=d["ms"] / d["launches"], terms_per_launch=d["terms"] // d["launches"],
+            frac=ALGO_OPS_PER_TERM * d["terms"] / (d["ms"] * 1e-3) / INT32_VALU_PEAK, kernel=kname)
+    dom_key = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_timed"])
+    dom = kernels[dom_key]
+    tot_ms = sum(v["avg_ms"] * v["launches_timed"] for v in kernels.values())
+    tot_terms = sum(v["terms_per_launch"] * v["launches_timed"] for v in kernels.values())
+    achieved = ALGO_OPS_PER_TERM * dom["terms_per_launch"] / (dom["avg_ms"] * 1e-3)
+    ctr = COUNTERS.get(dom["kernel"], {})
+    stats = {scan.kind: scan.read() for scan in scans}
+    agreement = {kind: [1.0 - s["n_mismatch_bits"] / max(s["n_compared"], 1) for s in st] for kind, st in stats.items()}
     out = {
         "metric": "bit-exact emulated MAC terms/sec on 1 MI355X",
         "value": terms_per_step * args.steps / elapsed,
@@ -144,33 +157,51 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "i32",
+        "dtype": "f32+i32 (exact binary32 products, int32 / binary64 sums, binary64 group conversion)",
         "data": "synthetic",
         "config": {
-            "workload": "configs[1]: bf16 A/B, fp32 C/D GEMM m=n=k=%d; step = generate(A,B ~ N(0,1)->bf16, C=0) + "
-                        "emulate(chained L=8, C_AFTER_EXACT, F=24, RNE) + emulate(fully fused L=%d, F=24, RNE) + compare"
-                        % (m, k),
+            "workload": "configs[4]: closed-loop scan, 16 parameter sets x 2^%d tiles 16x16x16 x {bf16 finite bit patterns, "
+                        "e4m3 x e5m2 N(0,1) scaled per tile}, C ~ N(0,1); step = per chunk of 2^%d tiles: generate A, B, C + "
+                        "native MFMA + 16 sets emulated and compared with the instruction (%s)"
+                        % (n_tiles.bit_length() - 1, chunk.bit_length() - 1,
+                           "fused: statistics formed inside the emulation kernels" if fused else "one emulation and one comparison launch per set"),
             "terms_per_step": terms_per_step,
-            "kernels": kernels,
-            "mismatch_count_chained_vs_fused": st["n_mismatch_bits"],
-            "n_compared": st["n_compared"],
-            "emulate_only_terms_per_s": terms_per_step / (t_chained + t_fused),
-            "emulate_ms": {"chained": t_chained * 1e3, "fused": t_fused * 1e3},
+            "tiles_per_type": n_tiles,
+            "chunk": chunk,
+            "fused": fused,
+            "n_compared_per_set": stats["bf16"][0]["n_compared"],
+            "agreement_with_mfma": {kind: dict(min=min(a), max=max(a)) for kind, a in agreement.items()},
+            "emulation_kernels": kernels,
+            "emulation_only_terms_per_s": tot_terms / (tot_ms * 1e-3),
         },
         "roofline": {
             "bound": "alu",
-            "kernel": "%s (%s)" % (dom_name, kernels[dom_name]),
+            "kernel": dom_key,
             "achieved": achieved / 1e12,
             "peak": INT32_VALU_PEAK / 1e12,
             "unit": "T INT32 lane-instr/s (8 algorithmic instr per MAC term)",
             "frac": achieved / INT32_VALU_PEAK,
-            "traffic": MEASURED_TRAFFIC.get((kernels[dom_name], args.size)),
+            "frac_time_weighted_all_emulation_kernels": ALGO_OPS_PER_TERM * tot_terms / (tot_ms * 1e-3) / INT32_VALU_PEAK,
+            "valu_instr_per_term": ctr.get("valu_instr_per_term"),
+            "valu_util": (ctr["valu_instr_per_term"] * dom["terms_per_launch"] / (dom["avg_ms"] * 1e-3) / INT32_VALU_PEAK) if ctr else None,
+            "traffic": ctr.get("traffic"),
+            "traffic_source": COUNTERS_SOURCE if ctr else None,
         },
     }
-    mm.model_destroy(chained)
-    mm.model_destroy(fused)
+    for scan in scans:
+        scan.close()
+    if not args.no_other_workloads:
+        # the other four workloads, once each, outside the timed region: end-to-end rates for context
+        other = {}
+        configs.config1(n_tiles=256)
+        for name, fn in (("configs[0]", lambda: configs.config1()), ("configs[1]", lambda: configs.config2()),
+                         ("configs[2]", lambda: configs.config3()), ("configs[3]", lambda: configs.config4(fused=fused))):
+            fn()                                  # (first call of a workload: kernel loading and allocator warm-up)
+            r = fn()
+            other[name] = dict(terms=r["terms"], ms=r["seconds"] * 1e3, terms_per_s=r["terms"] / r["seconds"])
+        out["config"]["other_workloads_end_to_end"] = other
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.size, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(args.cpu_seconds)
     print(json.dumps(out))
 
 
