@@ -184,8 +184,9 @@ class _Sampler:
         self.kept.append(rec)
 
 
-def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk=False, fused=True, sample_tiles=None):
-    """`fused`: the three variants share one pass over each chunk (mmaemu_emulate_compare_many, the no-flush variant's
+def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk=False, fused=True, sample_tiles=None,
+            first_tile=0):
+    """Tiles first_tile .. first_tile + n_tiles - 1 of the stream.  `fused`: the three variants share one pass over each chunk (mmaemu_emulate_compare_many, the no-flush variant's
     outputs as the reference, D never written); otherwise one emulation and one comparison per variant.
     `keep_first_chunk` / `sample_tiles`: operands and all three outputs of the first chunk / of the given tiles are
     kept (those chunks also write D) and returned under "dev" / "samples"."""
@@ -204,11 +205,11 @@ def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk
 
     def run():
         kern = None
-        for t0 in range(0, n_tiles, chunk):
-            nt = min(chunk, n_tiles - t0)
+        for t0 in range(first_tile, first_tile + n_tiles, chunk):
+            nt = min(chunk, first_tile + n_tiles - t0)
             config4_generate(A, B, C, t0, nt, seed)
             local = sampler.in_chunk(t0, nt)
-            keep = keep_first_chunk and t0 == 0
+            keep = keep_first_chunk and t0 == first_tile
             want_d = (not fused) or keep or bool(local)
             # ([variant][tile][m][n] for this chunk's tile count: the layout mmaemu_emulate_compare_many writes)
             dump = Dall.reshape(-1)[: nv * nt * m * n].view(nv, nt, m, n) if want_d else None
@@ -330,7 +331,9 @@ class ClosedLoopScan:
 
 
 def config5(n_tiles=1 << 24, chunk=1 << 16, seed=0, dev="cuda", kinds=("bf16", "fp8"), keep_first_chunk=False, fused=True,
-            sample_tiles=None):
+            sample_tiles=None, first_tile=0):
+    """Tiles first_tile .. first_tile + n_tiles - 1 of each operand type's stream; `keep_first_chunk` / `sample_tiles` as
+    in config4 (the chunks concerned write every set's D)."""
     out = {}
     for kind in kinds:
         ch = min(chunk, n_tiles)
@@ -340,10 +343,10 @@ def config5(n_tiles=1 << 24, chunk=1 << 16, seed=0, dev="cuda", kinds=("bf16", "
         sampler = _Sampler(sample_tiles)
 
         def run():
-            for t0 in range(0, n_tiles, ch):
-                nt = min(ch, n_tiles - t0)
+            for t0 in range(first_tile, first_tile + n_tiles, ch):
+                nt = min(ch, first_tile + n_tiles - t0)
                 local = sampler.in_chunk(t0, nt)
-                keep = keep_first_chunk and t0 == 0
+                keep = keep_first_chunk and t0 == first_tile
                 scan.chunk_step(t0, nt, dump=bool(keep or local))
                 if keep:
                     kept.update(A=scan.A.clone(), B=scan.B.clone(), C=scan.C.clone(), Dhw=scan.Dhw.clone(),

@@ -1,11 +1,10 @@
 """The five probing workloads at their real shapes, GPU against the CPU oracle.
 
-Configs 1-3 run at full size (config 2 is the workload bench.py times, in the same launch
-configuration).  Configs 4 and 5 stream 2^26 and 2^24 tiles per run at full size; by default they
-run a prefix of 2^22 / 2^18 tiles in the same chunked launch configuration (set MMAEMU_FULL=1 for the
-whole run) -- the counter-based generators make any prefix identical to the start of the full run.
-Everything the oracle can recompute in seconds is compared bit for bit: generated operands, emulated
-outputs (all of them, or a sample for config 3 and the streamed configs), and comparison statistics.
+All five run at their stated sizes.  Configs 4 and 5 stream 2^26 and 2^24 tiles per run (config 5 is the
+workload bench.py times, in the same launch configuration).  Everything the oracle can recompute in
+seconds is compared bit for bit: generated operands, emulated outputs (all of them, or a sample for
+config 3 and, for the streamed configs, a prefix plus tiles at hashed indices over the whole stream),
+and comparison statistics; the streamed runs are checked against their whole-run invariants as well.
 """
 import os
 
@@ -20,7 +19,6 @@ from oracle.rounding import RNE, RZ
 from gpu_utils import to_host
 from test_gpu_parity import assert_same, mm  # noqa: F401
 
-FULL = os.environ.get("MMAEMU_FULL", "0") == "1"
 THREADS = 8
 
 
@@ -126,99 +124,176 @@ def _config4_oracle_inputs(first_tile, nt):
     return A.reshape(nt, 32, 8), B.reshape(nt, 32, 8), C.reshape(nt, 32, 32)
 
 
-def test_config4_streamed(cfg, mm):
-    n_tiles = 1 << (26 if FULL else 22)
-    chunk = 1 << 14
-    r = cfg.config4(n_tiles=n_tiles, chunk=chunk, seed=0, keep_first_chunk=True)
-    assert r["kernel"].startswith("tiled 32x32")
-    variants = [ModelParams(group_len=8, frac_bits=24), ModelParams(group_len=8, frac_bits=24, ftz_in=True),
-                ModelParams(group_len=8, frac_bits=24, ftz_out=True)]
-    # whole-run invariants
+CONFIG4_ORACLE = [ModelParams(group_len=8, frac_bits=24), ModelParams(group_len=8, frac_bits=24, ftz_in=True),
+                  ModelParams(group_len=8, frac_bits=24, ftz_out=True)]
+
+
+def hashed_tiles(n_tiles, chunk, n_chunks, per_chunk, seed):
+    """Tile indices scattered over the whole stream: `per_chunk` tiles in each of `n_chunks` chunks picked by a seeded
+    generator, the last chunk always among them (with its last tile)."""
+    rng = np.random.default_rng(seed)
+    total_chunks = n_tiles // chunk
+    chunks = set(int(c) for c in rng.choice(total_chunks - 1, size=n_chunks - 1, replace=False)) | {total_chunks - 1}
+    tiles = []
+    for c in sorted(chunks):
+        local = set(int(x) for x in rng.choice(chunk, size=per_chunk, replace=False))
+        if c == total_chunks - 1:
+            local = set(list(local)[: per_chunk - 1]) | {chunk - 1}
+        tiles.extend(c * chunk + x for x in sorted(local))
+    return tiles
+
+
+def test_config4_at_its_stated_size(cfg, mm):
+    """All 2^26 tiles, three variants sharing one pass per chunk.  Whole-run invariants; the first chunk's operands and the
+    first 2^12 tiles of every variant against the oracle; 2^10 tiles at hashed indices over the whole stream (the last
+    chunk included) taken out of the run itself, operands and outputs against the oracle."""
+    n_tiles, chunk = 1 << 26, 1 << 14
+    samples = hashed_tiles(n_tiles, chunk, 64, 16, seed=4)
+    r = cfg.config4(n_tiles=n_tiles, chunk=chunk, seed=0, keep_first_chunk=True, sample_tiles=samples)
+    assert r["kernel"].startswith("multi x3 tiled 32x32"), r["kernel"]
+    total = n_tiles * 1024                                                     # 2^36 outputs per variant
     for name, st in r["stats"].items():
-        assert st["n_compared"] == n_tiles * 1024 and sum(st["ulp_hist"]) == n_tiles * 1024
-    none = r["stats"]["none"]
-    assert none["n_mismatch_bits"] == 0 and none["ulp_hist"][0] == n_tiles * 1024
-    assert r["stats"]["ftz_in"]["n_mismatch_bits"] > 0
-    # first chunk: operands and the first 2^12 tiles of every variant against the oracle, histograms of the chunk
+        assert st["n_compared"] == total and sum(st["ulp_hist"]) == total, name
+    none, fin, fout = (r["stats"][k] for k in ("none", "ftz_in", "ftz_out"))
+    assert none["n_mismatch_bits"] == 0 and none["ulp_hist"][0] == total and none["first_mismatch_index"] == mm.NO_MISMATCH
+    assert fin["n_mismatch_bits"] > total // 16 and fin["ulp_hist"][33] == 0
+    assert fout["n_mismatch_bits"] == fout["n_mismatch_nan_equiv"] == 0         # (no result of these inputs is subnormal)
+    # first chunk: operands, and the first 2^12 tiles of every variant
     A, B, C = _config4_oracle_inputs(0, chunk)
     assert_same(host(r["dev"]["A"], np.uint16), A.astype(np.uint16), "config4 A")
     assert_same(host(r["dev"]["B"], np.uint16), B.astype(np.uint16), "config4 B")
     assert_same(host(r["dev"]["C"], np.uint32), C, "config4 C")
     nchk = 1 << 12
     outs = []
-    for p, Dg in zip(variants, r["dev"]["D"]):
+    for p, Dg in zip(CONFIG4_ORACLE, r["dev"]["D"]):
         w, _ = o2lib.emulate_mma(p, A[:nchk], B[:nchk], C[:nchk], fm.FP16, fm.FP16)
         assert_same(host(Dg, np.uint32)[:nchk], w, "config4 %s" % (p,))
         outs.append(w)
-    # 2^10 tiles at scattered indices of the stream, regenerated and emulated in one small call each side
-    rng = np.random.default_rng(4)
-    import torch
-    from paper_2511_10909_amd import binding as b
-    for t0 in rng.integers(0, n_tiles - 16, size=64):
-        t0 = int(t0)
-        Ah, Bh, Ch = _config4_oracle_inputs(t0, 16)
-        dA = torch.empty((16, 32, 8), dtype=torch.int16, device="cuda")
-        dB = torch.empty((16, 32, 8), dtype=torch.int16, device="cuda")
-        dC = torch.empty((16, 32, 32), dtype=torch.int32, device="cuda")
-        dD = torch.empty((16, 32, 32), dtype=torch.int32, device="cuda")
-        cfg.config4_generate(dA, dB, dC, t0, 16, 0)
-        h = b.model_create(group_len=8, frac_bits=24, ftz_in=True)
-        b.emulate_mma(h, dA, dB, dC, dD, 32, 32, 8, 16, (b.FP16, b.FP16, b.FP32, b.FP32))
-        b.model_destroy(h)
-        w, _ = o2lib.emulate_mma(variants[1], Ah, Bh, Ch, fm.FP16, fm.FP16)
-        assert_same(host(dD, np.uint32), w, "config4 tiles at %d" % t0)
-    # statistics of a prefix that both sides can hold: compare() on the first 2^12 tiles
-    for p_out, name in zip(outs, ("none", "ftz_in", "ftz_out")):
-        st = torch.empty(b.STATS_BYTES, dtype=torch.uint8, device="cuda")
-        b.stats_reset(st)
-        Dg = r["dev"]["D"][("none", "ftz_in", "ftz_out").index(name)]
-        b.compare(Dg[:nchk], r["dev"]["D"][0][:nchk], nchk * 1024, st)
-        assert b.read_stats(st) == ostats.compare(p_out, outs[0]), name
+    # the statistics of that prefix, formed inside the fused kernels, against the oracle's comparison of its own outputs;
+    # the whole run's first mismatch lies in it
+    pre = cfg.config4(n_tiles=nchk, chunk=chunk, seed=0)
+    for name, w in zip(("none", "ftz_in", "ftz_out"), outs):
+        assert pre["stats"][name] == ostats.compare(w, outs[0]), name
+    assert fin["first_mismatch_index"] == pre["stats"]["ftz_in"]["first_mismatch_index"]
+    # the sampled tiles of the run itself
+    seen = []
+    for rec in r["samples"]:
+        nt = len(rec["tiles"])
+        gA, gB, gC = host(rec["A"], np.uint16), host(rec["B"], np.uint16), host(rec["C"], np.uint32)
+        gD = host(rec["D"], np.uint32)
+        for q, t in enumerate(rec["tiles"]):
+            Ah, Bh, Ch = _config4_oracle_inputs(t, 1)
+            assert_same(gA[q:q + 1], Ah.astype(np.uint16), "config4 A of tile %d" % t)
+            assert_same(gB[q:q + 1], Bh.astype(np.uint16), "config4 B of tile %d" % t)
+            assert_same(gC[q:q + 1], Ch, "config4 C of tile %d" % t)
+        for vi, p in enumerate(CONFIG4_ORACLE):
+            w, _ = o2lib.emulate_mma(p, gA.astype(np.uint16), gB.astype(np.uint16), gC, fm.FP16, fm.FP16)
+            assert_same(gD[vi], w, "config4 variant %d, tiles %s" % (vi, rec["tiles"][:3]))
+        seen.extend(rec["tiles"])
+    assert sorted(seen) == sorted(samples) and len(seen) == 1024 and max(seen) == n_tiles - 1
+    # the rational form of the oracle on a few outputs of the last sampled tile
+    last = r["samples"][-1]
+    gA, gB, gC, gD = host(last["A"], np.uint16), host(last["B"], np.uint16), host(last["C"], np.uint32), host(last["D"], np.uint32)
+    for vi, p in enumerate(CONFIG4_ORACLE):
+        for (i, j) in ((0, 0), (5, 17), (31, 31)):
+            assert int(gD[vi][-1, i, j]) == emulate_element(p, gA[-1, i].tolist(), gB[-1, j].tolist(), int(gC[-1, i, j]), fm.FP16, fm.FP16)
+    # the end of the stream on its own: output indices beyond 2^32 in the statistics
+    ntail = 1 << 10
+    tail = cfg.config4(n_tiles=ntail, chunk=chunk, seed=0, first_tile=n_tiles - ntail)
+    At, Bt, Ct = _config4_oracle_inputs(n_tiles - ntail, ntail)
+    wt = [o2lib.emulate_mma(p, At, Bt, Ct, fm.FP16, fm.FP16)[0] for p in CONFIG4_ORACLE]
+    base = (n_tiles - ntail) * 1024
+    for name, w in zip(("none", "ftz_in", "ftz_out"), wt):
+        assert tail["stats"][name] == ostats.compare(w, wt[0], index_base=base), name
+    assert tail["stats"]["ftz_in"]["first_mismatch_index"] > (1 << 35)
 
 
-def test_config5_closed_loop(cfg, mm):
-    n_tiles = 1 << (24 if FULL else 18)
-    chunk = 1 << 16
-    r = cfg.config5(n_tiles=n_tiles, chunk=chunk, seed=0, keep_first_chunk=True)
+def test_config4_unfused_path_agrees(cfg, mm):
+    """One emulation and one comparison per variant (the other route through the library) gives the same statistics."""
+    a = cfg.config4(n_tiles=1 << 16, chunk=1 << 14, fused=True)
+    b = cfg.config4(n_tiles=1 << 16, chunk=1 << 14, fused=False)
+    assert a["stats"] == b["stats"] and b["kernel"].startswith("tiled 32x32")
+
+
+def _config5_oracle_inputs(kind, first_tile, nt):
+    if kind == "bf16":
+        A = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=0), fm.BF16, 256, first_tile, nt)
+        B = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=1), fm.BF16, 256, first_tile, nt)
+    else:
+        A = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=0, scale_scope=ogen.SCALE_TILE,
+                                         scale_target=448.0), fm.E4M3, 256, first_tile, nt, threads=THREADS)
+        B = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=1, scale_scope=ogen.SCALE_TILE,
+                                         scale_target=57344.0), fm.E5M2, 256, first_tile, nt, threads=THREADS)
+    C = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=2), fm.FP32, 256, first_tile, nt, threads=THREADS)
+    return A.reshape(nt, 16, 16), B.reshape(nt, 16, 16), C.reshape(nt, 16, 16)
+
+
+def test_config5_at_its_stated_size(cfg, mm):
+    """Sixteen parameter sets x 2^24 tiles x two operand types, every tile through the native instruction.  Whole-run
+    invariants; first chunk's operands and the first 2^10 tiles of every set against the oracle; 2^10 tiles at hashed
+    indices over the whole stream (32 chunks, the last among them) out of the run itself; the statistics the fused
+    kernels form, against the oracle's comparison on a prefix."""
+    n_tiles, chunk = 1 << 24, 1 << 16
+    samples = hashed_tiles(n_tiles, chunk, 32, 32, seed=5)
+    r = cfg.config5(n_tiles=n_tiles, chunk=chunk, seed=0, keep_first_chunk=True, sample_tiles=samples)
     nchk = 1 << 10
+    total = n_tiles * 256                                                      # 2^32 outputs per set and type
     for kind, (ta, tb) in (("bf16", (fm.BF16, fm.BF16)), ("fp8", (fm.E4M3, fm.E5M2))):
         res = r[kind]
-        for st in res["stats"]:
-            assert st["n_compared"] == n_tiles * 256 and sum(st["ulp_hist"]) == n_tiles * 256
-        # generated operands of the first chunk
-        if kind == "bf16":
-            A = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=0), ta, 256, 0, chunk)
-            B = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=1), tb, 256, 0, chunk)
-        else:
-            A = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=0, scale_scope=ogen.SCALE_TILE,
-                                             scale_target=448.0), ta, 256, 0, chunk, threads=THREADS)
-            B = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=1, scale_scope=ogen.SCALE_TILE,
-                                             scale_target=57344.0), tb, 256, 0, chunk, threads=THREADS)
-        C = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=2), fm.FP32, 256, 0, chunk, threads=THREADS)
         npdt = np.uint16 if kind == "bf16" else np.uint8
-        assert_same(host(res["dev"]["A"], npdt).reshape(chunk, 256), A.astype(npdt), "config5 %s A" % kind)
-        assert_same(host(res["dev"]["B"], npdt).reshape(chunk, 256), B.astype(npdt), "config5 %s B" % kind)
-        assert_same(host(res["dev"]["C"], np.uint32).reshape(chunk, 256), C, "config5 %s C" % kind)
-        A, B, C = (x.reshape(chunk, 16, 16) for x in (A, B, C))
+        plist = [ModelParams(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(ftz), ftz_out=bool(ftz)) for F, L, rho, ftz in cfg.CONFIG5_MODELS]
+        assert all(k.startswith("multi") for k in res["kernels"]) and len(res["kernels"]) == 6, res["kernels"]
+        for st in res["stats"]:
+            assert st["n_compared"] == total and sum(st["ulp_hist"]) == total
+            assert 0 < st["n_mismatch_bits"] < total                             # (none of the sets is the instruction's arithmetic)
+        for a in res["agreement"]:
+            assert 0.0 < a < 1.0
+        # generated operands of the first chunk
+        A, B, C = _config5_oracle_inputs(kind, 0, chunk)
+        assert_same(host(res["dev"]["A"], npdt), A.astype(npdt), "config5 %s A" % kind)
+        assert_same(host(res["dev"]["B"], npdt), B.astype(npdt), "config5 %s B" % kind)
+        assert_same(host(res["dev"]["C"], np.uint32), C, "config5 %s C" % kind)
         Dhw = host(res["dev"]["Dhw"], np.uint32)
-        # every parameter set on the first 2^10 tiles; agreement with the native instruction recomputed from
-        # the oracle's outputs for those tiles
-        for (F, L, rho, ftz), Dg in zip(cfg.CONFIG5_MODELS, res["dev"]["D"]):
-            p = ModelParams(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(ftz), ftz_out=bool(ftz))
+        # every parameter set on the first 2^10 tiles
+        want = []
+        for p, Dg in zip(plist, res["dev"]["D"]):
             w, _ = o2lib.emulate_mma(p, A[:nchk], B[:nchk], C[:nchk], ta, tb)
             assert_same(host(Dg, np.uint32)[:nchk], w, "config5 %s %s" % (kind, p))
+            want.append(w)
+        # statistics of that prefix from the grouped launches (D never written), against the oracle's comparison of its own
+        # outputs with the instruction's output as the run produced it
+        pre = cfg.config5(n_tiles=nchk, chunk=chunk, seed=0, kinds=(kind,))[kind]
+        for i, w in enumerate(want):
+            assert pre["stats"][i] == ostats.compare(w, Dhw[:nchk]), (kind, i)
         # rational-arithmetic oracle on one tile row for two of the sets
         for mi in (0, 15):
-            F, L, rho, ftz = cfg.CONFIG5_MODELS[mi]
-            p = ModelParams(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(ftz), ftz_out=bool(ftz))
             Dg = host(res["dev"]["D"][mi], np.uint32)
             for j in range(16):
-                assert int(Dg[3, 5, j]) == emulate_element(p, A[3, 5].tolist(), B[3, j].tolist(), int(C[3, 5, j]), ta, tb)
-        # the agreement rate is a report, not a requirement (gfx950 is not among the paper's models); it must be
-        # a valid rate and the native output must at least be finite where the model's is
-        for a in res["agreement"]:
-            assert 0.0 <= a <= 1.0
-        assert Dhw.shape == (chunk, 16, 16)
+                assert int(Dg[3, 5, j]) == emulate_element(plist[mi], A[3, 5].tolist(), B[3, j].tolist(), int(C[3, 5, j]), ta, tb)
+        # the sampled tiles of the run itself
+        seen = []
+        for rec in res["samples"]:
+            t_first = rec["tiles"][0]
+            gA, gB, gC = host(rec["A"], npdt), host(rec["B"], npdt), host(rec["C"], np.uint32)
+            gD = host(rec["D"], np.uint32)
+            for q in (0, len(rec["tiles"]) - 1):                                # (operands: first and last sampled tile of the chunk)
+                Ah, Bh, Ch = _config5_oracle_inputs(kind, rec["tiles"][q], 1)
+                assert_same(gA[q:q + 1], Ah.astype(npdt), "config5 %s A of tile %d" % (kind, rec["tiles"][q]))
+                assert_same(gB[q:q + 1], Bh.astype(npdt), "config5 %s B of tile %d" % (kind, rec["tiles"][q]))
+                assert_same(gC[q:q + 1], Ch, "config5 %s C of tile %d" % (kind, rec["tiles"][q]))
+            for mi, p in enumerate(plist):
+                w, _ = o2lib.emulate_mma(p, gA, gB, gC, ta, tb)
+                assert_same(gD[mi], w, "config5 %s set %d, tiles from %d" % (kind, mi, t_first))
+            seen.extend(rec["tiles"])
+        assert sorted(seen) == sorted(samples) and len(seen) == 1024 and max(seen) == n_tiles - 1
+
+
+def test_config5_unfused_path_agrees(cfg, mm):
+    a = cfg.config5(n_tiles=1 << 17, chunk=1 << 16, fused=True)
+    b = cfg.config5(n_tiles=1 << 17, chunk=1 << 16, fused=False)
+    for kind in ("bf16", "fp8"):
+        assert a[kind]["stats"] == b[kind]["stats"], kind
+        assert all(k.startswith("tiled 16x16") for k in b[kind]["kernels"])
 
 
 def test_config1_replayed_from_a_hip_graph_gives_the_same_statistics():
