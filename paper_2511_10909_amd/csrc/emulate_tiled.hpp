@@ -514,6 +514,7 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
     uint32_t fl = p.flags;                            // the model's switches, one bit each (one scalar register)
     uint32_t out_mask = p.out_mask, nan_bits = p.nan_bits;
     uint32_t cur_model = 0;
+    bool slow_seen = false;                           // (several models) some group of the current model left the short route
     // the kernel's arguments once more, through a pointer the optimiser cannot see through (see slow_group)
     auto fetch_args = [&]() -> TiledArgs {
         if constexpr (MULTI) {
@@ -930,6 +931,50 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
     auto end_of_group = [&](uint32_t kg, const int (&emax)[R][C], uint32_t tagged) {
         refresh_switches();
         flush_accumulators();
+        if constexpr (MULTI && CMODE == MMAEMU_C_IN_GROUP && !USE_SD && VM != 2) {
+            // Short route (in the multi-model kernels only: the single-model kernels with 4 x 4 register blocks have no
+            // registers to spare for a second route and lose a wave of occupancy to it).  When the L truncated products and the truncated accumulator together fit 32 bits
+            // ((L + 1) 2^(F+2) <= 2^31), the accumulator is aligned like a product (one multiplication by 2^(F - e_max),
+            // exact, and the float -> int conversion that truncates toward zero), the whole sum S is a 32-bit integer,
+            // and rho(S 2^(e_max - F)) is the int -> float conversion (RNE to 24 bits) followed by an exact scaling --
+            // as long as the result cannot be subnormal or the accumulator non-finite: e_max - F >= -126 and
+            // e_max <= 127 for every output of the wavefront, and no tagged element in the group.  Anything else takes
+            // the binary64 route below.  Results here are normal numbers, zero or an overflow, so the output flush has
+            // nothing to do; RZ steps back where the conversion rounded away from zero.
+            const bool fits = ((uint64_t)(GL + 1) << (F + 2)) <= (1ull << 31) && F >= 1 && !(fe & FL_ACC16);
+            if (fits) {
+                uint32_t worst = (tagged & SENTINEL_MASK) ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        const uint32_t u = (uint32_t)(emax[r][c] - (F - 126));          // 0 .. 253 - F on this route
+                        worst = u > worst ? u : worst;
+                    }
+                if (__all(worst <= (uint32_t)(253 - F))) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            const float scale = __uint_as_float((uint32_t)(F + 127 - emax[r][c]) << 23);     // 2^(F - e_max), a normal number
+                            const int32_t S = S32[r][c] + (int32_t)(__uint_as_float(d[r][c]) * scale);
+                            float f = (float)S;
+                            if ((fe & FL_RZ)) {
+                                const int32_t diff = (int32_t)f - S;                   // (|S| < 2^31 - L: the conversion back is exact)
+                                if (diff != 0 && (diff ^ S) >= 0) f = __uint_as_float(__float_as_uint(f) - 1u);
+                            }
+                            uint32_t o = __float_as_uint(ldexpf(f, emax[r][c] - F));
+                            if ((fe & FL_RZ)) {
+                                if ((o & 0x7FFFFFFFu) == 0x7F800000u) o -= 1u;         // overflow: the largest finite number
+                                o &= out_mask;
+                            }
+                            d[r][c] = o;
+                        }
+                    return;
+                }
+            }
+        }
+        if constexpr (MULTI) slow_seen = true;
         double v[R][C];
         if (CMODE == MMAEMU_C_IN_GROUP) {
 #pragma unroll
@@ -1066,7 +1111,7 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
 
     // the groups of one staged chunk, unsplit modes
     auto plain_groups = [&](uint32_t k0) {
-        constexpr int GU = (R * C <= 4 && KC / GL <= 4 && CMODE != MMAEMU_C_AFTER_RD) ? KC / GL : 1;
+        constexpr int GU = (!MULTI && R * C <= 4 && KC / GL <= 4 && CMODE != MMAEMU_C_AFTER_RD) ? KC / GL : 1;
 #pragma unroll GU
         for (int g = 0; g < KC / GL; ++g) {
             reset_group();
@@ -1136,6 +1181,7 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int c = 0; c < C; ++c) d[r][c] = c0[r][c];
+            slow_seen = false;
             plain_groups(0);
             // Per output that differs from the reference: one LDS atomic on its histogram bucket (bucket 0 of the LDS
             // copy counts pairs that differ at distance 0: zeros of both signs, NaNs of two patterns), so the number of
@@ -1151,7 +1197,7 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
 #pragma unroll
                     for (int c = 0; c < C; ++c) {
                         uint32_t x = d[r][c];
-                        if ((x & 0x7FFFFFFFu) > 0x7F800000u) x = nan_bits;
+                        if (slow_seen && (x & 0x7FFFFFFFu) > 0x7F800000u) x = nan_bits;          // (the short route produces no NaN)
                         const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
                         if (dout) dout[dump_off + o] = x;
                         if (ref_first && mi == 0) ref[r][c] = x;
