@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="before the timed region, run 5 plain device copies of 64 MiB (a kernel of known traffic, "
                          "to scale FETCH_SIZE / WRITE_SIZE counters collected under rocprofv3 --pmc)")
+    ap.add_argument("--issue-rates", action="store_true",
+                    help="instead of the benchmark: time the library's issue-rate probes (one per hot-loop instruction) and "
+                         "print their lane-instructions per second as one JSON line")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target duration of the CPU-oracle sample")
     return ap.parse_args()
 
@@ -72,6 +75,28 @@ def cpu_baseline(target_seconds):
                 sample="tiles 0..%d of the bf16 half, all 16 parameter sets (emulation only): %d terms in %.2f s" % (nt - 1, terms, elapsed))
 
 
+def issue_rates(torch, mm):
+    """Lane-instructions per second of each probed instruction: 2048 workgroups x 256 lanes x 8 chains x 4096 iterations,
+    best of five launches timed with events."""
+    out = torch.zeros(256, dtype=torch.int32, device="cuda")
+    iters, wgs = 4096, 2048
+    rates = {}
+    for op, name in enumerate(mm.issue_probe_names()):
+        mm.issue_probe(op, 64, wgs, out)
+        best = None
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            mm.issue_probe(op, iters, wgs, out)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None or ms < best else best
+        rates[name] = wgs * 256 * 8 * iters / (best * 1e-3)
+    return dict(unit="lane-instructions/s", peak_assumed=INT32_VALU_PEAK, rates=rates,
+                frac_of_peak={k: v / INT32_VALU_PEAK for k, v in rates.items()})
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -86,6 +111,9 @@ def main():
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.issue_rates:
+        print(json.dumps(issue_rates(torch, mm)))
+        return
     n_tiles, chunk = args.tiles, min(args.chunk, args.tiles)
     fused = not args.unfused
     scans = [configs.ClosedLoopScan(kind, chunk, 0, "cuda", fused) for kind in ("bf16", "fp8")]

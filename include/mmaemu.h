@@ -459,6 +459,19 @@ mmaemu_status mmaemu_exact_dot_sample(const void *A, const void *B, const void *
                                       uint32_t n, uint32_t k, mmaemu_dtypes dtypes, uint64_t stride,
                                       mmaemu_err_stats *dev_err, void *hip_stream);
 
+/*
+ * Issue-rate probes: the measured counterpart of the vector-ALU peak that the emulation kernels' roofline is quoted
+ * against (the path is bound by integer / binary32 vector-ALU issue, not by the matrix cores or HBM).  Probe `op`
+ * (0 .. mmaemu_issue_probe_count() - 1, one per instruction the hot loops are made of; mmaemu_issue_probe_name gives
+ * its mnemonic, NULL beyond the last) enqueues `workgroups` workgroups of 256 threads that each issue
+ * 8 * iterations instances of the instruction per lane in eight independent chains; the caller times the launch
+ * (events on the stream) and divides workgroups * 256 * 8 * iterations by the duration.  `out`: 1 KiB of device
+ * memory that the probe may write.  Errors: INVALID_ARG (op, out), SHAPE (zero counts).
+ */
+uint32_t mmaemu_issue_probe_count(void);
+const char *mmaemu_issue_probe_name(uint32_t op);
+mmaemu_status mmaemu_issue_probe(uint32_t op, uint32_t iterations, uint32_t workgroups, void *out, void *hip_stream);
+
 const char *mmaemu_status_string(mmaemu_status s);
 const char *mmaemu_last_error(void); /* thread-local, never NULL */
 /* Name of the kernel family the calling thread's last successful mmaemu_emulate_mma

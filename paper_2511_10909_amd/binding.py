@@ -120,6 +120,10 @@ _lib.mmaemu_generate_noalloc.argtypes = [ctypes.POINTER(GenParams), _vp, ctypes.
 _lib.mmaemu_mfma_info.argtypes = [ctypes.c_int] + [ctypes.POINTER(_u32)] * 3 + [ctypes.POINTER(ctypes.c_int)] * 2
 _lib.mmaemu_mfma_probe.argtypes = [ctypes.c_int, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
 _lib.mmaemu_mfma_probe_scaled.argtypes = [ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _u32, _u64, _vp]
+_lib.mmaemu_issue_probe_count.restype = _u32
+_lib.mmaemu_issue_probe_name.restype = ctypes.c_char_p
+_lib.mmaemu_issue_probe_name.argtypes = [_u32]
+_lib.mmaemu_issue_probe.argtypes = [_u32, _u32, _u32, _vp, _vp]
 _lib.mmaemu_err_stats_reset.argtypes = [_vp, _vp]
 _lib.mmaemu_exact_dot_sample.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, Dtypes, _u64, _vp, _vp]
 
@@ -251,6 +255,14 @@ def mfma_probe(instr, A, B, C, D, k, batch, stream=None):
 
 def mfma_probe_scaled(instr, A, B, C, D, SA, SB, k, batch, stream=None):
     _check(_lib.mmaemu_mfma_probe_scaled(instr, _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(SA), _ptr(SB), k, batch, _stream(stream)))
+
+
+def issue_probe_names():
+    return [_lib.mmaemu_issue_probe_name(i).decode() for i in range(_lib.mmaemu_issue_probe_count())]
+
+
+def issue_probe(op, iterations, workgroups, out, stream=None):
+    _check(_lib.mmaemu_issue_probe(op, iterations, workgroups, _ptr(out), _stream(stream)))
 
 
 def err_stats_reset(dev_err, stream=None):

@@ -714,6 +714,18 @@ mmaemu_status mmaemu_mfma_probe_scaled(mmaemu_mfma_instr instr, const void *A, c
     return launch_mfma_probe_scaled((uint32_t)instr, A, B, C, D, SA, SB, k, batch, (hipStream_t)hip_stream);
 }
 
+uint32_t mmaemu_issue_probe_count(void) { return issue_probe_count(); }
+
+const char *mmaemu_issue_probe_name(uint32_t op) { return issue_probe_name(op); }
+
+mmaemu_status mmaemu_issue_probe(uint32_t op, uint32_t iterations, uint32_t workgroups, void *out, void *hip_stream)
+{
+    if (op >= issue_probe_count()) { set_error("issue_probe: unknown instruction %u", op); return MMAEMU_ERR_INVALID_ARG; }
+    if (iterations == 0 || workgroups == 0 || workgroups > (1u << 20)) { set_error("issue_probe: iterations and workgroups (up to 2^20) must be positive"); return MMAEMU_ERR_SHAPE; }
+    if (!out || ((uintptr_t)out & 3)) { set_error("issue_probe: out must be 1 KiB of 4-byte aligned device memory"); return MMAEMU_ERR_INVALID_ARG; }
+    return launch_issue_probe(op, iterations, workgroups, static_cast<uint32_t *>(out), (hipStream_t)hip_stream);
+}
+
 mmaemu_status mmaemu_err_stats_reset(mmaemu_err_stats *st, void *hip_stream)
 {
     if (!st) { set_error("err_stats_reset: NULL"); return MMAEMU_ERR_INVALID_ARG; }

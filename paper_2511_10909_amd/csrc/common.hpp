@@ -131,6 +131,11 @@ mmaemu_status launch_exact_dot_sample(const void *A, const void *B, const uint32
                                       uint32_t k, uint32_t ta, uint32_t tb, uint64_t stride,
                                       mmaemu_err_stats *st, hipStream_t s);
 
+// issue-rate probes (issue_rate.hip)
+uint32_t issue_probe_count();
+const char *issue_probe_name(uint32_t op);
+mmaemu_status launch_issue_probe(uint32_t op, uint32_t iters, uint32_t workgroups, uint32_t *out, hipStream_t s);
+
 // ---- device helpers -----------------------------------------------------------------
 #if defined(__HIPCC__)
 

@@ -338,6 +338,15 @@ __device__ __forceinline__ uint32_t multi_count_and_ref(uint32_t &ref_is_first)
 #endif
 }
 
+// Binary32 rounding mode of the wavefront (bits 1:0 of the MODE register): to nearest even, or toward zero.
+__device__ __forceinline__ void set_f32_round_toward_zero(bool on)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (on) __builtin_amdgcn_s_setreg((1 | (0 << 6) | (1 << 11)), 3);      // hwreg(MODE, offset 0, 2 bits) = 3
+    else __builtin_amdgcn_s_setreg((1 | (0 << 6) | (1 << 11)), 0);
+#endif
+}
+
 // Reduction over the 64 lanes of a wavefront with row shifts and row broadcasts of the data-parallel primitives (no LDS
 // traffic); the result is valid in lane 63.
 template <bool IS_MAX>
@@ -541,25 +550,38 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
     // workgroup -> items.  Consecutive workgroup ids go to different XCDs (8 of them, each
     // with its own L2); the remap hands every XCD a contiguous range of blocks so that
     // neighbours sharing A/B panels share an L2.
-    uint32_t wg = wg_index;                           // (blockIdx.x, or the workgroup's current pass with several models)
-    if (xcd_remap) wg = (wg & 7u) * (gridDim.x >> 3) + (wg >> 3);
-    const uint64_t item0 = (uint64_t)wg * SLOTS;
+    // (with several models a workgroup makes several passes, each over the items of one logical workgroup: what depends
+    // on the pass is set by the two routines below, the staging plans apart from the outputs' places, so that the
+    // next pass's operands can be fetched while the current pass's models run)
+    uint64_t item0;
     constexpr int NQA = (SLOTS * TM * (KC / 4) + 255) / 256, NQB = (SLOTS * TN * (KC / 4) + 255) / 256;
     const uint32_t esa = WIDE ? 4u : ((ta_.ta <= MMAEMU_FP8_E5M2 || ta_.ta >= MMAEMU_FP6_E2M3) ? 1u : 2u);      // bytes per element
     const uint32_t esb = WIDE ? 4u : ((ta_.tb <= MMAEMU_FP8_E5M2 || ta_.tb >= MMAEMU_FP6_E2M3) ? 1u : 2u);
     StagePlan<NQA> plan_a;
     StagePlan<NQB> plan_b;
-    make_plan<TM, KC, SLOTS, VS, ES, true, NQA>(plan_a, A, esa, item0, nitems, bm_count, bn_count, m, k);
-    make_plan<TN, KC, SLOTS, VS, ES, false, NQB>(plan_b, B, esb, item0, nitems, bm_count, bn_count, n, k);
-
-    const bool live = item0 + slot < nitems;
-    uint64_t my_it = item0 + slot;
-    my_it = my_it < nitems ? my_it : nitems - 1;
-    const uint32_t per_tile = bm_count * bn_count;
-    uint64_t my_tile; uint32_t my_rem;
-    split_item(my_it, per_tile, my_tile, my_rem);
-    const uint32_t i_base = (my_rem / bn_count) * TM + ti, j_base = (my_rem % bn_count) * TN + tj;
-    const uint64_t d_off = (my_tile * m + i_base) * (uint64_t)n + j_base;     // + TI*r*n + TJ*c
+    auto logical_wg = [&](uint32_t w) -> uint32_t { return xcd_remap ? (w & 7u) * (gridDim.x >> 3) + (w >> 3) : w; };
+    auto set_plans = [&](uint32_t w) {
+        const uint64_t it0 = (uint64_t)logical_wg(w) * SLOTS;
+        make_plan<TM, KC, SLOTS, VS, ES, true, NQA>(plan_a, A, esa, it0, nitems, bm_count, bn_count, m, k);
+        make_plan<TN, KC, SLOTS, VS, ES, false, NQB>(plan_b, B, esb, it0, nitems, bm_count, bn_count, n, k);
+    };
+    bool live;
+    uint64_t my_tile, d_off;                          // d_off: + TI*r*n + TJ*c
+    uint32_t i_base, j_base;
+    auto set_outputs = [&](uint32_t w) {
+        item0 = (uint64_t)logical_wg(w) * SLOTS;
+        live = item0 + slot < nitems;
+        uint64_t my_it = item0 + slot;
+        my_it = my_it < nitems ? my_it : nitems - 1;
+        const uint32_t per_tile = bm_count * bn_count;
+        uint32_t my_rem;
+        split_item(my_it, per_tile, my_tile, my_rem);
+        i_base = (my_rem / bn_count) * TM + ti;
+        j_base = (my_rem % bn_count) * TN + tj;
+        d_off = (my_tile * m + i_base) * (uint64_t)n + j_base;
+    };
+    set_plans(wg_index);
+    set_outputs(wg_index);
 
     // C in (each thread its own elements; measured faster here than moving the block through LDS)
     uint32_t d[R][C];
@@ -958,11 +980,7 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
                         for (int c = 0; c < C; ++c) {
                             const float scale = __uint_as_float((uint32_t)(F + 127 - emax[r][c]) << 23);     // 2^(F - e_max), a normal number
                             const int32_t S = S32[r][c] + (int32_t)(__uint_as_float(d[r][c]) * scale);
-                            float f = (float)S;
-                            if ((fe & FL_RZ)) {
-                                const int32_t diff = (int32_t)f - S;                   // (|S| < 2^31 - L: the conversion back is exact)
-                                if (diff != 0 && (diff ^ S) >= 0) f = __uint_as_float(__float_as_uint(f) - 1u);
-                            }
+                            const float f = (float)S;                                  // (truncates under RZ: see the model loop)
                             uint32_t o = __float_as_uint(ldexpf(f, emax[r][c] - F));
                             if ((fe & FL_RZ)) {
                                 if ((o & 0x7FFFFFFFu) == 0x7F800000u) o -= 1u;         // overflow: the largest finite number
@@ -1109,6 +1127,9 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
         else pass2f(g, emax);
     };
 
+    // (several models) the packed exponent maxima of every group, formed once per pass: they depend on the operands alone,
+    // so every model of the launch (all of one group length) starts its groups from them
+    __shared__ uint32_t m2_keep[MULTI ? KC / GL : 1][MULTI ? R * C : 1][MULTI ? 256 : 1];
     // the groups of one staged chunk, unsplit modes
     auto plain_groups = [&](uint32_t k0) {
         constexpr int GU = (!MULTI && R * C <= 4 && KC / GL <= 4 && CMODE != MMAEMU_C_AFTER_RD) ? KC / GL : 1;
@@ -1116,7 +1137,14 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
         for (int g = 0; g < KC / GL; ++g) {
             reset_group();
             load_scales(k0 + g * GL);
-            pass1(g);
+            if constexpr (MULTI) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) m2[r][c] = m2_keep[g][r * C + c][tid];
+            } else {
+                pass1(g);
+            }
             int emax[R][C]; uint32_t tagged = 0;
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -1135,12 +1163,15 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
         uint32_t ref_first;
         const uint32_t count = multi_count_and_ref(ref_first);
         const uint32_t *dref = mu->dref;
-        // the operands are staged once, as the first model wants them
-        fl = multi_hot(0).flags;
-        commit(3);
-        // accumulator inputs and reference: read once, held in registers across the models (a load per model would put
-        // a memory latency in front of every model's few hundred instructions)
+        // Passes of this workgroup: wg_index, wg_index + gridDim.x, ...  The operands of a pass are staged once, as the
+        // first model wants them.
+        const uint32_t nblocks = (uint32_t)((nitems + SLOTS - 1) / SLOTS);
+        uint32_t pass_wg = wg_index;
         uint32_t c0[R][C], ref[R][C];
+        for (;;) {
+        // accumulator inputs and reference: read once per pass (before the staging, which hides their latency), held in
+        // registers across the models (a load per model would put a memory latency in front of every model's few
+        // hundred instructions)
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -1149,6 +1180,18 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
                 c0[r][c] = Cm[o];
                 ref[r][c] = ref_first ? 0u : dref[o];
             }
+        fl = multi_hot(0).flags;
+        commit(3);
+        const uint32_t following = pass_wg + gridDim.x;
+#pragma unroll 1
+        for (int g = 0; g < KC / GL; ++g) {
+            reset_group();
+            pass1(g);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) m2_keep[g][r * C + c][tid] = m2[r][c];     // (each thread its own words: no barrier needed)
+        }
         int staged = (fl & FL_FTZ_IN) ? 1 : 0;                               // FlushSubnormal state of the staged values
 #pragma unroll 1
         for (uint32_t mi = 0; mi < count; ++mi) {
@@ -1158,6 +1201,10 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
             fl = hot.flags;
             out_mask = hot.out_mask;
             nan_bits = hot.nan_bits;
+            // rho = RZ-FP32: the model's groups run with the binary32 rounding mode "toward zero", so that the short route's
+            // int -> float conversion truncates (every other binary32 operation of the loop is exact in either mode, and
+            // the binary64 route checks the direction of its own conversion)
+            set_f32_round_toward_zero((fl & FL_RZ) != 0);
             const int want = (fl & FL_FTZ_IN) ? 1 : 0;
             if (want && !staged) {
                 // FlushSubnormal on the staged values, in place: whatever lies below the format's smallest normal
@@ -1229,6 +1276,15 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
                 atomicMin(&ml->first[mi], (unsigned long long)(mu->index_base + item0 * (uint64_t)(TM * TN) + wmin));
                 if (wmax) atomicMax(&ml->maxd[mi], wmax);
             }
+        }
+        set_f32_round_toward_zero(false);
+        // (fetching the next pass's operands before the models run, so that they arrive meanwhile, was measured and made the
+        // closed-loop scan slower: the registers they occupy cost more than the latency they hide)
+        if (following >= nblocks) break;
+        pass_wg = following;
+        set_plans(pass_wg);
+        prefetch(0);
+        set_outputs(pass_wg);
         }
         return;
     }
@@ -1442,9 +1498,8 @@ emulate_tiled_multi_kernel(MultiArgs mu_, const void *__restrict__ A, const void
     for (uint32_t i = tid; i < MULTI_MAX * 34 * HC; i += 256) (&ml.hist[0][0][0])[i] = 0;
     if (tid < MULTI_MAX) { ml.naneq[tid] = 0; ml.maxd[tid] = 0; ml.first[tid] = ~0ull; }
     // (the first staging's barriers come before any thread counts anything)
-#pragma unroll 1
-    for (uint32_t wg = blockIdx.x; wg < nblocks; wg += gridDim.x)
-        tiled_body<TM, TN, R, C, KC, LT, MMAEMU_C_IN_GROUP, NF, VM_, true>(mu_.t, A, B, Cm, nullptr, m, n, k, nitems, 1u, 1u, 0u, wg, &ml);
+    if (blockIdx.x < nblocks)
+        tiled_body<TM, TN, R, C, KC, LT, MMAEMU_C_IN_GROUP, NF, VM_, true>(mu_.t, A, B, Cm, nullptr, m, n, k, nitems, 1u, 1u, 0u, blockIdx.x, &ml);
     __syncthreads();
     // one global atomic per non-zero counter per workgroup; n_compared and bucket 0 are known up front: workgroup 0
     // adds the whole count once, every workgroup takes its non-zero buckets back out of bucket 0
