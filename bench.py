@@ -34,8 +34,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--tiles", type=int, default=1 << 24, help="tiles per operand type (the workload as stated: 2^24)")
-    ap.add_argument("--chunk", type=int, default=1 << 16, help="tiles generated and evaluated at a time")
+    ap.add_argument("--workload", choices=("scan", "subnormal"), default="scan",
+                    help="scan: the closed-loop scan (the headline); subnormal: the subnormal stress workload (2^26 fp16 32x32x8 "
+                         "tiles, three flush variants) as the step, for its own profile")
+    ap.add_argument("--tiles", type=int, default=0, help="tiles per operand type (default: the workload as stated, 2^24 / 2^26)")
+    ap.add_argument("--chunk", type=int, default=0, help="tiles generated and evaluated at a time (default 2^16 / 2^14)")
     ap.add_argument("--unfused", action="store_true", help="one emulation launch and one comparison launch per parameter set")
     ap.add_argument("--time-every", type=int, default=16, help="HIP events around the emulation launches of every n-th chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -73,6 +76,47 @@ def cpu_baseline(target_seconds):
         nt = int(min(1 << 20, max(nt * 2, nt * target_seconds / max(elapsed, 1e-3) * 0.9)))
     return dict(value=terms / elapsed, unit="terms/s", cores=used, kind="oracle",
                 sample="tiles 0..%d of the bf16 half, all 16 parameter sets (emulation only): %d terms in %.2f s" % (nt - 1, terms, elapsed))
+
+
+def subnormal_stress(args, torch, mm, configs, fused):
+    """The subnormal stress workload as the step (not the headline: it has fewer terms than the scan)."""
+    n_tiles = args.tiles or (1 << 26)
+    chunk = min(args.chunk or (1 << 14), n_tiles)
+    timed = []
+
+    def timer(name, terms, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        timed.append((name, terms, e0, e1))
+
+    for _ in range(args.warmup):
+        configs.config4(n_tiles=n_tiles, chunk=chunk, fused=fused)
+    secs, r = 0.0, None
+    for _ in range(args.steps):
+        r = configs.config4(n_tiles=n_tiles, chunk=chunk, fused=fused, timer=timer, time_every=args.time_every * 4)
+        secs += r["seconds"]
+    ms = sum(e0.elapsed_time(e1) for _, _, e0, e1 in timed)
+    terms = sum(t for _, t, _, _ in timed)
+    ctr = COUNTERS.get(r["kernel"], {})
+    frac = ALGO_OPS_PER_TERM * terms / (ms * 1e-3) / INT32_VALU_PEAK
+    return {
+        "metric": "bit-exact emulated MAC terms/sec on 1 MI355X", "value": r["terms"] * args.steps / secs, "unit": "terms/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": secs / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32+i32 (exact binary32 products, int32 sums)", "data": "synthetic",
+        "config": {"workload": "configs[3]: subnormal stress, 2^%d fp16 32x32x8 tiles, exponent fields uniform over the whole range, "
+                               "variants none / ftz_in / ftz_out each compared with the first (%s)"
+                               % (n_tiles.bit_length() - 1, "one fused launch per chunk" if fused else "one emulation and one comparison per variant"),
+                   "terms_per_step": r["terms"], "chunk": chunk, "fused": fused, "kernel": r["kernel"],
+                   "mismatches": {k: v["n_mismatch_bits"] for k, v in r["stats"].items()},
+                   "emulation_launches_timed": len(timed), "avg_emulation_launch_ms": ms / max(len(timed), 1)},
+        "roofline": {"bound": "alu", "kernel": r["kernel"], "achieved": frac * INT32_VALU_PEAK / 1e12, "peak": INT32_VALU_PEAK / 1e12,
+                     "unit": "T INT32 lane-instr/s (8 algorithmic instr per MAC term)", "frac": frac,
+                     "valu_instr_per_term": ctr.get("valu_instr_per_term"),
+                     "valu_util": (ctr["valu_instr_per_term"] * terms / (ms * 1e-3) / INT32_VALU_PEAK) if ctr else None,
+                     "traffic": ctr.get("traffic"), "traffic_source": COUNTERS_SOURCE if ctr else None},
+    }
 
 
 def issue_rates(torch, mm):
@@ -114,8 +158,18 @@ def main():
     if args.issue_rates:
         print(json.dumps(issue_rates(torch, mm)))
         return
-    n_tiles, chunk = args.tiles, min(args.chunk, args.tiles)
     fused = not args.unfused
+    if args.copy_calibration:
+        src = torch.arange(16 * 1024 * 1024, dtype=torch.int32, device=dev)       # 64 MiB read + 64 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)                                             # one elementwise kernel per call
+        torch.cuda.synchronize()
+    if args.workload == "subnormal":
+        print(json.dumps(subnormal_stress(args, torch, mm, configs, fused)))
+        return
+    n_tiles = args.tiles or (1 << 24)
+    chunk = min(args.chunk or (1 << 16), n_tiles)
     scans = [configs.ClosedLoopScan(kind, chunk, 0, "cuda", fused) for kind in ("bf16", "fp8")]
     n_sets = len(configs.CONFIG5_MODELS)
     timed = []                      # (kernel key, terms, start event, end event) of the emulation launches that carry events
@@ -135,12 +189,6 @@ def main():
                         timed.append(((scan.kind, name), terms, e0, e1))
                 scan.chunk_step(t0, nt, timer=timer)
 
-    if args.copy_calibration:
-        src = torch.arange(16 * 1024 * 1024, dtype=torch.int32, device=dev)       # 64 MiB read + 64 MiB written
-        dst = torch.empty_like(src)
-        for _ in range(5):
-            torch.add(src, 1, out=dst)                                             # one elementwise kernel per call
-        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()

@@ -71,6 +71,7 @@ from . import formats as fm
 from .rounding import to_fp32, to_fp16, floor_log2, RNE, RZ
 
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
+C_EXACT = 4        # Algorithm "E-FDPA": nothing is aligned or cut: the exact sum of the L products and c, converted once
 ALIGN_RZ = 0
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
 FAMILY_FDPA, FAMILY_FTZ_ADDMUL = 0, 1      # FAMILY_FTZ_ADDMUL: oracle/addmul.py, with P = group_len
@@ -291,6 +292,9 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None, tc=fm.FP32):
         else:
             S = _rd_frac(T * Fraction(2) ** (e_max - E), F2) + sc_al
         V = S * Fraction(2) ** E
+    elif p.c_mode == C_EXACT:
+        # Algorithm "E-FDPA": d = rho(c + sum a_k b_k), the sum exact
+        V = sum((s[k] * Fraction(2) ** e[k] for k in range(L)), Fraction(0)) + dc.value
     else:
         raise ValueError(p.c_mode)
 

@@ -12,7 +12,7 @@ LIB_PATH = os.path.join(_PKG, "libmmaemu.so")
 E4M3, E5M2, FP16, BF16, FP32, E8M0 = 0, 1, 2, 3, 4, 5
 E2M3, E3M2, E2M1 = 6, 7, 8                      # FP6 and FP4 operands, one code per byte
 TF32 = 9                                        # binary32 words whose low 13 mantissa bits are ignored
-C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD = 0, 1, 2, 3
+C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD, C_EXACT = 0, 1, 2, 3, 4
 RNE, RZ = 0, 1
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
 FAMILY_FDPA, FAMILY_FTZ_ADDMUL, FAMILY_GST_FDPA, FAMILY_FMA = 0, 1, 2, 3

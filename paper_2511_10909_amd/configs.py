@@ -185,8 +185,9 @@ class _Sampler:
 
 
 def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk=False, fused=True, sample_tiles=None,
-            first_tile=0):
-    """Tiles first_tile .. first_tile + n_tiles - 1 of the stream.  `fused`: the three variants share one pass over each chunk (mmaemu_emulate_compare_many, the no-flush variant's
+            first_tile=0, timer=None, time_every=64):
+    """Tiles first_tile .. first_tile + n_tiles - 1 of the stream.  `timer`, if given, is called as timer(name, terms, fn)
+    around the emulation launches of every `time_every`-th chunk (it must run fn).  `fused`: the three variants share one pass over each chunk (mmaemu_emulate_compare_many, the no-flush variant's
     outputs as the reference, D never written); otherwise one emulation and one comparison per variant.
     `keep_first_chunk` / `sample_tiles`: operands and all three outputs of the first chunk / of the given tiles are
     kept (those chunks also write D) and returned under "dev" / "samples"."""
@@ -205,8 +206,9 @@ def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk
 
     def run():
         kern = None
-        for t0 in range(first_tile, first_tile + n_tiles, chunk):
+        for ci, t0 in enumerate(range(first_tile, first_tile + n_tiles, chunk)):
             nt = min(chunk, first_tile + n_tiles - t0)
+            run_ = (lambda name, terms, fn: fn()) if (timer is None or ci % time_every) else timer
             config4_generate(A, B, C, t0, nt, seed)
             local = sampler.in_chunk(t0, nt)
             keep = keep_first_chunk and t0 == first_tile
@@ -214,11 +216,12 @@ def config4(n_tiles=1 << 26, chunk=1 << 14, seed=0, dev="cuda", keep_first_chunk
             # ([variant][tile][m][n] for this chunk's tile count: the layout mmaemu_emulate_compare_many writes)
             dump = Dall.reshape(-1)[: nv * nt * m * n].view(nv, nt, m, n) if want_d else None
             if fused:
-                mm.emulate_compare_many(models, A, B, C, None, dump, m, n, k, nt, dt, stats, index_base=t0 * m * n)
+                run_("variants", nv * nt * m * n * k,
+                     lambda: mm.emulate_compare_many(models, A, B, C, None, dump, m, n, k, nt, dt, stats, index_base=t0 * m * n))
                 kern = mm.last_kernel()
             else:
                 for i, h in enumerate(models):
-                    mm.emulate_mma(h, A, B, C, dump[i], m, n, k, nt, dt)
+                    run_("variant %d" % i, nt * m * n * k, lambda: mm.emulate_mma(h, A, B, C, dump[i], m, n, k, nt, dt))
                 kern = mm.last_kernel()
                 for i in range(nv):
                     mm.compare(dump[i], dump[0], nt * m * n, stats[i * mm.STATS_BYTES:], index_base=t0 * m * n)

@@ -84,7 +84,7 @@ mmaemu_status mmaemu_model_create(const mmaemu_model_params *p, mmaemu_model **o
         set_error("model_create: struct_size %u, expected %zu", p->struct_size, sizeof(mmaemu_model_params));
         return MMAEMU_ERR_INVALID_ARG;
     }
-    if (p->c_mode > MMAEMU_C_AFTER_RD_EVEN_ODD || p->out_round > MMAEMU_ROUND_RZ || p->ftz_in > 1 || p->ftz_out > 1) {
+    if (p->c_mode > MMAEMU_C_EXACT || p->out_round > MMAEMU_ROUND_RZ || p->ftz_in > 1 || p->ftz_out > 1) {
         set_error("model_create: enum field out of range");
         return MMAEMU_ERR_INVALID_ARG;
     }
@@ -283,6 +283,10 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     if ((((uintptr_t)A | (uintptr_t)B) & ab_mask) || (((uintptr_t)C | (uintptr_t)D) & (acc16 ? 1u : 3u))) {
         set_error("emulate_mma: pointers must be aligned to their element size");
         return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (mp.family == MMAEMU_FAMILY_FDPA && mp.c_mode == MMAEMU_C_EXACT && (SA || acc16)) {
+        set_error("emulate_mma: C_EXACT (E-FDPA) takes unscaled operands and FP32 accumulators");
+        return MMAEMU_ERR_UNSUPPORTED;
     }
     if (SA && mp.family == MMAEMU_FAMILY_FTZ_ADDMUL) { set_error("emulate_mma_scaled: block scales belong to the FDPA families"); return MMAEMU_ERR_UNSUPPORTED; }
     if (mp.family == MMAEMU_FAMILY_GST_FDPA) {

@@ -12,7 +12,9 @@
 
 namespace mmaemu {
 
-template <int TA, int TB>
+// EXACT: Algorithm "E-FDPA" (its 640-bit accumulator sits in private memory, so it gets instantiations of its own and the
+// other modes stay free of scratch memory)
+template <int TA, int TB, bool EXACT>
 __global__ void __launch_bounds__(256)
 emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A,
                        const typename Fmt<TB>::elem *__restrict__ B, const uint32_t *C, uint32_t *D,
@@ -38,7 +40,7 @@ emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A
         }
         for (uint32_t k0 = 0; k0 < k; k0 += p.L) {
             sr.k0 = k0;
-            d = fdpa_group(p, StaticFmt<TA>{}, StaticFmt<TB>{}, a + k0, b + k0, p.L, d, sr);
+            d = fdpa_group<EXACT>(p, StaticFmt<TA>{}, StaticFmt<TB>{}, a + k0, b + k0, p.L, d, sr);
         }
         if (acc16) reinterpret_cast<uint16_t *>(D)[o] = (uint16_t)((d & 0x7FFFFFFFu) > 0x7F800000u ? p.nan16 : float_bits_to_half_bits(d));
         else D[o] = d;
@@ -53,11 +55,16 @@ static mmaemu_status launch_t(const ModelArgs &p, const void *A, const void *B, 
     const uint64_t total = batch * m * n;
     uint64_t blocks = (total + 255) / 256;
     if (blocks > (1ull << 22)) blocks = 1ull << 22;     // grid-stride beyond that
-    hipLaunchKernelGGL((emulate_generic_kernel<TA, TB>), dim3((uint32_t)blocks), dim3(256), 0, s, p,
-                       (const typename Fmt<TA>::elem *)A, (const typename Fmt<TB>::elem *)B,
-                       (const uint32_t *)C, (uint32_t *)D, m, n, k, total, SA, SB, block);
+    if (p.c_mode == MMAEMU_C_EXACT)
+        hipLaunchKernelGGL((emulate_generic_kernel<TA, TB, true>), dim3((uint32_t)blocks), dim3(256), 0, s, p,
+                           (const typename Fmt<TA>::elem *)A, (const typename Fmt<TB>::elem *)B,
+                           (const uint32_t *)C, (uint32_t *)D, m, n, k, total, SA, SB, block);
+    else
+        hipLaunchKernelGGL((emulate_generic_kernel<TA, TB, false>), dim3((uint32_t)blocks), dim3(256), 0, s, p,
+                           (const typename Fmt<TA>::elem *)A, (const typename Fmt<TB>::elem *)B,
+                           (const uint32_t *)C, (uint32_t *)D, m, n, k, total, SA, SB, block);
     MMAEMU_HIP(hipGetLastError());
-    set_last_kernel(SA ? "general, block-scaled" : "general");
+    set_last_kernel(p.c_mode == MMAEMU_C_EXACT ? "general, exact sum" : (SA ? "general, block-scaled" : "general"));
     return MMAEMU_OK;
 }
 

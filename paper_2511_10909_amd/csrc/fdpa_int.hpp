@@ -230,7 +230,89 @@ __device__ __forceinline__ uint32_t finish_group(const ModelArgs &p, uint32_t d)
     return d;
 }
 
+// ---- Algorithm "E-FDPA": the exact sum ----------------------------------------------------------------------
+// A fixed-point number of XL 32-bit limbs, two's complement, bit 0 of limb 0 weighing 2^XBASE.  The lowest bit any
+// term can have is 2^-298 (two binary32 subnormals multiplied), the largest product is below 2^256, and 2^20 of those
+// add 20 bits: 640 bits hold every sum with its sign.
+constexpr int XL = 20;
+constexpr int XBASE = -320;
+
+// w += (-1)^neg * mag * 2^lsb, mag below 2^48
+__device__ __forceinline__ void wide_add(uint32_t (&w)[XL], uint64_t mag, int lsb, uint32_t neg)
+{
+    if (mag == 0) return;
+    const int pos = lsb - XBASE, first = pos >> 5;
+    const u128 v = (u128)mag << (pos & 31);                       // below 2^79: three limbs
+    uint32_t part[3] = {(uint32_t)v, (uint32_t)(v >> 32), (uint32_t)(v >> 64)};
+    uint32_t carry = 0;                                           // carry of the addition, or borrow of the subtraction
+    for (int i = first; i < XL; ++i) {
+        const uint32_t x = (i - first) < 3 ? part[i - first] : 0u;
+        if (i - first >= 3 && !carry) break;
+        const uint64_t old = w[i];
+        if (!neg) {
+            const uint64_t t = old + x + carry;
+            w[i] = (uint32_t)t;
+            carry = (uint32_t)(t >> 32);
+        } else {
+            const uint64_t t = old - x - carry;
+            w[i] = (uint32_t)t;
+            carry = (uint32_t)((t >> 32) & 1u);
+        }
+    }
+}
+
+// rho of the number held in w (consumed: it is negated in place when negative)
+__device__ __forceinline__ uint32_t wide_round(uint32_t (&w)[XL], uint32_t mode)
+{
+    const uint32_t neg = w[XL - 1] >> 31;
+    if (neg) {                                                    // magnitude: two's complement negation
+        uint32_t carry = 1;
+        for (int i = 0; i < XL; ++i) {
+            const uint64_t t = (uint64_t)(~w[i]) + carry;
+            w[i] = (uint32_t)t;
+            carry = (uint32_t)(t >> 32);
+        }
+    }
+    int top = XL - 1;
+    while (top >= 0 && w[top] == 0) --top;
+    if (top < 0) return 0u;                                       // an exact zero is +0.0
+    // the 64 bits from the leading bit downward, and whether anything lies below them
+    const int lead = 31 - __builtin_clz(w[top]);                  // bit index inside limb `top`
+    const int hi_bit = 32 * top + lead;                           // index of the leading bit in the whole number
+    uint64_t mag = 0;
+    uint32_t sticky = 0;
+    const int low_bit = hi_bit - 63;                              // index of the lowest bit taken (may be negative: then exact)
+    if (low_bit <= 0) {
+        // at most 64 bits in all: limbs 0 and 1 (and 2 cannot be non-zero here unless hi_bit >= 64)
+        mag = ((uint64_t)w[1] << 32) | w[0];
+        return round_to_fp32(neg, mag, XBASE, 0, mode);
+    }
+    const int l0 = low_bit >> 5, sh = low_bit & 31;               // the window starts inside limb l0
+    const uint32_t a0 = w[l0], a1 = w[l0 + 1], a2 = (l0 + 2 < XL) ? w[l0 + 2] : 0u;
+    const u128 win = ((u128)a2 << 64) | ((u128)a1 << 32) | a0;
+    mag = (uint64_t)(win >> sh);
+    if (sh && (a0 & ((1u << sh) - 1u))) sticky = 1;
+    for (int i = 0; i < l0; ++i) sticky |= (w[i] != 0);
+    return round_to_fp32(neg, mag, XBASE + low_bit, sticky, mode);
+}
+
 template <class FTA, class FTB>
+__device__ uint32_t exact_group(const ModelArgs &p, const FTA &fa, const FTB &fb, const void *a, const void *b, uint32_t L, const Dec &dc)
+{
+    uint32_t w[XL];
+    for (int i = 0; i < XL; ++i) w[i] = 0;
+    const int FA = fa.mb(), FB = fb.mb();
+    for (uint32_t k = 0; k < L; ++k) {
+        const Dec x = decode_as(fa, fa.load(a, k), p.ftz_in), y = decode_as(fb, fb.load(b, k), p.ftz_in);
+        wide_add(w, sig_product(fa, fb, x, y), x.exp + y.exp - FA - FB, x.sign ^ y.sign);
+    }
+    wide_add(w, dc.sig, dc.exp - 23, dc.sign);
+    return wide_round(w, p.out_round);
+}
+
+// WITH_EXACT: the exact mode is compiled in (the general kernel only: its wide accumulator lives in private memory, which
+// the tiled kernels' fall-back must not drag into every tiled kernel)
+template <bool WITH_EXACT = false, class FTA, class FTB>
 __device__ uint32_t fdpa_group(const ModelArgs &p, const FTA &fa, const FTB &fb, const void *a, const void *b, uint32_t L,
                                uint32_t c, const ScaleRef &sr)
 {
@@ -276,6 +358,10 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const FTA &fa, const FTB &fb,
     if (any_nan || (pinf && ninf)) return p.nan_bits;
     if (pinf) return 0x7F800000u;
     if (ninf) return 0xFF800000u;
+
+    if constexpr (WITH_EXACT) {
+        if (p.c_mode == MMAEMU_C_EXACT) return finish_group(p, exact_group(p, fa, fb, a, b, L, dc));
+    }
 
     if (p.c_mode == MMAEMU_C_AFTER_RD) {
         if (p.split == MMAEMU_SPLIT_NONE) {

@@ -1,0 +1,92 @@
+"""GPU parity of c_mode = C_EXACT (Algorithm "E-FDPA": exact sum of the group's products and the accumulator, one
+conversion) against the rational-arithmetic oracle, bit for bit: every operand type, whole exponent ranges (BF16 and
+FP32 sums span more than 500 binary places), special values, chained groups, both conversions and both flushes."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+from oracle import formats as fm
+from oracle.fdpa import ModelParams, C_EXACT
+from oracle.rounding import RNE, RZ
+from paper_2511_10909_amd import synth
+from helpers import f32_bits, fp16_bits, bf16_bits
+from o1_jobs import run_pool
+from test_gpu_parity import mm, gpu_emulate, assert_same  # noqa: F401
+
+PAIRS = [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, fm.E5M2), (fm.TF32, fm.TF32), (fm.FP32, fm.FP32),
+         (fm.E2M3, fm.E2M1), (fm.FP16, fm.BF16), (fm.E3M2, fm.E4M3)]
+
+
+def test_exact_mode_matches_the_rational_oracle(mm):
+    rng = np.random.default_rng(4242)
+    gpu, jobs, names = [], [], []
+    for idx, (ta, tb) in enumerate(PAIRS):
+        for variant in range(3):
+            L = [4, 2, 16][variant]
+            k = L * (1 + (idx + variant) % 3)
+            p = ModelParams(group_len=L if variant != 2 else 0, c_mode=C_EXACT, out_round=RZ if variant == 1 else RNE,
+                            ftz_in=variant == 1, ftz_out=variant == 2, nan_bits=0x7FFFFFFF if variant == 0 else 0x7FC00000)
+            if variant == 2:
+                k = 16
+            nb, m, n = 2, 17, 13
+            A = synth.random_bits(rng, (nb, m, k), ta)             # whole exponent range of the type
+            B = synth.random_bits(rng, (nb, n, k), tb)
+            if variant == 0:                                        # near-cancelling sums: pairs of equal magnitude, opposite sign
+                A[:, :, 1::2] = A[:, :, 0::2] ^ (1 << (synth.WIDTH[ta] - 1) if ta not in (fm.TF32, fm.FP32) else 1 << 31)
+                B[:, :, 1::2] = B[:, :, 0::2]
+                B[:, ::3, 1] ^= 1                                   # ... up to a last place here and there
+            C = synth.random_bits(rng, (nb, m, n), fm.FP32) if variant else synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 1, 254)
+            if variant == 1:
+                A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[ta], 0.02)
+                C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32], 0.03)
+            got = gpu_emulate(mm, p, A, B, C, ta, tb)
+            assert gpu_emulate.last_kernel == "general, exact sum", gpu_emulate.last_kernel
+            gpu.append(got)
+            jobs.append((dataclasses.asdict(p), A, B, C, ta, tb, None, None, 0))
+            names.append("types %d x %d, variant %d" % (ta, tb, variant))
+    want = run_pool(jobs, workers=12)
+    bad = []
+    for name, g, w in zip(names, gpu, want):
+        if not np.array_equal(g, w):
+            i = tuple(np.argwhere(g != w)[0])
+            bad.append("%s: %d of %d differ, first at %s: gpu %08x, oracle %08x" % (name, int((g != w).sum()), g.size, i, int(g[i]), int(w[i])))
+    assert not bad, "\n".join(bad)
+    assert sum(g.size for g in gpu) > 10000
+
+
+def test_worked_example_and_limits_on_the_gpu(mm):
+    a = [-2.0 ** 13, -0.5, -0.25, -0.125] + [0.0] * 12
+    b = [2.0 ** 10, 1.0, 1.0, 1.0] + [0.0] * 12
+    C = np.array([[[f32_bits(2.0 ** 23)]]], dtype=np.uint32)
+    for enc, t, L in ((fp16_bits, fm.FP16, 4), (bf16_bits, fm.BF16, 2)):
+        A = np.array([[[enc(x) for x in a]]], dtype=np.uint16)
+        B = np.array([[[enc(x) for x in b]]], dtype=np.uint16)
+        got = gpu_emulate(mm, ModelParams(group_len=L, c_mode=C_EXACT), A, B, C, t, t)
+        assert int(got[0, 0, 0]) == f32_bits(-0.875)               # Sec. 5: the CDNA1 entries of the table
+    # the extremes of the 640-bit accumulator: the largest and the smallest FP32 products in one group
+    big, tiny = 0x7F7FFFFF, 0x00000001
+    A = np.array([[[big, tiny, big, 0x80000001]]], dtype=np.uint32)
+    B = np.array([[[big, tiny, 0xFF7FFFFF, tiny]]], dtype=np.uint32)
+    Cz = np.zeros((1, 1, 1), dtype=np.uint32)
+    got = gpu_emulate(mm, ModelParams(group_len=4, c_mode=C_EXACT), A, B, Cz, fm.FP32, fm.FP32)
+    assert int(got[0, 0, 0]) == 0                                   # everything cancels exactly: +0.0
+    got = gpu_emulate(mm, ModelParams(group_len=2, c_mode=C_EXACT), A[:, :, :2], B[:, :, :2], Cz, fm.FP32, fm.FP32)
+    assert int(got[0, 0, 0]) == 0x7F800000                          # max * max overflows in the conversion
+
+
+def test_exact_mode_argument_checks(mm):
+    import torch
+    z = torch.zeros(64, dtype=torch.int32, device="cuda")
+    h = mm.model_create(group_len=4, c_mode=mm.C_EXACT)
+    with pytest.raises(mm.MmaemuError) as ei:
+        mm.emulate_mma(h, z, z, z, z, 1, 1, 4, 1, (mm.FP16, mm.FP16, mm.FP16, mm.FP16))
+    assert ei.value.status == 2
+    with pytest.raises(mm.MmaemuError) as ei:
+        mm.emulate_mma_scaled(h, z, z, z, z, z, z, 4, 1, 1, 4, 1, (mm.E4M3, mm.E4M3, mm.FP32, mm.FP32))
+    assert ei.value.status == 2
+    mm.model_destroy(h)
+    with pytest.raises(mm.MmaemuError):
+        mm.model_create(group_len=4, c_mode=mm.C_EXACT, frac_bits2=31)
