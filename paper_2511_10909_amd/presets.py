@@ -39,8 +39,8 @@ PAPER = {
     ("blackwell", "bf16"): _t(16, 25, mm.RZ),
     ("blackwell", "fp16"): _t(16, 25, mm.RZ),
     ("blackwell", "fp8"): _t(32, 25, mm.RZ),
-    ("cdna1", "bf16"): dict(group_len=2, frac_bits=40, out_round=mm.RNE, c_mode=mm.C_IN_GROUP),     # E-FDPA up to 40 bits
-    ("cdna1", "fp16"): dict(group_len=4, frac_bits=40, out_round=mm.RNE, c_mode=mm.C_IN_GROUP),
+    ("cdna1", "bf16"): dict(group_len=2, out_round=mm.RNE, c_mode=mm.C_EXACT),     # E-FDPA: exact sum, one conversion
+    ("cdna1", "fp16"): dict(group_len=4, out_round=mm.RNE, c_mode=mm.C_EXACT),
     ("cdna2", "bf16"): dict(group_len=2, family=mm.FAMILY_FTZ_ADDMUL),
     ("cdna2", "bf16_1k"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),
     ("cdna2", "fp16"): dict(group_len=4, family=mm.FAMILY_FTZ_ADDMUL),

@@ -66,6 +66,9 @@ def test_worked_example_and_limits_on_the_gpu(mm):
         B = np.array([[[enc(x) for x in b]]], dtype=np.uint16)
         got = gpu_emulate(mm, ModelParams(group_len=L, c_mode=C_EXACT), A, B, C, t, t)
         assert int(got[0, 0, 0]) == f32_bits(-0.875)               # Sec. 5: the CDNA1 entries of the table
+        from paper_2511_10909_amd import presets
+        kw = presets.PAPER[("cdna1", "fp16" if t == fm.FP16 else "bf16")]
+        assert kw["c_mode"] == mm.C_EXACT and kw["group_len"] == L
     # the extremes of the 640-bit accumulator: the largest and the smallest FP32 products in one group
     big, tiny = 0x7F7FFFFF, 0x00000001
     A = np.array([[[big, tiny, big, 0x80000001]]], dtype=np.uint32)
