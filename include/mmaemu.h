@@ -203,6 +203,11 @@ typedef struct {
                                         else nan_bits (infinities of both signs).  With group_len = 1 this is a chain
                                         of fused multiply-adds that pass payloads on, which is what the FP32 MFMA
                                         instructions of gfx950 do (they generate 0xFFC00000). */
+    uint32_t rd_toward_zero;         /* 0 / 1; C_AFTER_RD modes only.  1: every round-down of the summation's second step
+                                        (the product sum at F2 bits, the accumulator at F bits, the merges of a split
+                                        group) truncates toward zero instead: the hypothetical instruction of Sec. 6.2.4
+                                        whose deviation from the real result is symmetric, against which the bias of the
+                                        printed algorithms shows */
 } mmaemu_model_params;
 
 typedef struct mmaemu_model mmaemu_model; /* opaque, host memory, owned by the library */
@@ -338,7 +343,8 @@ mmaemu_status mmaemu_compare_many_classes(const mmaemu_model *const *models, uin
 enum { MMAEMU_GEN_ZERO = 0, MMAEMU_GEN_FINITE_BITS = 1, MMAEMU_GEN_UNIFORM_EXP = 2,
        MMAEMU_GEN_RANDOM_BITS = 3, MMAEMU_GEN_NORMAL = 4, MMAEMU_GEN_UNIFORM = 5,
        MMAEMU_GEN_NORMAL_OUTLIERS = 6, MMAEMU_GEN_CANCELLING = 7, MMAEMU_GEN_SIGNED_ZEROS = 8 };
-enum { MMAEMU_SCALE_NONE = 0, MMAEMU_SCALE_TENSOR = 1, MMAEMU_SCALE_TILE = 2 };
+enum { MMAEMU_SCALE_NONE = 0, MMAEMU_SCALE_TENSOR = 1, MMAEMU_SCALE_TILE = 2,
+       MMAEMU_SCALE_FACTOR = 3 /* every value times scale_target itself (Sec. 6.2.4 draws operands from 1000 x N(0,1)) */ };
 
 typedef struct {
     uint32_t struct_size;
@@ -462,6 +468,36 @@ mmaemu_status mmaemu_err_stats_reset(mmaemu_err_stats *dev_err, void *hip_stream
 mmaemu_status mmaemu_exact_dot_sample(const void *A, const void *B, const void *D, uint32_t m,
                                       uint32_t n, uint32_t k, mmaemu_dtypes dtypes, uint64_t stride,
                                       mmaemu_err_stats *dev_err, void *hip_stream);
+
+/*
+ * Distribution of the deviation of a model's (or an instruction's) outputs from the real result (Sec. 6.2.4: the
+ * round-down modes of Algorithms "TR-FDPA" / "GTR-FDPA" shift it toward the negative side; with rd_toward_zero it is
+ * symmetric).  For `batch` tiles A[batch][m][k], B[batch][n][k], C[batch][m][n] (FP32; NULL means zero) and
+ * D[batch][m][n] (FP32), every output whose flattened index (over the whole batch) is a multiple of `stride` is
+ * sampled: delta = D - (c + sum_k a_k b_k), the bracket taken exactly (a wide fixed-point sum: delta itself is exact).
+ *   n_samples                      samples with finite operands, accumulator and output
+ *   n_skipped                      the others (not counted anywhere else)
+ *   n_negative / n_zero / n_positive   sign of delta
+ *   bins[i]                        delta in [(i - 32) w, (i - 31) w) with w = 2^bin_exp; bins 0 and 63 also take
+ *                                  everything below / above the range
+ *   sum, sum_abs, sum_sq           of delta, |delta|, delta^2 in binary64 (each delta rounded once; accumulation order
+ *                                  unspecified)
+ * Accumulates into *dev_hist (device memory, 8-byte aligned; mmaemu_deviation_hist_reset clears it).  Operands of at
+ * most 16 bits (FP8, FP6, FP4, FP16, BF16).
+ * Errors: INVALID_ARG (NULL, alignment, bin_exp outside -280 .. 250), SHAPE (zero sizes, k > 2^20, stride 0, more than
+ * 2^44 samples), UNSUPPORTED (types).
+ */
+#define MMAEMU_DEVIATION_BINS 64
+typedef struct {
+    uint64_t n_samples, n_skipped, n_negative, n_zero, n_positive;
+    uint64_t bins[MMAEMU_DEVIATION_BINS];
+    double sum, sum_abs, sum_sq;
+} mmaemu_deviation_hist;
+
+mmaemu_status mmaemu_deviation_hist_reset(mmaemu_deviation_hist *dev_hist, void *hip_stream);
+mmaemu_status mmaemu_deviation_sample(const void *A, const void *B, const void *C, const void *D, uint32_t m, uint32_t n,
+                                      uint32_t k, uint64_t batch, mmaemu_dtypes dtypes, uint64_t stride, int32_t bin_exp,
+                                      mmaemu_deviation_hist *dev_hist, void *hip_stream);
 
 /*
  * Issue-rate probes: the measured counterpart of the vector-ALU peak that the emulation kernels' roofline is quoted

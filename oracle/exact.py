@@ -79,3 +79,47 @@ def error_stats(A, B, D, ta, tb, stride, stats=None, indices=None):
     st["sum_rel_err"] += float(sums["rel"])
     st["sum_signed_err"] += float(sums["sgn"])
     return st
+
+
+DEVIATION_BINS = 64
+
+
+def empty_deviation_hist():
+    return dict(n_samples=0, n_skipped=0, n_negative=0, n_zero=0, n_positive=0, bins=[0] * DEVIATION_BINS,
+                sum=0.0, sum_abs=0.0, sum_sq=0.0)
+
+
+def deviation_hist(A, B, C, D, ta, tb, stride, bin_exp, hist=None):
+    """Sec. 6.2.4: distribution of delta = D - D_real over sampled outputs, D_real = c + sum_k a_k b_k as an exact
+    rational.  A[batch][m][k], B[batch][n][k], C (None: zero) and D[batch][m][n] FP32 bits; the flattened index over
+    the whole batch is sampled when it is a multiple of `stride`.  Bin i holds delta in [(i - 32) w, (i - 31) w),
+    w = 2^bin_exp; the outermost bins take everything beyond.  Samples with a NaN or an infinity anywhere are skipped."""
+    h = empty_deviation_hist() if hist is None else hist
+    A = np.asarray(A); B = np.asarray(B); D = np.asarray(D, dtype=np.uint32)
+    nb, m, n = D.shape
+    w = Fraction(2) ** bin_exp
+    s1 = s2 = s3 = Fraction(0)
+    for idx in range(0, nb * m * n, stride):
+        t, rem = divmod(idx, m * n)
+        i, j = divmod(rem, n)
+        da = [fm.decode(int(x), ta) for x in A[t, i].tolist()]
+        db = [fm.decode(int(x), tb) for x in B[t, j].tolist()]
+        dc = fm.decode(int(C[t, i, j]) if C is not None else 0, fm.FP32)
+        dd = fm.decode(int(D[t, i, j]), fm.FP32)
+        if not (all(x.finite for x in da) and all(x.finite for x in db) and dc.finite and dd.finite):
+            h["n_skipped"] += 1
+            continue
+        real = dc.value + sum((x.value * y.value for x, y in zip(da, db)), Fraction(0))
+        delta = dd.value - real
+        h["n_samples"] += 1
+        h["n_negative" if delta < 0 else ("n_zero" if delta == 0 else "n_positive")] += 1
+        q = delta / w
+        fi = q.numerator // q.denominator                       # floor
+        h["bins"][min(max(fi + DEVIATION_BINS // 2, 0), DEVIATION_BINS - 1)] += 1
+        s1 += delta
+        s2 += abs(delta)
+        s3 += delta * delta
+    h["sum"] += float(s1)
+    h["sum_abs"] += float(s2)
+    h["sum_sq"] += float(s3)
+    return h

@@ -102,6 +102,7 @@ class ModelParams:
     wide_products: bool = False
     family: int = FAMILY_FDPA
     nan_propagate: bool = False  # FP32 operands only: a NaN result carries an operand's payload (see _specials)
+    rd_toward_zero: bool = False  # C_AFTER_RD only: Sec. 6.2.4's hypothetical TR-FDPA', every RD of the summation replaced by RZ
 
     def with_(self, **kw):
         return replace(self, **kw)
@@ -246,6 +247,7 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None, tc=fm.FP32):
         F2 = p.frac_bits2
         F_m = p.frac_bits_merge or F
         F_c = p.frac_bits_acc or F
+        rd = _rz_frac if p.rd_toward_zero else _rd_frac        # (Sec. 6.2.4: the hypothetical variant truncates instead)
         if p.split == SPLIT_NONE:
             parts = [range(L)]
         else:
@@ -273,13 +275,13 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None, tc=fm.FP32):
             e_max, T = sums[0]
         else:
             e_max = max(e_part for e_part, _ in sums)
-            T = sum((_rd_frac(T_part * Fraction(2) ** (e_part - e_max), F_m) for e_part, T_part in sums), Fraction(0))
+            T = sum((rd(T_part * Fraction(2) ** (e_part - e_max), F_m) for e_part, T_part in sums), Fraction(0))
         # rounded sum with the accumulator
         # (the accumulator always takes part, a zero one with the exponent of the subnormals, -126)
         E = max(([e_max] if e_max is not None else []) + [dc.exp])
         if e_max is None:
             e_max = E
-        sc_al = _rd_frac(dc.signed_sig * Fraction(2) ** (dc.exp - E), F_c)
+        sc_al = rd(dc.signed_sig * Fraction(2) ** (dc.exp - E), F_c)
         if p.acc_special_truncation and dc.exp < E - F_c - 1:
             sc_al = Fraction(0)                                   # special truncation
         if p.sum_drop_distance and E - e_max >= p.sum_drop_distance:
@@ -288,9 +290,9 @@ def fdpa_group(p, a_bits, b_bits, c_bits, ta, tb, scale_exp=None, tc=fm.FP32):
             S = T * Fraction(2) ** (e_max - E) + sc_al
             if S != 0:
                 lead = max(floor_log2(abs(S)), -126 - E)          # S counts units of 2^E; binary32's smallest normal exponent
-                S = _rd_frac(S * Fraction(2) ** (-lead), F2) * Fraction(2) ** lead
+                S = rd(S * Fraction(2) ** (-lead), F2) * Fraction(2) ** lead
         else:
-            S = _rd_frac(T * Fraction(2) ** (e_max - E), F2) + sc_al
+            S = rd(T * Fraction(2) ** (e_max - E), F2) + sc_al
         V = S * Fraction(2) ** E
     elif p.c_mode == C_EXACT:
         # Algorithm "E-FDPA": d = rho(c + sum a_k b_k), the sum exact

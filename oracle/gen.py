@@ -58,7 +58,7 @@ from .philox import philox4x32_10
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
 GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING, GEN_SIGNED_ZEROS = 5, 6, 7, 8
 VALUE_FAMILIES = (GEN_NORMAL, GEN_UNIFORM, GEN_NORMAL_OUTLIERS)
-SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
+SCALE_NONE, SCALE_TENSOR, SCALE_TILE, SCALE_FACTOR = 0, 1, 2, 3
 
 
 @dataclass(frozen=True)
@@ -260,6 +260,8 @@ def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
             z = z * (np.float64(gp.scale_target) / np.abs(z).max())
         elif gp.scale_scope == SCALE_TILE:
             z = z * (np.float64(gp.scale_target) / np.abs(z).max(axis=1, keepdims=True))
+        elif gp.scale_scope == SCALE_FACTOR:
+            z = z * np.float64(gp.scale_target)
         b32 = z.astype(np.float32).view(np.uint32).ravel()
         step = 1 << 18
         out = np.concatenate([cast_from_fp32(b32[i:i + step], fmt_id) for i in range(0, b32.size, step)])

@@ -23,7 +23,7 @@ class O2Params(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint32) for n in
                 ("group_len", "frac_bits", "align_round", "c_mode", "out_round", "ftz_in", "ftz_out", "nan_bits", "frac_bits2", "split", "acc_special_truncation",
                  "frac_bits_merge", "frac_bits_acc", "skip_zero_terms", "f2_at_leading_bit", "zero_result_positive",
-                 "sum_drop_distance", "family", "out_mant_bits", "wide_products", "acc_fp16", "nan_propagate")]
+                 "sum_drop_distance", "family", "out_mant_bits", "wide_products", "acc_fp16", "nan_propagate", "rd_toward_zero")]
 
 
 def _load():
@@ -39,7 +39,7 @@ def _params(p, tc=fm.FP32):
                     int(p.ftz_in), int(p.ftz_out), p.nan_bits, p.frac_bits2, p.split, int(p.acc_special_truncation),
                     p.frac_bits_merge, p.frac_bits_acc, int(p.skip_zero_terms), int(p.f2_at_leading_bit),
                     int(p.zero_result_positive), p.sum_drop_distance, p.family, p.out_mant_bits, int(p.wide_products),
-                    1 if tc == fm.FP16 else 0, int(p.nan_propagate))
+                    1 if tc == fm.FP16 else 0, int(p.nan_propagate), int(p.rd_toward_zero))
 
 
 _NP = {fm.E4M3: np.uint8, fm.E5M2: np.uint8, fm.FP16: np.uint16, fm.BF16: np.uint16, fm.FP32: np.uint32,

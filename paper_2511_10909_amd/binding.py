@@ -19,7 +19,7 @@ FAMILY_FDPA, FAMILY_FTZ_ADDMUL, FAMILY_GST_FDPA, FAMILY_FMA = 0, 1, 2, 3
 SCALE_FORMAT_E8M0, SCALE_FORMAT_UE4M3 = 0, 1
 GEN_ZERO, GEN_FINITE_BITS, GEN_UNIFORM_EXP, GEN_RANDOM_BITS, GEN_NORMAL = 0, 1, 2, 3, 4
 GEN_UNIFORM, GEN_NORMAL_OUTLIERS, GEN_CANCELLING, GEN_SIGNED_ZEROS = 5, 6, 7, 8
-SCALE_NONE, SCALE_TENSOR, SCALE_TILE = 0, 1, 2
+SCALE_NONE, SCALE_TENSOR, SCALE_TILE, SCALE_FACTOR = 0, 1, 2, 3
 (MFMA_F32_16X16X16_F16, MFMA_F32_16X16X16_BF16, MFMA_F32_32X32X8_F16, MFMA_F32_32X32X8_BF16,
  MFMA_F32_16X16X32_F16, MFMA_F32_16X16X32_BF16, MFMA_F32_16X16X32_FP8_FP8, MFMA_F32_16X16X32_FP8_BF8,
  MFMA_F32_16X16X32_BF8_FP8, MFMA_F32_16X16X32_BF8_BF8) = range(10)
@@ -62,7 +62,7 @@ class ModelParams(ctypes.Structure):
                 ("struct_size", "group_len", "frac_bits", "align_round", "c_mode", "frac_bits2", "out_round",
                  "out_mant_bits", "ftz_in", "ftz_out", "nan_bits", "split", "acc_special_truncation",
                  "frac_bits_merge", "frac_bits_acc", "f2_at_leading_bit", "skip_zero_terms", "zero_result_positive",
-                 "sum_drop_distance", "family", "wide_products", "gst_group", "scale_format", "nan_propagate")]
+                 "sum_drop_distance", "family", "wide_products", "gst_group", "scale_format", "nan_propagate", "rd_toward_zero")]
 
 
 class Dtypes(ctypes.Structure):
@@ -88,8 +88,18 @@ class ErrStats(ctypes.Structure):
                 ("max_rel_err", ctypes.c_double), ("sum_signed_err", ctypes.c_double)]
 
 
+DEVIATION_BINS = 64
+
+
+class DeviationHist(ctypes.Structure):
+    _fields_ = [("n_samples", ctypes.c_uint64), ("n_skipped", ctypes.c_uint64), ("n_negative", ctypes.c_uint64),
+                ("n_zero", ctypes.c_uint64), ("n_positive", ctypes.c_uint64), ("bins", ctypes.c_uint64 * DEVIATION_BINS),
+                ("sum", ctypes.c_double), ("sum_abs", ctypes.c_double), ("sum_sq", ctypes.c_double)]
+
+
 STATS_BYTES = ctypes.sizeof(Stats)
 ERR_STATS_BYTES = ctypes.sizeof(ErrStats)
+DEVIATION_HIST_BYTES = ctypes.sizeof(DeviationHist)
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("libmmaemu.so is not built (%s); run `python -m paper_2511_10909_amd.build` or "
@@ -126,6 +136,8 @@ _lib.mmaemu_issue_probe_name.argtypes = [_u32]
 _lib.mmaemu_issue_probe.argtypes = [_u32, _u32, _u32, _vp, _vp]
 _lib.mmaemu_err_stats_reset.argtypes = [_vp, _vp]
 _lib.mmaemu_exact_dot_sample.argtypes = [_vp, _vp, _vp, _u32, _u32, _u32, Dtypes, _u64, _vp, _vp]
+_lib.mmaemu_deviation_hist_reset.argtypes = [_vp, _vp]
+_lib.mmaemu_deviation_sample.argtypes = [_vp, _vp, _vp, _vp, _u32, _u32, _u32, _u64, Dtypes, _u64, ctypes.c_int32, _vp, _vp]
 
 
 def _status_string(s):
@@ -171,12 +183,12 @@ def model_create(group_len=0, frac_bits=24, c_mode=C_IN_GROUP, out_round=RNE, ft
                  nan_bits=0x7FC00000, align_round=0, frac_bits2=0, out_mant_bits=23, struct_size=None,
                  split=SPLIT_NONE, acc_special_truncation=False, frac_bits_merge=0, frac_bits_acc=0,
                  f2_at_leading_bit=False, skip_zero_terms=False, zero_result_positive=False, sum_drop_distance=0,
-                 family=FAMILY_FDPA, wide_products=False, gst_group=0, scale_format=0, nan_propagate=False):
+                 family=FAMILY_FDPA, wide_products=False, gst_group=0, scale_format=0, nan_propagate=False, rd_toward_zero=False):
     p = ModelParams(ctypes.sizeof(ModelParams) if struct_size is None else struct_size, group_len, frac_bits,
                     align_round, c_mode, frac_bits2, out_round, out_mant_bits, int(ftz_in), int(ftz_out), nan_bits,
                     split, int(acc_special_truncation), frac_bits_merge, frac_bits_acc, int(f2_at_leading_bit),
                     int(skip_zero_terms), int(zero_result_positive), sum_drop_distance, family, int(wide_products), gst_group, scale_format,
-                    int(nan_propagate))
+                    int(nan_propagate), int(rd_toward_zero))
     h = _vp()
     _check(_lib.mmaemu_model_create(ctypes.byref(p), ctypes.byref(h)))
     return h
@@ -274,6 +286,16 @@ def exact_dot_sample(A, B, D, m, n, k, dtypes, stride, dev_err, stream=None):
     _check(_lib.mmaemu_exact_dot_sample(_ptr(A), _ptr(B), _ptr(D), m, n, k, dt, stride, _ptr(dev_err), _stream(stream)))
 
 
+def deviation_hist_reset(dev_hist, stream=None):
+    _check(_lib.mmaemu_deviation_hist_reset(_ptr(dev_hist), _stream(stream)))
+
+
+def deviation_sample(A, B, C, D, m, n, k, batch, dtypes, stride, bin_exp, dev_hist, stream=None):
+    dt = dtypes if isinstance(dtypes, Dtypes) else Dtypes(*dtypes)
+    _check(_lib.mmaemu_deviation_sample(_ptr(A), _ptr(B), _ptr(C) if C is not None else None, _ptr(D), m, n, k, batch, dt, stride,
+                                        bin_exp, _ptr(dev_hist), _stream(stream)))
+
+
 # ---- unpacking of the device-side result structs (host copies; no arithmetic) -----------
 
 def _unpack(struct_type, dev_tensor):
@@ -299,3 +321,7 @@ def read_stats_array(dev_stats, count):
 
 def read_err_stats(dev_err):
     return _unpack(ErrStats, dev_err)
+
+
+def read_deviation_hist(dev_hist):
+    return _unpack(DeviationHist, dev_hist)

@@ -370,6 +370,58 @@ def config5(n_tiles=1 << 24, chunk=1 << 16, seed=0, dev="cuda", kinds=("bf16", "
 # ---------------------------------------------------------------------------------------------
 # Randomised validation of a candidate model against the native instruction (paper Sec. 3, Step 4).
 
+def bias_experiment_generate(A, B, C, first_tile, n_tiles, seed=0):
+    """Sec. 6.2.4's inputs: A, B ~ 1000 x N(0,1) in FP16, C ~ N(0,1) in FP32, 32x32x8 tiles."""
+    mm.generate(A, mm.FP16, 32 * 8, first_tile, n_tiles, mm.GEN_NORMAL, seed=seed, operand=0, scale_scope=mm.SCALE_FACTOR, scale_target=1000.0)
+    mm.generate(B, mm.FP16, 32 * 8, first_tile, n_tiles, mm.GEN_NORMAL, seed=seed, operand=1, scale_scope=mm.SCALE_FACTOR, scale_target=1000.0)
+    mm.generate(C, mm.FP32, 32 * 32, first_tile, n_tiles, mm.GEN_NORMAL, seed=seed, operand=2)
+
+
+BIAS_BIN_EXP = -5        # bins of 1/32: outputs lie around 2^21 .. 2^23, one place of binary32 there is 1/4 .. 1/2
+
+
+def bias_experiment(n_tiles=1 << 20, chunk=1 << 14, seed=0, stride=1, dev="cuda", keep_first_chunk=False, with_mfma=True):
+    """The numerical-bias experiment of Sec. 6.2.4 as a device workload: the CDNA3 model of v_mfma_f32_32x32x8_f16
+    (Algorithm "TR-FDPA", L = 8, F = 24, F2 = 31, RNE-FP32) and the hypothetical variant whose round-downs truncate
+    toward zero instead, on the paper's inputs; per variant the distribution of delta = D - D_real with D_real exact
+    (mmaemu_deviation_sample on every stride-th output), plus the same for this GPU's own instruction."""
+    from . import presets
+    m, n, k = 32, 32, 8
+    dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
+    A, B = _buf((chunk, m, k), mm.FP16, dev), _buf((chunk, n, k), mm.FP16, dev)
+    C, D = _buf((chunk, m, n), mm.FP32, dev), _buf((chunk, m, n), mm.FP32, dev)
+    base = presets.PAPER[("cdna3", "fp16")]
+    variants = [("rd", mm.model_create(**base)), ("rz", mm.model_create(**dict(base, rd_toward_zero=True)))]
+    names = [v[0] for v in variants] + (["mfma"] if with_mfma else [])
+    hists = {name: torch.empty(mm.DEVIATION_HIST_BYTES, dtype=torch.uint8, device=dev) for name in names}
+    for h in hists.values():
+        mm.deviation_hist_reset(h)
+    kernels, first = {}, {}
+
+    def run():
+        for t0 in range(0, n_tiles, chunk):
+            nt = min(chunk, n_tiles - t0)
+            bias_experiment_generate(A, B, C, t0, nt, seed)
+            for name, h in variants:
+                mm.emulate_mma(h, A, B, C, D, m, n, k, nt, dt)
+                kernels[name] = mm.last_kernel()
+                mm.deviation_sample(A, B, C, D, m, n, k, nt, dt, stride, BIAS_BIN_EXP, hists[name])
+                if keep_first_chunk and t0 == 0:
+                    first[name] = D.clone()
+            if with_mfma:
+                mm.mfma_probe(mm.MFMA_F32_32X32X8_F16, A, B, C, D, k, nt)
+                mm.deviation_sample(A, B, C, D, m, n, k, nt, dt, stride, BIAS_BIN_EXP, hists["mfma"])
+            if keep_first_chunk and t0 == 0:
+                first.update(A=A.clone(), B=B.clone(), C=C.clone())
+
+    _, secs = _timed(run)
+    for _, h in variants:
+        mm.model_destroy(h)
+    out = dict(terms=len(variants) * n_tiles * m * n * k, seconds=secs, kernels=kernels,
+               hists={name: mm.read_deviation_hist(h) for name, h in hists.items()}, first=first)
+    return out
+
+
 def validation_families(ta, tb):
     """Input families of Step 4: common distributions, all finite bit patterns, all bit patterns (NaN and infinities
     included: the paper calls this one the most important), and exponent ranges chosen to put the accumulator above,
@@ -489,6 +541,7 @@ def _report(argv=None):
     ap.add_argument("--tiles5", type=int, default=1 << 24, help="tiles of workload 5 per operand type (as stated: 2^24)")
     ap.add_argument("--unfused", action="store_true", help="workloads 4 and 5 with one emulation and one comparison per model")
     ap.add_argument("--size3", type=int, default=4096, help="m = n = k of workload 3")
+    ap.add_argument("--tiles6", type=int, default=1 << 20, help="tiles of the bias experiment (Sec. 6.2.4)")
     args = ap.parse_args(argv)
     config1(n_tiles=256)                                  # (first call: library load and allocator warm-up)
 
@@ -512,6 +565,10 @@ def _report(argv=None):
     for kind, v in r.items():
         row("5 (%s): 16x16x16, %d tiles, 16 models against the native MFMA" % (kind, args.tiles5), v,
             "agreement %.4f .. %.4f" % (min(v["agreement"]), max(v["agreement"])))
+    r = bias_experiment(n_tiles=args.tiles6)
+    means = ", ".join("%s: mean delta %+.4f (%d below, %d above)" % (name, h["sum"] / max(h["n_samples"], 1), h["n_negative"], h["n_positive"])
+                      for name, h in r["hists"].items())
+    row("6: deviation from the exact result, fp16 32x32x8, %d tiles, TR-FDPA as printed (rd) / truncating (rz) / this GPU's instruction" % args.tiles6, r, means)
     # beside the five: the validation loop of Sec. 3.1 Step 4 on one FP16 and one FP32 instruction of this GPU
     from . import presets
     for instr, name in ((mm.MFMA_F32_32X32X8_F16, "v_mfma_f32_32x32x8_f16"), (mm.MFMA_F32_16X16X4_F32, "v_mfma_f32_16x16x4_f32")):

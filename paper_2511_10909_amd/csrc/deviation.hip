@@ -1,0 +1,150 @@
+// Distribution of the deviation delta = D - D_real of a model's (or an instruction's) outputs from the real result
+// (Sec. 6.2.4: the bias of the round-down modes shows as a distribution of delta shifted toward the negative side,
+// against a symmetric one for the variant that truncates toward zero).  D_real = c + sum_k a_k b_k is taken exactly:
+// per sampled output one thread adds D and subtracts every product and the accumulator in a wide fixed-point number,
+// so delta itself is exact; only its binary64 image (for the three sums) is rounded.  Linear bins of width 2^bin_exp
+// around zero: bin i holds delta in [(i - 32) w, (i - 31) w), the outermost bins everything beyond.
+#include "common.hpp"
+#include "fdpa_int.hpp"
+
+namespace mmaemu {
+
+constexpr int DEV_WORDS = sizeof(mmaemu_deviation_hist) / 8;
+static_assert(DEV_WORDS == 5 + MMAEMU_DEVIATION_BINS + 3, "layout of mmaemu_deviation_hist");
+
+__global__ void deviation_reset_kernel(mmaemu_deviation_hist *h)
+{
+    uint64_t *w = reinterpret_cast<uint64_t *>(h);
+    if (threadIdx.x < DEV_WORDS) w[threadIdx.x] = 0ull;             // +0.0 is all-zero bits
+}
+
+__global__ void __launch_bounds__(256)
+deviation_kernel(const void *__restrict__ A, const void *__restrict__ B, const uint32_t *__restrict__ C,
+                 const uint32_t *__restrict__ D, uint32_t m, uint32_t n, uint32_t k, uint32_t ta, uint32_t tb, uint64_t stride,
+                 uint64_t nsamples, int bin_exp, mmaemu_deviation_hist *hist)
+{
+    constexpr int NB = MMAEMU_DEVIATION_BINS;
+    __shared__ uint32_t counts[5 + NB];
+    if (threadIdx.x < 5 + NB) counts[threadIdx.x] = 0u;
+    __syncthreads();
+    const DynFmt fa = dyn_fmt(ta), fb = dyn_fmt(tb);
+    const uint32_t esa = (uint32_t)fa.width_ / 8u, esb = (uint32_t)fb.width_ / 8u;
+    const uint64_t per_tile = (uint64_t)m * n;
+    const int unit_bit = bin_exp - XBASE;                            // index of the bit that weighs one bin width
+    double sum = 0.0, sum_abs = 0.0, sum_sq = 0.0;
+    // (a workgroup handles at most 2^32 / 256 samples: the 32-bit LDS counters cannot overflow, see the launch)
+    for (uint64_t sidx = (uint64_t)blockIdx.x * 256u + threadIdx.x; sidx < nsamples; sidx += (uint64_t)gridDim.x * 256u) {
+        const uint64_t o = sidx * stride;
+        const uint64_t tile = o / per_tile;
+        const uint32_t rem = (uint32_t)(o - tile * per_tile), i = rem / n, j = rem - i * n;
+        const uint8_t *a = static_cast<const uint8_t *>(A) + (tile * m + i) * (uint64_t)k * esa;
+        const uint8_t *b = static_cast<const uint8_t *>(B) + (tile * n + j) * (uint64_t)k * esb;
+        uint32_t w[XL];
+        for (int q = 0; q < XL; ++q) w[q] = 0u;
+        bool bad = false;
+        for (uint32_t kk = 0; kk < k; ++kk) {
+            const Dec x = decode_as(fa, fa.load(a, kk), 0u), y = decode_as(fb, fb.load(b, kk), 0u);
+            bad |= x.cls == CLS_INF || x.cls == CLS_NAN || y.cls == CLS_INF || y.cls == CLS_NAN;
+            wide_add(w, sig_product(fa, fb, x, y), x.exp + y.exp - fa.mb() - fb.mb(), (x.sign ^ y.sign) ^ 1u);   // - a b
+        }
+        const uint32_t cb = C ? C[o] : 0u, db = D[o];
+        bad |= (cb & 0x7F800000u) == 0x7F800000u || (db & 0x7F800000u) == 0x7F800000u;
+        if (bad) { atomicAdd(&counts[1], 1u); continue; }
+        {
+            const uint32_t Ec = (cb >> 23) & 0xFFu, Ed = (db >> 23) & 0xFFu;
+            wide_add(w, (cb & 0x7FFFFFu) | (Ec ? 0x800000u : 0u), (int)(Ec ? Ec : 1u) - 150, (cb >> 31) ^ 1u);        // - c
+            wide_add(w, (db & 0x7FFFFFu) | (Ed ? 0x800000u : 0u), (int)(Ed ? Ed : 1u) - 150, db >> 31);               // + D
+        }
+        const uint32_t neg = w[XL - 1] >> 31;
+        if (neg) {
+            uint32_t carry = 1;
+            for (int q = 0; q < XL; ++q) {
+                const uint64_t t = (uint64_t)(~w[q]) + carry;
+                w[q] = (uint32_t)t;
+                carry = (uint32_t)(t >> 32);
+            }
+        }
+        int top = XL - 1;
+        while (top >= 0 && w[top] == 0u) --top;
+        atomicAdd(&counts[0], 1u);
+        if (top < 0) {                                               // delta = 0
+            atomicAdd(&counts[3], 1u);
+            atomicAdd(&counts[5 + NB / 2], 1u);
+            continue;
+        }
+        atomicAdd(&counts[neg ? 2 : 4], 1u);
+        const int hi_bit = 32 * top + (31 - __builtin_clz(w[top]));
+        // floor(delta / 2^bin_exp) from the magnitude: its bits from unit_bit upward, and whether anything lies below
+        int fi;
+        if (hi_bit < unit_bit) fi = neg ? -1 : 0;
+        else if (hi_bit - unit_bit >= 6) fi = neg ? -NB : NB;
+        else {
+            const int limb = unit_bit >> 5, off = unit_bit & 31;
+            uint32_t v = w[limb] >> off;
+            if (off && limb + 1 < XL) v |= w[limb + 1] << (32 - off);
+            const int q = (int)(v & 63u);
+            bool below = (off != 0) && (w[limb] & ((1u << off) - 1u)) != 0u;
+            for (int t = 0; t < limb; ++t) below |= w[t] != 0u;
+            fi = neg ? (below ? -q - 1 : -q) : q;
+        }
+        int bin = fi + NB / 2;
+        bin = bin < 0 ? 0 : (bin > NB - 1 ? NB - 1 : bin);
+        atomicAdd(&counts[5 + bin], 1u);
+        // binary64 image of delta: the 64 bits from the leading one downward, converted once
+        const int low_bit = hi_bit - 63;
+        uint64_t mag;
+        int lsb;
+        if (low_bit <= 0) { mag = ((uint64_t)w[1] << 32) | w[0]; lsb = XBASE; }
+        else {
+            const int l0 = low_bit >> 5, sh = low_bit & 31;
+            const uint32_t a0 = w[l0], a1 = w[l0 + 1], a2 = (l0 + 2 < XL) ? w[l0 + 2] : 0u;
+            const u128 win = ((u128)a2 << 64) | ((u128)a1 << 32) | a0;
+            mag = (uint64_t)(win >> sh);
+            lsb = XBASE + low_bit;
+        }
+        const double ad = ldexp((double)mag, lsb);
+        sum += neg ? -ad : ad;
+        sum_abs += ad;
+        sum_sq += ad * ad;
+    }
+    // the three sums: over the wavefront by lane exchanges, then one atomic per wavefront
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        sum += __shfl_xor(sum, off, 64);
+        sum_abs += __shfl_xor(sum_abs, off, 64);
+        sum_sq += __shfl_xor(sum_sq, off, 64);
+    }
+    double *gd = reinterpret_cast<double *>(reinterpret_cast<uint64_t *>(hist) + 5 + NB);
+    if ((threadIdx.x & 63u) == 0u) {
+        if (sum != 0.0) atomicAdd(&gd[0], sum);
+        if (sum_abs != 0.0) { atomicAdd(&gd[1], sum_abs); atomicAdd(&gd[2], sum_sq); }
+    }
+    __syncthreads();
+    if (threadIdx.x < 5 + NB && counts[threadIdx.x])
+        atomicAdd(reinterpret_cast<unsigned long long *>(hist) + threadIdx.x, (unsigned long long)counts[threadIdx.x]);
+}
+
+mmaemu_status launch_deviation_reset(mmaemu_deviation_hist *h, hipStream_t s)
+{
+    hipLaunchKernelGGL(deviation_reset_kernel, dim3(1), dim3(128), 0, s, h);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
+mmaemu_status launch_deviation_sample(const void *A, const void *B, const uint32_t *C, const uint32_t *D, uint32_t m, uint32_t n,
+                                      uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, uint64_t stride, int bin_exp,
+                                      mmaemu_deviation_hist *h, hipStream_t s)
+{
+    const uint64_t total = batch * m * n;
+    const uint64_t nsamples = (total + stride - 1) / stride;
+    if (nsamples == 0) return MMAEMU_OK;
+    uint64_t blocks = (nsamples + 255) / 256;
+    if (blocks > 4096) blocks = 4096;                                // grid-stride beyond that
+    if ((nsamples + blocks - 1) / blocks > 0xFFFFFFFFull) { set_error("deviation_sample: more than 2^44 samples in one call"); return MMAEMU_ERR_SHAPE; }
+    hipLaunchKernelGGL(deviation_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, A, B, C, D, m, n, k, ta, tb, stride, nsamples,
+                       bin_exp, h);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
+} // namespace mmaemu

@@ -31,7 +31,9 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     // (the tiled kernels tag BF16 and TF32 products of 2^128 and more as infinities: without that rule such products need
     // the general kernel's integer range)
     const bool wide_bf16 = p.wide_products && (ta == MMAEMU_BF16 || tb == MMAEMU_BF16 || ta == MMAEMU_TF32);
-    const bool tiled_mode = p.c_mode != MMAEMU_C_EXACT &&
+    // (rounding toward zero in place of the round-downs: the tiled kernels have it for unsplit groups with the plain F2 rule)
+    const bool rz_ok = !p.rd_toward_zero || (p.split == MMAEMU_SPLIT_NONE && !p.f2_at_leading_bit);
+    const bool tiled_mode = p.c_mode != MMAEMU_C_EXACT && rz_ok &&
                             ((p.c_mode == MMAEMU_C_AFTER_RD && !wide_bf16) || (p.c_mode != MMAEMU_C_AFTER_RD && !p.skip_zero_terms && !p.zero_result_positive));
     // block scales run tiled when every group lies inside one block (all of its products then share one scale
     // exponent) and the values stay binary32 (FP8 / FP16 operands, F below 30)

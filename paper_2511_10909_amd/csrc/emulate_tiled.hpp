@@ -829,11 +829,16 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
         const int E = have_T ? (ec > em ? ec : em) : ec;           // the accumulator always takes part
         if (have_T && p.sum_drop_distance && E - em >= p.sum_drop_distance) have_T = false;
         if (!have_T) T = 0.0;
-        double sc = __builtin_floor(ldexp((double)__uint_as_float(cb), p.Fc - E));               // RD_Fc(c at E), units of 2^(E - Fc)
+        const double sc_exact = ldexp((double)__uint_as_float(cb), p.Fc - E);
+        double sc = __builtin_floor(sc_exact);                                                    // RD_Fc(c at E), units of 2^(E - Fc)
+        // (Sec. 6.2.4's hypothetical variant: both roundings truncate toward zero; unsplit groups, plain F2 rule)
+        if ((fe & FL_RD_AS_RZ)) sc = __builtin_trunc(sc_exact);
         if ((fe & FL_SPECIAL_TRUNC) && ec < E - p.Fc - 1 && Ec != 0xFFu) sc = 0.0;             // (an infinite or NaN accumulator stays)
         double val;
         if (!(fe & FL_F2_LEADING)) {
-            const double T2 = __builtin_floor(ldexp(T, (em - FT) - (E - p.F2)));                  // RD_F2(T at E)
+            const double T_exact = ldexp(T, (em - FT) - (E - p.F2));
+            double T2 = __builtin_floor(T_exact);                                                 // RD_F2(T at E)
+            if ((fe & FL_RD_AS_RZ)) T2 = __builtin_trunc(T_exact);
             val = ldexp(ldexp(T2, Fmax - p.F2) + ldexp(sc, Fmax - p.Fc), E - Fmax);
         } else {
             // exact two-term sum as s + err (Knuth's TwoSum); then round down to F2 bits below the leading bit

@@ -91,6 +91,19 @@ __device__ __forceinline__ i128 align_rd(i128 v, int lsb, int unit)
     return sh > -127 ? (v >> (-sh)) : (v >> 127);      // arithmetic shift = floor
 }
 
+// The rounding of the summation's second step (the sum of the products and the accumulator brought to E, the merges of
+// a split group): toward minus infinity as the algorithms print it, or -- Sec. 6.2.4's hypothetical instruction -- toward
+// zero: the magnitude of a negative value loses its low bits instead.
+__device__ __forceinline__ i128 align_step(const ModelArgs &p, i128 v, int lsb, int unit)
+{
+    if (p.rd_toward_zero && v < 0 && unit > lsb) {
+        const int drop = unit - lsb;
+        const u128 mag = (u128)(-v);
+        return drop > 127 ? (i128)0 : -(i128)(mag >> drop);
+    }
+    return align_rd(v, lsb, unit);
+}
+
 __device__ __forceinline__ int bitlen128(u128 x)
 {
     const uint64_t hi = (uint64_t)(x >> 64), lo = (uint64_t)x;
@@ -173,7 +186,7 @@ __device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, bool 
     // the accumulator always takes part, a zero one with the exponent of the subnormals
     const int E = have_T ? (dc.exp > emax ? dc.exp : emax) : dc.exp;
     const i128 sc = dc.sign ? -(i128)dc.sig : (i128)dc.sig;
-    i128 sc2 = align_rd(sc, dc.exp - 23, E - p.Fc);
+    i128 sc2 = align_step(p, sc, dc.exp - 23, E - p.Fc);
     if (p.acc_special_truncation && dc.exp < E - p.Fc - 1) sc2 = 0;
     const int unit_c = E - p.Fc;
     if (have_T && p.sum_drop_distance && E - emax >= p.sum_drop_distance) have_T = false;      // T' = 0
@@ -184,15 +197,15 @@ __device__ __forceinline__ uint32_t rounded_sum_with_c(const ModelArgs &p, bool 
     if (p.f2_at_leading_bit) {
         // T far below the accumulator's unit is first rounded down to units of 2^(unit_c - 64):
         // rounding down in two steps equals rounding down once
-        if (unit_c - unit_T > 64) { T = align_rd(T, unit_T, unit_c - 64); unit_T = unit_c - 64; }
+        if (unit_c - unit_T > 64) { T = align_step(p, T, unit_T, unit_c - 64); unit_T = unit_c - 64; }
         unit = unit_T < unit_c ? unit_T : unit_c;
         S = (i128)((u128)T << (unit_T - unit)) + (i128)((u128)sc2 << (unit_c - unit));
         if (S == 0) return 0u;
         int lead = bitlen128((u128)(S < 0 ? -S : S)) - 1 + unit;
         lead = lead < -126 ? -126 : lead;                  // no lower than binary32's smallest normal exponent
-        if (lead - p.F2 > unit) { S = align_rd(S, unit, lead - p.F2); unit = lead - p.F2; }
+        if (lead - p.F2 > unit) { S = align_step(p, S, unit, lead - p.F2); unit = lead - p.F2; }
     } else {
-        const i128 T2 = align_rd(T, unit_T, E - p.F2);
+        const i128 T2 = align_step(p, T, unit_T, E - p.F2);
         unit = (E - p.F2) < unit_c ? (E - p.F2) : unit_c;
         S = (i128)((u128)T2 << ((E - p.F2) - unit)) + (i128)((u128)sc2 << (unit_c - unit));
     }
@@ -381,7 +394,7 @@ __device__ uint32_t fdpa_group(const ModelArgs &p, const FTA &fa, const FTB &fb,
         }
         i128 T = 0;
         for (int g = 0; g < np_; ++g)
-            if (hp[g]) T += align_rd((i128)Tp[g], ep[g] - p.F, emax - p.Fm);
+            if (hp[g]) T += align_step(p, (i128)Tp[g], ep[g] - p.F, emax - p.Fm);
         return finish_group(p, rounded_sum_with_c(p, any, (int64_t)T, emax, emax - p.Fm, dc));
     }
 

@@ -307,8 +307,9 @@ gen_normal_kernel(GenArgs g, T *out, uint64_t g0, uint64_t total, uint64_t blk0,
     if (t >= nblk) return;
     double z[4];
     block_normals(g, blk0 + t, z);
-    const bool scaled = absmax != nullptr;
-    const double scale = scaled ? g.scale_target / *absmax : 1.0;
+    const bool by_factor = g.scale_scope == MMAEMU_SCALE_FACTOR;          // every value times scale_target itself
+    const bool scaled = by_factor || absmax != nullptr;
+    const double scale = by_factor ? g.scale_target : (absmax != nullptr ? g.scale_target / *absmax : 1.0);
     write_block<T>(g, out, blk0 + t, z, scale, scaled, g0, total);
 }
 
@@ -411,7 +412,7 @@ static mmaemu_status launch_typed(const GenArgs &ga, void *out, uint64_t ept, ui
     const bool value_family = ga.family == MMAEMU_GEN_NORMAL || ga.family == MMAEMU_GEN_UNIFORM || ga.family == MMAEMU_GEN_NORMAL_OUTLIERS;
     if (!value_family) {
         hipLaunchKernelGGL((gen_bits_kernel<T>), dim3((uint32_t)grid), dim3(256), 0, s, ga, (T *)out, g0, total, blk0, nblk);
-    } else if (ga.scale_scope == MMAEMU_SCALE_NONE) {
+    } else if (ga.scale_scope == MMAEMU_SCALE_NONE || ga.scale_scope == MMAEMU_SCALE_FACTOR) {
         hipLaunchKernelGGL((gen_normal_kernel<T>), dim3((uint32_t)grid), dim3(256), 0, s, ga, (T *)out, g0, total, blk0, nblk,
                            (const double *)nullptr);
     } else if (ga.scale_scope == MMAEMU_SCALE_TENSOR) {

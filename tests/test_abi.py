@@ -40,7 +40,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_struct_sizes_match_binding():
     from paper_2511_10909_amd import binding as mm
-    assert ctypes.sizeof(mm.ModelParams) == 96
+    assert ctypes.sizeof(mm.ModelParams) == 100
+    assert ctypes.sizeof(mm.DeviationHist) == 8 * 72
     assert ctypes.sizeof(mm.Stats) == 8 * 39
     assert ctypes.sizeof(mm.ErrStats) == 8 * 44
     assert ctypes.sizeof(mm.GenParams) == 48
@@ -54,7 +55,8 @@ def test_host_side_validation_needs_no_gpu():
     mm.model_destroy(None)
     for kw, status in ((dict(frac_bits=49), 2), (dict(frac_bits=41, frac_bits2=31, c_mode=2), 2), (dict(out_round=2), 1), (dict(c_mode=5), 1), (dict(align_round=1), 2),
                        (dict(out_mant_bits=13), 2), (dict(out_mant_bits=10, out_round=1), 2), (dict(frac_bits2=31), 2), (dict(c_mode=2, frac_bits2=49), 2), (dict(split=1), 2), (dict(c_mode=2, split=4), 1),
-                       (dict(c_mode=3, frac_bits2=31, frac_bits_acc=24), 2), (dict(c_mode=2, frac_bits_merge=24), 2), (dict(skip_zero_terms=2), 1), (dict(family=4), 1), (dict(family=2), 2), (dict(family=1, group_len=8), 2), (dict(family=1, group_len=4, ftz_out=True), 2), (dict(struct_size=40), 1), (dict(group_len=(1 << 20) + 1), 2)):
+                       (dict(c_mode=3, frac_bits2=31, frac_bits_acc=24), 2), (dict(c_mode=2, frac_bits_merge=24), 2), (dict(skip_zero_terms=2), 1), (dict(family=4), 1), (dict(family=2), 2), (dict(family=1, group_len=8), 2), (dict(family=1, group_len=4, ftz_out=True), 2), (dict(struct_size=40), 1),
+                       (dict(rd_toward_zero=True), 2), (dict(c_mode=2, frac_bits2=31, rd_toward_zero=2), 2), (dict(group_len=(1 << 20) + 1), 2)):
         with pytest.raises(mm.MmaemuError) as ei:
             mm.model_create(**kw)
         assert ei.value.status == status, kw

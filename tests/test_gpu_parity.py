@@ -34,7 +34,7 @@ def gpu_emulate(mm, p, A, B, C, ta, tb, tc=fm.FP32):
                         frac_bits_acc=p.frac_bits_acc, f2_at_leading_bit=p.f2_at_leading_bit,
                         skip_zero_terms=p.skip_zero_terms, zero_result_positive=p.zero_result_positive,
                         sum_drop_distance=p.sum_drop_distance, family=p.family, out_mant_bits=p.out_mant_bits,
-                        wide_products=p.wide_products, nan_propagate=p.nan_propagate)
+                        wide_products=p.wide_products, nan_propagate=p.nan_propagate, rd_toward_zero=p.rd_toward_zero)
     try:
         dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(NP[tc]))
         dD = dev_empty((nb, m, n), NP[tc])

@@ -21,7 +21,7 @@ def gpu_emulate_scaled(mm, p, A, B, C, SA, SB, block, ta, tb):
                         frac_bits_acc=p.frac_bits_acc, f2_at_leading_bit=p.f2_at_leading_bit,
                         skip_zero_terms=p.skip_zero_terms, zero_result_positive=p.zero_result_positive,
                         sum_drop_distance=p.sum_drop_distance, out_mant_bits=p.out_mant_bits,
-                        wide_products=p.wide_products)
+                        wide_products=p.wide_products, rd_toward_zero=p.rd_toward_zero)
     try:
         dD = dev_empty((nb, m, n), np.uint32)
         mm.emulate_mma_scaled(h, to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(np.uint32)), dD,
