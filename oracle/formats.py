@@ -25,6 +25,7 @@ from fractions import Fraction
 E4M3, E5M2, FP16, BF16, FP32 = 0, 1, 2, 3, 4
 E2M3, E3M2, E2M1 = 6, 7, 8          # (5 is the E8M0 scale code, which is no operand type)
 TF32 = 9                            # a binary32 word whose low 13 mantissa bits are ignored (8 exponent, 10 mantissa bits)
+FP64 = 10                           # binary64: Algorithms "FMA" / "Phi_FMA" are stated for FP64 as well as FP32
 
 
 @dataclass(frozen=True)
@@ -56,6 +57,7 @@ FORMATS = {
     E3M2: Format("e3m2", 3, 2, 3, False, True),
     E2M1: Format("e2m1", 2, 1, 1, False, True),
     TF32: Format("tf32", 8, 10, 127, True, False, 13),
+    FP64: Format("fp64", 11, 52, 1023, True),
 }
 
 ZERO, SUBNORMAL, NORMAL, INF, NAN = "zero", "subnormal", "normal", "inf", "nan"

@@ -244,10 +244,61 @@ def _generate_scale_codes(gp, elems_per_tile, first_tile, n_tiles):
     return out.astype(np.uint32).reshape(n_tiles, elems_per_tile)
 
 
+def _generate_fp64(gp, elems_per_tile, first_tile, n_tiles, threads=1):
+    """binary64 output (uint64 patterns).  Value families: the binary64 value itself (times scale_target under
+    SCALE_FACTOR; the other scale scopes are not defined here), one word per element as for every other format.  Bit
+    families: element g owns the two words 2g (low half, lo) and 2g + 1 (high half, hi):
+      RANDOM_BITS   hi:lo
+      FINITE_BITS   v = floor(hi:lo * 2 * nmag / 2^64) with nmag = 2047 * 2^52 finite magnitudes; sign = v >= nmag
+      UNIFORM_EXP   sign = hi bit 31; exponent field chosen by the low 31 bits of hi exactly as for FP32; mantissa =
+                    (hi's low 20 bits):lo
+      SIGNED_ZEROS  as for the other formats, decided by hi
+    """
+    total = n_tiles * elems_per_tile
+    if gp.family == GEN_ZERO:
+        return np.zeros((n_tiles, elems_per_tile), dtype=np.uint64)
+    if gp.family in VALUE_FAMILIES:
+        z = normal_values(gp, elems_per_tile, first_tile, n_tiles, threads)
+        if gp.scale_scope == SCALE_FACTOR:
+            z = z * np.float64(gp.scale_target)
+        elif gp.scale_scope != SCALE_NONE:
+            raise ValueError("binary64 output: no scaling, or a constant factor")
+        return np.ascontiguousarray(z, dtype=np.float64).view(np.uint64).reshape(n_tiles, elems_per_tile)
+    g = np.arange(first_tile * elems_per_tile, first_tile * elems_per_tile + total, dtype=np.uint64)
+    lo = _words(gp.seed, gp.operand, g * np.uint64(2)).astype(np.uint64)
+    hi = _words(gp.seed, gp.operand, g * np.uint64(2) + np.uint64(1)).astype(np.uint64)
+    if gp.family == GEN_RANDOM_BITS:
+        out = (hi << np.uint64(32)) | lo
+    elif gp.family == GEN_FINITE_BITS:
+        # floor((hi * 2^32 + lo) * 2047 * 2^53 / 2^64) = hi * 2047 * 2^21 + floor(lo * 2047 / 2^11)
+        v = hi * np.uint64(2047) * np.uint64(1 << 21) + ((lo * np.uint64(2047)) >> np.uint64(11))
+        nmag = np.uint64(2047 << 52)
+        sign = (v >= nmag).astype(np.uint64)
+        out = (sign << np.uint64(63)) | (v - sign * nmag)
+    elif gp.family == GEN_UNIFORM_EXP:
+        nch = gp.exp_hi - gp.exp_lo + 1 + (1 if gp.exp_zero else 0)
+        sign = hi >> np.uint64(31)
+        idx = ((hi & np.uint64(0x7FFFFFFF)) * np.uint64(nch)) >> np.uint64(31)
+        if gp.exp_zero:
+            E = np.where(idx == 0, np.uint64(0), np.uint64(gp.exp_lo) + idx - np.uint64(1))
+        else:
+            E = np.uint64(gp.exp_lo) + idx
+        out = (sign << np.uint64(63)) | (E << np.uint64(52)) | ((hi & np.uint64(0xFFFFF)) << np.uint64(32)) | lo
+    elif gp.family == GEN_SIGNED_ZEROS:
+        sign, kind = (hi >> np.uint64(29)) & np.uint64(1), hi >> np.uint64(30)
+        mag = np.where(kind == 2, np.uint64(1023 << 52), np.where(kind == 3, np.uint64(1), np.uint64(0)))
+        out = (sign << np.uint64(63)) | mag
+    else:
+        raise ValueError("family %d is not defined for binary64 output" % gp.family)
+    return out.reshape(n_tiles, elems_per_tile)
+
+
 def generate(gp, fmt_id, elems_per_tile, first_tile, n_tiles, threads=1):
     """Raw bit patterns (uint32 array, shape (n_tiles, elems_per_tile)) of one operand."""
     if fmt_id == E8M0:
         return _generate_scale_codes(gp, elems_per_tile, first_tile, n_tiles)
+    if fmt_id == fm.FP64:
+        return _generate_fp64(gp, elems_per_tile, first_tile, n_tiles, threads)
     f = fm.FORMATS[fmt_id]
     total = n_tiles * elems_per_tile
     if gp.family == GEN_ZERO:

@@ -95,6 +95,36 @@ def to_fp16(v, mode):
     return (sign << 15) | mag
 
 
+def to_fp64(v, mode):
+    """Round the exact rational v to binary64 bits: the rules of to_fp32 on the binary64 grid (52 mantissa bits,
+    exponents -1022 .. 1023, gradual underflow, overflow to infinity under RNE, exact zero -> +0.0)."""
+    v = Fraction(v)
+    if v == 0:
+        return 0
+    sign = 1 if v < 0 else 0
+    a = -v if sign else v
+    e = max(floor_log2(a), -1022)
+    q = a / Fraction(2) ** (e - 52)
+    n = q.numerator // q.denominator
+    rem = q - n
+    if mode == RNE:
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (n & 1)):
+            n += 1
+    elif mode != RZ:
+        raise ValueError(mode)
+    if n == (1 << 53):
+        n >>= 1
+        e += 1
+    if e > 1023:
+        mag = 0x7FF0000000000000 if mode == RNE else 0x7FEFFFFFFFFFFFFF
+    elif n < (1 << 52):
+        assert e == -1022
+        mag = n
+    else:
+        mag = ((e + 1023) << 52) | (n - (1 << 52))
+    return (sign << 63) | mag
+
+
 def rne_fp32(v):
     return to_fp32(v, RNE)
 

@@ -15,7 +15,8 @@ library's own definition:
 
 Ordered-integer distance: map FP32 bits b to key(b) = b if the sign bit is clear,
 else -(b & 0x7FFFFFFF); the distance is |key(x) - key(y)| (so +0 and -0 coincide
-and adjacent floats are at distance 1).  FP16 outputs: the same on 16-bit patterns.
+and adjacent floats are at distance 1).  FP16 outputs: the same on 16-bit patterns.  FP64 outputs (width 64): the
+same on 64-bit patterns, with bucket 32 also taking every distance of 2^32 and more.
 """
 import numpy as np
 
@@ -24,12 +25,17 @@ N_BUCKETS = 34
 
 
 def ordered_key(bits, width=32):
+    if width == 64:                      # (Python integers: the keys span 65 bits' worth of distance)
+        sign = 1 << 63
+        return np.array([-(int(b) & (sign - 1)) if int(b) & sign else int(b) for b in np.asarray(bits).ravel()], dtype=object)
     b = np.asarray(bits, dtype=np.uint32).astype(np.int64)
     sign = 1 << (width - 1)
     return np.where(b & sign, -(b & (sign - 1)), b)
 
 
 def is_nan(bits, width=32):
+    if width == 64:
+        return (np.asarray(bits, dtype=np.uint64) & np.uint64(0x7FFFFFFFFFFFFFFF)) > np.uint64(0x7FF0000000000000)
     b = np.asarray(bits, dtype=np.uint32)
     return (b & ((1 << (width - 1)) - 1)) > (0x7F800000 if width == 32 else 0x7C00)
 
@@ -41,10 +47,10 @@ def empty_stats():
 
 def compare(d0, d1, stats=None, index_base=0, width=32):
     """Accumulate the comparison of two FP32 (width 32) or FP16 (width 16) bit arrays into `stats` (a dict)."""
-    assert width in (32, 16)
+    assert width in (64, 32, 16)
     st = empty_stats() if stats is None else stats
-    x = np.asarray(d0, dtype=np.uint32).ravel()
-    y = np.asarray(d1, dtype=np.uint32).ravel()
+    x = np.asarray(d0, dtype=np.uint64 if width == 64 else np.uint32).ravel()
+    y = np.asarray(d1, dtype=np.uint64 if width == 64 else np.uint32).ravel()
     assert x.shape == y.shape
     st["n_compared"] += int(x.size)
     diff = x != y
@@ -61,10 +67,10 @@ def compare(d0, d1, stats=None, index_base=0, width=32):
     dist = np.abs(ordered_key(x[num], width) - ordered_key(y[num], width))
     if dist.size:
         st["max_ulp_dist"] = max(st["max_ulp_dist"], int(dist.max()))
-        # bucket = bit length of the distance
+        # bucket = bit length of the distance (at most 32: only 64-bit patterns lie farther apart)
         bl = np.zeros(dist.shape, dtype=np.int64)
-        for i in range(33):
-            bl += dist >= (1 << i)
+        for i in range(32):
+            bl += (dist >= (1 << i)).astype(np.int64)
         for i, c in zip(*np.unique(bl, return_counts=True)):
             st["ulp_hist"][int(i)] += int(c)
     return st
