@@ -63,7 +63,10 @@ typedef enum {
      * sign, the 8 exponent bits and the top 10 mantissa bits count; the low 13 bits are ignored on input (a NaN whose
      * payload lies only there reads as an infinity).  Pairs with itself only; mmaemu_generate does not take it
      * (every MMAEMU_FP32 stream is a TF32 stream). */
-    MMAEMU_TF32 = 9
+    MMAEMU_TF32 = 9,
+    /* binary64, eight bytes per element: the other format Algorithms "FMA" and "Phi_FMA" are stated for.  Taken by the
+     * FMA family (all four arrays FP64), mmaemu_generate, mmaemu_compare and the FP64 MFMA probes. */
+    MMAEMU_FP64 = 10
 } mmaemu_dtype;
 
 typedef struct {
@@ -151,7 +154,10 @@ enum { MMAEMU_SCALE_FORMAT_E8M0 = 0, MMAEMU_SCALE_FORMAT_UE4M3 = 1 };
  *   a b + d as if to infinite precision, rounded once to binary32, ties to even; subnormal inputs and results kept;
  *   overflow gives infinity.  The sign of an exact zero is IEEE-754's: +0.0, except that a zero product and a zero
  *   accumulator of the same sign keep that sign.  Special values as in Sec. 4.2 (every NaN result is nan_bits), or with
- *   nan_propagate the payload rule described at that field, applied per step.  Uses nan_bits and nan_propagate only;
+ *   nan_propagate the payload rule described at that field, applied per step.  With dtypes = (FP64, FP64, FP64, FP64) the
+ *   same chain on binary64 (Algorithm "FMA" with F = FP64), the NaN pattern being nan_bits widened as a conversion from
+ *   binary32 to binary64 widens a NaN (sign, exponent field all ones, the 23 mantissa bits on top of the 52) and the
+ *   quiet bit of the payload rule bit 51.  Uses nan_bits and nan_propagate only;
  *   group_len must be 0 or 1 and every other field must hold its default (frac_bits is ignored).
  *   (The FDPA family with group_len = 1, c_mode = C_AFTER_EXACT and frac_bits wide enough for the whole product, 46
  *   for FP32 operands, computes the same chain except for that sign: there an exact zero is always +0.0.)
@@ -256,7 +262,8 @@ mmaemu_status mmaemu_emulate_mma_scaled(const mmaemu_model *model, const void *A
  *   ulp_hist[33]     exactly one of the two values is NaN
  * Ordered-integer distance: key(b) = b if the sign bit is clear, else -(b & 0x7FFFFFFF);
  * distance = |key(x) - key(y)|.  For FP16 outputs the same on 16-bit patterns (sign bit 0x8000, NaN above 0x7C00;
- * only buckets 0..16 and 33 can fill).
+ * only buckets 0..16 and 33 can fill).  For FP64 outputs the same on 64-bit patterns; ulp_hist[32] then also holds every
+ * distance of 2^32 and more, and max_ulp_dist can take all 64 bits.
  */
 typedef struct {
     uint64_t n_compared;
@@ -384,8 +391,9 @@ mmaemu_status mmaemu_generate_noalloc(const mmaemu_gen_params *gen, void *out, m
  * Native-instruction probe: the device under test of the closed loop (paper Sec. 3.3:
  * instruction-level MMA interfaces through intrinsics).  Runs one real v_mfma
  * instruction per tile on the same operand layout as mmaemu_emulate_mma:
- * A[batch][M][k], B[batch][N][k], C/D[batch][M][N] (FP32) with M, N and K_native fixed by
- * the instruction; k <= K_native, the missing k positions are fed as zeros.
+ * A[batch][M][k], B[batch][N][k], C/D[batch][M][N] (FP32; FP64 for the two binary64 forms, whose pointers must
+ * be 8-byte aligned) with M, N and K_native fixed by the instruction; k <= K_native, the missing k positions are
+ * fed as zeros.
  */
 typedef enum {
     MMAEMU_MFMA_F32_16X16X16_F16 = 0,
@@ -429,7 +437,10 @@ typedef enum {
     MMAEMU_MFMA_F32_32X32X1_2B_F32 = 74,
     MMAEMU_MFMA_F32_16X16X1_4B_F32 = 75,
     MMAEMU_MFMA_F32_4X4X1_16B_F32 = 76,
-    MMAEMU_MFMA_COUNT = 77
+    /* binary64 forms (the device under test for Algorithm "Phi_FMA" with F = FP64): A, B, C and D all MMAEMU_FP64 */
+    MMAEMU_MFMA_F64_16X16X4_F64 = 77,
+    MMAEMU_MFMA_F64_4X4X4_4B_F64 = 78, /* four blocks per issue, a block is a tile as above */
+    MMAEMU_MFMA_COUNT = 79
 } mmaemu_mfma_instr;
 
 /* Shape and operand types of an instruction (host-side query). */

@@ -12,6 +12,7 @@ LIB_PATH = os.path.join(_PKG, "libmmaemu.so")
 E4M3, E5M2, FP16, BF16, FP32, E8M0 = 0, 1, 2, 3, 4, 5
 E2M3, E3M2, E2M1 = 6, 7, 8                      # FP6 and FP4 operands, one code per byte
 TF32 = 9                                        # binary32 words whose low 13 mantissa bits are ignored
+FP64 = 10                                       # binary64: the FMA family, the generators, the comparison, two MFMA forms
 C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD, C_AFTER_RD_EVEN_ODD, C_EXACT = 0, 1, 2, 3, 4
 RNE, RZ = 0, 1
 SPLIT_NONE, SPLIT_EVEN_ODD, SPLIT_HALVES, SPLIT_QUARTERS = 0, 1, 2, 3
@@ -46,8 +47,9 @@ MFMA_SCALE32_IDS = tuple(range(43, 68))
 MFMA_F32_16X16X4_F32, MFMA_F32_32X32X2_F32 = 41, 42
 # multi-block forms (one issue = 64 / m tiles): 32x32x4_2b, 16x16x4_4b, 4x4x4_16b for FP16 and BF16; 32x32x1_2b, 16x16x1_4b, 4x4x1_16b for FP32
 MFMA_MULTIBLOCK_F16_IDS, MFMA_MULTIBLOCK_BF16_IDS, MFMA_MULTIBLOCK_F32_IDS = (68, 69, 70), (71, 72, 73), (74, 75, 76)
-MFMA_UNSCALED_IDS = tuple(range(10)) + tuple(range(35, 43)) + tuple(range(68, 77))
-ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1, TF32: 4}
+MFMA_F64_16X16X4_F64, MFMA_F64_4X4X4_4B_F64 = 77, 78
+MFMA_UNSCALED_IDS = tuple(range(10)) + tuple(range(35, 43)) + tuple(range(68, 79))
+ELEM_BYTES = {E4M3: 1, E5M2: 1, FP16: 2, BF16: 2, FP32: 4, E8M0: 1, E2M3: 1, E3M2: 1, E2M1: 1, TF32: 4, FP64: 8}
 NO_MISMATCH = (1 << 64) - 1
 
 

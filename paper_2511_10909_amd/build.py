@@ -29,11 +29,23 @@ def _compile(src):
     return src, obj, r
 
 
-def build_library(verbose=True, jobs=8):
+def _stale(src):
+    """True when the object of `src` is older than the source or than any header."""
+    obj = os.path.join(OBJ, src[:-4] + ".o")
+    if not os.path.exists(obj):
+        return True
+    deps = [os.path.join(CSRC, src)] + [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hpp")]
+    deps += [os.path.join(ROOT, "include", f) for f in os.listdir(os.path.join(ROOT, "include"))]
+    return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
+
+
+def build_library(verbose=True, jobs=8, only_stale=False):
+    """Compiles every source (only_stale: those whose object is out of date) and links the library."""
     os.makedirs(OBJ, exist_ok=True)
+    todo = [s for s in sources() if not only_stale or _stale(s)]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        results = list(ex.map(_compile, sources()))
-    objs = []
+        results = list(ex.map(_compile, todo))
+    objs = [os.path.join(OBJ, s[:-4] + ".o") for s in sources() if s not in todo]
     for src, obj, r in results:
         warn = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip())
         if r.returncode != 0:
@@ -49,4 +61,4 @@ def build_library(verbose=True, jobs=8):
 
 
 if __name__ == "__main__":
-    print(build_library())
+    print(build_library(only_stale="--stale" in sys.argv[1:]))

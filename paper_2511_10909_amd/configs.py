@@ -21,7 +21,7 @@ import torch
 
 from . import binding as mm
 
-_TORCH = {1: torch.uint8, 2: torch.int16, 4: torch.int32}
+_TORCH = {1: torch.uint8, 2: torch.int16, 4: torch.int32, 8: torch.int64}
 
 
 def _buf(shape, dtype_id, dev):
@@ -426,8 +426,9 @@ def validation_families(ta, tb):
     """Input families of Step 4: common distributions, all finite bit patterns, all bit patterns (NaN and infinities
     included: the paper calls this one the most important), and exponent ranges chosen to put the accumulator above,
     below and anywhere relative to the products.  Each entry: (name, generator arguments for A, for B, for C)."""
-    full = {mm.FP32: (1, 254), mm.FP16: (1, 30), mm.BF16: (1, 254), mm.E4M3: (0, 15), mm.E5M2: (0, 30), mm.E2M3: (0, 3), mm.E3M2: (0, 7), mm.E2M1: (0, 3)}
-    mid = {mm.FP32: (120, 134), mm.FP16: (11, 19), mm.BF16: (120, 134), mm.E4M3: (3, 11), mm.E5M2: (11, 19), mm.E2M3: (1, 2), mm.E3M2: (2, 5), mm.E2M1: (1, 2)}
+    cs = 896 if ta == mm.FP64 else 0           # exponent codes of the accumulator's format: binary64's bias is 1023, binary32's 127
+    full = {mm.FP64: (1, 2046), mm.FP32: (1, 254), mm.FP16: (1, 30), mm.BF16: (1, 254), mm.E4M3: (0, 15), mm.E5M2: (0, 30), mm.E2M3: (0, 3), mm.E3M2: (0, 7), mm.E2M1: (0, 3)}
+    mid = {mm.FP64: (1016, 1030), mm.FP32: (120, 134), mm.FP16: (11, 19), mm.BF16: (120, 134), mm.E4M3: (3, 11), mm.E5M2: (11, 19), mm.E2M3: (1, 2), mm.E3M2: (2, 5), mm.E2M1: (1, 2)}
 
     def ue(rng, zero=True):
         return dict(family=mm.GEN_UNIFORM_EXP, exp_lo=rng[0], exp_hi=rng[1], exp_zero=zero)
@@ -437,21 +438,26 @@ def validation_families(ta, tb):
     fams = [(name, dict(family=f), dict(family=f), dict(family=f)) for name, f in simple]
     # adversarial sums: products cancelling pairwise up to last-place perturbations, accumulator near the residue
     canc = dict(family=mm.GEN_CANCELLING, exp_zero=False)
-    if ta != mm.FP32:       # (the generator does not build cancelling pairs of FP32 values)
+    if ta not in (mm.FP32, mm.FP64):       # (the generator does not build cancelling pairs of FP32 / FP64 values)
         fams.append(("cancelling", dict(canc, exp_lo=mid[ta][0], exp_hi=mid[ta][1]), dict(canc, exp_lo=mid[tb][0], exp_hi=mid[tb][1]),
                      ue((100, 135))))
     # zeros of both signs, +-1 and the smallest subnormals: exact zeros from zeros, whose sign a model must get right
     zs = dict(family=mm.GEN_SIGNED_ZEROS)
     fams.append(("signed_zeros", zs, zs, zs))
-    fams.append(("mid_exp_c_above", ue(mid[ta]), ue(mid[tb]), ue((125, 145), zero=False)))
-    fams.append(("mid_exp_c_below", ue(mid[ta]), ue(mid[tb]), ue((80, 129))))
-    fams.append(("wide_exp_c_any", ue(full[ta]), ue(full[tb]), ue((1, 254))))
+    fams.append(("mid_exp_c_above", ue(mid[ta]), ue(mid[tb]), ue((cs + 125, cs + 145), zero=False)))
+    fams.append(("mid_exp_c_below", ue(mid[ta]), ue(mid[tb]), ue((cs + 80, cs + 129))))
+    fams.append(("wide_exp_c_any", ue(full[ta]), ue(full[tb]), ue((1, 2046) if cs else (1, 254))))
     # every product at one exponent, the accumulator 20 to 32 binary places above it (where whole sums drop out)
-    bias = {mm.FP32: 127, mm.FP16: 15, mm.BF16: 127, mm.E4M3: 7, mm.E5M2: 15, mm.E2M3: 1, mm.E3M2: 3, mm.E2M1: 1}
-    one = {mm.FP32: 128, mm.FP16: 16, mm.BF16: 128, mm.E4M3: 8, mm.E5M2: 16, mm.E2M3: 2, mm.E3M2: 4, mm.E2M1: 2}
+    bias = {mm.FP64: 1023, mm.FP32: 127, mm.FP16: 15, mm.BF16: 127, mm.E4M3: 7, mm.E5M2: 15, mm.E2M3: 1, mm.E3M2: 3, mm.E2M1: 1}
+    one = {mm.FP64: 1024, mm.FP32: 128, mm.FP16: 16, mm.BF16: 128, mm.E4M3: 8, mm.E5M2: 16, mm.E2M3: 2, mm.E3M2: 4, mm.E2M1: 2}
     e_prod = (one[ta] - bias[ta]) + (one[tb] - bias[tb])
     fams.append(("one_exp_c_far_above", ue((one[ta], one[ta]), zero=False), ue((one[tb], one[tb]), zero=False),
-                 ue((127 + e_prod + 20, 127 + e_prod + 32), zero=False)))
+                 ue((cs + 127 + e_prod + (49 if cs else 20), cs + 127 + e_prod + (61 if cs else 32)), zero=False)))
+    if ta == mm.FP64:
+        # products around the bottom of binary64's subnormal range
+        tiny = ue((483, 489))
+        fams.append(("tiny_products_c_zero", tiny, tiny, dict(family=mm.GEN_ZERO)))
+        fams.append(("tiny_products_c_subnormal", tiny, tiny, ue((0, 2))))
     if ta == tb and ta in (mm.BF16, mm.FP32):
         # products around the bottom of binary32's subnormal range, with a zero and with a subnormal accumulator
         tiny = ue((46, 52))
@@ -508,7 +514,8 @@ def validate_against_mfma(instr, model_kwargs, n_tiles=4096, seeds=(0,), dev="cu
     info = mm.mfma_info(instr)
     m, n, k, ta, tb = info["m"], info["n"], info["k"], info["a"], info["b"]
     A, B = _buf((n_tiles, m, k), ta, dev), _buf((n_tiles, n, k), tb, dev)
-    C, Dhw, D = (_buf((n_tiles, m, n), mm.FP32, dev) for _ in range(3))
+    tc = mm.FP64 if ta == mm.FP64 else mm.FP32            # the binary64 forms accumulate in binary64
+    C, Dhw, D = (_buf((n_tiles, m, n), tc, dev) for _ in range(3))
     h = mm.model_create(**model_kwargs)
     fams = validation_families(ta, tb)
     stats = {name: _stats_buf(dev) for name, _, _, _ in fams}
@@ -518,10 +525,10 @@ def validate_against_mfma(instr, model_kwargs, n_tiles=4096, seeds=(0,), dev="cu
             for seed in seeds:
                 mm.generate(A, ta, m * k, 0, n_tiles, seed=seed, operand=0, **ga)
                 mm.generate(B, tb, n * k, 0, n_tiles, seed=seed, operand=1, **gb)
-                mm.generate(C, mm.FP32, m * n, 0, n_tiles, seed=seed, operand=2, **gc)
+                mm.generate(C, tc, m * n, 0, n_tiles, seed=seed, operand=2, **gc)
                 mm.mfma_probe(instr, A, B, C, Dhw, k, n_tiles)
-                mm.emulate_mma(h, A, B, C, D, m, n, k, n_tiles, (ta, tb, mm.FP32, mm.FP32))
-                mm.compare(D, Dhw, n_tiles * m * n, stats[name])
+                mm.emulate_mma(h, A, B, C, D, m, n, k, n_tiles, (ta, tb, tc, tc))
+                mm.compare(D, Dhw, n_tiles * m * n, stats[name], d=tc)
 
     _, secs = _timed(run)
     kernel = mm.last_kernel()

@@ -259,6 +259,20 @@ static mmaemu_status emulate_impl(const mmaemu_model *model, const void *A, cons
     if (!model || model->magic != MODEL_MAGIC) { set_error("emulate_mma: bad model handle"); return MMAEMU_ERR_INVALID_ARG; }
     if (m == 0 || n == 0 || k == 0) { set_error("emulate_mma: zero dimension (m=%u n=%u k=%u)", m, n, k); return MMAEMU_ERR_SHAPE; }
     if (k > (1u << 20)) { set_error("emulate_mma: k=%u > 2^20", k); return MMAEMU_ERR_SHAPE; }
+    if (dt.a == MMAEMU_FP64 || dt.b == MMAEMU_FP64 || dt.c == MMAEMU_FP64 || dt.d == MMAEMU_FP64) {
+        // binary64 is the other format Algorithms "FMA" / "Phi_FMA" name: that family only, all four arrays binary64
+        const mmaemu_model_params &mq = model->params;
+        if (mq.family != MMAEMU_FAMILY_FMA || dt.a != MMAEMU_FP64 || dt.b != MMAEMU_FP64 || dt.c != MMAEMU_FP64 || dt.d != MMAEMU_FP64 || SA) {
+            set_error("emulate_mma: FP64 arrays go with the FMA family, all four of them FP64, unscaled");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        const uint64_t mn_ = (uint64_t)m * n;
+        if (batch && (mn_ > (1ull << 40) || batch > (1ull << 62) / mn_ || batch * mn_ > (1ull << 48))) { set_error("emulate_mma: problem too large"); return MMAEMU_ERR_SHAPE; }
+        if (batch == 0) return MMAEMU_OK;
+        if (!A || !B || !C || !D) { set_error("emulate_mma: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
+        if (((uintptr_t)A | (uintptr_t)B | (uintptr_t)C | (uintptr_t)D) & 7) { set_error("emulate_mma: pointers must be aligned to their element size"); return MMAEMU_ERR_INVALID_ARG; }
+        return launch_emulate_fma64(A, B, C, D, m, n, k, batch, mq.nan_bits, mq.nan_propagate != 0, (hipStream_t)hip_stream);
+    }
     if (dt.a > MMAEMU_TF32 || dt.b > MMAEMU_TF32 || dt.c > MMAEMU_FP32 || dt.d > MMAEMU_FP32) {
         set_error("emulate_mma: dtype out of range");
         return MMAEMU_ERR_INVALID_ARG;
@@ -536,13 +550,14 @@ mmaemu_status mmaemu_stats_reset(mmaemu_stats *st, void *hip_stream)
 mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uint64_t index_base, mmaemu_dtype d,
                              mmaemu_stats *st, void *hip_stream)
 {
-    if (d != MMAEMU_FP32 && d != MMAEMU_FP16) { set_error("compare: FP32 or FP16 outputs"); return MMAEMU_ERR_UNSUPPORTED; }
-    const uintptr_t amask = d == MMAEMU_FP32 ? 3 : 1;
+    if (d != MMAEMU_FP32 && d != MMAEMU_FP16 && d != MMAEMU_FP64) { set_error("compare: FP32, FP16 or FP64 outputs"); return MMAEMU_ERR_UNSUPPORTED; }
+    const uintptr_t amask = d == MMAEMU_FP64 ? 7 : (d == MMAEMU_FP32 ? 3 : 1);
     if (!st) { set_error("compare: NULL stats"); return MMAEMU_ERR_INVALID_ARG; }
     if (count == 0) return MMAEMU_OK;
     if (!D0 || !D1) { set_error("compare: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
     if (((uintptr_t)D0 | (uintptr_t)D1) & amask) { set_error("compare: pointers must be aligned to the element size"); return MMAEMU_ERR_INVALID_ARG; }
     if (count > (1ull << 48)) { set_error("compare: count too large"); return MMAEMU_ERR_SHAPE; }
+    if (d == MMAEMU_FP64) return launch_compare64(D0, D1, count, index_base, st, (hipStream_t)hip_stream);
     return launch_compare(D0, D1, count, index_base, d == MMAEMU_FP16, st, (hipStream_t)hip_stream);
 }
 
@@ -557,9 +572,32 @@ static mmaemu_status generate_check(const mmaemu_gen_params *g, void *out, mmaem
         return MMAEMU_ERR_INVALID_ARG;
     }
     if (dtype == MMAEMU_TF32) { set_error("generate: TF32 streams are FP32 streams (generate MMAEMU_FP32)"); return MMAEMU_ERR_UNSUPPORTED; }
-    if ((uint32_t)dtype > MMAEMU_FP4_E2M1 || g->family > MMAEMU_GEN_SIGNED_ZEROS || g->scale_scope > MMAEMU_SCALE_FACTOR) {
+    if (((uint32_t)dtype > MMAEMU_FP4_E2M1 && dtype != MMAEMU_FP64) || g->family > MMAEMU_GEN_SIGNED_ZEROS || g->scale_scope > MMAEMU_SCALE_FACTOR) {
         set_error("generate: enum out of range");
         return MMAEMU_ERR_INVALID_ARG;
+    }
+    if (dtype == MMAEMU_FP64) {
+        // binary64 output: the value families unscaled or times a constant, and the bit families that have a 64-bit reading
+        const bool value_family = g->family == MMAEMU_GEN_NORMAL || g->family == MMAEMU_GEN_UNIFORM || g->family == MMAEMU_GEN_NORMAL_OUTLIERS;
+        if (g->family == MMAEMU_GEN_CANCELLING || (value_family && (g->scale_scope == MMAEMU_SCALE_TENSOR || g->scale_scope == MMAEMU_SCALE_TILE))) {
+            set_error("generate: FP64 output takes no CANCELLING family and no per-tensor / per-tile scaling");
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        if (ept == 0) { set_error("generate: elems_per_tile = 0"); return MMAEMU_ERR_SHAPE; }
+        if (n_tiles > (1ull << 61) / ept || first_tile > (1ull << 61) / ept || (first_tile + n_tiles) > (1ull << 61) / ept) {
+            set_error("generate: element index range too large");
+            return MMAEMU_ERR_SHAPE;
+        }
+        if (g->family == MMAEMU_GEN_UNIFORM_EXP && (g->exp_lo > g->exp_hi || g->exp_hi > 2047u)) {
+            set_error("generate: exponent-field range %u..%u outside 0..2047", g->exp_lo, g->exp_hi);
+            return MMAEMU_ERR_UNSUPPORTED;
+        }
+        if (value_family && g->scale_scope != MMAEMU_SCALE_NONE && !(g->scale_target > 0.0)) { set_error("generate: scale_target must be positive"); return MMAEMU_ERR_INVALID_ARG; }
+        if (n_tiles == 0) return MMAEMU_OK;
+        if (!out) { set_error("generate: NULL output"); return MMAEMU_ERR_INVALID_ARG; }
+        if ((uintptr_t)out & 7) { set_error("generate: output not aligned to its element size"); return MMAEMU_ERR_INVALID_ARG; }
+        *run = true;
+        return MMAEMU_OK;
     }
     if (dtype == MMAEMU_E8M0 && g->family != MMAEMU_GEN_ZERO && g->family != MMAEMU_GEN_RANDOM_BITS &&
         g->family != MMAEMU_GEN_UNIFORM_EXP) {
@@ -633,7 +671,16 @@ static bool is_scaled_instr(uint32_t i)
 mmaemu_status mmaemu_mfma_info(mmaemu_mfma_instr instr, uint32_t *m, uint32_t *n, uint32_t *k_native, mmaemu_dtype *a,
                                mmaemu_dtype *b)
 {
-    if ((uint32_t)instr >= MMAEMU_MFMA_F32_32X32X4_2B_F16 && (uint32_t)instr < MMAEMU_MFMA_COUNT) {     // multi-block forms
+    if ((uint32_t)instr == MMAEMU_MFMA_F64_16X16X4_F64 || (uint32_t)instr == MMAEMU_MFMA_F64_4X4X4_4B_F64) {
+        const uint32_t mm_ = (uint32_t)instr == MMAEMU_MFMA_F64_16X16X4_F64 ? 16u : 4u;
+        if (m) *m = mm_;
+        if (n) *n = mm_;
+        if (k_native) *k_native = 4;
+        if (a) *a = MMAEMU_FP64;
+        if (b) *b = MMAEMU_FP64;
+        return MMAEMU_OK;
+    }
+    if ((uint32_t)instr >= MMAEMU_MFMA_F32_32X32X4_2B_F16 && (uint32_t)instr <= MMAEMU_MFMA_F32_4X4X1_16B_F32) {     // multi-block forms
         const uint32_t q = (uint32_t)instr - MMAEMU_MFMA_F32_32X32X4_2B_F16, shape = q % 3, type = q / 3;
         const uint32_t mm_ = shape == 0 ? 32u : (shape == 1 ? 16u : 4u);
         if (m) *m = mm_;
@@ -701,8 +748,9 @@ mmaemu_status mmaemu_mfma_probe(mmaemu_mfma_instr instr, const void *A, const vo
     if (batch > (1ull << 40)) { set_error("mfma_probe: batch too large"); return MMAEMU_ERR_SHAPE; }
     if (batch == 0) return MMAEMU_OK;
     if (!A || !B || !C || !D) { set_error("mfma_probe: NULL device pointer"); return MMAEMU_ERR_INVALID_ARG; }
-    const uintptr_t ab_align = (uintptr_t)(fmt_info(ta).width / 8 - 1);
-    if (((uintptr_t)A | (uintptr_t)B) & ab_align || ((uintptr_t)C | (uintptr_t)D) & 3) {
+    const bool f64 = ta == MMAEMU_FP64;
+    const uintptr_t ab_align = f64 ? 7 : (uintptr_t)(fmt_info(ta).width / 8 - 1);
+    if (((uintptr_t)A | (uintptr_t)B) & ab_align || ((uintptr_t)C | (uintptr_t)D) & (f64 ? 7 : 3)) {
         set_error("mfma_probe: misaligned pointer");
         return MMAEMU_ERR_INVALID_ARG;
     }

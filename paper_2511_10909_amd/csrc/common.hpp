@@ -112,6 +112,9 @@ mmaemu_status launch_emulate_addmul(const ModelArgs &p, const void *A, const voi
 // Algorithm "Phi_FMA": binary32 operands and accumulators, a chain of fused multiply-adds in k order
 mmaemu_status launch_emulate_fma(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
                                  uint64_t batch, uint32_t nan_bits, bool nan_propagate, hipStream_t s);
+// the same chain on binary64 patterns (one v_fma_f64 per step)
+mmaemu_status launch_emulate_fma64(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                                   uint64_t batch, uint32_t nan_bits, bool nan_propagate, hipStream_t s);
 // Algorithm "GST-FDPA": FP4 operands, scale codes SA / SB per `block` elements (L, G, F, rho, NaN pattern, scale format)
 struct GstArgs { uint32_t L, G, block, F, out_round, scale_format, nan_bits; };
 mmaemu_status launch_emulate_gst(const GstArgs &g, const void *A, const void *B, const void *C, void *D, const uint8_t *SA,
@@ -119,6 +122,7 @@ mmaemu_status launch_emulate_gst(const GstArgs &g, const void *A, const void *B,
 mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s);
 mmaemu_status launch_compare(const void *d0, const void *d1, uint64_t count, uint64_t base, bool half,
                              mmaemu_stats *st, hipStream_t s);
+mmaemu_status launch_compare64(const void *d0, const void *d1, uint64_t count, uint64_t base, mmaemu_stats *st, hipStream_t s);
 mmaemu_status launch_generate(const mmaemu_gen_params &g, void *out, uint32_t dtype, uint64_t ept,
                               uint64_t first_tile, uint64_t n_tiles, void *workspace, hipStream_t s);
 // the same with the running maximum of the per-tensor scaling in the library's own static device array

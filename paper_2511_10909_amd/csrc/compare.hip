@@ -67,17 +67,79 @@ __device__ __forceinline__ void one_vector(const uint4 &x, const uint4 &y, uint6
     }
 }
 
+// per-workgroup state in LDS
+struct WgStats {
+    uint32_t hist[34 * 32];
+    uint32_t mism, nan_equiv;
+    unsigned long long first, maxd;
+    uint32_t tot[34];
+};
+
+__device__ __forceinline__ void wg_init(WgStats &ws)
+{
+    for (uint32_t i = threadIdx.x; i < 34 * 32; i += blockDim.x) ws.hist[i] = 0;
+    if (threadIdx.x == 0) { ws.mism = 0; ws.nan_equiv = 0; ws.first = ~0ull; ws.maxd = 0; }
+    __syncthreads();
+}
+
+// lanes -> wavefront -> workgroup -> the caller's struct
+__device__ __forceinline__ void wg_flush(WgStats &ws, Local lc, uint64_t count, mmaemu_stats *st)
+{
+    // one set of LDS atomics per wavefront, not per lane: 64 lanes on one address take 64 turns
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        lc.mism += __shfl_xor(lc.mism, o);
+        lc.nan_equiv += __shfl_xor(lc.nan_equiv, o);
+        const unsigned long long f = __shfl_xor((unsigned long long)lc.first, o), d = __shfl_xor((unsigned long long)lc.maxd, o);
+        lc.first = f < lc.first ? f : lc.first;
+        lc.maxd = d > lc.maxd ? d : lc.maxd;
+    }
+    if ((threadIdx.x & 63u) == 0) {
+        if (lc.mism) {
+            atomicAdd(&ws.mism, lc.mism);
+            atomicMin(&ws.first, (unsigned long long)lc.first);
+        }
+        if (lc.nan_equiv) atomicAdd(&ws.nan_equiv, lc.nan_equiv);
+        if (lc.maxd) atomicMax(&ws.maxd, (unsigned long long)lc.maxd);
+    }
+    __syncthreads();
+
+    unsigned long long *g = reinterpret_cast<unsigned long long *>(st);
+    if (threadIdx.x < 34) {
+        uint32_t t = 0;
+        for (int cpy = 0; cpy < 32; ++cpy) t += ws.hist[threadIdx.x * 32 + cpy];
+        ws.tot[threadIdx.x] = t;
+        if (threadIdx.x >= 1 && t) atomicAdd(&g[5 + threadIdx.x], (unsigned long long)t);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t nonzero = 0;
+        for (int b = 1; b < 34; ++b) nonzero += ws.tot[b];
+        // n_compared and bucket 0 are known up front: workgroup 0 adds the whole count once,
+        // every workgroup takes its non-zero buckets back out of bucket 0 (sums are modular,
+        // so the order does not matter); equal inputs then cost no further atomics at all
+        if (blockIdx.x == 0) {
+            atomicAdd(&g[0], (unsigned long long)count);
+            atomicAdd(&g[5 + 0], (unsigned long long)count);
+        }
+        if (nonzero) atomicAdd(&g[5 + 0], 0ull - (unsigned long long)nonzero);
+        if (ws.mism) {
+            atomicAdd(&g[1], (unsigned long long)ws.mism);
+            atomicMin(&g[3], ws.first);
+        }
+        if (ws.nan_equiv) atomicAdd(&g[2], (unsigned long long)ws.nan_equiv);
+        if (ws.maxd) atomicMax(&g[4], ws.maxd);
+    }
+}
+
 template <int W, typename T>
 __global__ void __launch_bounds__(1024)
 compare_kernel(const T *__restrict__ d0, const T *__restrict__ d1, uint64_t count, uint64_t base, mmaemu_stats *st)
 {
     constexpr uint32_t EPV = 128 / W;                    // elements per 128-bit load
-    __shared__ uint32_t hist[34 * 32];
-    __shared__ uint32_t s_mism, s_nan;
-    __shared__ unsigned long long s_first, s_maxd;
-    for (uint32_t i = threadIdx.x; i < 34 * 32; i += blockDim.x) hist[i] = 0;
-    if (threadIdx.x == 0) { s_mism = 0; s_nan = 0; s_first = ~0ull; s_maxd = 0; }
-    __syncthreads();
+    __shared__ WgStats ws;
+    wg_init(ws);
+    uint32_t *hist = ws.hist;
 
     Local lc = {0, 0, ~0ull, 0};
     const uint64_t nvec = count / EPV;
@@ -98,57 +160,68 @@ compare_kernel(const T *__restrict__ d0, const T *__restrict__ d1, uint64_t coun
         for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride)
             one_pair<W>(d0[i], d1[i], base + i, lc, hist);
     }
-    // one set of LDS atomics per wavefront, not per lane: 64 lanes on one address take 64 turns
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        lc.mism += __shfl_xor(lc.mism, o);
-        lc.nan_equiv += __shfl_xor(lc.nan_equiv, o);
-        const unsigned long long f = __shfl_xor((unsigned long long)lc.first, o), d = __shfl_xor((unsigned long long)lc.maxd, o);
-        lc.first = f < lc.first ? f : lc.first;
-        lc.maxd = d > lc.maxd ? d : lc.maxd;
-    }
-    if ((threadIdx.x & 63u) == 0) {
-        if (lc.mism) {
-            atomicAdd(&s_mism, lc.mism);
-            atomicMin(&s_first, (unsigned long long)lc.first);
-        }
-        if (lc.nan_equiv) atomicAdd(&s_nan, lc.nan_equiv);
-        if (lc.maxd) atomicMax(&s_maxd, (unsigned long long)lc.maxd);
-    }
-    __syncthreads();
+    wg_flush(ws, lc, count, st);
+}
 
-    unsigned long long *g = reinterpret_cast<unsigned long long *>(st);
-    __shared__ uint32_t tot[34];
-    if (threadIdx.x < 34) {
-        uint32_t t = 0;
-        for (int cpy = 0; cpy < 32; ++cpy) t += hist[threadIdx.x * 32 + cpy];
-        tot[threadIdx.x] = t;
-        if (threadIdx.x >= 1 && t) atomicAdd(&g[5 + threadIdx.x], (unsigned long long)t);
+// binary64 patterns: the same statistics; the ordered distance can take 64 bits, and the last distance bucket (32) also
+// holds everything from 2^32 upward
+__device__ __forceinline__ void one_pair64(uint64_t x, uint64_t y, uint64_t idx, Local &lc, uint32_t *hist)
+{
+    constexpr uint64_t MAG = 0x7FFFFFFFFFFFFFFFull, INF = 0x7FF0000000000000ull;
+    const bool nx = (x & MAG) > INF, ny = (y & MAG) > INF;
+    uint32_t bucket;
+    if (x != y) {
+        lc.mism += 1;
+        lc.first = idx < lc.first ? idx : lc.first;
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t nonzero = 0;
-        for (int b = 1; b < 34; ++b) nonzero += tot[b];
-        // n_compared and bucket 0 are known up front: workgroup 0 adds the whole count once,
-        // every workgroup takes its non-zero buckets back out of bucket 0 (sums are modular,
-        // so the order does not matter); equal inputs then cost no further atomics at all
-        if (blockIdx.x == 0) {
-            atomicAdd(&g[0], (unsigned long long)count);
-            atomicAdd(&g[5 + 0], (unsigned long long)count);
-        }
-        if (nonzero) atomicAdd(&g[5 + 0], 0ull - (unsigned long long)nonzero);
-        if (s_mism) {
-            atomicAdd(&g[1], (unsigned long long)s_mism);
-            atomicMin(&g[3], s_first);
-        }
-        if (s_nan) atomicAdd(&g[2], (unsigned long long)s_nan);
-        if (s_maxd) atomicMax(&g[4], s_maxd);
+    if (nx || ny) {
+        bucket = (nx && ny) ? 0u : 33u;
+        if (nx && ny && x != y) lc.nan_equiv += 1;
+    } else {
+        // |key(x) - key(y)| without leaving 64 bits: same sign: difference of the magnitudes; else their sum (< 2^64)
+        const uint64_t ax = x & MAG, ay = y & MAG;
+        const uint64_t dist = ((x ^ y) >> 63) ? ax + ay : (ax > ay ? ax - ay : ay - ax);
+        lc.maxd = dist > lc.maxd ? dist : lc.maxd;
+        const uint32_t bl = dist ? 64u - (uint32_t)__builtin_clzll(dist) : 0u;
+        bucket = bl > 32u ? 32u : bl;
     }
+    if (bucket) atomicAdd(&hist[bucket * 32u + (threadIdx.x & 31u)], 1u);
+}
+
+__global__ void __launch_bounds__(1024)
+compare64_kernel(const uint64_t *__restrict__ d0, const uint64_t *__restrict__ d1, uint64_t count, uint64_t base, mmaemu_stats *st)
+{
+    __shared__ WgStats ws;
+    wg_init(ws);
+    Local lc = {0, 0, ~0ull, 0};
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    const uint64_t nvec = count / 2;
+    if (((reinterpret_cast<uintptr_t>(d0) | reinterpret_cast<uintptr_t>(d1)) & 15) == 0) {
+        const ulonglong2 *v0 = reinterpret_cast<const ulonglong2 *>(d0), *v1 = reinterpret_cast<const ulonglong2 *>(d1);
+        for (uint64_t v = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; v < nvec; v += stride) {
+            const ulonglong2 x = v0[v], y = v1[v];
+            one_pair64(x.x, y.x, base + 2 * v, lc, ws.hist);
+            one_pair64(x.y, y.y, base + 2 * v + 1, lc, ws.hist);
+        }
+        if ((count & 1) && blockIdx.x == 0 && threadIdx.x == 0) one_pair64(d0[count - 1], d1[count - 1], base + count - 1, lc, ws.hist);
+    } else {
+        for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += stride) one_pair64(d0[i], d1[i], base + i, lc, ws.hist);
+    }
+    wg_flush(ws, lc, count, st);
 }
 
 mmaemu_status launch_stats_reset(mmaemu_stats *st, hipStream_t s)
 {
     hipLaunchKernelGGL(stats_reset_kernel, dim3(1), dim3(64), 0, s, st);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
+mmaemu_status launch_compare64(const void *d0, const void *d1, uint64_t count, uint64_t base, mmaemu_stats *st, hipStream_t s)
+{
+    uint64_t blocks = (count + 16383) / 16384;
+    blocks = blocks < 1 ? 1 : (blocks > 256 ? 256 : blocks);
+    hipLaunchKernelGGL(compare64_kernel, dim3((uint32_t)blocks), dim3(1024), 0, s, (const uint64_t *)d0, (const uint64_t *)d1, count, base, st);
     MMAEMU_HIP(hipGetLastError());
     return MMAEMU_OK;
 }

@@ -245,6 +245,107 @@ static mmaemu_status launch_p(const void *A, const void *B, const void *C, void 
     return launch_v<PROPAGATE, false, 1>(A, B, C, D, m, n, k, batch, nan_bits, s);
 }
 
+// ---- binary64 (Algorithms "FMA" / "Phi_FMA" with F = FP64) ----------------------------------------------------------------
+// v_fma_f64 is the standard's operation on binary64 (subnormals always kept), so a step is again one instruction plus the
+// model's NaN rule.  The model's NaN pattern is a binary32 word; here it is widened the way a conversion between the
+// formats widens a NaN: sign, exponent field all ones, the 23 mantissa bits at the top of the 52.
+__device__ __forceinline__ bool is_nan64(uint64_t b) { return (b & 0x7FFFFFFFFFFFFFFFull) > 0x7FF0000000000000ull; }
+__device__ __forceinline__ bool is_inf64(uint64_t b) { return (b & 0x7FFFFFFFFFFFFFFFull) == 0x7FF0000000000000ull; }
+__device__ __forceinline__ bool is_zero64(uint64_t b) { return (b & 0x7FFFFFFFFFFFFFFFull) == 0ull; }
+
+template <bool PROPAGATE>
+__device__ __forceinline__ uint64_t fma_step64(uint64_t x, uint64_t y, uint64_t d, uint64_t nan64)
+{
+    uint64_t r = (uint64_t)__double_as_longlong(__builtin_fma(__longlong_as_double((long long)x), __longlong_as_double((long long)y),
+                                                              __longlong_as_double((long long)d)));
+    if (is_nan64(r)) {
+        r = nan64;
+        if (PROPAGATE) {
+            constexpr uint64_t QUIET = 1ull << 51;
+            if (is_nan64(x)) r = x | QUIET;
+            else if (is_nan64(y)) r = y | QUIET;
+            else if ((is_inf64(x) && is_zero64(y)) || (is_inf64(y) && is_zero64(x))) r = nan64;
+            else if (is_nan64(d)) r = d | QUIET;
+        }
+    }
+    return r;
+}
+
+// One thread per output; a workgroup owns a 16x16 block of D when m and n allow (a wavefront then shares 4 rows of A and
+// 16 of B), else 256 outputs in row-major order.  VEC2: k even and 16-byte aligned rows: two k per load.
+template <bool PROPAGATE, bool BLOCKED, bool VEC2>
+__global__ void __launch_bounds__(256)
+emulate_fma64_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B, const uint64_t *C, uint64_t *D, uint32_t m,
+                     uint32_t n, uint32_t k, uint64_t total, uint64_t nblocks, uint64_t nan64)
+{
+    const uint64_t mn = (uint64_t)m * n;
+    for (uint64_t w = blockIdx.x; w < nblocks; w += gridDim.x) {
+        uint64_t t;
+        uint32_t i, j;
+        if (BLOCKED) {
+            const uint32_t bpr = n / 16u;
+            const uint64_t bpt = (uint64_t)(m / 16u) * bpr;
+            t = w / bpt;
+            const uint32_t r = (uint32_t)(w - t * bpt);
+            i = 16u * (r / bpr) + threadIdx.x / 16u;
+            j = 16u * (r % bpr) + threadIdx.x % 16u;
+        } else {
+            const uint64_t o = w * 256u + threadIdx.x;
+            if (o >= total) continue;
+            t = o / mn;
+            const uint32_t r = (uint32_t)(o - t * mn);
+            i = r / n;
+            j = r - i * n;
+        }
+        const uint64_t o = t * mn + (uint64_t)i * n + j;
+        const uint64_t *a = A + (t * m + i) * (uint64_t)k;
+        const uint64_t *b = B + (t * n + j) * (uint64_t)k;
+        uint64_t d = C[o];
+        if (VEC2) {
+            for (uint32_t k0 = 0; k0 < k; k0 += 2) {
+                const ulonglong2 x = *reinterpret_cast<const ulonglong2 *>(a + k0), y = *reinterpret_cast<const ulonglong2 *>(b + k0);
+                d = fma_step64<PROPAGATE>(x.x, y.x, d, nan64);
+                d = fma_step64<PROPAGATE>(x.y, y.y, d, nan64);
+            }
+        } else {
+            for (uint32_t kk = 0; kk < k; ++kk) d = fma_step64<PROPAGATE>(a[kk], b[kk], d, nan64);
+        }
+        D[o] = d;
+    }
+}
+
+template <bool PROPAGATE, bool BLOCKED, bool VEC2>
+static mmaemu_status launch64_v(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                                uint64_t batch, uint64_t nan64, hipStream_t s)
+{
+    const uint64_t total = batch * m * n;
+    const uint64_t nblocks = (total + 255) / 256;
+    const uint64_t grid = nblocks < 16384 ? nblocks : 16384;
+    hipLaunchKernelGGL((emulate_fma64_kernel<PROPAGATE, BLOCKED, VEC2>), dim3((uint32_t)grid), dim3(256), 0, s, (const uint64_t *)A,
+                       (const uint64_t *)B, (const uint64_t *)C, (uint64_t *)D, m, n, k, total, nblocks, nan64);
+    MMAEMU_HIP(hipGetLastError());
+    set_last_kernel("fma chain fp64%s%s%s", PROPAGATE ? ", payloads" : "", BLOCKED ? ", 16x16 blocks" : "", VEC2 ? ", 128-bit loads" : "");
+    return MMAEMU_OK;
+}
+
+mmaemu_status launch_emulate_fma64(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                                   uint64_t batch, uint32_t nan_bits, bool nan_propagate, hipStream_t s)
+{
+    const uint64_t nan64 = ((uint64_t)(nan_bits >> 31) << 63) | 0x7FF0000000000000ull | ((uint64_t)(nan_bits & 0x7FFFFFu) << 29);
+    const bool blocked = m % 16 == 0 && n % 16 == 0;
+    const bool vec2 = k % 2 == 0 && ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0;
+#define GO(P, BL, V) return launch64_v<P, BL, V>(A, B, C, D, m, n, k, batch, nan64, s)
+    if (nan_propagate) {
+        if (blocked) { if (vec2) GO(true, true, true); GO(true, true, false); }
+        if (vec2) GO(true, false, true);
+        GO(true, false, false);
+    }
+    if (blocked) { if (vec2) GO(false, true, true); GO(false, true, false); }
+    if (vec2) GO(false, false, true);
+    GO(false, false, false);
+#undef GO
+}
+
 mmaemu_status launch_emulate_fma(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
                                  uint64_t batch, uint32_t nan_bits, bool nan_propagate, hipStream_t s)
 {

@@ -437,9 +437,102 @@ static mmaemu_status launch_typed(const GenArgs &ga, void *out, uint64_t ept, ui
     return MMAEMU_OK;
 }
 
+// ---- binary64 output ------------------------------------------------------------------------
+// Value families: the binary64 value itself (times scale_target under SCALE_FACTOR), one word per element as for every
+// other format.  Bit families: element g owns the words 2g (low half) and 2g + 1 (high half), so a Philox block holds
+// two elements:
+//   RANDOM_BITS   hi:lo
+//   FINITE_BITS   v = floor(hi:lo * 2 nmag / 2^64), nmag = 2047 * 2^52 finite magnitudes; sign = v >= nmag
+//   UNIFORM_EXP   sign = hi bit 31; exponent field from hi's low 31 bits as for FP32; mantissa = (hi's low 20 bits):lo
+//   SIGNED_ZEROS  decided by hi as for the other formats
+__global__ void __launch_bounds__(256)
+gen_bits64_kernel(GenArgs g, uint64_t *out, uint64_t g0, uint64_t total, uint64_t blk0, uint64_t nblk)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= nblk) return;
+    const uint64_t blk = blk0 + t;
+    uint32_t w[4];
+    block_words(g, blk, w);
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint64_t e = 2 * blk + j;
+        if (e < g0 || e - g0 >= total) continue;
+        const uint32_t lo = w[2 * j], hi = w[2 * j + 1];
+        uint64_t v;
+        if (g.family == MMAEMU_GEN_RANDOM_BITS) v = ((uint64_t)hi << 32) | lo;
+        else if (g.family == MMAEMU_GEN_FINITE_BITS) {
+            constexpr uint64_t NMAG = 2047ull << 52;
+            const uint64_t u = __umul64hi(((uint64_t)hi << 32) | lo, 2ull * NMAG);
+            const uint64_t sign = u >= NMAG;
+            v = (sign << 63) | (u - sign * NMAG);
+        } else if (g.family == MMAEMU_GEN_SIGNED_ZEROS) {
+            const uint32_t kind = hi >> 30;
+            const uint64_t mag = kind == 2u ? (1023ull << 52) : (kind == 3u ? 1ull : 0ull);
+            v = ((uint64_t)((hi >> 29) & 1u) << 63) | mag;
+        } else {                                                     // UNIFORM_EXP
+            const uint32_t idx = (uint32_t)(((uint64_t)(hi & 0x7FFFFFFFu) * g.nchoices) >> 31);
+            const uint64_t E = g.exp_zero ? (idx == 0 ? 0u : g.exp_lo + idx - 1u) : g.exp_lo + idx;
+            v = ((uint64_t)(hi >> 31) << 63) | (E << 52) | ((uint64_t)(hi & 0xFFFFFu) << 32) | lo;
+        }
+        out[e - g0] = v;
+    }
+}
+
+__global__ void __launch_bounds__(256)
+gen_normal64_kernel(GenArgs g, uint64_t *out, uint64_t g0, uint64_t total, uint64_t blk0, uint64_t nblk)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= nblk) return;
+    double z[4];
+    block_normals(g, blk0 + t, z);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const uint64_t e = 4 * (blk0 + t) + j;
+        if (e < g0 || e - g0 >= total) continue;
+        const double v = g.scale_scope == MMAEMU_SCALE_FACTOR ? z[j] * g.scale_target : z[j];
+        out[e - g0] = (uint64_t)__double_as_longlong(v);
+    }
+}
+
+static mmaemu_status launch_generate64(const GenArgs &ga, void *out, uint64_t ept, uint64_t first_tile, uint64_t n_tiles, hipStream_t s)
+{
+    const uint64_t g0 = first_tile * ept, total = n_tiles * ept;
+    const bool value_family = ga.family == MMAEMU_GEN_NORMAL || ga.family == MMAEMU_GEN_UNIFORM || ga.family == MMAEMU_GEN_NORMAL_OUTLIERS;
+    const uint64_t wpe = value_family ? 1 : 2;
+    const uint64_t blk0 = (g0 * wpe) >> 2, nblk = (((g0 + total) * wpe - 1) >> 2) - blk0 + 1;
+    const uint64_t grid = (nblk + 255) / 256;
+    if (grid > 0x7FFFFFFFull) { set_error("generate: too many elements for one call"); return MMAEMU_ERR_SHAPE; }
+    if (value_family) hipLaunchKernelGGL(gen_normal64_kernel, dim3((uint32_t)grid), dim3(256), 0, s, ga, (uint64_t *)out, g0, total, blk0, nblk);
+    else hipLaunchKernelGGL(gen_bits64_kernel, dim3((uint32_t)grid), dim3(256), 0, s, ga, (uint64_t *)out, g0, total, blk0, nblk);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
 mmaemu_status launch_generate(const mmaemu_gen_params &gp, void *out, uint32_t dtype, uint64_t ept,
                               uint64_t first_tile, uint64_t n_tiles, void *workspace, hipStream_t s)
 {
+    if (dtype == MMAEMU_FP64) {
+        const uint64_t total64 = n_tiles * ept;
+        if (gp.family == MMAEMU_GEN_ZERO) {
+            uint64_t grid = (2 * total64 + 255) / 256;
+            grid = grid < 1 ? 1 : (grid > 4096 ? 4096 : grid);
+            hipLaunchKernelGGL(zero_kernel, dim3((uint32_t)grid), dim3(256), 0, s, (uint32_t *)out, 2 * total64, (uint8_t *)out, 0u);
+            MMAEMU_HIP(hipGetLastError());
+            return MMAEMU_OK;
+        }
+        GenArgs g64 = {};
+        g64.family = gp.family;
+        g64.operand = gp.operand;
+        g64.k0 = (uint32_t)gp.seed;
+        g64.k1 = (uint32_t)(gp.seed >> 32);
+        g64.exp_lo = gp.exp_lo;
+        g64.exp_zero = gp.exp_zero ? 1u : 0u;
+        g64.nchoices = gp.exp_hi - gp.exp_lo + 1u + g64.exp_zero;
+        g64.dtype = dtype;
+        g64.scale_scope = gp.scale_scope;
+        g64.scale_target = gp.scale_target;
+        return launch_generate64(g64, out, ept, first_tile, n_tiles, s);
+    }
     const FmtInfo f = fmt_info(dtype);
     const uint64_t total = n_tiles * ept;
     if (gp.family == MMAEMU_GEN_ZERO) {

@@ -237,6 +237,61 @@ mfma_multiblock_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict_
     }
 }
 
+// ---- binary64 forms ----------------------------------------------------------------------------------------------------
+// Register layout (one-hot operands on raw registers, then fixed by exact small-integer tests), l = lane:
+//   16x16x4:    A row i = l % 16, k = l / 16 (same for B with column j); C/D register r: row 4 r + l / 16, column l % 16
+//               (the rows of a lane are 4 apart, where the binary32 forms hold 4 consecutive rows)
+//   4x4x4_4b:   A row i = l % 4 of block (l / 4) % 4, k = l / 16 (same for B); C/D: block (l / 4) % 4, row l / 16, column l % 4
+typedef double v4f64 __attribute__((ext_vector_type(4)));
+
+template <int M>
+__global__ void __launch_bounds__(256)
+mfma_f64_kernel(const double *__restrict__ A, const double *__restrict__ B, const double *C, double *D, uint32_t k, uint64_t batch)
+{
+    constexpr int NB = M == 16 ? 1 : 4;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t wave = ((uint64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const uint64_t nwaves = ((uint64_t)gridDim.x * blockDim.x) >> 6;
+    const uint64_t issues = (batch + NB - 1) / NB;
+    for (uint64_t w = wave; w < issues; w += nwaves) {
+        const uint32_t kk = lane / 16u;
+        if constexpr (M == 16) {
+            const uint32_t rc = lane % 16u;
+            const double a = kk < k ? A[(w * 16 + rc) * (uint64_t)k + kk] : 0.0;
+            const double b = kk < k ? B[(w * 16 + rc) * (uint64_t)k + kk] : 0.0;
+            const double *c = C + w * 256u;
+            double *d = D + w * 256u;
+            v4f64 acc;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = c[(4 * r + kk) * 16 + rc];
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) d[(4 * r + kk) * 16 + rc] = acc[r];
+        } else {
+            const uint64_t t = w * 4 + (lane / 4u) % 4u;
+            const uint32_t rc = lane % 4u;
+            const bool live = t < batch;
+            const double a = live && kk < k ? A[(t * 4 + rc) * (uint64_t)k + kk] : 0.0;
+            const double b = live && kk < k ? B[(t * 4 + rc) * (uint64_t)k + kk] : 0.0;
+            double acc = live ? C[t * 16u + kk * 4u + rc] : 0.0;
+            acc = __builtin_amdgcn_mfma_f64_4x4x4f64(a, b, acc, 0, 0, 0);
+            if (live) D[t * 16u + kk * 4u + rc] = acc;
+        }
+    }
+}
+
+template <int M>
+static mmaemu_status launch_f64(const void *A, const void *B, const void *C, void *D, uint32_t k, uint64_t batch, hipStream_t s)
+{
+    const uint64_t issues = M == 16 ? batch : (batch + 3) / 4;
+    uint64_t blocks = (issues + 3) / 4;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipLaunchKernelGGL((mfma_f64_kernel<M>), dim3((uint32_t)blocks), dim3(256), 0, s, (const double *)A, (const double *)B,
+                       (const double *)C, (double *)D, k, batch);
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
 template <int M, int TYPE>
 static mmaemu_status launch_mb(const void *A, const void *B, const void *C, void *D, uint32_t k, uint64_t batch, hipStream_t s)
 {
@@ -294,6 +349,8 @@ mmaemu_status launch_mfma_probe(uint32_t instr, const void *A, const void *B, co
     case MMAEMU_MFMA_F32_32X32X1_2B_F32: return launch_mb<32, 2>(A, B, C, D, k, batch, s);
     case MMAEMU_MFMA_F32_16X16X1_4B_F32: return launch_mb<16, 2>(A, B, C, D, k, batch, s);
     case MMAEMU_MFMA_F32_4X4X1_16B_F32: return launch_mb<4, 2>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F64_16X16X4_F64: return launch_f64<16>(A, B, C, D, k, batch, s);
+    case MMAEMU_MFMA_F64_4X4X4_4B_F64: return launch_f64<4>(A, B, C, D, k, batch, s);
     default:
         set_error("unknown mfma instruction %u", instr);
         return MMAEMU_ERR_INVALID_ARG;
