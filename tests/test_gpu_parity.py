@@ -130,7 +130,8 @@ def test_emulate_argument_errors(mm):
                          ((h, x, x, x, x, 0, 4, 8, 1, dt), 3),
                          ((h, x, x, x, x, 4, 4, 8, 1, (fm.FP32, fm.FP16, fm.FP32, fm.FP32)), 2),
                          ((h, x, x, x, x, 4, 4, 8, 1, (fm.FP16, fm.FP16, fm.FP16, fm.FP32)), 2),
-                         ((h, x, x, x, x, 4, 4, 8, 1, (10, fm.FP16, fm.FP32, fm.FP32)), 1),
+                         ((h, x, x, x, x, 4, 4, 8, 1, (11, fm.FP16, fm.FP32, fm.FP32)), 1),
+                         ((h, x, x, x, x, 4, 4, 8, 1, (10, fm.FP16, fm.FP32, fm.FP32)), 2),      # binary64 goes with the FMA family only
                          ((h, x, x, x, x, 4, 4, 8, 1, (fm.TF32, fm.FP16, fm.FP32, fm.FP32)), 2),   # TF32 pairs with itself only
                          ((h, None, x, x, x, 4, 4, 8, 1, dt), 1)):
         with pytest.raises(mm.MmaemuError) as ei:
