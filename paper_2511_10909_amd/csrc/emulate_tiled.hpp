@@ -79,7 +79,8 @@ __device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b)
 // ---- decode while staging --------------------------------------------------------------
 
 // One element -> exact binary32 value (every supported operand value is a binary32 number)
-// and e' = max(E, 1) - 1, or the sentinel tag for NaN / infinities.  `wild` is raised by a
+// and e' = max(E, 1) - 1, or the sentinel tag for NaN / infinities (whose staged value is a NaN, or the infinity itself:
+// the sums of a group that meets one are not used, and special_products reads the group's classes off these values).  `wild` is raised by a
 // finite non-zero value outside [2^-31, 2^32), whose products may leave binary32 (BF16 only).
 // `zbias` (0, or ZBIAS when terms with a zero significand must not take part in exponent maxima):
 // a non-zero element's e' is raised by zbias and a zero element's e' is 0, so that a product with
@@ -99,21 +100,21 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, uint
         // the value is the pattern moved to the top half of a binary32 word
         const bool flushed = ftz_in && E == 0;                  // FlushSubnormal: -> +0.0
         val = __uint_as_float(flushed ? 0u : bits << 16);
-        if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
+        if (E == EMASK) ex = SENTINEL;                          // (the value stays the NaN or infinity it is)
         else wild |= !flushed && (bits & 0x7FFFu) != 0 && (E - 96u) > 62u;
     } else if (T == MMAEMU_TF32) {
         // (bits: the word without its 13 surplus bits) the value is the pattern moved back into place
         const bool flushed = ftz_in && E == 0;
         val = __uint_as_float(flushed ? 0u : bits << 13);
-        if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
+        if (E == EMASK) ex = SENTINEL;
         else wild |= !flushed && (bits & 0x3FFFFu) != 0 && (E - 96u) > 62u;
     } else if (T == MMAEMU_FP16) {
         _Float16 h;
         const uint16_t hb = (uint16_t)bits;
         __builtin_memcpy(&h, &hb, 2);
-        val = (float)h;                                          // exact, subnormals included
+        val = (float)h;                                          // exact, subnormals included; NaN and infinity as themselves
         if (ftz_in && E == 0) val = 0.0f;
-        if (E == EMASK) { ex = SENTINEL; val = 0.0f; }
+        if (E == EMASK) ex = SENTINEL;
     } else {
         uint32_t M = bits & MMASK, sign = (bits >> (F::EB + F::MB)) & 1u;
         const bool special = F::IEEE ? (E == EMASK) : (!F::NOSPEC && E == EMASK && M == MMASK);
@@ -121,7 +122,10 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, uint
         const uint32_t sig = E ? (M | (1u << F::MB)) : M;
         const float mag = ldexpf((float)sig, (int)(E ? E : 1u) - F::BIAS - F::MB);   // exact
         val = __uint_as_float(__float_as_uint(mag) | (sign << 31));
-        if (special) { ex = SENTINEL; val = 0.0f; }
+        if (special) {
+            ex = SENTINEL;
+            val = __uint_as_float((F::IEEE && M == 0) ? (0x7F800000u | (sign << 31)) : 0x7FC00000u);
+        }
     }
 }
 
@@ -464,6 +468,74 @@ __device__ __noinline__ BlockVals<R * C> special_block(const void *A, const void
     return out;
 }
 
+// The special values of Sec. 4.2 for the tagged outputs of a thread's R x C block, from the group's staged values
+// (binary32, or binary64 when DBL; a[r * SA + kk], b[c * SB + kk], kk < LEN; NaN and infinite elements are staged as
+// themselves, flushed ones as zeros).  IEEE multiplication of the staged values classifies every product:
+// NaN for a NaN operand and for infinity times zero, an infinity of the product's sign for an infinite operand; with
+// `overflow_rule` (TR-FDPA: a finite product of magnitude 2^128 or more counts as an infinity) the threshold moves from
+// infinity down to 2^128 (binary64 products are exact; a group held in binary32 has no such product).  Per output two
+// running maxima over the products' bit patterns are kept, one signed and one unsigned: patterns of positive numbers
+// order like the numbers with +infinity and the positive NaNs on top (signed maximum), patterns of negative numbers
+// order by magnitude above every positive pattern (unsigned maximum).  For binary64 the high words do: a NaN the
+// multiplier makes is the quiet one, and an infinity has a zero low word.  The caller lets the accumulator join and
+// applies the rules.  Out of line, like special_block.
+template <int R, int C, int SA, int SB, int LEN, bool DBL>
+__device__ __forceinline__ uint2 special_products_of(const void *a_, const void *b_, bool overflow_rule)
+{
+    typedef typename std::conditional<DBL, double, float>::type V;
+    const V *a = static_cast<const V *>(a_), *b = static_cast<const V *>(b_);
+    constexpr uint32_t INF_PAT = DBL ? 0x7FF00000u : 0x7F800000u;
+    const uint32_t thr = (DBL && overflow_rule) ? 0x47F00000u : INF_PAT;       // high word of 2^128
+    int32_t pmax[R][C];
+    uint32_t nmax[R][C];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int c = 0; c < C; ++c) { pmax[r][c] = (int32_t)0x80000000u; nmax[r][c] = 0u; }
+#pragma unroll 1
+    for (int kk = 0; kk < LEN; ++kk) {
+        V av[R], bv[C];
+#pragma unroll
+        for (int r = 0; r < R; ++r) av[r] = a[r * SA + kk];
+#pragma unroll
+        for (int c = 0; c < C; ++c) bv[c] = b[c * SB + kk];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const V pr = av[r] * bv[c];
+                uint32_t w;
+                if constexpr (DBL) w = (uint32_t)__double2hiint(pr);
+                else w = __float_as_uint(pr);
+                pmax[r][c] = (int32_t)w > pmax[r][c] ? (int32_t)w : pmax[r][c];
+                nmax[r][c] = w > nmax[r][c] ? w : nmax[r][c];
+            }
+    }
+    uint32_t nan = 0, pos = 0, neg = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int c = 0; c < C; ++c) {
+            const uint32_t bit = 1u << (r * C + c);
+            if (pmax[r][c] > (int32_t)INF_PAT || nmax[r][c] > (0x80000000u | INF_PAT)) nan |= bit;
+            if (pmax[r][c] >= (int32_t)thr) pos |= bit;
+            if (nmax[r][c] >= (0x80000000u | thr)) neg |= bit;
+        }
+    return make_uint2(nan, pos | (neg << 16));
+}
+
+// SA_F, SB_F / SA_D, SB_D: row strides of a thread's rows of A and B in the binary32 / binary64 staging (elements);
+// how: bit 0, the values are binary64; bit 1, the product-overflow rule applies.
+// Returns x: outputs (bit r * C + c) with a NaN product; y: with a product counted as +infinity (low half) / -infinity
+// (high half).
+template <int R, int C, int SA_F, int SB_F, int SA_D, int SB_D, int LEN>
+__device__ __noinline__ uint2 special_products(const void *a, const void *b, uint32_t how)
+{
+    static_assert(R * C <= 16, "one bit per output in each half of a word");
+    if (how & 1u) return special_products_of<R, C, SA_D, SB_D, LEN, true>(a, b, (how & 2u) != 0);
+    return special_products_of<R, C, SA_F, SB_F, LEN, false>(a, b, (how & 2u) != 0);
+}
+
 // ---- the kernel -------------------------------------------------------------------------
 // TM x TN : block of D per slot;  R x C: register block per thread;
 // KC      : k elements staged at a time;
@@ -777,7 +849,9 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
         uint32_t e = m2[r][c];
         const uint32_t lo = e & 0xFFFFu, hi = e >> 16;
         int em = (int)(lo > hi ? lo : hi) + ta_.ebase;
-        bool to_slow = IS_RD && VM != 0 && em >= 126;
+        // the product-overflow rule may apply (a product is below 2^(em + 2)); with `wide_products` such products keep
+        // their values, which binary64 holds
+        bool to_slow = IS_RD && VM != 0 && em >= 127 && !(fl & FL_WIDE_PRODUCTS);
         if constexpr (SC) {
             const int s = (int)sca[r] + (int)scb[c] - 254;
             sadj[r][c] = s;
@@ -913,30 +987,57 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
             }
         }
         if (tagged & SENTINEL_MASK) {                                   // rare: the group met a tagged element
-            BlockVals<R * C> cin;
-            uint32_t tm = 0;
-#pragma unroll
-            for (int i = 0; i < R * C; ++i) cin.v[i] = 0;
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (tg[r][c] & SENTINEL_MASK) {
-                        cin.v[r * C + c] = d[r][c];
-                        tm |= 1u << (r * C + c);
-                    }
             // NaN and infinity results first, for the whole block at once; then the integer routine for what is left
             // (the model parameters are fetched from the kernel-argument segment here, as in slow_group)
             const TiledArgs q = fetch_args();
-            const bool inf_final = !SC && (q.p.c_mode != MMAEMU_C_AFTER_RD || q.p.wide_products);
-            const BlockVals<R * C> sp = special_block<R, C, TI, TJ>(A, B, my_tile * m + i_base, my_tile * n + j_base, k, kg, cin, tm, q.ta, q.tb,
-                                                                    q.p.L, q.p.ftz_in, q.p.nan_bits, inf_final);
+            if constexpr (!SC && LT != 0) {
+                // the group lies inside the staged chunk: classes and signs from the staged values.  Under the
+                // product-overflow rule (the RD modes without `wide_products`) BF16 / TF32 groups are also tagged for a
+                // large maximum exponent alone; of those, what the routine leaves unsettled has no special operand and
+                // no product of 2^128 or more, and the value computed above stands.
+                const bool rule = IS_RD && !q.p.wide_products;
+                const uint32_t off = kg % KC;
+                const bool dbl = VM == 2 || (VM == 1 && chunk_is_double);
+                const void *pa = dbl ? static_cast<const void *>(avd + off) : static_cast<const void *>(av + off);
+                const void *pb = dbl ? static_cast<const void *>(bvd + off) : static_cast<const void *>(bv + off);
+                const uint2 sp = special_products<R, C, TI * VS, TJ * VS, TI * VSD, TJ * VSD, LT>(pa, pb, (dbl ? 1u : 0u) | (rule ? 2u : 0u));
 #pragma unroll
-            for (int r = 0; r < R; ++r)
+                for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int c = 0; c < C; ++c)
-                    if (tg[r][c] & SENTINEL_MASK)
-                        dn[r][c] = ((sp.settled >> (r * C + c)) & 1u) ? sp.v[r * C + c] : slow_group(r, c, kg, d[r][c]);
+                    for (int c = 0; c < C; ++c)
+                        if (tg[r][c] & SENTINEL_MASK) {
+                            const uint32_t i = r * C + c, cb = d[r][c];
+                            bool nn = (sp.x >> i) & 1u, pp = (sp.y >> i) & 1u, mm = (sp.y >> (16 + i)) & 1u;
+                            if ((cb & 0x7FFFFFFFu) > 0x7F800000u) nn = true;                       // the accumulator joins
+                            else if ((cb & 0x7FFFFFFFu) == 0x7F800000u) { if (cb >> 31) mm = true; else pp = true; }
+                            if (nn || (pp && mm)) dn[r][c] = q.p.nan_bits;
+                            else if (pp || mm) dn[r][c] = pp ? 0x7F800000u : 0xFF800000u;
+                            // (else: tagged for its large maximum exponent alone -- a tagged element always gives one
+                            // of the above -- and no product reached 2^128: the value computed above stands)
+                        }
+            } else {
+                BlockVals<R * C> cin;
+                uint32_t tm = 0;
+#pragma unroll
+                for (int i = 0; i < R * C; ++i) cin.v[i] = 0;
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+                        if (tg[r][c] & SENTINEL_MASK) {
+                            cin.v[r * C + c] = d[r][c];
+                            tm |= 1u << (r * C + c);
+                        }
+                const bool inf_final = !SC && (q.p.c_mode != MMAEMU_C_AFTER_RD || q.p.wide_products);
+                const BlockVals<R * C> sp = special_block<R, C, TI, TJ>(A, B, my_tile * m + i_base, my_tile * n + j_base, k, kg, cin, tm, q.ta, q.tb,
+                                                                        q.p.L, q.p.ftz_in, q.p.nan_bits, inf_final);
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+                        if (tg[r][c] & SENTINEL_MASK)
+                            dn[r][c] = ((sp.settled >> (r * C + c)) & 1u) ? sp.v[r * C + c] : slow_group(r, c, kg, d[r][c]);
+            }
         }
 #pragma unroll
         for (int r = 0; r < R; ++r)

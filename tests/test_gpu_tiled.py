@@ -163,3 +163,29 @@ def test_tiled_unaligned_pointers(mm):
     assert mm.last_kernel() == "general"
     assert_same(to_host(dD, np.uint32).reshape(nb, m, n), want, "A/B off by 2 bytes")
     mm.model_destroy(h)
+
+
+@pytest.mark.parametrize("ta,tb", [(fm.BF16, fm.BF16), (fm.FP16, fm.FP16), (fm.E5M2, fm.E5M2), (fm.E4M3, fm.E5M2), (fm.BF16, fm.E5M2)])
+def test_all_bit_patterns_in_the_tiled_kernels(mm, ta, tb):
+    # Sec. 3.1 Step 4's third input type (random bit streams, NaN and infinities included) and Sec. 4.2: most groups hold
+    # a special value, or (BF16 under TR-FDPA) a finite product of 2^128 or more.  The kernels settle those groups from
+    # the staged values; every output against the C form of the oracle, a sample against the rational form.
+    from oracle.fdpa import emulate_mma as o1_emulate, C_AFTER_RD
+    rng = np.random.default_rng(7100 + 8 * ta + tb)
+    for (m, n, k, nb, L) in ((16, 16, 32, 6, 16), (32, 32, 8, 3, 8), (64, 64, 32, 1, 4), (16, 16, 16, 9, 8)):
+        A = synth.random_bits(rng, (nb, m, k), ta, finite=False)
+        B = synth.random_bits(rng, (nb, n, k), tb, finite=False)
+        C = np.where(rng.random((nb, m, n)) < 0.5, synth.random_bits(rng, (nb, m, n), fm.FP32, finite=False),
+                     synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 100, 150)).astype(np.uint32)
+        models = [ModelParams(group_len=L, frac_bits=24), ModelParams(group_len=L, frac_bits=13, c_mode=C_AFTER_EXACT, out_round=RZ, ftz_in=True, ftz_out=True),
+                  ModelParams(group_len=L, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD, nan_bits=0xFFC00000),
+                  ModelParams(group_len=L, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD, ftz_in=True, skip_zero_terms=True, f2_at_leading_bit=True,
+                              zero_result_positive=True, sum_drop_distance=28)]
+        for p in models:
+            want, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
+            got = gpu_emulate(mm, p, A, B, C, ta, tb)
+            assert gpu_emulate.last_kernel.startswith("tiled"), gpu_emulate.last_kernel
+            assert_same(got, want, "all bit patterns %s %s" % ((m, n, k, nb), p))
+            assert_same(got[:1, :2, :n], o1_emulate(p, A[:1, :2], B[:1], C[:1, :2], ta, tb), "rational form %s" % (p,))
+            special = ((want & 0x7F800000) == 0x7F800000).mean()
+            assert 0.05 < special < 0.999, special
