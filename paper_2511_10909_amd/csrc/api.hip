@@ -391,16 +391,16 @@ mmaemu_status mmaemu_emulate_mma_scaled(const mmaemu_model *model, const void *A
     return emulate_impl(model, A, B, C, D, (const uint8_t *)SA, (const uint8_t *)SB, block, m, n, k, batch, dt, hip_stream);
 }
 
-// class of a model in the multi-model kernels: models of equal class share launches; negative: not taken there
+// whether the multi-model kernel takes a model (then with its arithmetic kind there)
 static mmaemu_status many_class(const mmaemu_model_params &mp, const void *A, const void *B, uint32_t m, uint32_t n, uint32_t k,
-                                mmaemu_dtypes dt, ModelArgs &p, bool &fused, int &vm, int &nf)
+                                mmaemu_dtypes dt, ModelArgs &p, bool &fused, uint32_t &kind)
 {
     fused = false;
-    vm = nf = 0;
+    kind = 0;
     if (mp.family == MMAEMU_FAMILY_FDPA && is_ab_type(dt.a) && is_ab_type(dt.b)) {
         const mmaemu_status st = fdpa_model_args(mp, k, false, p);
         if (st != MMAEMU_OK) return st;
-        fused = multi_class(p, dt.a, dt.b, m, n, k, A, B, vm, nf);
+        fused = scan_takes(p, dt.a, dt.b, m, n, k, A, B, kind);
     }
     return MMAEMU_OK;
 }
@@ -418,10 +418,10 @@ mmaemu_status mmaemu_compare_many_classes(const mmaemu_model *const *models, uin
         if (!models[i] || models[i]->magic != MODEL_MAGIC) { set_error("compare_many_classes: bad model handle at %u", i); return MMAEMU_ERR_INVALID_ARG; }
         ModelArgs p;
         bool fused;
-        int vm, nf;
-        const mmaemu_status st = many_class(models[i]->params, nullptr, nullptr, m, n, k, dt, p, fused, vm, nf);
+        uint32_t kind;
+        const mmaemu_status st = many_class(models[i]->params, nullptr, nullptr, m, n, k, dt, p, fused, kind);
         if (st != MMAEMU_OK) return st;
-        class_of_model[i] = fused ? (int32_t)(((uint32_t)vm << 16) | ((uint32_t)nf << 8) | p.L) : -1;
+        class_of_model[i] = fused ? 0 : -1;                     // one class: the kernel takes any mix of group lengths and widths
     }
     return MMAEMU_OK;
 }
@@ -454,20 +454,19 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     uint32_t *dout = static_cast<uint32_t *>(D_out);
 
     // which models the multi-model kernels take, and in which variant
-    struct Item { ModelArgs p; bool fused, done; int vm, nf; };
+    struct Item { ModelArgs p; bool fused, done; uint32_t kind; };
     Item items[MMAEMU_COMPARE_MANY_MAX];
     bool all_one = n_models <= (uint32_t)MULTI_MAX;
     for (uint32_t i = 0; i < n_models; ++i) {
         Item &it = items[i];
         it.fused = false;
         it.done = false;
-        it.vm = it.nf = 0;
-        const mmaemu_status cst = many_class(models[i]->params, A, B, m, n, k, dt, it.p, it.fused, it.vm, it.nf);
+        it.kind = 0;
+        const mmaemu_status cst = many_class(models[i]->params, A, B, m, n, k, dt, it.p, it.fused, it.kind);
         if (cst != MMAEMU_OK) return cst;
         // (within a launch the models that flush subnormal inputs come last; a leading reference model that flushes
         // can therefore share its launch with flushing models only)
-        all_one = all_one && it.fused && it.vm == items[0].vm && it.nf == items[0].nf && it.p.L == items[0].p.L &&
-                  !(items[0].p.ftz_in && !it.p.ftz_in);
+        all_one = all_one && it.fused && !(items[0].p.ftz_in && !it.p.ftz_in);
     }
     bool any_unfused = false;
     for (uint32_t i = 0; i < n_models; ++i) any_unfused = any_unfused || !items[i].fused;
@@ -477,30 +476,32 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     }
     const uint32_t *ref = static_cast<const uint32_t *>(Dref);
 
-    // fused launch of `first` (if not UINT32_MAX: it leads the launch and is the reference) and every model of its
-    // class not yet run; at most MULTI_MAX per launch, FlushSubnormal sets last so that the operands are staged twice at most
-    auto run_class = [&](uint32_t lead, int vm, int nf, uint32_t L, bool ref_is_first) -> mmaemu_status {
+    // fused launch of `lead` (if not UINT32_MAX: it leads the launch and is the reference) and every model the kernel
+    // takes that has not run yet; at most MULTI_MAX per launch, FlushSubnormal sets last so that the staged operands are
+    // flushed once at most
+    auto run_class = [&](uint32_t lead, bool ref_is_first) -> mmaemu_status {
         for (;;) {
             MultiLaunch ml = {};
-            ml.L = L; ml.vm = vm; ml.nf = nf;
+            uint32_t kinds[MULTI_MAX] = {};
             ml.ref_is_first = ref_is_first;
             ml.dref = ref;
             ml.dout = dout;
             ml.out_stride = count;
             ml.index_base = index_base;
             ml.stats = dev_stats;
-            if (ref_is_first) { ml.slot[0] = lead; ml.models[0] = items[lead].p; ml.count = 1; items[lead].done = true; }
+            if (ref_is_first) { ml.slot[0] = lead; ml.models[0] = items[lead].p; kinds[0] = items[lead].kind; ml.count = 1; items[lead].done = true; }
             for (int pass = (ref_is_first && items[lead].p.ftz_in) ? 1 : 0; pass < 2; ++pass)
                 for (uint32_t i = 0; i < n_models && ml.count < (uint32_t)MULTI_MAX; ++i) {
                     Item &it = items[i];
-                    if (it.done || !it.fused || it.vm != vm || it.nf != nf || it.p.L != L || (int)(it.p.ftz_in != 0) != pass) continue;
+                    if (it.done || !it.fused || (int)(it.p.ftz_in != 0) != pass) continue;
                     ml.slot[ml.count] = i;
                     ml.models[ml.count] = it.p;
+                    kinds[ml.count] = it.kind;
                     ml.count += 1;
                     it.done = true;
                 }
             if (ml.count == 0) return MMAEMU_OK;
-            const mmaemu_status st = launch_multi(ml, A, B, C, m, n, k, batch, dt.a, dt.b, s);
+            const mmaemu_status st = launch_scan(ml, kinds, A, B, C, m, n, k, batch, dt.a, dt.b, s);
             if (st != MMAEMU_OK) return st;
             if (ref_is_first) {                    // what is left of the class compares with the first model's stored outputs
                 ref_is_first = false;
@@ -513,7 +514,7 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     if (!ref) {
         // the reference is model 0's output: it runs first
         if (items[0].fused) {
-            const mmaemu_status st = run_class(0, items[0].vm, items[0].nf, items[0].p.L, true);
+            const mmaemu_status st = run_class(0, true);
             if (st != MMAEMU_OK) return st;
         } else {
             mmaemu_status st = emulate_impl(models[0], A, B, C, dout, nullptr, nullptr, 1, m, n, k, batch, dt, hip_stream);
@@ -527,7 +528,7 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     for (uint32_t i = 0; i < n_models; ++i) {
         if (items[i].done) continue;
         if (items[i].fused) {
-            const mmaemu_status st = run_class(UINT32_MAX, items[i].vm, items[i].nf, items[i].p.L, false);
+            const mmaemu_status st = run_class(UINT32_MAX, false);
             if (st != MMAEMU_OK) return st;
         } else {
             uint32_t *Di = dout + (uint64_t)i * count;

@@ -102,6 +102,11 @@ bool multi_class(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint3
                  int &vm, int &nf);
 mmaemu_status launch_multi(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
                            uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
+// The one-launch form: models of any group length and arithmetic kind together (emulate_scan.hip).  scan_takes: whether
+// it takes a model, and the model's arithmetic kind; launch_scan: kinds[i] belongs to ml.models[i] (ml.L, vm, nf unused).
+bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind);
+mmaemu_status launch_scan(const MultiLaunch &ml, const uint32_t *kinds, const void *A, const void *B, const void *C, uint32_t m, uint32_t n,
+                          uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                      uint32_t tb, hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr,

@@ -1,0 +1,544 @@
+// The closed-loop scan in one launch (Sec. 3.1 Step 4: many candidate parameter sets over the same random tiles, each
+// compared bit by bit with a reference, Eq. 2): up to MULTI_MAX T-FDPA models of *any* group length, internal width and
+// fold period share the staged operands of a pass.
+//
+// The per-class multi-model kernels of emulate_tiled.hpp stage and decode A and B, load C and the reference and form
+// the exponent maxima once per launch, and a launch holds the models of one group length and arithmetic variant only;
+// for the sixteen sets of the scan that fixed part is paid six times per operand type and is as much as 1.4 models'
+// worth of work each time.  Here it is paid once:
+//   * a workgroup pass stages four 16x16x16 tiles (one 32x32x8 tile) as those kernels do (same LDS layout and helpers);
+//   * pass 1 runs once at the finest granularity, a quarter group of four products: the packed 16-bit maximum of each
+//     quarter is kept in LDS, two quarters per dword and thread;
+//   * the model loop reads per model six scalars from the kernel-argument segment (F, switches, output mask, NaN
+//     pattern, L, arithmetic kind); a group's maximum is the maximum of its quarters; pass 2 is a run-time loop over
+//     the group in steps of four k (one 128-bit LDS read per row and step);
+//   * arithmetic kinds: 0, the whole group summed in 32 bits; 1, folded into binary64 every four terms; 2, every term;
+//     3, F of 30 and more: terms truncated and summed in binary64 (values widened on load where the chunk is held in
+//     binary32);
+//   * the group epilogue, the special values (special_products) and the statistics are those of the per-class kernels.
+// Models that flush subnormal inputs come last in a launch (the staged values are flushed in place once).
+#include "emulate_tiled.hpp"
+
+namespace mmaemu {
+
+struct ScanArgs {
+    uint32_t ta, tb;
+    int32_t ebase;                     // Exp = e' + ebase for a product
+    uint32_t count;                    // models in this launch, 1 .. MULTI_MAX
+    uint32_t ref_is_first;             // no reference array: the first model's outputs are the reference
+    const uint32_t *dref;              // reference outputs [batch][m][n], or null
+    uint32_t *dout;                    // null, or every model's outputs: model i at dout + slot[i] * out_stride
+    uint64_t out_stride, index_base;
+    uint64_t *stats;                   // the caller's mmaemu_stats array as 64-bit words
+    uint32_t slot[MULTI_MAX];
+    struct Hot { int32_t F; uint32_t flags, out_mask, nan_bits, L, kind; } hot[MULTI_MAX];
+};
+
+__device__ __forceinline__ ScanArgs::Hot scan_hot(uint32_t mi)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef const __attribute__((address_space(4))) ScanArgs *KArgs;
+    KArgs sa = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
+    ScanArgs::Hot h;
+    h.F = sa->hot[mi].F; h.flags = sa->hot[mi].flags; h.out_mask = sa->hot[mi].out_mask; h.nan_bits = sa->hot[mi].nan_bits;
+    h.L = sa->hot[mi].L; h.kind = sa->hot[mi].kind;
+    return h;
+#else
+    return ScanArgs::Hot{};
+#endif
+}
+
+// TM x TM x KC tiles (16 x 16 x 16 or 32 x 32 x 8), 2 x 2 outputs per thread; ADAPT: BF16 operands, whose staged chunk is
+// held in binary64 when any element lies outside [2^-31, 2^32).
+template <int TM, int KC, bool ADAPT>
+__global__ void __launch_bounds__(256)
+emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm, uint64_t nitems, uint32_t nblocks)
+{
+    constexpr int R = 2, C = 2, TN = TM;
+    constexpr int TI = TM / R, TJ = TN / C, TPS = TI * TJ, SLOTS = 256 / TPS;
+    static_assert(TPS * SLOTS == 256, "thread layout");
+    constexpr int VS = KC + 4, VSD = KC + 2, ES = KC / 2 + (KC == 16 ? 2 : 4);
+    constexpr int NQ4 = KC / 4;                                   // quarter groups per row
+    constexpr int NK2 = (NQ4 + 1) / 2;                            // dwords of kept maxima per output
+    constexpr int VBYTES = SLOTS * TM * (ADAPT ? VSD * 8 : VS * 4);
+    constexpr int EBYTES = SLOTS * TM * ES * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char smem[2 * VBYTES + 2 * EBYTES];
+    __shared__ uint32_t m2k[NK2][R * C][256];
+    __shared__ MultiLds ml;
+    constexpr int HC = HIST_COPIES;
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t i = tid; i < MULTI_MAX * 34 * HC; i += 256) (&ml.hist[0][0][0])[i] = 0;
+    if (tid < MULTI_MAX) { ml.naneq[tid] = 0; ml.maxd[tid] = 0; ml.first[tid] = ~0ull; }
+    // (the first staging's barriers come before any thread counts anything)
+
+    unsigned char *Av_raw = smem, *Bv_raw = smem + VBYTES;
+    uint32_t *Ae = reinterpret_cast<uint32_t *>(smem + 2 * VBYTES);
+    uint32_t *Be = reinterpret_cast<uint32_t *>(smem + 2 * VBYTES + EBYTES);
+    const ScanArgs *sa = reinterpret_cast<const ScanArgs *>(opaque_kernarg_ptr());
+    const uint32_t slot = tid / TPS, ti = (tid % TPS) / TJ, tj = tid % TJ;
+    const uint32_t ta = sa_.ta, tb = sa_.tb;
+    const int ebase = sa_.ebase;
+    const uint32_t esa = (ta <= MMAEMU_FP8_E5M2 || ta >= MMAEMU_FP6_E2M3) ? 1u : 2u;
+    const uint32_t esb = (tb <= MMAEMU_FP8_E5M2 || tb >= MMAEMU_FP6_E2M3) ? 1u : 2u;
+    const float *av = reinterpret_cast<const float *>(Av_raw) + (slot * TM + ti) * VS;
+    const float *bv = reinterpret_cast<const float *>(Bv_raw) + (slot * TN + tj) * VS;
+    const double *avd = reinterpret_cast<const double *>(Av_raw) + (slot * TM + ti) * VSD;
+    const double *bvd = reinterpret_cast<const double *>(Bv_raw) + (slot * TN + tj) * VSD;
+    const uint32_t *ae = Ae + (slot * TM + ti) * ES;
+    const uint32_t *be = Be + (slot * TN + tj) * ES;
+    const uint32_t count = sa_.count, ref_first = sa_.ref_is_first;
+    const uint32_t *dref = sa->dref;
+
+    constexpr int NQ = (SLOTS * TM * (KC / 4) + 255) / 256;
+    for (uint32_t pass_wg = blockIdx.x; pass_wg < nblocks; pass_wg += gridDim.x) {
+        // ---- this pass's tiles: staging plans, outputs, operands in flight ----
+        const uint64_t item0 = (uint64_t)pass_wg * SLOTS;
+        StagePlan<NQ> plan_a, plan_b;
+        make_plan<TM, KC, SLOTS, VS, ES, true, NQ>(plan_a, A, esa, item0, nitems, 1u, 1u, TM, KC);
+        make_plan<TN, KC, SLOTS, VS, ES, false, NQ>(plan_b, B, esb, item0, nitems, 1u, 1u, TN, KC);
+        uint2 raw_a[NQ], raw_b[NQ];
+        load_panel<NQ>(esa, plan_a, 0, raw_a);
+        load_panel<NQ>(esb, plan_b, 0, raw_b);
+        const bool live = item0 + slot < nitems;
+        const uint64_t my_tile = live ? item0 + slot : nitems - 1;
+        const uint64_t d_off = (my_tile * TM + ti) * (uint64_t)TN + tj;             // + TI * r * TN + TJ * c
+        uint32_t c0[R][C], ref[R][C];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int c = 0; c < C; ++c) {
+                const uint64_t o = d_off + (uint64_t)(TI * r) * TN + TJ * c;
+                c0[r][c] = Cm[o];
+                ref[r][c] = ref_first ? 0u : dref[o];
+            }
+        // ---- decode and stage (as the first model wants them) ----
+        bool chunk_is_double = false;
+        int staged;
+        {
+            const uint32_t ftz0 = scan_hot(0).flags & FL_FTZ_IN;
+            staged = ftz0 ? 1 : 0;
+            float fa[NQ][4], fb[NQ][4];
+            uint2 xa[NQ], xb[NQ];
+            bool wild = decode_any<NQ>(ta, raw_a, ftz0, 0u, fa, xa);
+            wild |= decode_any<NQ>(tb, raw_b, ftz0, 0u, fb, xb);
+            if (ADAPT) chunk_is_double = __syncthreads_or(wild) != 0;         // (also protects the previous pass's readers)
+            else __syncthreads();
+            store_panel<NQ, VS, VSD>(plan_a, fa, xa, Av_raw, Ae, chunk_is_double, 3);
+            store_panel<NQ, VS, VSD>(plan_b, fb, xb, Bv_raw, Be, chunk_is_double, 3);
+            __syncthreads();
+        }
+        // ---- pass 1, once: the maximum of e'_a + e'_b over each quarter group, two quarters per kept dword ----
+#pragma unroll
+        for (int q = 0; q < NQ4; ++q) {
+            uint2 ea[R], eb[C];
+#pragma unroll
+            for (int r = 0; r < R; ++r) ea[r] = *reinterpret_cast<const uint2 *>(ae + TI * r * ES + 2 * q);
+#pragma unroll
+            for (int c = 0; c < C; ++c) eb[c] = *reinterpret_cast<const uint2 *>(be + TJ * c * ES + 2 * q);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const uint32_t x = pk_max_u16(pk_add_u16(ea[r].x, eb[c].x), pk_add_u16(ea[r].y, eb[c].y));
+                    const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
+                    const uint32_t mx = lo > hi ? lo : hi;
+                    // (each thread its own words: no barrier needed)
+                    if (q % 2 == 0) m2k[q / 2][r * C + c][tid] = mx;
+                    else m2k[q / 2][r * C + c][tid] |= mx << 16;
+                }
+        }
+
+        // ---- the models ----
+#pragma unroll 1
+        for (uint32_t mi = 0; mi < count; ++mi) {
+            const ScanArgs::Hot hot = scan_hot(mi);
+            const int F = hot.F;
+            const uint32_t fl = hot.flags, out_mask = hot.out_mask, nan_bits = hot.nan_bits, L = hot.L, kind = hot.kind;
+            // rho = RZ-FP32: the short route's int -> float conversion truncates under the binary32 rounding mode "toward
+            // zero" (every other binary32 operation of the loop is exact in either mode, and the binary64 route checks the
+            // direction of its own conversion)
+            set_f32_round_toward_zero((fl & FL_RZ) != 0);
+            if ((fl & FL_FTZ_IN) && !staged) {
+                // FlushSubnormal on the staged values, in place (exponents do not change: a subnormal keeps Exp = 1 - bias)
+                __syncthreads();
+                const float min_a = min_normal_of(ta), min_b = min_normal_of(tb);
+                if (chunk_is_double) {
+                    double *va = reinterpret_cast<double *>(Av_raw), *vb = reinterpret_cast<double *>(Bv_raw);
+                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TM * VSD; i += 256) if (__builtin_fabs(va[i]) < (double)min_a) va[i] = 0.0;
+                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TN * VSD; i += 256) if (__builtin_fabs(vb[i]) < (double)min_b) vb[i] = 0.0;
+                } else {
+                    float *va = reinterpret_cast<float *>(Av_raw), *vb = reinterpret_cast<float *>(Bv_raw);
+                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TM * VS; i += 256) if (__builtin_fabsf(va[i]) < min_a) va[i] = 0.0f;
+                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TN * VS; i += 256) if (__builtin_fabsf(vb[i]) < min_b) vb[i] = 0.0f;
+                }
+                __syncthreads();
+                staged = 1;
+            }
+            uint32_t d[R][C];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) d[r][c] = c0[r][c];
+            bool slow_seen = false;                           // some group left the short route (a NaN may have come out of it)
+            // The groups of one model, specialised on the group length GL and the arithmetic kind so that the loops
+            // unroll and the LDS addresses of a group are immediate offsets.
+            auto run_groups = [&](auto gl_c, auto kind_c) {
+                constexpr int GL = decltype(gl_c)::value, KIND = decltype(kind_c)::value;
+                constexpr int U2 = (GL / 4 <= 2) ? 2 : 1;             // (a whole group of 16 in flight costs a wave of occupancy)
+                if constexpr (GL <= KC) {
+                const bool fits = KIND == 0 && ((uint64_t)(GL + 1) << (F + 2)) <= (1ull << 31) && F >= 1;
+#pragma unroll 1
+                for (int g = 0; g < KC / GL; ++g) {
+                    const uint32_t kg = g * GL;
+                    // e_max of the group: its quarters' maxima, then the accumulator
+                    int emax[R][C];
+                    uint32_t tagged = 0, tg[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            uint32_t e;
+                            if constexpr (GL == 4) {
+                                e = (m2k[g / 2][r * C + c][tid] >> (16 * (g & 1))) & 0xFFFFu;
+                            } else {
+                                uint32_t x = m2k[g * (GL / 8)][r * C + c][tid];
+                                if constexpr (GL == 16) x = pk_max_u16(x, m2k[g * 2 + 1][r * C + c][tid]);
+                                const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
+                                e = lo > hi ? lo : hi;
+                            }
+                            tg[r][c] = e & 0xC000u;
+                            tagged |= e;
+                            const int em = (int)e + ebase;
+                            uint32_t dd = d[r][c];
+                            if ((fl & FL_FTZ_IN) && (dd & 0x7F800000u) == 0) { dd = 0; d[r][c] = 0; }     // FlushSubnormal on the accumulator
+                            const uint32_t Ec = (dd >> 23) & 0xFFu;                                        // (a flushed subnormal keeps Exp = -126)
+                            const int ec = (int)(Ec ? Ec : 1u) - 127;
+                            emax[r][c] = ec > em ? ec : em;
+                        }
+                    tagged &= 0xC000u;
+                    // ---- pass 2 ----
+                    int32_t S32[R][C];
+                    double Sd[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) { S32[r][c] = 0; Sd[r][c] = 0.0; }
+                    auto fold = [&]() {
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) { Sd[r][c] += (double)S32[r][c]; S32[r][c] = 0; }
+                    };
+                    if ((ADAPT && chunk_is_double) || KIND == 3) {
+                        // binary64: exact product, exact scaling; the float -> int conversion truncates, or (KIND 3: F of 30
+                        // and more) v_trunc_f64 and a binary64 sum, exact below 2^53
+                        double scale[R][C];
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) scale[r][c] = __hiloint2double((F - emax[r][c] + 1023) << 20, 0);   // 2^(F - e_max), always normal
+#pragma unroll 1
+                        for (int q = 0; q < GL; q += 2) {
+                            double a[R][2], b[C][2];
+                            if (ADAPT && chunk_is_double) {
+#pragma unroll
+                                for (int r = 0; r < R; ++r) { const double2 v = *reinterpret_cast<const double2 *>(avd + TI * r * VSD + kg + q); a[r][0] = v.x; a[r][1] = v.y; }
+#pragma unroll
+                                for (int c = 0; c < C; ++c) { const double2 v = *reinterpret_cast<const double2 *>(bvd + TJ * c * VSD + kg + q); b[c][0] = v.x; b[c][1] = v.y; }
+                            } else {
+#pragma unroll
+                                for (int r = 0; r < R; ++r) { const float2 v = *reinterpret_cast<const float2 *>(av + TI * r * VS + kg + q); a[r][0] = (double)v.x; a[r][1] = (double)v.y; }
+#pragma unroll
+                                for (int c = 0; c < C; ++c) { const float2 v = *reinterpret_cast<const float2 *>(bv + TJ * c * VS + kg + q); b[c][0] = (double)v.x; b[c][1] = (double)v.y; }
+                            }
+#pragma unroll
+                            for (int w = 0; w < 2; ++w) {
+#pragma unroll
+                                for (int r = 0; r < R; ++r)
+#pragma unroll
+                                    for (int c = 0; c < C; ++c) {
+                                        const double t = (a[r][w] * b[c][w]) * scale[r][c];
+                                        if constexpr (KIND == 3) Sd[r][c] += __builtin_trunc(t);
+                                        else S32[r][c] += (int32_t)t;
+                                    }
+                                if constexpr (KIND == 2) fold();
+                            }
+                            if constexpr (KIND == 1) { if ((q & 2) != 0) fold(); }
+                        }
+                    } else {
+                        // binary32 values: the product is exact, the scaling aligns it, the conversion truncates toward zero
+                        float scale[R][C];
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                int se = F + 127 - emax[r][c];                         // biased exponent of 2^(F - e_max)
+                                se = se < 1 ? 1 : (se > 254 ? 254 : se);               // the clamps never change a truncated term
+                                scale[r][c] = __uint_as_float((uint32_t)se << 23);
+                            }
+#pragma unroll U2
+                        for (int q = 0; q < GL; q += 4) {
+                            float a[R][4], b[C][4];
+#pragma unroll
+                            for (int r = 0; r < R; ++r) {
+                                const float4 v = *reinterpret_cast<const float4 *>(av + TI * r * VS + kg + q);
+                                a[r][0] = v.x; a[r][1] = v.y; a[r][2] = v.z; a[r][3] = v.w;
+                            }
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                const float4 v = *reinterpret_cast<const float4 *>(bv + TJ * c * VS + kg + q);
+                                b[c][0] = v.x; b[c][1] = v.y; b[c][2] = v.z; b[c][3] = v.w;
+                            }
+#pragma unroll
+                            for (int w = 0; w < 4; ++w) {
+#pragma unroll
+                                for (int r = 0; r < R; ++r)
+#pragma unroll
+                                    for (int c = 0; c < C; ++c) S32[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale[r][c]);
+                                if constexpr (KIND == 2) fold();
+                            }
+                            if constexpr (KIND == 1) fold();
+                        }
+                    }
+
+                    // ---- end of the group ----
+                    // Short route: when the GL truncated products and the truncated accumulator together fit 32 bits, the
+                    // accumulator is aligned like a product, the whole sum is a 32-bit integer, and rho is the int -> float
+                    // conversion followed by an exact scaling -- as long as the result cannot be subnormal and nothing is
+                    // tagged: e_max - F >= -126 and e_max <= 127 for every output of the wavefront.
+                    bool done = false;
+                    if constexpr (KIND == 0) {
+                        if (fits) {
+                            uint32_t worst = tagged ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+#pragma unroll
+                                for (int c = 0; c < C; ++c) {
+                                    const uint32_t u = (uint32_t)(emax[r][c] - (F - 126));          // 0 .. 253 - F on this route
+                                    worst = u > worst ? u : worst;
+                                }
+                            if (__all(worst <= (uint32_t)(253 - F))) {
+#pragma unroll
+                                for (int r = 0; r < R; ++r)
+#pragma unroll
+                                    for (int c = 0; c < C; ++c) {
+                                        const float scale = __uint_as_float((uint32_t)(F + 127 - emax[r][c]) << 23);     // 2^(F - e_max), a normal number
+                                        const int32_t S = S32[r][c] + (int32_t)(__uint_as_float(d[r][c]) * scale);
+                                        const float f = (float)S;                                  // (truncates under RZ)
+                                        uint32_t o = __float_as_uint(ldexpf(f, emax[r][c] - F));
+                                        if ((fl & FL_RZ)) {
+                                            if ((o & 0x7FFFFFFFu) == 0x7F800000u) o -= 1u;         // overflow: the largest finite number
+                                            o &= out_mask;
+                                        }
+                                        d[r][c] = o;
+                                    }
+                                done = true;
+                            }
+                        }
+                    }
+                    if (!done) {
+                        slow_seen = true;
+                        uint32_t dn[R][C];
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                const double T = Sd[r][c] + (double)S32[r][c];
+                                const int unit = emax[r][c] - F;
+                                // the accumulator, aligned and truncated like every other term
+                                const double tc = __builtin_trunc(ldexp((double)__uint_as_float(d[r][c]), -unit));
+                                const double v = ldexp(T + tc, unit);                          // exact: integers below 2^53
+                                uint32_t o = __float_as_uint((float)v);
+                                if ((fl & FL_RZ)) {
+                                    const double back = (double)__uint_as_float(o);
+                                    if (__builtin_fabs(back) > __builtin_fabs(v)) o -= 1u;     // rounded away from zero: step back
+                                    o &= out_mask;                                             // RZ-E8M13 cuts further, still toward zero
+                                }
+                                if ((fl & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                                dn[r][c] = o;
+                            }
+                        if (tagged) {
+                            // NaN and infinite operands (Sec. 4.2): classes and signs from the staged values
+                            const bool dbl = ADAPT && chunk_is_double;
+                            const void *pa = dbl ? static_cast<const void *>(avd + kg) : static_cast<const void *>(av + kg);
+                            const void *pb = dbl ? static_cast<const void *>(bvd + kg) : static_cast<const void *>(bv + kg);
+                            const uint2 sp = special_products<R, C, TI * VS, TJ * VS, TI * VSD, TJ * VSD, GL>(pa, pb, dbl ? 1u : 0u);
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+#pragma unroll
+                                for (int c = 0; c < C; ++c)
+                                    if (tg[r][c]) {
+                                        const uint32_t i = r * C + c, cb = d[r][c];
+                                        bool nn = (sp.x >> i) & 1u, pp = (sp.y >> i) & 1u, mm = (sp.y >> (16 + i)) & 1u;
+                                        if ((cb & 0x7FFFFFFFu) > 0x7F800000u) nn = true;                       // the accumulator joins
+                                        else if ((cb & 0x7FFFFFFFu) == 0x7F800000u) { if (cb >> 31) mm = true; else pp = true; }
+                                        if (nn || (pp && mm)) dn[r][c] = nan_bits;
+                                        else if (pp || mm) dn[r][c] = pp ? 0x7F800000u : 0xFF800000u;
+                                    }
+                        }
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+                    }
+                }
+                }
+            };
+            auto by_kind = [&](auto gl_c) {
+                if (kind == 0) run_groups(gl_c, std::integral_constant<int, 0>{});
+                else if (kind == 1) run_groups(gl_c, std::integral_constant<int, 1>{});
+                else if (kind == 2) run_groups(gl_c, std::integral_constant<int, 2>{});
+                else run_groups(gl_c, std::integral_constant<int, 3>{});
+            };
+            if (L == 4) by_kind(std::integral_constant<int, 4>{});
+            else if (L == 8) by_kind(std::integral_constant<int, 8>{});
+            else by_kind(std::integral_constant<int, 16>{});
+
+            // ---- this model's outputs against the reference ----
+            // Per output that differs: one LDS atomic on its histogram bucket (bucket 0 of the LDS copy counts pairs that
+            // differ at distance 0: zeros of both signs, NaNs of two patterns), so the number of mismatches is the
+            // histogram's sum; the largest distance and the first index are reduced over the wavefront with row shifts,
+            // and lane 63 puts them into LDS.
+            uint32_t maxd = 0;
+            uint32_t first_off = 0xFFFFFFFFu;
+            if (live) {
+                uint32_t *dout = sa->dout;
+                const uint64_t dump_off = (uint64_t)sa->slot[mi] * sa->out_stride;
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        uint32_t x = d[r][c];
+                        if (slow_seen && (x & 0x7FFFFFFFu) > 0x7F800000u) x = nan_bits;          // (the short route produces no NaN)
+                        const uint64_t o = d_off + (uint64_t)(TI * r) * TN + TJ * c;
+                        if (dout) dout[dump_off + o] = x;
+                        if (ref_first && mi == 0) ref[r][c] = x;
+                        const uint32_t y = ref[r][c];
+                        if (x != y) {
+                            const uint32_t off = (uint32_t)((TI * r) * TN + TJ * c);
+                            first_off = off < first_off ? off : first_off;
+                            const uint32_t ax = x & 0x7FFFFFFFu, ay = y & 0x7FFFFFFFu;
+                            const bool nx = ax > 0x7F800000u, ny = ay > 0x7F800000u;
+                            uint32_t bucket;
+                            if (nx || ny) {
+                                bucket = (nx && ny) ? 0u : 33u;
+                                if (nx && ny) atomicAdd(&ml.naneq[mi], 1u);                      // (rare)
+                            } else {
+                                // distance of the ordered keys (sign-magnitude patterns read as signed integers): below 2^32
+                                const int32_t kx = (x >> 31) ? -(int32_t)ax : (int32_t)ax, ky = (y >> 31) ? -(int32_t)ay : (int32_t)ay;
+                                const uint32_t dist = kx >= ky ? (uint32_t)kx - (uint32_t)ky : (uint32_t)ky - (uint32_t)kx;
+                                maxd = dist > maxd ? dist : maxd;
+                                bucket = dist ? 32u - (uint32_t)__builtin_clz(dist) : 0u;
+                            }
+                            atomicAdd(&ml.hist[mi][bucket][tid & (HC - 1)], 1u);
+                        }
+                    }
+            }
+            // (offsets relative to the first output of this pass of the workgroup: 32 bits do for the reduction)
+            const uint32_t rel = first_off == 0xFFFFFFFFu ? 0xFFFFFFFFu : (uint32_t)(d_off - item0 * (uint64_t)(TM * TN)) + first_off;
+            const uint32_t wmin = wave_reduce_to_lane63<false>(rel), wmax = wave_reduce_to_lane63<true>(maxd);
+            if ((tid & 63u) == 63u && wmin != 0xFFFFFFFFu) {
+                atomicMin(&ml.first[mi], (unsigned long long)(sa->index_base + item0 * (uint64_t)(TM * TN) + wmin));
+                if (wmax) atomicMax(&ml.maxd[mi], wmax);
+            }
+        }
+        set_f32_round_toward_zero(false);
+    }
+    __syncthreads();
+    // one global atomic per non-zero counter per workgroup; n_compared and bucket 0 are known up front: workgroup 0 adds
+    // the whole count once, every workgroup takes its non-zero buckets back out of bucket 0
+    unsigned long long *gst = reinterpret_cast<unsigned long long *>(sa->stats);
+    for (uint32_t i = tid; i < count * 34u; i += 256) {
+        const uint32_t mi = i / 34u, b = i - mi * 34u;
+        unsigned long long *g = gst + (uint64_t)sa->slot[mi] * STATS_WORDS;
+        if (b == 0) {
+            uint32_t nonzero = 0, mism = 0;
+            for (int bb = 1; bb < 34; ++bb)
+                for (int cpy = 0; cpy < HC; ++cpy) nonzero += ml.hist[mi][bb][cpy];
+            for (int cpy = 0; cpy < HC; ++cpy) mism += ml.hist[mi][0][cpy];         // differing patterns at distance 0
+            mism += nonzero;
+            const unsigned long long total = (unsigned long long)nitems * (TM * TN);
+            if (blockIdx.x == 0) { atomicAdd(&g[0], total); atomicAdd(&g[5], total); }
+            if (nonzero) atomicAdd(&g[5], 0ull - (unsigned long long)nonzero);
+            if (mism) {
+                atomicAdd(&g[1], (unsigned long long)mism);
+                atomicMin(&g[3], ml.first[mi]);
+            }
+            if (ml.naneq[mi]) atomicAdd(&g[2], (unsigned long long)ml.naneq[mi]);
+            if (ml.maxd[mi]) atomicMax(&g[4], (unsigned long long)ml.maxd[mi]);
+        } else {
+            uint32_t t = 0;
+            for (int cpy = 0; cpy < HC; ++cpy) t += ml.hist[mi][b][cpy];
+            if (t) atomicAdd(&g[5 + b], (unsigned long long)t);
+        }
+    }
+}
+
+template <int TM, int KC, bool ADAPT>
+static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const void *B, const uint32_t *C, uint64_t batch, hipStream_t s)
+{
+    constexpr int SLOTS = 256 / ((TM / 2) * (TM / 2));
+    const uint64_t blocks = (batch + SLOTS - 1) / SLOTS;
+    if (blocks > 0x7FFFFFFFull) { set_error("emulate_compare_many: too many blocks"); return MMAEMU_ERR_SHAPE; }
+    if (blocks == 0) return MMAEMU_OK;
+    // Persistent workgroups: every workgroup ends with a few dozen global atomics on the same few cache lines.  Long
+    // launches take 2048 workgroups (the dispatcher balances a grid beyond the resident set); short ones as many as the
+    // device holds at once, and of those just enough that all make the same number of passes.
+    uint32_t grid = 2048u;
+    if (blocks < 8u * 2048u) {
+        static uint32_t resident[16] = {};
+        int dev = 0;
+        MMAEMU_HIP(hipGetDevice(&dev));
+        uint32_t &res = resident[dev & 15];
+        if (!res) {
+            int per_cu = 0, cus = 0;
+            MMAEMU_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, emulate_scan_kernel<TM, KC, ADAPT>, 256, 0));
+            MMAEMU_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+            res = (uint32_t)(per_cu > 0 ? per_cu : 1) * (uint32_t)(cus > 0 ? cus : 1);
+        }
+        const uint64_t passes = (blocks + res - 1) / res;
+        grid = (uint32_t)((blocks + passes - 1) / passes);
+    }
+    hipLaunchKernelGGL((emulate_scan_kernel<TM, KC, ADAPT>), dim3(grid), dim3(256), 0, s, sa, A, B, C, batch, (uint32_t)blocks);
+    MMAEMU_HIP(hipGetLastError());
+    set_last_kernel("multi x%u tiled %dx%d r2x2 kc=%d any L vm=%d", sa.count, TM, TM, KC, ADAPT ? 1 : 0);
+    return MMAEMU_OK;
+}
+
+// Whether the one-launch kernel takes a model (then `kind` is its arithmetic kind): T-FDPA with the accumulator inside
+// the sum on whole 16x16x16 / 32x32x8 tiles of FP8 / FP16 / BF16 / FP6 / FP4 operands, group length 4, 8 or 16.
+bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind)
+{
+    int vm, nf;
+    if (!multi_class(p, ta, tb, m, n, k, A, B, vm, nf)) return false;
+    kind = vm == 2 ? 3u : (nf == 0 ? 0u : (nf == 4 ? 1u : 2u));
+    return true;
+}
+
+mmaemu_status launch_scan(const MultiLaunch &ml, const uint32_t *kinds, const void *A, const void *B, const void *C, uint32_t m, uint32_t n,
+                          uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s)
+{
+    ScanArgs sa = {};
+    sa.ta = ta;
+    sa.tb = tb;
+    sa.ebase = 2 - fmt_info(ta).bias - fmt_info(tb).bias;
+    sa.count = ml.count;
+    sa.ref_is_first = ml.ref_is_first ? 1u : 0u;
+    sa.dref = ml.dref;
+    sa.dout = ml.dout;
+    sa.out_stride = ml.out_stride;
+    sa.index_base = ml.index_base;
+    sa.stats = reinterpret_cast<uint64_t *>(ml.stats);
+    for (uint32_t i = 0; i < ml.count; ++i) {
+        sa.slot[i] = ml.slot[i];
+        sa.hot[i] = ScanArgs::Hot{ml.models[i].F, ml.models[i].flags, ml.models[i].out_mask, ml.models[i].nan_bits, ml.models[i].L, kinds[i]};
+    }
+    const bool adapt = ta == MMAEMU_BF16 || tb == MMAEMU_BF16;
+    const uint32_t *Cm = static_cast<const uint32_t *>(C);
+    if (m == 16 && n == 16 && k == 16) return adapt ? launch_scan_cfg<16, 16, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<16, 16, false>(sa, A, B, Cm, batch, s);
+    if (m == 32 && n == 32 && k == 8) return adapt ? launch_scan_cfg<32, 8, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<32, 8, false>(sa, A, B, Cm, batch, s);
+    set_error("emulate_compare_many: no kernel for this shape");
+    return MMAEMU_ERR_UNSUPPORTED;
+}
+
+} // namespace mmaemu

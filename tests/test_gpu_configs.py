@@ -242,7 +242,7 @@ def test_config5_at_its_stated_size(cfg, mm):
         res = r[kind]
         npdt = np.uint16 if kind == "bf16" else np.uint8
         plist = [ModelParams(group_len=L, frac_bits=F, out_round=rho, ftz_in=bool(ftz), ftz_out=bool(ftz)) for F, L, rho, ftz in cfg.CONFIG5_MODELS]
-        assert all(k.startswith("multi") for k in res["kernels"]) and len(res["kernels"]) == 6, res["kernels"]
+        assert all(k.startswith("multi x16") for k in res["kernels"]) and len(res["kernels"]) == 1, res["kernels"]     # one launch per chunk
         for st in res["stats"]:
             assert st["n_compared"] == total and sum(st["ulp_hist"]) == total
             assert 0 < st["n_mismatch_bits"] < total                             # (none of the sets is the instruction's arithmetic)
