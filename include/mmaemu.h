@@ -276,8 +276,9 @@ typedef struct {
 
 /* Sets *dev_stats to the empty state (all zero, first_mismatch_index = UINT64_MAX). */
 mmaemu_status mmaemu_stats_reset(mmaemu_stats *dev_stats, void *hip_stream);
-/* Accumulates the comparison of D0[0..count) with D1[0..count): FP32 bit patterns (`d` = MMAEMU_FP32) or FP16 bit
- * patterns (`d` = MMAEMU_FP16, the outputs of models run with c = d = FP16); other types: MMAEMU_ERR_UNSUPPORTED.
+/* Accumulates the comparison of D0[0..count) with D1[0..count): FP32 bit patterns (`d` = MMAEMU_FP32), FP16 bit
+ * patterns (`d` = MMAEMU_FP16, the outputs of models run with c = d = FP16) or FP64 bit patterns (`d` = MMAEMU_FP64, the
+ * FMA family on binary64); other types: MMAEMU_ERR_UNSUPPORTED.
  * Pointers aligned to the element size.  count = 0 is a no-op. */
 mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uint64_t index_base,
                              mmaemu_dtype d, mmaemu_stats *dev_stats, void *hip_stream);
@@ -292,9 +293,9 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
  * D_out: NULL, or device memory for n_models * batch * m * n FP32 patterns; model i's outputs are then also written
  * at D_out + i * batch * m * n.  D_out must not overlap A, B, C or Dref.
  * Models of the FDPA family with c_mode C_IN_GROUP, no variation switches, frac_bits <= 40 and group length 4, 8 or
- * 16, on 16 x 16 x 16 or 32 x 32 x 8 tiles with 8-byte aligned A and B of 8- or 16-bit types, run in kernels that stage
- * and decode the operands once for up to 16 models of equal group length and keep every output in registers: D
- * reaches memory only on request.  Any other model runs through mmaemu_emulate_mma and mmaemu_compare and needs
+ * 16, on 16 x 16 x 16 or 32 x 32 x 8 tiles with 8-byte aligned A and B of 8- or 16-bit types, run in a kernel that stages
+ * and decodes the operands once for up to 16 models (any mix of group lengths and widths) and keeps every output in
+ * registers: D reaches memory only on request.  Any other model runs through mmaemu_emulate_mma and mmaemu_compare and needs
  * D_out, as does a reference taken from models[0] when the models do not all fit one such launch.
  * At most MMAEMU_COMPARE_MANY_MAX models per call.  batch = 0 is a no-op.
  * Errors: as mmaemu_emulate_mma; UNSUPPORTED (FP16 accumulators; D_out needed but NULL), INVALID_ARG (n_models, NULL).

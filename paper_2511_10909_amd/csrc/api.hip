@@ -482,26 +482,25 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     auto run_class = [&](uint32_t lead, bool ref_is_first) -> mmaemu_status {
         for (;;) {
             MultiLaunch ml = {};
-            uint32_t kinds[MULTI_MAX] = {};
             ml.ref_is_first = ref_is_first;
             ml.dref = ref;
             ml.dout = dout;
             ml.out_stride = count;
             ml.index_base = index_base;
             ml.stats = dev_stats;
-            if (ref_is_first) { ml.slot[0] = lead; ml.models[0] = items[lead].p; kinds[0] = items[lead].kind; ml.count = 1; items[lead].done = true; }
+            if (ref_is_first) { ml.slot[0] = lead; ml.models[0] = items[lead].p; ml.kind[0] = items[lead].kind; ml.count = 1; items[lead].done = true; }
             for (int pass = (ref_is_first && items[lead].p.ftz_in) ? 1 : 0; pass < 2; ++pass)
                 for (uint32_t i = 0; i < n_models && ml.count < (uint32_t)MULTI_MAX; ++i) {
                     Item &it = items[i];
                     if (it.done || !it.fused || (int)(it.p.ftz_in != 0) != pass) continue;
                     ml.slot[ml.count] = i;
                     ml.models[ml.count] = it.p;
-                    kinds[ml.count] = it.kind;
+                    ml.kind[ml.count] = it.kind;
                     ml.count += 1;
                     it.done = true;
                 }
             if (ml.count == 0) return MMAEMU_OK;
-            const mmaemu_status st = launch_scan(ml, kinds, A, B, C, m, n, k, batch, dt.a, dt.b, s);
+            const mmaemu_status st = launch_scan(ml, A, B, C, m, n, k, batch, dt.a, dt.b, s);
             if (st != MMAEMU_OK) return st;
             if (ref_is_first) {                    // what is left of the class compares with the first model's stored outputs
                 ref_is_first = false;

@@ -82,31 +82,26 @@ mmaemu_status hip_fail(hipError_t e, const char *what);
 mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                              uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb,
                              hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr, uint32_t block = 1);
-// Several models over the same operands, each compared with a reference inside the kernel (the closed-loop scan).
-// multi_class: whether the multi-model kernels take a model on this problem, and which kernel variant it needs there;
-// models of one variant and one group length share a launch of at most MULTI_MAX models.
+// Several models over the same operands, each compared with a reference inside the kernel (the closed-loop scan;
+// emulate_scan.hip): at most MULTI_MAX models of any group length and width per launch.
 constexpr int MULTI_MAX = 16;
 struct MultiLaunch {
     uint32_t count;
     uint32_t slot[MULTI_MAX];          // place of each model in the caller's arrays (D_out, statistics)
     ModelArgs models[MULTI_MAX];
-    uint32_t L;                        // the common group length, and the variant as multi_class names it
-    int vm, nf;
+    uint32_t kind[MULTI_MAX];          // arithmetic kind of each model, as scan_takes names it
     bool ref_is_first;                 // the first model's outputs are the reference (dref is not read)
     const uint32_t *dref;
     uint32_t *dout;                    // null, or the start of the caller's output array
     uint64_t out_stride, index_base;
     mmaemu_stats *stats;               // the start of the caller's statistics array
 };
-bool multi_class(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B,
-                 int &vm, int &nf);
-mmaemu_status launch_multi(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
-                           uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
-// The one-launch form: models of any group length and arithmetic kind together (emulate_scan.hip).  scan_takes: whether
-// it takes a model, and the model's arithmetic kind; launch_scan: kinds[i] belongs to ml.models[i] (ml.L, vm, nf unused).
+// scan_takes: whether that kernel takes a model on this problem, and the arithmetic kind the model needs there
+// (0: a group's aligned terms summed in 32 bits; 1: folded into binary64 every four terms; 2: every term; 3: F of 30
+// and more, terms truncated and summed in binary64)
 bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind);
-mmaemu_status launch_scan(const MultiLaunch &ml, const uint32_t *kinds, const void *A, const void *B, const void *C, uint32_t m, uint32_t n,
-                          uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
+mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
+                          uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                      uint32_t tb, hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr,

@@ -66,57 +66,4 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     return launch_emulate_generic(p, A, B, Cm, D, m, n, k, batch, ta, tb, s, SA, SB, scaled ? block : 1u);
 }
 
-// ---- several models per launch ----------------------------------------------------------------
-
-// Whether the multi-model kernels take this model on this problem, and the kernel variant it needs there (value mode,
-// fold period: the same choice launch_fold makes for one model).
-bool multi_class(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B,
-                 int &vm, int &nf)
-{
-    if (p.c_mode != MMAEMU_C_IN_GROUP || p.skip_zero_terms || p.zero_result_positive || (p.flags & (FL_ACC16 | FL_NAN_PROPAGATE))) return false;
-    if (!((m == 16 && n == 16 && k == 16) || (m == 32 && n == 32 && k == 8))) return false;
-    if (ta == MMAEMU_FP32 || tb == MMAEMU_FP32 || ta == MMAEMU_TF32 || tb == MMAEMU_TF32) return false;
-    if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) return false;
-    if (p.F > 40) return false;
-    if (!(p.L == 4 || p.L == 8 || (p.L == 16 && k == 16))) return false;
-    vm = p.F >= 30 ? 2 : ((ta == MMAEMU_BF16 || tb == MMAEMU_BF16) ? 1 : 0);
-    const uint64_t term = 1ull << (p.F + 2);                // |aligned term| < 2^(F+2)
-    nf = vm == 2 ? 0 : ((uint64_t)p.L * term <= (1ull << 31) ? 0 : (4 * term <= (1ull << 31) ? 4 : 1));
-    return true;
-}
-
-// One launch: the models of `ml` (all of one class as multi_class names it) over the batch's tiles.
-mmaemu_status launch_multi(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
-                           uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s)
-{
-    MultiArgs mu = {};
-    mu.t.p = ml.models[0];
-    mu.t.ta = ta;
-    mu.t.tb = tb;
-    mu.t.sa = nullptr;
-    mu.t.sb = nullptr;
-    mu.t.block = 1;
-    mu.t.ebase = 2 - fmt_info(ta).bias - fmt_info(tb).bias;
-    mu.count = ml.count;
-    mu.ref_is_first = ml.ref_is_first ? 1u : 0u;
-    mu.dref = ml.dref;
-    mu.dout = ml.dout;
-    mu.out_stride = ml.out_stride;
-    mu.index_base = ml.index_base;
-    mu.stats = reinterpret_cast<uint64_t *>(ml.stats);
-    for (uint32_t i = 0; i < ml.count; ++i) {
-        mu.slot[i] = ml.slot[i];
-        mu.models[i] = ml.models[i];
-        mu.hot[i] = MultiArgs::Hot{ml.models[i].F, ml.models[i].flags, ml.models[i].out_mask, ml.models[i].nan_bits};
-    }
-    const MultiCall call = {A, B, static_cast<const uint32_t *>(C), m, n, k, batch};
-    bool handled = false;
-    mmaemu_status st;
-    if (ml.vm == 2) st = launch_multi_shape<2>(mu, call, ml.L, ml.nf, s, handled);
-    else if (ml.vm == 1) st = launch_multi_shape<1>(mu, call, ml.L, ml.nf, s, handled);
-    else st = launch_multi_shape<0>(mu, call, ml.L, ml.nf, s, handled);
-    if (st == MMAEMU_OK && !handled) { set_error("emulate_compare_many: no kernel for this shape"); return MMAEMU_ERR_UNSUPPORTED; }
-    return st;
-}
-
 } // namespace mmaemu

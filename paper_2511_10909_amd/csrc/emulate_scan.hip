@@ -2,11 +2,10 @@
 // compared bit by bit with a reference, Eq. 2): up to MULTI_MAX T-FDPA models of *any* group length, internal width and
 // fold period share the staged operands of a pass.
 //
-// The per-class multi-model kernels of emulate_tiled.hpp stage and decode A and B, load C and the reference and form
-// the exponent maxima once per launch, and a launch holds the models of one group length and arithmetic variant only;
-// for the sixteen sets of the scan that fixed part is paid six times per operand type and is as much as 1.4 models'
-// worth of work each time.  Here it is paid once:
-//   * a workgroup pass stages four 16x16x16 tiles (one 32x32x8 tile) as those kernels do (same LDS layout and helpers);
+// Staging and decoding A and B, loading C and the reference and forming the exponent maxima cost about as much as
+// running one model, so that part is paid once per pass for all the models of a launch:
+//   * a workgroup pass stages four 16x16x16 tiles (one 32x32x8 tile) as the single-model kernels of emulate_tiled.hpp do
+//     (same LDS layout and helpers);
 //   * pass 1 runs once at the finest granularity, a quarter group of four products: the packed 16-bit maximum of each
 //     quarter is kept in LDS, two quarters per dword and thread;
 //   * the model loop reads per model six scalars from the kernel-argument segment (F, switches, output mask, NaN
@@ -15,7 +14,13 @@
 //   * arithmetic kinds: 0, the whole group summed in 32 bits; 1, folded into binary64 every four terms; 2, every term;
 //     3, F of 30 and more: terms truncated and summed in binary64 (values widened on load where the chunk is held in
 //     binary32);
-//   * the group epilogue, the special values (special_products) and the statistics are those of the per-class kernels.
+//   * group epilogue: the binary64 route of the single-model kernels, or (kind 0, every output of the wavefront with a
+//     normal result and no tagged element) a 32-bit route: the accumulator aligned like a product, the sum an integer,
+//     rho one int -> float conversion under the wavefront's rounding mode and an exact scaling;
+//   * every output is compared with the reference in registers; a differing output does one LDS atomic on a histogram
+//     bucket, the largest distance and first index are reduced over the wavefront by row shifts; a persistent workgroup
+//     writes its non-zero counters out once, at its end (a global atomic on a shared cache line costs about as much as a
+//     thousand instructions of a wave).
 // Models that flush subnormal inputs come last in a launch (the staged values are flushed in place once).
 #include "emulate_tiled.hpp"
 
@@ -505,18 +510,23 @@ static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const vo
     return MMAEMU_OK;
 }
 
-// Whether the one-launch kernel takes a model (then `kind` is its arithmetic kind): T-FDPA with the accumulator inside
-// the sum on whole 16x16x16 / 32x32x8 tiles of FP8 / FP16 / BF16 / FP6 / FP4 operands, group length 4, 8 or 16.
+// Whether the kernel takes a model, and the model's arithmetic kind: T-FDPA with the accumulator inside the sum on whole
+// 16x16x16 / 32x32x8 tiles of FP8 / FP16 / BF16 / FP6 / FP4 operands, group length 4, 8 or 16, F up to 40.
 bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind)
 {
-    int vm, nf;
-    if (!multi_class(p, ta, tb, m, n, k, A, B, vm, nf)) return false;
-    kind = vm == 2 ? 3u : (nf == 0 ? 0u : (nf == 4 ? 1u : 2u));
+    if (p.c_mode != MMAEMU_C_IN_GROUP || p.skip_zero_terms || p.zero_result_positive || (p.flags & (FL_ACC16 | FL_NAN_PROPAGATE))) return false;
+    if (!((m == 16 && n == 16 && k == 16) || (m == 32 && n == 32 && k == 8))) return false;
+    if (ta == MMAEMU_FP32 || tb == MMAEMU_FP32 || ta == MMAEMU_TF32 || tb == MMAEMU_TF32) return false;
+    if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) return false;
+    if (p.F > 40) return false;
+    if (!(p.L == 4 || p.L == 8 || (p.L == 16 && k == 16))) return false;
+    const uint64_t term = 1ull << (p.F + 2);                // |aligned term| < 2^(F+2)
+    kind = p.F >= 30 ? 3u : ((uint64_t)p.L * term <= (1ull << 31) ? 0u : (4 * term <= (1ull << 31) ? 1u : 2u));
     return true;
 }
 
-mmaemu_status launch_scan(const MultiLaunch &ml, const uint32_t *kinds, const void *A, const void *B, const void *C, uint32_t m, uint32_t n,
-                          uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s)
+mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
+                          uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s)
 {
     ScanArgs sa = {};
     sa.ta = ta;
@@ -531,7 +541,7 @@ mmaemu_status launch_scan(const MultiLaunch &ml, const uint32_t *kinds, const vo
     sa.stats = reinterpret_cast<uint64_t *>(ml.stats);
     for (uint32_t i = 0; i < ml.count; ++i) {
         sa.slot[i] = ml.slot[i];
-        sa.hot[i] = ScanArgs::Hot{ml.models[i].F, ml.models[i].flags, ml.models[i].out_mask, ml.models[i].nan_bits, ml.models[i].L, kinds[i]};
+        sa.hot[i] = ScanArgs::Hot{ml.models[i].F, ml.models[i].flags, ml.models[i].out_mask, ml.models[i].nan_bits, ml.models[i].L, ml.kind[i]};
     }
     const bool adapt = ta == MMAEMU_BF16 || tb == MMAEMU_BF16;
     const uint32_t *Cm = static_cast<const uint32_t *>(C);

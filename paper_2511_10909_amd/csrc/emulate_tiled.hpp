@@ -297,50 +297,7 @@ struct TiledArgs {
     uint32_t block;
 };
 
-// Several models over the same staged operands (the closed-loop scan of Sec. 3.1 Step 4: many candidate parameter sets,
-// each compared bit by bit with a reference, Eq. 2).  The table travels in the kernel-argument segment, whose first
-// bytes are still a TiledArgs.
-struct MultiArgs {
-    TiledArgs t;                       // operand types, exponent base; t.p is not used
-    uint32_t count;                    // models in this launch, 1 .. MULTI_MAX
-    uint32_t ref_is_first;             // no reference array: the first model's outputs are the reference
-    const uint32_t *dref;              // reference outputs [batch][m][n], or null
-    uint32_t *dout;                    // null, or every model's outputs: model i at dout + slot[i] * out_stride
-    uint64_t out_stride;               // elements
-    uint64_t index_base;               // added to the flattened output index in first_mismatch_index
-    uint64_t *stats;                   // the caller's mmaemu_stats array as 64-bit words (39 per struct)
-    uint32_t slot[MULTI_MAX];          // model i's place in the caller's arrays
-    struct Hot { int32_t F; uint32_t flags, out_mask, nan_bits; } hot[MULTI_MAX];     // what the model loop reads per model
-    ModelArgs models[MULTI_MAX];       // all parameters, for the rare routes
-};
-constexpr int STATS_WORDS = 39;        // sizeof(mmaemu_stats) / 8
-
-// The multi-model kernels' per-model scalars, read straight from the kernel-argument segment with scalar loads (the
-// segment pointer keeps its constant address space here, so the values arrive in scalar registers).
-__device__ __forceinline__ MultiArgs::Hot multi_hot(uint32_t mi)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    typedef const __attribute__((address_space(4))) MultiArgs *KArgs;
-    KArgs mu = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    MultiArgs::Hot h;
-    h.F = mu->hot[mi].F; h.flags = mu->hot[mi].flags; h.out_mask = mu->hot[mi].out_mask; h.nan_bits = mu->hot[mi].nan_bits;
-    return h;
-#else
-    return MultiArgs::Hot{};
-#endif
-}
-__device__ __forceinline__ uint32_t multi_count_and_ref(uint32_t &ref_is_first)
-{
-#if defined(__HIP_DEVICE_COMPILE__)
-    typedef const __attribute__((address_space(4))) MultiArgs *KArgs;
-    KArgs mu = (KArgs)__builtin_amdgcn_kernarg_segment_ptr();
-    ref_is_first = mu->ref_is_first;
-    return mu->count;
-#else
-    ref_is_first = 0;
-    return 0;
-#endif
-}
+constexpr int STATS_WORDS = 39;        // sizeof(mmaemu_stats) / 8 in 64-bit words
 
 // Binary32 rounding mode of the wavefront (bits 1:0 of the MODE register): to nearest even, or toward zero.
 __device__ __forceinline__ void set_f32_round_toward_zero(bool on)
@@ -551,19 +508,12 @@ struct MultiLds {
     unsigned long long first[MULTI_MAX];
 };
 
-// MULTI: the staged operands serve several models in turn (MultiArgs in the kernel-argument segment): whole k in one
-//          staged chunk, C_IN_GROUP, fixed group length; per model the outputs are compared with the reference in
-//          registers and only the statistics leave the workgroup (D on request).
-template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF, int VM_, bool MULTI>
+template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF, int VM_>
 __device__ __forceinline__ void
 tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm,
            uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nitems, uint32_t bm_count,
-           uint32_t bn_count, uint32_t xcd_remap, uint32_t wg_index, MultiLds *ml)
+           uint32_t bn_count, uint32_t xcd_remap, uint32_t wg_index)
 {
-    static_assert(!MULTI || (CMODE == MMAEMU_C_IN_GROUP && LT != 0 && VM_ <= 2), "several models: plain fused groups inside one staged chunk");
-    // (several models: whole tiles, so the row length of C and D is a constant and every output of a thread sits at a
-    // fixed offset from its first one; without that the model loop keeps three 64-bit addresses per output alive)
-    if constexpr (MULTI) { m = TM; n = TN; }
     constexpr bool SC = VM_ == 3;                     // block scales
     constexpr bool WIDE = VM_ == 4;                   // elements in 32-bit words (TF32)
     constexpr int VM = SC ? 0 : (WIDE ? 1 : VM_);     // how values are held
@@ -590,23 +540,11 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
     uint32_t *Be = reinterpret_cast<uint32_t *>(smem + VBYTES_A + VBYTES_B + EBYTES_A);
 
     const ModelArgs &p = ta_.p;
-    // (with several models these four are reloaded per model)
     int F = p.F;
     uint32_t fl = p.flags;                            // the model's switches, one bit each (one scalar register)
     uint32_t out_mask = p.out_mask, nan_bits = p.nan_bits;
-    uint32_t cur_model = 0;
-    bool slow_seen = false;                           // (several models) some group of the current model left the short route
     // the kernel's arguments once more, through a pointer the optimiser cannot see through (see slow_group)
-    auto fetch_args = [&]() -> TiledArgs {
-        if constexpr (MULTI) {
-            const MultiArgs *mu = reinterpret_cast<const MultiArgs *>(opaque_kernarg_ptr());
-            TiledArgs q = mu->t;
-            q.p = mu->models[cur_model];
-            return q;
-        } else {
-            return *reinterpret_cast<const TiledArgs *>(opaque_kernarg_ptr());
-        }
-    };
+    auto fetch_args = [&]() -> TiledArgs { return *reinterpret_cast<const TiledArgs *>(opaque_kernarg_ptr()); };
     // The group epilogues test the switches on a copy that is made opaque each time: otherwise every test is
     // hoisted out of the loops as a wave-wide mask (two scalar registers apiece, live across the hot loops).
     const int ec_floor = (fl & FL_ACC16) ? -14 : -126;          // smallest Exp of the accumulator's type
@@ -666,7 +604,7 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
                 d[r][c] = (fl & FL_ACC16) ? half_bits_to_float_bits(reinterpret_cast<const uint16_t *>(Cm)[o]) : Cm[o];
             }
     };
-    if constexpr (!MULTI) load_acc();
+    load_acc();
 
     const float *av = reinterpret_cast<const float *>(Av_raw) + (slot * TM + ti) * VS;
     const float *bv = reinterpret_cast<const float *>(Bv_raw) + (slot * TN + tj) * VS;
@@ -1059,46 +997,6 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
     auto end_of_group = [&](uint32_t kg, const int (&emax)[R][C], uint32_t tagged) {
         refresh_switches();
         flush_accumulators();
-        if constexpr (MULTI && CMODE == MMAEMU_C_IN_GROUP && !USE_SD && VM != 2) {
-            // Short route (in the multi-model kernels only: the single-model kernels with 4 x 4 register blocks have no
-            // registers to spare for a second route and lose a wave of occupancy to it).  When the L truncated products and the truncated accumulator together fit 32 bits
-            // ((L + 1) 2^(F+2) <= 2^31), the accumulator is aligned like a product (one multiplication by 2^(F - e_max),
-            // exact, and the float -> int conversion that truncates toward zero), the whole sum S is a 32-bit integer,
-            // and rho(S 2^(e_max - F)) is the int -> float conversion (RNE to 24 bits) followed by an exact scaling --
-            // as long as the result cannot be subnormal or the accumulator non-finite: e_max - F >= -126 and
-            // e_max <= 127 for every output of the wavefront, and no tagged element in the group.  Anything else takes
-            // the binary64 route below.  Results here are normal numbers, zero or an overflow, so the output flush has
-            // nothing to do; RZ steps back where the conversion rounded away from zero.
-            const bool fits = ((uint64_t)(GL + 1) << (F + 2)) <= (1ull << 31) && F >= 1 && !(fe & FL_ACC16);
-            if (fits) {
-                uint32_t worst = (tagged & SENTINEL_MASK) ? 0xFFFFFFFFu : 0u;
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int c = 0; c < C; ++c) {
-                        const uint32_t u = (uint32_t)(emax[r][c] - (F - 126));          // 0 .. 253 - F on this route
-                        worst = u > worst ? u : worst;
-                    }
-                if (__all(worst <= (uint32_t)(253 - F))) {
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int c = 0; c < C; ++c) {
-                            const float scale = __uint_as_float((uint32_t)(F + 127 - emax[r][c]) << 23);     // 2^(F - e_max), a normal number
-                            const int32_t S = S32[r][c] + (int32_t)(__uint_as_float(d[r][c]) * scale);
-                            const float f = (float)S;                                  // (truncates under RZ: see the model loop)
-                            uint32_t o = __float_as_uint(ldexpf(f, emax[r][c] - F));
-                            if ((fe & FL_RZ)) {
-                                if ((o & 0x7FFFFFFFu) == 0x7F800000u) o -= 1u;         // overflow: the largest finite number
-                                o &= out_mask;
-                            }
-                            d[r][c] = o;
-                        }
-                    return;
-                }
-            }
-        }
-        if constexpr (MULTI) slow_seen = true;
         double v[R][C];
         if (CMODE == MMAEMU_C_IN_GROUP) {
 #pragma unroll
@@ -1233,24 +1131,14 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
         else pass2f(g, emax);
     };
 
-    // (several models) the packed exponent maxima of every group, formed once per pass: they depend on the operands alone,
-    // so every model of the launch (all of one group length) starts its groups from them
-    __shared__ uint32_t m2_keep[MULTI ? KC / GL : 1][MULTI ? R * C : 1][MULTI ? 256 : 1];
     // the groups of one staged chunk, unsplit modes
     auto plain_groups = [&](uint32_t k0) {
-        constexpr int GU = (!MULTI && R * C <= 4 && KC / GL <= 4 && CMODE != MMAEMU_C_AFTER_RD) ? KC / GL : 1;
+        constexpr int GU = (R * C <= 4 && KC / GL <= 4 && CMODE != MMAEMU_C_AFTER_RD) ? KC / GL : 1;
 #pragma unroll GU
         for (int g = 0; g < KC / GL; ++g) {
             reset_group();
             load_scales(k0 + g * GL);
-            if constexpr (MULTI) {
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int c = 0; c < C; ++c) m2[r][c] = m2_keep[g][r * C + c][tid];
-            } else {
-                pass1(g);
-            }
+            pass1(g);
             int emax[R][C]; uint32_t tagged = 0;
 #pragma unroll
             for (int r = 0; r < R; ++r)
@@ -1262,138 +1150,6 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
     };
 
     prefetch(0);
-    if constexpr (MULTI) {
-        // ---- several models over one staged chunk (k == KC); statistics of each against the reference ----
-        const MultiArgs *mu = reinterpret_cast<const MultiArgs *>(opaque_kernarg_ptr());
-        constexpr int HC = HIST_COPIES;
-        uint32_t ref_first;
-        const uint32_t count = multi_count_and_ref(ref_first);
-        const uint32_t *dref = mu->dref;
-        // Passes of this workgroup: wg_index, wg_index + gridDim.x, ...  The operands of a pass are staged once, as the
-        // first model wants them.
-        const uint32_t nblocks = (uint32_t)((nitems + SLOTS - 1) / SLOTS);
-        uint32_t pass_wg = wg_index;
-        uint32_t c0[R][C], ref[R][C];
-        for (;;) {
-        // accumulator inputs and reference: read once per pass (before the staging, which hides their latency), held in
-        // registers across the models (a load per model would put a memory latency in front of every model's few
-        // hundred instructions)
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
-                c0[r][c] = Cm[o];
-                ref[r][c] = ref_first ? 0u : dref[o];
-            }
-        fl = multi_hot(0).flags;
-        commit(3);
-        const uint32_t following = pass_wg + gridDim.x;
-#pragma unroll 1
-        for (int g = 0; g < KC / GL; ++g) {
-            reset_group();
-            pass1(g);
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int c = 0; c < C; ++c) m2_keep[g][r * C + c][tid] = m2[r][c];     // (each thread its own words: no barrier needed)
-        }
-        int staged = (fl & FL_FTZ_IN) ? 1 : 0;                               // FlushSubnormal state of the staged values
-#pragma unroll 1
-        for (uint32_t mi = 0; mi < count; ++mi) {
-            cur_model = mi;
-            const MultiArgs::Hot hot = multi_hot(mi);
-            F = hot.F;
-            fl = hot.flags;
-            out_mask = hot.out_mask;
-            nan_bits = hot.nan_bits;
-            // rho = RZ-FP32: the model's groups run with the binary32 rounding mode "toward zero", so that the short route's
-            // int -> float conversion truncates (every other binary32 operation of the loop is exact in either mode, and
-            // the binary64 route checks the direction of its own conversion)
-            set_f32_round_toward_zero((fl & FL_RZ) != 0);
-            const int want = (fl & FL_FTZ_IN) ? 1 : 0;
-            if (want && !staged) {
-                // FlushSubnormal on the staged values, in place: whatever lies below the format's smallest normal
-                // number becomes +0.0 (exponents do not change: a subnormal keeps Exp = 1 - bias).  The host puts the
-                // flushing models last, so the operands are never fetched again and the staging plans die early.
-                __syncthreads();
-                const float min_a = min_normal_of(ta_.ta), min_b = min_normal_of(ta_.tb);
-                if (chunk_is_double) {
-                    double *va = reinterpret_cast<double *>(Av_raw), *vb = reinterpret_cast<double *>(Bv_raw);
-                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TM * VSD; i += 256) if (__builtin_fabs(va[i]) < (double)min_a) va[i] = 0.0;
-                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TN * VSD; i += 256) if (__builtin_fabs(vb[i]) < (double)min_b) vb[i] = 0.0;
-                } else {
-                    float *va = reinterpret_cast<float *>(Av_raw), *vb = reinterpret_cast<float *>(Bv_raw);
-                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TM * VS; i += 256) if (__builtin_fabsf(va[i]) < min_a) va[i] = 0.0f;
-                    _Pragma("unroll 1") for (uint32_t i = tid; i < SLOTS * TN * VS; i += 256) if (__builtin_fabsf(vb[i]) < min_b) vb[i] = 0.0f;
-                }
-                __syncthreads();
-                staged = 1;
-            }
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int c = 0; c < C; ++c) d[r][c] = c0[r][c];
-            slow_seen = false;
-            plain_groups(0);
-            // Per output that differs from the reference: one LDS atomic on its histogram bucket (bucket 0 of the LDS
-            // copy counts pairs that differ at distance 0: zeros of both signs, NaNs of two patterns), so the number of
-            // mismatches is the histogram's sum; the largest distance and the first index are reduced over the wavefront
-            // with row shifts, and lane 63 puts them into LDS.
-            uint32_t maxd = 0;
-            uint32_t first_off = 0xFFFFFFFFu;               // smallest offset (from the thread's first output) of a mismatch
-            if (live) {
-                uint32_t *dout = mu->dout;
-                const uint64_t dump_off = (uint64_t)mu->slot[mi] * mu->out_stride;
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int c = 0; c < C; ++c) {
-                        uint32_t x = d[r][c];
-                        if (slow_seen && (x & 0x7FFFFFFFu) > 0x7F800000u) x = nan_bits;          // (the short route produces no NaN)
-                        const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
-                        if (dout) dout[dump_off + o] = x;
-                        if (ref_first && mi == 0) ref[r][c] = x;
-                        const uint32_t y = ref[r][c];
-                        if (x != y) {
-                            const uint32_t off = (uint32_t)((TI * r) * TN + TJ * c);         // (a constant: nothing per output stays alive across models)
-                            first_off = off < first_off ? off : first_off;
-                            const uint32_t ax = x & 0x7FFFFFFFu, ay = y & 0x7FFFFFFFu;
-                            const bool nx = ax > 0x7F800000u, ny = ay > 0x7F800000u;
-                            uint32_t bucket;
-                            if (nx || ny) {
-                                bucket = (nx && ny) ? 0u : 33u;
-                                if (nx && ny) atomicAdd(&ml->naneq[mi], 1u);                 // (rare)
-                            } else {
-                                // distance of the ordered keys (sign-magnitude patterns read as signed integers): below 2^32
-                                const int32_t kx = (x >> 31) ? -(int32_t)ax : (int32_t)ax, ky = (y >> 31) ? -(int32_t)ay : (int32_t)ay;
-                                const uint32_t dist = kx >= ky ? (uint32_t)kx - (uint32_t)ky : (uint32_t)ky - (uint32_t)kx;
-                                maxd = dist > maxd ? dist : maxd;
-                                bucket = dist ? 32u - (uint32_t)__builtin_clz(dist) : 0u;
-                            }
-                            atomicAdd(&ml->hist[mi][bucket][tid & (HC - 1)], 1u);
-                        }
-                    }
-            }
-            // (offsets relative to the first output of this pass of the workgroup: 32 bits do for the reduction)
-            const uint32_t rel = first_off == 0xFFFFFFFFu ? 0xFFFFFFFFu : (uint32_t)(d_off - item0 * (uint64_t)(TM * TN)) + first_off;
-            const uint32_t wmin = wave_reduce_to_lane63<false>(rel), wmax = wave_reduce_to_lane63<true>(maxd);
-            if ((tid & 63u) == 63u && wmin != 0xFFFFFFFFu) {
-                atomicMin(&ml->first[mi], (unsigned long long)(mu->index_base + item0 * (uint64_t)(TM * TN) + wmin));
-                if (wmax) atomicMax(&ml->maxd[mi], wmax);
-            }
-        }
-        set_f32_round_toward_zero(false);
-        // (fetching the next pass's operands before the models run, so that they arrive meanwhile, was measured and made the
-        // closed-loop scan slower: the registers they occupy cost more than the latency they hide)
-        if (following >= nblocks) break;
-        pass_wg = following;
-        set_plans(pass_wg);
-        prefetch(0);
-        set_outputs(pass_wg);
-        }
-        return;
-    }
     if (LT != 0) {
         for (uint32_t k0 = 0; k0 < k; k0 += KC) {
             commit(3);
@@ -1586,56 +1342,7 @@ emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__re
                      uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nitems, uint32_t bm_count,
                      uint32_t bn_count, uint32_t xcd_remap)
 {
-    tiled_body<TM, TN, R, C, KC, LT, CMODE, NF, VM_, false>(ta_, A, B, Cm, D, m, n, k, nitems, bm_count, bn_count, xcd_remap, blockIdx.x, nullptr);
-}
-
-// Several models per launch (MultiArgs first, so that the argument segment still starts with a TiledArgs).  A
-// workgroup makes `passes` passes, each over the tiles of one logical workgroup of the single-model kernels, and
-// writes its statistics out once: a global atomic per non-zero counter and workgroup, on a handful of addresses that
-// every workgroup shares, costs about as much as a thousand instructions of a wave.
-template <int TM, int TN, int R, int C, int KC, int LT, int NF, int VM_>
-__global__ void __launch_bounds__(256)
-emulate_tiled_multi_kernel(MultiArgs mu_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm,
-                           uint32_t m, uint32_t n, uint32_t k, uint64_t nitems, uint32_t nblocks)
-{
-    __shared__ MultiLds ml;
-    const uint32_t tid = threadIdx.x;
-    constexpr int HC = HIST_COPIES;
-    for (uint32_t i = tid; i < MULTI_MAX * 34 * HC; i += 256) (&ml.hist[0][0][0])[i] = 0;
-    if (tid < MULTI_MAX) { ml.naneq[tid] = 0; ml.maxd[tid] = 0; ml.first[tid] = ~0ull; }
-    // (the first staging's barriers come before any thread counts anything)
-    if (blockIdx.x < nblocks)
-        tiled_body<TM, TN, R, C, KC, LT, MMAEMU_C_IN_GROUP, NF, VM_, true>(mu_.t, A, B, Cm, nullptr, m, n, k, nitems, 1u, 1u, 0u, blockIdx.x, &ml);
-    __syncthreads();
-    // one global atomic per non-zero counter per workgroup; n_compared and bucket 0 are known up front: workgroup 0
-    // adds the whole count once, every workgroup takes its non-zero buckets back out of bucket 0
-    const MultiArgs *mu = reinterpret_cast<const MultiArgs *>(opaque_kernarg_ptr());
-    const uint32_t count = mu->count;
-    unsigned long long *gst = reinterpret_cast<unsigned long long *>(mu->stats);
-    for (uint32_t i = tid; i < count * 34u; i += 256) {
-        const uint32_t mi = i / 34u, b = i - mi * 34u;
-        unsigned long long *g = gst + (uint64_t)mu->slot[mi] * STATS_WORDS;
-        if (b == 0) {
-            uint32_t nonzero = 0, mism = 0;
-            for (int bb = 1; bb < 34; ++bb)
-                for (int cpy = 0; cpy < HC; ++cpy) nonzero += ml.hist[mi][bb][cpy];
-            for (int cpy = 0; cpy < HC; ++cpy) mism += ml.hist[mi][0][cpy];         // differing patterns at distance 0
-            mism += nonzero;
-            const unsigned long long total = (unsigned long long)nitems * (TM * TN);
-            if (blockIdx.x == 0) { atomicAdd(&g[0], total); atomicAdd(&g[5], total); }
-            if (nonzero) atomicAdd(&g[5], 0ull - (unsigned long long)nonzero);
-            if (mism) {
-                atomicAdd(&g[1], (unsigned long long)mism);
-                atomicMin(&g[3], ml.first[mi]);
-            }
-            if (ml.naneq[mi]) atomicAdd(&g[2], (unsigned long long)ml.naneq[mi]);
-            if (ml.maxd[mi]) atomicMax(&g[4], (unsigned long long)ml.maxd[mi]);
-        } else {
-            uint32_t t = 0;
-            for (int cpy = 0; cpy < HC; ++cpy) t += ml.hist[mi][b][cpy];
-            if (t) atomicAdd(&g[5 + b], (unsigned long long)t);
-        }
-    }
+    tiled_body<TM, TN, R, C, KC, LT, CMODE, NF, VM_>(ta_, A, B, Cm, D, m, n, k, nitems, bm_count, bn_count, xcd_remap, blockIdx.x);
 }
 
 // ---- host side ---------------------------------------------------------------------------
@@ -1752,93 +1459,6 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
     }
     return MMAEMU_OK;
 }
-
-// ---- several models per launch ---------------------------------------------------------------
-struct MultiCall {
-    const void *A, *B;
-    const uint32_t *C;
-    uint32_t m, n, k;
-    uint64_t batch;
-};
-
-template <int TM, int TN, int R, int C, int KC, int LT, int NF, int VM>
-static mmaemu_status launch_multi_cfg(const MultiArgs &mu, const MultiCall &c, hipStream_t s)
-{
-    constexpr int SLOTS = 256 / ((TM / R) * (TN / C));
-    const uint64_t nitems = c.batch;                               // whole tiles: one block of D per tile
-    const uint64_t blocks = (nitems + SLOTS - 1) / SLOTS;
-    if (blocks > 0x7FFFFFFFull) { set_error("emulate_compare_many: too many blocks"); return MMAEMU_ERR_SHAPE; }
-    // Every workgroup ends with a few dozen global atomics on the same few cache lines, which the memory system takes one
-    // after the other.  Long launches (eight passes or more per workgroup at 2048 workgroups) amortise that tail and gain
-    // from the dispatcher's balancing of a grid beyond the resident set; short ones take as many workgroups as the device
-    // holds at once, and of those just enough that all make the same number of passes (measured: 30 % faster at 2^14
-    // tiles 16x16x16 per launch, 3 % slower at 2^16).
-    if (blocks == 0) return MMAEMU_OK;
-    uint32_t grid = 2048u;
-    if (blocks < 8u * 2048u) {
-        static uint32_t resident[16] = {};
-        int dev = 0;
-        MMAEMU_HIP(hipGetDevice(&dev));
-        uint32_t &res = resident[dev & 15];
-        if (!res) {
-            int per_cu = 0, cus = 0;
-            MMAEMU_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, emulate_tiled_multi_kernel<TM, TN, R, C, KC, LT, NF, VM>, 256, 0));
-            MMAEMU_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-            res = (uint32_t)(per_cu > 0 ? per_cu : 1) * (uint32_t)(cus > 0 ? cus : 1);
-        }
-        const uint64_t passes = (blocks + res - 1) / res;
-        grid = (uint32_t)((blocks + passes - 1) / passes);
-    }
-    hipLaunchKernelGGL((emulate_tiled_multi_kernel<TM, TN, R, C, KC, LT, NF, VM>), dim3(grid), dim3(256), 0, s,
-                       mu, c.A, c.B, c.C, c.m, c.n, c.k, nitems, (uint32_t)blocks);
-    MMAEMU_HIP(hipGetLastError());
-    set_last_kernel("multi x%u tiled %dx%d r%dx%d kc=%d L=%d c_mode=0 fold=%d vm=%d", mu.count, TM, TN, R, C, KC, LT, NF, VM);
-    return MMAEMU_OK;
-}
-
-template <int TM, int TN, int R, int C, int KC, int LT, int VM>
-static mmaemu_status launch_multi_fold(const MultiArgs &mu, const MultiCall &c, int nf, hipStream_t s)
-{
-    if constexpr (VM == 2) {
-        return launch_multi_cfg<TM, TN, R, C, KC, LT, 0, VM>(mu, c, s);
-    } else {
-        if (nf == 0) return launch_multi_cfg<TM, TN, R, C, KC, LT, 0, VM>(mu, c, s);
-        if constexpr (LT > 4) {                                 // (four terms that fit 32 bits are a whole group of four)
-            if (nf == 4) return launch_multi_cfg<TM, TN, R, C, KC, LT, 4, VM>(mu, c, s);
-        }
-        return launch_multi_cfg<TM, TN, R, C, KC, LT, 1, VM>(mu, c, s);
-    }
-}
-
-template <int TM, int TN, int R, int C, int KC, int VM>
-static mmaemu_status launch_multi_L(const MultiArgs &mu, const MultiCall &c, uint32_t L, int nf, hipStream_t s, bool &handled)
-{
-    handled = true;
-    if (L == 4) return launch_multi_fold<TM, TN, R, C, KC, 4, VM>(mu, c, nf, s);
-    if (L == 8) return launch_multi_fold<TM, TN, R, C, KC, 8, VM>(mu, c, nf, s);
-    if constexpr (KC >= 16) {
-        if (L == 16) return launch_multi_fold<TM, TN, R, C, KC, 16, VM>(mu, c, nf, s);
-    }
-    handled = false;
-    return MMAEMU_OK;
-}
-
-// the shapes whose whole k is one staged chunk: 16 x 16 x 16 and 32 x 32 x 8 tiles; nf: fold period as launch_fold picks it
-template <int VM>
-mmaemu_status launch_multi_shape(const MultiArgs &mu, const MultiCall &c, uint32_t L, int nf, hipStream_t s, bool &handled)
-{
-    handled = false;
-    // 2 x 2 register blocks throughout: with the accumulator inputs and the reference held in registers across the
-    // models, a 4 x 4 block would not fit two waves per SIMD
-    if (c.m == 16 && c.n == 16 && c.k == 16) return launch_multi_L<16, 16, 2, 2, 16, VM>(mu, c, L, nf, s, handled);
-    if (c.m == 32 && c.n == 32 && c.k == 8) return launch_multi_L<32, 32, 2, 2, 8, VM>(mu, c, L, nf, s, handled);
-    return MMAEMU_OK;
-}
-#define MMAEMU_MULTI_SIG(VM) \
-    mmaemu_status launch_multi_shape<VM>(const MultiArgs &, const MultiCall &, uint32_t, int, hipStream_t, bool &)
-extern template MMAEMU_MULTI_SIG(0);
-extern template MMAEMU_MULTI_SIG(1);
-extern template MMAEMU_MULTI_SIG(2);
 
 // explicit instantiations live in emulate_tiled_c<CMODE>v<VM>.hip (one translation unit each)
 #define MMAEMU_TILED_SIG(CM, VM)                                                                                        \
