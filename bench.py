@@ -38,7 +38,7 @@ def parse():
                     help="scan: the closed-loop scan (the headline); subnormal: the subnormal stress workload (2^26 fp16 32x32x8 "
                          "tiles, three flush variants) as the step, for its own profile")
     ap.add_argument("--tiles", type=int, default=0, help="tiles per operand type (default: the workload as stated, 2^24 / 2^26)")
-    ap.add_argument("--chunk", type=int, default=0, help="tiles generated and evaluated at a time (default 2^16 / 2^14)")
+    ap.add_argument("--chunk", type=int, default=0, help="tiles generated and evaluated at a time (default 2^16)")
     ap.add_argument("--unfused", action="store_true", help="one emulation launch and one comparison launch per parameter set")
     ap.add_argument("--time-every", type=int, default=16, help="HIP events around the emulation launches of every n-th chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -81,7 +81,7 @@ def cpu_baseline(target_seconds):
 def subnormal_stress(args, torch, mm, configs, fused):
     """The subnormal stress workload as the step (not the headline: it has fewer terms than the scan)."""
     n_tiles = args.tiles or (1 << 26)
-    chunk = min(args.chunk or (1 << 14), n_tiles)
+    chunk = min(args.chunk or (1 << 16), n_tiles)
     timed = []
 
     def timer(name, terms, fn):
