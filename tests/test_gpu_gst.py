@@ -16,7 +16,8 @@ def gpu_gst(mm, A, B, C, SA, SB, L, G, kb, F, rho, fmt, nan_bits=0x7FFFFFFF):
     try:
         dD = dev_empty((nb, m, n), np.uint32)
         mm.emulate_mma_scaled(h, to_dev(A), to_dev(B), to_dev(C), dD, to_dev(SA), to_dev(SB), kb, m, n, k, nb, (mm.E2M1, mm.E2M1, mm.FP32, mm.FP32))
-        assert mm.last_kernel() == "gst-fdpa"
+        want_kernel = "gst-fdpa, 16x16 blocks through LDS" if (m % 16 == 0 and n % 16 == 0 and G % 4 == 0 and (L or k) <= 256) else "gst-fdpa"
+        assert mm.last_kernel() == want_kernel, mm.last_kernel()
         return to_host(dD, np.uint32)
     finally:
         mm.model_destroy(h)
@@ -42,6 +43,38 @@ def test_gst_matches_oracle(mm, fmt, kb):
         want = o2lib.emulate_gst(A, B, C, SA, SB, L, G, kb, F, rho, fmt)
         got = gpu_gst(mm, A, B, C, SA, SB, L, G, kb, F, rho, fmt)
         assert_same(got, want, "gst L=%d G=%d kb=%d F=%d" % (L, G, kb, F))
+
+
+@pytest.mark.parametrize("fmt,kb", [(1, 16), (0, 32), (1, 32), (0, 16)])
+def test_gst_blocks_through_lds(mm, fmt, kb):
+    # shapes that take the kernel with operand sharing (16 x 16 blocks of D, dot products by v_dot4_i32_i8): every output
+    # against the C form of the oracle, a sample against the rational form
+    from oracle import gst as ogst
+    rng = np.random.default_rng(160 + 2 * kb + fmt)
+    for trial in range(8):
+        L, G = [(64, 16), (32, 8), (0, 16), (128, 4), (256, 16), (64, 32)][trial % 6]
+        if G > kb:
+            G = kb
+        k = 256 if L == 256 else 128
+        F = int(rng.choice([6, 20, 35, 40]))
+        rho = int(rng.integers(0, 2))
+        nb, m, n = [(3, 16, 16), (2, 32, 48), (1, 48, 16)][trial % 3]
+        A = rng.integers(0, 256, (nb, m, k)).astype(np.uint8)
+        B = rng.integers(0, 16, (nb, n, k)).astype(np.uint8)
+        lo, hi = ((0x08, 0x7F) if trial % 3 else (0x00, 0x100)) if fmt == 1 else ((100, 150) if trial % 3 else (0, 256))
+        SA = rng.integers(lo, hi, (nb, m, k // kb)).astype(np.uint8)
+        SB = rng.integers(lo, hi, (nb, n, k // kb)).astype(np.uint8)
+        C = (rng.standard_normal((nb, m, n)) * 2.0 ** rng.integers(-30, 30, (nb, m, n))).astype(np.float32).view(np.uint32)
+        C.flat[0] = 0x7F800000
+        C.flat[-1] = 0xFFC00000
+        want = o2lib.emulate_gst(A, B, C, SA, SB, L, G, kb, F, rho, fmt)
+        got = gpu_gst(mm, A, B, C, SA, SB, L, G, kb, F, rho, fmt)
+        assert mm.last_kernel() == "gst-fdpa, 16x16 blocks through LDS"
+        assert_same(got, want, "gst blocks L=%d G=%d kb=%d F=%d" % (L, G, kb, F))
+        for (ti, ii, jj) in ((0, 0, 0), (0, 1, 2), (nb - 1, m - 1, n - 1), (0, 5, 15)):
+            w1 = ogst.emulate_element(A[ti, ii].tolist(), B[ti, jj].tolist(), int(C[ti, ii, jj]), SA[ti, ii].tolist(), SB[ti, jj].tolist(),
+                                      L or k, G, kb, F, rho, fmt)
+            assert int(got[ti, ii, jj]) == w1, ("rational form", ti, ii, jj)
 
 
 def test_gst_presets_and_errors(mm):
