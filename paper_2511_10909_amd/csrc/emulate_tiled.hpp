@@ -1427,18 +1427,16 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
 {
     handled = false;
     const uint64_t outputs = batch * m * n;
-    // whole small tiles of a batch (binary64 values need twice the LDS: fewer tiles per workgroup; half groups keep
-    // a second set of sums and maxima per output: smaller register blocks)
-    constexpr bool BIG_BLOCKS = (VM == 0 || VM == 3) && CMODE != CM_RD_HALVES && CMODE != CM_RD_QUARTERS;
+    // Whole small tiles of a batch.  16 x 16 tiles take 2 x 2 register blocks: at about 100 vector registers such a kernel
+    // runs four or five waves per SIMD, which on tiles this small is worth more than the halved LDS traffic of 4 x 4
+    // blocks at two waves (measured 15 to 30 % on 16x16x16 / 16x16x32 tiles; 32x32x8 tiles are 4 to 10 % faster with 4 x 4).
+    // Half and quarter groups keep a second set of sums and maxima per output: no 4 x 4 blocks for them anywhere.
     constexpr bool BIG_BLOCKS_OK = CMODE != CM_RD_HALVES && CMODE != CM_RD_QUARTERS;
     if constexpr (CMODE == CM_RD_QUARTERS) {
         // (groups of 32 on 16 x 16 tiles: staged 32 k at a time)
         if (m == 16 && n == 16 && k % 32 == 0 && ta.p.L == 32) return launch_L<16, 16, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     }
-    if (m == 16 && n == 16 && k % 16 == 0) {
-        if constexpr (BIG_BLOCKS) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
-        else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
-    }
+    if (m == 16 && n == 16 && k % 16 == 0) return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if constexpr (VM == 4) {
         // (the TF32 instructions' own shape, 16 x 16 x 8)
         if (m == 16 && n == 16 && k % 8 == 0) return launch_L<16, 16, 2, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
@@ -1453,10 +1451,7 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
         return launch_L<32, 32, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
         return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
-    if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) {
-        if constexpr (BIG_BLOCKS) return launch_L<16, 16, 4, 4, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
-        else return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
-    }
+    if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     return MMAEMU_OK;
 }
 
