@@ -1442,7 +1442,7 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
         if (m == 16 && n == 16 && k % 8 == 0) return launch_L<16, 16, 2, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     }
     if (m == 32 && n == 32 && k % 8 == 0 && k % 32 != 0)
-        return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     // blocks of a larger problem: 4x4 register blocks once there are enough outputs to fill
     // the chip with them (256 CUs x 4 SIMDs x 2 waves x 64 lanes x 16), 2x2 blocks otherwise
     if (BIG_BLOCKS_OK && m % 64 == 0 && n % 64 == 0 && k % 32 == 0 && outputs >= (1ull << 21))
@@ -1450,7 +1450,7 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
     if (m % 32 == 0 && n % 32 == 0 && k % 32 == 0)
         return launch_L<32, 32, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
-        return launch_L<32, 32, 4, 4, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+        return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     return MMAEMU_OK;
 }
