@@ -55,8 +55,11 @@ __device__ __forceinline__ ScanArgs::Hot scan_hot(uint32_t mi)
 
 // TM x TM x KC tiles (16 x 16 x 16 or 32 x 32 x 8), 2 x 2 outputs per thread; ADAPT: BF16 operands, whose staged chunk is
 // held in binary64 when any element lies outside [2^-31, 2^32).
+// (Four waves per SIMD are asked for outright: left alone the compiler settles at about 150 vector registers and three waves;
+// the handful of registers that go to scratch instead cost less than the fourth wave brings: +6 % on both workloads.
+// Five waves were slower.)
 template <int TM, int KC, bool ADAPT>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
 emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm, uint64_t nitems, uint32_t nblocks)
 {
     constexpr int R = 2, C = 2, TN = TM;

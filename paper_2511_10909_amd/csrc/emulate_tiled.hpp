@@ -501,7 +501,7 @@ __device__ __noinline__ uint2 special_products(const void *a, const void *b, uin
 // VM      : value mode (see the head of this file).
 // Per-workgroup statistics of the multi-model kernels, in LDS: filled by every pass of a workgroup over its tiles,
 // written out once at the end of the kernel.
-constexpr int HIST_COPIES = 4;
+constexpr int HIST_COPIES = 2;
 struct MultiLds {
     uint32_t hist[MULTI_MAX][34][HIST_COPIES];     // pairs that differ, by bucket (bucket 0: patterns differ at distance 0)
     uint32_t naneq[MULTI_MAX], maxd[MULTI_MAX];
