@@ -79,7 +79,6 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
     if (tid < MULTI_MAX) { ml.naneq[tid] = 0; ml.maxd[tid] = 0; ml.first[tid] = ~0ull; }
     // (the first staging's barriers come before any thread counts anything)
 
-    constexpr int NQ = (SLOTS * TM * (KC / 4) + 255) / 256;          // operand quads a thread stages per matrix
     unsigned char *Av_raw = smem, *Bv_raw = smem + VBYTES;
     uint32_t *Ae = reinterpret_cast<uint32_t *>(smem + 2 * VBYTES);
     uint32_t *Be = reinterpret_cast<uint32_t *>(smem + 2 * VBYTES + EBYTES);
@@ -98,43 +97,28 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
     const uint32_t count = sa_.count, ref_first = sa_.ref_is_first;
     const uint32_t *dref = sa->dref;
 
-    // A pass's global loads (operand quads, accumulator inputs, reference) are issued one pass ahead, right after the
-    // previous pass has been staged, so that they arrive while its models run.
-    StagePlan<NQ> plan_a, plan_b;                                 // (the LDS offsets in them depend on the thread alone)
-    uint2 nraw_a[NQ], nraw_b[NQ];
-    uint32_t nc0[R][C], nref[R][C];
-    auto fetch_pass = [&](uint32_t wg) {
-        const uint64_t it0 = (uint64_t)wg * SLOTS;
-        make_plan<TM, KC, SLOTS, VS, ES, true, NQ>(plan_a, A, esa, it0, nitems, 1u, 1u, TM, KC);
-        make_plan<TN, KC, SLOTS, VS, ES, false, NQ>(plan_b, B, esb, it0, nitems, 1u, 1u, TN, KC);
-        load_panel<NQ>(esa, plan_a, 0, nraw_a);
-        load_panel<NQ>(esb, plan_b, 0, nraw_b);
-        const uint64_t tile = it0 + slot < nitems ? it0 + slot : nitems - 1;
-        const uint64_t off = (tile * TM + ti) * (uint64_t)TN + tj;
+    constexpr int NQ = (SLOTS * TM * (KC / 4) + 255) / 256;
+    for (uint32_t pass_wg = blockIdx.x; pass_wg < nblocks; pass_wg += gridDim.x) {
+        // ---- this pass's tiles: staging plans, outputs, operands in flight ----
+        const uint64_t item0 = (uint64_t)pass_wg * SLOTS;
+        StagePlan<NQ> plan_a, plan_b;
+        make_plan<TM, KC, SLOTS, VS, ES, true, NQ>(plan_a, A, esa, item0, nitems, 1u, 1u, TM, KC);
+        make_plan<TN, KC, SLOTS, VS, ES, false, NQ>(plan_b, B, esb, item0, nitems, 1u, 1u, TN, KC);
+        uint2 raw_a[NQ], raw_b[NQ];
+        load_panel<NQ>(esa, plan_a, 0, raw_a);
+        load_panel<NQ>(esb, plan_b, 0, raw_b);
+        const bool live = item0 + slot < nitems;
+        const uint64_t my_tile = live ? item0 + slot : nitems - 1;
+        const uint64_t d_off = (my_tile * TM + ti) * (uint64_t)TN + tj;             // + TI * r * TN + TJ * c
+        uint32_t c0[R][C], ref[R][C];
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                const uint64_t o = off + (uint64_t)(TI * r) * TN + TJ * c;
-                nc0[r][c] = Cm[o];
-                nref[r][c] = ref_first ? 0u : dref[o];
+                const uint64_t o = d_off + (uint64_t)(TI * r) * TN + TJ * c;
+                c0[r][c] = Cm[o];
+                ref[r][c] = ref_first ? 0u : dref[o];
             }
-    };
-    if (blockIdx.x < nblocks) fetch_pass(blockIdx.x);
-    for (uint32_t pass_wg = blockIdx.x; pass_wg < nblocks; pass_wg += gridDim.x) {
-        // ---- this pass's tiles ----
-        const uint64_t item0 = (uint64_t)pass_wg * SLOTS;
-        const bool live = item0 + slot < nitems;
-        const uint64_t my_tile = live ? item0 + slot : nitems - 1;
-        const uint64_t d_off = (my_tile * TM + ti) * (uint64_t)TN + tj;             // + TI * r * TN + TJ * c
-        uint2 raw_a[NQ], raw_b[NQ];
-        uint32_t c0[R][C], ref[R][C];
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) { raw_a[q] = nraw_a[q]; raw_b[q] = nraw_b[q]; }
-#pragma unroll
-        for (int r = 0; r < R; ++r)
-#pragma unroll
-            for (int c = 0; c < C; ++c) { c0[r][c] = nc0[r][c]; ref[r][c] = nref[r][c]; }
         // ---- decode and stage (as the first model wants them) ----
         bool chunk_is_double = false;
         int staged;
@@ -151,7 +135,6 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             store_panel<NQ, VS, VSD>(plan_b, fb, xb, Bv_raw, Be, chunk_is_double, 3);
             __syncthreads();
         }
-        if (pass_wg + gridDim.x < nblocks) fetch_pass(pass_wg + gridDim.x);
         // ---- pass 1, once: the maximum of e'_a + e'_b over each quarter group, two quarters per kept dword ----
 #pragma unroll
         for (int q = 0; q < NQ4; ++q) {
