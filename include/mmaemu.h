@@ -71,8 +71,8 @@ typedef enum {
 
 typedef struct {
     uint32_t a, b, c, d; /* mmaemu_dtype values; a, b in {E4M3, E5M2, FP16, BF16, FP32, E2M3, E3M2, E2M1, TF32} (the FP6 /
-                            FP4 types pair with each other and with the FP8 types, TF32 and FP32 each with itself; TF32
-                            and FP32 operands and frac_bits above 40 run in the general kernel); c = d = FP32, or c = d = FP16
+                            FP4 types pair with each other and with the FP8 types, TF32 and FP32 each with itself; FP32
+                            operands and frac_bits above 40 run in the general kernel); c = d = FP32, or c = d = FP16
                             (Algorithm "T-FDPA" with F_C = FP16: the accumulator is decoded as binary16, Exp >= -14,
                             rho is RNE-FP16 of Table "Conversion functions" (RZ likewise), both flushes use 2^-14, the
                             NaN pattern is the low half of nan_bits; c_mode C_IN_GROUP or C_AFTER_EXACT only) */

@@ -204,7 +204,9 @@ __device__ __forceinline__ void make_plan(StagePlan<NQ> &pl, const void *base, u
         uint64_t tile; uint32_t rem;
         split_item(it, bm_count * bn_count, tile, rem);
         const uint32_t blk = IS_A ? rem / bn_count : rem % bn_count;
-        const uint64_t grow = tile * rows_per_tile + (uint64_t)blk * ROWS + row;
+        uint32_t rit = blk * ROWS + row;                      // row inside the tile
+        rit = rit < rows_per_tile ? rit : rows_per_tile - 1;  // (a ragged edge block repeats the tile's last row)
+        const uint64_t grow = tile * rows_per_tile + rit;
         pl.src[i] = reinterpret_cast<const uint8_t *>(base) + grow * k * esize;
         pl.voff[i] = (slot * ROWS + row) * VS + 4 * kq;
         pl.eoff[i] = (slot * ROWS + row) * ES + 2 * kq;
@@ -595,14 +597,30 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
 
     // C in (each thread its own elements; measured faster here than moving the block through LDS)
     uint32_t d[R][C];
+    // Ragged m or n (32 x 32 blocks of a larger problem, groups inside a staged chunk): edge blocks stage the tile's last
+    // row again for the rows beyond it, their threads load the accumulator of the clamped place and store nothing there.
+    constexpr bool EDGES = TM == 32 && TN == 32 && !SC && LT != 0;
+    const bool ragged = EDGES && ((m % TM) | (n % TN)) != 0;      // uniform
     auto load_acc = [&]() {
+        auto take = [&](int r, int c, uint64_t o) {
+            d[r][c] = (fl & FL_ACC16) ? half_bits_to_float_bits(reinterpret_cast<const uint16_t *>(Cm)[o]) : Cm[o];
+        };
+        if constexpr (EDGES) {
+            if (ragged) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        const uint32_t i = i_base + TI * r, j = j_base + TJ * c;
+                        take(r, c, (my_tile * m + (i < m ? i : m - 1)) * (uint64_t)n + (j < n ? j : n - 1));
+                    }
+                return;
+            }
+        }
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
-                d[r][c] = (fl & FL_ACC16) ? half_bits_to_float_bits(reinterpret_cast<const uint16_t *>(Cm)[o]) : Cm[o];
-            }
+            for (int c = 0; c < C; ++c) take(r, c, d_off + (uint64_t)(TI * r) * n + TJ * c);
     };
     load_acc();
 
@@ -1324,15 +1342,29 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
 #pragma unroll
         for (int c = 0; c < C; ++c)
             if ((d[r][c] & 0x7FFFFFFFu) > 0x7F800000u) d[r][c] = nan_bits;
+    auto put = [&](int r, int c) {
+        const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
+        if (fl & FL_ACC16) reinterpret_cast<uint16_t *>(D)[o] = (uint16_t)(d[r][c] == nan_bits ? p.nan16 : float_bits_to_half_bits(d[r][c]));
+        else D[o] = d[r][c];
+    };
+    if constexpr (EDGES) {
+        if (ragged) {
+            if (live) {
+                set_outputs(wg_index);                            // (the places again, rather than kept across the loops)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c)
+                        if (i_base + TI * r < m && j_base + TJ * c < n) put(r, c);
+            }
+            return;
+        }
+    }
     if (live) {
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const uint64_t o = d_off + (uint64_t)(TI * r) * n + TJ * c;
-                if (fl & FL_ACC16) reinterpret_cast<uint16_t *>(D)[o] = (uint16_t)(d[r][c] == nan_bits ? p.nan16 : float_bits_to_half_bits(d[r][c]));
-                else D[o] = d[r][c];
-            }
+            for (int c = 0; c < C; ++c) put(r, c);
     }
 }
 
@@ -1352,7 +1384,7 @@ static mmaemu_status launch_cfg(const TiledArgs &ta, const void *A, const void *
                                 uint32_t n, uint32_t k, uint64_t batch, hipStream_t s)
 {
     constexpr int SLOTS = 256 / ((TM / R) * (TN / C));
-    const uint32_t bm = m / TM, bn = n / TN;
+    const uint32_t bm = (m + TM - 1) / TM, bn = (n + TN - 1) / TN;          // (edge blocks: see launch_tiled_shape)
     const uint64_t nitems = batch * bm * bn;
     const uint64_t blocks = (nitems + SLOTS - 1) / SLOTS;
     if (blocks > 0x7FFFFFFFull) { set_error("emulate_mma: too many blocks"); return MMAEMU_ERR_SHAPE; }
@@ -1385,7 +1417,7 @@ static mmaemu_status launch_fold(const TiledArgs &ta, const void *A, const void 
 
 template <int TM, int TN, int R, int C, int KC, int CMODE, int VM>
 static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B, const void *Cm, void *D, uint32_t m,
-                              uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, bool &handled)
+                              uint32_t n, uint32_t k, uint64_t batch, hipStream_t s, bool &handled, bool edges = false)
 {
     handled = true;
     const uint32_t L = ta.p.L;
@@ -1413,8 +1445,8 @@ static mmaemu_status launch_L(const TiledArgs &ta, const void *A, const void *B,
     if constexpr (KC >= 32) {
         if (L == 32) return launch_fold<TM, TN, R, C, KC, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     }
-    if constexpr (VM != 3) {        // (a scaled group lies inside one chunk)
-        if (L % KC == 0) return launch_fold<TM, TN, R, C, KC, 0, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+    if constexpr (VM != 3) {        // (a scaled group lies inside one chunk; so must the groups of a problem with edge blocks)
+        if (L % KC == 0 && !edges) return launch_fold<TM, TN, R, C, KC, 0, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
     }
     handled = false;
     return MMAEMU_OK;
@@ -1452,6 +1484,13 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
     if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
         return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    // Ragged m or n, more than one block each way: 32 x 32 blocks whose edge blocks repeat the last row and store only
+    // what lies inside (groups of 4 to 32 terms, which lie inside a staged chunk; not the block-scaled kernels).  Tiles
+    // of at most one block stay with the general kernel: padded to 32 x 32 they would mostly compute nothing.
+    if constexpr (VM != 3) {
+        if (m > 32 && n > 32 && k % 32 == 0) return launch_L<32, 32, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled, true);
+        if (m > 32 && n > 32 && k % 8 == 0) return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled, true);
+    }
     return MMAEMU_OK;
 }
 
