@@ -53,19 +53,37 @@ __device__ __forceinline__ ScanArgs::Hot scan_hot(uint32_t mi)
 #endif
 }
 
-// TM x TM x KC tiles (16 x 16 x 16 or 32 x 32 x 8), 2 x 2 outputs per thread; ADAPT: BF16 operands, whose staged chunk is
+// TM x TM x KC tiles (16 x 16 x 16, 16 x 16 x 32, 32 x 32 x 8 or 32 x 32 x 16: the whole k of a tile is staged at once), 2 x 2
+// outputs per thread; ADAPT: BF16 operands, whose staged chunk is
 // held in binary64 when any element lies outside [2^-31, 2^32).
-// (Four waves per SIMD are asked for outright: left alone the compiler settles at about 150 vector registers and three waves;
-// the handful of registers that go to scratch instead cost less than the fourth wave brings: +6 % on both workloads.
-// Five waves were slower.)
+// (Four waves per SIMD are asked for outright where the LDS allows four workgroups per CU: left alone the compiler settles
+// at about 150 vector registers and three waves; the handful of registers that go to scratch instead cost less than the
+// fourth wave brings: +6 % on both workloads.  Five waves were slower.  The 16 x 16 x 32 instantiations hold two or three
+// workgroups per CU and are compiled for that many waves.)
+// LDS of one workgroup: staged values and exponents, the kept quarter maxima, the statistics
 template <int TM, int KC, bool ADAPT>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4)))
+constexpr int scan_lds_bytes()
+{
+    constexpr int SLOTS = 256 / ((TM / 2) * (TM / 2));
+    constexpr int VS = KC + 4, VSD = KC + 2, ES = KC / 2 + (KC == 8 ? 4 : 2);
+    return 2 * SLOTS * TM * (ADAPT ? VSD * 8 : VS * 4) + 2 * SLOTS * TM * ES * 4 + ((KC / 4 + 1) / 2) * 4 * 256 * 4 + (int)sizeof(MultiLds);
+}
+// workgroups (of four waves, one per SIMD) that a CU's 160 KB of LDS hold, four at most: the waves per SIMD to compile for
+template <int TM, int KC, bool ADAPT>
+constexpr int scan_waves()
+{
+    constexpr int by_lds = (160 * 1024) / scan_lds_bytes<TM, KC, ADAPT>();
+    return by_lds >= 4 ? 4 : by_lds;
+}
+
+template <int TM, int KC, bool ADAPT>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(scan_waves<TM, KC, ADAPT>(), scan_waves<TM, KC, ADAPT>())))
 emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm, uint64_t nitems, uint32_t nblocks)
 {
     constexpr int R = 2, C = 2, TN = TM;
     constexpr int TI = TM / R, TJ = TN / C, TPS = TI * TJ, SLOTS = 256 / TPS;
     static_assert(TPS * SLOTS == 256, "thread layout");
-    constexpr int VS = KC + 4, VSD = KC + 2, ES = KC / 2 + (KC == 16 ? 2 : 4);
+    constexpr int VS = KC + 4, VSD = KC + 2, ES = KC / 2 + (KC == 8 ? 4 : 2);
     constexpr int NQ4 = KC / 4;                                   // quarter groups per row
     constexpr int NK2 = (NQ4 + 1) / 2;                            // dwords of kept maxima per output
     constexpr int VBYTES = SLOTS * TM * (ADAPT ? VSD * 8 : VS * 4);
@@ -210,7 +228,8 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                                 e = (m2k[g / 2][r * C + c][tid] >> (16 * (g & 1))) & 0xFFFFu;
                             } else {
                                 uint32_t x = m2k[g * (GL / 8)][r * C + c][tid];
-                                if constexpr (GL == 16) x = pk_max_u16(x, m2k[g * 2 + 1][r * C + c][tid]);
+#pragma unroll
+                                for (int i = 1; i < GL / 8; ++i) x = pk_max_u16(x, m2k[g * (GL / 8) + i][r * C + c][tid]);
                                 const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
                                 e = lo > hi ? lo : hi;
                             }
@@ -400,7 +419,8 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             };
             if (L == 4) by_kind(std::integral_constant<int, 4>{});
             else if (L == 8) by_kind(std::integral_constant<int, 8>{});
-            else by_kind(std::integral_constant<int, 16>{});
+            else if (L == 16) by_kind(std::integral_constant<int, 16>{});
+            else by_kind(std::integral_constant<int, 32>{});                 // (no code where KC is below 32)
 
             // ---- this model's outputs against the reference ----
             // Per output that differs: one LDS atomic on its histogram bucket (bucket 0 of the LDS copy counts pairs that
@@ -514,15 +534,15 @@ static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const vo
 }
 
 // Whether the kernel takes a model, and the model's arithmetic kind: T-FDPA with the accumulator inside the sum on whole
-// 16x16x16 / 32x32x8 tiles of FP8 / FP16 / BF16 / FP6 / FP4 operands, group length 4, 8 or 16, F up to 40.
+// 16x16x16, 16x16x32, 32x32x8 or 32x32x16 tiles of FP8 / FP16 / BF16 / FP6 / FP4 operands, group length 4, 8, 16 or 32, F up to 40.
 bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind)
 {
     if (p.c_mode != MMAEMU_C_IN_GROUP || p.skip_zero_terms || p.zero_result_positive || (p.flags & (FL_ACC16 | FL_NAN_PROPAGATE))) return false;
-    if (!((m == 16 && n == 16 && k == 16) || (m == 32 && n == 32 && k == 8))) return false;
+    if (!((m == 16 && n == 16 && (k == 16 || k == 32)) || (m == 32 && n == 32 && (k == 8 || k == 16)))) return false;
     if (ta == MMAEMU_FP32 || tb == MMAEMU_FP32 || ta == MMAEMU_TF32 || tb == MMAEMU_TF32) return false;
     if ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 7) return false;
     if (p.F > 40) return false;
-    if (!(p.L == 4 || p.L == 8 || (p.L == 16 && k == 16))) return false;
+    if (!(p.L == 4 || p.L == 8 || p.L == 16 || p.L == 32) || p.L > k) return false;
     const uint64_t term = 1ull << (p.F + 2);                // |aligned term| < 2^(F+2)
     kind = p.F >= 30 ? 3u : ((uint64_t)p.L * term <= (1ull << 31) ? 0u : (4 * term <= (1ull << 31) ? 1u : 2u));
     return true;
@@ -550,6 +570,8 @@ mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, c
     const uint32_t *Cm = static_cast<const uint32_t *>(C);
     if (m == 16 && n == 16 && k == 16) return adapt ? launch_scan_cfg<16, 16, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<16, 16, false>(sa, A, B, Cm, batch, s);
     if (m == 32 && n == 32 && k == 8) return adapt ? launch_scan_cfg<32, 8, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<32, 8, false>(sa, A, B, Cm, batch, s);
+    if (m == 16 && n == 16 && k == 32) return adapt ? launch_scan_cfg<16, 32, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<16, 32, false>(sa, A, B, Cm, batch, s);
+    if (m == 32 && n == 32 && k == 16) return adapt ? launch_scan_cfg<32, 16, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<32, 16, false>(sa, A, B, Cm, batch, s);
     set_error("emulate_compare_many: no kernel for this shape");
     return MMAEMU_ERR_UNSUPPORTED;
 }

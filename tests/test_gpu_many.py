@@ -82,6 +82,33 @@ def test_sixteen_sets_against_a_reference_array(mm, ta, tb):
         assert got_stats[i] == ostats.compare(want[i], ref, index_base=5_000_000_000), (i, p)
 
 
+@pytest.mark.parametrize("ta,tb,m,k", [(fm.BF16, fm.BF16, 16, 32), (fm.E4M3, fm.E5M2, 16, 32), (fm.FP16, fm.FP16, 16, 32),
+                                       (fm.FP16, fm.FP16, 32, 16), (fm.BF16, fm.BF16, 32, 16), (fm.E5M2, fm.E4M3, 32, 16)])
+def test_sixteen_sets_on_the_longer_tile_shapes(mm, ta, tb, m, k):
+    # 16x16x32 and 32x32x16 (the shapes of the newer MFMA instructions): the whole k of a tile staged at once, groups of up to 32
+    rng = np.random.default_rng(300 + 8 * ta + k)
+    nb = 53
+    A, B, C = make_case(rng, ta, tb, nb, m, m, k, c_exp=(100, 140))
+    if ta == fm.BF16:
+        A[: nb // 2] = synth.narrow_exponent_bits(rng, (nb // 2, m, k), ta, 110, 140)
+        B[: nb // 2] = synth.narrow_exponent_bits(rng, (nb // 2, m, k), tb, 110, 140)
+    A[-6:] = synth.sprinkle(rng, A[-6:], synth.SPECIAL_CODES[ta], 0.02)        # NaN and infinities in the last tiles
+    plist = sets16()
+    want = oracle_outputs(plist, A, B, C, ta, tb)
+    ref = want[6].copy()
+    flat = ref.reshape(-1)
+    idx = rng.choice(flat.size, size=flat.size // 40, replace=False)
+    flat[idx] += rng.integers(1, 1000, size=idx.size).astype(np.uint32)
+    got_stats, got_D, kern, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, index_base=77)
+    assert kern.startswith("multi x16 tiled %dx%d r2x2 kc=%d" % (m, m, k)), kern
+    for i, p in enumerate(plist):
+        assert_same(got_D[i], want[i], "set %d %s" % (i, p))
+        assert got_stats[i] == ostats.compare(want[i], ref, index_base=77), (i, p)
+    # the rational form of the oracle on the first tile
+    for i in (1, 7, 12, 15):
+        assert_same(got_D[i][:1], o1_emulate(plist[i], A[:1], B[:1], C[:1], ta, tb), "rational oracle, set %d" % i)
+
+
 def test_sets_without_dump_give_the_same_statistics_and_accumulate(mm):
     rng = np.random.default_rng(7)
     ta, tb = fm.E4M3, fm.E5M2
