@@ -292,11 +292,15 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
  * output), or, when Dref is NULL, the output of models[0] (whose own row then reports no mismatch).
  * D_out: NULL, or device memory for n_models * batch * m * n FP32 patterns; model i's outputs are then also written
  * at D_out + i * batch * m * n.  D_out must not overlap A, B, C or Dref.
- * Models of the FDPA family with c_mode C_IN_GROUP, no variation switches, frac_bits <= 40 and group length 4, 8, 16
- * or 32, on 16 x 16 x 16, 16 x 16 x 32, 32 x 32 x 8 or 32 x 32 x 16 tiles with 8-byte aligned A and B of 8- or 16-bit types, run in a kernel that stages
- * and decodes the operands once for up to 16 models (any mix of group lengths and widths) and keeps every output in
- * registers: D reaches memory only on request.  Any other model runs through mmaemu_emulate_mma and mmaemu_compare and needs
- * D_out, as does a reference taken from models[0] when the models do not all fit one such launch.
+ * Models of the FDPA family with frac_bits <= 40 and group length 4, 8, 16 or 32, on 16 x 16 x 16, 16 x 16 x 32,
+ * 32 x 32 x 8 or 32 x 32 x 16 tiles with 8-byte aligned A and B of 8- or 16-bit types, run in a kernel that stages and
+ * decodes the operands once for up to 16 models (any mix of group lengths and widths) and keeps every output in
+ * registers: D reaches memory only on request.  Two families of models run that way, each in launches of its own:
+ * c_mode C_IN_GROUP without variation switches (Algorithm "T-FDPA"), and c_mode C_AFTER_RD with unsplit groups
+ * (Algorithm "TR-FDPA") and any of its variation switches (sets that keep zero terms out of the maxima launch apart from
+ * those that do not, and then also by ftz_in; not: wide_products with BF16 operands).  Any other model runs through
+ * mmaemu_emulate_mma and mmaemu_compare and needs D_out, as does a reference taken from models[0] when the models do not
+ * all fit one such launch.
  * At most MMAEMU_COMPARE_MANY_MAX models per call.  batch = 0 is a no-op.
  * Errors: as mmaemu_emulate_mma; UNSUPPORTED (FP16 accumulators; D_out needed but NULL), INVALID_ARG (n_models, NULL).
  */

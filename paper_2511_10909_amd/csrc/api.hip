@@ -393,14 +393,15 @@ mmaemu_status mmaemu_emulate_mma_scaled(const mmaemu_model *model, const void *A
 
 // whether the multi-model kernel takes a model (then with its arithmetic kind there)
 static mmaemu_status many_class(const mmaemu_model_params &mp, const void *A, const void *B, uint32_t m, uint32_t n, uint32_t k,
-                                mmaemu_dtypes dt, ModelArgs &p, bool &fused, uint32_t &kind)
+                                mmaemu_dtypes dt, ModelArgs &p, bool &fused, uint32_t &kind, uint32_t &cls)
 {
     fused = false;
     kind = 0;
+    cls = 0;
     if (mp.family == MMAEMU_FAMILY_FDPA && is_ab_type(dt.a) && is_ab_type(dt.b)) {
         const mmaemu_status st = fdpa_model_args(mp, k, false, p);
         if (st != MMAEMU_OK) return st;
-        fused = scan_takes(p, dt.a, dt.b, m, n, k, A, B, kind);
+        fused = scan_takes(p, dt.a, dt.b, m, n, k, A, B, kind, cls);
     }
     return MMAEMU_OK;
 }
@@ -418,10 +419,10 @@ mmaemu_status mmaemu_compare_many_classes(const mmaemu_model *const *models, uin
         if (!models[i] || models[i]->magic != MODEL_MAGIC) { set_error("compare_many_classes: bad model handle at %u", i); return MMAEMU_ERR_INVALID_ARG; }
         ModelArgs p;
         bool fused;
-        uint32_t kind;
-        const mmaemu_status st = many_class(models[i]->params, nullptr, nullptr, m, n, k, dt, p, fused, kind);
+        uint32_t kind, cls;
+        const mmaemu_status st = many_class(models[i]->params, nullptr, nullptr, m, n, k, dt, p, fused, kind, cls);
         if (st != MMAEMU_OK) return st;
-        class_of_model[i] = fused ? 0 : -1;                     // one class: the kernel takes any mix of group lengths and widths
+        class_of_model[i] = fused ? (int32_t)cls : -1;          // (within a class the kernel takes any mix of group lengths and widths)
     }
     return MMAEMU_OK;
 }
@@ -454,7 +455,7 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     uint32_t *dout = static_cast<uint32_t *>(D_out);
 
     // which models the multi-model kernels take, and in which variant
-    struct Item { ModelArgs p; bool fused, done; uint32_t kind; };
+    struct Item { ModelArgs p; bool fused, done; uint32_t kind, cls; };
     Item items[MMAEMU_COMPARE_MANY_MAX];
     bool all_one = n_models <= (uint32_t)MULTI_MAX;
     for (uint32_t i = 0; i < n_models; ++i) {
@@ -462,11 +463,12 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
         it.fused = false;
         it.done = false;
         it.kind = 0;
-        const mmaemu_status cst = many_class(models[i]->params, A, B, m, n, k, dt, it.p, it.fused, it.kind);
+        it.cls = 0;
+        const mmaemu_status cst = many_class(models[i]->params, A, B, m, n, k, dt, it.p, it.fused, it.kind, it.cls);
         if (cst != MMAEMU_OK) return cst;
         // (within a launch the models that flush subnormal inputs come last; a leading reference model that flushes
         // can therefore share its launch with flushing models only)
-        all_one = all_one && it.fused && !(items[0].p.ftz_in && !it.p.ftz_in);
+        all_one = all_one && it.fused && it.cls == items[0].cls && !(items[0].p.ftz_in && !it.p.ftz_in);
     }
     bool any_unfused = false;
     for (uint32_t i = 0; i < n_models; ++i) any_unfused = any_unfused || !items[i].fused;
@@ -479,9 +481,10 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     // fused launch of `lead` (if not UINT32_MAX: it leads the launch and is the reference) and every model the kernel
     // takes that has not run yet; at most MULTI_MAX per launch, FlushSubnormal sets last so that the staged operands are
     // flushed once at most
-    auto run_class = [&](uint32_t lead, bool ref_is_first) -> mmaemu_status {
+    auto run_class = [&](uint32_t lead, bool ref_is_first, uint32_t cls) -> mmaemu_status {
         for (;;) {
             MultiLaunch ml = {};
+            ml.cls = cls;
             ml.ref_is_first = ref_is_first;
             ml.dref = ref;
             ml.dout = dout;
@@ -492,7 +495,7 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
             for (int pass = (ref_is_first && items[lead].p.ftz_in) ? 1 : 0; pass < 2; ++pass)
                 for (uint32_t i = 0; i < n_models && ml.count < (uint32_t)MULTI_MAX; ++i) {
                     Item &it = items[i];
-                    if (it.done || !it.fused || (int)(it.p.ftz_in != 0) != pass) continue;
+                    if (it.done || !it.fused || it.cls != cls || (int)(it.p.ftz_in != 0) != pass) continue;
                     ml.slot[ml.count] = i;
                     ml.models[ml.count] = it.p;
                     ml.kind[ml.count] = it.kind;
@@ -513,7 +516,7 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     if (!ref) {
         // the reference is model 0's output: it runs first
         if (items[0].fused) {
-            const mmaemu_status st = run_class(0, true);
+            const mmaemu_status st = run_class(0, true, items[0].cls);
             if (st != MMAEMU_OK) return st;
         } else {
             mmaemu_status st = emulate_impl(models[0], A, B, C, dout, nullptr, nullptr, 1, m, n, k, batch, dt, hip_stream);
@@ -527,7 +530,7 @@ mmaemu_status mmaemu_emulate_compare_many(const mmaemu_model *const *models, uin
     for (uint32_t i = 0; i < n_models; ++i) {
         if (items[i].done) continue;
         if (items[i].fused) {
-            const mmaemu_status st = run_class(UINT32_MAX, false);
+            const mmaemu_status st = run_class(UINT32_MAX, false, items[i].cls);
             if (st != MMAEMU_OK) return st;
         } else {
             uint32_t *Di = dout + (uint64_t)i * count;

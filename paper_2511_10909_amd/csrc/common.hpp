@@ -90,6 +90,7 @@ struct MultiLaunch {
     uint32_t slot[MULTI_MAX];          // place of each model in the caller's arrays (D_out, statistics)
     ModelArgs models[MULTI_MAX];
     uint32_t kind[MULTI_MAX];          // arithmetic kind of each model, as scan_takes names it
+    uint32_t cls;                      // the class all of them belong to, as scan_takes names it
     bool ref_is_first;                 // the first model's outputs are the reference (dref is not read)
     const uint32_t *dref;
     uint32_t *dout;                    // null, or the start of the caller's output array
@@ -98,8 +99,9 @@ struct MultiLaunch {
 };
 // scan_takes: whether that kernel takes a model on this problem, and the arithmetic kind the model needs there
 // (0: a group's aligned terms summed in 32 bits; 1: folded into binary64 every four terms; 2: every term; 3: F of 30
-// and more, terms truncated and summed in binary64)
-bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind);
+// and more, terms truncated and summed in binary64), and the class of models that can share its launch
+bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind,
+                uint32_t &cls);
 mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
                           uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,

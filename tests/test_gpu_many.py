@@ -21,7 +21,12 @@ SETS16 = [(16, 4, RNE, 0), (16, 8, RZ, 1), (16, 16, RNE, 1), (16, 64, RZ, 0), (2
 
 def _handles(mm, plist):
     return [mm.model_create(group_len=p.group_len, frac_bits=p.frac_bits, frac_bits2=p.frac_bits2, c_mode=p.c_mode, out_round=p.out_round,
-                            ftz_in=p.ftz_in, ftz_out=p.ftz_out, nan_bits=p.nan_bits, out_mant_bits=p.out_mant_bits) for p in plist]
+                            ftz_in=p.ftz_in, ftz_out=p.ftz_out, nan_bits=p.nan_bits, out_mant_bits=p.out_mant_bits, split=p.split,
+                            acc_special_truncation=p.acc_special_truncation, frac_bits_merge=p.frac_bits_merge,
+                            frac_bits_acc=p.frac_bits_acc, f2_at_leading_bit=p.f2_at_leading_bit,
+                            skip_zero_terms=p.skip_zero_terms, zero_result_positive=p.zero_result_positive,
+                            sum_drop_distance=p.sum_drop_distance, wide_products=p.wide_products, rd_toward_zero=p.rd_toward_zero)
+            for p in plist]
 
 
 def run_many(mm, plist, A, B, C, ta, tb, ref=None, dump=True, index_base=0, stats=None):
@@ -178,6 +183,82 @@ def test_special_values_and_wide_bf16_inside_the_fused_kernels(mm):
     st, D, _, _ = run_many(mm, plist, A, B, C, fm.BF16, fm.BF16, ref=C)
     for i, p in enumerate(plist):
         assert_same(D[i], o1_emulate(p, A, B, C, fm.BF16, fm.BF16), "rational oracle, set %d" % i)
+
+
+def rd_sets(rng, k, count):
+    """TR-FDPA sets (unsplit groups) with the variation switches drawn at random, group lengths the fused kernel takes."""
+    from test_gpu_tiled_rd import random_rd_params
+    out = []
+    while len(out) < count:
+        p = random_rd_params(rng, k).with_(group_len=int(rng.choice([L for L in (4, 8, 16, 32) if L <= k])))
+        if p.f2_at_leading_bit and rng.integers(0, 3) == 0:
+            p = p.with_(f2_at_leading_bit=False, rd_toward_zero=True)          # Sec. 6.2.4's truncating variant
+        out.append(p)
+    return out
+
+
+@pytest.mark.parametrize("ta,tb,m,k", [(fm.BF16, fm.BF16, 16, 16), (fm.FP16, fm.FP16, 32, 8), (fm.E4M3, fm.E5M2, 16, 32), (fm.FP16, fm.FP16, 16, 16),
+                                       (fm.BF16, fm.BF16, 32, 16), (fm.E5M2, fm.E5M2, 16, 16), (fm.BF16, fm.FP16, 16, 32)])
+def test_tr_fdpa_sets_in_the_fused_kernel(mm, ta, tb, m, k):
+    # Alg. "TR-FDPA" and its variations, sixteen sets per call: zero terms in or out of the maxima and input flushes make
+    # up to three launches; operands over the whole format (BF16: finite products of 2^128 and more, Sec. 4.2's rule),
+    # NaN and infinities sprinkled in, zeros among operands and accumulators
+    rng = np.random.default_rng(400 + 8 * ta + tb + k)
+    nb = 41
+    A, B, C = make_case(rng, ta, tb, nb, m, m, k, special_frac=0.004)
+    half = nb // 2
+    A[:half] = synth.narrow_exponent_bits(rng, (half, m, k), ta, *((110, 140) if ta == fm.BF16 else (1, 14)))
+    B[:half] = synth.narrow_exponent_bits(rng, (half, m, k), tb, *((110, 140) if tb == fm.BF16 else (1, 14)))
+    C[:half] = synth.narrow_exponent_bits(rng, (half, m, m), fm.FP32, 100, 150)
+    A = synth.sprinkle(rng, A, np.array([0, 1 << (A.dtype.itemsize * 8 - 1)], dtype=A.dtype), 0.1)
+    A[1, 0, :] = 0
+    C = np.where(rng.random(C.shape) < 0.1, np.uint32(0x80000000), C).astype(np.uint32)
+    plist = rd_sets(rng, k, 16)
+    want = oracle_outputs(plist, A, B, C, ta, tb)
+    ref = want[5].copy()
+    flat = ref.reshape(-1)
+    idx = rng.choice(flat.size, size=flat.size // 30, replace=False)
+    flat[idx] += rng.integers(1, 300, size=idx.size).astype(np.uint32)
+    hs = _handles(mm, plist)
+    cls = mm.compare_many_classes(hs, m, m, k, (ta, tb, fm.FP32, fm.FP32))
+    for h in hs:
+        mm.model_destroy(h)
+    assert min(cls) >= 1 and max(cls) <= 3, cls
+    got_stats, got_D, kern, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, index_base=1 << 34)
+    assert kern.startswith("multi") and kern.endswith(" rd"), kern
+    for i, p in enumerate(plist):
+        assert_same(got_D[i], want[i], "set %d %s" % (i, p))
+        assert got_stats[i] == ostats.compare(want[i], ref, index_base=1 << 34), (i, p)
+    # without the dump: the same statistics
+    st2, _, _, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, dump=False, index_base=1 << 34)
+    assert st2 == got_stats
+    # the rational form of the oracle on the first tile and on one of the wide-range tiles
+    for i in (0, 3, 9, 14):
+        for t in (0, nb - 1):
+            assert_same(got_D[i][t:t + 1, :4], o1_emulate(plist[i], A[t:t + 1, :4], B[t:t + 1], C[t:t + 1, :4], ta, tb), "rational oracle, set %d tile %d" % (i, t))
+
+
+def test_t_fdpa_and_tr_fdpa_sets_in_one_call(mm):
+    # a list that mixes both families and a set outside the fused kernels; the first model is the reference
+    rng = np.random.default_rng(55)
+    ta = tb = fm.FP16
+    A, B, C = make_case(rng, ta, tb, 29, 16, 16, 16, c_exp=(100, 140))
+    rd = ModelParams(group_len=8, frac_bits=24, frac_bits2=31, c_mode=C_AFTER_RD)
+    plist = [rd, ModelParams(group_len=8, frac_bits=24), rd.with_(out_round=RZ), rd.with_(skip_zero_terms=True, zero_result_positive=True),
+             ModelParams(group_len=16, frac_bits=27, out_round=RZ), rd.with_(group_len=2), rd.with_(frac_bits2=24, ftz_in=True)]
+    want = oracle_outputs(plist, A, B, C, ta, tb)
+    for ref in (None, want[4]):
+        st, D, _, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref)
+        base = want[0] if ref is None else ref
+        for i in range(len(plist)):
+            assert_same(D[i], want[i], "set %d" % i)
+            assert st[i] == ostats.compare(want[i], base), i
+    # TR-FDPA sets of one class alone need no output array, with the first as the reference too
+    same = [rd, rd.with_(out_round=RZ), rd.with_(frac_bits=20), rd.with_(group_len=4, frac_bits2=27)]
+    w = oracle_outputs(same, A, B, C, ta, tb)
+    st, _, kern, _ = run_many(mm, same, A, B, C, ta, tb, ref=None, dump=False)
+    assert kern == "multi x4 tiled 16x16 r2x2 kc=16 any L vm=0 rd", kern
+    assert st == [ostats.compare(x, w[0]) for x in w]
 
 
 def test_models_outside_the_fused_kernels_fall_back(mm):
