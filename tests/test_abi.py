@@ -117,3 +117,27 @@ def test_fma_family_argument_checks():
         mm.emulate_mma_scaled(h, ok, ok, ok, ok, ok, ok, 4, 16, 16, 4, 1, (mm.FP32,) * 4, stream=0)
     mm.emulate_mma(h, None, None, None, None, 16, 16, 4, 0, (mm.FP32,) * 4, stream=0)     # batch = 0: no-op
     mm.model_destroy(h)
+
+
+def test_compare_many_classes_is_a_host_side_query():
+    """Which models mmaemu_emulate_compare_many runs in common launches: decided on the host, no GPU needed."""
+    from paper_2511_10909_amd import binding as mm
+    rd = dict(group_len=8, frac_bits=24, frac_bits2=31, c_mode=mm.C_AFTER_RD)
+    sets = [dict(group_len=8, frac_bits=24), dict(group_len=16, frac_bits=32, out_round=mm.RZ, ftz_in=True),      # T-FDPA: class 0
+            rd, dict(rd, f2_at_leading_bit=True, sum_drop_distance=28, acc_special_truncation=True),               # TR-FDPA: class 1
+            dict(rd, skip_zero_terms=True), dict(rd, skip_zero_terms=True, ftz_in=True),                           # zero terms out of the maxima: 2, 3
+            dict(rd, split=mm.SPLIT_HALVES), dict(group_len=8, frac_bits=24, c_mode=mm.C_AFTER_EXACT),             # not in the scan kernel
+            dict(group_len=2, frac_bits=24), dict(group_len=8, frac_bits=44)]
+    hs = [mm.model_create(**kw) for kw in sets]
+    dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
+    assert mm.compare_many_classes(hs, 16, 16, 16, dt) == [0, 0, 1, 1, 2, 3, -1, -1, -1, -1]
+    assert mm.compare_many_classes(hs[:6], 32, 32, 16, dt) == [0, 0, 1, 1, 2, 3]
+    assert mm.compare_many_classes(hs[:6], 16, 16, 32, (mm.BF16, mm.BF16, mm.FP32, mm.FP32)) == [0, 0, 1, 1, 2, 3]
+    assert mm.compare_many_classes(hs[:3], 16, 16, 64, dt) == [-1, -1, -1]          # shapes the kernel does not stage whole
+    assert mm.compare_many_classes(hs[:3], 20, 20, 16, dt) == [-1, -1, -1]
+    assert mm.compare_many_classes(hs[:3], 16, 16, 16, (mm.TF32, mm.TF32, mm.FP32, mm.FP32)) == [-1, -1, -1]
+    wide = mm.model_create(**dict(rd, wide_products=True))
+    assert mm.compare_many_classes([wide], 16, 16, 16, (mm.BF16, mm.BF16, mm.FP32, mm.FP32)) == [-1]
+    assert mm.compare_many_classes([wide], 16, 16, 16, dt) == [1]
+    for h in hs + [wide]:
+        mm.model_destroy(h)
