@@ -37,7 +37,7 @@ struct ScanArgs {
     uint64_t *stats;                   // the caller's mmaemu_stats array as 64-bit words
     uint32_t zbias;                    // ZBIAS when zero terms stay out of the exponent maxima (TR-FDPA sets with that switch), else 0
     uint32_t slot[MULTI_MAX];
-    struct Hot { int32_t F; uint32_t flags, out_mask, nan_bits, L, kind; int32_t F2, Fc, drop; } hot[MULTI_MAX];
+    struct Hot { int32_t F; uint32_t flags, out_mask, nan_bits, L, kind; int32_t F2, Fc, drop, Fm; uint32_t parts; } hot[MULTI_MAX];
 };
 
 __device__ __forceinline__ ScanArgs::Hot scan_hot(uint32_t mi)
@@ -48,7 +48,7 @@ __device__ __forceinline__ ScanArgs::Hot scan_hot(uint32_t mi)
     ScanArgs::Hot h;
     h.F = sa->hot[mi].F; h.flags = sa->hot[mi].flags; h.out_mask = sa->hot[mi].out_mask; h.nan_bits = sa->hot[mi].nan_bits;
     h.L = sa->hot[mi].L; h.kind = sa->hot[mi].kind;
-    h.F2 = sa->hot[mi].F2; h.Fc = sa->hot[mi].Fc; h.drop = sa->hot[mi].drop;
+    h.F2 = sa->hot[mi].F2; h.Fc = sa->hot[mi].Fc; h.drop = sa->hot[mi].drop; h.Fm = sa->hot[mi].Fm; h.parts = sa->hot[mi].parts;
     return h;
 #else
     return ScanArgs::Hot{};
@@ -114,7 +114,8 @@ constexpr int scan_waves()
 }
 
 // FAM 0: T-FDPA, the accumulator a term of the sum; FAM 1: TR-FDPA (unsplit groups), the accumulator added after the
-// products' sum with the two round-downs.
+// products' sum with the two round-downs; FAM 2: GTR-FDPA's merge of sub-group sums with the sub-groups being the two
+// halves or the four quarters of a group (binary32 values only: FP8 / FP16 operands, a sub-group's sum in 32 bits).
 template <int TM, int KC, bool ADAPT, int FAM>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(scan_waves<TM, KC, ADAPT>(), scan_waves<TM, KC, ADAPT>())))
 emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm, uint64_t nitems, uint32_t nblocks)
@@ -184,7 +185,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             staged = ftz0 ? 1 : 0;
             float fa[NQ][4], fb[NQ][4];
             uint2 xa[NQ], xb[NQ];
-            const uint32_t zbias = FAM == 1 ? sa_.zbias : 0u;
+            const uint32_t zbias = FAM != 0 ? sa_.zbias : 0u;
             bool wild = decode_any<NQ>(ta, raw_a, ftz0, zbias, fa, xa);
             wild |= decode_any<NQ>(tb, raw_b, ftz0, zbias, fb, xb);
             if (ADAPT) chunk_is_double = __syncthreads_or(wild) != 0;         // (also protects the previous pass's readers)
@@ -224,6 +225,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             // zero" (every other binary32 operation of the loop is exact in either mode, and the binary64 route checks the
             // direction of its own conversion)
             if constexpr (FAM == 0) set_f32_round_toward_zero((fl & FL_RZ) != 0);
+            (void)kind;
             if ((fl & FL_FTZ_IN) && !staged) {
                 // FlushSubnormal on the staged values, in place (exponents do not change: a subnormal keeps Exp = 1 - bias)
                 __syncthreads();
@@ -479,10 +481,156 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                 else if (kind == 2) run_groups(gl_c, std::integral_constant<int, 2>{});
                 else run_groups(gl_c, std::integral_constant<int, 3>{});
             };
+            // Split groups (Algorithm "GTR-FDPA", steps 3 to 5, with consecutive sub-groups): every sub-group of SL terms is
+            // summed at its own maximum; the sums are rounded down to F_m bits at the largest maximum of the sub-groups
+            // that hold a product and added; then as TR-FDPA with F_m in the place of F.
+            auto run_split = [&](auto sl_c, auto ns_c) {
+                constexpr int SL = decltype(sl_c)::value, NS = decltype(ns_c)::value, GLT = SL * NS;
+                constexpr int US = (SL / 4 <= 2) ? 2 : 1;
+                if constexpr (GLT <= KC && !ADAPT) {
+#pragma unroll 1
+                for (int g = 0; g < KC / GLT; ++g) {
+                    const uint32_t kg = g * GLT;
+                    // the packed maximum of sub-group sg of the staged tile (SL terms), from the kept quarter maxima
+                    auto sub_max = [&](int sg, int r, int c) -> uint32_t {
+                        if constexpr (SL == 4) {
+                            return (m2k[sg / 2][r * C + c][tid] >> (16 * (sg & 1))) & 0xFFFFu;
+                        } else {
+                            uint32_t x = m2k[sg * (SL / 8)][r * C + c][tid];
+#pragma unroll
+                            for (int i = 1; i < SL / 8; ++i) x = pk_max_u16(x, m2k[sg * (SL / 8) + i][r * C + c][tid]);
+                            const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
+                            return lo > hi ? lo : hi;
+                        }
+                    };
+                    int em[R][C];
+                    uint32_t tg[R][C], have[R][C], tagged = 0;
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            tg[r][c] = 0;
+                            have[r][c] = 0;
+                            int best = 0, first = 0;
+#pragma unroll
+                            for (int q = 0; q < NS; ++q) {
+                                const uint32_t e = sub_max(g * NS + q, r, c);
+                                tg[r][c] |= e & 0xC000u;
+                                tagged |= e;
+                                const int eq = (int)e + ebase;
+                                if (q == 0) first = eq;
+                                if (!(fl & FL_SKIP_ZERO) || e >= 2 * ZBIAS) {
+                                    best = (!have[r][c] || eq > best) ? eq : best;
+                                    have[r][c] |= 1u << q;
+                                }
+                            }
+                            em[r][c] = have[r][c] ? best : first;
+                        }
+                    tagged &= 0xC000u;
+                    double Tm[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) Tm[r][c] = 0.0;
+                    // (one sub-group at a time, its maximum read again: four sets of maxima and sums in flight cost registers)
+#pragma unroll 1
+                    for (int q = 0; q < NS; ++q) {
+                        int32_t S32[R][C];
+                        int eq[R][C];
+                        float scale[R][C];
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                S32[r][c] = 0;
+                                eq[r][c] = (int)sub_max(g * NS + q, r, c) + ebase;
+                                int se = F + 127 - eq[r][c];                           // biased exponent of 2^(F - e_max)
+                                se = se < 1 ? 1 : (se > 254 ? 254 : se);               // the clamps never change a truncated term
+                                scale[r][c] = __uint_as_float((uint32_t)se << 23);
+                            }
+#pragma unroll US
+                        for (int t = 0; t < SL; t += 4) {
+                            float a[R][4], b[C][4];
+#pragma unroll
+                            for (int r = 0; r < R; ++r) {
+                                const float4 v = *reinterpret_cast<const float4 *>(av + TI * r * VS + kg + q * SL + t);
+                                a[r][0] = v.x; a[r][1] = v.y; a[r][2] = v.z; a[r][3] = v.w;
+                            }
+#pragma unroll
+                            for (int c = 0; c < C; ++c) {
+                                const float4 v = *reinterpret_cast<const float4 *>(bv + TJ * c * VS + kg + q * SL + t);
+                                b[c][0] = v.x; b[c][1] = v.y; b[c][2] = v.z; b[c][3] = v.w;
+                            }
+#pragma unroll
+                            for (int w = 0; w < 4; ++w)
+#pragma unroll
+                                for (int r = 0; r < R; ++r)
+#pragma unroll
+                                    for (int c = 0; c < C; ++c) S32[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale[r][c]);
+                        }
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c)
+                                if ((have[r][c] >> q) & 1u) Tm[r][c] += __builtin_floor(ldexp((double)S32[r][c], (eq[r][c] - F) - (em[r][c] - hot.Fm)));
+                    }
+                    slow_seen = true;
+                    uint32_t dn[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            if ((fl & FL_FTZ_IN) && (d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;             // FlushSubnormal on the accumulator
+                            const double v = scan_rd_value(Tm[r][c], have[r][c] != 0, em[r][c], hot.Fm, d[r][c], hot.F2, hot.Fc, hot.drop, fl);
+                            uint32_t o = __float_as_uint((float)v);
+                            if ((fl & FL_RZ)) {
+                                const double back = (double)__uint_as_float(o);
+                                if (__builtin_fabs(back) > __builtin_fabs(v)) o -= 1u;         // rounded away from zero: step back
+                                o &= out_mask;
+                            }
+                            if ((fl & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                            if ((fl & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
+                            dn[r][c] = o;
+                        }
+                    if (tagged) {
+                        // NaN and infinite operands (Sec. 4.2): classes and signs from the staged values of the whole group
+                        const uint2 sp = special_products<R, C, TI * VS, TJ * VS, TI * VSD, TJ * VSD, GLT>(av + kg, bv + kg, 2u);
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c)
+                                if (tg[r][c]) {
+                                    const uint32_t i = r * C + c, cb = d[r][c];
+                                    bool nn = (sp.x >> i) & 1u, pp = (sp.y >> i) & 1u, mm = (sp.y >> (16 + i)) & 1u;
+                                    if ((cb & 0x7FFFFFFFu) > 0x7F800000u) nn = true;                       // the accumulator joins
+                                    else if ((cb & 0x7FFFFFFFu) == 0x7F800000u) { if (cb >> 31) mm = true; else pp = true; }
+                                    if (nn || (pp && mm)) dn[r][c] = nan_bits;
+                                    else if (pp || mm) dn[r][c] = pp ? 0x7F800000u : 0xFF800000u;
+                                }
+                    }
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+                }
+                }
+            };
+            if constexpr (FAM == 2) {
+                const uint32_t parts = hot.parts, SLr = L / parts;              // sub-groups of a group, terms of a sub-group
+                if (parts == 2) {
+                    if (SLr == 4) run_split(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
+                    else if (SLr == 8) run_split(std::integral_constant<int, 8>{}, std::integral_constant<int, 2>{});
+                    else run_split(std::integral_constant<int, 16>{}, std::integral_constant<int, 2>{});
+                } else {
+                    if (SLr == 4) run_split(std::integral_constant<int, 4>{}, std::integral_constant<int, 4>{});
+                    else run_split(std::integral_constant<int, 8>{}, std::integral_constant<int, 4>{});
+                }
+            } else {
             if (L == 4) by_kind(std::integral_constant<int, 4>{});
             else if (L == 8) by_kind(std::integral_constant<int, 8>{});
             else if (L == 16) by_kind(std::integral_constant<int, 16>{});
             else by_kind(std::integral_constant<int, 32>{});                 // (no code where KC is below 32)
+            }
 
             // ---- this model's outputs against the reference ----
             // Per output that differs: one LDS atomic on its histogram bucket (bucket 0 of the LDS copy counts pairs that
@@ -591,14 +739,15 @@ static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const vo
     }
     hipLaunchKernelGGL((emulate_scan_kernel<TM, KC, ADAPT, FAM>), dim3(grid), dim3(256), 0, s, sa, A, B, C, batch, (uint32_t)blocks);
     MMAEMU_HIP(hipGetLastError());
-    set_last_kernel("multi x%u tiled %dx%d r2x2 kc=%d any L vm=%d%s", sa.count, TM, TM, KC, ADAPT ? 1 : 0, FAM == 1 ? " rd" : "");
+    set_last_kernel("multi x%u tiled %dx%d r2x2 kc=%d any L vm=%d%s", sa.count, TM, TM, KC, ADAPT ? 1 : 0, FAM == 1 ? " rd" : (FAM == 2 ? " rd split" : ""));
     return MMAEMU_OK;
 }
 
 // Whether the kernel takes a model, the model's arithmetic kind, and the class of models it can share a launch with:
 // 0, T-FDPA with the accumulator inside the sum; 1, TR-FDPA (unsplit groups, any of the variation switches); 2 and 3,
 // TR-FDPA sets that keep zero terms out of the exponent maxima (the staged exponents then differ), without and with
-// FlushSubnormal on the inputs (which decides what a zero is).  Whole 16x16x16, 16x16x32, 32x32x8 or 32x32x16 tiles of
+// FlushSubnormal on the inputs (which decides what a zero is); 4 to 6, the same three for groups split in halves or
+// quarters.  Whole 16x16x16, 16x16x32, 32x32x8 or 32x32x16 tiles of
 // FP8 / FP16 / BF16 / FP6 / FP4 operands, group length 4, 8, 16 or 32, F up to 40.
 bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind,
                 uint32_t &cls)
@@ -613,6 +762,11 @@ bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32
         // variant of the round-downs exists for the plain F2 rule)
         if ((p.wide_products && bf16) || (p.rd_toward_zero && p.f2_at_leading_bit)) return false;
         cls = p.skip_zero_terms ? (p.ftz_in ? 3u : 2u) : 1u;
+    } else if (p.c_mode == MMAEMU_C_AFTER_RD && (p.split == MMAEMU_SPLIT_HALVES || p.split == MMAEMU_SPLIT_QUARTERS)) {
+        // halves or quarters of at least four terms, each summed in 32 bits, from binary32 values
+        const uint32_t parts = p.split == MMAEMU_SPLIT_HALVES ? 2u : 4u;
+        if (bf16 || p.rd_toward_zero || p.F >= 30 || p.L < 4 * parts || ((uint64_t)(p.L / parts) << (p.F + 2)) > (1ull << 31)) return false;
+        cls = 4u + (p.skip_zero_terms ? (p.ftz_in ? 2u : 1u) : 0u);
     } else {
         return false;
     }
@@ -630,10 +784,17 @@ template <int FAM>
 static mmaemu_status launch_scan_shape(const ScanArgs &sa, const void *A, const void *B, const uint32_t *Cm, uint32_t m, uint32_t n, uint32_t k,
                                        uint64_t batch, bool adapt, hipStream_t s)
 {
+    if constexpr (FAM == 2) {                    // (binary32 values only)
+        if (m == 16 && n == 16 && k == 16) return launch_scan_cfg<16, 16, false, FAM>(sa, A, B, Cm, batch, s);
+        if (m == 32 && n == 32 && k == 8) return launch_scan_cfg<32, 8, false, FAM>(sa, A, B, Cm, batch, s);
+        if (m == 16 && n == 16 && k == 32) return launch_scan_cfg<16, 32, false, FAM>(sa, A, B, Cm, batch, s);
+        if (m == 32 && n == 32 && k == 16) return launch_scan_cfg<32, 16, false, FAM>(sa, A, B, Cm, batch, s);
+    } else {
     if (m == 16 && n == 16 && k == 16) return adapt ? launch_scan_cfg<16, 16, true, FAM>(sa, A, B, Cm, batch, s) : launch_scan_cfg<16, 16, false, FAM>(sa, A, B, Cm, batch, s);
     if (m == 32 && n == 32 && k == 8) return adapt ? launch_scan_cfg<32, 8, true, FAM>(sa, A, B, Cm, batch, s) : launch_scan_cfg<32, 8, false, FAM>(sa, A, B, Cm, batch, s);
     if (m == 16 && n == 16 && k == 32) return adapt ? launch_scan_cfg<16, 32, true, FAM>(sa, A, B, Cm, batch, s) : launch_scan_cfg<16, 32, false, FAM>(sa, A, B, Cm, batch, s);
     if (m == 32 && n == 32 && k == 16) return adapt ? launch_scan_cfg<32, 16, true, FAM>(sa, A, B, Cm, batch, s) : launch_scan_cfg<32, 16, false, FAM>(sa, A, B, Cm, batch, s);
+    }
     set_error("emulate_compare_many: no kernel for this shape");
     return MMAEMU_ERR_UNSUPPORTED;
 }
@@ -644,7 +805,7 @@ mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, c
     ScanArgs sa = {};
     sa.ta = ta;
     sa.tb = tb;
-    sa.zbias = ml.cls >= 2 ? ZBIAS : 0u;
+    sa.zbias = (ml.cls >= 1 && (ml.cls - 1) % 3 != 0) ? ZBIAS : 0u;
     sa.ebase = 2 - fmt_info(ta).bias - fmt_info(tb).bias - 2 * (int)sa.zbias;
     sa.count = ml.count;
     sa.ref_is_first = ml.ref_is_first ? 1u : 0u;
@@ -656,11 +817,14 @@ mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, c
     for (uint32_t i = 0; i < ml.count; ++i) {
         const ModelArgs &p = ml.models[i];
         sa.slot[i] = ml.slot[i];
-        sa.hot[i] = ScanArgs::Hot{p.F, p.flags, p.out_mask, p.nan_bits, p.L, ml.kind[i], p.F2, p.Fc, p.sum_drop_distance};
+        sa.hot[i] = ScanArgs::Hot{p.F, p.flags, p.out_mask, p.nan_bits, p.L, ml.kind[i], p.F2, p.Fc, p.sum_drop_distance, p.Fm,
+                                  p.split == MMAEMU_SPLIT_QUARTERS ? 4u : 2u};
     }
     const bool adapt = ta == MMAEMU_BF16 || tb == MMAEMU_BF16;
     const uint32_t *Cm = static_cast<const uint32_t *>(C);
-    return ml.cls == 0 ? launch_scan_shape<0>(sa, A, B, Cm, m, n, k, batch, adapt, s) : launch_scan_shape<1>(sa, A, B, Cm, m, n, k, batch, adapt, s);
+    if (ml.cls == 0) return launch_scan_shape<0>(sa, A, B, Cm, m, n, k, batch, adapt, s);
+    if (ml.cls <= 3) return launch_scan_shape<1>(sa, A, B, Cm, m, n, k, batch, adapt, s);
+    return launch_scan_shape<2>(sa, A, B, Cm, m, n, k, batch, false, s);
 }
 
 } // namespace mmaemu

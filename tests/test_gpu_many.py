@@ -238,6 +238,55 @@ def test_tr_fdpa_sets_in_the_fused_kernel(mm, ta, tb, m, k):
             assert_same(got_D[i][t:t + 1, :4], o1_emulate(plist[i], A[t:t + 1, :4], B[t:t + 1], C[t:t + 1, :4], ta, tb), "rational oracle, set %d tile %d" % (i, t))
 
 
+@pytest.mark.parametrize("ta,tb,m,k", [(fm.FP16, fm.FP16, 16, 16), (fm.E4M3, fm.E5M2, 16, 32), (fm.FP16, fm.FP16, 32, 8), (fm.E5M2, fm.E5M2, 32, 16),
+                                       (fm.E4M3, fm.E4M3, 16, 16), (fm.FP16, fm.E5M2, 16, 32)])
+def test_split_group_sets_in_the_fused_kernel(mm, ta, tb, m, k):
+    # groups split in halves or quarters (Alg. "GTR-FDPA", steps 3 to 5, on consecutive sub-groups) with the variation
+    # switches drawn at random; whole sub-groups of zero products, NaN and infinities, zero accumulators
+    from oracle.fdpa import SPLIT_HALVES, SPLIT_QUARTERS
+    from test_gpu_tiled_rd import random_rd_params
+    rng = np.random.default_rng(500 + 8 * ta + tb + k)
+    nb = 37
+    A, B, C = make_case(rng, ta, tb, nb, m, m, k, special_frac=0.004)
+    half = nb // 2
+    A[:half] = synth.narrow_exponent_bits(rng, (half, m, k), ta, 1, 14)
+    B[:half] = synth.narrow_exponent_bits(rng, (half, m, k), tb, 1, 14)
+    C[:half] = synth.narrow_exponent_bits(rng, (half, m, m), fm.FP32, 100, 150)
+    A = synth.sprinkle(rng, A, np.array([0, 1 << (A.dtype.itemsize * 8 - 1)], dtype=A.dtype), 0.15)
+    A[0, 1, : k // 2] = 0                       # one whole half without a live term
+    A[1, 3, : 3 * (k // 4)] = 0                 # three quarters of a row
+    A[2, 0, :] = 0
+    C = np.where(rng.random(C.shape) < 0.1, np.uint32(0x80000000), C).astype(np.uint32)
+    plist = []
+    while len(plist) < 16:
+        L = int(rng.choice([L for L in (8, 16, 32) if L <= k]))
+        split = int(rng.choice([SPLIT_HALVES] + ([SPLIT_QUARTERS] * 2 if L >= 16 else [])))
+        p = random_rd_params(rng, k).with_(group_len=L, split=split, frac_bits=int(rng.choice([5, 13, 20, 24])),
+                                           frac_bits_merge=int(rng.choice([0, 13, 24, 28])))
+        fc = p.frac_bits_acc or p.frac_bits
+        plist.append(p.with_(frac_bits2=min(p.frac_bits2, fc + 40)))
+    want = oracle_outputs(plist, A, B, C, ta, tb)
+    ref = want[2].copy()
+    flat = ref.reshape(-1)
+    idx = rng.choice(flat.size, size=flat.size // 30, replace=False)
+    flat[idx] += rng.integers(1, 300, size=idx.size).astype(np.uint32)
+    hs = _handles(mm, plist)
+    cls = mm.compare_many_classes(hs, m, m, k, (ta, tb, fm.FP32, fm.FP32))
+    for h in hs:
+        mm.model_destroy(h)
+    assert min(cls) >= 4 and max(cls) <= 6, cls
+    got_stats, got_D, kern, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, index_base=123)
+    assert kern.startswith("multi") and kern.endswith(" rd split"), kern
+    for i, p in enumerate(plist):
+        assert_same(got_D[i], want[i], "set %d %s" % (i, p))
+        assert got_stats[i] == ostats.compare(want[i], ref, index_base=123), (i, p)
+    st2, _, _, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, dump=False, index_base=123)
+    assert st2 == got_stats
+    for i in (0, 5, 11):
+        for t in (0, 1, nb - 1):
+            assert_same(got_D[i][t:t + 1, :4], o1_emulate(plist[i], A[t:t + 1, :4], B[t:t + 1], C[t:t + 1, :4], ta, tb), "rational oracle, set %d tile %d" % (i, t))
+
+
 def test_t_fdpa_and_tr_fdpa_sets_in_one_call(mm):
     # a list that mixes both families and a set outside the fused kernels; the first model is the reference
     rng = np.random.default_rng(55)
