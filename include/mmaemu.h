@@ -297,9 +297,10 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
  * decodes the operands once for up to 16 models (any mix of group lengths and widths) and keeps every output in
  * registers: D reaches memory only on request.  Two families of models run that way, each in launches of its own:
  * c_mode C_IN_GROUP without variation switches (Algorithm "T-FDPA"), and c_mode C_AFTER_RD (Algorithm "TR-FDPA") with
- * any of its variation switches, unsplit groups apart from groups split in halves or quarters (those on FP8 / FP16
- * operands with sub-groups of at least four terms; sets that keep zero terms out of the maxima launch apart from those
- * that do not, and then also by ftz_in; not: wide_products with BF16 operands, the even / odd split).  Any other model runs through
+ * any of its variation switches: unsplit groups, groups split in halves or quarters, and the even / odd split of
+ * Algorithm "GTR-FDPA" launch apart from each other (split groups on FP8 / FP16 operands only, halves and quarters of
+ * at least four terms; sets that keep zero terms out of the maxima launch apart from those that do not, and then also
+ * by ftz_in; not: wide_products with BF16 operands).  Any other model runs through
  * mmaemu_emulate_mma and mmaemu_compare and needs D_out, as does a reference taken from models[0] when the models do not
  * all fit one such launch.
  * At most MMAEMU_COMPARE_MANY_MAX models per call.  batch = 0 is a no-op.

@@ -98,26 +98,28 @@ __device__ __forceinline__ double scan_rd_value(double T, bool have_T, int em, i
 }
 
 // LDS of one workgroup: staged values and exponents, the kept quarter maxima, the statistics
-template <int TM, int KC, bool ADAPT>
+template <int TM, int KC, bool ADAPT, int FAM>
 constexpr int scan_lds_bytes()
 {
     constexpr int SLOTS = 256 / ((TM / 2) * (TM / 2));
     constexpr int VS = KC + 4, VSD = KC + 2, ES = KC / 2 + (KC == 8 ? 4 : 2);
-    return 2 * SLOTS * TM * (ADAPT ? VSD * 8 : VS * 4) + 2 * SLOTS * TM * ES * 4 + ((KC / 4 + 1) / 2) * 4 * 256 * 4 + (int)sizeof(MultiLds);
+    constexpr int KEPT = FAM == 3 ? KC / 4 : (KC / 4 + 1) / 2;            // dwords of kept maxima per output
+    return 2 * SLOTS * TM * (ADAPT ? VSD * 8 : VS * 4) + 2 * SLOTS * TM * ES * 4 + KEPT * 4 * 256 * 4 + (int)sizeof(MultiLds);
 }
 // workgroups (of four waves, one per SIMD) that a CU's 160 KB of LDS hold, four at most: the waves per SIMD to compile for
-template <int TM, int KC, bool ADAPT>
+template <int TM, int KC, bool ADAPT, int FAM>
 constexpr int scan_waves()
 {
-    constexpr int by_lds = (160 * 1024) / scan_lds_bytes<TM, KC, ADAPT>();
+    constexpr int by_lds = (160 * 1024) / scan_lds_bytes<TM, KC, ADAPT, FAM>();
     return by_lds >= 4 ? 4 : by_lds;
 }
 
 // FAM 0: T-FDPA, the accumulator a term of the sum; FAM 1: TR-FDPA (unsplit groups), the accumulator added after the
 // products' sum with the two round-downs; FAM 2: GTR-FDPA's merge of sub-group sums with the sub-groups being the two
-// halves or the four quarters of a group (binary32 values only: FP8 / FP16 operands, a sub-group's sum in 32 bits).
+// halves or the four quarters of a group (binary32 values only: FP8 / FP16 operands, a sub-group's sum in 32 bits); FAM 3:
+// GTR-FDPA as printed, the sub-groups being the even and the odd products.
 template <int TM, int KC, bool ADAPT, int FAM>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(scan_waves<TM, KC, ADAPT>(), scan_waves<TM, KC, ADAPT>())))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(scan_waves<TM, KC, ADAPT, FAM>(), scan_waves<TM, KC, ADAPT, FAM>())))
 emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm, uint64_t nitems, uint32_t nblocks)
 {
     constexpr int R = 2, C = 2, TN = TM;
@@ -129,7 +131,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
     constexpr int VBYTES = SLOTS * TM * (ADAPT ? VSD * 8 : VS * 4);
     constexpr int EBYTES = SLOTS * TM * ES * 4;
     __shared__ __attribute__((aligned(16))) unsigned char smem[2 * VBYTES + 2 * EBYTES];
-    __shared__ uint32_t m2k[NK2][R * C][256];
+    __shared__ uint32_t m2k[FAM == 3 ? NQ4 : NK2][R * C][256];            // (FAM 3: a quarter's even and odd maximum, one dword)
     __shared__ MultiLds ml;
     constexpr int HC = HIST_COPIES;
     const uint32_t tid = threadIdx.x;
@@ -210,7 +212,8 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                     const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
                     const uint32_t mx = lo > hi ? lo : hi;
                     // (each thread its own words: no barrier needed)
-                    if (q % 2 == 0) m2k[q / 2][r * C + c][tid] = mx;
+                    if constexpr (FAM == 3) m2k[q][r * C + c][tid] = x;           // low half: the even k, high half: the odd k
+                    else if (q % 2 == 0) m2k[q / 2][r * C + c][tid] = mx;
                     else m2k[q / 2][r * C + c][tid] |= mx << 16;
                 }
         }
@@ -253,7 +256,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             auto run_groups = [&](auto gl_c, auto kind_c) {
                 constexpr int GL = decltype(gl_c)::value, KIND = decltype(kind_c)::value;
                 constexpr int U2 = (GL / 4 <= 2) ? 2 : 1;             // (a whole group of 16 in flight costs a wave of occupancy)
-                if constexpr (GL <= KC) {
+                if constexpr (GL <= KC && FAM <= 1) {
                 const bool fits = KIND == 0 && ((uint64_t)(GL + 1) << (F + 2)) <= (1ull << 31) && F >= 1;
 #pragma unroll 1
                 for (int g = 0; g < KC / GL; ++g) {
@@ -487,7 +490,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             auto run_split = [&](auto sl_c, auto ns_c) {
                 constexpr int SL = decltype(sl_c)::value, NS = decltype(ns_c)::value, GLT = SL * NS;
                 constexpr int US = (SL / 4 <= 2) ? 2 : 1;
-                if constexpr (GLT <= KC && !ADAPT) {
+                if constexpr (GLT <= KC && !ADAPT && FAM == 2) {
 #pragma unroll 1
                 for (int g = 0; g < KC / GLT; ++g) {
                     const uint32_t kg = g * GLT;
@@ -615,7 +618,118 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                 }
                 }
             };
-            if constexpr (FAM == 2) {
+            // Algorithm "GTR-FDPA": the even and the odd products of a group are aligned at their own maxima (which pass 1's
+            // packed arithmetic keeps apart: even k in the low halves) and summed apart; then merged as above.
+            auto run_even_odd = [&](auto gl_c) {
+                constexpr int GL = decltype(gl_c)::value;
+                constexpr int UE = (GL / 4 <= 2) ? 2 : 1;
+                if constexpr (GL <= KC && !ADAPT && FAM == 3) {
+#pragma unroll 1
+                for (int g = 0; g < KC / GL; ++g) {
+                    const uint32_t kg = g * GL;
+                    int ee[R][C], eo[R][C];
+                    uint32_t tg[R][C], tagged = 0;
+                    bool he[R][C], ho[R][C];
+                    float scale_e[R][C], scale_o[R][C];
+                    int32_t Se[R][C], So[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            uint32_t x = m2k[g * (GL / 4)][r * C + c][tid];
+#pragma unroll
+                            for (int i = 1; i < GL / 4; ++i) x = pk_max_u16(x, m2k[g * (GL / 4) + i][r * C + c][tid]);
+                            const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
+                            tg[r][c] = x & SENTINEL_MASK;
+                            tagged |= x;
+                            ee[r][c] = (int)lo + ebase;
+                            eo[r][c] = (int)hi + ebase;
+                            he[r][c] = !(fl & FL_SKIP_ZERO) || lo >= 2 * ZBIAS;
+                            ho[r][c] = !(fl & FL_SKIP_ZERO) || hi >= 2 * ZBIAS;
+                            int se = F + 127 - ee[r][c], so = F + 127 - eo[r][c];
+                            se = se < 1 ? 1 : (se > 254 ? 254 : se);                  // the clamps never change a truncated term
+                            so = so < 1 ? 1 : (so > 254 ? 254 : so);
+                            scale_e[r][c] = __uint_as_float((uint32_t)se << 23);
+                            scale_o[r][c] = __uint_as_float((uint32_t)so << 23);
+                            Se[r][c] = 0;
+                            So[r][c] = 0;
+                        }
+                    tagged &= SENTINEL_MASK;
+#pragma unroll UE
+                    for (int t = 0; t < GL; t += 4) {
+                        float a[R][4], b[C][4];
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            const float4 v = *reinterpret_cast<const float4 *>(av + TI * r * VS + kg + t);
+                            a[r][0] = v.x; a[r][1] = v.y; a[r][2] = v.z; a[r][3] = v.w;
+                        }
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            const float4 v = *reinterpret_cast<const float4 *>(bv + TJ * c * VS + kg + t);
+                            b[c][0] = v.x; b[c][1] = v.y; b[c][2] = v.z; b[c][3] = v.w;
+                        }
+#pragma unroll
+                        for (int w = 0; w < 4; ++w)
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+#pragma unroll
+                                for (int c = 0; c < C; ++c) {
+                                    if (w & 1) So[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale_o[r][c]);
+                                    else Se[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale_e[r][c]);
+                                }
+                    }
+                    slow_seen = true;
+                    uint32_t dn[R][C];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) {
+                            const bool h0 = he[r][c], h1 = ho[r][c];
+                            const int em = (h0 && h1) ? (ee[r][c] > eo[r][c] ? ee[r][c] : eo[r][c]) : (h0 ? ee[r][c] : eo[r][c]);
+                            double T = 0.0;
+                            if (h0) T += __builtin_floor(ldexp((double)Se[r][c], (ee[r][c] - F) - (em - hot.Fm)));
+                            if (h1) T += __builtin_floor(ldexp((double)So[r][c], (eo[r][c] - F) - (em - hot.Fm)));
+                            if ((fl & FL_FTZ_IN) && (d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;             // FlushSubnormal on the accumulator
+                            const double v = scan_rd_value(T, h0 || h1, em, hot.Fm, d[r][c], hot.F2, hot.Fc, hot.drop, fl);
+                            uint32_t o = __float_as_uint((float)v);
+                            if ((fl & FL_RZ)) {
+                                const double back = (double)__uint_as_float(o);
+                                if (__builtin_fabs(back) > __builtin_fabs(v)) o -= 1u;         // rounded away from zero: step back
+                                o &= out_mask;
+                            }
+                            if ((fl & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                            if ((fl & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
+                            dn[r][c] = o;
+                        }
+                    if (tagged) {
+                        // NaN and infinite operands (Sec. 4.2): classes and signs from the staged values of the whole group
+                        const uint2 sp = special_products<R, C, TI * VS, TJ * VS, TI * VSD, TJ * VSD, GL>(av + kg, bv + kg, 2u);
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int c = 0; c < C; ++c)
+                                if (tg[r][c]) {
+                                    const uint32_t i = r * C + c, cb = d[r][c];
+                                    bool nn = (sp.x >> i) & 1u, pp = (sp.y >> i) & 1u, mm = (sp.y >> (16 + i)) & 1u;
+                                    if ((cb & 0x7FFFFFFFu) > 0x7F800000u) nn = true;                       // the accumulator joins
+                                    else if ((cb & 0x7FFFFFFFu) == 0x7F800000u) { if (cb >> 31) mm = true; else pp = true; }
+                                    if (nn || (pp && mm)) dn[r][c] = nan_bits;
+                                    else if (pp || mm) dn[r][c] = pp ? 0x7F800000u : 0xFF800000u;
+                                }
+                    }
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+                }
+                }
+            };
+            if constexpr (FAM == 3) {
+                if (L == 4) run_even_odd(std::integral_constant<int, 4>{});
+                else if (L == 8) run_even_odd(std::integral_constant<int, 8>{});
+                else if (L == 16) run_even_odd(std::integral_constant<int, 16>{});
+                else run_even_odd(std::integral_constant<int, 32>{});
+            } else if constexpr (FAM == 2) {
                 const uint32_t parts = hot.parts, SLr = L / parts;              // sub-groups of a group, terms of a sub-group
                 if (parts == 2) {
                     if (SLr == 4) run_split(std::integral_constant<int, 4>{}, std::integral_constant<int, 2>{});
@@ -739,7 +853,7 @@ static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const vo
     }
     hipLaunchKernelGGL((emulate_scan_kernel<TM, KC, ADAPT, FAM>), dim3(grid), dim3(256), 0, s, sa, A, B, C, batch, (uint32_t)blocks);
     MMAEMU_HIP(hipGetLastError());
-    set_last_kernel("multi x%u tiled %dx%d r2x2 kc=%d any L vm=%d%s", sa.count, TM, TM, KC, ADAPT ? 1 : 0, FAM == 1 ? " rd" : (FAM == 2 ? " rd split" : ""));
+    set_last_kernel("multi x%u tiled %dx%d r2x2 kc=%d any L vm=%d%s", sa.count, TM, TM, KC, ADAPT ? 1 : 0, FAM == 1 ? " rd" : (FAM == 2 ? " rd split" : (FAM == 3 ? " rd even/odd" : "")));
     return MMAEMU_OK;
 }
 
@@ -747,7 +861,7 @@ static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const vo
 // 0, T-FDPA with the accumulator inside the sum; 1, TR-FDPA (unsplit groups, any of the variation switches); 2 and 3,
 // TR-FDPA sets that keep zero terms out of the exponent maxima (the staged exponents then differ), without and with
 // FlushSubnormal on the inputs (which decides what a zero is); 4 to 6, the same three for groups split in halves or
-// quarters.  Whole 16x16x16, 16x16x32, 32x32x8 or 32x32x16 tiles of
+// quarters; 7 to 9, for the even / odd split.  Whole 16x16x16, 16x16x32, 32x32x8 or 32x32x16 tiles of
 // FP8 / FP16 / BF16 / FP6 / FP4 operands, group length 4, 8, 16 or 32, F up to 40.
 bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k, const void *A, const void *B, uint32_t &kind,
                 uint32_t &cls)
@@ -767,6 +881,10 @@ bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32
         const uint32_t parts = p.split == MMAEMU_SPLIT_HALVES ? 2u : 4u;
         if (bf16 || p.rd_toward_zero || p.F >= 30 || p.L < 4 * parts || ((uint64_t)(p.L / parts) << (p.F + 2)) > (1ull << 31)) return false;
         cls = 4u + (p.skip_zero_terms ? (p.ftz_in ? 2u : 1u) : 0u);
+    } else if (p.c_mode == MMAEMU_C_AFTER_RD && p.split == MMAEMU_SPLIT_EVEN_ODD) {
+        // the even and the odd products of a group (Algorithm "GTR-FDPA"), each summed in 32 bits, from binary32 values
+        if (bf16 || p.rd_toward_zero || p.F >= 30 || ((uint64_t)(p.L / 2) << (p.F + 2)) > (1ull << 31)) return false;
+        cls = 7u + (p.skip_zero_terms ? (p.ftz_in ? 2u : 1u) : 0u);
     } else {
         return false;
     }
@@ -784,7 +902,7 @@ template <int FAM>
 static mmaemu_status launch_scan_shape(const ScanArgs &sa, const void *A, const void *B, const uint32_t *Cm, uint32_t m, uint32_t n, uint32_t k,
                                        uint64_t batch, bool adapt, hipStream_t s)
 {
-    if constexpr (FAM == 2) {                    // (binary32 values only)
+    if constexpr (FAM >= 2) {                    // (binary32 values only)
         if (m == 16 && n == 16 && k == 16) return launch_scan_cfg<16, 16, false, FAM>(sa, A, B, Cm, batch, s);
         if (m == 32 && n == 32 && k == 8) return launch_scan_cfg<32, 8, false, FAM>(sa, A, B, Cm, batch, s);
         if (m == 16 && n == 16 && k == 32) return launch_scan_cfg<16, 32, false, FAM>(sa, A, B, Cm, batch, s);
@@ -824,7 +942,8 @@ mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, c
     const uint32_t *Cm = static_cast<const uint32_t *>(C);
     if (ml.cls == 0) return launch_scan_shape<0>(sa, A, B, Cm, m, n, k, batch, adapt, s);
     if (ml.cls <= 3) return launch_scan_shape<1>(sa, A, B, Cm, m, n, k, batch, adapt, s);
-    return launch_scan_shape<2>(sa, A, B, Cm, m, n, k, batch, false, s);
+    if (ml.cls <= 6) return launch_scan_shape<2>(sa, A, B, Cm, m, n, k, batch, false, s);
+    return launch_scan_shape<3>(sa, A, B, Cm, m, n, k, batch, false, s);
 }
 
 } // namespace mmaemu

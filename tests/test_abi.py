@@ -127,11 +127,11 @@ def test_compare_many_classes_is_a_host_side_query():
             rd, dict(rd, f2_at_leading_bit=True, sum_drop_distance=28, acc_special_truncation=True),               # TR-FDPA: class 1
             dict(rd, skip_zero_terms=True), dict(rd, skip_zero_terms=True, ftz_in=True),                           # zero terms out of the maxima: 2, 3
             dict(rd, split=mm.SPLIT_HALVES),                                                                       # halves / quarters: 4 to 6
-            dict(group_len=8, frac_bits=24, c_mode=mm.C_AFTER_EXACT), dict(rd, split=mm.SPLIT_EVEN_ODD),           # not in the scan kernel
+            dict(group_len=8, frac_bits=24, c_mode=mm.C_AFTER_EXACT), dict(rd, split=mm.SPLIT_EVEN_ODD),           # not in the scan kernel; even / odd: 7 to 9
             dict(group_len=2, frac_bits=24), dict(group_len=8, frac_bits=44)]
     hs = [mm.model_create(**kw) for kw in sets]
     dt = (mm.FP16, mm.FP16, mm.FP32, mm.FP32)
-    assert mm.compare_many_classes(hs, 16, 16, 16, dt) == [0, 0, 1, 1, 2, 3, 4, -1, -1, -1, -1]
+    assert mm.compare_many_classes(hs, 16, 16, 16, dt) == [0, 0, 1, 1, 2, 3, 4, -1, 7, -1, -1]
     assert mm.compare_many_classes(hs[:6], 32, 32, 16, dt) == [0, 0, 1, 1, 2, 3]
     assert mm.compare_many_classes(hs[:6], 16, 16, 32, (mm.BF16, mm.BF16, mm.FP32, mm.FP32)) == [0, 0, 1, 1, 2, 3]
     assert mm.compare_many_classes(hs[:3], 16, 16, 64, dt) == [-1, -1, -1]          # shapes the kernel does not stage whole
