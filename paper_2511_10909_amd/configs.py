@@ -549,6 +549,46 @@ def validate_against_mfma(instr, model_kwargs, n_tiles=4096, seeds=(0,), dev="cu
     return out
 
 
+def scan_against_mfma(instr, candidates, n_tiles=1 << 16, seeds=(0,), families=None, dev="cuda"):
+    """Sec. 3.1 Step 4 for a list of candidate models at once: every input family (or the named ones) is generated,
+    run through the native instruction `instr` and through all `candidates` (keyword dicts for model_create) in one
+    mmaemu_emulate_compare_many call per family and seed, each candidate compared bit for bit with the instruction.
+    Returns {"mismatches": [[per family] per candidate], "families": names, "total": [per candidate], "seconds",
+    "terms", "classes": the launch class of each candidate (-1: one emulation and one comparison launch of its own)}.
+    A candidate with total 0 reproduces the instruction on every input tried."""
+    info = mm.mfma_info(instr)
+    m, n, k, ta, tb = info["m"], info["n"], info["k"], info["a"], info["b"]
+    dt = (ta, tb, mm.FP32, mm.FP32)
+    A, B = _buf((n_tiles, m, k), ta, dev), _buf((n_tiles, n, k), tb, dev)
+    C, Dhw = _buf((n_tiles, m, n), mm.FP32, dev), _buf((n_tiles, m, n), mm.FP32, dev)
+    hs = [mm.model_create(**kw) for kw in candidates]
+    try:
+        classes = mm.compare_many_classes(hs, m, n, k, dt)
+        # (only models outside the scan kernel need their outputs in memory; the call wants one array for all then)
+        Dall = _buf((len(hs), n_tiles, m, n), mm.FP32, dev) if min(classes) < 0 else None
+        fams = [f for f in validation_families(ta, tb) if families is None or f[0] in families]
+        stats = {name: _stats_array(len(hs), dev) for name, _, _, _ in fams}
+
+        def run():
+            for name, ga, gb, gc in fams:
+                for seed in seeds:
+                    mm.generate(A, ta, m * k, 0, n_tiles, seed=seed, operand=0, **ga)
+                    mm.generate(B, tb, n * k, 0, n_tiles, seed=seed, operand=1, **gb)
+                    mm.generate(C, mm.FP32, m * n, 0, n_tiles, seed=seed, operand=2, **gc)
+                    mm.mfma_probe(instr, A, B, C, Dhw, k, n_tiles)
+                    mm.emulate_compare_many(hs, A, B, C, Dhw, Dall, m, n, k, n_tiles, dt, stats[name])
+
+        _, secs = _timed(run)
+        per = {name: mm.read_stats_array(st, len(hs)) for name, st in stats.items()}
+    finally:
+        for h in hs:
+            mm.model_destroy(h)
+    names = [f[0] for f in fams]
+    mism = [[per[name][i]["n_mismatch_bits"] for name in names] for i in range(len(candidates))]
+    return dict(mismatches=mism, families=names, total=[sum(row) for row in mism], seconds=secs, classes=classes,
+                terms=len(candidates) * len(fams) * len(seeds) * n_tiles * m * n * k)
+
+
 def _report(argv=None):
     """`python -m paper_2511_10909_amd.configs`: the five workloads end to end, one table row each."""
     import argparse
