@@ -484,6 +484,50 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                 else if (kind == 2) run_groups(gl_c, std::integral_constant<int, 2>{});
                 else run_groups(gl_c, std::integral_constant<int, 3>{});
             };
+            // End of a split group: T, the merged sum of the sub-groups in units of 2^(em - F_m) (hv: some product took
+            // part); then as TR-FDPA with F_m in the place of F, rho, and Sec. 4.2's special values from the staged values
+            // of the whole group of GLT terms at kg.
+            auto finish_merged = [&](auto glt_c, uint32_t kg, const double (&T)[R][C], const bool (&hv)[R][C], const int (&em)[R][C],
+                                     const uint32_t (&tg)[R][C], uint32_t tagged) {
+                constexpr int GLT = decltype(glt_c)::value;
+                slow_seen = true;
+                uint32_t dn[R][C];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) {
+                        if ((fl & FL_FTZ_IN) && (d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;                 // FlushSubnormal on the accumulator
+                        const double v = scan_rd_value(T[r][c], hv[r][c], em[r][c], hot.Fm, d[r][c], hot.F2, hot.Fc, hot.drop, fl);
+                        uint32_t o = __float_as_uint((float)v);
+                        if ((fl & FL_RZ)) {
+                            const double back = (double)__uint_as_float(o);
+                            if (__builtin_fabs(back) > __builtin_fabs(v)) o -= 1u;             // rounded away from zero: step back
+                            o &= out_mask;
+                        }
+                        if ((fl & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                        if ((fl & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
+                        dn[r][c] = o;
+                    }
+                if (tagged) {
+                    const uint2 sp = special_products<R, C, TI * VS, TJ * VS, TI * VSD, TJ * VSD, GLT>(av + kg, bv + kg, 2u);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int c = 0; c < C; ++c)
+                            if (tg[r][c]) {
+                                const uint32_t i = r * C + c, cb = d[r][c];
+                                bool nn = (sp.x >> i) & 1u, pp = (sp.y >> i) & 1u, mm = (sp.y >> (16 + i)) & 1u;
+                                if ((cb & 0x7FFFFFFFu) > 0x7F800000u) nn = true;                           // the accumulator joins
+                                else if ((cb & 0x7FFFFFFFu) == 0x7F800000u) { if (cb >> 31) mm = true; else pp = true; }
+                                if (nn || (pp && mm)) dn[r][c] = nan_bits;
+                                else if (pp || mm) dn[r][c] = pp ? 0x7F800000u : 0xFF800000u;
+                            }
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+            };
             // Split groups (Algorithm "GTR-FDPA", steps 3 to 5, with consecutive sub-groups): every sub-group of SL terms is
             // summed at its own maximum; the sums are rounded down to F_m bits at the largest maximum of the sub-groups
             // that hold a product and added; then as TR-FDPA with F_m in the place of F.
@@ -577,44 +621,12 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                             for (int c = 0; c < C; ++c)
                                 if ((have[r][c] >> q) & 1u) Tm[r][c] += __builtin_floor(ldexp((double)S32[r][c], (eq[r][c] - F) - (em[r][c] - hot.Fm)));
                     }
-                    slow_seen = true;
-                    uint32_t dn[R][C];
+                    bool hv[R][C];
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int c = 0; c < C; ++c) {
-                            if ((fl & FL_FTZ_IN) && (d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;             // FlushSubnormal on the accumulator
-                            const double v = scan_rd_value(Tm[r][c], have[r][c] != 0, em[r][c], hot.Fm, d[r][c], hot.F2, hot.Fc, hot.drop, fl);
-                            uint32_t o = __float_as_uint((float)v);
-                            if ((fl & FL_RZ)) {
-                                const double back = (double)__uint_as_float(o);
-                                if (__builtin_fabs(back) > __builtin_fabs(v)) o -= 1u;         // rounded away from zero: step back
-                                o &= out_mask;
-                            }
-                            if ((fl & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
-                            if ((fl & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
-                            dn[r][c] = o;
-                        }
-                    if (tagged) {
-                        // NaN and infinite operands (Sec. 4.2): classes and signs from the staged values of the whole group
-                        const uint2 sp = special_products<R, C, TI * VS, TJ * VS, TI * VSD, TJ * VSD, GLT>(av + kg, bv + kg, 2u);
-#pragma unroll
-                        for (int r = 0; r < R; ++r)
-#pragma unroll
-                            for (int c = 0; c < C; ++c)
-                                if (tg[r][c]) {
-                                    const uint32_t i = r * C + c, cb = d[r][c];
-                                    bool nn = (sp.x >> i) & 1u, pp = (sp.y >> i) & 1u, mm = (sp.y >> (16 + i)) & 1u;
-                                    if ((cb & 0x7FFFFFFFu) > 0x7F800000u) nn = true;                       // the accumulator joins
-                                    else if ((cb & 0x7FFFFFFFu) == 0x7F800000u) { if (cb >> 31) mm = true; else pp = true; }
-                                    if (nn || (pp && mm)) dn[r][c] = nan_bits;
-                                    else if (pp || mm) dn[r][c] = pp ? 0x7F800000u : 0xFF800000u;
-                                }
-                    }
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+                        for (int c = 0; c < C; ++c) hv[r][c] = have[r][c] != 0;
+                    finish_merged(std::integral_constant<int, GLT>{}, kg, Tm, hv, em, tg, tagged);
                 }
                 }
             };
@@ -678,49 +690,21 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                                     else Se[r][c] += (int32_t)((a[r][w] * b[c][w]) * scale_e[r][c]);
                                 }
                     }
-                    slow_seen = true;
-                    uint32_t dn[R][C];
+                    double T[R][C];
+                    int em[R][C];
+                    bool hv[R][C];
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
                         for (int c = 0; c < C; ++c) {
                             const bool h0 = he[r][c], h1 = ho[r][c];
-                            const int em = (h0 && h1) ? (ee[r][c] > eo[r][c] ? ee[r][c] : eo[r][c]) : (h0 ? ee[r][c] : eo[r][c]);
-                            double T = 0.0;
-                            if (h0) T += __builtin_floor(ldexp((double)Se[r][c], (ee[r][c] - F) - (em - hot.Fm)));
-                            if (h1) T += __builtin_floor(ldexp((double)So[r][c], (eo[r][c] - F) - (em - hot.Fm)));
-                            if ((fl & FL_FTZ_IN) && (d[r][c] & 0x7F800000u) == 0) d[r][c] = 0;             // FlushSubnormal on the accumulator
-                            const double v = scan_rd_value(T, h0 || h1, em, hot.Fm, d[r][c], hot.F2, hot.Fc, hot.drop, fl);
-                            uint32_t o = __float_as_uint((float)v);
-                            if ((fl & FL_RZ)) {
-                                const double back = (double)__uint_as_float(o);
-                                if (__builtin_fabs(back) > __builtin_fabs(v)) o -= 1u;         // rounded away from zero: step back
-                                o &= out_mask;
-                            }
-                            if ((fl & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
-                            if ((fl & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
-                            dn[r][c] = o;
+                            em[r][c] = (h0 && h1) ? (ee[r][c] > eo[r][c] ? ee[r][c] : eo[r][c]) : (h0 ? ee[r][c] : eo[r][c]);
+                            T[r][c] = 0.0;
+                            if (h0) T[r][c] += __builtin_floor(ldexp((double)Se[r][c], (ee[r][c] - F) - (em[r][c] - hot.Fm)));
+                            if (h1) T[r][c] += __builtin_floor(ldexp((double)So[r][c], (eo[r][c] - F) - (em[r][c] - hot.Fm)));
+                            hv[r][c] = h0 || h1;
                         }
-                    if (tagged) {
-                        // NaN and infinite operands (Sec. 4.2): classes and signs from the staged values of the whole group
-                        const uint2 sp = special_products<R, C, TI * VS, TJ * VS, TI * VSD, TJ * VSD, GL>(av + kg, bv + kg, 2u);
-#pragma unroll
-                        for (int r = 0; r < R; ++r)
-#pragma unroll
-                            for (int c = 0; c < C; ++c)
-                                if (tg[r][c]) {
-                                    const uint32_t i = r * C + c, cb = d[r][c];
-                                    bool nn = (sp.x >> i) & 1u, pp = (sp.y >> i) & 1u, mm = (sp.y >> (16 + i)) & 1u;
-                                    if ((cb & 0x7FFFFFFFu) > 0x7F800000u) nn = true;                       // the accumulator joins
-                                    else if ((cb & 0x7FFFFFFFu) == 0x7F800000u) { if (cb >> 31) mm = true; else pp = true; }
-                                    if (nn || (pp && mm)) dn[r][c] = nan_bits;
-                                    else if (pp || mm) dn[r][c] = pp ? 0x7F800000u : 0xFF800000u;
-                                }
-                    }
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+                    finish_merged(gl_c, kg, T, hv, em, tg, tagged);
                 }
                 }
             };
