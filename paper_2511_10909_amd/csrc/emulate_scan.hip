@@ -1,11 +1,14 @@
 // The closed-loop scan in one launch (Sec. 3.1 Step 4: many candidate parameter sets over the same random tiles, each
-// compared bit by bit with a reference, Eq. 2): up to MULTI_MAX T-FDPA models of *any* group length, internal width and
-// fold period share the staged operands of a pass.
+// compared bit by bit with a reference, Eq. 2): up to MULTI_MAX models of one family and of *any* group length, internal
+// width and fold period share the staged operands of a pass.  Families (one kernel instantiation each): T-FDPA with the
+// accumulator inside the sum; TR-FDPA (the accumulator added after the products' sum, with the two round-downs and the
+// variation switches); TR-FDPA on groups split in halves or quarters; GTR-FDPA (the even / odd split).  What follows
+// describes the first; the others differ in what a group's maximum covers and in the group epilogue.
 //
 // Staging and decoding A and B, loading C and the reference and forming the exponent maxima cost about as much as
 // running one model, so that part is paid once per pass for all the models of a launch:
-//   * a workgroup pass stages four 16x16x16 tiles (one 32x32x8 tile) as the single-model kernels of emulate_tiled.hpp do
-//     (same LDS layout and helpers);
+//   * a workgroup pass stages four 16x16x16 or 16x16x32 tiles (one 32x32x8 or 32x32x16 tile), the whole k at once, as the
+//     single-model kernels of emulate_tiled.hpp do (same LDS layout and helpers);
 //   * pass 1 runs once at the finest granularity, a quarter group of four products: the packed 16-bit maximum of each
 //     quarter is kept in LDS, two quarters per dword and thread;
 //   * the model loop reads per model six scalars from the kernel-argument segment (F, switches, output mask, NaN
