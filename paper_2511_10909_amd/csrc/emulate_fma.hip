@@ -8,7 +8,8 @@
 // returns: whenever a step's result is a NaN the model's own rule replaces it (Sec. 4.2: one pattern nan_bits, or the
 // payload rule of the nan_propagate variation).
 //
-// HBM-bound on instruction-shaped tiles: a 16x16x4 tile reads 1.5 KiB and writes 1 KiB for 1024 terms.  Mid-sized
+// HBM-bound on instruction-shaped tiles: a 16x16x4 tile reads 1.5 KiB and writes 1 KiB for 1024 terms (those keep several
+// blocks in flight per thread).  Mid-sized
 // problems are walked in 16x16 blocks of D so that a wavefront shares 4 rows of A and 16 rows of B in the caches; large
 // ones (m, n multiples of 64, k of 16 and at least 64) take the LDS-tiled kernel below.
 #include "common.hpp"
@@ -84,6 +85,47 @@ emulate_fma_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ 
             for (uint32_t kk = 0; kk < k; ++kk) d = fma_step<PROPAGATE>(a[kk], b[kk], d, nan_bits);
         }
         D[o] = d;
+    }
+}
+
+// Instruction-shaped tiles (k of 2 or 4, a row one 8- or 16-byte load): the same walk in 16x16 blocks with U blocks in
+// flight per thread, their loads issued together.  The kernel is bound by memory latency, not by arithmetic: one block at a
+// time left it at 0.45 of the HBM peak.
+template <bool PROPAGATE, int VEC, int U>
+__global__ void __launch_bounds__(256)
+emulate_fma_short_kernel(const uint32_t *__restrict__ A, const uint32_t *__restrict__ B, const uint32_t *C, uint32_t *D, uint32_t m,
+                         uint32_t n, uint64_t nblocks, uint32_t nan_bits)
+{
+    typedef typename std::conditional<VEC == 4, uint4, uint2>::type Row;          // (k = VEC)
+    const uint64_t mn = (uint64_t)m * n;
+    const uint32_t bpr = n / 16u;
+    const uint64_t bpt = (uint64_t)(m / 16u) * bpr;
+    for (uint64_t w0 = (uint64_t)blockIdx.x * U; w0 < nblocks; w0 += (uint64_t)gridDim.x * U) {
+        uint64_t o[U];
+        Row x[U], y[U];
+        uint32_t d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint64_t w = w0 + u;
+            w = w < nblocks ? w : nblocks - 1;                                    // (surplus slots repeat the last block and store nothing)
+            const uint64_t t = w / bpt;
+            const uint32_t r = (uint32_t)(w - t * bpt);
+            const uint32_t i = 16u * (r / bpr) + threadIdx.x / 16u, j = 16u * (r % bpr) + threadIdx.x % 16u;
+            o[u] = t * mn + (uint64_t)i * n + j;
+            x[u] = *reinterpret_cast<const Row *>(A + (t * m + i) * (uint64_t)VEC);
+            y[u] = *reinterpret_cast<const Row *>(B + (t * n + j) * (uint64_t)VEC);
+            d[u] = C[o[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            d[u] = fma_step<PROPAGATE>(x[u].x, y[u].x, d[u], nan_bits);
+            d[u] = fma_step<PROPAGATE>(x[u].y, y[u].y, d[u], nan_bits);
+            if constexpr (VEC == 4) {
+                d[u] = fma_step<PROPAGATE>(x[u].z, y[u].z, d[u], nan_bits);
+                d[u] = fma_step<PROPAGATE>(x[u].w, y[u].w, d[u], nan_bits);
+            }
+            if (w0 + u < nblocks) D[o[u]] = d[u];
+        }
     }
 }
 
@@ -235,6 +277,21 @@ static mmaemu_status launch_p(const void *A, const void *B, const void *C, void 
         }
     }
     const int vec = (k % 4 == 0 && (addr & 15) == 0) ? 4 : ((k % 2 == 0 && (addr & 7) == 0) ? 2 : 1);
+    if (blocked && (int)k == vec && vec >= 2) {
+        // (D may alias C here too: a thread reads exactly the elements of C it later writes)
+        constexpr int U = 4;
+        const uint64_t nblocks = batch * (m / 16) * (n / 16), groups = (nblocks + U - 1) / U;
+        const uint32_t grid = (uint32_t)(groups < 16384 ? groups : 16384);
+        if (vec == 4)
+            hipLaunchKernelGGL((emulate_fma_short_kernel<PROPAGATE, 4, U>), dim3(grid), dim3(256), 0, s, (const uint32_t *)A, (const uint32_t *)B,
+                               (const uint32_t *)C, (uint32_t *)D, m, n, nblocks, nan_bits);
+        else
+            hipLaunchKernelGGL((emulate_fma_short_kernel<PROPAGATE, 2, U>), dim3(grid), dim3(256), 0, s, (const uint32_t *)A, (const uint32_t *)B,
+                               (const uint32_t *)C, (uint32_t *)D, m, n, nblocks, nan_bits);
+        MMAEMU_HIP(hipGetLastError());
+        set_last_kernel("fma chain%s, 16x16 blocks, %d-bit loads, %d blocks in flight", PROPAGATE ? ", payloads" : "", vec * 32, U);
+        return MMAEMU_OK;
+    }
     if (blocked) {
         if (vec == 4) return launch_v<PROPAGATE, true, 4>(A, B, C, D, m, n, k, batch, nan_bits, s);
         if (vec == 2) return launch_v<PROPAGATE, true, 2>(A, B, C, D, m, n, k, batch, nan_bits, s);

@@ -43,8 +43,8 @@ def zero_case(rng, nb, m, n, k):
 
 
 SHAPES = [  # (tiles, m, n, k, offset_words, expected kernel variant)
-    (6, 16, 16, 4, 0, "fma chain, 16x16 blocks, 128-bit loads"),
-    (2, 32, 32, 2, 0, "fma chain, 16x16 blocks, 64-bit loads"),
+    (6, 16, 16, 4, 0, "fma chain, 16x16 blocks, 128-bit loads, 4 blocks in flight"),
+    (2, 32, 32, 2, 0, "fma chain, 16x16 blocks, 64-bit loads, 4 blocks in flight"),
     (3, 32, 32, 1, 0, "fma chain, 16x16 blocks"),
     (40, 4, 4, 1, 0, "fma chain"),
     (3, 5, 7, 3, 0, "fma chain"),
@@ -76,9 +76,9 @@ def test_fma_family_kernel_names(mm):
     rng = np.random.default_rng(1)
     A, B, C = fp32_case(rng, 1, 16, 16, 4, 1)
     gpu_fma(mm, A, B, C, nan_propagate=True)
-    assert gpu_fma.last_kernel == "fma chain, payloads, 16x16 blocks, 128-bit loads"
+    assert gpu_fma.last_kernel == "fma chain, payloads, 16x16 blocks, 128-bit loads, 4 blocks in flight"
     gpu_fma(mm, A, B, C)
-    assert gpu_fma.last_kernel == "fma chain, 16x16 blocks, 128-bit loads"
+    assert gpu_fma.last_kernel == "fma chain, 16x16 blocks, 128-bit loads, 4 blocks in flight"
 
 
 def test_fma_family_differs_from_the_fdpa_chain_only_in_the_sign_of_zero(mm):
