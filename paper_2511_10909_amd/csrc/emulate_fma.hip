@@ -371,6 +371,43 @@ emulate_fma64_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict_
     }
 }
 
+// k = 4 in 16x16 blocks (the shape of the binary64 instruction): U blocks in flight per thread, their loads issued together
+template <bool PROPAGATE, int U>
+__global__ void __launch_bounds__(256)
+emulate_fma64_short_kernel(const uint64_t *__restrict__ A, const uint64_t *__restrict__ B, const uint64_t *C, uint64_t *D, uint32_t m,
+                           uint32_t n, uint64_t nblocks, uint64_t nan64)
+{
+    const uint64_t mn = (uint64_t)m * n;
+    const uint32_t bpr = n / 16u;
+    const uint64_t bpt = (uint64_t)(m / 16u) * bpr;
+    for (uint64_t w0 = (uint64_t)blockIdx.x * U; w0 < nblocks; w0 += (uint64_t)gridDim.x * U) {
+        uint64_t o[U], d[U];
+        ulonglong2 x0[U], x1[U], y0[U], y1[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            uint64_t w = w0 + u;
+            w = w < nblocks ? w : nblocks - 1;                                    // (surplus slots repeat the last block and store nothing)
+            const uint64_t t = w / bpt;
+            const uint32_t r = (uint32_t)(w - t * bpt);
+            const uint32_t i = 16u * (r / bpr) + threadIdx.x / 16u, j = 16u * (r % bpr) + threadIdx.x % 16u;
+            o[u] = t * mn + (uint64_t)i * n + j;
+            const ulonglong2 *a = reinterpret_cast<const ulonglong2 *>(A + (t * m + i) * 4ull);
+            const ulonglong2 *b = reinterpret_cast<const ulonglong2 *>(B + (t * n + j) * 4ull);
+            x0[u] = a[0]; x1[u] = a[1];
+            y0[u] = b[0]; y1[u] = b[1];
+            d[u] = C[o[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            d[u] = fma_step64<PROPAGATE>(x0[u].x, y0[u].x, d[u], nan64);
+            d[u] = fma_step64<PROPAGATE>(x0[u].y, y0[u].y, d[u], nan64);
+            d[u] = fma_step64<PROPAGATE>(x1[u].x, y1[u].x, d[u], nan64);
+            d[u] = fma_step64<PROPAGATE>(x1[u].y, y1[u].y, d[u], nan64);
+            if (w0 + u < nblocks) D[o[u]] = d[u];
+        }
+    }
+}
+
 template <bool PROPAGATE, bool BLOCKED, bool VEC2>
 static mmaemu_status launch64_v(const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
                                 uint64_t batch, uint64_t nan64, hipStream_t s)
@@ -391,6 +428,20 @@ mmaemu_status launch_emulate_fma64(const void *A, const void *B, const void *C, 
     const uint64_t nan64 = ((uint64_t)(nan_bits >> 31) << 63) | 0x7FF0000000000000ull | ((uint64_t)(nan_bits & 0x7FFFFFu) << 29);
     const bool blocked = m % 16 == 0 && n % 16 == 0;
     const bool vec2 = k % 2 == 0 && ((reinterpret_cast<uintptr_t>(A) | reinterpret_cast<uintptr_t>(B)) & 15) == 0;
+    if (blocked && vec2 && k == 4) {
+        constexpr int U = 4;
+        const uint64_t nblocks = batch * (m / 16) * (n / 16), groups = (nblocks + U - 1) / U;
+        const uint32_t grid = (uint32_t)(groups < 16384 ? groups : 16384);
+        if (nan_propagate)
+            hipLaunchKernelGGL((emulate_fma64_short_kernel<true, U>), dim3(grid), dim3(256), 0, s, (const uint64_t *)A, (const uint64_t *)B,
+                               (const uint64_t *)C, (uint64_t *)D, m, n, nblocks, nan64);
+        else
+            hipLaunchKernelGGL((emulate_fma64_short_kernel<false, U>), dim3(grid), dim3(256), 0, s, (const uint64_t *)A, (const uint64_t *)B,
+                               (const uint64_t *)C, (uint64_t *)D, m, n, nblocks, nan64);
+        MMAEMU_HIP(hipGetLastError());
+        set_last_kernel("fma chain fp64%s, 16x16 blocks, 128-bit loads, %d blocks in flight", nan_propagate ? ", payloads" : "", U);
+        return MMAEMU_OK;
+    }
 #define GO(P, BL, V) return launch64_v<P, BL, V>(A, B, C, D, m, n, k, batch, nan64, s)
     if (nan_propagate) {
         if (blocked) { if (vec2) GO(true, true, true); GO(true, true, false); }

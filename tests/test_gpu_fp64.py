@@ -53,7 +53,8 @@ def fp64_case(rng, nb, m, n, k, trial):
 
 
 SHAPES = [  # (tiles, m, n, k, offset_words, kernel)
-    (3, 16, 16, 4, 0, "fma chain fp64, 16x16 blocks, 128-bit loads"),
+    (3, 16, 16, 4, 0, "fma chain fp64, 16x16 blocks, 128-bit loads, 4 blocks in flight"),
+    (1, 32, 16, 6, 0, "fma chain fp64, 16x16 blocks, 128-bit loads"),
     (20, 4, 4, 4, 0, "fma chain fp64, 128-bit loads"),
     (2, 16, 32, 3, 0, "fma chain fp64, 16x16 blocks"),
     (3, 5, 7, 3, 0, "fma chain fp64"),
