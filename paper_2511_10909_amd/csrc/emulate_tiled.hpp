@@ -1368,8 +1368,17 @@ tiled_body(const TiledArgs &ta_, const void *__restrict__ A, const void *__restr
     }
 }
 
+// (On 32 x 32 x 8 tiles with groups of 4 or 8 the kernels of every accumulation mode but the first need 132 to 134 vector
+// registers for binary32 values, a few over the budget of four waves per SIMD: those are compiled for four waves outright,
+// +4 to 10 %.  The BF16 kernels, at 137 to 140, lose by it.)
+template <int TM, int R, int C, int KC, int LT, int CMODE, int VM>
+constexpr int tiled_min_waves()
+{
+    return (TM == 32 && R == 4 && C == 2 && KC == 8 && LT != 0 && CMODE != MMAEMU_C_IN_GROUP && VM == 0) ? 4 : 1;
+}
+
 template <int TM, int TN, int R, int C, int KC, int LT, int CMODE, int NF, int VM_>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(tiled_min_waves<TM, R, C, KC, LT, CMODE, VM_>())))
 emulate_tiled_kernel(TiledArgs ta_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm,
                      uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nitems, uint32_t bm_count,
                      uint32_t bn_count, uint32_t xcd_remap)
