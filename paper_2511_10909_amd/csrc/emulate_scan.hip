@@ -158,6 +158,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
     const uint32_t *ae = Ae + (slot * TM + ti) * ES;
     const uint32_t *be = Be + (slot * TN + tj) * ES;
     const uint32_t count = sa_.count, ref_first = sa_.ref_is_first;
+    const bool dumping = sa_.dout != nullptr;
     const uint32_t *dref = sa->dref;
 
     constexpr int NQ = (SLOTS * TM * (KC / 4) + 255) / 256;
@@ -741,8 +742,9 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             uint32_t maxd = 0;
             uint32_t first_off = 0xFFFFFFFFu;
             if (live) {
-                uint32_t *dout = sa->dout;
-                const uint64_t dump_off = (uint64_t)sa->slot[mi] * sa->out_stride;
+                uint32_t *dout = nullptr;
+                uint64_t dump_off = 0;
+                if (dumping) { dout = sa->dout; dump_off = (uint64_t)sa->slot[mi] * sa->out_stride; }       // (uniform)
 #pragma unroll
                 for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -750,7 +752,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                         uint32_t x = d[r][c];
                         if (slow_seen && (x & 0x7FFFFFFFu) > 0x7F800000u) x = nan_bits;          // (the short route produces no NaN)
                         const uint64_t o = d_off + (uint64_t)(TI * r) * TN + TJ * c;
-                        if (dout) dout[dump_off + o] = x;
+                        if (dumping) dout[dump_off + o] = x;
                         if (ref_first && mi == 0) ref[r][c] = x;
                         const uint32_t y = ref[r][c];
                         if (x != y) {
@@ -764,10 +766,11 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                                 if (nx && ny) atomicAdd(&ml.naneq[mi], 1u);                      // (rare)
                             } else {
                                 // distance of the ordered keys (sign-magnitude patterns read as signed integers): below 2^32
-                                const int32_t kx = (x >> 31) ? -(int32_t)ax : (int32_t)ax, ky = (y >> 31) ? -(int32_t)ay : (int32_t)ay;
+                                const int32_t sx = (int32_t)x >> 31, sy = (int32_t)y >> 31;                    // 0 or -1
+                                const int32_t kx = ((int32_t)ax ^ sx) - sx, ky = ((int32_t)ay ^ sy) - sy;       // -|x| for a negative x
                                 const uint32_t dist = kx >= ky ? (uint32_t)kx - (uint32_t)ky : (uint32_t)ky - (uint32_t)kx;
                                 maxd = dist > maxd ? dist : maxd;
-                                bucket = dist ? 32u - (uint32_t)__builtin_clz(dist) : 0u;
+                                bucket = 32u - (uint32_t)__clz((int)dist);                                      // (__clz(0) = 32)
                             }
                             atomicAdd(&ml.hist[mi][bucket][tid & (HC - 1)], 1u);
                         }
