@@ -269,20 +269,22 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                     int emax[R][C];
                     uint32_t tagged = 0, tg[R][C];
                     bool have[R][C];                          // (FAM 1) a product took part
+                    auto group_max = [&](int r, int c) -> uint32_t {
+                        if constexpr (GL == 4) {
+                            return (m2k[g / 2][r * C + c][tid] >> (16 * (g & 1))) & 0xFFFFu;
+                        } else {
+                            uint32_t x = m2k[g * (GL / 8)][r * C + c][tid];
+#pragma unroll
+                            for (int i = 1; i < GL / 8; ++i) x = pk_max_u16(x, m2k[g * (GL / 8) + i][r * C + c][tid]);
+                            const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
+                            return lo > hi ? lo : hi;
+                        }
+                    };
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
                         for (int c = 0; c < C; ++c) {
-                            uint32_t e;
-                            if constexpr (GL == 4) {
-                                e = (m2k[g / 2][r * C + c][tid] >> (16 * (g & 1))) & 0xFFFFu;
-                            } else {
-                                uint32_t x = m2k[g * (GL / 8)][r * C + c][tid];
-#pragma unroll
-                                for (int i = 1; i < GL / 8; ++i) x = pk_max_u16(x, m2k[g * (GL / 8) + i][r * C + c][tid]);
-                                const uint32_t lo = x & 0xFFFFu, hi = x >> 16;
-                                e = lo > hi ? lo : hi;
-                            }
+                            uint32_t e = group_max(r, c);
                             const int em = (int)e + ebase;
                             have[r][c] = true;
                             if constexpr (FAM == 1) {
@@ -318,6 +320,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
 #pragma unroll
                             for (int c = 0; c < C; ++c) { Sd[r][c] += (double)S32[r][c]; S32[r][c] = 0; }
                     };
+                    float fscale[R][C];                           // 2^(F - e_max) in binary32, where pass 2 runs in binary32
                     if ((ADAPT && chunk_is_double) || KIND == 3) {
                         // binary64: exact product, exact scaling; the float -> int conversion truncates, or (KIND 3: F of 30
                         // and more) v_trunc_f64 and a binary64 sum, exact below 2^53
@@ -356,7 +359,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                         }
                     } else {
                         // binary32 values: the product is exact, the scaling aligns it, the conversion truncates toward zero
-                        float scale[R][C];
+                        float (&scale)[R][C] = fscale;
 #pragma unroll
                         for (int r = 0; r < R; ++r)
 #pragma unroll
@@ -411,7 +414,9 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                                 for (int r = 0; r < R; ++r)
 #pragma unroll
                                     for (int c = 0; c < C; ++c) {
-                                        const float scale = __uint_as_float((uint32_t)(F + 127 - emax[r][c]) << 23);     // 2^(F - e_max), a normal number
+                                        // 2^(F - e_max), a normal number on this route (so pass 2's clamps left it alone)
+                                        // (the BF16 kernels form it again: kept across their binary64 branch it costs registers)
+                                        const float scale = ADAPT ? __uint_as_float((uint32_t)(F + 127 - emax[r][c]) << 23) : fscale[r][c];
                                         const int32_t S = S32[r][c] + (int32_t)(__uint_as_float(d[r][c]) * scale);
                                         const float f = (float)S;                                  // (truncates under RZ)
                                         uint32_t o = __float_as_uint(ldexpf(f, emax[r][c] - F));
