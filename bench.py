@@ -280,6 +280,18 @@ def main():
             fn()                                  # (first call of a workload: kernel loading and allocator warm-up)
             r = fn()
             other[name] = dict(terms=r["terms"], ms=r["seconds"] * 1e3, terms_per_s=r["terms"] / r["seconds"])
+        # beside the five: Step 4 on sixteen TR-FDPA candidates at once (the fitted gfx950 set with other widths and group
+        # lengths) against the native 16x16x16 instructions, three input families of 2^16 tiles each
+        from paper_2511_10909_amd import presets
+        for name, instr in (("tr_fdpa_candidates_fp16", mm.MFMA_F32_16X16X16_F16), ("tr_fdpa_candidates_bf16", mm.MFMA_F32_16X16X16_BF16)):
+            fitted = presets.GFX950_MFMA[instr]
+            cands = [dict(fitted, frac_bits=F, frac_bits2=F2, group_len=L) for F in (20, 24) for F2 in (27, 31) for L in (4, 8, 16, 8)][:16]
+            cands[15] = dict(fitted)
+            fams = ("normal", "finite_bits", "random_bits")
+            configs.scan_against_mfma(instr, cands, n_tiles=1 << 12, families=fams)
+            r = configs.scan_against_mfma(instr, cands, n_tiles=1 << 16, families=fams)
+            other[name] = dict(terms=r["terms"], ms=r["seconds"] * 1e3, terms_per_s=r["terms"] / r["seconds"],
+                               candidates_without_mismatch=sum(1 for t in r["total"] if t == 0))
         out["config"]["other_workloads_end_to_end"] = other
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_seconds)
