@@ -26,12 +26,12 @@ ALGO_OPS_PER_TERM = 8                       # accounting floor of INT32 VALU ins
 # vector-ALU lane-instructions per MAC term (SQ_INSTS_VALU x 64 / terms) and HBM bytes per launch (FETCH_SIZE + WRITE_SIZE,
 # scaled by a copy kernel of known size).  Keyed by the kernel's name: a kernel that has changed since reports null.
 COUNTERS = {
-    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=0": {"valu_instr_per_term": 11.09, "traffic": 206792276},
-    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=1": {"valu_instr_per_term": 11.70, "traffic": 337147111},
-    "multi x3 tiled 32x32 r2x2 kc=8 any L vm=0": {"valu_instr_per_term": 11.83, "traffic": 336450010},
+    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=0": {"valu_instr_per_term": 10.77, "traffic": 184950664, "chunk": 1 << 16},
+    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=1": {"valu_instr_per_term": 11.50, "traffic": 336611449, "chunk": 1 << 16},
+    "multi x3 tiled 32x32 r2x2 kc=8 any L vm=0": {"valu_instr_per_term": 11.40, "traffic": 1342744835, "chunk": 1 << 18},
 }
 COUNTERS_SOURCE = ("profiles/closed_loop_scan_trace_and_counters.md, profiles/subnormal_stress_trace_and_counters.md (rocprofv3 --pmc SQ_INSTS_VALU; "
-                   "FETCH_SIZE, WRITE_SIZE scaled by a 64 MiB copy); traffic per launch of 2^16 tiles")
+                   "FETCH_SIZE, WRITE_SIZE scaled by a 64 MiB copy); traffic per launch")
 
 
 def parse():
@@ -43,7 +43,7 @@ def parse():
                     help="scan: the closed-loop scan (the headline); subnormal: the subnormal stress workload (2^26 fp16 32x32x8 "
                          "tiles, three flush variants) as the step, for its own profile")
     ap.add_argument("--tiles", type=int, default=0, help="tiles per operand type (default: the workload as stated, 2^24 / 2^26)")
-    ap.add_argument("--chunk", type=int, default=0, help="tiles generated and evaluated at a time (default 2^16)")
+    ap.add_argument("--chunk", type=int, default=0, help="tiles generated and evaluated at a time (default 2^16; 2^18 for the subnormal workload)")
     ap.add_argument("--unfused", action="store_true", help="one emulation launch and one comparison launch per parameter set")
     ap.add_argument("--time-every", type=int, default=16, help="HIP events around the emulation launches of every n-th chunk")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -86,7 +86,7 @@ def cpu_baseline(target_seconds):
 def subnormal_stress(args, torch, mm, configs, fused):
     """The subnormal stress workload as the step (not the headline: it has fewer terms than the scan)."""
     n_tiles = args.tiles or (1 << 26)
-    chunk = min(args.chunk or (1 << 16), n_tiles)
+    chunk = min(args.chunk or (1 << 18), n_tiles)
     timed = []
 
     def timer(name, terms, fn):
@@ -104,7 +104,8 @@ def subnormal_stress(args, torch, mm, configs, fused):
         secs += r["seconds"]
     ms = sum(e0.elapsed_time(e1) for _, _, e0, e1 in timed)
     terms = sum(t for _, t, _, _ in timed)
-    ctr = COUNTERS.get(r["kernel"], {}) if chunk == (1 << 16) else {}       # (the counters were taken on launches of 2^16 tiles)
+    ctr = COUNTERS.get(r["kernel"], {})
+    ctr = ctr if chunk == ctr.get("chunk") else {}                           # (the counters were taken on launches of that many tiles)
     frac = ALGO_OPS_PER_TERM * terms / (ms * 1e-3) / INT32_VALU_PEAK
     return {
         "metric": "bit-exact emulated MAC terms/sec on 1 MI355X", "value": r["terms"] * args.steps / secs, "unit": "terms/s", "n_gpus": 1,
@@ -224,7 +225,8 @@ def main():
     tot_ms = sum(v["avg_ms"] * v["launches_timed"] for v in kernels.values())
     tot_terms = sum(v["terms_per_launch"] * v["launches_timed"] for v in kernels.values())
     achieved = ALGO_OPS_PER_TERM * dom["terms_per_launch"] / (dom["avg_ms"] * 1e-3)
-    ctr = COUNTERS.get(dom["kernel"], {}) if chunk == (1 << 16) else {}     # (the counters were taken on launches of 2^16 tiles)
+    ctr = COUNTERS.get(dom["kernel"], {})
+    ctr = ctr if chunk == ctr.get("chunk") else {}                           # (the counters were taken on launches of that many tiles)
     stats = {scan.kind: scan.read() for scan in scans}
     agreement = {kind: [1.0 - s["n_mismatch_bits"] / max(s["n_compared"], 1) for s in st] for kind, st in stats.items()}
     out = {

@@ -184,7 +184,7 @@ class _Sampler:
         self.kept.append(rec)
 
 
-def config4(n_tiles=1 << 26, chunk=1 << 16, seed=0, dev="cuda", keep_first_chunk=False, fused=True, sample_tiles=None,
+def config4(n_tiles=1 << 26, chunk=1 << 18, seed=0, dev="cuda", keep_first_chunk=False, fused=True, sample_tiles=None,
             first_tile=0, timer=None, time_every=64):
     """Tiles first_tile .. first_tile + n_tiles - 1 of the stream.  `timer`, if given, is called as timer(name, terms, fn)
     around the emulation launches of every `time_every`-th chunk (it must run fn).  `fused`: the three variants share one pass over each chunk (mmaemu_emulate_compare_many, the no-flush variant's
