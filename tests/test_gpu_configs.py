@@ -32,10 +32,11 @@ def host(t, np_dtype):
     return to_host(t, np_dtype)
 
 
-def test_config1_full(cfg, mm):
+@pytest.mark.parametrize("fused", [True, False])
+def test_config1_full(cfg, mm, fused):
     nt = 10000
-    r = cfg.config1(n_tiles=nt, seed=0)
-    assert r["kernel"].startswith("tiled 16x16")
+    r = cfg.config1(n_tiles=nt, seed=0, fused=fused)
+    assert r["kernel"].startswith("multi x2 tiled 16x16" if fused else "tiled 16x16"), r["kernel"]
     A = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=0), fm.FP16, 256, 0, nt)
     B = ogen.generate(ogen.GenParams(family=ogen.GEN_FINITE_BITS, seed=0, operand=1), fm.FP16, 256, 0, nt)
     C = ogen.generate(ogen.GenParams(family=ogen.GEN_NORMAL, seed=0, operand=2), fm.FP32, 256, 0, nt)
