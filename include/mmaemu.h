@@ -295,7 +295,8 @@ mmaemu_status mmaemu_compare(const void *D0, const void *D1, uint64_t count, uin
  * Models of the FDPA family with frac_bits <= 40 and group length 4, 8, 16 or 32, on 16 x 16 x 16, 16 x 16 x 32,
  * 32 x 32 x 8 or 32 x 32 x 16 tiles with 8-byte aligned A and B of 8- or 16-bit types, run in a kernel that stages and
  * decodes the operands once for up to 16 models (any mix of group lengths and widths) and keeps every output in
- * registers: D reaches memory only on request.  Two families of models run that way, each in launches of its own:
+ * registers: D reaches memory only on request (on tiles of one group, models that differ only in the output conversion
+ * also share the group's sum).  Two families of models run that way, each in launches of its own:
  * c_mode C_IN_GROUP without variation switches (Algorithm "T-FDPA"), and c_mode C_AFTER_RD (Algorithm "TR-FDPA") with
  * any of its variation switches: unsplit groups, groups split in halves or quarters, and the even / odd split of
  * Algorithm "GTR-FDPA" launch apart from each other (split groups on FP8 / FP16 operands only, halves and quarters of

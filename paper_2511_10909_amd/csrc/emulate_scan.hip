@@ -40,7 +40,7 @@ struct ScanArgs {
     uint64_t *stats;                   // the caller's mmaemu_stats array as 64-bit words
     uint32_t zbias;                    // ZBIAS when zero terms stay out of the exponent maxima (TR-FDPA sets with that switch), else 0
     uint32_t slot[MULTI_MAX];
-    struct Hot { int32_t F; uint32_t flags, out_mask, nan_bits, L, kind; int32_t F2, Fc, drop, Fm; uint32_t parts; } hot[MULTI_MAX];
+    struct Hot { int32_t F; uint32_t flags, out_mask, nan_bits, L, kind; int32_t F2, Fc, drop, Fm; uint32_t parts, twin; } hot[MULTI_MAX];
 };
 
 __device__ __forceinline__ ScanArgs::Hot scan_hot(uint32_t mi)
@@ -51,7 +51,7 @@ __device__ __forceinline__ ScanArgs::Hot scan_hot(uint32_t mi)
     ScanArgs::Hot h;
     h.F = sa->hot[mi].F; h.flags = sa->hot[mi].flags; h.out_mask = sa->hot[mi].out_mask; h.nan_bits = sa->hot[mi].nan_bits;
     h.L = sa->hot[mi].L; h.kind = sa->hot[mi].kind;
-    h.F2 = sa->hot[mi].F2; h.Fc = sa->hot[mi].Fc; h.drop = sa->hot[mi].drop; h.Fm = sa->hot[mi].Fm; h.parts = sa->hot[mi].parts;
+    h.F2 = sa->hot[mi].F2; h.Fc = sa->hot[mi].Fc; h.drop = sa->hot[mi].drop; h.Fm = sa->hot[mi].Fm; h.parts = sa->hot[mi].parts; h.twin = sa->hot[mi].twin;
     return h;
 #else
     return ScanArgs::Hot{};
@@ -121,7 +121,10 @@ constexpr int scan_waves()
 // products' sum with the two round-downs; FAM 2: GTR-FDPA's merge of sub-group sums with the sub-groups being the two
 // halves or the four quarters of a group (binary32 values only: FP8 / FP16 operands, a sub-group's sum in 32 bits); FAM 3:
 // GTR-FDPA as printed, the sub-groups being the even and the odd products.
-template <int TM, int KC, bool ADAPT, int FAM>
+// TWIN (FAM 0, tiles of one group): a model marked `twin` is followed by one that differs from it only in the output
+// conversion (rounding, E8M13, output flush, NaN pattern); the two share the group's maximum and sum, and only the end of
+// the group and the statistics run twice.
+template <int TM, int KC, bool ADAPT, int FAM, bool TWIN>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(scan_waves<TM, KC, ADAPT, FAM>(), scan_waves<TM, KC, ADAPT, FAM>())))
 emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *Cm, uint64_t nitems, uint32_t nblocks)
 {
@@ -227,7 +230,12 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
         for (uint32_t mi = 0; mi < count; ++mi) {
             const ScanArgs::Hot hot = scan_hot(mi);
             const int F = hot.F;
-            const uint32_t fl = hot.flags, out_mask = hot.out_mask, nan_bits = hot.nan_bits, L = hot.L, kind = hot.kind;
+            const uint32_t fl = hot.flags, L = hot.L, kind = hot.kind;
+            typename std::conditional<TWIN, uint32_t, const uint32_t>::type out_mask = hot.out_mask, nan_bits = hot.nan_bits;
+            typename std::conditional<TWIN, uint32_t, const uint32_t>::type fe = fl;   // the switches the end of a group reads (a twin brings its own)
+            const bool twin = TWIN && hot.twin != 0;
+            uint32_t dfirst[TWIN ? R : 1][TWIN ? C : 1];      // the first model's outputs of a pair of twins
+            const uint32_t nan_first = hot.nan_bits;
             // rho = RZ-FP32: the short route's int -> float conversion truncates under the binary32 rounding mode "toward
             // zero" (every other binary32 operation of the loop is exact in either mode, and the binary64 route checks the
             // direction of its own conversion)
@@ -398,6 +406,34 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                     // accumulator is aligned like a product, the whole sum is a 32-bit integer, and rho is the int -> float
                     // conversion followed by an exact scaling -- as long as the result cannot be subnormal and nothing is
                     // tagged: e_max - F >= -126 and e_max <= 127 for every output of the wavefront.
+                    uint32_t dkeep[TWIN ? R : 1][TWIN ? C : 1];
+                    if constexpr (TWIN) {
+                        if (twin) {
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+#pragma unroll
+                                for (int c = 0; c < C; ++c) dkeep[r][c] = d[r][c];
+                        }
+                    }
+                    constexpr int TWINS = TWIN ? 2 : 1;
+#pragma unroll 1
+                    for (int tw = 0; tw < TWINS && (tw == 0 || twin); ++tw) {
+                    if constexpr (TWIN) {
+                        if (tw == 1) {
+                            // the twin: the first model's outputs aside, the accumulator back, the twin's output conversion
+                            const ScanArgs::Hot h2 = scan_hot(mi + 1);
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+#pragma unroll
+                                for (int c = 0; c < C; ++c) { dfirst[r][c] = d[r][c]; d[r][c] = dkeep[r][c]; }
+                            if constexpr (TWIN) {
+                                fe = h2.flags;
+                                out_mask = h2.out_mask;
+                                nan_bits = h2.nan_bits;
+                            }
+                            set_f32_round_toward_zero((fe & FL_RZ) != 0);
+                        }
+                    }
                     bool done = false;
                     if constexpr (KIND == 0 && FAM == 0) {
                         if (fits) {
@@ -420,7 +456,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                                         const int32_t S = S32[r][c] + (int32_t)(__uint_as_float(d[r][c]) * scale);
                                         const float f = (float)S;                                  // (truncates under RZ)
                                         uint32_t o = __float_as_uint(ldexpf(f, emax[r][c] - F));
-                                        if ((fl & FL_RZ)) {
+                                        if ((fe & FL_RZ)) {
                                             if ((o & 0x7FFFFFFFu) == 0x7F800000u) o -= 1u;         // overflow: the largest finite number
                                             o &= out_mask;
                                         }
@@ -449,12 +485,12 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                                     v = scan_rd_value(T, have[r][c], emax[r][c], F, d[r][c], hot.F2, hot.Fc, hot.drop, fl);
                                 }
                                 uint32_t o = __float_as_uint((float)v);
-                                if ((fl & FL_RZ)) {
+                                if ((fe & FL_RZ)) {
                                     const double back = (double)__uint_as_float(o);
                                     if (__builtin_fabs(back) > __builtin_fabs(v)) o -= 1u;     // rounded away from zero: step back
                                     o &= out_mask;                                             // RZ-E8M13 cuts further, still toward zero
                                 }
-                                if ((fl & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
+                                if ((fe & FL_FTZ_OUT) && (o & 0x7F800000u) == 0) o &= 0x80000000u;
                                 if (FAM == 1 && (fl & FL_ZERO_POSITIVE) && (o & 0x7FFFFFFFu) == 0) o = 0u;
                                 dn[r][c] = o;
                             }
@@ -483,6 +519,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                         for (int r = 0; r < R; ++r)
 #pragma unroll
                             for (int c = 0; c < C; ++c) d[r][c] = dn[r][c];
+                    }
                     }
                 }
                 }
@@ -744,6 +781,12 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             // differ at distance 0: zeros of both signs, NaNs of two patterns), so the number of mismatches is the
             // histogram's sum; the largest distance and the first index are reduced over the wavefront with row shifts,
             // and lane 63 puts them into LDS.
+            // (a pair of twins: the first model's outputs were set aside; then the twin's, in the next place of the arrays)
+            constexpr int ACCOUNTS = TWIN ? 2 : 1;
+#pragma unroll 1
+            for (int acc = 0; acc < ACCOUNTS && (acc == 0 || twin); ++acc) {
+            const bool set_aside = TWIN && twin && acc == 0;
+            if (TWIN && acc == 1) ++mi;
             uint32_t maxd = 0;
             uint32_t first_off = 0xFFFFFFFFu;
             if (live) {
@@ -754,8 +797,8 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
                 for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int c = 0; c < C; ++c) {
-                        uint32_t x = d[r][c];
-                        if (slow_seen && (x & 0x7FFFFFFFu) > 0x7F800000u) x = nan_bits;          // (the short route produces no NaN)
+                        uint32_t x = set_aside ? dfirst[TWIN ? r : 0][TWIN ? c : 0] : d[r][c];
+                        if (slow_seen && (x & 0x7FFFFFFFu) > 0x7F800000u) x = set_aside ? nan_first : nan_bits;          // (the short route produces no NaN)
                         const uint64_t o = d_off + (uint64_t)(TI * r) * TN + TJ * c;
                         if (dumping) dout[dump_off + o] = x;
                         if (ref_first && mi == 0) ref[r][c] = x;
@@ -787,6 +830,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             if ((tid & 63u) == 63u && wmin != 0xFFFFFFFFu) {
                 atomicMin(&ml.first[mi], (unsigned long long)(sa->index_base + item0 * (uint64_t)(TM * TN) + wmin));
                 if (wmax) atomicMax(&ml.maxd[mi], wmax);
+            }
             }
         }
         set_f32_round_toward_zero(false);
@@ -821,7 +865,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
     }
 }
 
-template <int TM, int KC, bool ADAPT, int FAM>
+template <int TM, int KC, bool ADAPT, int FAM, bool TWIN = false>
 static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const void *B, const uint32_t *C, uint64_t batch, hipStream_t s)
 {
     constexpr int SLOTS = 256 / ((TM / 2) * (TM / 2));
@@ -839,16 +883,16 @@ static mmaemu_status launch_scan_cfg(const ScanArgs &sa, const void *A, const vo
         uint32_t &res = resident[dev & 15];
         if (!res) {
             int per_cu = 0, cus = 0;
-            MMAEMU_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, emulate_scan_kernel<TM, KC, ADAPT, FAM>, 256, 0));
+            MMAEMU_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, emulate_scan_kernel<TM, KC, ADAPT, FAM, TWIN>, 256, 0));
             MMAEMU_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
             res = (uint32_t)(per_cu > 0 ? per_cu : 1) * (uint32_t)(cus > 0 ? cus : 1);
         }
         const uint64_t passes = (blocks + res - 1) / res;
         grid = (uint32_t)((blocks + passes - 1) / passes);
     }
-    hipLaunchKernelGGL((emulate_scan_kernel<TM, KC, ADAPT, FAM>), dim3(grid), dim3(256), 0, s, sa, A, B, C, batch, (uint32_t)blocks);
+    hipLaunchKernelGGL((emulate_scan_kernel<TM, KC, ADAPT, FAM, TWIN>), dim3(grid), dim3(256), 0, s, sa, A, B, C, batch, (uint32_t)blocks);
     MMAEMU_HIP(hipGetLastError());
-    set_last_kernel("multi x%u tiled %dx%d r2x2 kc=%d any L vm=%d%s", sa.count, TM, TM, KC, ADAPT ? 1 : 0, FAM == 1 ? " rd" : (FAM == 2 ? " rd split" : (FAM == 3 ? " rd even/odd" : "")));
+    set_last_kernel("multi x%u tiled %dx%d r2x2 kc=%d any L vm=%d%s", sa.count, TM, TM, KC, ADAPT ? 1 : 0, FAM == 1 ? " rd" : (FAM == 2 ? " rd split" : (FAM == 3 ? " rd even/odd" : (TWIN ? ", twins share sums" : ""))));
     return MMAEMU_OK;
 }
 
@@ -893,6 +937,18 @@ bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32
     return true;
 }
 
+// tiles of one group whose launch holds twins (models that differ only in the output conversion)
+static mmaemu_status launch_scan_twins(const ScanArgs &sa, const void *A, const void *B, const uint32_t *Cm, uint32_t m, uint32_t n, uint32_t k,
+                                       uint64_t batch, bool adapt, hipStream_t s)
+{
+    if (m == 16 && n == 16 && k == 16) return adapt ? launch_scan_cfg<16, 16, true, 0, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<16, 16, false, 0, true>(sa, A, B, Cm, batch, s);
+    if (m == 32 && n == 32 && k == 8) return adapt ? launch_scan_cfg<32, 8, true, 0, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<32, 8, false, 0, true>(sa, A, B, Cm, batch, s);
+    if (m == 16 && n == 16 && k == 32) return adapt ? launch_scan_cfg<16, 32, true, 0, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<16, 32, false, 0, true>(sa, A, B, Cm, batch, s);
+    if (m == 32 && n == 32 && k == 16) return adapt ? launch_scan_cfg<32, 16, true, 0, true>(sa, A, B, Cm, batch, s) : launch_scan_cfg<32, 16, false, 0, true>(sa, A, B, Cm, batch, s);
+    set_error("emulate_compare_many: no kernel for this shape");
+    return MMAEMU_ERR_UNSUPPORTED;
+}
+
 template <int FAM>
 static mmaemu_status launch_scan_shape(const ScanArgs &sa, const void *A, const void *B, const uint32_t *Cm, uint32_t m, uint32_t n, uint32_t k,
                                        uint64_t batch, bool adapt, hipStream_t s)
@@ -927,14 +983,40 @@ mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, c
     sa.out_stride = ml.out_stride;
     sa.index_base = ml.index_base;
     sa.stats = reinterpret_cast<uint64_t *>(ml.stats);
+    // Order within the launch.  T-FDPA models on tiles of one group (L = k) that differ only in the output conversion
+    // (rounding, E8M13, output flush, NaN pattern) are twins: the second is moved next to the first (never across the
+    // line between sets that flush their inputs and sets that do not: twins agree on that), and the kernel computes
+    // their common maximum and sum once.
+    uint32_t order[MULTI_MAX], n_order = 0;
+    bool placed[MULTI_MAX] = {}, twin_of_next[MULTI_MAX] = {};
+    bool any_twin = false;
+    const uint32_t conversion_only = FL_RZ | FL_FTZ_OUT;
     for (uint32_t i = 0; i < ml.count; ++i) {
+        if (placed[i]) continue;
+        placed[i] = true;
+        order[n_order++] = i;
         const ModelArgs &p = ml.models[i];
-        sa.slot[i] = ml.slot[i];
-        sa.hot[i] = ScanArgs::Hot{p.F, p.flags, p.out_mask, p.nan_bits, p.L, ml.kind[i], p.F2, p.Fc, p.sum_drop_distance, p.Fm,
-                                  p.split == MMAEMU_SPLIT_QUARTERS ? 4u : 2u};
+        if (ml.cls != 0 || p.L != k) continue;
+        for (uint32_t j = i + 1; j < ml.count; ++j) {
+            const ModelArgs &q = ml.models[j];
+            if (placed[j] || q.L != p.L || q.F != p.F || ml.kind[j] != ml.kind[i] || ((q.flags ^ p.flags) & ~conversion_only) != 0) continue;
+            placed[j] = true;
+            twin_of_next[n_order - 1] = true;
+            order[n_order++] = j;
+            any_twin = true;
+            break;
+        }
+    }
+    for (uint32_t q = 0; q < ml.count; ++q) {
+        const uint32_t i = order[q];
+        const ModelArgs &p = ml.models[i];
+        sa.slot[q] = ml.slot[i];
+        sa.hot[q] = ScanArgs::Hot{p.F, p.flags, p.out_mask, p.nan_bits, p.L, ml.kind[i], p.F2, p.Fc, p.sum_drop_distance, p.Fm,
+                                  p.split == MMAEMU_SPLIT_QUARTERS ? 4u : 2u, twin_of_next[q] ? 1u : 0u};
     }
     const bool adapt = ta == MMAEMU_BF16 || tb == MMAEMU_BF16;
     const uint32_t *Cm = static_cast<const uint32_t *>(C);
+    if (ml.cls == 0 && any_twin) return launch_scan_twins(sa, A, B, Cm, m, n, k, batch, adapt, s);
     if (ml.cls == 0) return launch_scan_shape<0>(sa, A, B, Cm, m, n, k, batch, adapt, s);
     if (ml.cls <= 3) return launch_scan_shape<1>(sa, A, B, Cm, m, n, k, batch, adapt, s);
     if (ml.cls <= 6) return launch_scan_shape<2>(sa, A, B, Cm, m, n, k, batch, false, s);

@@ -328,6 +328,45 @@ def test_even_odd_sets_in_the_fused_kernel(mm, ta, tb, m, k):
             assert_same(got_D[i][t:t + 1, :6], o1_emulate(plist[i], A[t:t + 1, :6], B[t:t + 1], C[t:t + 1, :6], ta, tb), "rational oracle, set %d tile %d" % (i, t))
 
 
+@pytest.mark.parametrize("ta,tb,m,k", [(fm.FP16, fm.FP16, 16, 16), (fm.BF16, fm.BF16, 16, 16), (fm.FP16, fm.FP16, 32, 8), (fm.E4M3, fm.E5M2, 16, 32),
+                                       (fm.BF16, fm.BF16, 32, 16), (fm.E5M2, fm.E5M2, 32, 8)])
+def test_twins_share_their_sums(mm, ta, tb, m, k):
+    # tiles of one group: sets that differ only in the output conversion (rounding, E8M13, output flush, NaN pattern) are
+    # evaluated in pairs that share the group's maximum and sum; every set's outputs and statistics as if alone
+    rng = np.random.default_rng(700 + 8 * ta + tb + k)
+    nb = 45
+    A, B, C = make_case(rng, ta, tb, nb, m, m, k, special_frac=0.003)
+    half = nb // 2
+    A[:half] = synth.narrow_exponent_bits(rng, (half, m, k), ta, *((110, 140) if ta == fm.BF16 else (1, 14)))
+    B[:half] = synth.narrow_exponent_bits(rng, (half, m, k), tb, *((110, 140) if tb == fm.BF16 else (1, 14)))
+    C[:half] = synth.narrow_exponent_bits(rng, (half, m, m), fm.FP32, 100, 150)
+    C[half:half + 4] = synth.narrow_exponent_bits(rng, (4, m, m), fm.FP32, 0, 3)          # subnormal accumulators and results
+    a = ModelParams(group_len=k, frac_bits=16)
+    b = ModelParams(group_len=k, frac_bits=24 if k <= 16 else 20, nan_bits=0x7FFFFFFF)
+    c = ModelParams(group_len=k, frac_bits=20, ftz_in=True)
+    w = ModelParams(group_len=k, frac_bits=32)                                             # binary64 sums
+    plist = [a, b, a.with_(out_round=RZ), c, a.with_(out_round=RZ, out_mant_bits=13), b.with_(out_round=RZ, nan_bits=0xFFC00000),
+             c.with_(ftz_out=True, out_round=RZ), a.with_(ftz_out=True), w, w.with_(out_round=RZ, ftz_out=True),
+             ModelParams(group_len=k // 2, frac_bits=16), ModelParams(group_len=k // 2, frac_bits=16, out_round=RZ)]   # (two groups per tile: no twins)
+    want = oracle_outputs(plist, A, B, C, ta, tb)
+    ref = want[1].copy()
+    flat = ref.reshape(-1)
+    idx = rng.choice(flat.size, size=flat.size // 25, replace=False)
+    flat[idx] += rng.integers(1, 500, size=idx.size).astype(np.uint32)
+    got_stats, got_D, kern, _ = run_many(mm, plist, A, B, C, ta, tb, ref=ref, index_base=9)
+    assert kern.startswith("multi x12") and kern.endswith("twins share sums"), kern
+    for i, p in enumerate(plist):
+        assert_same(got_D[i], want[i], "set %d %s" % (i, p))
+        assert got_stats[i] == ostats.compare(want[i], ref, index_base=9), (i, p)
+    # the first set as the reference, its twin compared with it; no outputs written
+    pl2 = [plist[1], plist[5], plist[3], plist[6], plist[7]]
+    w2 = [want[1], want[5], want[3], want[6], want[7]]
+    st, _, kern, _ = run_many(mm, pl2, A, B, C, ta, tb, ref=None, dump=False)
+    assert kern.endswith("twins share sums"), kern
+    assert st == [ostats.compare(x, w2[0]) for x in w2]
+    assert st[1]["n_mismatch_bits"] > 0
+
+
 def test_t_fdpa_and_tr_fdpa_sets_in_one_call(mm):
     # a list that mixes both families and a set outside the fused kernels; the first model is the reference
     rng = np.random.default_rng(55)
