@@ -165,6 +165,34 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
     const uint32_t *dref = sa->dref;
 
     constexpr int NQ = (SLOTS * TM * (KC / 4) + 255) / 256;
+    // AHEAD (the 32 x 32 tiles of FP8 / FP16 operands, whose kernels have registers to spare under the four-wave budget):
+    // a pass's global loads (operand quads, accumulator inputs, reference) are issued one pass ahead, right after the
+    // previous pass has been staged, so that they arrive while its models run.
+    constexpr bool AHEAD = TM == 32 && !ADAPT && FAM == 0;
+    constexpr int NA = AHEAD ? NQ : 1, RA = AHEAD ? R : 1, CA = AHEAD ? C : 1;
+    uint2 nraw_a[NA], nraw_b[NA];
+    uint32_t nc0[RA][CA], nref[RA][CA];
+    auto fetch_pass = [&](uint32_t wg) {
+        if constexpr (AHEAD) {
+            const uint64_t it0 = (uint64_t)wg * SLOTS;
+            StagePlan<NQ> pa, pb;
+            make_plan<TM, KC, SLOTS, VS, ES, true, NQ>(pa, A, esa, it0, nitems, 1u, 1u, TM, KC);
+            make_plan<TN, KC, SLOTS, VS, ES, false, NQ>(pb, B, esb, it0, nitems, 1u, 1u, TN, KC);
+            load_panel<NQ>(esa, pa, 0, nraw_a);
+            load_panel<NQ>(esb, pb, 0, nraw_b);
+            const uint64_t tile = it0 + slot < nitems ? it0 + slot : nitems - 1;
+            const uint64_t off = (tile * TM + ti) * (uint64_t)TN + tj;
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    const uint64_t o = off + (uint64_t)(TI * r) * TN + TJ * c;
+                    nc0[r][c] = Cm[o];
+                    nref[r][c] = ref_first ? 0u : dref[o];
+                }
+        }
+    };
+    if (AHEAD && blockIdx.x < nblocks) fetch_pass(blockIdx.x);
     for (uint32_t pass_wg = blockIdx.x; pass_wg < nblocks; pass_wg += gridDim.x) {
         // ---- this pass's tiles: staging plans, outputs, operands in flight ----
         const uint64_t item0 = (uint64_t)pass_wg * SLOTS;
@@ -172,8 +200,13 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
         make_plan<TM, KC, SLOTS, VS, ES, true, NQ>(plan_a, A, esa, item0, nitems, 1u, 1u, TM, KC);
         make_plan<TN, KC, SLOTS, VS, ES, false, NQ>(plan_b, B, esb, item0, nitems, 1u, 1u, TN, KC);
         uint2 raw_a[NQ], raw_b[NQ];
-        load_panel<NQ>(esa, plan_a, 0, raw_a);
-        load_panel<NQ>(esb, plan_b, 0, raw_b);
+        if constexpr (AHEAD) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) { raw_a[q] = nraw_a[q]; raw_b[q] = nraw_b[q]; }
+        } else {
+            load_panel<NQ>(esa, plan_a, 0, raw_a);
+            load_panel<NQ>(esb, plan_b, 0, raw_b);
+        }
         const bool live = item0 + slot < nitems;
         const uint64_t my_tile = live ? item0 + slot : nitems - 1;
         const uint64_t d_off = (my_tile * TM + ti) * (uint64_t)TN + tj;             // + TI * r * TN + TJ * c
@@ -182,9 +215,14 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
         for (int r = 0; r < R; ++r)
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                const uint64_t o = d_off + (uint64_t)(TI * r) * TN + TJ * c;
-                c0[r][c] = Cm[o];
-                ref[r][c] = ref_first ? 0u : dref[o];
+                if constexpr (AHEAD) {
+                    c0[r][c] = nc0[r][c];
+                    ref[r][c] = nref[r][c];
+                } else {
+                    const uint64_t o = d_off + (uint64_t)(TI * r) * TN + TJ * c;
+                    c0[r][c] = Cm[o];
+                    ref[r][c] = ref_first ? 0u : dref[o];
+                }
             }
         // ---- decode and stage (as the first model wants them) ----
         bool chunk_is_double = false;
@@ -203,6 +241,7 @@ emulate_scan_kernel(ScanArgs sa_, const void *__restrict__ A, const void *__rest
             store_panel<NQ, VS, VSD>(plan_b, fb, xb, Bv_raw, Be, chunk_is_double, 3);
             __syncthreads();
         }
+        if (AHEAD && pass_wg + gridDim.x < nblocks) fetch_pass(pass_wg + gridDim.x);
         // ---- pass 1, once: the maximum of e'_a + e'_b over each quarter group, two quarters per kept dword ----
 #pragma unroll
         for (int q = 0; q < NQ4; ++q) {
