@@ -104,6 +104,11 @@ bool scan_takes(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32
                 uint32_t &cls);
 mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, const void *C, uint32_t m, uint32_t n, uint32_t k,
                           uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
+// Algorithm "E-FDPA" in 16 x 16 blocks with the operands shared through LDS (emulate_efdpa.hip); efdpa_blocks_take: whether
+// it takes the problem (else the general kernel does)
+bool efdpa_blocks_take(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k);
+mmaemu_status launch_emulate_efdpa(const ModelArgs &p, const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n,
+                                   uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                      uint32_t tb, hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr,

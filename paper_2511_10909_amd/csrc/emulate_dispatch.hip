@@ -63,6 +63,8 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
         else st = launch_vm<0>(t, A, B, Cm, D, m, n, k, batch, s, handled);
         if (handled) return st;
     }
+    // Algorithm "E-FDPA" on whole 16 x 16 blocks: operands shared through LDS, the exact sum held in a pair of binary64 numbers
+    if (!scaled && efdpa_blocks_take(p, ta, tb, m, n, k)) return launch_emulate_efdpa(p, A, B, Cm, D, m, n, k, batch, ta, tb, s);
     return launch_emulate_generic(p, A, B, Cm, D, m, n, k, batch, ta, tb, s, SA, SB, scaled ? block : 1u);
 }
 

@@ -1,0 +1,173 @@
+// Algorithm "E-FDPA" (the exact sum of a group's products and the accumulator, converted once) with operand sharing: a
+// workgroup owns a 16 x 16 block of D, one output per thread; the rows of A and B that the block needs are decoded once,
+// into LDS, as binary64 values (32 values of k at a time).
+//
+// Every product of two operands of at most 24 significant bits is exact in binary64.  A thread keeps the running sum as
+// an unevaluated pair hi + lo of binary64 numbers: each product is added to hi with Knuth's TwoSum, whose error term is
+// added to lo with a second TwoSum; as long as that second error is zero, hi + lo is the exact sum (about 106 bits of
+// it, which covers every FP16 or FP8 group and BF16 groups of ordinary data).  At the end of the group the pair is
+// brought to hi = RN(sum), lo = sum - hi, hi is rounded to odd where lo is not zero, and one hardware conversion to
+// binary32 then rounds correctly (53 bits are more than 24 + 2).  A group whose sum did not stay exact (BF16 or TF32
+// operands spread over hundreds of binary places) is run again by the integer routine with its 640-bit accumulator.
+// NaN and infinite operands need nothing of their own: binary64 arithmetic gives NaN for a NaN, for infinity times
+// zero and for infinities of both signs, and the infinity otherwise, which is Sec. 4.2's rule.
+#include "emulate_tiled.hpp"
+
+namespace mmaemu {
+
+// one element as the binary64 number it denotes (NaN and infinities as themselves); FlushSubnormal on request
+__device__ __forceinline__ double efdpa_value(uint32_t t, const void *p, uint64_t idx, uint32_t ftz_in)
+{
+    float v = 0.0f;
+    uint32_t ex;
+    bool wild = false;
+    switch (t) {   // uniform
+    case MMAEMU_FP8_E4M3: decode_elem<MMAEMU_FP8_E4M3>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP8_E5M2: decode_elem<MMAEMU_FP8_E5M2>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP6_E2M3: decode_elem<MMAEMU_FP6_E2M3>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP6_E3M2: decode_elem<MMAEMU_FP6_E3M2>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP4_E2M1: decode_elem<MMAEMU_FP4_E2M1>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP16: decode_elem<MMAEMU_FP16>(static_cast<const uint16_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_TF32: decode_elem<MMAEMU_TF32>(static_cast<const uint32_t *>(p)[idx] >> 13, ftz_in, 0u, v, ex, wild); break;
+    default: decode_elem<MMAEMU_BF16>(static_cast<const uint16_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
+    }
+    return (double)v;
+}
+
+// s + e = a + b exactly (s = RN(a + b)), for finite operands
+__device__ __forceinline__ void two_sum(double a, double b, double &s, double &e)
+{
+    s = a + b;
+    const double bb = s - a;
+    e = (a - (s - bb)) + (b - bb);
+}
+
+constexpr int EKC = 32;                       // values of k staged at a time
+
+__global__ void __launch_bounds__(256)
+emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *C,
+                            uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nblocks)
+{
+    constexpr int VS = EKC + 2;               // row stride in doubles: rows spread over the banks, pairs stay 16-byte aligned
+    __shared__ __attribute__((aligned(16))) double As[16][VS];
+    __shared__ __attribute__((aligned(16))) double Bs[16][VS];
+    const uint32_t tid = threadIdx.x, i = tid / 16u, j = tid % 16u;
+    const uint32_t bpr = n / 16u, bpt = (m / 16u) * bpr;
+    const uint32_t esa = (ta <= MMAEMU_FP8_E5M2 || (ta >= MMAEMU_FP6_E2M3 && ta != MMAEMU_TF32)) ? 1u : (ta == MMAEMU_TF32 ? 4u : 2u);
+    const uint32_t esb = (tb <= MMAEMU_FP8_E5M2 || (tb >= MMAEMU_FP6_E2M3 && tb != MMAEMU_TF32)) ? 1u : (tb == MMAEMU_TF32 ? 4u : 2u);
+    const uint32_t L = p.L;
+    for (uint64_t w = blockIdx.x; w < nblocks; w += gridDim.x) {
+        const uint64_t t = w / bpt;
+        const uint32_t r = (uint32_t)(w - t * bpt), bi = r / bpr, bj = r - bi * bpr;
+        const uint64_t arow0 = t * m + 16u * bi, brow0 = t * n + 16u * bj;          // first row of the block in A and in B
+        const uint64_t o = (arow0 + i) * (uint64_t)n + 16u * bj + j;
+        uint32_t d = C[o];
+        double hi = 0.0, lo = 0.0;
+        double lost = 0.0;                                 // what the pair could not hold (0 while the sum is exact; NaN after an infinity)
+        uint32_t cin = d;                                  // the accumulator the group at hand started from
+        for (uint32_t k0 = 0; k0 < k; k0 += EKC) {
+            const uint32_t kc = k - k0 < (uint32_t)EKC ? k - k0 : (uint32_t)EKC;
+            __syncthreads();                               // (the previous chunk's readers)
+            for (uint32_t e = tid; e < 16u * kc; e += 256u) {
+                const uint32_t row = e / kc, kk = e - row * kc;
+                As[row][kk] = efdpa_value(ta, A, (arow0 + row) * (uint64_t)k + k0 + kk, p.ftz_in);
+                Bs[row][kk] = efdpa_value(tb, B, (brow0 + row) * (uint64_t)k + k0 + kk, p.ftz_in);
+            }
+            __syncthreads();
+            // the groups (or the part of a longer group) inside this chunk
+            for (uint32_t g0 = 0; g0 < kc; g0 += (L < kc ? L : kc)) {
+                const uint32_t glen = L < kc ? L : kc;
+                if ((k0 + g0) % L == 0) {
+                    // a group starts: the accumulator (flushed if the model flushes inputs) is its first term
+                    cin = d;
+                    if (p.ftz_in && (cin & 0x7F800000u) == 0) cin = 0;
+                    hi = (double)__uint_as_float(cin);
+                    lo = 0.0;
+                    lost = 0.0;
+                }
+                auto term = [&](double x, double y) {
+                    const double prod = x * y;                             // exact
+                    double s, e, l2, e2;
+                    two_sum(hi, prod, s, e);
+                    two_sum(lo, e, l2, e2);
+                    hi = s;
+                    lo = l2;
+                    lost += __builtin_fabs(e2);
+                };
+                if (glen % 2 == 0) {
+                    // (g0 is even then: pairs of k come with one 128-bit LDS read per row)
+#pragma unroll 2
+                    for (uint32_t kk = g0; kk < g0 + glen; kk += 2) {
+                        const double2 x = *reinterpret_cast<const double2 *>(&As[i][kk]), y = *reinterpret_cast<const double2 *>(&Bs[j][kk]);
+                        term(x.x, y.x);
+                        term(x.y, y.y);
+                    }
+                } else {
+                    for (uint32_t kk = g0; kk < g0 + glen; ++kk) term(As[i][kk], Bs[j][kk]);
+                }
+                const bool inexact = !(lost == 0.0);                       // (also true for the NaN that infinities leave there)
+                if ((k0 + g0 + glen) % L == 0) {
+                    // the group ends
+                    uint32_t out;
+                    const uint64_t hb = (uint64_t)__double_as_longlong(hi);
+                    if ((hb & 0x7FFFFFFFFFFFFFFFull) > 0x7FF0000000000000ull) {
+                        out = p.nan_bits;
+                    } else if ((hb & 0x7FFFFFFFFFFFFFFFull) == 0x7FF0000000000000ull) {
+                        out = (hb >> 63) ? 0xFF800000u : 0x7F800000u;
+                    } else if (inexact) {
+                        // the sum left the pair's reach: the integer routine, from the operands in memory
+                        const uint32_t gk = k0 + g0 + glen - L;
+                        const uint8_t *ap = static_cast<const uint8_t *>(A) + ((arow0 + i) * (uint64_t)k + gk) * esa;
+                        const uint8_t *bp = static_cast<const uint8_t *>(B) + ((brow0 + j) * (uint64_t)k + gk) * esb;
+                        out = fdpa_group<true>(p, dyn_fmt(ta), dyn_fmt(tb), ap, bp, L, d, no_scales());
+                    } else {
+                        double h, l;
+                        two_sum(hi, lo, h, l);                             // h = RN(sum), l = sum - h
+                        if (l != 0.0) {
+                            // round to odd: of h and its neighbour on l's side, the one whose last bit is set
+                            long long b = __double_as_longlong(h);
+                            if ((b & 1ll) == 0) b += ((l > 0.0) == (h > 0.0)) ? 1ll : -1ll;      // (h is not zero here: |l| <= ulp(h) / 2)
+                            h = __longlong_as_double(b);
+                        }
+                        out = __float_as_uint((float)h);                   // RNE, gradual underflow, overflow to infinity
+                        if (p.out_round == MMAEMU_ROUND_RZ) {
+                            const double back = (double)__uint_as_float(out);
+                            if (__builtin_fabs(back) > __builtin_fabs(h)) out -= 1u;             // rounded away from zero: step back
+                        }
+                        if (h == 0.0) out = 0u;                            // an exact zero is +0.0
+                        // (out_mask, output flush, sign of a zero result)
+                        out &= p.out_mask;
+                        if (p.ftz_out && (out & 0x7F800000u) == 0) out &= 0x80000000u;
+                        if (p.zero_result_positive && (out & 0x7FFFFFFFu) == 0) out = 0u;
+                    }
+                    d = out;
+                }
+            }
+        }
+        D[o] = d;
+    }
+}
+
+// Whether the kernel takes the problem: whole 16 x 16 blocks, operands of at most 24 significant bits other than FP32
+// words, and groups that either lie inside a staged chunk of 32 (L = 1, 2, 4, 8, 16, 32) or are made of whole chunks.
+bool efdpa_blocks_take(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k)
+{
+    if (p.c_mode != MMAEMU_C_EXACT || (p.flags & (FL_ACC16 | FL_NAN_PROPAGATE))) return false;
+    if (ta == MMAEMU_FP32 || tb == MMAEMU_FP32) return false;
+    if (m % 16 != 0 || n % 16 != 0 || p.L == 0 || k % p.L != 0) return false;
+    return (p.L <= (uint32_t)EKC && EKC % p.L == 0) || p.L % EKC == 0;
+}
+
+mmaemu_status launch_emulate_efdpa(const ModelArgs &p, const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n,
+                                   uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s)
+{
+    const uint64_t nblocks = batch * (m / 16) * (n / 16);
+    const uint64_t grid = nblocks < (1ull << 16) ? nblocks : (1ull << 16);
+    hipLaunchKernelGGL(emulate_efdpa_blocks_kernel, dim3((uint32_t)grid), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C, (uint32_t *)D,
+                       m, n, k, nblocks);
+    MMAEMU_HIP(hipGetLastError());
+    set_last_kernel("e-fdpa, 16x16 blocks through LDS");
+    return MMAEMU_OK;
+}
+
+} // namespace mmaemu

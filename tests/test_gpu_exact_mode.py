@@ -93,3 +93,77 @@ def test_exact_mode_argument_checks(mm):
     mm.model_destroy(h)
     with pytest.raises(mm.MmaemuError):
         mm.model_create(group_len=4, c_mode=mm.C_EXACT, frac_bits2=31)
+
+
+def _exact_cases(rng):
+    """(name, params, A, B, C, ta, tb) on whole 16x16 blocks: narrow exponents (the sum stays within the pair of binary64
+    numbers the block kernel keeps), whole ranges (BF16 / TF32 groups leave it and take the integer routine), cancelling
+    pairs, special values."""
+    out = []
+    pairs = [p for p in PAIRS if fm.FP32 not in p]
+    for idx, (ta, tb) in enumerate(pairs):
+        for variant in range(4):
+            L = [4, 2, 16, 64][variant]
+            k = [12, 6, 48, 64][variant]
+            p = ModelParams(group_len=L, c_mode=C_EXACT, out_round=RZ if variant in (1, 3) else RNE, ftz_in=variant == 1, ftz_out=variant == 2,
+                            nan_bits=0x7FFFFFFF if variant == 0 else 0x7FC00000, out_mant_bits=13 if variant == 3 else 23)
+            nb, m, n = 2, 32, 16
+            if variant in (0, 3):
+                A = synth.random_bits(rng, (nb, m, k), ta)
+                B = synth.random_bits(rng, (nb, n, k), tb)
+            else:
+                lo_hi = {fm.BF16: (100, 150), fm.TF32: (100, 150), fm.FP16: (1, 30), fm.E4M3: (0, 15), fm.E5M2: (0, 30), fm.E2M3: (0, 3), fm.E3M2: (0, 7), fm.E2M1: (0, 3)}
+                A = synth.narrow_exponent_bits(rng, (nb, m, k), ta, *lo_hi[ta])
+                B = synth.narrow_exponent_bits(rng, (nb, n, k), tb, *lo_hi[tb])
+            if variant == 0:
+                A[:, :, 1::2] = A[:, :, 0::2] ^ (1 << (synth.WIDTH[ta] - 1) if ta != fm.TF32 else 1 << 31)
+                B[:, :, 1::2] = B[:, :, 0::2]
+                B[:, ::3, 1] ^= 1
+            C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 90, 160) if variant in (1, 2) else synth.random_bits(rng, (nb, m, n), fm.FP32)
+            if variant == 1:
+                A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[ta], 0.02)
+                C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32], 0.03)
+                C[0, 0, :4] = [0, 0x80000000, 1, 0x80000001]                  # zeros and subnormal accumulators
+            out.append(("types %d x %d, variant %d" % (ta, tb, variant), p, A, B, C, ta, tb))
+    return out
+
+
+def test_exact_mode_in_blocks_matches_the_rational_oracle(mm):
+    rng = np.random.default_rng(4343)
+    gpu, jobs, names = [], [], []
+    for name, p, A, B, C, ta, tb in _exact_cases(rng):
+        got = gpu_emulate(mm, p, A, B, C, ta, tb)
+        assert gpu_emulate.last_kernel == "e-fdpa, 16x16 blocks through LDS", gpu_emulate.last_kernel
+        # the same problem without B's last row runs in the general kernel (n = 15): the two routes agree
+        via_general = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, tb)
+        assert gpu_emulate.last_kernel == "general, exact sum"
+        assert_same(got[:, :, :-1], via_general, "block kernel against the general kernel, " + name)
+        keep = slice(0, 1) if "variant 3" in name else slice(0, 2)           # (the oracle on one tile of the longest case)
+        gpu.append(got[keep, ::3])
+        jobs.append((dataclasses.asdict(p), A[keep, ::3], B[keep], C[keep, ::3], ta, tb, None, None, 0))
+        names.append(name)
+    want = run_pool(jobs, workers=12)
+    bad = []
+    for name, g, w in zip(names, gpu, want):
+        if not np.array_equal(g, w):
+            i = tuple(np.argwhere(g != w)[0])
+            bad.append("%s: %d of %d differ, first at %s: gpu %08x, oracle %08x" % (name, int((g != w).sum()), g.size, i, int(g[i]), int(w[i])))
+    assert not bad, "\n".join(bad)
+
+
+def test_exact_mode_blocks_on_ordinary_data_at_size(mm):
+    # N(0,1)-like operands on many tiles: every sum stays within the pair of binary64 numbers; against the general kernel
+    rng = np.random.default_rng(4344)
+    for ta, L, k in ((fm.FP16, 4, 16), (fm.BF16, 2, 16), (fm.E4M3, 16, 32)):
+        nb, m, n = 64, 32, 32
+        lo_hi = {fm.BF16: (117, 130), fm.FP16: (5, 18), fm.E4M3: (2, 10)}[ta]
+        A = synth.narrow_exponent_bits(rng, (nb, m, k), ta, *lo_hi)
+        B = synth.narrow_exponent_bits(rng, (nb, n, k), ta, *lo_hi)
+        C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 117, 130)
+        for rho in (RNE, RZ):
+            p = ModelParams(group_len=L, c_mode=C_EXACT, out_round=rho)
+            got = gpu_emulate(mm, p, A, B, C, ta, ta)
+            assert gpu_emulate.last_kernel == "e-fdpa, 16x16 blocks through LDS"
+            ref = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, ta)
+            assert gpu_emulate.last_kernel == "general, exact sum"
+            assert_same(got[:, :, :-1], ref, "types %d L %d rho %d" % (ta, L, rho))
