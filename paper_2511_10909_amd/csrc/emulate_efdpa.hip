@@ -2,16 +2,11 @@
 // workgroup owns a 16 x 16 block of D, one output per thread; the rows of A and B that the block needs are decoded once,
 // into LDS, as binary64 values (32 values of k at a time).
 //
-// Every product of two operands of at most 24 significant bits is exact in binary64.  A thread keeps the running sum as
-// an unevaluated pair hi + lo of binary64 numbers: each product is added to hi with Knuth's TwoSum, whose error term is
-// added to lo with a second TwoSum; as long as that second error is zero, hi + lo is the exact sum (about 106 bits of
-// it, which covers every FP16 or FP8 group and BF16 groups of ordinary data).  At the end of the group the pair is
-// brought to hi = RN(sum), lo = sum - hi, hi is rounded to odd where lo is not zero, and one hardware conversion to
-// binary32 then rounds correctly (53 bits are more than 24 + 2).  A group whose sum did not stay exact (BF16 or TF32
-// operands spread over hundreds of binary places) is run again by the integer routine with its 640-bit accumulator.
-// NaN and infinite operands need nothing of their own: binary64 arithmetic gives NaN for a NaN, for infinity times
-// zero and for infinities of both signs, and the infinity otherwise, which is Sec. 4.2's rule.
+// A thread keeps the exact sum as an unevaluated pair of binary64 numbers (efdpa_pair.hpp); a group whose sum does not stay
+// exact there (BF16 or TF32 operands spread over hundreds of binary places) is run again by the integer routine with its
+// 640-bit accumulator.
 #include "emulate_tiled.hpp"
+#include "efdpa_pair.hpp"
 
 namespace mmaemu {
 
@@ -34,14 +29,6 @@ __device__ __forceinline__ double efdpa_value(uint32_t t, const void *p, uint64_
     return (double)v;
 }
 
-// s + e = a + b exactly (s = RN(a + b)), for finite operands
-__device__ __forceinline__ void two_sum(double a, double b, double &s, double &e)
-{
-    s = a + b;
-    const double bb = s - a;
-    e = (a - (s - bb)) + (b - bb);
-}
-
 constexpr int EKC = 32;                       // values of k staged at a time
 
 __global__ void __launch_bounds__(256)
@@ -62,9 +49,8 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
         const uint64_t arow0 = t * m + 16u * bi, brow0 = t * n + 16u * bj;          // first row of the block in A and in B
         const uint64_t o = (arow0 + i) * (uint64_t)n + 16u * bj + j;
         uint32_t d = C[o];
-        double hi = 0.0, lo = 0.0;
-        double lost = 0.0;                                 // what the pair could not hold (0 while the sum is exact; NaN after an infinity)
-        uint32_t cin = d;                                  // the accumulator the group at hand started from
+        ExactPair sum;
+        sum.start(0u);
         for (uint32_t k0 = 0; k0 < k; k0 += EKC) {
             const uint32_t kc = k - k0 < (uint32_t)EKC ? k - k0 : (uint32_t)EKC;
             __syncthreads();                               // (the previous chunk's readers)
@@ -79,66 +65,28 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
                 const uint32_t glen = L < kc ? L : kc;
                 if ((k0 + g0) % L == 0) {
                     // a group starts: the accumulator (flushed if the model flushes inputs) is its first term
-                    cin = d;
-                    if (p.ftz_in && (cin & 0x7F800000u) == 0) cin = 0;
-                    hi = (double)__uint_as_float(cin);
-                    lo = 0.0;
-                    lost = 0.0;
+                    sum.start((p.ftz_in && (d & 0x7F800000u) == 0) ? 0u : d);
                 }
-                auto term = [&](double x, double y) {
-                    const double prod = x * y;                             // exact
-                    double s, e, l2, e2;
-                    two_sum(hi, prod, s, e);
-                    two_sum(lo, e, l2, e2);
-                    hi = s;
-                    lo = l2;
-                    lost += __builtin_fabs(e2);
-                };
                 if (glen % 2 == 0) {
                     // (g0 is even then: pairs of k come with one 128-bit LDS read per row)
 #pragma unroll 2
                     for (uint32_t kk = g0; kk < g0 + glen; kk += 2) {
                         const double2 x = *reinterpret_cast<const double2 *>(&As[i][kk]), y = *reinterpret_cast<const double2 *>(&Bs[j][kk]);
-                        term(x.x, y.x);
-                        term(x.y, y.y);
+                        sum.add(x.x, y.x);
+                        sum.add(x.y, y.y);
                     }
                 } else {
-                    for (uint32_t kk = g0; kk < g0 + glen; ++kk) term(As[i][kk], Bs[j][kk]);
+                    for (uint32_t kk = g0; kk < g0 + glen; ++kk) sum.add(As[i][kk], Bs[j][kk]);
                 }
-                const bool inexact = !(lost == 0.0);                       // (also true for the NaN that infinities leave there)
                 if ((k0 + g0 + glen) % L == 0) {
                     // the group ends
                     uint32_t out;
-                    const uint64_t hb = (uint64_t)__double_as_longlong(hi);
-                    if ((hb & 0x7FFFFFFFFFFFFFFFull) > 0x7FF0000000000000ull) {
-                        out = p.nan_bits;
-                    } else if ((hb & 0x7FFFFFFFFFFFFFFFull) == 0x7FF0000000000000ull) {
-                        out = (hb >> 63) ? 0xFF800000u : 0x7F800000u;
-                    } else if (inexact) {
+                    if (!sum.finish(p, out)) {
                         // the sum left the pair's reach: the integer routine, from the operands in memory
                         const uint32_t gk = k0 + g0 + glen - L;
                         const uint8_t *ap = static_cast<const uint8_t *>(A) + ((arow0 + i) * (uint64_t)k + gk) * esa;
                         const uint8_t *bp = static_cast<const uint8_t *>(B) + ((brow0 + j) * (uint64_t)k + gk) * esb;
                         out = fdpa_group<true>(p, dyn_fmt(ta), dyn_fmt(tb), ap, bp, L, d, no_scales());
-                    } else {
-                        double h, l;
-                        two_sum(hi, lo, h, l);                             // h = RN(sum), l = sum - h
-                        if (l != 0.0) {
-                            // round to odd: of h and its neighbour on l's side, the one whose last bit is set
-                            long long b = __double_as_longlong(h);
-                            if ((b & 1ll) == 0) b += ((l > 0.0) == (h > 0.0)) ? 1ll : -1ll;      // (h is not zero here: |l| <= ulp(h) / 2)
-                            h = __longlong_as_double(b);
-                        }
-                        out = __float_as_uint((float)h);                   // RNE, gradual underflow, overflow to infinity
-                        if (p.out_round == MMAEMU_ROUND_RZ) {
-                            const double back = (double)__uint_as_float(out);
-                            if (__builtin_fabs(back) > __builtin_fabs(h)) out -= 1u;             // rounded away from zero: step back
-                        }
-                        if (h == 0.0) out = 0u;                            // an exact zero is +0.0
-                        // (out_mask, output flush, sign of a zero result)
-                        out &= p.out_mask;
-                        if (p.ftz_out && (out & 0x7F800000u) == 0) out &= 0x80000000u;
-                        if (p.zero_result_positive && (out & 0x7FFFFFFFu) == 0) out = 0u;
                     }
                     d = out;
                 }

@@ -9,8 +9,18 @@
 // truncation toward zero to F fractional bits and the exact integer sum -- followed by
 // the conversion rho and the optional output flush (Algorithm "FTZ-Add/FTZ-Mul").
 #include "fdpa_int.hpp"
+#include "efdpa_pair.hpp"
 
 namespace mmaemu {
+
+// a decoded element as the binary64 number it denotes (at most 24 significant bits: exact)
+template <class FT>
+__device__ __forceinline__ double dec_value(const FT &f, const Dec &x)
+{
+    if (x.cls == CLS_NAN) return __longlong_as_double(0x7FF8000000000000ll);
+    const double mag = x.cls == CLS_INF ? __longlong_as_double(0x7FF0000000000000ll) : ldexp((double)x.sig, x.exp - f.mb());
+    return x.sign ? -mag : mag;
+}
 
 // EXACT: Algorithm "E-FDPA" (its 640-bit accumulator sits in private memory, so it gets instantiations of its own and the
 // other modes stay free of scratch memory)
@@ -40,6 +50,20 @@ emulate_generic_kernel(ModelArgs p, const typename Fmt<TA>::elem *__restrict__ A
         }
         for (uint32_t k0 = 0; k0 < k; k0 += p.L) {
             sr.k0 = k0;
+            if constexpr (EXACT) {
+                // first in a pair of binary64 numbers, which holds the exact sum of most groups; the 640-bit accumulator
+                // only where it does not (the payload variation goes there directly)
+                if (!(p.flags & FL_NAN_PROPAGATE)) {
+                    const StaticFmt<TA> fa{};
+                    const StaticFmt<TB> fb{};
+                    ExactPair sum;
+                    sum.start((p.ftz_in && (d & 0x7F800000u) == 0) ? 0u : d);
+                    for (uint32_t kk = 0; kk < p.L; ++kk)
+                        sum.add(dec_value(fa, decode_as(fa, fa.load(a + k0, kk), p.ftz_in)), dec_value(fb, decode_as(fb, fb.load(b + k0, kk), p.ftz_in)));
+                    uint32_t out;
+                    if (sum.finish(p, out)) { d = out; continue; }
+                }
+            }
             d = fdpa_group<EXACT>(p, StaticFmt<TA>{}, StaticFmt<TB>{}, a + k0, b + k0, p.L, d, sr);
         }
         if (acc16) reinterpret_cast<uint16_t *>(D)[o] = (uint16_t)((d & 0x7FFFFFFFu) > 0x7F800000u ? p.nan16 : float_bits_to_half_bits(d));
