@@ -4,7 +4,9 @@
 //
 // A thread keeps the exact sum as an unevaluated pair of binary64 numbers (efdpa_pair.hpp); a group whose sum does not stay
 // exact there (BF16 or TF32 operands spread over hundreds of binary places) is run again by the integer routine with its
-// 640-bit accumulator.
+// 640-bit accumulator.  That routine costs the kernel which contains it 100 registers against 58, and with them half of
+// its waves, so where D is not C it sits in a kernel of its own: the block kernel leaves a mark in D (a NaN pattern that
+// no result has) at each output it could not finish, and a second launch runs those outputs' chains from C again.
 #include "emulate_tiled.hpp"
 #include "efdpa_pair.hpp"
 
@@ -31,9 +33,11 @@ __device__ __forceinline__ double efdpa_value(uint32_t t, const void *p, uint64_
 
 constexpr int EKC = 32;                       // values of k staged at a time
 
+// MARK: leave `mark` in D where a group's sum left the pair's reach, instead of running the integer routine here
+template <bool MARK>
 __global__ void __launch_bounds__(256)
 emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__restrict__ A, const void *__restrict__ B, const uint32_t *C,
-                            uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nblocks)
+                            uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t nblocks, uint32_t mark)
 {
     constexpr int VS = EKC + 2;               // row stride in doubles: rows spread over the banks, pairs stay 16-byte aligned
     __shared__ __attribute__((aligned(16))) double As[16][VS];
@@ -49,6 +53,7 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
         const uint64_t arow0 = t * m + 16u * bi, brow0 = t * n + 16u * bj;          // first row of the block in A and in B
         const uint64_t o = (arow0 + i) * (uint64_t)n + 16u * bj + j;
         uint32_t d = C[o];
+        bool marked = false;
         ExactPair sum;
         sum.start(0u);
         for (uint32_t k0 = 0; k0 < k; k0 += EKC) {
@@ -83,15 +88,41 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
                     uint32_t out;
                     if (!sum.finish(p, out)) {
                         // the sum left the pair's reach: the integer routine, from the operands in memory
-                        const uint32_t gk = k0 + g0 + glen - L;
-                        const uint8_t *ap = static_cast<const uint8_t *>(A) + ((arow0 + i) * (uint64_t)k + gk) * esa;
-                        const uint8_t *bp = static_cast<const uint8_t *>(B) + ((brow0 + j) * (uint64_t)k + gk) * esb;
-                        out = fdpa_group<true>(p, dyn_fmt(ta), dyn_fmt(tb), ap, bp, L, d, no_scales());
+                        if constexpr (MARK) {
+                            marked = true;                 // (in the second launch; what this chain gives from here on is not used)
+                            out = 0u;
+                        } else {
+                            const uint32_t gk = k0 + g0 + glen - L;
+                            const uint8_t *ap = static_cast<const uint8_t *>(A) + ((arow0 + i) * (uint64_t)k + gk) * esa;
+                            const uint8_t *bp = static_cast<const uint8_t *>(B) + ((brow0 + j) * (uint64_t)k + gk) * esb;
+                            out = fdpa_group<true>(p, dyn_fmt(ta), dyn_fmt(tb), ap, bp, L, d, no_scales());
+                        }
                     }
                     d = out;
                 }
             }
         }
+        D[o] = marked ? mark : d;
+    }
+}
+
+// The second launch: every output that carries the mark, from its accumulator in C, through the integer routine.
+__global__ void __launch_bounds__(256)
+emulate_efdpa_marked_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__restrict__ A, const void *__restrict__ B,
+                            const uint32_t *__restrict__ C, uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t total, uint32_t mark)
+{
+    const uint32_t esa = (ta <= MMAEMU_FP8_E5M2 || (ta >= MMAEMU_FP6_E2M3 && ta != MMAEMU_TF32)) ? 1u : (ta == MMAEMU_TF32 ? 4u : 2u);
+    const uint32_t esb = (tb <= MMAEMU_FP8_E5M2 || (tb >= MMAEMU_FP6_E2M3 && tb != MMAEMU_TF32)) ? 1u : (tb == MMAEMU_TF32 ? 4u : 2u);
+    const uint64_t mn = (uint64_t)m * n;
+    for (uint64_t o = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (uint64_t)gridDim.x * blockDim.x) {
+        if (D[o] != mark) continue;
+        const uint64_t t = o / mn;
+        const uint32_t r = (uint32_t)(o - t * mn), i = r / n, j = r - i * n;
+        const uint8_t *ap = static_cast<const uint8_t *>(A) + (t * m + i) * (uint64_t)k * esa;
+        const uint8_t *bp = static_cast<const uint8_t *>(B) + (t * n + j) * (uint64_t)k * esb;
+        uint32_t d = C[o];
+        for (uint32_t k0 = 0; k0 < k; k0 += p.L)
+            d = fdpa_group<true>(p, dyn_fmt(ta), dyn_fmt(tb), ap + (uint64_t)k0 * esa, bp + (uint64_t)k0 * esb, p.L, d, no_scales());
         D[o] = d;
     }
 }
@@ -102,7 +133,7 @@ bool efdpa_blocks_take(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m,
 {
     if (p.c_mode != MMAEMU_C_EXACT || (p.flags & (FL_ACC16 | FL_NAN_PROPAGATE))) return false;
     if (ta == MMAEMU_FP32 || tb == MMAEMU_FP32) return false;
-    if (m % 16 != 0 || n % 16 != 0 || p.L == 0 || k % p.L != 0) return false;
+    if (m % 16 != 0 || n % 16 != 0 || p.L == 0 || k == 0 || k % p.L != 0) return false;    // (k > 0: every output is a group's result, so none is the mark)
     return (p.L <= (uint32_t)EKC && EKC % p.L == 0) || p.L % EKC == 0;
 }
 
@@ -111,8 +142,24 @@ mmaemu_status launch_emulate_efdpa(const ModelArgs &p, const void *A, const void
 {
     const uint64_t nblocks = batch * (m / 16) * (n / 16);
     const uint64_t grid = nblocks < (1ull << 16) ? nblocks : (1ull << 16);
-    hipLaunchKernelGGL(emulate_efdpa_blocks_kernel, dim3((uint32_t)grid), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C, (uint32_t *)D,
-                       m, n, k, nblocks);
+    if (C == D) {
+        // in place: the accumulators are gone once the block kernel has run, so it finishes every output itself
+        hipLaunchKernelGGL(emulate_efdpa_blocks_kernel<false>, dim3((uint32_t)grid), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C,
+                           (uint32_t *)D, m, n, k, nblocks, 0u);
+        MMAEMU_HIP(hipGetLastError());
+        set_last_kernel("e-fdpa, 16x16 blocks through LDS, in place");
+        return MMAEMU_OK;
+    }
+    // a NaN pattern other than the model's: results are never NaN except as that one
+    const uint32_t mark = p.nan_bits == 0x7FEDCBA9u ? 0x7FEDCBA8u : 0x7FEDCBA9u;
+    hipLaunchKernelGGL(emulate_efdpa_blocks_kernel<true>, dim3((uint32_t)grid), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C,
+                       (uint32_t *)D, m, n, k, nblocks, mark);
+    MMAEMU_HIP(hipGetLastError());
+    const uint64_t total = batch * m * n;
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > (1ull << 20)) blocks = 1ull << 20;
+    hipLaunchKernelGGL(emulate_efdpa_marked_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C, (uint32_t *)D,
+                       m, n, k, total, mark);
     MMAEMU_HIP(hipGetLastError());
     set_last_kernel("e-fdpa, 16x16 blocks through LDS");
     return MMAEMU_OK;

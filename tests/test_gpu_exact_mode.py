@@ -138,6 +138,15 @@ def test_exact_mode_in_blocks_matches_the_rational_oracle(mm):
         via_general = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, tb)
         assert gpu_emulate.last_kernel == "general, exact sum"
         assert_same(got[:, :, :-1], via_general, "block kernel against the general kernel, " + name)
+        # in place the block kernel finishes every output itself; elsewhere it marks those it cannot finish for a second
+        # launch, with a NaN pattern that moves out of the way of the model's own
+        in_place = gpu_emulate(mm, p, A, B, C, ta, tb, in_place=True)
+        assert gpu_emulate.last_kernel == "e-fdpa, 16x16 blocks through LDS, in place", gpu_emulate.last_kernel
+        assert_same(in_place, got, "in place against out of place, " + name)
+        if "variant 0" in name:
+            q = dataclasses.replace(p, nan_bits=0x7FEDCBA9)
+            other = gpu_emulate(mm, q, A, B, C, ta, tb)
+            assert_same(other, np.where(got == p.nan_bits, np.uint32(q.nan_bits), got), "another NaN pattern, " + name)
         keep = slice(0, 1) if "variant 3" in name else slice(0, 2)           # (the oracle on one tile of the longest case)
         gpu.append(got[keep, ::3])
         jobs.append((dataclasses.asdict(p), A[keep, ::3], B[keep], C[keep, ::3], ta, tb, None, None, 0))

@@ -25,7 +25,7 @@ PAIRS = [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, f
          (fm.E4M3, fm.E4M3), (fm.E5M2, fm.E5M2), (fm.FP16, fm.BF16), (fm.E4M3, fm.FP16), (fm.BF16, fm.E5M2)]
 
 
-def gpu_emulate(mm, p, A, B, C, ta, tb, tc=fm.FP32):
+def gpu_emulate(mm, p, A, B, C, ta, tb, tc=fm.FP32, in_place=False):
     nb, m, k = A.shape
     n = B.shape[1]
     h = mm.model_create(group_len=p.group_len, frac_bits=p.frac_bits, frac_bits2=p.frac_bits2, c_mode=p.c_mode, out_round=p.out_round,
@@ -37,7 +37,7 @@ def gpu_emulate(mm, p, A, B, C, ta, tb, tc=fm.FP32):
                         wide_products=p.wide_products, nan_propagate=p.nan_propagate, rd_toward_zero=p.rd_toward_zero)
     try:
         dA, dB, dC = to_dev(A.astype(NP[ta])), to_dev(B.astype(NP[tb])), to_dev(C.astype(NP[tc]))
-        dD = dev_empty((nb, m, n), NP[tc])
+        dD = dC if in_place else dev_empty((nb, m, n), NP[tc])      # (D may be C itself)
         mm.emulate_mma(h, dA, dB, dC, dD, m, n, k, nb, (ta, tb, tc, tc))
         gpu_emulate.last_kernel = mm.last_kernel()
         return to_host(dD, NP[tc]).astype(np.uint32)
