@@ -1493,12 +1493,13 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
     if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
         return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
-    // Ragged m or n, more than one block each way: 32 x 32 blocks whose edge blocks repeat the last row and store only
-    // what lies inside (groups of 4 to 32 terms, which lie inside a staged chunk; not the block-scaled kernels).  Tiles
-    // of at most one block stay with the general kernel: padded to 32 x 32 they would mostly compute nothing.
+    // Ragged m or n: 32 x 32 blocks whose edge blocks repeat the last row and store only what lies inside (groups of 4
+    // to 32 terms, which lie inside a staged chunk; not the block-scaled kernels).  Tiles of 17 to 31 rows and columns
+    // fill at least 28 % of their one block, which still beats one thread per output several times over (20 x 20 tiles:
+    // x 5); narrower ones stay with the general kernel: padded to 32 x 32 they would mostly compute nothing.
     if constexpr (VM != 3) {
-        if (m > 32 && n > 32 && k % 32 == 0) return launch_L<32, 32, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled, true);
-        if (m > 32 && n > 32 && k % 8 == 0) return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled, true);
+        if (m > 16 && n > 16 && k % 32 == 0) return launch_L<32, 32, 2, 2, 32, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled, true);
+        if (m > 16 && n > 16 && k % 8 == 0) return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled, true);
     }
     return MMAEMU_OK;
 }

@@ -55,7 +55,8 @@ def check_sample_against_rational_form(rng, p, A, B, C, ta, tb, got, what, count
         assert got[t, i, j] == want, "%s: output %s: got %08x, the rational form gives %08x" % (what, (t, i, j), got[t, i, j], want)
 
 
-SHAPES = [(33, 47, 32, 2), (70, 100, 64, 1), (45, 33, 24, 3), (95, 129, 32, 1), (64, 40, 8, 2), (34, 64, 32, 1)]
+SHAPES = [(33, 47, 32, 2), (70, 100, 64, 1), (45, 33, 24, 3), (95, 129, 32, 1), (64, 40, 8, 2), (34, 64, 32, 1),
+          (20, 20, 16, 5), (32, 33, 32, 2), (17, 31, 8, 3), (33, 17, 64, 2)]       # (the last four: one block one way or both)
 
 
 @pytest.mark.parametrize("ta,tb", [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.E5M2, fm.FP16)])
@@ -108,10 +109,10 @@ def test_ragged_shapes_split_groups(mm):
                 assert kernel.startswith("tiled 32x32"), what
 
 
-def test_small_ragged_tiles_and_long_groups_keep_the_general_kernel(mm):
-    # at most one block each way, or groups that span several staged chunks
+def test_narrow_ragged_tiles_and_long_groups_keep_the_general_kernel(mm):
+    # at most 16 rows or columns (and no multiple of 16 both ways), or groups that span several staged chunks
     rng = np.random.default_rng(8901)
-    for (m, n, k, nb, L) in ((20, 20, 16, 3, 8), (32, 33, 32, 2, 8), (70, 100, 128, 1, 64), (70, 100, 64, 1, 0)):
+    for (m, n, k, nb, L) in ((12, 12, 16, 3, 8), (16, 33, 32, 2, 8), (40, 9, 32, 2, 8), (70, 100, 128, 1, 64), (70, 100, 64, 1, 0)):
         p = ModelParams(group_len=L, frac_bits=24)
         A, B, C = operands(rng, fm.FP16, fm.FP16, nb, m, n, k, "special")
         want, _ = o2lib.emulate_mma(p, A, B, C, fm.FP16, fm.FP16)
