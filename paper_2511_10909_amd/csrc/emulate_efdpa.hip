@@ -54,24 +54,27 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
         const uint64_t o = (arow0 + i) * (uint64_t)n + 16u * bj + j;
         uint32_t d = C[o];
         bool marked = false;
+        uint32_t into = 0;                                 // terms of the current group already added
         ExactPair sum;
         sum.start(0u);
         for (uint32_t k0 = 0; k0 < k; k0 += EKC) {
             const uint32_t kc = k - k0 < (uint32_t)EKC ? k - k0 : (uint32_t)EKC;
             __syncthreads();                               // (the previous chunk's readers)
-            for (uint32_t e = tid; e < 16u * kc; e += 256u) {
-                const uint32_t row = e / kc, kk = e - row * kc;
-                As[row][kk] = efdpa_value(ta, A, (arow0 + row) * (uint64_t)k + k0 + kk, p.ftz_in);
-                Bs[row][kk] = efdpa_value(tb, B, (brow0 + row) * (uint64_t)k + k0 + kk, p.ftz_in);
+            // (thread (i, j) stages columns j and j + 16 of row i of both operands)
+            for (uint32_t kk = j; kk < kc; kk += 16u) {
+                As[i][kk] = efdpa_value(ta, A, (arow0 + i) * (uint64_t)k + k0 + kk, p.ftz_in);
+                Bs[i][kk] = efdpa_value(tb, B, (brow0 + i) * (uint64_t)k + k0 + kk, p.ftz_in);
             }
             __syncthreads();
-            // the groups (or the part of a longer group) inside this chunk
-            for (uint32_t g0 = 0; g0 < kc; g0 += (L < kc ? L : kc)) {
-                const uint32_t glen = L < kc ? L : kc;
-                if ((k0 + g0) % L == 0) {
+            // the groups (or the part of a longer group) inside this chunk: a group of at most 32 terms starts and ends
+            // here (L divides 32, k0 and k, so it divides kc), a longer one is made of whole chunks
+            const uint32_t glen = L < kc ? L : kc;
+            for (uint32_t g0 = 0; g0 < kc; g0 += glen) {
+                if (into == 0) {
                     // a group starts: the accumulator (flushed if the model flushes inputs) is its first term
                     sum.start((p.ftz_in && (d & 0x7F800000u) == 0) ? 0u : d);
                 }
+                into += glen;
                 if (glen % 2 == 0) {
                     // (g0 is even then: pairs of k come with one 128-bit LDS read per row)
 #pragma unroll 2
@@ -83,8 +86,9 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
                 } else {
                     for (uint32_t kk = g0; kk < g0 + glen; ++kk) sum.add(As[i][kk], Bs[j][kk]);
                 }
-                if ((k0 + g0 + glen) % L == 0) {
+                if (into == L) {
                     // the group ends
+                    into = 0;
                     uint32_t out;
                     if (!sum.finish(p, out)) {
                         // the sum left the pair's reach: the integer routine, from the operands in memory
