@@ -109,6 +109,10 @@ mmaemu_status launch_scan(const MultiLaunch &ml, const void *A, const void *B, c
 bool efdpa_blocks_take(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m, uint32_t n, uint32_t k);
 mmaemu_status launch_emulate_efdpa(const ModelArgs &p, const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n,
                                    uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
+// the same model for any shape and FP32 operands too: one thread per output, the pair alone, then the marked outputs
+bool efdpa_pairs_take(const ModelArgs &p, const void *C, const void *D, uint32_t k);
+mmaemu_status launch_emulate_efdpa_pairs(const ModelArgs &p, const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n,
+                                         uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s);
 mmaemu_status launch_emulate_generic(const ModelArgs &p, const void *A, const void *B, const void *C, void *D,
                                      uint32_t m, uint32_t n, uint32_t k, uint64_t batch, uint32_t ta,
                                      uint32_t tb, hipStream_t s, const uint8_t *SA = nullptr, const uint8_t *SB = nullptr,

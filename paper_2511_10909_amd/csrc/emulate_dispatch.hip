@@ -65,6 +65,7 @@ mmaemu_status launch_emulate(const ModelArgs &p, const void *A, const void *B, c
     }
     // Algorithm "E-FDPA" on whole 16 x 16 blocks: operands shared through LDS, the exact sum held in a pair of binary64 numbers
     if (!scaled && efdpa_blocks_take(p, ta, tb, m, n, k)) return launch_emulate_efdpa(p, A, B, Cm, D, m, n, k, batch, ta, tb, s);
+    if (!scaled && efdpa_pairs_take(p, Cm, D, k)) return launch_emulate_efdpa_pairs(p, A, B, Cm, D, m, n, k, batch, ta, tb, s);
     return launch_emulate_generic(p, A, B, Cm, D, m, n, k, batch, ta, tb, s, SA, SB, scaled ? block : 1u);
 }
 

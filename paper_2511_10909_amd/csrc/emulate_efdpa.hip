@@ -7,6 +7,8 @@
 // 640-bit accumulator.  That routine costs the kernel which contains it 100 registers against 58, and with them half of
 // its waves, so where D is not C it sits in a kernel of its own: the block kernel leaves a mark in D (a NaN pattern that
 // no result has) at each output it could not finish, and a second launch runs those outputs' chains from C again.
+// Shapes that are not whole blocks, and FP32 operands, take the same two launches with one thread per output and the
+// operands read from memory.
 #include "emulate_tiled.hpp"
 #include "efdpa_pair.hpp"
 
@@ -26,9 +28,20 @@ __device__ __forceinline__ double efdpa_value(uint32_t t, const void *p, uint64_
     case MMAEMU_FP4_E2M1: decode_elem<MMAEMU_FP4_E2M1>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
     case MMAEMU_FP16: decode_elem<MMAEMU_FP16>(static_cast<const uint16_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
     case MMAEMU_TF32: decode_elem<MMAEMU_TF32>(static_cast<const uint32_t *>(p)[idx] >> 13, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP32: {
+        const uint32_t w = static_cast<const uint32_t *>(p)[idx];
+        v = __uint_as_float((ftz_in && (w & 0x7F800000u) == 0) ? 0u : w);
+        break;
+    }
     default: decode_elem<MMAEMU_BF16>(static_cast<const uint16_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
     }
     return (double)v;
+}
+
+// bytes per element as the arrays hold them
+__device__ __host__ __forceinline__ uint32_t efdpa_esize(uint32_t t)
+{
+    return (t == MMAEMU_FP32 || t == MMAEMU_TF32) ? 4u : ((t == MMAEMU_FP16 || t == MMAEMU_BF16) ? 2u : 1u);
 }
 
 constexpr int EKC = 32;                       // values of k staged at a time
@@ -44,8 +57,7 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
     __shared__ __attribute__((aligned(16))) double Bs[16][VS];
     const uint32_t tid = threadIdx.x, i = tid / 16u, j = tid % 16u;
     const uint32_t bpr = n / 16u, bpt = (m / 16u) * bpr;
-    const uint32_t esa = (ta <= MMAEMU_FP8_E5M2 || (ta >= MMAEMU_FP6_E2M3 && ta != MMAEMU_TF32)) ? 1u : (ta == MMAEMU_TF32 ? 4u : 2u);
-    const uint32_t esb = (tb <= MMAEMU_FP8_E5M2 || (tb >= MMAEMU_FP6_E2M3 && tb != MMAEMU_TF32)) ? 1u : (tb == MMAEMU_TF32 ? 4u : 2u);
+    const uint32_t esa = efdpa_esize(ta), esb = efdpa_esize(tb);
     const uint32_t L = p.L;
     for (uint64_t w = blockIdx.x; w < nblocks; w += gridDim.x) {
         const uint64_t t = w / bpt;
@@ -110,13 +122,36 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
     }
 }
 
+// Any shape, one thread per output: the pair alone, a mark where it does not hold a group's sum.
+__global__ void __launch_bounds__(256)
+emulate_efdpa_pairs_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__restrict__ A, const void *__restrict__ B,
+                           const uint32_t *__restrict__ C, uint32_t *__restrict__ D, uint32_t m, uint32_t n, uint32_t k, uint64_t total,
+                           uint32_t mark)
+{
+    const uint64_t mn = (uint64_t)m * n;
+    for (uint64_t o = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (uint64_t)gridDim.x * blockDim.x) {
+        // (a 64-bit division costs about as much as four terms: 32-bit arithmetic where the output index allows it)
+        const uint64_t t = (total >> 32) == 0 ? (uint64_t)((uint32_t)o / (uint32_t)mn) : o / mn;
+        const uint32_t r = (uint32_t)(o - t * mn), i = r / n, j = r - i * n;
+        const uint64_t a0 = (t * m + i) * (uint64_t)k, b0 = (t * n + j) * (uint64_t)k;
+        uint32_t d = C[o];
+        bool marked = false;
+        for (uint32_t k0 = 0; k0 < k && !marked; k0 += p.L) {
+            ExactPair sum;
+            sum.start((p.ftz_in && (d & 0x7F800000u) == 0) ? 0u : d);
+            for (uint32_t kk = k0; kk < k0 + p.L; ++kk) sum.add(efdpa_value(ta, A, a0 + kk, p.ftz_in), efdpa_value(tb, B, b0 + kk, p.ftz_in));
+            marked = !sum.finish(p, d);
+        }
+        D[o] = marked ? mark : d;
+    }
+}
+
 // The second launch: every output that carries the mark, from its accumulator in C, through the integer routine.
 __global__ void __launch_bounds__(256)
 emulate_efdpa_marked_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__restrict__ A, const void *__restrict__ B,
                             const uint32_t *__restrict__ C, uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t total, uint32_t mark)
 {
-    const uint32_t esa = (ta <= MMAEMU_FP8_E5M2 || (ta >= MMAEMU_FP6_E2M3 && ta != MMAEMU_TF32)) ? 1u : (ta == MMAEMU_TF32 ? 4u : 2u);
-    const uint32_t esb = (tb <= MMAEMU_FP8_E5M2 || (tb >= MMAEMU_FP6_E2M3 && tb != MMAEMU_TF32)) ? 1u : (tb == MMAEMU_TF32 ? 4u : 2u);
+    const uint32_t esa = efdpa_esize(ta), esb = efdpa_esize(tb);
     const uint64_t mn = (uint64_t)m * n;
     for (uint64_t o = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (uint64_t)gridDim.x * blockDim.x) {
         if (D[o] != mark) continue;
@@ -125,8 +160,13 @@ emulate_efdpa_marked_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
         const uint8_t *ap = static_cast<const uint8_t *>(A) + (t * m + i) * (uint64_t)k * esa;
         const uint8_t *bp = static_cast<const uint8_t *>(B) + (t * n + j) * (uint64_t)k * esb;
         uint32_t d = C[o];
-        for (uint32_t k0 = 0; k0 < k; k0 += p.L)
-            d = fdpa_group<true>(p, dyn_fmt(ta), dyn_fmt(tb), ap + (uint64_t)k0 * esa, bp + (uint64_t)k0 * esb, p.L, d, no_scales());
+        if (ta == MMAEMU_FP32) {           // (pairs with itself; the run-time format table has no 32-bit significands)
+            for (uint32_t k0 = 0; k0 < k; k0 += p.L)
+                d = fdpa_group<true>(p, StaticFmt<MMAEMU_FP32>{}, StaticFmt<MMAEMU_FP32>{}, ap + (uint64_t)k0 * 4u, bp + (uint64_t)k0 * 4u, p.L, d, no_scales());
+        } else {
+            for (uint32_t k0 = 0; k0 < k; k0 += p.L)
+                d = fdpa_group<true>(p, dyn_fmt(ta), dyn_fmt(tb), ap + (uint64_t)k0 * esa, bp + (uint64_t)k0 * esb, p.L, d, no_scales());
+        }
         D[o] = d;
     }
 }
@@ -139,6 +179,46 @@ bool efdpa_blocks_take(const ModelArgs &p, uint32_t ta, uint32_t tb, uint32_t m,
     if (ta == MMAEMU_FP32 || tb == MMAEMU_FP32) return false;
     if (m % 16 != 0 || n % 16 != 0 || p.L == 0 || k == 0 || k % p.L != 0) return false;    // (k > 0: every output is a group's result, so none is the mark)
     return (p.L <= (uint32_t)EKC && EKC % p.L == 0) || p.L % EKC == 0;
+}
+
+// Whether the pair of launches for any shape takes the problem: D apart from C (the second launch reads C), k > 0 (every
+// output is then a group's result, so none is the mark).
+bool efdpa_pairs_take(const ModelArgs &p, const void *C, const void *D, uint32_t k)
+{
+    return p.c_mode == MMAEMU_C_EXACT && !(p.flags & (FL_ACC16 | FL_NAN_PROPAGATE)) && C != D && p.L != 0 && k != 0 && k % p.L == 0;
+}
+
+static uint32_t efdpa_mark(const ModelArgs &p)
+{
+    // a NaN pattern other than the model's: results are never NaN except as that one
+    return p.nan_bits == 0x7FEDCBA9u ? 0x7FEDCBA8u : 0x7FEDCBA9u;
+}
+
+static mmaemu_status launch_marked(const ModelArgs &p, const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n, uint32_t k,
+                                   uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s)
+{
+    const uint64_t total = batch * m * n;
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > (1ull << 20)) blocks = 1ull << 20;
+    hipLaunchKernelGGL(emulate_efdpa_marked_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C, (uint32_t *)D,
+                       m, n, k, total, efdpa_mark(p));
+    MMAEMU_HIP(hipGetLastError());
+    return MMAEMU_OK;
+}
+
+mmaemu_status launch_emulate_efdpa_pairs(const ModelArgs &p, const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n,
+                                         uint32_t k, uint64_t batch, uint32_t ta, uint32_t tb, hipStream_t s)
+{
+    const uint64_t total = batch * m * n;
+    uint64_t blocks = (total + 255) / 256;
+    if (blocks > (1ull << 20)) blocks = 1ull << 20;
+    hipLaunchKernelGGL(emulate_efdpa_pairs_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C, (uint32_t *)D,
+                       m, n, k, total, efdpa_mark(p));
+    MMAEMU_HIP(hipGetLastError());
+    const mmaemu_status st = launch_marked(p, A, B, C, D, m, n, k, batch, ta, tb, s);
+    if (st != MMAEMU_OK) return st;
+    set_last_kernel("e-fdpa, one thread per output");
+    return MMAEMU_OK;
 }
 
 mmaemu_status launch_emulate_efdpa(const ModelArgs &p, const void *A, const void *B, const void *C, void *D, uint32_t m, uint32_t n,
@@ -154,17 +234,11 @@ mmaemu_status launch_emulate_efdpa(const ModelArgs &p, const void *A, const void
         set_last_kernel("e-fdpa, 16x16 blocks through LDS, in place");
         return MMAEMU_OK;
     }
-    // a NaN pattern other than the model's: results are never NaN except as that one
-    const uint32_t mark = p.nan_bits == 0x7FEDCBA9u ? 0x7FEDCBA8u : 0x7FEDCBA9u;
     hipLaunchKernelGGL(emulate_efdpa_blocks_kernel<true>, dim3((uint32_t)grid), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C,
-                       (uint32_t *)D, m, n, k, nblocks, mark);
+                       (uint32_t *)D, m, n, k, nblocks, efdpa_mark(p));
     MMAEMU_HIP(hipGetLastError());
-    const uint64_t total = batch * m * n;
-    uint64_t blocks = (total + 255) / 256;
-    if (blocks > (1ull << 20)) blocks = 1ull << 20;
-    hipLaunchKernelGGL(emulate_efdpa_marked_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, p, ta, tb, A, B, (const uint32_t *)C, (uint32_t *)D,
-                       m, n, k, total, mark);
-    MMAEMU_HIP(hipGetLastError());
+    const mmaemu_status st = launch_marked(p, A, B, C, D, m, n, k, batch, ta, tb, s);
+    if (st != MMAEMU_OK) return st;
     set_last_kernel("e-fdpa, 16x16 blocks through LDS");
     return MMAEMU_OK;
 }

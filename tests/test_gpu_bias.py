@@ -32,9 +32,9 @@ def same_hist(got, want, what):
 
 def test_truncating_variant_matches_the_rational_oracle(mm):
     rng = np.random.default_rng(777)
-    cases = [("unsplit fp16, ragged (general)", TRZ, fm.FP16, (3, 20, 20, 16), "general"),
-             ("unsplit bf16, ragged (general)", TRZ.with_(frac_bits=20, frac_bits2=27, out_round=1), fm.BF16, (3, 20, 20, 16), "general"),
-             ("even/odd fp8 (general)", TRZ.with_(c_mode=C_AFTER_RD_EVEN_ODD, group_len=16), fm.E5M2, (3, 20, 20, 32), "general"),
+    cases = [("unsplit fp16, ragged (general)", TRZ, fm.FP16, (5, 12, 20, 16), "general"),
+             ("unsplit bf16, ragged (general)", TRZ.with_(frac_bits=20, frac_bits2=27, out_round=1), fm.BF16, (5, 12, 20, 16), "general"),
+             ("even/odd fp8 (general)", TRZ.with_(c_mode=C_AFTER_RD_EVEN_ODD, group_len=16), fm.E5M2, (5, 12, 20, 32), "general"),
              ("halves, F_m = 20 (general)", TRZ.with_(split=SPLIT_HALVES, frac_bits_merge=20, group_len=8), fm.FP16, (4, 16, 16, 16), "general"),
              ("quarters (general)", TRZ.with_(split=SPLIT_QUARTERS, frac_bits=13, group_len=16), fm.E4M3, (4, 16, 16, 32), "general"),
              ("leading-bit F2 rule, zero terms skipped (general)", TRZ.with_(f2_at_leading_bit=True, skip_zero_terms=True, zero_result_positive=True), fm.BF16, (4, 16, 16, 16), "general"),

@@ -43,7 +43,11 @@ def test_exact_mode_matches_the_rational_oracle(mm):
                 A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[ta], 0.02)
                 C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32], 0.03)
             got = gpu_emulate(mm, p, A, B, C, ta, tb)
+            assert gpu_emulate.last_kernel == "e-fdpa, one thread per output", gpu_emulate.last_kernel
+            # in place the accumulators do not outlive the first launch: the general kernel, which finishes every output itself
+            in_place = gpu_emulate(mm, p, A, B, C, ta, tb, in_place=True)
             assert gpu_emulate.last_kernel == "general, exact sum", gpu_emulate.last_kernel
+            assert_same(in_place, got, "in place against out of place, types %d x %d, variant %d" % (ta, tb, variant))
             gpu.append(got)
             jobs.append((dataclasses.asdict(p), A, B, C, ta, tb, None, None, 0))
             names.append("types %d x %d, variant %d" % (ta, tb, variant))
@@ -134,8 +138,8 @@ def test_exact_mode_in_blocks_matches_the_rational_oracle(mm):
     for name, p, A, B, C, ta, tb in _exact_cases(rng):
         got = gpu_emulate(mm, p, A, B, C, ta, tb)
         assert gpu_emulate.last_kernel == "e-fdpa, 16x16 blocks through LDS", gpu_emulate.last_kernel
-        # the same problem without B's last row runs in the general kernel (n = 15): the two routes agree
-        via_general = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, tb)
+        # the same problem without B's last row (n = 15), in place, runs in the general kernel: the two routes agree
+        via_general = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, tb, in_place=True)
         assert gpu_emulate.last_kernel == "general, exact sum"
         assert_same(got[:, :, :-1], via_general, "block kernel against the general kernel, " + name)
         # in place the block kernel finishes every output itself; elsewhere it marks those it cannot finish for a second
@@ -173,6 +177,9 @@ def test_exact_mode_blocks_on_ordinary_data_at_size(mm):
             p = ModelParams(group_len=L, c_mode=C_EXACT, out_round=rho)
             got = gpu_emulate(mm, p, A, B, C, ta, ta)
             assert gpu_emulate.last_kernel == "e-fdpa, 16x16 blocks through LDS"
-            ref = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, ta)
+            ref = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, ta, in_place=True)
             assert gpu_emulate.last_kernel == "general, exact sum"
+            one = gpu_emulate(mm, p, A, B[:, :-1], C[:, :, :-1], ta, ta)
+            assert gpu_emulate.last_kernel == "e-fdpa, one thread per output"
+            assert_same(one, ref, "one thread per output, types %d L %d rho %d" % (ta, L, rho))
             assert_same(got[:, :, :-1], ref, "types %d L %d rho %d" % (ta, L, rho))

@@ -85,7 +85,7 @@ def _inputs(rng, ta, tb, nb, m, n, k, idx):
 
 
 def _group_shape(kw, idx):
-    """Group length and k that every mode of the case accepts; shapes with odd m and n (no tiled kernel takes those)."""
+    """Group length and k that every mode of the case accepts; tiles of 15 x 27 (no tiled kernel takes tiles of fewer than 16 rows)."""
     L = [8, 16, 4, 32][idx % 4]
     if kw.get("split") == SPLIT_QUARTERS:
         L = max(L, 16) if idx % 2 else 32
@@ -101,9 +101,9 @@ def results(mm):
     for idx, (name, kw) in enumerate(CASES):
         L, k = _group_shape(kw, idx)
         p = ModelParams(group_len=L, **kw)
-        # not block-scaled: 3 tiles of 19 x 21 (1197 outputs)
+        # not block-scaled: 3 tiles of 15 x 27 (1215 outputs)
         ta, tb = PAIRS[idx % len(PAIRS)]
-        A, B, C = _inputs(rng, ta, tb, 3, 19, 21, k, idx)
+        A, B, C = _inputs(rng, ta, tb, 3, 15, 27, k, idx)
         got = gpu_emulate(mm, p, A, B, C, ta, tb)
         assert gpu_emulate.last_kernel == "general", (name, gpu_emulate.last_kernel)
         gpu.append(got)
@@ -114,10 +114,10 @@ def results(mm):
         block = 8 if idx % 2 else 32
         ks = max(k, block)
         ks += (-ks) % L
-        A, B, C = _inputs(rng, ta, tb, 3, 19, 21, ks, idx + 1)
+        A, B, C = _inputs(rng, ta, tb, 3, 15, 27, ks, idx + 1)
         lo, hi = [(100, 150), (40, 215)][idx % 2]
-        SA = rng.integers(lo, hi, size=(3, 19, ks // block)).astype(np.uint8)
-        SB = rng.integers(lo, hi, size=(3, 21, ks // block)).astype(np.uint8)
+        SA = rng.integers(lo, hi, size=(3, 15, ks // block)).astype(np.uint8)
+        SB = rng.integers(lo, hi, size=(3, 27, ks // block)).astype(np.uint8)
         if idx % 5 == 0:
             SA[0, 0, 0] = 0xFF          # a NaN scale
         got = gpu_emulate_scaled(mm, p, A, B, C, SA, SB, block, ta, tb)
@@ -128,7 +128,7 @@ def results(mm):
         # operands held in 32-bit words (TF32: 10 mantissa bits count; FP32: whole 48-bit products), for some of the cases
         if idx in WORD_CASES:
             for tw in (fm.TF32, fm.FP32):
-                A, B, C = _inputs(rng, tw, tw, 3, 19, 21, k, idx + 2)
+                A, B, C = _inputs(rng, tw, tw, 3, 15, 27, k, idx + 2)
                 if idx % 2:         # exponents close together: alignment matters
                     A = synth.narrow_exponent_bits(rng, A.shape, tw, 118, 136)
                     B = synth.narrow_exponent_bits(rng, B.shape, tw, 118, 136)
