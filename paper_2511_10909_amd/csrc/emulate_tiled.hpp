@@ -1493,6 +1493,15 @@ mmaemu_status launch_tiled_shape(const TiledArgs &ta, const void *A, const void 
     if (m % 32 == 0 && n % 32 == 0 && k % 8 == 0)
         return launch_L<32, 32, 4, 2, 8, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
     if (m % 16 == 0 && n % 16 == 0 && k % 16 == 0) return launch_L<16, 16, 2, 2, 16, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s, handled);
+    // The shapes of the four-product instructions (32x32x4 and 16x16x4 per block, k = 4 or an odd multiple of it, groups
+    // of four): one quad of k per row and pass.
+    if constexpr ((CMODE == MMAEMU_C_IN_GROUP || CMODE == MMAEMU_C_AFTER_RD) && (VM == 0 || VM == 1)) {
+        if (k % 4 == 0 && ta.p.L == 4 && ((m == 32 && n == 32) || (m == 16 && n == 16))) {
+            handled = true;
+            if (m == 32) return launch_fold<32, 32, 4, 2, 4, 4, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+            return launch_fold<16, 16, 2, 2, 4, 4, CMODE, VM>(ta, A, B, Cm, D, m, n, k, batch, s);
+        }
+    }
     // Ragged m or n: 32 x 32 blocks whose edge blocks repeat the last row and store only what lies inside (groups of 4
     // to 32 terms, which lie inside a staged chunk; not the block-scaled kernels).  Tiles of 17 to 31 rows and columns
     // fill at least 28 % of their one block, which still beats one thread per output several times over (20 x 20 tiles:

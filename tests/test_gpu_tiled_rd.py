@@ -214,3 +214,36 @@ def test_tiled_rd_products_around_the_overflow_threshold(mm, ta, tb):
             assert_same(got, want, "overflow threshold %d %s" % (trial, p))
         special = ((want & 0x7F800000) == 0x7F800000).mean()
         assert 0.002 < special < 0.98, special              # both kinds of outputs occur
+
+
+@pytest.mark.parametrize("ta,tb", [(fm.FP16, fm.FP16), (fm.BF16, fm.BF16), (fm.E4M3, fm.E5M2), (fm.FP16, fm.BF16)])
+def test_four_product_shapes(mm, ta, tb):
+    """32x32x4 and 16x16x4 tiles (the blocks of the four-product instructions) and odd multiples of four products, groups
+    of four: the tiled kernels stage one quad of k per row; both the fused and the round-down modes."""
+    from oracle.fdpa import C_IN_GROUP
+    from oracle.fdpa import emulate_mma as o1_emulate
+    rng = np.random.default_rng(5200 + 8 * ta + tb)
+    tiled = cases = 0
+    for (m, n, k, nb) in ((32, 32, 4, 7), (16, 16, 4, 21), (16, 16, 12, 5), (32, 32, 20, 3)):
+        for mode in ("narrow", "full", "special"):
+            for cm in (C_IN_GROUP, C_AFTER_RD):
+                if cm == C_AFTER_RD:
+                    p = random_rd_params(rng, k).with_(group_len=4)
+                else:
+                    p = ModelParams(group_len=4, frac_bits=int(rng.choice([3, 13, 24, 25, 27, 28])), c_mode=cm, out_round=int(rng.integers(0, 2)),
+                                    ftz_in=bool(rng.integers(0, 4) == 0), ftz_out=bool(rng.integers(0, 4) == 0))
+                A, B, C = operands(rng, ta, tb, nb, m, n, k, mode)
+                print("four products", ta, tb, (m, n, k, nb), mode, p, flush=True)
+                want, _ = o2lib.emulate_mma(p, A, B, C, ta, tb)
+                got = gpu_emulate(mm, p, A, B, C, ta, tb)
+                what = "four products %s %s %s %s" % ((m, n, k, nb), mode, p, gpu_emulate.last_kernel)
+                assert_same(got, want, what)
+                cases += 1
+                tiled += "kc=4" in gpu_emulate.last_kernel
+                if cm == C_IN_GROUP:
+                    assert "kc=4 L=4" in gpu_emulate.last_kernel, what
+                # a few outputs against the rational form
+                for (t, i, j) in [(nb - 1, m - 1, n - 1)] + [(int(rng.integers(nb)), int(rng.integers(m)), int(rng.integers(n))) for _ in range(3)]:
+                    one = o1_emulate(p, A[t:t + 1, i:i + 1, :], B[t:t + 1, j:j + 1, :], C[t:t + 1, i:i + 1, j:j + 1], ta, tb)[0, 0, 0]
+                    assert got[t, i, j] == one, "%s: output %s: got %08x, the rational form gives %08x" % (what, (t, i, j), got[t, i, j], one)
+    assert tiled >= 0.7 * cases, (tiled, cases)          # (some of the random round-down variations run in the general kernel)
