@@ -119,3 +119,26 @@ def test_narrow_ragged_tiles_and_long_groups_keep_the_general_kernel(mm):
         got, kernel = emulate_guarded(mm, p, A, B, C, fm.FP16, fm.FP16)
         assert_same(got, want, "general %s" % ((m, n, k, nb, L),))
         assert kernel == "general", kernel
+
+
+def test_ragged_shapes_tf32(mm):
+    # operands in 32-bit words (four to a 128-bit load): edge blocks of one block and of several, three modes
+    from test_gpu_tf32 import tf32_case
+    rng = np.random.default_rng(8902)
+    trial = 0
+    for (m, n, k, nb) in ((20, 20, 16, 5), (33, 47, 32, 2), (17, 31, 8, 3), (70, 41, 64, 1)):
+        for cm in (C_IN_GROUP, C_AFTER_EXACT, C_AFTER_RD):
+            trial += 1
+            L = int(rng.choice([L for L in (4, 8, 16, 32) if k % L == 0 and (k % 32 == 0 or L <= 8)]))
+            p = ModelParams(group_len=L, frac_bits=int(rng.choice([13, 24, 25, 27])), c_mode=cm, out_round=int(rng.integers(0, 2)),
+                            ftz_in=bool(rng.integers(0, 4) == 0), ftz_out=bool(rng.integers(0, 4) == 0))
+            if cm == C_AFTER_RD:
+                p = p.with_(frac_bits2=31)
+            A, B, C = tf32_case(rng, nb, m, n, k, trial)
+            print("ragged tf32", (m, n, k, nb), p, flush=True)
+            want, _ = o2lib.emulate_mma(p, A, B, C, fm.TF32, fm.TF32)
+            got, kernel = emulate_guarded(mm, p, A, B, C, fm.TF32, fm.TF32)
+            what = "ragged tf32 %s %s %s" % ((m, n, k, nb), p, kernel)
+            assert_same(got, want, what)
+            assert kernel.startswith("tiled 32x32") and "vm=4" in kernel, what
+            check_sample_against_rational_form(rng, p, A, B, C, fm.TF32, fm.TF32, got, what, count=4)
