@@ -1,11 +1,13 @@
 // Distribution of the deviation delta = D - D_real of a model's (or an instruction's) outputs from the real result
 // (Sec. 6.2.4: the bias of the round-down modes shows as a distribution of delta shifted toward the negative side,
 // against a symmetric one for the variant that truncates toward zero).  D_real = c + sum_k a_k b_k is taken exactly:
-// per sampled output one thread adds D and subtracts every product and the accumulator in a wide fixed-point number,
-// so delta itself is exact; only its binary64 image (for the three sums) is rounded.  Linear bins of width 2^bin_exp
+// per sampled output one thread adds D and subtracts every product and the accumulator, in an unevaluated pair of
+// binary64 numbers while that is exact and in a wide fixed-point number otherwise, so delta itself is exact; only its
+// binary64 image (for the three sums) is rounded.  Linear bins of width 2^bin_exp
 // around zero: bin i holds delta in [(i - 32) w, (i - 31) w), the outermost bins everything beyond.
 #include "common.hpp"
 #include "fdpa_int.hpp"
+#include "efdpa_pair.hpp"
 
 namespace mmaemu {
 
@@ -16,6 +18,66 @@ __global__ void deviation_reset_kernel(mmaemu_deviation_hist *h)
 {
     uint64_t *w = reinterpret_cast<uint64_t *>(h);
     if (threadIdx.x < DEV_WORDS) w[threadIdx.x] = 0ull;             // +0.0 is all-zero bits
+}
+
+// The same through the wide fixed-point number (exact for any finite operands): sign, whether delta is zero,
+// floor(delta / 2^bin_exp) clamped to +-NB, and |delta|'s binary64 image (its 64 bits from the leading one downward,
+// converted once).
+__device__ __noinline__ void delta_wide(DynFmt fa, DynFmt fb, const uint8_t *a, const uint8_t *b, uint32_t k, uint32_t cb, uint32_t db,
+                                        int unit_bit, uint32_t &neg, bool &zero, int &fi, double &ad)
+{
+    constexpr int NB = MMAEMU_DEVIATION_BINS;
+    uint32_t w[XL];
+    for (int q = 0; q < XL; ++q) w[q] = 0u;
+    for (uint32_t kk = 0; kk < k; ++kk) {
+        const Dec x = decode_as(fa, fa.load(a, kk), 0u), y = decode_as(fb, fb.load(b, kk), 0u);
+        wide_add(w, sig_product(fa, fb, x, y), x.exp + y.exp - fa.mb() - fb.mb(), (x.sign ^ y.sign) ^ 1u);   // - a b
+    }
+    {
+        const uint32_t Ec = (cb >> 23) & 0xFFu, Ed = (db >> 23) & 0xFFu;
+        wide_add(w, (cb & 0x7FFFFFu) | (Ec ? 0x800000u : 0u), (int)(Ec ? Ec : 1u) - 150, (cb >> 31) ^ 1u);        // - c
+        wide_add(w, (db & 0x7FFFFFu) | (Ed ? 0x800000u : 0u), (int)(Ed ? Ed : 1u) - 150, db >> 31);               // + D
+    }
+    neg = w[XL - 1] >> 31;
+    if (neg) {
+        uint32_t carry = 1;
+        for (int q = 0; q < XL; ++q) {
+            const uint64_t t = (uint64_t)(~w[q]) + carry;
+            w[q] = (uint32_t)t;
+            carry = (uint32_t)(t >> 32);
+        }
+    }
+    int top = XL - 1;
+    while (top >= 0 && w[top] == 0u) --top;
+    zero = top < 0;
+    fi = 0;
+    ad = 0.0;
+    if (zero) return;
+    const int hi_bit = 32 * top + (31 - __builtin_clz(w[top]));
+    // floor(delta / 2^bin_exp) from the magnitude: its bits from unit_bit upward, and whether anything lies below
+    if (hi_bit < unit_bit) fi = neg ? -1 : 0;
+    else if (hi_bit - unit_bit >= 6) fi = neg ? -NB : NB;
+    else {
+        const int limb = unit_bit >> 5, off = unit_bit & 31;
+        uint32_t v = w[limb] >> off;
+        if (off && limb + 1 < XL) v |= w[limb + 1] << (32 - off);
+        const int q = (int)(v & 63u);
+        bool below = (off != 0) && (w[limb] & ((1u << off) - 1u)) != 0u;
+        for (int t = 0; t < limb; ++t) below |= w[t] != 0u;
+        fi = neg ? (below ? -q - 1 : -q) : q;
+    }
+    const int low_bit = hi_bit - 63;
+    uint64_t mag;
+    int lsb;
+    if (low_bit <= 0) { mag = ((uint64_t)w[1] << 32) | w[0]; lsb = XBASE; }
+    else {
+        const int l0 = low_bit >> 5, sh = low_bit & 31;
+        const uint32_t a0 = w[l0], a1 = w[l0 + 1], a2 = (l0 + 2 < XL) ? w[l0 + 2] : 0u;
+        const u128 win = ((u128)a2 << 64) | ((u128)a1 << 32) | a0;
+        mag = (uint64_t)(win >> sh);
+        lsb = XBASE + low_bit;
+    }
+    ad = ldexp((double)mag, lsb);
 }
 
 __global__ void __launch_bounds__(256)
@@ -39,70 +101,53 @@ deviation_kernel(const void *__restrict__ A, const void *__restrict__ B, const u
         const uint32_t rem = (uint32_t)(o - tile * per_tile), i = rem / n, j = rem - i * n;
         const uint8_t *a = static_cast<const uint8_t *>(A) + (tile * m + i) * (uint64_t)k * esa;
         const uint8_t *b = static_cast<const uint8_t *>(B) + (tile * n + j) * (uint64_t)k * esb;
-        uint32_t w[XL];
-        for (int q = 0; q < XL; ++q) w[q] = 0u;
-        bool bad = false;
+        // delta first as an unevaluated pair of binary64 numbers (efdpa_pair.hpp): D, then every product and the accumulator
+        // taken away; while the pair holds the sum exactly (always for FP16 / FP8 operands; BF16 or FP32 operands spread
+        // over hundreds of binary places may leave it) sign, bin and binary64 image follow from the normalised pair
+        const uint32_t cb = C ? C[o] : 0u, db = D[o];
+        bool bad = (cb & 0x7F800000u) == 0x7F800000u || (db & 0x7F800000u) == 0x7F800000u;
+        ExactPair pr;
+        pr.start(db);
         for (uint32_t kk = 0; kk < k; ++kk) {
             const Dec x = decode_as(fa, fa.load(a, kk), 0u), y = decode_as(fb, fb.load(b, kk), 0u);
             bad |= x.cls == CLS_INF || x.cls == CLS_NAN || y.cls == CLS_INF || y.cls == CLS_NAN;
-            wide_add(w, sig_product(fa, fb, x, y), x.exp + y.exp - fa.mb() - fb.mb(), (x.sign ^ y.sign) ^ 1u);   // - a b
+            pr.add(-dec_value(fa, x), dec_value(fb, y));
         }
-        const uint32_t cb = C ? C[o] : 0u, db = D[o];
-        bad |= (cb & 0x7F800000u) == 0x7F800000u || (db & 0x7F800000u) == 0x7F800000u;
         if (bad) { atomicAdd(&counts[1], 1u); continue; }
-        {
-            const uint32_t Ec = (cb >> 23) & 0xFFu, Ed = (db >> 23) & 0xFFu;
-            wide_add(w, (cb & 0x7FFFFFu) | (Ec ? 0x800000u : 0u), (int)(Ec ? Ec : 1u) - 150, (cb >> 31) ^ 1u);        // - c
-            wide_add(w, (db & 0x7FFFFFu) | (Ed ? 0x800000u : 0u), (int)(Ed ? Ed : 1u) - 150, db >> 31);               // + D
-        }
-        const uint32_t neg = w[XL - 1] >> 31;
-        if (neg) {
-            uint32_t carry = 1;
-            for (int q = 0; q < XL; ++q) {
-                const uint64_t t = (uint64_t)(~w[q]) + carry;
-                w[q] = (uint32_t)t;
-                carry = (uint32_t)(t >> 32);
+        pr.add(-(double)__uint_as_float(cb), 1.0);
+        uint32_t neg;
+        bool zero;
+        int fi;
+        double ad;
+        if (pr.lost == 0.0) {
+            double h, l;
+            two_sum(pr.hi, pr.lo, h, l);                                 // h = RN(delta), l = delta - h
+            neg = h < 0.0;
+            zero = h == 0.0;
+            ad = __builtin_fabs(h);
+            // floor(delta / 2^bin_exp): of h, and one less where h is a whole number of bins and l lies below it (a
+            // fractional h / w keeps at least one of its own last places to either side, more than |l / w|)
+            const double qh = ldexp(h, -bin_exp);
+            if (qh >= (double)NB) fi = NB;
+            else if (qh <= -(double)NB) fi = -NB;
+            else if (qh == 0.0) fi = neg ? -1 : 0;                       // (h / w below the binary64 range)
+            else {
+                const double fl = __builtin_floor(qh);
+                fi = (int)fl - ((fl == qh && l < 0.0) ? 1 : 0);
             }
+        } else {
+            delta_wide(fa, fb, a, b, k, cb, db, unit_bit, neg, zero, fi, ad);
         }
-        int top = XL - 1;
-        while (top >= 0 && w[top] == 0u) --top;
         atomicAdd(&counts[0], 1u);
-        if (top < 0) {                                               // delta = 0
+        if (zero) {
             atomicAdd(&counts[3], 1u);
             atomicAdd(&counts[5 + NB / 2], 1u);
             continue;
         }
         atomicAdd(&counts[neg ? 2 : 4], 1u);
-        const int hi_bit = 32 * top + (31 - __builtin_clz(w[top]));
-        // floor(delta / 2^bin_exp) from the magnitude: its bits from unit_bit upward, and whether anything lies below
-        int fi;
-        if (hi_bit < unit_bit) fi = neg ? -1 : 0;
-        else if (hi_bit - unit_bit >= 6) fi = neg ? -NB : NB;
-        else {
-            const int limb = unit_bit >> 5, off = unit_bit & 31;
-            uint32_t v = w[limb] >> off;
-            if (off && limb + 1 < XL) v |= w[limb + 1] << (32 - off);
-            const int q = (int)(v & 63u);
-            bool below = (off != 0) && (w[limb] & ((1u << off) - 1u)) != 0u;
-            for (int t = 0; t < limb; ++t) below |= w[t] != 0u;
-            fi = neg ? (below ? -q - 1 : -q) : q;
-        }
         int bin = fi + NB / 2;
         bin = bin < 0 ? 0 : (bin > NB - 1 ? NB - 1 : bin);
         atomicAdd(&counts[5 + bin], 1u);
-        // binary64 image of delta: the 64 bits from the leading one downward, converted once
-        const int low_bit = hi_bit - 63;
-        uint64_t mag;
-        int lsb;
-        if (low_bit <= 0) { mag = ((uint64_t)w[1] << 32) | w[0]; lsb = XBASE; }
-        else {
-            const int l0 = low_bit >> 5, sh = low_bit & 31;
-            const uint32_t a0 = w[l0], a1 = w[l0 + 1], a2 = (l0 + 2 < XL) ? w[l0 + 2] : 0u;
-            const u128 win = ((u128)a2 << 64) | ((u128)a1 << 32) | a0;
-            mag = (uint64_t)(win >> sh);
-            lsb = XBASE + low_bit;
-        }
-        const double ad = ldexp((double)mag, lsb);
         sum += neg ? -ad : ad;
         sum_abs += ad;
         sum_sq += ad * ad;

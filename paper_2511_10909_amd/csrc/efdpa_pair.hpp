@@ -8,8 +8,18 @@
 // for a NaN, for infinity times zero and for infinities of both signs, and the infinity otherwise (Sec. 4.2's rule).
 #pragma once
 #include "common.hpp"
+#include "fdpa_int.hpp"
 
 namespace mmaemu {
+
+// a decoded element as the binary64 number it denotes (at most 24 significant bits: exact)
+template <class FT>
+__device__ __forceinline__ double dec_value(const FT &f, const Dec &x)
+{
+    if (x.cls == CLS_NAN) return __longlong_as_double(0x7FF8000000000000ll);
+    const double mag = x.cls == CLS_INF ? __longlong_as_double(0x7FF0000000000000ll) : ldexp((double)x.sig, x.exp - f.mb());
+    return x.sign ? -mag : mag;
+}
 
 // s + e = a + b exactly (s = RN(a + b)), for finite operands
 __device__ __forceinline__ void two_sum(double a, double b, double &s, double &e)

@@ -13,15 +13,6 @@
 
 namespace mmaemu {
 
-// a decoded element as the binary64 number it denotes (at most 24 significant bits: exact)
-template <class FT>
-__device__ __forceinline__ double dec_value(const FT &f, const Dec &x)
-{
-    if (x.cls == CLS_NAN) return __longlong_as_double(0x7FF8000000000000ll);
-    const double mag = x.cls == CLS_INF ? __longlong_as_double(0x7FF0000000000000ll) : ldexp((double)x.sig, x.exp - f.mb());
-    return x.sign ? -mag : mag;
-}
-
 // EXACT: Algorithm "E-FDPA" (its 640-bit accumulator sits in private memory, so it gets instantiations of its own and the
 // other modes stay free of scratch memory)
 template <int TA, int TB, bool EXACT>
