@@ -107,16 +107,20 @@ def test_deviation_sample_matches_oracle(mm):
     for idx, (ta, tb, shape, stride, bin_exp, with_c) in enumerate((
             (fm.FP16, fm.FP16, (5, 32, 32, 8), 1, -5, True), (fm.BF16, fm.BF16, (7, 16, 16, 16), 7, -12, False),
             (fm.E4M3, fm.E5M2, (3, 16, 16, 32), 3, -9, True), (fm.FP16, fm.BF16, (2, 9, 13, 5), 1, 2, True),
-            (fm.E2M3, fm.E2M1, (4, 16, 16, 64), 5, -6, True))):
+            (fm.E2M3, fm.E2M1, (4, 16, 16, 64), 5, -6, True), (fm.BF16, fm.BF16, (3, 16, 16, 8), 1, 0, True))):
         nb, m, n, k = shape
         lo_hi = {fm.FP16: (10, 24), fm.BF16: (118, 132), fm.E4M3: (3, 12), fm.E5M2: (10, 20), fm.E2M3: (0, 3), fm.E2M1: (0, 3)}
         A = synth.narrow_exponent_bits(rng, (nb, m, k), ta, *lo_hi[ta])
         B = synth.narrow_exponent_bits(rng, (nb, n, k), tb, *lo_hi[tb])
         C = synth.narrow_exponent_bits(rng, (nb, m, n), fm.FP32, 118, 132) if with_c else None
+        if idx == 5:         # whole exponent range: many sums leave the pair of binary64 numbers for the wide accumulator
+            A = synth.random_bits(rng, (nb, m, k), ta)
+            B = synth.random_bits(rng, (nb, n, k), tb)
+            C = synth.random_bits(rng, (nb, m, n), fm.FP32)
         if idx == 0:
             A = synth.sprinkle(rng, A, synth.SPECIAL_CODES[ta], 0.003)
             C = synth.sprinkle(rng, C, synth.SPECIAL_CODES[fm.FP32], 0.01)
-        p = ModelParams(group_len=k, frac_bits=[24, 10, 13, 6, 30][idx], frac_bits2=31, c_mode=C_AFTER_RD)
+        p = ModelParams(group_len=k, frac_bits=[24, 10, 13, 6, 30, 24][idx], frac_bits2=31, c_mode=C_AFTER_RD)
         D = o2lib.emulate_mma(p, A, B, C if with_c else np.zeros((nb, m, n), np.uint32), ta, tb)[0]
         if idx == 1:
             D[0, 0, :4] = [0x7F800000, 0x7FC00000, 0x00000001, 0x80000001]        # skipped; tiny outputs, far off
