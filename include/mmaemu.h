@@ -506,7 +506,7 @@ mmaemu_status mmaemu_exact_dot_sample(const void *A, const void *B, const void *
  * Accumulates into *dev_hist (device memory, 8-byte aligned; mmaemu_deviation_hist_reset clears it).  Operands of at
  * most 16 bits (FP8, FP6, FP4, FP16, BF16).
  * Errors: INVALID_ARG (NULL, alignment, bin_exp outside -280 .. 250), SHAPE (zero sizes, k > 2^20, stride 0, more than
- * 2^44 samples), UNSUPPORTED (types).
+ * 2^43 samples), UNSUPPORTED (types).
  */
 #define MMAEMU_DEVIATION_BINS 64
 typedef struct {

@@ -5,8 +5,6 @@
 // binary64 numbers while that is exact and in a wide fixed-point number otherwise, so delta itself is exact; only its
 // binary64 image (for the three sums) is rounded.  Linear bins of width 2^bin_exp
 // around zero: bin i holds delta in [(i - 32) w, (i - 31) w), the outermost bins everything beyond.
-#include "common.hpp"
-#include "fdpa_int.hpp"
 #include "efdpa_pair.hpp"
 
 namespace mmaemu {
@@ -18,6 +16,31 @@ __global__ void deviation_reset_kernel(mmaemu_deviation_hist *h)
 {
     uint64_t *w = reinterpret_cast<uint64_t *>(h);
     if (threadIdx.x < DEV_WORDS) w[threadIdx.x] = 0ull;             // +0.0 is all-zero bits
+}
+
+// Elements kk .. kk + 7 of a row (bits as elem_bits gives them): `vec` says that the row's bytes from kk on are 16-byte
+// aligned (8-byte for one-byte elements), so one or two wide loads bring them; per-element loads of 64 lanes, each in a
+// row of its own, keep the address unit busy for longer than all the arithmetic of a sample takes.
+__device__ __forceinline__ void load8(uint32_t t, uint32_t esize, const uint8_t *row, uint32_t kk, bool vec, uint32_t (&r)[8])
+{
+    if (!vec) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r[q] = elem_bits(t, esize, row, kk + q);
+    } else if (esize == 2) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(row + 2u * kk);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { r[2 * q] = w[q] & 0xFFFFu; r[2 * q + 1] = w[q] >> 16; }
+    } else if (esize == 1) {
+        const uint2 v = *reinterpret_cast<const uint2 *>(row + kk);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { r[q] = (v.x >> (8 * q)) & 0xFFu; r[4 + q] = (v.y >> (8 * q)) & 0xFFu; }
+    } else {
+        const uint4 v0 = *reinterpret_cast<const uint4 *>(row + 4u * kk), v1 = *reinterpret_cast<const uint4 *>(row + 4u * kk + 16u);
+        const uint32_t w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+#pragma unroll
+        for (int q = 0; q < 8; ++q) r[q] = t == MMAEMU_TF32 ? w[q] >> 13 : w[q];
+    }
 }
 
 // The same through the wide fixed-point number (exact for any finite operands): sign, whether delta is zero,
@@ -93,6 +116,7 @@ deviation_kernel(const void *__restrict__ A, const void *__restrict__ B, const u
     const uint32_t esa = (uint32_t)fa.width_ / 8u, esb = (uint32_t)fb.width_ / 8u;
     const uint64_t per_tile = (uint64_t)m * n;
     const int unit_bit = bin_exp - XBASE;                            // index of the bit that weighs one bin width
+    const bool vec_a = (reinterpret_cast<uintptr_t>(A) & 15u) == 0 && k % 8u == 0, vec_b = (reinterpret_cast<uintptr_t>(B) & 15u) == 0 && k % 8u == 0;
     double sum = 0.0, sum_abs = 0.0, sum_sq = 0.0;
     // (a workgroup handles at most 2^32 / 256 samples: the 32-bit LDS counters cannot overflow, see the launch)
     for (uint64_t sidx = (uint64_t)blockIdx.x * 256u + threadIdx.x; sidx < nsamples; sidx += (uint64_t)gridDim.x * 256u) {
@@ -108,10 +132,24 @@ deviation_kernel(const void *__restrict__ A, const void *__restrict__ B, const u
         bool bad = (cb & 0x7F800000u) == 0x7F800000u || (db & 0x7F800000u) == 0x7F800000u;
         ExactPair pr;
         pr.start(db);
-        for (uint32_t kk = 0; kk < k; ++kk) {
-            const Dec x = decode_as(fa, fa.load(a, kk), 0u), y = decode_as(fb, fb.load(b, kk), 0u);
-            bad |= x.cls == CLS_INF || x.cls == CLS_NAN || y.cls == CLS_INF || y.cls == CLS_NAN;
-            pr.add(-dec_value(fa, x), dec_value(fb, y));
+        const double finite_max = 0x1.fffffffffffffp+1023;
+        uint32_t kk = 0;
+        for (; kk + 8 <= k; kk += 8) {
+            // (eight elements of each row fetched before the first is used: one wait per eight terms)
+            uint32_t ra[8], rb[8];
+            load8(ta, esa, a, kk, vec_a, ra);
+            load8(tb, esb, b, kk, vec_b, rb);
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const double x = elem_value(ta, ra[q], 0u), y = elem_value(tb, rb[q], 0u);
+                bad |= !(__builtin_fabs(x) <= finite_max) || !(__builtin_fabs(y) <= finite_max);
+                pr.add(-x, y);
+            }
+        }
+        for (; kk < k; ++kk) {
+            const double x = elem_value(ta, elem_bits(ta, esa, a, kk), 0u), y = elem_value(tb, elem_bits(tb, esb, b, kk), 0u);
+            bad |= !(__builtin_fabs(x) <= finite_max) || !(__builtin_fabs(y) <= finite_max);
+            pr.add(-x, y);
         }
         if (bad) { atomicAdd(&counts[1], 1u); continue; }
         pr.add(-(double)__uint_as_float(cb), 1.0);
@@ -152,17 +190,25 @@ deviation_kernel(const void *__restrict__ A, const void *__restrict__ B, const u
         sum_abs += ad;
         sum_sq += ad * ad;
     }
-    // the three sums: over the wavefront by lane exchanges, then one atomic per wavefront
+    // the three sums: over the wavefront by lane exchanges, over the workgroup through LDS, then one atomic per workgroup
+    // and sum (thousands of wavefronts adding to the same three words took longer than everything else in the kernel)
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         sum += __shfl_xor(sum, off, 64);
         sum_abs += __shfl_xor(sum_abs, off, 64);
         sum_sq += __shfl_xor(sum_sq, off, 64);
     }
-    double *gd = reinterpret_cast<double *>(reinterpret_cast<uint64_t *>(hist) + 5 + NB);
+    __shared__ double wave_sums[4][3];
     if ((threadIdx.x & 63u) == 0u) {
-        if (sum != 0.0) atomicAdd(&gd[0], sum);
-        if (sum_abs != 0.0) { atomicAdd(&gd[1], sum_abs); atomicAdd(&gd[2], sum_sq); }
+        wave_sums[threadIdx.x >> 6][0] = sum;
+        wave_sums[threadIdx.x >> 6][1] = sum_abs;
+        wave_sums[threadIdx.x >> 6][2] = sum_sq;
+    }
+    __syncthreads();
+    double *gd = reinterpret_cast<double *>(reinterpret_cast<uint64_t *>(hist) + 5 + NB);
+    if (threadIdx.x < 3) {
+        const double t = (wave_sums[0][threadIdx.x] + wave_sums[1][threadIdx.x]) + (wave_sums[2][threadIdx.x] + wave_sums[3][threadIdx.x]);
+        if (t != 0.0) atomicAdd(&gd[threadIdx.x], t);
     }
     __syncthreads();
     if (threadIdx.x < 5 + NB && counts[threadIdx.x])
@@ -184,8 +230,8 @@ mmaemu_status launch_deviation_sample(const void *A, const void *B, const uint32
     const uint64_t nsamples = (total + stride - 1) / stride;
     if (nsamples == 0) return MMAEMU_OK;
     uint64_t blocks = (nsamples + 255) / 256;
-    if (blocks > 4096) blocks = 4096;                                // grid-stride beyond that
-    if ((nsamples + blocks - 1) / blocks > 0xFFFFFFFFull) { set_error("deviation_sample: more than 2^44 samples in one call"); return MMAEMU_ERR_SHAPE; }
+    if (blocks > 2048) blocks = 2048;                                // grid-stride beyond that: two rounds of what the chip holds
+    if ((nsamples + blocks - 1) / blocks > 0xFFFFFFFFull) { set_error("deviation_sample: more than 2^43 samples in one call"); return MMAEMU_ERR_SHAPE; }
     hipLaunchKernelGGL(deviation_kernel, dim3((uint32_t)blocks), dim3(256), 0, s, A, B, C, D, m, n, k, ta, tb, stride, nsamples,
                        bin_exp, h);
     MMAEMU_HIP(hipGetLastError());

@@ -7,8 +7,7 @@
 // rounds the exact sum correctly.  NaN and infinite operands need nothing of their own: binary64 arithmetic gives NaN
 // for a NaN, for infinity times zero and for infinities of both signs, and the infinity otherwise (Sec. 4.2's rule).
 #pragma once
-#include "common.hpp"
-#include "fdpa_int.hpp"
+#include "emulate_tiled.hpp"
 
 namespace mmaemu {
 
@@ -19,6 +18,41 @@ __device__ __forceinline__ double dec_value(const FT &f, const Dec &x)
     if (x.cls == CLS_NAN) return __longlong_as_double(0x7FF8000000000000ll);
     const double mag = x.cls == CLS_INF ? __longlong_as_double(0x7FF0000000000000ll) : ldexp((double)x.sig, x.exp - f.mb());
     return x.sign ? -mag : mag;
+}
+
+// bytes per element as the arrays hold them
+__device__ __host__ __forceinline__ uint32_t elem_bytes(uint32_t t)
+{
+    return (t == MMAEMU_FP32 || t == MMAEMU_TF32) ? 4u : ((t == MMAEMU_FP16 || t == MMAEMU_BF16) ? 2u : 1u);
+}
+
+// element idx of an array of `esize`-byte elements: its bits (TF32 without its 13 surplus bits)
+__device__ __forceinline__ uint32_t elem_bits(uint32_t t, uint32_t esize, const void *p, uint64_t idx)
+{
+    if (esize == 1) return static_cast<const uint8_t *>(p)[idx];
+    if (esize == 2) return static_cast<const uint16_t *>(p)[idx];
+    const uint32_t w = static_cast<const uint32_t *>(p)[idx];
+    return t == MMAEMU_TF32 ? w >> 13 : w;
+}
+
+// the binary64 number that an element's bits denote (NaN and infinities as themselves); FlushSubnormal on request
+__device__ __forceinline__ double elem_value(uint32_t t, uint32_t bits, uint32_t ftz_in)
+{
+    float v = 0.0f;
+    uint32_t ex;
+    bool wild = false;
+    switch (t) {   // uniform
+    case MMAEMU_FP8_E4M3: decode_elem<MMAEMU_FP8_E4M3>(bits, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP8_E5M2: decode_elem<MMAEMU_FP8_E5M2>(bits, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP6_E2M3: decode_elem<MMAEMU_FP6_E2M3>(bits, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP6_E3M2: decode_elem<MMAEMU_FP6_E3M2>(bits, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP4_E2M1: decode_elem<MMAEMU_FP4_E2M1>(bits, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP16: decode_elem<MMAEMU_FP16>(bits, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_TF32: decode_elem<MMAEMU_TF32>(bits, ftz_in, 0u, v, ex, wild); break;
+    case MMAEMU_FP32: v = __uint_as_float((ftz_in && (bits & 0x7F800000u) == 0) ? 0u : bits); break;
+    default: decode_elem<MMAEMU_BF16>(bits, ftz_in, 0u, v, ex, wild); break;
+    }
+    return (double)v;
 }
 
 // s + e = a + b exactly (s = RN(a + b)), for finite operands

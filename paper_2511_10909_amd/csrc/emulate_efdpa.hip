@@ -9,40 +9,9 @@
 // no result has) at each output it could not finish, and a second launch runs those outputs' chains from C again.
 // Shapes that are not whole blocks, and FP32 operands, take the same two launches with one thread per output and the
 // operands read from memory.
-#include "emulate_tiled.hpp"
 #include "efdpa_pair.hpp"
 
 namespace mmaemu {
-
-// one element as the binary64 number it denotes (NaN and infinities as themselves); FlushSubnormal on request
-__device__ __forceinline__ double efdpa_value(uint32_t t, const void *p, uint64_t idx, uint32_t ftz_in)
-{
-    float v = 0.0f;
-    uint32_t ex;
-    bool wild = false;
-    switch (t) {   // uniform
-    case MMAEMU_FP8_E4M3: decode_elem<MMAEMU_FP8_E4M3>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
-    case MMAEMU_FP8_E5M2: decode_elem<MMAEMU_FP8_E5M2>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
-    case MMAEMU_FP6_E2M3: decode_elem<MMAEMU_FP6_E2M3>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
-    case MMAEMU_FP6_E3M2: decode_elem<MMAEMU_FP6_E3M2>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
-    case MMAEMU_FP4_E2M1: decode_elem<MMAEMU_FP4_E2M1>(static_cast<const uint8_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
-    case MMAEMU_FP16: decode_elem<MMAEMU_FP16>(static_cast<const uint16_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
-    case MMAEMU_TF32: decode_elem<MMAEMU_TF32>(static_cast<const uint32_t *>(p)[idx] >> 13, ftz_in, 0u, v, ex, wild); break;
-    case MMAEMU_FP32: {
-        const uint32_t w = static_cast<const uint32_t *>(p)[idx];
-        v = __uint_as_float((ftz_in && (w & 0x7F800000u) == 0) ? 0u : w);
-        break;
-    }
-    default: decode_elem<MMAEMU_BF16>(static_cast<const uint16_t *>(p)[idx], ftz_in, 0u, v, ex, wild); break;
-    }
-    return (double)v;
-}
-
-// bytes per element as the arrays hold them
-__device__ __host__ __forceinline__ uint32_t efdpa_esize(uint32_t t)
-{
-    return (t == MMAEMU_FP32 || t == MMAEMU_TF32) ? 4u : ((t == MMAEMU_FP16 || t == MMAEMU_BF16) ? 2u : 1u);
-}
 
 constexpr int EKC = 32;                       // values of k staged at a time
 
@@ -57,7 +26,7 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
     __shared__ __attribute__((aligned(16))) double Bs[16][VS];
     const uint32_t tid = threadIdx.x, i = tid / 16u, j = tid % 16u;
     const uint32_t bpr = n / 16u, bpt = (m / 16u) * bpr;
-    const uint32_t esa = efdpa_esize(ta), esb = efdpa_esize(tb);
+    const uint32_t esa = elem_bytes(ta), esb = elem_bytes(tb);
     const uint32_t L = p.L;
     for (uint64_t w = blockIdx.x; w < nblocks; w += gridDim.x) {
         const uint64_t t = w / bpt;
@@ -74,8 +43,8 @@ emulate_efdpa_blocks_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *_
             __syncthreads();                               // (the previous chunk's readers)
             // (thread (i, j) stages columns j and j + 16 of row i of both operands)
             for (uint32_t kk = j; kk < kc; kk += 16u) {
-                As[i][kk] = efdpa_value(ta, A, (arow0 + i) * (uint64_t)k + k0 + kk, p.ftz_in);
-                Bs[i][kk] = efdpa_value(tb, B, (brow0 + i) * (uint64_t)k + k0 + kk, p.ftz_in);
+                As[i][kk] = elem_value(ta, elem_bits(ta, esa, A, (arow0 + i) * (uint64_t)k + k0 + kk), p.ftz_in);
+                Bs[i][kk] = elem_value(tb, elem_bits(tb, esb, B, (brow0 + i) * (uint64_t)k + k0 + kk), p.ftz_in);
             }
             __syncthreads();
             // the groups (or the part of a longer group) inside this chunk: a group of at most 32 terms starts and ends
@@ -129,6 +98,7 @@ emulate_efdpa_pairs_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__
                            uint32_t mark)
 {
     const uint64_t mn = (uint64_t)m * n;
+    const uint32_t esa = elem_bytes(ta), esb = elem_bytes(tb);
     for (uint64_t o = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (uint64_t)gridDim.x * blockDim.x) {
         // (a 64-bit division costs about as much as four terms: 32-bit arithmetic where the output index allows it)
         const uint64_t t = (total >> 32) == 0 ? (uint64_t)((uint32_t)o / (uint32_t)mn) : o / mn;
@@ -139,7 +109,7 @@ emulate_efdpa_pairs_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__
         for (uint32_t k0 = 0; k0 < k && !marked; k0 += p.L) {
             ExactPair sum;
             sum.start((p.ftz_in && (d & 0x7F800000u) == 0) ? 0u : d);
-            for (uint32_t kk = k0; kk < k0 + p.L; ++kk) sum.add(efdpa_value(ta, A, a0 + kk, p.ftz_in), efdpa_value(tb, B, b0 + kk, p.ftz_in));
+            for (uint32_t kk = k0; kk < k0 + p.L; ++kk) sum.add(elem_value(ta, elem_bits(ta, esa, A, a0 + kk), p.ftz_in), elem_value(tb, elem_bits(tb, esb, B, b0 + kk), p.ftz_in));
             marked = !sum.finish(p, d);
         }
         D[o] = marked ? mark : d;
@@ -151,7 +121,7 @@ __global__ void __launch_bounds__(256)
 emulate_efdpa_marked_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__restrict__ A, const void *__restrict__ B,
                             const uint32_t *__restrict__ C, uint32_t *D, uint32_t m, uint32_t n, uint32_t k, uint64_t total, uint32_t mark)
 {
-    const uint32_t esa = efdpa_esize(ta), esb = efdpa_esize(tb);
+    const uint32_t esa = elem_bytes(ta), esb = elem_bytes(tb);
     const uint64_t mn = (uint64_t)m * n;
     for (uint64_t o = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; o < total; o += (uint64_t)gridDim.x * blockDim.x) {
         if (D[o] != mark) continue;
