@@ -294,6 +294,12 @@ def main():
             r = configs.scan_against_mfma(instr, cands, n_tiles=1 << 16, families=fams)
             other[name] = dict(terms=r["terms"], ms=r["seconds"] * 1e3, terms_per_s=r["terms"] / r["seconds"],
                                candidates_without_mismatch=sum(1 for t in r["total"] if t == 0))
+        # the deviation histograms of Sec. 6.2.4 (TR-FDPA as printed, its truncating variant, the native instruction) on
+        # 2^18 FP16 32x32x8 tiles, every output against its exact result
+        configs.bias_experiment(n_tiles=1 << 12)
+        r = configs.bias_experiment(n_tiles=1 << 18)
+        other["bias_experiment_fp16"] = dict(terms=r["terms"], ms=r["seconds"] * 1e3, terms_per_s=r["terms"] / r["seconds"],
+                                             mean_delta={k: h["sum"] / max(h["n_samples"], 1) for k, h in r["hists"].items()})
         out["config"]["other_workloads_end_to_end"] = other
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.cpu_seconds)
