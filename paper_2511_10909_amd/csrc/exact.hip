@@ -2,11 +2,12 @@
 // (methodology of the paper's Sec. 6.2.4: deviation of a model's output from the real
 // result; the real result here is the exact integer dot product of the FP8 operands).
 //
-// One wavefront per sampled output: lanes stride over k, each accumulating exact integer
-// products in units of 2^LSB0 (LSB0 = the smallest last-place exponent a product can
-// have); an FP8 product is below 2^33 in value and a multiple of 2^-32, so it needs at
-// most 66 bits; per-lane sums are kept in two 64-bit integers split by shift size and
-// combined into a two-limb (128-bit) signed value that is exact for any k <= 2^20.
+// One wavefront per sampled output: lanes stride over k, each accumulating exact products
+// in units of 2^LSB0 (LSB0 = the smallest last-place exponent a product can have); an FP8
+// product is below 2^33 in value and a multiple of 2^-32, so it needs at most 66 bits;
+// per-lane sums are kept in two binary64 numbers that split every product at 2^(LSB0 + 32),
+// both exact, and combined into a two-limb (128-bit) signed value that is exact for any
+// k <= 2^20.
 #include "common.hpp"
 
 namespace mmaemu {
@@ -65,6 +66,17 @@ __device__ __forceinline__ double mag_to_double(uint64_t hi, uint64_t lo, int ls
     return ldexp((double)hi, 64 + lsb) + ldexp((double)lo, lsb);
 }
 
+// the four FP8 elements of a word as binary32 numbers (exact), by v_cvt_pk_f32_fp8 / v_cvt_pk_f32_bf8: on gfx950 these
+// take the OCP encodings (E4M3 with the single NaN pattern S.1111.111 and no infinity, E5M2 with IEEE-style specials)
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+template <int T> __device__ __forceinline__ void fp8x4_values(uint32_t w, float (&v)[4])
+{
+    f32x2 lo, hi;
+    if (T == MMAEMU_FP8_E4M3) { lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false); hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true); }
+    else { lo = __builtin_amdgcn_cvt_pk_f32_bf8((int)w, false); hi = __builtin_amdgcn_cvt_pk_f32_bf8((int)w, true); }
+    v[0] = lo.x; v[1] = lo.y; v[2] = hi.x; v[3] = hi.y;
+}
+
 template <int TA, int TB>
 __global__ void __launch_bounds__(256)
 exact_dot_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, const uint32_t *__restrict__ D,
@@ -86,34 +98,38 @@ exact_dot_kernel(const uint8_t *__restrict__ A, const uint8_t *__restrict__ B, c
         const uint64_t o = sidx * stride;
         const uint32_t i = (uint32_t)(o / n), j = (uint32_t)(o % n);
         const uint8_t *a = A + (uint64_t)i * k, *b = B + (uint64_t)j * k;
-        // Per lane: four consecutive k per 32-bit load.  A product p * 2^sh (p < 2^8, sh <= 58)
-        // goes to one of two 64-bit sums by the size of its shift -- units 2^LSB0 for sh < 32,
-        // units 2^(LSB0+32) otherwise -- so each addend is below 2^39 and neither sum can
-        // overflow for any k <= 2^20; the two are combined into 128 bits once per sample.
-        int64_t acc_lo = 0, acc_hi = 0;
-        bool bad = false;
+        // Per lane: four consecutive k per 32-bit load, decoded by the hardware's own FP8 -> binary32 conversions (two
+        // elements per instruction); a product is exact in binary32 (at most 8 significant bits, 2^-32 <= |p| < 2^33).
+        // Its binary64 image is split at 2^(LSB0 + 32) by adding and subtracting a constant whose last place that is:
+        // the upper part is a multiple of 2^(LSB0 + 32), the lower part a multiple of 2^LSB0 of at most 2^(LSB0 + 31),
+        // and with at most 2^14 terms per lane (k <= 2^20) both sums stay below 2^53 of their units, i.e. exact.
+        // A NaN or an infinity among the operands makes one of the sums a NaN or an infinity.
+        constexpr double SPLIT = 0x1.8p+52 * (LSB0 + 32 >= 0 ? (double)(1ull << (LSB0 + 32 >= 0 ? LSB0 + 32 : 0)) : 1.0 / (double)(1ull << (LSB0 + 32 >= 0 ? 0 : -(LSB0 + 32))));
+        double sum_hi = 0.0, sum_lo = 0.0;
         for (uint32_t q = 4 * lane; q < k; q += 256) {
             uint32_t wa, wb;
             if (q + 4 <= k && (((uintptr_t)(a + q) | (uintptr_t)(b + q)) & 3) == 0) {
                 wa = *reinterpret_cast<const uint32_t *>(a + q);
                 wb = *reinterpret_cast<const uint32_t *>(b + q);
             } else {
-                wa = wb = 0;
+                wa = wb = 0;                                                     // (padding bytes are zero: +0.0)
                 for (uint32_t u = 0; u < 4 && q + u < k; ++u) { wa |= (uint32_t)a[q + u] << (8 * u); wb |= (uint32_t)b[q + u] << (8 * u); }
             }
+            float va[4], vb[4];
+            fp8x4_values<TA>(wa, va);
+            fp8x4_values<TB>(wb, vb);
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                uint32_t sa, sb, na, nb; int ea, eb; bool xa, xb;
-                dec8<TA>((wa >> (8 * u)) & 0xFFu, sa, ea, na, xa);
-                dec8<TB>((wb >> (8 * u)) & 0xFFu, sb, eb, nb, xb);
-                bad |= xa | xb;                                                 // (padding bytes are zero: finite)
-                const int sh = (ea - Fmt<TA>::MB) + (eb - Fmt<TB>::MB) - LSB0;  // 0 .. 58
-                const int64_t pr = (int64_t)(sa * sb);
-                const int64_t sp = (na ^ nb) ? -pr : pr;
-                if (sh < 32) acc_lo += (int64_t)((uint64_t)sp << sh);
-                else acc_hi += (int64_t)((uint64_t)sp << (sh - 32));
+                const double pd = (double)(va[u] * vb[u]);
+                const double upper = (pd + SPLIT) - SPLIT;
+                sum_hi += upper;
+                sum_lo += pd - upper;
             }
         }
+        const double finite_max = 0x1.fffffffffffffp+1023;
+        bool bad = !(__builtin_fabs(sum_hi) <= finite_max) || !(__builtin_fabs(sum_lo) <= finite_max);
+        const int64_t acc_hi = bad ? 0 : (int64_t)__builtin_ldexp(sum_hi, -(LSB0 + 32));
+        const int64_t acc_lo = bad ? 0 : (int64_t)__builtin_ldexp(sum_lo, -LSB0);
         I128 acc = {(uint64_t)acc_lo, acc_lo < 0 ? -1ll : 0ll};
         acc = add128(acc, shl128(I128{(uint64_t)acc_hi, acc_hi < 0 ? -1ll : 0ll}, 32));
         // wavefront reduction of the two-limb sums

@@ -326,6 +326,37 @@ def test_exact_dot_sample_matches_oracle(mm):
             assert got[key] == pytest.approx(want[key], rel=1e-9, abs=1e-300), key
 
 
+def test_exact_dot_every_pair_of_codes(mm):
+    # every pair of FP8 codes as the one non-zero product of a dot product of four: D holds the exact product (every one is
+    # a binary32 number), so each finite pair must be counted as equal, and each pair with a NaN or an infinity as skipped
+    from fractions import Fraction
+    for ta, tb in ((fm.E4M3, fm.E5M2), (fm.E5M2, fm.E5M2), (fm.E4M3, fm.E4M3), (fm.E5M2, fm.E4M3)):
+        A = np.zeros((256, 4), dtype=np.uint8)
+        B = np.zeros((256, 4), dtype=np.uint8)
+        A[:, 1] = np.arange(256)
+        B[:, 1] = np.arange(256)
+        B[:, 3] = 0x80                             # (a negative zero elsewhere in the row changes nothing)
+        da = [fm.decode(c, ta) for c in range(256)]
+        db = [fm.decode(c, tb) for c in range(256)]
+        D = np.zeros((256, 256), dtype=np.uint32)
+        finite = 0
+        for i in range(256):
+            for j in range(256):
+                if da[i].finite and db[j].finite:
+                    finite += 1
+                    D[i, j] = np.float32(float(da[i].value * db[j].value)).view(np.uint32)
+                    assert Fraction(float(np.uint32(D[i, j]).view(np.float32))) == da[i].value * db[j].value
+                    if D[i, j] == 0x80000000:
+                        D[i, j] = 0                # (an exact zero is +0.0)
+        st = dev_empty(mm.ERR_STATS_BYTES)
+        mm.err_stats_reset(st)
+        mm.exact_dot_sample(to_dev(A), to_dev(B), to_dev(D), 256, 256, 4, (ta, tb, fm.FP32, fm.FP32), 1, st)
+        got = mm.read_err_stats(st)
+        assert got["n_samples"] == finite and got["n_skipped"] == 65536 - finite, (ta, tb, got["n_samples"], got["n_skipped"], finite)
+        assert got["n_equal_rne"] == finite and got["max_abs_err"] == 0.0, (ta, tb, got["n_equal_rne"], got["max_abs_err"])
+        assert 0 < 65536 - finite < 6000
+
+
 @pytest.mark.parametrize("ta,tb,L,cm", [(fm.FP16, fm.FP16, 0, C_IN_GROUP), (fm.BF16, fm.BF16, 8, C_AFTER_EXACT), (fm.E4M3, fm.E5M2, 32, C_IN_GROUP),
                                         (fm.FP16, fm.FP16, 1 << 20, C_AFTER_EXACT)])
 def test_emulate_longest_dot_products(mm, ta, tb, L, cm):
