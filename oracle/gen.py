@@ -31,8 +31,9 @@ Families (r = first word, r1 = second word):
                 operand share (r_2i, r_2i+1)):  u1 = (r_2i + 0.5) / 2^32,
                 phi = 2 pi r_2i+1 / 2^32 (+ half a step), radius = sqrt(-2 ln u1);
                 element 2i gets radius*cos(phi), element 2i+1 radius*sin(phi).
-                ln, sin, cos and sqrt are evaluated in binary64 with +, *, / only
-                (series below, fixed operation order, no fused multiply-add), so
+                ln, sin and cos are evaluated in binary64 with +, *, / only
+                (series below, fixed operation order, no fused multiply-add), and the
+                square root is IEEE-754's own correctly rounded operation, so
                 that any IEEE-754 machine produces the same bits.  The value is
                 optionally multiplied by scale_target / absmax (absmax over the
                 whole call, or over each tile), rounded to binary32 (RNE), then to
@@ -123,8 +124,6 @@ HALF_PI = float.fromhex("0x1.921fb54442d18p+0")
 LOG_TERMS = 12     # ln m = 2 s (1 + s^2/3 + ... + s^(2*12)/(2*12+1)),  s = (m-1)/(m+1)
 SIN_TERMS = 10     # through theta^19
 COS_TERMS = 11     # through theta^20
-SQRT_ITERS = 5
-SQRT_SEED = 0x1FF8000000000000
 
 
 def _ln_unit(r):
@@ -142,11 +141,8 @@ def _ln_unit(r):
     return lnm + (ex - 1 - 33).astype(np.float64) * LN2
 
 
-def _sqrt_heron(x):
-    y = ((x.view(np.uint64) >> np.uint64(1)) + np.uint64(SQRT_SEED)).view(np.float64)
-    for _ in range(SQRT_ITERS):
-        y = 0.5 * (y + x / y)
-    return y
+def _sqrt(x):
+    return np.sqrt(x)                                     # correctly rounded (IEEE-754 squareRoot)
 
 
 def _sincos_quarter(theta):
@@ -162,7 +158,7 @@ def _sincos_quarter(theta):
 
 def normal_pairs(r_even, r_odd):
     """Box-Muller: two uint32 arrays -> (z_even, z_odd) binary64."""
-    radius = _sqrt_heron(-2.0 * _ln_unit(r_even))
+    radius = _sqrt(-2.0 * _ln_unit(r_even))
     quad = (r_odd >> np.uint32(30)).astype(np.int64)
     frac = ((r_odd & np.uint32(0x3FFFFFFF)).astype(np.float64) + 0.5) * (1.0 / (1 << 30))
     s, c = _sincos_quarter(frac * HALF_PI)

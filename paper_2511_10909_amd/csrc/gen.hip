@@ -145,7 +145,7 @@ __global__ void zero_kernel(uint32_t *out, uint64_t nwords, uint8_t *tail, uint3
 }
 
 // ---- NORMAL family --------------------------------------------------------------------
-// binary64 elementary functions from +, *, / only, in a fixed order
+// binary64 elementary functions from +, *, / only, in a fixed order (the square root is IEEE-754's own operation)
 
 __device__ __forceinline__ double ln_unit(uint32_t r)       // ln((r + 0.5) / 2^32)
 {
@@ -170,14 +170,6 @@ __device__ __forceinline__ double ln_unit(uint32_t r)       // ln((r + 0.5) / 2^
     poly = poly * s2 + 1.0;
     const double lnm = (2.0 * s) * poly;
     return lnm + (double)(ex - 33) * 0x1.62e42fefa39efp-1;
-}
-
-__device__ __forceinline__ double sqrt_heron(double x)
-{
-    double y = __longlong_as_double((long long)(((unsigned long long)__double_as_longlong(x) >> 1) + 0x1FF8000000000000ull));
-#pragma unroll
-    for (int i = 0; i < 5; ++i) y = 0.5 * (y + x / y);
-    return y;
 }
 
 __device__ __forceinline__ void sincos_quarter(double th, double &sn, double &cs)
@@ -211,7 +203,7 @@ __device__ __forceinline__ void sincos_quarter(double th, double &sn, double &cs
 // Box-Muller on one word pair
 __device__ __forceinline__ void normal_pair(uint32_t r_even, uint32_t r_odd, double &z_even, double &z_odd)
 {
-    const double radius = sqrt_heron(-2.0 * ln_unit(r_even));
+    const double radius = __builtin_sqrt(-2.0 * ln_unit(r_even));   // IEEE-754 squareRoot: correctly rounded
     const uint32_t quad = r_odd >> 30;
     const double frac = ((double)(r_odd & 0x3FFFFFFFu) + 0.5) * (1.0 / 1073741824.0);
     double s, c;

@@ -125,6 +125,20 @@ def test_generate_binary64_matches_cpu_twin(mm, family, kw):
         assert_same(to_host(out, np.uint64), want, "generate fp64")
 
 
+def test_normal_stream_in_binary64_at_size(mm):
+    # 2^23 values of the N(0,1) series as binary64 numbers, before any narrowing hides a last place: the series' square
+    # root is the IEEE-754 operation on both sides, so a device routine that were not correctly rounded would show here
+    ept, nt = 4096, 2048
+    gp = ogen.GenParams(family=ogen.GEN_NORMAL, seed=5, operand=1)
+    out = dev_empty((nt, ept), np.uint64)
+    mm.generate(out, FP64, ept, 0, nt, ogen.GEN_NORMAL, seed=5, operand=1)
+    got = to_host(out, np.uint64)
+    step = 256
+    for t0 in range(0, nt, step):
+        want = ogen.generate(gp, fm.FP64, ept, t0, step, threads=8)
+        assert_same(got[t0:t0 + step], want, "N(0,1) in binary64, tiles %d.." % t0)
+
+
 def test_compare_binary64_matches_oracle(mm):
     rng = np.random.default_rng(18)
     for count, misalign in ((1, 0), (1000, 0), (100003, 0), (4099, 1), (1 << 19, 0)):

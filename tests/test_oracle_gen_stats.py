@@ -136,8 +136,12 @@ def test_elementary_functions_against_libm():
     r = np.random.default_rng(1).integers(0, 1 << 32, size=20000, dtype=np.uint64).astype(np.uint32)
     want = np.log((r.astype(np.float64) + 0.5) / 2.0 ** 32)
     assert np.abs(gen._ln_unit(r) - want).max() < 1e-12
-    x = np.exp(np.random.default_rng(2).uniform(np.log(1e-10), np.log(50), 20000))
-    assert np.abs(gen._sqrt_heron(x) / np.sqrt(x) - 1).max() < 1e-15
+    # the square root is the correctly rounded one: its square brackets x within one last place, exactly checked in integers
+    from fractions import Fraction
+    x = np.exp(np.random.default_rng(2).uniform(np.log(1e-10), np.log(50), 2000))
+    for xv, yv in zip(x.tolist(), gen._sqrt(x).tolist()):
+        y, half_ulp = Fraction(yv), Fraction(np.spacing(yv)) / 2
+        assert (y - half_ulp) ** 2 <= Fraction(xv) <= (y + half_ulp) ** 2
     th = np.linspace(0, np.pi / 2, 10001)
     s, c = gen._sincos_quarter(th)
     assert np.abs(s - np.sin(th)).max() < 1e-15 and np.abs(c - np.cos(th)).max() < 1e-15
