@@ -115,6 +115,15 @@ __device__ __forceinline__ void decode_elem(uint32_t bits, uint32_t ftz_in, uint
         val = (float)h;                                          // exact, subnormals included; NaN and infinity as themselves
         if (ftz_in && E == 0) val = 0.0f;
         if (E == EMASK) ex = SENTINEL;
+    } else if (T == MMAEMU_FP8_E4M3 || T == MMAEMU_FP8_E5M2) {
+        // the hardware's own conversion (gfx950 takes the OCP encodings): exact, subnormals included
+        const uint32_t M = bits & MMASK, sign = (bits >> 7) & 1u;
+        val = T == MMAEMU_FP8_E4M3 ? __builtin_amdgcn_cvt_f32_fp8((int)bits, 0) : __builtin_amdgcn_cvt_f32_bf8((int)bits, 0);
+        if (ftz_in && E == 0) val = 0.0f;
+        if (F::IEEE ? (E == EMASK) : (E == EMASK && M == MMASK)) {
+            ex = SENTINEL;
+            val = __uint_as_float((F::IEEE && M == 0) ? (0x7F800000u | (sign << 31)) : 0x7FC00000u);
+        }
     } else {
         uint32_t M = bits & MMASK, sign = (bits >> (F::EB + F::MB)) & 1u;
         const bool special = F::IEEE ? (E == EMASK) : (!F::NOSPEC && E == EMASK && M == MMASK);
