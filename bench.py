@@ -26,9 +26,9 @@ ALGO_OPS_PER_TERM = 8                       # accounting floor of INT32 VALU ins
 # vector-ALU lane-instructions per MAC term (SQ_INSTS_VALU x 64 / terms) and HBM bytes per launch (FETCH_SIZE + WRITE_SIZE,
 # scaled by a copy kernel of known size).  Keyed by the kernel's name: a kernel that has changed since reports null.
 COUNTERS = {
-    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=0": {"valu_instr_per_term": 10.71, "traffic": 185159904, "chunk": 1 << 16},
-    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=1": {"valu_instr_per_term": 11.52, "traffic": 336601583, "chunk": 1 << 16},
-    "multi x3 tiled 32x32 r2x2 kc=8 any L vm=0, twins share sums": {"valu_instr_per_term": 10.15, "traffic": 1342821199, "chunk": 1 << 18},
+    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=0": {"valu_instr_per_term": 10.71, "traffic": 184924024, "chunk": 1 << 16},
+    "multi x16 tiled 16x16 r2x2 kc=16 any L vm=1": {"valu_instr_per_term": 11.52, "traffic": 338665326, "chunk": 1 << 16},
+    "multi x3 tiled 32x32 r2x2 kc=8 any L vm=0, twins share sums": {"valu_instr_per_term": 10.15, "traffic": 1342820407, "chunk": 1 << 18},
 }
 COUNTERS_SOURCE = ("profiles/closed_loop_scan_trace_and_counters.md, profiles/subnormal_stress_trace_and_counters.md (rocprofv3 --pmc SQ_INSTS_VALU; "
                    "FETCH_SIZE, WRITE_SIZE scaled by a 64 MiB copy); traffic per launch")
