@@ -139,11 +139,13 @@ deviation_kernel(const void *__restrict__ A, const void *__restrict__ B, const u
             uint32_t ra[8], rb[8];
             load8(ta, esa, a, kk, vec_a, ra);
             load8(tb, esb, b, kk, vec_b, rb);
+            double xa[8], xb[8];
+            elem_values(ta, ra, 0u, xa);                             // (one branch on the type per eight elements)
+            elem_values(tb, rb, 0u, xb);
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
-                const double x = elem_value(ta, ra[q], 0u), y = elem_value(tb, rb[q], 0u);
-                bad |= !(__builtin_fabs(x) <= finite_max) || !(__builtin_fabs(y) <= finite_max);
-                pr.add(-x, y);
+                bad |= !(__builtin_fabs(xa[q]) <= finite_max) || !(__builtin_fabs(xb[q]) <= finite_max);
+                pr.add(-xa[q], xb[q]);
             }
         }
         for (; kk < k; ++kk) {

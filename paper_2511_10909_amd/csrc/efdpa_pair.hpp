@@ -55,6 +55,37 @@ __device__ __forceinline__ double elem_value(uint32_t t, uint32_t bits, uint32_t
     return (double)v;
 }
 
+// the same for N elements of one type with a single (uniform) branch on the type
+template <int N>
+__device__ __forceinline__ void elem_values(uint32_t t, const uint32_t (&bits)[N], uint32_t ftz_in, double (&v)[N])
+{
+    auto all = [&](auto type_tag) {
+        constexpr int T = decltype(type_tag)::value;
+#pragma unroll
+        for (int q = 0; q < N; ++q) {
+            float f = 0.0f;
+            uint32_t ex;
+            bool wild = false;
+            decode_elem<T>(bits[q], ftz_in, 0u, f, ex, wild);
+            v[q] = (double)f;
+        }
+    };
+    switch (t) {
+    case MMAEMU_FP8_E4M3: all(std::integral_constant<int, MMAEMU_FP8_E4M3>{}); break;
+    case MMAEMU_FP8_E5M2: all(std::integral_constant<int, MMAEMU_FP8_E5M2>{}); break;
+    case MMAEMU_FP6_E2M3: all(std::integral_constant<int, MMAEMU_FP6_E2M3>{}); break;
+    case MMAEMU_FP6_E3M2: all(std::integral_constant<int, MMAEMU_FP6_E3M2>{}); break;
+    case MMAEMU_FP4_E2M1: all(std::integral_constant<int, MMAEMU_FP4_E2M1>{}); break;
+    case MMAEMU_FP16: all(std::integral_constant<int, MMAEMU_FP16>{}); break;
+    case MMAEMU_TF32: all(std::integral_constant<int, MMAEMU_TF32>{}); break;
+    case MMAEMU_FP32:
+#pragma unroll
+        for (int q = 0; q < N; ++q) v[q] = (double)__uint_as_float((ftz_in && (bits[q] & 0x7F800000u) == 0) ? 0u : bits[q]);
+        break;
+    default: all(std::integral_constant<int, MMAEMU_BF16>{}); break;
+    }
+}
+
 // s + e = a + b exactly (s = RN(a + b)), for finite operands
 __device__ __forceinline__ void two_sum(double a, double b, double &s, double &e)
 {
