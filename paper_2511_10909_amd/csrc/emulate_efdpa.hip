@@ -109,7 +109,19 @@ emulate_efdpa_pairs_kernel(ModelArgs p, uint32_t ta, uint32_t tb, const void *__
         for (uint32_t k0 = 0; k0 < k && !marked; k0 += p.L) {
             ExactPair sum;
             sum.start((p.ftz_in && (d & 0x7F800000u) == 0) ? 0u : d);
-            for (uint32_t kk = k0; kk < k0 + p.L; ++kk) sum.add(elem_value(ta, elem_bits(ta, esa, A, a0 + kk), p.ftz_in), elem_value(tb, elem_bits(tb, esb, B, b0 + kk), p.ftz_in));
+            uint32_t kk = k0;
+            for (; kk + 4 <= k0 + p.L; kk += 4) {
+                // (four elements of each row fetched, then decoded behind one branch on the type)
+                uint32_t ra[4], rb[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) { ra[q] = elem_bits(ta, esa, A, a0 + kk + q); rb[q] = elem_bits(tb, esb, B, b0 + kk + q); }
+                double xa[4], xb[4];
+                elem_values(ta, ra, p.ftz_in, xa);
+                elem_values(tb, rb, p.ftz_in, xb);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) sum.add(xa[q], xb[q]);
+            }
+            for (; kk < k0 + p.L; ++kk) sum.add(elem_value(ta, elem_bits(ta, esa, A, a0 + kk), p.ftz_in), elem_value(tb, elem_bits(tb, esb, B, b0 + kk), p.ftz_in));
             marked = !sum.finish(p, d);
         }
         D[o] = marked ? mark : d;
